@@ -1,0 +1,168 @@
+/*
+ * pbz -- blockwise orthonormal-transform codec and compressed-space operations for
+ * AMD Instinct MI355X (gfx950).  C ABI.
+ *
+ * The method is the one of arXiv 2406.11209 ("What Operations can be Performed Directly on
+ * Compressed Arrays, and with What Error?"); citations below name that paper's sections,
+ * algorithms and tables.
+ *
+ * A compressed array is the tuple {s, i, N, F} of Sec. III-B:
+ *   s  original shape                      (host, passed to the calls that need it)
+ *   i  block shape                         (fixed by the codec handle)
+ *   N  biggest coefficient of every block  (device; one working-type float per block, row-major
+ *                                           over the block grid b = ceil(s / i))
+ *   F  kept bin indices                    (device; block-major [block][kept index], kept indices in
+ *                                           row-major order of the intra-block coordinate)
+ * plus the pruning mask P and the two type tags, which live in the codec handle.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device pointers on the current device; "host" pointers are ordinary
+ *     host memory read during the call.  The library never takes ownership of caller memory.
+ *   - Arrays are contiguous, row-major (last dimension fastest).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All device work is
+ *     enqueued on it and the call returns without synchronising; scalar results are written to
+ *     device memory by the enqueued work.
+ *   - The return value is PBZ_OK or a negative pbz_status.  All argument checks happen on the host
+ *     before anything is launched, so a failing call has touched no device memory.  Nothing throws
+ *     or aborts across this boundary.
+ *   - The only device memory the library allocates is a few small constant tables (transform
+ *     matrices, kept-position table) owned by the codec handle, created at the first launch that
+ *     needs them and released by pbz_codec_destroy.
+ *   - Non-finite input values are a precondition violation: results are unspecified (no trap).
+ *
+ * Arithmetic precision.  The working float type f (Sec. III-A, "Data type conversion") is the storage
+ * type of N.  The transform and the binning decision are carried out in FP32 only when f is FP32 (or a
+ * 16-bit type) and the index type is int8; for every wider index type, and for f = FP64, they are
+ * carried out in FP64, because an FP32 transform error of a few 1e-7 N shifts r*C/N by more than the
+ * allowed index mismatch rate once r >= 32767.  Element-wise addition always rebins in FP64.
+ * Reductions multiply integer block sums by N in FP64 and accumulate in FP64 in a fixed order (results
+ * are bit-reproducible run to run).
+ */
+#ifndef PBZ_H
+#define PBZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PBZ_MAX_NDIM 8
+#define PBZ_MAX_BLOCK_EXTENT 256   /* per-dimension block extent limit */
+#define PBZ_MAX_BLOCK_VOLUME 4096  /* elements per block limit */
+
+/* Float types of Sec. III-A ("Data type conversion"): array element types and the working type f. */
+typedef enum { PBZ_F64 = 0, PBZ_F32 = 1, PBZ_BF16 = 2, PBZ_F16 = 3 } pbz_ftype;
+/* Bin index types of Sec. III-A ("Binning"); the index radius is r = 2^(bits-1) - 1.
+ * PBZ_I64 is declared because the paper lists it, but is rejected with PBZ_ERR_TYPE: its radius is not
+ * representable in FP64. */
+typedef enum { PBZ_I8 = 0, PBZ_I16 = 1, PBZ_I32 = 2, PBZ_I64 = 3 } pbz_itype;
+
+typedef enum {
+  PBZ_OK = 0,
+  PBZ_ERR_NULL = -1,        /* a required pointer is NULL */
+  PBZ_ERR_NDIM = -2,        /* ndim outside 1..PBZ_MAX_NDIM */
+  PBZ_ERR_BLOCK_SHAPE = -3, /* a block extent is not a power of two, or exceeds the limits above */
+  PBZ_ERR_TYPE = -4,        /* unknown or unsupported float / index type */
+  PBZ_ERR_MASK_EMPTY = -5,  /* the pruning mask keeps nothing */
+  PBZ_ERR_DC_PRUNED = -6,   /* mean / variance / covariance need the first coefficient of each block */
+  PBZ_ERR_SHAPE = -7,       /* an array extent or n_blocks is < 1, or sizes overflow */
+  PBZ_ERR_WORKSPACE = -8,   /* workspace smaller than pbz_layout reports */
+  PBZ_ERR_SCALAR = -9,      /* non-finite scalar */
+  PBZ_ERR_HIP = -10,        /* the HIP runtime reported an error (no device, launch failure, ...) */
+  PBZ_ERR_ALLOC = -11       /* host allocation failed */
+} pbz_status;
+
+/* Kernel families, for pbz_codec_set_kernel_path / pbz_kernel_name. */
+typedef enum { PBZ_PATH_AUTO = 0, PBZ_PATH_GENERIC = 1 } pbz_kernel_path;
+
+typedef struct pbz_codec pbz_codec; /* opaque compression settings (Sec. III-A): i, f, index type, P */
+
+/* Create the settings object: block shape i (each extent a power of two, possibly non-hypercubic;
+ * Sec. III-A "Blocking"), working float type f, index type, pruning mask P (Sec. III-A "Pruning").
+ *   block_shape  host, ndim entries.
+ *   mask         host, prod(block_shape) bytes, row-major over the block, non-zero = keep; NULL keeps all.
+ * Needs no GPU.  On success *out owns the handle; release it with pbz_codec_destroy. */
+int pbz_codec_create(pbz_codec** out, int ndim, const int64_t* block_shape, pbz_ftype work_type,
+                     pbz_itype index_type, const uint8_t* mask);
+void pbz_codec_destroy(pbz_codec* codec);
+
+/* Force the slow fully general kernels (PBZ_PATH_GENERIC) instead of the specialised ones; for testing. */
+int pbz_codec_set_kernel_path(pbz_codec* codec, pbz_kernel_path path);
+
+/* Sizes of the compressed form of an array of shape `shape` (host, ndim entries): number of blocks
+ * prod(ceil(s / i)), kept indices per block sum(P), bytes of N and of F, and the bytes of scratch the
+ * reduction entry points need (independent of shape).  Any output pointer may be NULL.  Needs no GPU. */
+int pbz_layout(const pbz_codec* codec, const int64_t* shape, int64_t* n_blocks, int64_t* kept_per_block,
+               size_t* n_bytes, size_t* f_bytes, size_t* workspace_bytes);
+
+/* Storage of the serialised compressed form in bits, following the component list of Sec. IV-C:
+ * 4 (type tags) + 64 d (s) + 64 (end marker) + 64 d (i) + prod(i) (P) + f prod(b) (N) + bits sum(P) prod(b) (F).
+ * Needs no GPU. */
+int pbz_compressed_bits(const pbz_codec* codec, const int64_t* shape, uint64_t* bits);
+
+/* Sec. III-A, all five steps fused: convert x to the compute type, tile into blocks (zero padding at the
+ * high end of each dimension), orthonormal DCT-II along every block dimension, N_k = max |C_k| over the
+ * whole block, I = rint(r C / N_k) (ties to even; an all-zero block gives N = 0, I = 0), F = I[P].
+ *   x       device, prod(shape) elements of x_type.
+ *   N, F    device, sizes from pbz_layout; written. */
+int pbz_compress(const pbz_codec* codec, const void* x, pbz_ftype x_type, const int64_t* shape, void* N,
+                 void* F, void* stream);
+
+/* Sec. III-B: C = N F / r at the mask positions and zero elsewhere, inverse transform, merge blocks,
+ * crop to `shape`, convert to y_type (round to nearest even).
+ *   y       device, prod(shape) elements of y_type; written. */
+int pbz_decompress(const pbz_codec* codec, const void* N, const void* F, const int64_t* shape, void* y,
+                   pbz_ftype y_type, void* stream);
+
+/* Algorithm 1: F_out = -F_in (N is unchanged and not touched).  F_out may alias F_in. */
+int pbz_negate(const pbz_codec* codec, int64_t n_blocks, const void* F_in, void* F_out, void* stream);
+
+/* Algorithm 5: N_out = N_in |x| (rounded to f), F_out = F_in sign(x) with sign(0) = 0.
+ * Outputs may alias the corresponding inputs. */
+int pbz_mul_scalar(const pbz_codec* codec, int64_t n_blocks, const void* N_in, const void* F_in, double x,
+                   void* N_out, void* F_out, void* stream);
+
+/* Algorithm 2: per block C = F1 N1 + F2 N2, N = max|C| / r, F = rint(C / N) (N = 0 gives F = 0).
+ * Both operands must come from this codec and the same array shape.  Outputs may alias an operand. */
+int pbz_add(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+            const void* F2, void* N_out, void* F_out, void* stream);
+
+/* Reductions.  Each writes one FP64 scalar to out (device).  `workspace` is device scratch of at
+ * least the size pbz_layout reports, 16-byte aligned; concurrent calls must use distinct workspaces.
+ *   pbz_dot                Algorithm 6   sum(C1 . C2)
+ *   pbz_norm2              Algorithm 10  ||C||_2
+ *   pbz_cosine_similarity  Algorithm 11  dot / (||A|| ||B||)
+ *   pbz_mean               Algorithm 7   mean of the first coefficients / prod(sqrt(i))
+ *   pbz_covariance         Algorithm 8   first coefficients centred by their mean over blocks, then
+ *                                        sum(C1 . C2) / (n_blocks prod(i))
+ *   pbz_variance           Algorithm 9   covariance(A, A)
+ * mean, covariance and variance return PBZ_ERR_DC_PRUNED when P drops the first coefficient (Sec. IV-A).
+ * n_blocks may be a sub-range of an array's blocks (e.g. one time step of a series). */
+int pbz_dot(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+            const void* F2, double* out, void* workspace, size_t workspace_bytes, void* stream);
+int pbz_covariance(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                   const void* F2, double* out, void* workspace, size_t workspace_bytes, void* stream);
+int pbz_cosine_similarity(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1,
+                          const void* N2, const void* F2, double* out, void* workspace,
+                          size_t workspace_bytes, void* stream);
+int pbz_norm2(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
+              void* workspace, size_t workspace_bytes, void* stream);
+int pbz_mean(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
+             void* workspace, size_t workspace_bytes, void* stream);
+int pbz_variance(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Name of the kernel family pbz_compress ("compress") or pbz_decompress ("decompress") would run for
+ * this shape and array type: "generic" or the name of a specialised kernel.  Host only; returns a static
+ * string, or NULL on invalid arguments. */
+const char* pbz_kernel_name(const pbz_codec* codec, const char* op, const int64_t* shape, pbz_ftype array_type);
+
+/* Human-readable text for a status code (static string, never NULL). */
+const char* pbz_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBZ_H */

@@ -1,0 +1,264 @@
+"""Thin Python binding of the pbz C ABI (include/pbz.h): argument marshalling only.
+
+Every step of the method runs in the HIP kernels behind the C entry points; PyTorch is used here for
+device memory and streams, nothing else.  There is no CPU or PyTorch fallback: if libpbz.so is missing
+the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libpbz.so")
+
+PBZ_F64, PBZ_F32, PBZ_BF16, PBZ_F16 = 0, 1, 2, 3
+PBZ_I8, PBZ_I16, PBZ_I32, PBZ_I64 = 0, 1, 2, 3
+PBZ_PATH_AUTO, PBZ_PATH_GENERIC = 0, 1
+PBZ_MAX_NDIM = 8
+
+FTYPES = {"f64": PBZ_F64, "f32": PBZ_F32, "bf16": PBZ_BF16, "f16": PBZ_F16}
+ITYPES = {"i8": PBZ_I8, "i16": PBZ_I16, "i32": PBZ_I32, "i64": PBZ_I64, 8: PBZ_I8, 16: PBZ_I16, 32: PBZ_I32, 64: PBZ_I64}
+
+_c = ctypes
+_p = _c.c_void_p
+_i64p = _c.POINTER(_c.c_int64)
+
+# name -> (restype, argtypes); mirrors include/pbz.h declaration by declaration
+SIGNATURES = {
+    "pbz_codec_create": (_c.c_int, [_c.POINTER(_p), _c.c_int, _i64p, _c.c_int, _c.c_int, _c.POINTER(_c.c_uint8)]),
+    "pbz_codec_destroy": (None, [_p]),
+    "pbz_codec_set_kernel_path": (_c.c_int, [_p, _c.c_int]),
+    "pbz_layout": (_c.c_int, [_p, _i64p, _i64p, _i64p, _c.POINTER(_c.c_size_t), _c.POINTER(_c.c_size_t),
+                              _c.POINTER(_c.c_size_t)]),
+    "pbz_compressed_bits": (_c.c_int, [_p, _i64p, _c.POINTER(_c.c_uint64)]),
+    "pbz_compress": (_c.c_int, [_p, _p, _c.c_int, _i64p, _p, _p, _p]),
+    "pbz_decompress": (_c.c_int, [_p, _p, _p, _i64p, _p, _c.c_int, _p]),
+    "pbz_negate": (_c.c_int, [_p, _c.c_int64, _p, _p, _p]),
+    "pbz_mul_scalar": (_c.c_int, [_p, _c.c_int64, _p, _p, _c.c_double, _p, _p, _p]),
+    "pbz_add": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _p]),
+    "pbz_dot": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_covariance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_cosine_similarity": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_mean": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_variance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_kernel_name": (_c.c_char_p, [_p, _c.c_char_p, _i64p, _c.c_int]),
+    "pbz_status_string": (_c.c_char_p, [_c.c_int]),
+}
+
+_lib = None
+
+
+class PbzError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"pbz status {status}: {text}")
+        self.status = status
+
+
+def load_library(path: Optional[str] = None):
+    """dlopen libpbz.so and declare every entry point.  Raises if the library has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2406_11209_amd.build` "
+                           "(there is no fallback implementation)")
+    lib = ctypes.CDLL(path)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().pbz_status_string(int(status)).decode()
+
+
+def check(status: int) -> None:
+    if status != 0:
+        raise PbzError(status, status_string(status))
+
+
+def _shape_arr(shape: Sequence[int]):
+    return (_c.c_int64 * len(shape))(*[int(v) for v in shape])
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _ftype_of(t) -> int:
+    torch = _torch()
+    return {torch.float64: PBZ_F64, torch.float32: PBZ_F32, torch.bfloat16: PBZ_BF16, torch.float16: PBZ_F16}[t.dtype]
+
+
+def _torch_ftype(code: int):
+    torch = _torch()
+    return {PBZ_F64: torch.float64, PBZ_F32: torch.float32, PBZ_BF16: torch.bfloat16, PBZ_F16: torch.float16}[code]
+
+
+def _torch_itype(code: int):
+    torch = _torch()
+    return {PBZ_I8: torch.int8, PBZ_I16: torch.int16, PBZ_I32: torch.int32}[code]
+
+
+def _ptr(t) -> int:
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("pbz takes contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return _torch().cuda.current_stream().cuda_stream
+
+
+@dataclass(frozen=True)
+class Layout:
+    n_blocks: int
+    kept_per_block: int
+    n_bytes: int
+    f_bytes: int
+    workspace_bytes: int
+
+
+class Codec:
+    """Compression settings (block shape, working float type, index type, mask); owns a pbz_codec."""
+
+    def __init__(self, block_shape: Sequence[int], work_type: str = "f32", index_type="i8",
+                 mask: Optional[np.ndarray] = None):
+        self._lib = load_library()
+        self._h = _p()
+        self.block_shape = tuple(int(v) for v in block_shape)
+        self.work_type = FTYPES[work_type] if isinstance(work_type, str) else int(work_type)
+        self.index_type = ITYPES[index_type]   # "i8".."i64" or the bit count
+        m = None
+        if mask is not None:
+            mm = np.ascontiguousarray(np.asarray(mask).reshape(-1) != 0, dtype=np.uint8)
+            if mm.size != int(np.prod(self.block_shape)):
+                raise ValueError("mask must have the block's shape")
+            m = mm.ctypes.data_as(_c.POINTER(_c.c_uint8))
+        check(self._lib.pbz_codec_create(_c.byref(self._h), len(self.block_shape), _shape_arr(self.block_shape),
+                                         self.work_type, self.index_type, m))
+        self._ws = {}
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            self._lib.pbz_codec_destroy(h)
+
+    # ---- host-only calls -------------------------------------------------------------------
+    def set_kernel_path(self, path: int) -> None:
+        check(self._lib.pbz_codec_set_kernel_path(self._h, int(path)))
+
+    def layout(self, shape: Sequence[int]) -> Layout:
+        if len(shape) != len(self.block_shape):
+            raise ValueError("shape and block shape must have the same dimensionality")
+        nb, kp = _c.c_int64(), _c.c_int64()
+        n_b, f_b, w_b = _c.c_size_t(), _c.c_size_t(), _c.c_size_t()
+        check(self._lib.pbz_layout(self._h, _shape_arr(shape), _c.byref(nb), _c.byref(kp), _c.byref(n_b),
+                                   _c.byref(f_b), _c.byref(w_b)))
+        return Layout(nb.value, kp.value, n_b.value, f_b.value, w_b.value)
+
+    def compressed_bits(self, shape: Sequence[int]) -> int:
+        bits = _c.c_uint64()
+        check(self._lib.pbz_compressed_bits(self._h, _shape_arr(shape), _c.byref(bits)))
+        return bits.value
+
+    def kernel_name(self, op: str, shape: Sequence[int], array_type: str) -> Optional[str]:
+        res = self._lib.pbz_kernel_name(self._h, op.encode(), _shape_arr(shape), FTYPES[array_type])
+        return None if res is None else res.decode()
+
+    # ---- device memory plumbing ------------------------------------------------------------
+    def empty_compressed(self, shape: Sequence[int], device="cuda"):
+        torch = _torch()
+        lay = self.layout(shape)
+        N = torch.empty(lay.n_blocks, dtype=_torch_ftype(self.work_type), device=device)
+        F = torch.empty((lay.n_blocks, lay.kept_per_block), dtype=_torch_itype(self.index_type), device=device)
+        return N, F
+
+    def workspace(self, device):
+        torch = _torch()
+        key = (device.type, device.index)
+        if key not in self._ws:
+            self._ws[key] = torch.empty(self.layout([1] * len(self.block_shape)).workspace_bytes, dtype=torch.uint8,
+                                        device=device)
+        return self._ws[key]
+
+    # ---- codec -----------------------------------------------------------------------------
+    def compress(self, x, N=None, F=None):
+        """pbz_compress: x (device tensor) -> (N, F)."""
+        if N is None or F is None:
+            N, F = self.empty_compressed(x.shape, x.device)
+        check(self._lib.pbz_compress(self._h, _ptr(x), _ftype_of(x), _shape_arr(x.shape), _ptr(N), _ptr(F), _stream()))
+        return N, F
+
+    def decompress(self, N, F, shape: Sequence[int], dtype=None, out=None):
+        """pbz_decompress: (N, F) -> array of `shape` in `dtype` (a torch dtype; default: the working type)."""
+        torch = _torch()
+        if out is None:
+            out = torch.empty(tuple(int(v) for v in shape), dtype=dtype or _torch_ftype(self.work_type), device=N.device)
+        check(self._lib.pbz_decompress(self._h, _ptr(N), _ptr(F), _shape_arr(shape), _ptr(out), _ftype_of(out), _stream()))
+        return out
+
+    # ---- element-wise operations -------------------------------------------------------------
+    def negate(self, F, out=None):
+        out = _torch().empty_like(F) if out is None else out
+        check(self._lib.pbz_negate(self._h, F.shape[0], _ptr(F), _ptr(out), _stream()))
+        return out
+
+    def mul_scalar(self, N, F, x: float, N_out=None, F_out=None):
+        torch = _torch()
+        N_out = torch.empty_like(N) if N_out is None else N_out
+        F_out = torch.empty_like(F) if F_out is None else F_out
+        check(self._lib.pbz_mul_scalar(self._h, F.shape[0], _ptr(N), _ptr(F), float(x), _ptr(N_out), _ptr(F_out), _stream()))
+        return N_out, F_out
+
+    def add(self, N1, F1, N2, F2, N_out=None, F_out=None):
+        torch = _torch()
+        N_out = torch.empty_like(N1) if N_out is None else N_out
+        F_out = torch.empty_like(F1) if F_out is None else F_out
+        check(self._lib.pbz_add(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), _ptr(N_out), _ptr(F_out),
+                                _stream()))
+        return N_out, F_out
+
+    # ---- reductions (each returns a 1-element float64 device tensor) --------------------------
+    def _reduce2(self, fn, N1, F1, N2, F2, out):
+        torch = _torch()
+        out = torch.empty(1, dtype=torch.float64, device=N1.device) if out is None else out
+        ws = self.workspace(N1.device)
+        check(fn(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
+
+    def _reduce1(self, fn, N, F, out):
+        torch = _torch()
+        out = torch.empty(1, dtype=torch.float64, device=N.device) if out is None else out
+        ws = self.workspace(N.device)
+        check(fn(self._h, F.shape[0], _ptr(N), _ptr(F), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
+
+    def dot(self, N1, F1, N2, F2, out=None):
+        return self._reduce2(self._lib.pbz_dot, N1, F1, N2, F2, out)
+
+    def covariance(self, N1, F1, N2, F2, out=None):
+        return self._reduce2(self._lib.pbz_covariance, N1, F1, N2, F2, out)
+
+    def cosine_similarity(self, N1, F1, N2, F2, out=None):
+        return self._reduce2(self._lib.pbz_cosine_similarity, N1, F1, N2, F2, out)
+
+    def norm2(self, N, F, out=None):
+        return self._reduce1(self._lib.pbz_norm2, N, F, out)
+
+    def mean(self, N, F, out=None):
+        return self._reduce1(self._lib.pbz_mean, N, F, out)
+
+    def variance(self, N, F, out=None):
+        return self._reduce1(self._lib.pbz_variance, N, F, out)

@@ -1,0 +1,97 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <mutex>
+
+#include "pbz.h"
+
+namespace pbz {
+
+constexpr int kMaxDevices = 16;
+constexpr int kReducePartialSlots = 8;      // doubles per workgroup partial
+constexpr int kReduceMaxGroups = 2048;      // upper bound on reduction workgroups
+constexpr size_t kWorkspaceBytes = size_t(kReduceMaxGroups) * kReducePartialSlots * sizeof(double);
+
+// Per-device constant tables, created lazily at the first launch.
+struct DeviceTables {
+  bool ready = false;
+  double* H = nullptr;          // concatenated forward matrices H_d[m][q], row-major, one per dimension
+  int32_t* kept_pos = nullptr;  // [vol] position in F of intra-block entry j, or -1 when pruned
+};
+
+}  // namespace pbz
+
+struct pbz_codec {
+  int ndim;
+  int64_t block[PBZ_MAX_NDIM];
+  int vol;              // prod(block)
+  pbz_ftype ftype;      // working type f: storage type of N
+  pbz_itype itype;
+  int index_bits;
+  double r;             // index radius 2^(bits-1) - 1
+  bool compute_f64;     // transform and binning precision
+  uint8_t* mask;        // [vol] 0/1
+  int32_t* kept_pos;    // [vol]
+  int kept;             // sum(P)
+  bool dc_kept;
+  int box[PBZ_MAX_NDIM];  // mask == low-frequency corner box of these extents (box[0] = 0 when it is not)
+  int h_offset[PBZ_MAX_NDIM];
+  int h_total;
+  double* H_host;       // concatenated matrices
+  pbz_kernel_path path;
+  mutable std::mutex mu;
+  mutable pbz::DeviceTables dev[pbz::kMaxDevices];
+};
+
+namespace pbz {
+
+inline int ftype_bytes(int t) { return t == PBZ_F64 ? 8 : t == PBZ_F32 ? 4 : 2; }
+inline int itype_bytes(int t) { return 1 << t; }
+
+// Geometry of one compress / decompress call, passed to kernels by value.
+struct Geom {
+  int ndim;
+  int vol;
+  int kept;
+  int pad_;
+  int64_t n_blocks;
+  int64_t shape[PBZ_MAX_NDIM];
+  int64_t stride[PBZ_MAX_NDIM];
+  int64_t grid[PBZ_MAX_NDIM];
+  int32_t block[PBZ_MAX_NDIM];
+  int32_t h_offset[PBZ_MAX_NDIM];
+};
+
+int ensure_tables(const pbz_codec* c, const DeviceTables** out);
+
+// generic kernels (any ndim, any power-of-two block shape within the limits, any types)
+int launch_compress_generic(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* x, int xtype,
+                            void* N, void* F, hipStream_t s);
+int launch_decompress_generic(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* N,
+                              const void* F, void* y, int ytype, hipStream_t s);
+
+// specialised codec kernels; return 1 when they handled the call, 0 when the shape / types are not
+// covered (caller falls back to the generic kernels), negative on a HIP error
+int try_compress_fast(const pbz_codec* c, const Geom& g, const void* x, int xtype, void* N, void* F,
+                      hipStream_t s, bool dry_run, const char** name);
+int try_decompress_fast(const pbz_codec* c, const Geom& g, const void* N, const void* F, void* y, int ytype,
+                        hipStream_t s, bool dry_run, const char** name);
+
+// element-wise compressed-space operations
+int launch_negate(const pbz_codec* c, int64_t n_blocks, const void* Fin, void* Fout, hipStream_t s);
+int launch_mul_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x,
+                      void* Nout, void* Fout, hipStream_t s);
+int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+               const void* F2, void* Nout, void* Fout, hipStream_t s);
+
+enum ReduceOp { kDot = 0, kNorm2 = 1, kCosine = 2, kMean = 3, kCovariance = 4, kVariance = 5 };
+int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1,
+                  const void* N2, const void* F2, double* out, void* workspace, hipStream_t s);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? PBZ_OK : PBZ_ERR_HIP; }
+
+}  // namespace pbz

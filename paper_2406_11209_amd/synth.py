@@ -149,7 +149,9 @@ def full_shape(config: int) -> Tuple[int, ...]:
     return _FULL_SHAPES[config]
 
 
-def _cast(x64: np.ndarray, dtype: str) -> np.ndarray:
+def _cast(x64: Optional[np.ndarray], dtype: str) -> Optional[np.ndarray]:
+    if x64 is None:
+        return None
     if dtype == "f64":
         return x64
     if dtype == "f32":
@@ -159,17 +161,19 @@ def _cast(x64: np.ndarray, dtype: str) -> np.ndarray:
     raise ValueError(dtype)
 
 
-def make_workload(config: int, shape: Optional[Sequence[int]] = None) -> Workload:
+def make_workload(config: int, shape: Optional[Sequence[int]] = None, second: bool = True) -> Workload:
     """Workload ``config`` (1..5), at its full shape or at ``shape`` (same recipe, fewer
     elements; bump counts are kept, so reduced shapes are denser in bumps).
 
-    Array A uses seed BASE_SEED + 10 * config, the second operand B uses that seed + 1.
+    Array A uses seed BASE_SEED + 10 * config, the second operand B uses that seed + 1
+    (``second=False`` skips generating B and leaves it None).
     """
     shape = tuple(int(v) for v in (shape if shape is not None else _FULL_SHAPES[config]))
     seeds = (BASE_SEED + 10 * config, BASE_SEED + 10 * config + 1)
 
     def two(fn):
-        return tuple(fn(np.random.Generator(np.random.PCG64(s))) for s in seeds)
+        a = fn(np.random.Generator(np.random.PCG64(seeds[0])))
+        return a, (fn(np.random.Generator(np.random.PCG64(seeds[1]))) if second else None)
 
     if config == 1:
         A, B = two(lambda g: add_noise(bump_field(shape, 16, g), 0.01, g))
@@ -183,14 +187,14 @@ def make_workload(config: int, shape: Optional[Sequence[int]] = None) -> Workloa
         # A = surface-height-like series h_t; B = a small zero-mean velocity-like series.
         gA, gB = (np.random.Generator(np.random.PCG64(s)) for s in seeds)
         A = drifting_series(shape[0], shape[1:], 32, gA, base=1.0, scale=0.1)
-        B = drifting_series(shape[0], shape[1:], 32, gB, base=0.0, scale=0.05)
+        B = drifting_series(shape[0], shape[1:], 32, gB, base=0.0, scale=0.05) if second else None
         return Workload("cfg3_series_f32_b1x16x16_i8", shape, (1, 16, 16), "f32", "f32", 8, None,
                         _cast(A, "f32"), _cast(B, "f32"))
     if config == 4:
         A, B = two(lambda g: add_noise(bump_field(shape, 64, g), 1e-3, g))
         return Workload("cfg4_3d_f64_b4x4x4_i16", shape, (4, 4, 4), "f64", "f64", 16, None, A, B)
     if config == 5:
-        A, B = two(lambda g: _cast(add_noise(bump_field(shape, 64, g), 1e-3, g), "bf16"))
+        A, B = two(lambda g: _cast(add_noise(bump_field(shape, 64, g), 1e-3, g), "bf16"))   # cast early: 4 GiB in FP64
         return Workload("cfg5_3d_bf16_b8x8x8_i8_mask4x4x4", shape, (8, 8, 8), "bf16", "f32", 8,
                         low_frequency_mask((8, 8, 8), (4, 4, 4)), A, B)
     raise ValueError("config must be 1..5")

@@ -1,0 +1,206 @@
+"""Helpers of the GPU parity tests: run one workload through the HIP path and through the oracle, and
+compare to the stated tolerances.
+
+Tolerances
+----------
+* Indices: bit-exact, except that an entry whose pre-rounding value t (as the oracle computes it in FP64)
+  lies within TAU of a rounding boundary k + 1/2 may differ by one; at most 1e-4 of the entries may
+  differ at all.  TAU = r * u * (2 + sum(i)) with u the unit round-off of the precision the binning
+  decision is taken in (2^-24 when the kernels bin in FP32: working type FP32/16-bit with int8 indices;
+  2^-53 otherwise), the bound on how far a transform in that precision can move t.
+* N: relative 1e-6 (FP32 and 16-bit working types; one rounding of a value whose FP32 computation is
+  accurate to a few ulp) / 1e-13 (FP64).
+* Decompressed arrays and scalars: relative 1e-5 when the working type is FP32 or narrower, 1e-12 when
+  it is FP64; arrays relative to the array's largest magnitude, scalars relative to their own magnitude
+  plus a floor at the natural scale of a sum that cancels (||A|| ||B|| for dot and covariance, ...).
+* Decompress and every operation are compared on identical (N, F): the oracle is run on the compressed
+  arrays the GPU produced (a legitimately flipped tie moves a decoded coefficient by N/r, which would
+  swamp 1e-5 otherwise).
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+from oracle import pbz_oracle as po
+from paper_2406_11209_amd.api import Codec
+
+TORCH_DTYPE = {"f64": torch.float64, "f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+MAX_MISMATCH_FRACTION = 1e-4
+
+
+def value_tol(ftype: str) -> float:
+    return 1e-12 if ftype == "f64" else 1e-5
+
+
+def n_tol(ftype: str) -> float:
+    return {"f64": 1e-13, "f32": 1e-6, "f16": 1e-3, "bf16": 8e-3}[ftype]
+
+
+def bins_in_f32(ftype: str, index_bits: int) -> bool:
+    return ftype != "f64" and index_bits == 8
+
+
+def tie_band(block: Sequence[int], ftype: str, index_bits: int) -> float:
+    u = 2.0 ** -24 if bins_in_f32(ftype, index_bits) else 2.0 ** -53
+    return po.index_radius(index_bits) * u * (2 + sum(block))
+
+
+def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def to_host_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def oracle_compressed(N: torch.Tensor, F: torch.Tensor, shape, block, index_bits, ftype, mask) -> po.Compressed:
+    """The oracle's view of a compressed array that lives on the GPU (same bits)."""
+    P = np.ones(tuple(block), dtype=bool) if mask is None else np.asarray(mask, dtype=bool).reshape(tuple(block))
+    grid = po.block_grid(shape, block)
+    return po.Compressed(s=tuple(shape), i=tuple(block), N=to_host_f64(N).reshape(grid), F=F.cpu().numpy(), P=P,
+                         index_bits=index_bits, ftype=ftype)
+
+
+def check_indices(F_gpu: np.ndarray, F_ref: np.ndarray, t_ref: np.ndarray, tau: float, what: str = "F"):
+    assert F_gpu.shape == F_ref.shape, (F_gpu.shape, F_ref.shape)
+    diff = F_gpu.astype(np.int64) - F_ref.astype(np.int64)
+    bad = diff != 0
+    n_bad = int(bad.sum())
+    if n_bad == 0:
+        return 0
+    assert np.max(np.abs(diff)) <= 1, f"{what}: an index differs by more than 1"
+    frac = n_bad / diff.size
+    dist = np.abs(np.abs(t_ref[bad] - np.floor(t_ref[bad])) - 0.5)
+    assert np.all(dist <= tau), (f"{what}: {int((dist > tau).sum())} mismatches are not rounding ties "
+                                 f"(worst distance {dist.max():.3e} > band {tau:.3e})")
+    allowed = max(1.0 / diff.size, MAX_MISMATCH_FRACTION)
+    assert frac <= allowed, f"{what}: {n_bad} of {diff.size} indices differ ({frac:.2e} > {allowed:.2e})"
+    return n_bad
+
+
+def check_N(N_gpu: np.ndarray, N_ref: np.ndarray, ftype: str, what: str = "N"):
+    N_gpu = N_gpu.reshape(-1)
+    N_ref = N_ref.reshape(-1)
+    assert np.all(np.isfinite(N_gpu))
+    assert np.all(np.abs(N_gpu - N_ref) <= n_tol(ftype) * np.abs(N_ref)), \
+        f"{what}: worst relative error {np.max(np.abs(N_gpu - N_ref) / np.maximum(np.abs(N_ref), 1e-300)):.3e}"
+
+
+def check_array(y_gpu: np.ndarray, y_ref: np.ndarray, tol: float, what: str = "array"):
+    scale = float(np.max(np.abs(y_ref))) if y_ref.size else 0.0
+    err = float(np.max(np.abs(y_gpu - y_ref))) if y_ref.size else 0.0
+    assert err <= tol * scale + 1e-300, f"{what}: max error {err:.3e} > {tol:.0e} * {scale:.3e}"
+
+
+def check_scalar(got: float, want: float, tol: float, floor: float, what: str):
+    assert math.isfinite(got), what
+    assert abs(got - want) <= tol * abs(want) + tol * floor, \
+        f"{what}: got {got!r}, oracle {want!r}, |diff| {abs(got - want):.3e}"
+
+
+class Case:
+    """One array pair + settings, run through both implementations."""
+
+    def __init__(self, A: np.ndarray, B: Optional[np.ndarray], dtype: str, block, index_bits: int, ftype: str,
+                 mask: Optional[np.ndarray] = None, path: int = 0):
+        self.dtype, self.block, self.bits, self.ftype, self.mask = dtype, tuple(block), index_bits, ftype, mask
+        self.shape = tuple(A.shape)
+        self.codec = Codec(self.block, ftype, index_bits, mask)
+        if path:
+            self.codec.set_kernel_path(path)
+        self.hostA, self.hostB = A, B
+        self.xA = to_device(A, dtype)
+        self.xB = None if B is None else to_device(B, dtype)
+        self.tau = tie_band(self.block, ftype, index_bits)
+        self.tol = value_tol(ftype)
+
+    def host_f64(self, x: np.ndarray) -> np.ndarray:
+        if self.dtype == "bf16":
+            return po.bf16_bits_to_f64(x)
+        return np.asarray(x, dtype=np.float64)
+
+    # --- codec -------------------------------------------------------------------------------
+    def check_compress(self, which="A"):
+        x_dev = self.xA if which == "A" else self.xB
+        x_host = self.hostA if which == "A" else self.hostB
+        N, F = self.codec.compress(x_dev)
+        torch.cuda.synchronize()
+        ref = po.compress(self.host_f64(x_host), self.block, self.bits, self.ftype, self.mask)
+        check_N(to_host_f64(N), ref.N, self.ftype)
+        n_bad = check_indices(F.cpu().numpy(), ref.F, ref.t, self.tau)
+        return N, F, ref, n_bad
+
+    def oc(self, N, F) -> po.Compressed:
+        return oracle_compressed(N, F, self.shape, self.block, self.bits, self.ftype, self.mask)
+
+    def check_decompress(self, N, F, out_dtype: Optional[str] = None):
+        out_dtype = out_dtype or self.dtype
+        y = self.codec.decompress(N, F, self.shape, TORCH_DTYPE[out_dtype])
+        torch.cuda.synchronize()
+        ref = po.decompress(self.oc(N, F))
+        tol = self.tol
+        if out_dtype in ("bf16", "f16"):      # the output cast dominates: half an ulp of the output type
+            tol = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11}[out_dtype] * 1.01
+            err = np.abs(to_host_f64(y) - ref)
+            assert np.all(err <= tol * np.abs(ref) + self.tol * np.max(np.abs(ref)) + 1e-30), \
+                f"decompress[{out_dtype}]: worst {np.max(err):.3e}"
+        else:
+            check_array(to_host_f64(y), ref, tol, f"decompress[{out_dtype}]")
+        return y
+
+    # --- element-wise ops ------------------------------------------------------------------------
+    def check_negate(self, N, F):
+        G = self.codec.negate(F)
+        torch.cuda.synchronize()
+        assert np.array_equal(G.cpu().numpy(), po.negate(self.oc(N, F)).F)
+        return G
+
+    def check_mul_scalar(self, N, F, x: float):
+        N2, F2 = self.codec.mul_scalar(N, F, x)
+        torch.cuda.synchronize()
+        ref = po.multiply_scalar(self.oc(N, F), x)
+        assert np.array_equal(F2.cpu().numpy(), ref.F)
+        assert np.array_equal(to_host_f64(N2), ref.N.reshape(-1)), "mul_scalar: N must match bit for bit"
+        return N2, F2
+
+    def check_add(self, N1, F1, N2, F2):
+        N3, F3 = self.codec.add(N1, F1, N2, F2)
+        torch.cuda.synchronize()
+        ref = po.add(self.oc(N1, F1), self.oc(N2, F2))
+        # the kernel takes the printed operation order in FP64, like the oracle: ties included, exact
+        check_N(to_host_f64(N3), ref.N, self.ftype, "add.N")
+        check_indices(F3.cpu().numpy(), ref.F, ref.t, po.index_radius(self.bits) * 2.0 ** -50, "add.F")
+        return N3, F3
+
+    # --- reductions ------------------------------------------------------------------------------
+    def check_reductions(self, N1, F1, N2, F2, ops=("dot", "norm2", "cosine_similarity", "mean", "covariance", "variance")):
+        A, B = self.oc(N1, F1), self.oc(N2, F2)
+        na, nb = po.norm2(A), po.norm2(B)
+        n_el = float(A.n_blocks) * float(np.prod(self.block))
+        out = {}
+        for op in ops:
+            if op == "dot":
+                got, want, floor = self.codec.dot(N1, F1, N2, F2), po.dot(A, B), na * nb
+            elif op == "norm2":
+                got, want, floor = self.codec.norm2(N1, F1), na, 0.0
+            elif op == "cosine_similarity":
+                got, want, floor = self.codec.cosine_similarity(N1, F1, N2, F2), po.cosine_similarity(A, B), 1.0
+            elif op == "mean":
+                got, want, floor = self.codec.mean(N1, F1), po.mean(A), na / math.sqrt(n_el)
+            elif op == "covariance":
+                got, want, floor = self.codec.covariance(N1, F1, N2, F2), po.covariance(A, B), na * nb / n_el
+            elif op == "variance":
+                got, want, floor = self.codec.variance(N1, F1), po.variance(A), na * na / n_el
+            else:
+                raise ValueError(op)
+            torch.cuda.synchronize()
+            got = float(got.item())
+            check_scalar(got, want, self.tol, floor, op)
+            out[op] = got
+        return out

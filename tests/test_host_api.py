@@ -1,0 +1,144 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the header
+declares, validates arguments before touching a device, and does the layout / storage arithmetic of
+Sec. III-B and Sec. IV-C.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2406_11209_amd import api
+from paper_2406_11209_amd.api import Codec, PbzError
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "pbz.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pbz_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = api.load_library()
+    names = header_functions()
+    assert len(names) == 18
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(api.SIGNATURES) == names        # the binding covers exactly the header
+
+
+def test_status_strings():
+    for code in range(0, -12, -1):
+        assert api.status_string(code) not in ("", "unknown status")
+    assert api.status_string(-99) == "unknown status"
+
+
+def _create(ndim, block, ftype=api.PBZ_F32, itype=api.PBZ_I8, mask=None):
+    lib = api.load_library()
+    h = ctypes.c_void_p()
+    arr = (ctypes.c_int64 * max(1, len(block)))(*block)
+    m = None if mask is None else (ctypes.c_uint8 * len(mask))(*mask)
+    st = lib.pbz_codec_create(ctypes.byref(h), ndim, arr, ftype, itype, m)
+    if st == 0:
+        lib.pbz_codec_destroy(h)
+    return st
+
+
+def test_codec_create_validation():
+    assert _create(2, [8, 8]) == 0
+    assert _create(0, [8]) == -2
+    assert _create(9, [2] * 9) == -2
+    assert _create(2, [8, 6]) == -3              # not a power of two
+    assert _create(2, [0, 8]) == -3
+    assert _create(1, [512]) == -3               # extent limit
+    assert _create(2, [128, 64]) == -3           # volume limit
+    assert _create(2, [8, 8], ftype=7) == -4
+    assert _create(2, [8, 8], itype=api.PBZ_I64) == -4
+    assert _create(2, [2, 2], mask=[0, 0, 0, 0]) == -5
+    assert _create(2, [2, 2], mask=[0, 1, 0, 0]) == 0
+    lib = api.load_library()
+    assert lib.pbz_codec_create(None, 2, (ctypes.c_int64 * 2)(8, 8), 1, 0, None) == -1
+    lib.pbz_codec_destroy(None)                  # tolerated
+
+
+def test_layout_matches_survey_table():
+    rows = [((256, 256), (8, 8), "f32", "i8", None, 1024, 64, 4096, 65536),
+            ((4096, 4096), (8, 8), "f32", "i16", (4, 4), 262144, 16, 1048576, 8388608),
+            ((64, 1024, 1024), (1, 16, 16), "f32", "i8", None, 262144, 256, 1048576, 67108864),
+            ((512, 512, 512), (4, 4, 4), "f64", "i16", None, 2097152, 64, 16777216, 268435456),
+            ((1024, 1024, 512), (8, 8, 8), "f32", "i8", (4, 4, 4), 1048576, 64, 4194304, 67108864)]
+    for shape, block, ft, it, keep, nb, kept, nbytes, fbytes in rows:
+        mask = None
+        if keep:
+            mask = np.zeros(block, dtype=bool)
+            mask[tuple(slice(0, k) for k in keep)] = True
+        lay = Codec(block, ft, it, mask).layout(shape)
+        assert (lay.n_blocks, lay.kept_per_block, lay.n_bytes, lay.f_bytes) == (nb, kept, nbytes, fbytes)
+        assert lay.workspace_bytes >= 8 * 5
+
+
+def test_layout_ragged_and_errors():
+    c = Codec((2, 4), "f32", "i16")
+    lay = c.layout((3, 5))
+    assert (lay.n_blocks, lay.kept_per_block, lay.n_bytes, lay.f_bytes) == (4, 8, 16, 64)
+    with pytest.raises(PbzError) as e:
+        c.layout((3, 0))
+    assert e.value.status == -7
+    with pytest.raises(PbzError):
+        c.layout((2**40, 2**40))
+
+
+def test_compressed_bits_follow_the_papers_component_list(golden):
+    # Sec. IV-C example: (3,224,224), block 4^3, FP32 N, int16, no pruning -> ratio ~2.91; int8 + half pruned -> ~10.66
+    for s, u, i, f, ib, kept, want in golden("paper_compression_ratios.txt"):
+        s = tuple(int(v) for v in s.split(","))
+        i = tuple(int(v) for v in i.split(","))
+        mask = np.zeros(int(np.prod(i)), dtype=bool)
+        mask[: int(kept)] = True
+        c = Codec(i, {32: "f32", 64: "f64"}[int(f)], int(ib), mask)
+        bits = c.compressed_bits(s)
+        d, nb = len(s), 3136
+        assert bits == 4 + 64 * d + 64 + 64 * d + int(np.prod(i)) + int(f) * nb + int(ib) * int(kept) * nb
+        assert abs(int(u) * int(np.prod(s)) / bits - float(want)) < 0.01
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch():
+    lib = api.load_library()
+    c = Codec((8, 8), "f32", "i8")
+    h = c._h
+    shape = (ctypes.c_int64 * 2)(16, 16)
+    bad_shape = (ctypes.c_int64 * 2)(16, -1)
+    p = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
+    assert lib.pbz_compress(h, None, 1, shape, p, p, None) == -1
+    assert lib.pbz_compress(h, p, 9, shape, p, p, None) == -4
+    assert lib.pbz_compress(h, p, 1, bad_shape, p, p, None) == -7
+    assert lib.pbz_decompress(h, p, None, shape, p, 1, None) == -1
+    assert lib.pbz_decompress(h, p, p, shape, p, -1, None) == -4
+    assert lib.pbz_negate(h, 0, p, p, None) == -7
+    assert lib.pbz_negate(h, 4, None, p, None) == -1
+    assert lib.pbz_mul_scalar(h, 4, p, p, float("nan"), p, p, None) == -9
+    assert lib.pbz_mul_scalar(h, 4, p, p, float("inf"), p, p, None) == -9
+    assert lib.pbz_add(h, 4, p, p, p, None, p, p, None) == -1
+    assert lib.pbz_dot(h, 4, p, p, p, p, p, p, 16, None) == -8          # workspace too small
+    assert lib.pbz_dot(h, 4, p, p, p, p, p, ctypes.c_void_p(257), 1 << 20, None) == -8   # misaligned
+    assert lib.pbz_norm2(h, 4, p, p, None, p, 1 << 20, None) == -1
+    assert lib.pbz_dot(h, -3, p, p, p, p, p, p, 1 << 20, None) == -7
+    mask = np.ones((8, 8), dtype=bool)
+    mask[0, 0] = False
+    nodc = Codec((8, 8), "f32", "i8", mask)
+    for fn in (lib.pbz_mean, lib.pbz_variance):
+        assert fn(nodc._h, 4, p, p, p, p, 1 << 20, None) == -6
+    assert lib.pbz_covariance(nodc._h, 4, p, p, p, p, p, p, 1 << 20, None) == -6
+
+
+def test_kernel_name_and_path_switch():
+    c = Codec((8, 8), "f32", "i8")
+    assert c.kernel_name("compress", (64, 64), "f32") is not None
+    assert c.kernel_name("nonsense", (64, 64), "f32") is None
+    c.set_kernel_path(api.PBZ_PATH_GENERIC)
+    assert c.kernel_name("compress", (64, 64), "f32") == "generic"
+    assert c.kernel_name("decompress", (64, 64), "f32") == "generic"
+    with pytest.raises(PbzError):
+        c.set_kernel_path(5)
