@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+A "step" is one pass of every hot-path operation over one synthetic workload that is already resident
+in HBM: compress(A), decompress, negate, multiply by a scalar, add(A, B), dot, L2 norm, mean,
+covariance, variance, cosine similarity (B is compressed once, outside the timed region).  The default
+workload is the 512^3 FP64 volume with 4x4x4 blocks and int16 indices (the largest configuration whose
+operation list is exactly compress / decompress / dot / norm); `--config 5` selects the 1 GiB bfloat16
+volume, `--config 1..3` the smaller ones.
+
+Prints one JSON line:  value = GB/s of uncompressed input pushed through the whole step;  `ops` has the
+per-operation times (HIP events on the launch stream, inside the timed region), GB/s of uncompressed
+input (codec) or of compressed bytes read (reductions), GB/s of algorithmic bytes moved and that as a
+fraction of the 8 TB/s HBM peak;  `roofline` describes the dominant kernel (compress);  `cpu_baseline`
+is the FP64 numpy oracle timed on a bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, sample_shape):
+    """Time the oracle (as it stands) on a corner sub-array of A and B: the same step as the GPU's."""
+    from oracle import pbz_oracle as po
+    import threadpoolctl
+
+    sl = tuple(slice(0, s) for s in sample_shape)
+    a = wl.as_f64(np.ascontiguousarray(wl.A[sl]))
+    b = wl.as_f64(np.ascontiguousarray(wl.B[sl]))
+    cores = os.cpu_count() or 1
+    try:
+        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
+    except Exception:
+        pass
+    po.compress(a[tuple(slice(0, 2 * i) for i in wl.block)], wl.block, wl.index_bits, wl.ftype, wl.mask)  # warm-up
+    B = po.compress(b, wl.block, wl.index_bits, wl.ftype, wl.mask)
+    t0 = time.perf_counter()
+    A = po.compress(a, wl.block, wl.index_bits, wl.ftype, wl.mask)
+    t_compress = time.perf_counter() - t0
+    po.decompress(A)
+    po.negate(A)
+    po.multiply_scalar(A, -2.5)
+    po.add(A, B)
+    po.dot(A, B)
+    po.norm2(A)
+    po.mean(A)
+    po.covariance(A, B)
+    po.variance(A)
+    po.cosine_similarity(A, B)
+    dt = time.perf_counter() - t0
+    in_bytes = a.size * wl.elem_bytes
+    return {"value": in_bytes / dt / 1e9, "unit": "GB/s of uncompressed input through one whole step",
+            "cores": int(cores), "kind": "oracle",
+            "sample": "corner sub-array %s of the workload's A and B (%d elements), one step, %.1f s; "
+                      "compress alone %.3f GB/s" % ("x".join(map(str, sample_shape)), a.size, dt,
+                                                    in_bytes / t_compress / 1e9)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (blocks are independent; see DESIGN.md for how it "
+              "would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2406_11209_amd import synth
+    from paper_2406_11209_amd.api import Codec
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t_gen = time.perf_counter()
+    wl = synth.make_workload(args.config)
+    t_gen = time.perf_counter() - t_gen
+    tdt = {"f64": torch.float64, "f32": torch.float32, "bf16": torch.bfloat16}[wl.dtype]
+
+    def up(x):
+        if wl.dtype == "bf16":
+            return torch.from_numpy(x.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(x).to(dev)
+
+    xA, xB = up(wl.A), up(wl.B)
+    codec = Codec(wl.block, wl.ftype, wl.index_bits, wl.mask)
+    lay = codec.layout(wl.shape)
+    in_bytes = xA.numel() * xA.element_size()
+    comp_bytes = lay.n_bytes + lay.f_bytes
+
+    N1, F1 = codec.empty_compressed(wl.shape, dev)
+    N2, F2 = codec.compress(xB)
+    Nn, Fn = codec.empty_compressed(wl.shape, dev)   # outputs of the element-wise ops
+    y = torch.empty_like(xA)
+    scal = torch.empty(8, dtype=torch.float64, device=dev)
+    has_dc = wl.mask is None or bool(np.asarray(wl.mask).reshape(-1)[0])
+
+    # (name, callable, algorithmic bytes moved, bytes the headline GB/s is quoted on)
+    ops = [
+        ("compress", lambda: codec.compress(xA, N1, F1), in_bytes + comp_bytes, in_bytes),
+        ("decompress", lambda: codec.decompress(N1, F1, wl.shape, out=y), in_bytes + comp_bytes, in_bytes),
+        ("negate", lambda: codec.negate(F1, out=Fn), 2 * lay.f_bytes, lay.f_bytes),
+        ("mul_scalar", lambda: codec.mul_scalar(N1, F1, -2.5, N_out=Nn, F_out=Fn), 2 * comp_bytes, comp_bytes),
+        ("add", lambda: codec.add(N1, F1, N2, F2, N_out=Nn, F_out=Fn), 3 * comp_bytes, 2 * comp_bytes),
+        ("dot", lambda: codec.dot(N1, F1, N2, F2, out=scal[0:1]), 2 * comp_bytes, 2 * comp_bytes),
+        ("norm2", lambda: codec.norm2(N1, F1, out=scal[1:2]), comp_bytes, comp_bytes),
+        ("cosine_similarity", lambda: codec.cosine_similarity(N1, F1, N2, F2, out=scal[2:3]), 2 * comp_bytes,
+         2 * comp_bytes),
+    ]
+    if has_dc:
+        dc_bytes = lay.n_bytes + lay.n_blocks * (lay.f_bytes // (lay.n_blocks * lay.kept_per_block))
+        ops += [
+            ("mean", lambda: codec.mean(N1, F1, out=scal[3:4]), dc_bytes, dc_bytes),
+            ("covariance", lambda: codec.covariance(N1, F1, N2, F2, out=scal[4:5]), 2 * comp_bytes, 2 * comp_bytes),
+            ("variance", lambda: codec.variance(N1, F1, out=scal[5:6]), comp_bytes, comp_bytes),
+        ]
+
+    def step(events=None):
+        for i, (_, fn, _, _) in enumerate(ops):
+            if events is not None:
+                events[i][0].record()
+            fn()
+            if events is not None:
+                events[i][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    per_op = {}
+    for i, (name, _, moved, quoted) in enumerate(ops):
+        ms = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
+        per_op[name] = {"ms": round(ms, 4), "gbps": round(quoted / ms / 1e6, 1),
+                        "gbps_moved": round(moved / ms / 1e6, 1),
+                        "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    comp = per_op["compress"]
+    roofline = {"bound": "hbm", "kernel": codec.kernel_name("compress", wl.shape, wl.dtype),
+                "achieved": comp["gbps_moved"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(comp["gbps_moved"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": in_bytes + comp_bytes}
+
+    out = {
+        "metric": "compress/decompress GB/s + compressed dot/L2-norm GB/s; fraction of HBM peak",
+        "value": round(in_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s of uncompressed input through one whole hot-path step",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f64": "f64", "f32": "f32", "bf16": "f32"}[wl.dtype] if wl.index_bits == 8 or wl.ftype == "f64" else "f64",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "shape": list(wl.shape), "block": list(wl.block), "array_dtype": wl.dtype,
+                   "index_bits": wl.index_bits, "kept_per_block": lay.kept_per_block,
+                   "uncompressed_bytes": in_bytes, "compressed_bytes": comp_bytes,
+                   "input_generation_s": round(t_gen, 1)},
+        "ops": per_op,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        sample = {1: (256, 256), 2: (1024, 1024), 3: (2, 1024, 1024), 4: (128, 128, 128), 5: (128, 128, 128)}[args.config]
+        out["cpu_baseline"] = cpu_baseline(wl, sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

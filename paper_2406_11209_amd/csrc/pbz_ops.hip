@@ -119,6 +119,15 @@ __device__ __forceinline__ uint32_t pack_dword(const int* v) {
   return uint32_t(v[0]);
 }
 
+// F1 N1 + F2 N2 with both products and the sum rounded separately (Algorithm 2 as printed): a fused
+// multiply-add would skip one rounding and break A + (-A) == 0 when N has more than 37 significant bits.
+__device__ __forceinline__ double unfused_sum_of_products(double f1, double n1, double f2, double n2) {
+#pragma clang fp contract(off)
+  const double p1 = f1 * n1;
+  const double p2 = f2 * n2;
+  return p1 + p2;
+}
+
 template <int kIType>
 struct PerDword {
   static constexpr int value = kIType == PBZ_I8 ? 4 : kIType == PBZ_I16 ? 2 : 1;
@@ -224,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
         unpack_dword<kIType>(bw[w], fb);
 #pragma unroll
         for (int e = 0; e < kPer; ++e) {
-          double ce = __dadd_rn(__dmul_rn(fa[e], n1), __dmul_rn(fb[e], n2));
+          double ce = unfused_sum_of_products(fa[e], n1, fb[e], n2);
           c[w * kPer + e] = ce;
           m = fmax(m, fabs(ce));
         }
@@ -263,16 +272,16 @@ __global__ __launch_bounds__(64) void k_add_generic(const void* __restrict__ N1,
     const double n1 = load_float<double>(N1, ntype, k), n2 = load_float<double>(N2, ntype, k);
     double m = 0.0;
     for (int j = threadIdx.x; j < kept; j += 64) {
-      double ce = __dadd_rn(__dmul_rn(double(load_index(F1, itype, k * kept + j)), n1),
-                            __dmul_rn(double(load_index(F2, itype, k * kept + j)), n2));
+      double ce = unfused_sum_of_products(double(load_index(F1, itype, k * kept + j)), n1,
+                                          double(load_index(F2, itype, k * kept + j)), n2);
       m = fmax(m, fabs(ce));
     }
     for (int off = 32; off > 0; off >>= 1) m = fmax(m, __shfl_xor(m, off, 64));
     const double n = m / r;
     // F_out may alias an operand: every lane re-reads only the entries it then overwrites
     for (int j = threadIdx.x; j < kept; j += 64) {
-      double ce = __dadd_rn(__dmul_rn(double(load_index(F1, itype, k * kept + j)), n1),
-                            __dmul_rn(double(load_index(F2, itype, k * kept + j)), n2));
+      double ce = unfused_sum_of_products(double(load_index(F1, itype, k * kept + j)), n1,
+                                          double(load_index(F2, itype, k * kept + j)), n2);
       double t = n > 0.0 ? ce / n : 0.0;
       t = fmin(fmax(rint(t), -r), r);
       store_index(Fout, itype, k * kept + j, int64_t(t));

@@ -65,6 +65,32 @@ def bump_field(shape: Sequence[int], n_bumps: int, rng: np.random.Generator,
     return (head.T @ tail).reshape(shape)
 
 
+def noisy_bump_field(shape: Sequence[int], n_bumps: int, noise_sigma: float, rng: np.random.Generator,
+                     dtype: str) -> np.ndarray:
+    """bump_field(...) + N(0, noise_sigma) cast to ``dtype``, generated slab by slab along the first
+    dimension so that the 1 GiB volumes never exist in float64.  Draw order: all bump parameters first
+    (as in bump_field), then the noise in row-major order."""
+    shape = tuple(int(v) for v in shape)
+    d = len(shape)
+    mu = [rng.uniform(0.0, n, size=n_bumps) for n in shape]
+    sigma = rng.uniform(8.0, 32.0, size=n_bumps)
+    amp = rng.uniform(-1.0, 1.0, size=n_bumps)
+    tables = [_gauss_1d(shape[t], mu[t], sigma) for t in range(d)]
+    tail = tables[1]
+    for t in range(2, d):
+        tail = (tail[:, :, None] * tables[t][:, None, :]).reshape(n_bumps, -1)
+    head = (tables[0] * amp[:, None]).T                      # (shape[0], K)
+    row = tail.shape[1]
+    out = np.empty((shape[0], row), dtype={"f64": np.float64, "f32": np.float32, "bf16": np.uint16}[dtype])
+    step = max(1, (1 << 24) // row)
+    for lo in range(0, shape[0], step):
+        hi = min(shape[0], lo + step)
+        slab = head[lo:hi] @ tail
+        slab += noise_sigma * rng.standard_normal(slab.shape)
+        out[lo:hi] = to_bf16_bits(slab) if dtype == "bf16" else slab
+    return out.reshape(shape)
+
+
 def add_noise(x: np.ndarray, sigma: float, rng: np.random.Generator) -> np.ndarray:
     """x + N(0, sigma) (sigma is the standard deviation), in place, slab by slab."""
     flat = x.reshape(-1)
@@ -176,13 +202,12 @@ def make_workload(config: int, shape: Optional[Sequence[int]] = None, second: bo
         return a, (fn(np.random.Generator(np.random.PCG64(seeds[1]))) if second else None)
 
     if config == 1:
-        A, B = two(lambda g: add_noise(bump_field(shape, 16, g), 0.01, g))
-        return Workload("cfg1_2d_f32_b8x8_i8", shape, (8, 8), "f32", "f32", 8, None,
-                        _cast(A, "f32"), _cast(B, "f32"))
+        A, B = two(lambda g: noisy_bump_field(shape, 16, 0.01, g, "f32"))
+        return Workload("cfg1_2d_f32_b8x8_i8", shape, (8, 8), "f32", "f32", 8, None, A, B)
     if config == 2:
-        A, B = two(lambda g: add_noise(bump_field(shape, 256, g), 0.01, g))
+        A, B = two(lambda g: noisy_bump_field(shape, 256, 0.01, g, "f32"))
         return Workload("cfg2_2d_f32_b8x8_i16_mask4x4", shape, (8, 8), "f32", "f32", 16,
-                        low_frequency_mask((8, 8), (4, 4)), _cast(A, "f32"), _cast(B, "f32"))
+                        low_frequency_mask((8, 8), (4, 4)), A, B)
     if config == 3:
         # A = surface-height-like series h_t; B = a small zero-mean velocity-like series.
         gA, gB = (np.random.Generator(np.random.PCG64(s)) for s in seeds)
@@ -191,10 +216,10 @@ def make_workload(config: int, shape: Optional[Sequence[int]] = None, second: bo
         return Workload("cfg3_series_f32_b1x16x16_i8", shape, (1, 16, 16), "f32", "f32", 8, None,
                         _cast(A, "f32"), _cast(B, "f32"))
     if config == 4:
-        A, B = two(lambda g: add_noise(bump_field(shape, 64, g), 1e-3, g))
+        A, B = two(lambda g: noisy_bump_field(shape, 64, 1e-3, g, "f64"))
         return Workload("cfg4_3d_f64_b4x4x4_i16", shape, (4, 4, 4), "f64", "f64", 16, None, A, B)
     if config == 5:
-        A, B = two(lambda g: _cast(add_noise(bump_field(shape, 64, g), 1e-3, g), "bf16"))   # cast early: 4 GiB in FP64
+        A, B = two(lambda g: noisy_bump_field(shape, 64, 1e-3, g, "bf16"))
         return Workload("cfg5_3d_bf16_b8x8x8_i8_mask4x4x4", shape, (8, 8, 8), "bf16", "f32", 8,
                         low_frequency_mask((8, 8, 8), (4, 4, 4)), A, B)
     raise ValueError("config must be 1..5")
