@@ -6,7 +6,16 @@
 // linear copy on MI355X), transforms in registers with the even/odd-split DCT of pbz_dct.h, and writes
 // N and F.  There is no workgroup barrier anywhere; LDS, where used, is private to a wave.
 //
-// Family "lane": one lane owns one whole block (blocks of at most 64 elements: 8x8, 4x4x4).
+// Family "lane":   one lane owns one whole block (blocks of at most 64 elements: 8x8, 4x4x4).  Indices leave
+//                   through a wave-private LDS transpose when a block's F is 64 bytes or more, so that every
+//                   store instruction of the wave writes one contiguous span.
+// Family "quad16":  16x16 blocks, 16 blocks per wave.  Each lane first holds a 16-row x 4-column strip (the
+//                   column transform runs in registers), the wave exchanges through LDS, then each lane
+//                   holds four whole rows (row transform); rows leave as 16-byte pieces in linear order.
+// Family "oct8":    8x8x8 blocks of bfloat16 input, 8 blocks per wave.  Each lane first holds one z-plane of
+//                   a block (x and y transforms), the wave exchanges through LDS, then each lane holds one
+//                   y-row of all eight z-planes (z transform).  Decompression needs no exchange: every
+//                   lane rebuilds its own z-plane from the block's few kept coefficients.
 //
 // Preconditions checked on the host (otherwise the call falls back to the general kernels): the array
 // reduces to at most three dimensions (leading dimensions with block extent 1 fold into the slowest one),
@@ -116,6 +125,33 @@ __device__ __forceinline__ float abs_t<float>(float v) { return fabsf(v); }
 template <>
 __device__ __forceinline__ double abs_t<double>(double v) { return fabs(v); }
 
+// Orders this wave's LDS writes before its later LDS reads.  LDS operations of one wave execute in
+// order; the fences keep the compiler from moving accesses across, no workgroup barrier is involved.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ uint4 f4_bits(const float* v) {
+  return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+}
+__device__ __forceinline__ void bits_f4(const uint4& u, float* v) {
+  v[0] = __uint_as_float(u.x); v[1] = __uint_as_float(u.y); v[2] = __uint_as_float(u.z); v[3] = __uint_as_float(u.w);
+}
+
+// H[m][q] of the length-8 orthonormal DCT-II as a compile-time table (for lane-dependent rows)
+struct Dct8Table {
+  float h[8][8];
+  constexpr Dct8Table() : h{} {
+    for (int m = 0; m < 8; ++m)
+      for (int q = 0; q < 8; ++q)
+        h[m][q] = float((q == 0 ? dct::cx_sqrt(1.0 / 8.0) : dct::cx_sqrt(2.0 / 8.0)) *
+                        dct::cos_frac((long long)(2 * m + 1) * q, 8));
+  }
+};
+__constant__ Dct8Table c_dct8 = Dct8Table();
+
 // forward transform of a register-resident [BZ][BY][BX] block, one dimension after the other
 template <typename T, int BZ, int BY, int BX>
 __device__ __forceinline__ void forward_block(T* v) {
@@ -218,12 +254,32 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
     }
     w[kw] = IdxPack<IT>::pack(q);
   }
-  if (active) {
-    const int64_t block = (bz * g.gy + by) * g.gx + bx;
-    N[block] = NT(m);
-    uint4* dst = reinterpret_cast<uint4*>(F + block * KEPT);
+  const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 64;   // first block of this wave
+  if (active) N[block0 + lane] = NT(m);
+  constexpr int P = KW / 4;                                   // 16-byte pieces of F per block
+  if constexpr (P >= 4) {
+    // Lane-strided 16-byte stores 64 bytes or more apart run at about half the write bandwidth of linear
+    // ones, so the pieces are transposed through LDS first: lane l puts piece p at l*P + (p ^ (l % P)) (the XOR
+    // spreads the lanes over the banks), then the wave reads the staging area linearly and stores every
+    // piece to its place; the pieces one instruction stores are a permutation of one contiguous span.
+    __shared__ uint4 stage[4][64 * P];
+    uint4* st = stage[threadIdx.x >> 6];
 #pragma unroll
-    for (int k = 0; k < KW / 4; ++k) dst[k] = make_uint4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
+    for (int p = 0; p < P; ++p)
+      st[lane * P + (p ^ (lane & (P - 1)))] = make_uint4(w[4 * p], w[4 * p + 1], w[4 * p + 2], w[4 * p + 3]);
+    wave_lds_sync();
+    const int n_active = int(g.gx - tx * 64 < 64 ? g.gx - tx * 64 : 64);
+    uint4* dst = reinterpret_cast<uint4*>(F + block0 * KEPT);
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+      const int idx = j * 64 + lane;
+      const int src = idx / P, piece = (idx % P) ^ (src & (P - 1));
+      if (src < n_active) dst[src * P + piece] = st[idx];
+    }
+  } else if (active) {
+    uint4* dst = reinterpret_cast<uint4*>(F + (block0 + lane) * KEPT);
+#pragma unroll
+    for (int k = 0; k < P; ++k) dst[k] = make_uint4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
   }
 }
 
@@ -278,6 +334,286 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
         for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
       }
     }
+}
+
+
+// =====================================================================================================
+// Family "quad16": 2-D 16x16 blocks, FP32 arrays, FP32 arithmetic, int8 indices, nothing pruned
+// =====================================================================================================
+constexpr int kQuadRow = 65;   // uint4 per LDS row: 64 + 1 of padding so that column reads spread over the banks
+
+__global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float* __restrict__ x, float* __restrict__ N,
+                                                         int8_t* __restrict__ F) {
+  __shared__ uint4 lds[2][16 * kQuadRow];
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = int64_t(blockIdx.x) * 2 + (threadIdx.x >> 6);
+  if (wave >= g.n_tiles) return;
+  uint4* st = lds[threadIdx.x >> 6];
+  const int64_t tx = wave % g.tiles_x;
+  const int64_t rest = wave / g.tiles_x;
+  const int64_t by = rest % g.gy, bz = rest / g.gy;
+
+  // phase A: lane = (block b, column quarter q); strip of 16 rows x 4 columns; transform along y
+  {
+    const int b = lane >> 2, q = lane & 3;
+    const int64_t bx = tx * 16 + b;
+    const int64_t bxc = bx < g.gx ? bx : g.gx - 1;
+    float v[64];
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      const int64_t yy = by * 16 + yy0;
+      uint4 u = make_uint4(0u, 0u, 0u, 0u);
+      if (yy < g.Y) u = *reinterpret_cast<const uint4*>(x + (bz * g.Y + yy) * g.X + bxc * 16 + q * 4);
+      bits_f4(u, v + yy0 * 4);
+    }
+#pragma unroll
+    for (int xl = 0; xl < 4; ++xl) dct::forward<float, 16, 4>(v + xl);
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) st[yy0 * kQuadRow + lane] = f4_bits(v + yy0 * 4);
+  }
+  wave_lds_sync();
+  // phase B: lane = (row yrow, block group bsub); four whole rows, one from each of blocks 4j + bsub; transform along x
+  const int yrow = lane & 15, bsub = lane >> 4;
+  float u[64];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int xq = 0; xq < 4; ++xq) bits_f4(st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq], u + j * 16 + xq * 4);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) dct::forward<float, 16, 1>(u + j * 16);
+
+  const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 16;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(u[j * 16 + i]));
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));   // the 16 rows of the block
+    const float inv = m > 0.0f ? float(g.r) / m : 0.0f;
+    uint32_t w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      int q4[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) q4[e] = int(rintf(u[j * 16 + k * 4 + e] * inv));
+      w[k] = IdxPack<int8_t>::pack(q4);
+    }
+    const int blk = 4 * j + bsub;
+    if (tx * 16 + blk < g.gx) {
+      // piece index within the wave's span of F: blk * 16 + yrow == j * 64 + lane, linear in the lane
+      reinterpret_cast<uint4*>(F + (block0 + blk) * 256)[yrow] = make_uint4(w[0], w[1], w[2], w[3]);
+      if (yrow == 0) N[block0 + blk] = m;
+    }
+  }
+}
+
+__global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const float* __restrict__ N,
+                                                           const int8_t* __restrict__ F, float* __restrict__ y) {
+  __shared__ uint4 lds[2][16 * kQuadRow];
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = int64_t(blockIdx.x) * 2 + (threadIdx.x >> 6);
+  if (wave >= g.n_tiles) return;
+  uint4* st = lds[threadIdx.x >> 6];
+  const int64_t tx = wave % g.tiles_x;
+  const int64_t rest = wave / g.tiles_x;
+  const int64_t by = rest % g.gy, bz = rest / g.gy;
+  const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 16;
+  {
+    const int yrow = lane & 15, bsub = lane >> 4;
+    float u[64];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int64_t blk = 4 * j + bsub;
+      if (tx * 16 + blk >= g.gx) blk = g.gx - 1 - tx * 16;     // past the end: decode the last block again, stored nowhere
+      const uint4 f = reinterpret_cast<const uint4*>(F + (block0 + blk) * 256)[yrow];
+      const float scale = N[block0 + blk] / float(g.r);
+      const uint32_t w[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+      for (int i = 0; i < 16; ++i) u[j * 16 + i] = scale * float(IdxPack<int8_t>::get(w[i >> 2], i & 3));
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dct::inverse<float, 16, 1, 16>(u + j * 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int xq = 0; xq < 4; ++xq) st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq] = f4_bits(u + j * 16 + xq * 4);
+  }
+  wave_lds_sync();
+  const int b = lane >> 2, q = lane & 3;
+  const int64_t bx = tx * 16 + b;
+  float v[64];
+#pragma unroll
+  for (int yy0 = 0; yy0 < 16; ++yy0) bits_f4(st[yy0 * kQuadRow + lane], v + yy0 * 4);
+#pragma unroll
+  for (int xl = 0; xl < 4; ++xl) dct::inverse<float, 16, 4, 16>(v + xl);
+  if (bx < g.gx) {
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      const int64_t yy = by * 16 + yy0;
+      if (yy < g.Y) *reinterpret_cast<uint4*>(y + (bz * g.Y + yy) * g.X + bx * 16 + q * 4) = f4_bits(v + yy0 * 4);
+    }
+  }
+}
+
+// =====================================================================================================
+// Family "oct8": 3-D 8x8x8 blocks, bfloat16 arrays, FP32 arithmetic, int8 indices, low-frequency box kept
+// =====================================================================================================
+// LDS exchange layout: block b occupies 128 sixteen-byte slots ordered [y][z][half row]; the low four bits
+// of the slot are XORed with swz(b) ^ 2y so that both the plane-wise writes and the row-wise reads touch
+// sixteen different bank groups per sixteen lanes.
+__device__ __forceinline__ int oct_swz(int b) { return (b & 1) | ((b >> 1) << 2); }
+__device__ __forceinline__ int oct_slot(int b, int yy, int z, int h) {
+  return b * 128 + yy * 16 + (((z << 1) | h) ^ oct_swz(b) ^ (yy << 1));
+}
+
+template <int KZ, int KY, int KX>
+__global__ __launch_bounds__(128) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x, float* __restrict__ N,
+                                                       int8_t* __restrict__ F) {
+  static_assert(KX == 4 || KX == 8, "a kept row is one or two dwords of int8");
+  constexpr int KEPT = KZ * KY * KX;
+  __shared__ uint4 lds[2][8 * 128];
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = int64_t(blockIdx.x) * 2 + (threadIdx.x >> 6);
+  if (wave >= g.n_tiles) return;
+  uint4* st = lds[threadIdx.x >> 6];
+  const int64_t tx = wave % g.tiles_x;
+  const int64_t rest = wave / g.tiles_x;
+  const int64_t by = rest % g.gy, bz = rest / g.gy;
+
+  // phase A: lane = (plane z, block b); one 8x8 z-plane; transforms along x and y
+  {
+    const int z = lane >> 3, b = lane & 7;
+    const int64_t bx = tx * 8 + b;
+    const int64_t bxc = bx < g.gx ? bx : g.gx - 1;
+    const int64_t zz = bz * 8 + z;
+    float v[64];
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) {
+      const int64_t yy = by * 8 + yy0;
+      uint4 u = make_uint4(0u, 0u, 0u, 0u);
+      if (zz < g.Z && yy < g.Y) u = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 8);
+      Unpack<float, bf16_t>::run(u, v + yy0 * 8);
+    }
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) dct::forward<float, 8, 1>(v + yy0 * 8);
+#pragma unroll
+    for (int xx = 0; xx < 8; ++xx) dct::forward<float, 8, 8>(v + xx);
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) st[oct_slot(b, yy0, z, h)] = f4_bits(v + yy0 * 8 + h * 4);
+  }
+  wave_lds_sync();
+  // phase B: lane = (block bb, row j); the row y = j of all eight planes; transform along z
+  const int bb = lane >> 3, j = lane & 7;
+  float u[64];
+#pragma unroll
+  for (int z = 0; z < 8; ++z)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) bits_f4(st[oct_slot(bb, j, z, h)], u + z * 8 + h * 4);
+#pragma unroll
+  for (int xx = 0; xx < 8; ++xx) dct::forward<float, 8, 8>(u + xx);
+
+  float m = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) m = fmaxf(m, fabsf(u[i]));
+#pragma unroll
+  for (int off = 1; off < 8; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));     // the 8 rows of the block
+  const float inv = m > 0.0f ? float(g.r) / m : 0.0f;
+
+  // kept entries of this lane: z < KZ, x < KX when j < KY; staged in LDS at their position in the wave's span of F
+  wave_lds_sync();                       // everyone has read its phase-B data; the buffer can be reused
+  uint32_t* st32 = reinterpret_cast<uint32_t*>(st);
+  if (j < KY) {
+#pragma unroll
+    for (int z = 0; z < KZ; ++z)
+#pragma unroll
+      for (int k = 0; k < KX / 4; ++k) {
+        int q4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) q4[e] = int(rintf(u[z * 8 + k * 4 + e] * inv));
+        st32[(bb * KEPT + (z * KY + j) * KX) / 4 + k] = IdxPack<int8_t>::pack(q4);
+      }
+  }
+  wave_lds_sync();
+  const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 8;
+  constexpr int PIECES = 8 * KEPT / 16;            // 16-byte pieces of F per wave
+  constexpr int PPB = KEPT / 16;                   // per block
+  static_assert(KEPT % 16 == 0, "F blocks are whole 16-byte vectors");
+#pragma unroll
+  for (int p0 = 0; p0 < PIECES; p0 += 64) {
+    const int p = p0 + lane;
+    if (p < PIECES && tx * 8 + p / PPB < g.gx) reinterpret_cast<uint4*>(F + block0 * KEPT)[p] = st[p];
+  }
+  if (j == 0 && tx * 8 + bb < g.gx) N[block0 + bb] = m;
+}
+
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // hardware conversion, round to nearest even
+  float2v f = {a, b};
+  bf16x2 h = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+template <int KZ, int KY, int KX>
+__global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float* __restrict__ N,
+                                                         const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
+  constexpr int KEPT = KZ * KY * KX;
+  static_assert(KEPT % 16 == 0, "F blocks are whole 16-byte vectors");
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (wave >= g.n_tiles) return;
+  const int64_t tx = wave % g.tiles_x;
+  const int64_t rest = wave / g.tiles_x;
+  const int64_t by = rest % g.gy, bz = rest / g.gy;
+  const int z = lane >> 3, b = lane & 7;
+  const int64_t bx = tx * 8 + b;
+  const int64_t zz = bz * 8 + z;
+  if (bx >= g.gx || zz >= g.Z) return;
+  const int64_t block = (bz * g.gy + by) * g.gx + bx;
+
+  uint32_t w[KEPT / 4];
+#pragma unroll
+  for (int k = 0; k < KEPT / 16; ++k) {
+    const uint4 f = reinterpret_cast<const uint4*>(F + block * KEPT)[k];
+    w[4 * k] = f.x; w[4 * k + 1] = f.y; w[4 * k + 2] = f.z; w[4 * k + 3] = f.w;
+  }
+  // this lane's plane z of the inverse z transform: sum_q (N / r) H[z][q] C[q][.][.]
+  const float scale = N[block] / float(g.r);
+  float hz[KZ];
+#pragma unroll
+  for (int q = 0; q < KZ; ++q) hz[q] = scale * c_dct8.h[z][q];
+  float v[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) v[i] = 0.0f;
+#pragma unroll
+  for (int yy0 = 0; yy0 < KY; ++yy0)
+#pragma unroll
+    for (int xx = 0; xx < KX; ++xx) {
+      float acc = 0.0f;
+#pragma unroll
+      for (int q = 0; q < KZ; ++q) {
+        const int jf = (q * KY + yy0) * KX + xx;
+        acc += hz[q] * float(IdxPack<int8_t>::get(w[jf >> 2], jf & 3));
+      }
+      v[yy0 * 8 + xx] = acc;
+    }
+#pragma unroll
+  for (int xx = 0; xx < KX; ++xx) dct::inverse<float, 8, 8, KY>(v + xx);
+#pragma unroll
+  for (int yy0 = 0; yy0 < 8; ++yy0) dct::inverse<float, 8, 1, KX>(v + yy0 * 8);
+#pragma unroll
+  for (int yy0 = 0; yy0 < 8; ++yy0) {
+    const int64_t yy = by * 8 + yy0;
+    if (yy < g.Y) {
+      const float* r8 = v + yy0 * 8;
+      *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 8) =
+          make_uint4(pack_bf16x2(r8[0], r8[1]), pack_bf16x2(r8[2], r8[3]), pack_bf16x2(r8[4], r8[5]),
+                     pack_bf16x2(r8[6], r8[7]));
+    }
+  }
 }
 
 // ---- host side --------------------------------------------------------------------------------------
@@ -375,11 +711,73 @@ using Lane_f32_8x8_i16 = LaneKernel<double, float, int16_t, float, 1, 8, 8, 1, 8
 // 3-D 4x4x4, FP64 arrays, int16
 using Lane_f64_4x4x4_i16 = LaneKernel<double, double, int16_t, double, 4, 4, 4, 4, 4, 4>;
 
+// 2-D 16x16 FP32 int8, nothing pruned
+struct Quad16Kernel {
+  static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
+    return f.ok && !c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 1 &&
+           f.by == 16 && f.bx == 16 && f.kz == 1 && f.ky == 16 && f.kx == 16 && (f.g.X * 4) % 16 == 0;
+  }
+  static void prepare(FastGeom& g) {
+    g.tiles_x = (g.gx + 15) / 16;
+    g.n_tiles = g.gz * g.gy * g.tiles_x;
+  }
+  static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
+    prepare(g);
+    const int64_t groups = (g.n_tiles + 1) / 2;
+    if (groups > 0x7fffffff) return 0;
+    hipLaunchKernelGGL(k_compress_quad16, dim3(unsigned(groups)), dim3(128), 0, s, g, static_cast<const float*>(x),
+                       static_cast<float*>(N), static_cast<int8_t*>(F));
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+  static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
+    prepare(g);
+    const int64_t groups = (g.n_tiles + 1) / 2;
+    if (groups > 0x7fffffff) return 0;
+    hipLaunchKernelGGL(k_decompress_quad16, dim3(unsigned(groups)), dim3(128), 0, s, g, static_cast<const float*>(N),
+                       static_cast<const int8_t*>(F), static_cast<float*>(y));
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+};
+
+// 3-D 8x8x8 bfloat16 arrays, FP32 arithmetic and N, int8, box KZ x KY x KX kept
+template <int KZ, int KY, int KX>
+struct Oct8Kernel {
+  static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
+    return f.ok && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 8 &&
+           f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX && (f.g.X * 2) % 16 == 0;
+  }
+  static void prepare(FastGeom& g) {
+    g.tiles_x = (g.gx + 7) / 8;
+    g.n_tiles = g.gz * g.gy * g.tiles_x;
+  }
+  static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
+    prepare(g);
+    const int64_t groups = (g.n_tiles + 1) / 2;
+    if (groups > 0x7fffffff) return 0;
+    hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX>), dim3(unsigned(groups)), dim3(128), 0, s, g,
+                       static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F));
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+  static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
+    prepare(g);
+    const int64_t groups = (g.n_tiles + 3) / 4;
+    if (groups > 0x7fffffff) return 0;
+    hipLaunchKernelGGL((k_decompress_oct8<KZ, KY, KX>), dim3(unsigned(groups)), dim3(256), 0, s, g,
+                       static_cast<const float*>(N), static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+};
+using Oct8_box4 = Oct8Kernel<4, 4, 4>;
+using Oct8_full = Oct8Kernel<8, 8, 8>;
+
 #define PBZ_FOR_EACH_LANE_KERNEL(X)                        \
   X(Lane_f32_8x8_i8, "lane_f32_8x8_i8")                    \
   X(Lane_f32_8x8_i16_box4, "lane_f32_8x8_i16_box4x4")      \
   X(Lane_f32_8x8_i16, "lane_f32_8x8_i16")                  \
-  X(Lane_f64_4x4x4_i16, "lane_f64_4x4x4_i16")
+  X(Lane_f64_4x4x4_i16, "lane_f64_4x4x4_i16")          \
+  X(Quad16Kernel, "quad16_f32_16x16_i8")                   \
+  X(Oct8_box4, "oct8_bf16_8x8x8_i8_box4x4x4")              \
+  X(Oct8_full, "oct8_bf16_8x8x8_i8")
 
 }  // namespace
 
