@@ -31,10 +31,38 @@ namespace {
 struct FastGeom {
   int64_t Z, Y, X;        // array extents after folding
   int64_t gz, gy, gx;     // block grid
-  int64_t tiles_x;        // waves needed to cover gx blocks
-  int64_t n_tiles;
+  uint32_t tiles_x;       // waves needed to cover the gx blocks of one block row
+  uint32_t tiles_yx;      // gy * tiles_x: waves per z-slab of blocks
   double r;
 };
+
+// Which tile does this wave own?  Grid x runs over the tiles of one z-slab (kWaves per workgroup), grid y / z
+// over the slabs.  Everything here is uniform over the wave and 32-bit, so it compiles to a handful of
+// scalar instructions instead of 64-bit vector divisions.
+template <int kWaves>
+__device__ __forceinline__ bool decode_tile(const FastGeom& g, int64_t& tx, int64_t& by, int64_t& bz) {
+  const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t t = blockIdx.x * kWaves + w;
+  const uint32_t slab = blockIdx.y + blockIdx.z * gridDim.y;
+  if (t >= g.tiles_yx || slab >= g.gz) return false;
+  const uint32_t row = t / g.tiles_x;
+  tx = t - row * g.tiles_x;
+  by = row;
+  bz = slab;
+  return true;
+}
+
+// launch geometry shared by all kernels; false when the tile counts do not fit the grid limits
+inline bool tile_grid(FastGeom& g, int blocks_per_wave, int waves_per_group, dim3* grid) {
+  const int64_t tiles_x = (g.gx + blocks_per_wave - 1) / blocks_per_wave;
+  const int64_t tiles_yx = tiles_x * g.gy;
+  if (tiles_yx >= (int64_t(1) << 31) || g.gz > int64_t(65535) * 65535) return false;
+  g.tiles_x = uint32_t(tiles_x);
+  g.tiles_yx = uint32_t(tiles_yx);
+  const unsigned gy = unsigned(g.gz < 65535 ? g.gz : 65535);
+  *grid = dim3(unsigned((tiles_yx + waves_per_group - 1) / waves_per_group), gy, unsigned((g.gz + gy - 1) / gy));
+  return true;
+}
 
 // ---- element conversion ------------------------------------------------------------------------------
 template <typename T, typename XT>
@@ -195,7 +223,10 @@ __device__ __forceinline__ void inverse_block(T* v) {
 // =====================================================================================================
 // Family "lane": one lane = one block
 // =====================================================================================================
-template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX>
+// kRagged: the slow dimensions are not multiples of the block extents, so some block rows lie outside the
+// array.  Such rows are still loaded (from a clamped, valid address: a branch around a load would make the
+// compiler wait for all outstanding loads at the join) and zeroed afterwards.
+template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX, bool kRagged>
 __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __restrict__ x, NT* __restrict__ N,
                                                        IT* __restrict__ F) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
@@ -206,11 +237,8 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   static_assert(BX * sizeof(XT) % 16 == 0 && (KEPT * sizeof(IT)) % 16 == 0, "rows and F blocks are whole 16-byte vectors");
 
   const int lane = threadIdx.x & 63;
-  const int64_t wave = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
-  if (wave >= g.n_tiles) return;
-  const int64_t tx = wave % g.tiles_x;
-  const int64_t rest = wave / g.tiles_x;
-  const int64_t by = rest % g.gy, bz = rest / g.gy;
+  int64_t tx, by, bz;
+  if (!decode_tile<4>(g, tx, by, bz)) return;
   const int64_t bx = tx * 64 + lane;
   const bool active = bx < g.gx;
   const int64_t bxc = active ? bx : g.gx - 1;   // lanes past the end re-read the last block and store nothing
@@ -220,16 +248,28 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   for (int z = 0; z < BZ; ++z)
 #pragma unroll
     for (int y = 0; y < BY; ++y) {
-      const int64_t zz = bz * BZ + z, yy = by * BY + y;
-      if (zz < g.Z && yy < g.Y) {   // uniform over the wave
-        const uint4* p = reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * BX);
-#pragma unroll
-        for (int k = 0; k < RV; ++k) raw[(z * BY + y) * RV + k] = p[k];
-      } else {
-#pragma unroll
-        for (int k = 0; k < RV; ++k) raw[(z * BY + y) * RV + k] = make_uint4(0u, 0u, 0u, 0u);
+      int64_t zz = bz * BZ + z, yy = by * BY + y;
+      if constexpr (kRagged) {
+        zz = zz < g.Z ? zz : g.Z - 1;
+        yy = yy < g.Y ? yy : g.Y - 1;
       }
+      const uint4* p = reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * BX);
+#pragma unroll
+      for (int k = 0; k < RV; ++k) raw[(z * BY + y) * RV + k] = p[k];
     }
+  if constexpr (kRagged) {
+#pragma unroll
+    for (int z = 0; z < BZ; ++z)
+#pragma unroll
+      for (int y = 0; y < BY; ++y) {
+        const uint32_t keep = (bz * BZ + z < g.Z && by * BY + y < g.Y) ? 0xffffffffu : 0u;   // uniform over the wave
+#pragma unroll
+        for (int k = 0; k < RV; ++k) {
+          uint4& u = raw[(z * BY + y) * RV + k];
+          u.x &= keep; u.y &= keep; u.z &= keep; u.w &= keep;
+        }
+      }
+  }
   T v[VOL];
 #pragma unroll
   for (int i = 0; i < ROWS * RV; ++i) Unpack<T, XT>::run(raw[i], v + i * PER16);
@@ -283,7 +323,7 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   }
 }
 
-template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX>
+template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX, bool kRagged>
 __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* __restrict__ N, const IT* __restrict__ F,
                                                          XT* __restrict__ y) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
@@ -294,11 +334,8 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
   constexpr int PER = IdxPack<IT>::per;
 
   const int lane = threadIdx.x & 63;
-  const int64_t wave = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
-  if (wave >= g.n_tiles) return;
-  const int64_t tx = wave % g.tiles_x;
-  const int64_t rest = wave / g.tiles_x;
-  const int64_t by = rest % g.gy, bz = rest / g.gy;
+  int64_t tx, by, bz;
+  if (!decode_tile<4>(g, tx, by, bz)) return;
   const int64_t bx = tx * 64 + lane;
   if (bx >= g.gx) return;
   const int64_t block = (bz * g.gy + by) * g.gx + bx;
@@ -328,7 +365,7 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
 #pragma unroll
     for (int yy0 = 0; yy0 < BY; ++yy0) {
       const int64_t zz = bz * BZ + z, yy = by * BY + yy0;
-      if (zz < g.Z && yy < g.Y) {
+      if (!kRagged || (zz < g.Z && yy < g.Y)) {
         uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * BX);
 #pragma unroll
         for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
@@ -342,16 +379,14 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
 // =====================================================================================================
 constexpr int kQuadRow = 65;   // uint4 per LDS row: 64 + 1 of padding so that column reads spread over the banks
 
+template <bool kRagged>
 __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float* __restrict__ x, float* __restrict__ N,
                                                          int8_t* __restrict__ F) {
   __shared__ uint4 lds[2][16 * kQuadRow];
   const int lane = threadIdx.x & 63;
-  const int64_t wave = int64_t(blockIdx.x) * 2 + (threadIdx.x >> 6);
-  if (wave >= g.n_tiles) return;
+  int64_t tx, by, bz;
+  if (!decode_tile<2>(g, tx, by, bz)) return;
   uint4* st = lds[threadIdx.x >> 6];
-  const int64_t tx = wave % g.tiles_x;
-  const int64_t rest = wave / g.tiles_x;
-  const int64_t by = rest % g.gy, bz = rest / g.gy;
 
   // phase A: lane = (block b, column quarter q); strip of 16 rows x 4 columns; transform along y
   {
@@ -359,12 +394,20 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
     const int64_t bx = tx * 16 + b;
     const int64_t bxc = bx < g.gx ? bx : g.gx - 1;
     float v[64];
+    uint4 raw[16];
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
-      const int64_t yy = by * 16 + yy0;
-      uint4 u = make_uint4(0u, 0u, 0u, 0u);
-      if (yy < g.Y) u = *reinterpret_cast<const uint4*>(x + (bz * g.Y + yy) * g.X + bxc * 16 + q * 4);
-      bits_f4(u, v + yy0 * 4);
+      int64_t yy = by * 16 + yy0;
+      if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;     // rows past the end: load a valid row, zero it below
+      raw[yy0] = *reinterpret_cast<const uint4*>(x + (bz * g.Y + yy) * g.X + bxc * 16 + q * 4);
+    }
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      if constexpr (kRagged) {
+        const uint32_t keep = by * 16 + yy0 < g.Y ? 0xffffffffu : 0u;
+        raw[yy0].x &= keep; raw[yy0].y &= keep; raw[yy0].z &= keep; raw[yy0].w &= keep;
+      }
+      bits_f4(raw[yy0], v + yy0 * 4);
     }
 #pragma unroll
     for (int xl = 0; xl < 4; ++xl) dct::forward<float, 16, 4>(v + xl);
@@ -412,12 +455,9 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const flo
                                                            const int8_t* __restrict__ F, float* __restrict__ y) {
   __shared__ uint4 lds[2][16 * kQuadRow];
   const int lane = threadIdx.x & 63;
-  const int64_t wave = int64_t(blockIdx.x) * 2 + (threadIdx.x >> 6);
-  if (wave >= g.n_tiles) return;
+  int64_t tx, by, bz;
+  if (!decode_tile<2>(g, tx, by, bz)) return;
   uint4* st = lds[threadIdx.x >> 6];
-  const int64_t tx = wave % g.tiles_x;
-  const int64_t rest = wave / g.tiles_x;
-  const int64_t by = rest % g.gy, bz = rest / g.gy;
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 16;
   {
     const int yrow = lane & 15, bsub = lane >> 4;
@@ -467,33 +507,43 @@ __device__ __forceinline__ int oct_slot(int b, int yy, int z, int h) {
   return b * 128 + yy * 16 + (((z << 1) | h) ^ oct_swz(b) ^ (yy << 1));
 }
 
-template <int KZ, int KY, int KX>
+template <int KZ, int KY, int KX, bool kRagged>
 __global__ __launch_bounds__(128) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x, float* __restrict__ N,
                                                        int8_t* __restrict__ F) {
   static_assert(KX == 4 || KX == 8, "a kept row is one or two dwords of int8");
   constexpr int KEPT = KZ * KY * KX;
   __shared__ uint4 lds[2][8 * 128];
   const int lane = threadIdx.x & 63;
-  const int64_t wave = int64_t(blockIdx.x) * 2 + (threadIdx.x >> 6);
-  if (wave >= g.n_tiles) return;
+  int64_t tx, by, bz;
+  if (!decode_tile<2>(g, tx, by, bz)) return;
   uint4* st = lds[threadIdx.x >> 6];
-  const int64_t tx = wave % g.tiles_x;
-  const int64_t rest = wave / g.tiles_x;
-  const int64_t by = rest % g.gy, bz = rest / g.gy;
 
   // phase A: lane = (plane z, block b); one 8x8 z-plane; transforms along x and y
   {
     const int z = lane >> 3, b = lane & 7;
     const int64_t bx = tx * 8 + b;
     const int64_t bxc = bx < g.gx ? bx : g.gx - 1;
-    const int64_t zz = bz * 8 + z;
+    int64_t zz = bz * 8 + z;
+    uint32_t keep_z = 0xffffffffu;
+    if constexpr (kRagged) {
+      keep_z = zz < g.Z ? 0xffffffffu : 0u;      // planes / rows past the end: load a valid row, zero it below
+      zz = zz < g.Z ? zz : g.Z - 1;
+    }
     float v[64];
+    uint4 raw[8];
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
-      const int64_t yy = by * 8 + yy0;
-      uint4 u = make_uint4(0u, 0u, 0u, 0u);
-      if (zz < g.Z && yy < g.Y) u = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 8);
-      Unpack<float, bf16_t>::run(u, v + yy0 * 8);
+      int64_t yy = by * 8 + yy0;
+      if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;
+      raw[yy0] = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 8);
+    }
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) {
+      if constexpr (kRagged) {
+        const uint32_t keep = by * 8 + yy0 < g.Y ? keep_z : 0u;
+        raw[yy0].x &= keep; raw[yy0].y &= keep; raw[yy0].z &= keep; raw[yy0].w &= keep;
+      }
+      Unpack<float, bf16_t>::run(raw[yy0], v + yy0 * 8);
     }
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) dct::forward<float, 8, 1>(v + yy0 * 8);
@@ -563,11 +613,8 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float
   constexpr int KEPT = KZ * KY * KX;
   static_assert(KEPT % 16 == 0, "F blocks are whole 16-byte vectors");
   const int lane = threadIdx.x & 63;
-  const int64_t wave = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
-  if (wave >= g.n_tiles) return;
-  const int64_t tx = wave % g.tiles_x;
-  const int64_t rest = wave / g.tiles_x;
-  const int64_t by = rest % g.gy, bz = rest / g.gy;
+  int64_t tx, by, bz;
+  if (!decode_tile<4>(g, tx, by, bz)) return;
   const int z = lane >> 3, b = lane & 7;
   const int64_t bx = tx * 8 + b;
   const int64_t zz = bz * 8 + z;
@@ -682,24 +729,26 @@ struct LaneKernel {
            int(c->ftype) == xtype_code<NT>() && f.bz == BZ && f.by == BY && f.bx == BX && f.kz == KZ && f.ky == KY &&
            f.kx == KX && (f.g.X * sizeof(XT)) % 16 == 0;
   }
-  static void prepare(FastGeom& g) {
-    g.tiles_x = (g.gx + 63) / 64;
-    g.n_tiles = g.gz * g.gy * g.tiles_x;
-  }
   static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
-    prepare(g);
-    const int64_t groups = (g.n_tiles + 3) / 4;
-    if (groups > 0x7fffffff) return 0;
-    hipLaunchKernelGGL((k_compress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX>), dim3(unsigned(groups)), dim3(256), 0, s,
-                       g, static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F));
+    dim3 grid;
+    if (!tile_grid(g, 64, 4, &grid)) return 0;
+    if (g.Z % BZ || g.Y % BY)
+      hipLaunchKernelGGL((k_compress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, true>), grid, dim3(256), 0, s, g,
+                         static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F));
+    else
+      hipLaunchKernelGGL((k_compress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, false>), grid, dim3(256), 0, s, g,
+                         static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
-    prepare(g);
-    const int64_t groups = (g.n_tiles + 3) / 4;
-    if (groups > 0x7fffffff) return 0;
-    hipLaunchKernelGGL((k_decompress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX>), dim3(unsigned(groups)), dim3(256), 0,
-                       s, g, static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
+    dim3 grid;
+    if (!tile_grid(g, 64, 4, &grid)) return 0;
+    if (g.Z % BZ || g.Y % BY)
+      hipLaunchKernelGGL((k_decompress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, true>), grid, dim3(256), 0, s, g,
+                         static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
+    else
+      hipLaunchKernelGGL((k_decompress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, false>), grid, dim3(256), 0, s, g,
+                         static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
@@ -717,23 +766,21 @@ struct Quad16Kernel {
     return f.ok && !c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 1 &&
            f.by == 16 && f.bx == 16 && f.kz == 1 && f.ky == 16 && f.kx == 16 && (f.g.X * 4) % 16 == 0;
   }
-  static void prepare(FastGeom& g) {
-    g.tiles_x = (g.gx + 15) / 16;
-    g.n_tiles = g.gz * g.gy * g.tiles_x;
-  }
   static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
-    prepare(g);
-    const int64_t groups = (g.n_tiles + 1) / 2;
-    if (groups > 0x7fffffff) return 0;
-    hipLaunchKernelGGL(k_compress_quad16, dim3(unsigned(groups)), dim3(128), 0, s, g, static_cast<const float*>(x),
-                       static_cast<float*>(N), static_cast<int8_t*>(F));
+    dim3 grid;
+    if (!tile_grid(g, 16, 2, &grid)) return 0;
+    if (g.Y % 16)
+      hipLaunchKernelGGL(k_compress_quad16<true>, grid, dim3(128), 0, s, g, static_cast<const float*>(x),
+                         static_cast<float*>(N), static_cast<int8_t*>(F));
+    else
+      hipLaunchKernelGGL(k_compress_quad16<false>, grid, dim3(128), 0, s, g, static_cast<const float*>(x),
+                         static_cast<float*>(N), static_cast<int8_t*>(F));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
-    prepare(g);
-    const int64_t groups = (g.n_tiles + 1) / 2;
-    if (groups > 0x7fffffff) return 0;
-    hipLaunchKernelGGL(k_decompress_quad16, dim3(unsigned(groups)), dim3(128), 0, s, g, static_cast<const float*>(N),
+    dim3 grid;
+    if (!tile_grid(g, 16, 2, &grid)) return 0;
+    hipLaunchKernelGGL(k_decompress_quad16, grid, dim3(128), 0, s, g, static_cast<const float*>(N),
                        static_cast<const int8_t*>(F), static_cast<float*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
@@ -746,24 +793,22 @@ struct Oct8Kernel {
     return f.ok && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 8 &&
            f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX && (f.g.X * 2) % 16 == 0;
   }
-  static void prepare(FastGeom& g) {
-    g.tiles_x = (g.gx + 7) / 8;
-    g.n_tiles = g.gz * g.gy * g.tiles_x;
-  }
   static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
-    prepare(g);
-    const int64_t groups = (g.n_tiles + 1) / 2;
-    if (groups > 0x7fffffff) return 0;
-    hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX>), dim3(unsigned(groups)), dim3(128), 0, s, g,
-                       static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F));
+    dim3 grid;
+    if (!tile_grid(g, 8, 2, &grid)) return 0;
+    if (g.Z % 8 || g.Y % 8)
+      hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, true>), grid, dim3(128), 0, s, g, static_cast<const bf16_t*>(x),
+                         static_cast<float*>(N), static_cast<int8_t*>(F));
+    else
+      hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, false>), grid, dim3(128), 0, s, g, static_cast<const bf16_t*>(x),
+                         static_cast<float*>(N), static_cast<int8_t*>(F));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
-    prepare(g);
-    const int64_t groups = (g.n_tiles + 3) / 4;
-    if (groups > 0x7fffffff) return 0;
-    hipLaunchKernelGGL((k_decompress_oct8<KZ, KY, KX>), dim3(unsigned(groups)), dim3(256), 0, s, g,
-                       static_cast<const float*>(N), static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
+    dim3 grid;
+    if (!tile_grid(g, 8, 4, &grid)) return 0;
+    hipLaunchKernelGGL((k_decompress_oct8<KZ, KY, KX>), grid, dim3(256), 0, s, g, static_cast<const float*>(N),
+                       static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
