@@ -129,8 +129,9 @@ int pbz_mul_scalar(const pbz_codec* codec, int64_t n_blocks, const void* N_in, c
 int pbz_add(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
             const void* F2, void* N_out, void* F_out, void* stream);
 
-/* Reductions.  Each writes one FP64 scalar to out (device).  `workspace` is device scratch of at
- * least the size pbz_layout reports, 16-byte aligned; concurrent calls must use distinct workspaces.
+/* Reductions.  Each writes one FP64 scalar to out (device).  `workspace` is device scratch of at least the
+ * size pbz_layout reports, 16-byte aligned; its contents on entry do not matter.  Calls that may run
+ * concurrently must use distinct workspaces.
  *   pbz_dot                Algorithm 6   sum(C1 . C2)
  *   pbz_norm2              Algorithm 10  ||C||_2
  *   pbz_cosine_similarity  Algorithm 11  dot / (||A|| ||B||)

@@ -13,7 +13,7 @@ namespace pbz {
 
 constexpr int kMaxDevices = 16;
 constexpr int kReducePartialSlots = 8;      // doubles per workgroup partial
-constexpr int kReduceMaxGroups = 2048;      // upper bound on reduction workgroups
+constexpr int kReduceMaxGroups = 4096;      // upper bound on reduction workgroups
 constexpr size_t kWorkspaceBytes = size_t(kReduceMaxGroups) * kReducePartialSlots * sizeof(double);
 
 // Per-device constant tables, created lazily at the first launch.

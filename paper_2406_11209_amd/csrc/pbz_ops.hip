@@ -137,19 +137,34 @@ struct PerDword {
 // Algorithm 1 (and the F part of Algorithm 5): F_out = sign * F_in over 16-byte vectors
 // ---------------------------------------------------------------------------------------------
 template <int kIType, int kSign>
+__device__ __forceinline__ uint4 apply_sign(uint4 a) {
+  if (kSign == 0) return make_uint4(0u, 0u, 0u, 0u);
+  if (kSign < 0) {
+    a.x = negate_packed<kIType>(a.x);
+    a.y = negate_packed<kIType>(a.y);
+    a.z = negate_packed<kIType>(a.z);
+    a.w = negate_packed<kIType>(a.w);
+  }
+  return a;
+}
+
+// Each workgroup streams one contiguous run of kThreads * kUnroll vectors: kUnroll independent loads per thread
+// (kThreads vectors apart), then the stores.
+template <int kIType, int kSign>
 __global__ __launch_bounds__(kThreads) void k_scale_sign_vec(const uint4* __restrict__ in, uint4* __restrict__ out,
                                                              int64_t nvec) {
-  const int64_t nthreads = int64_t(gridDim.x) * kThreads;
-  for (int64_t v = int64_t(blockIdx.x) * kThreads + threadIdx.x; v < nvec; v += nthreads) {
-    uint4 a = make_uint4(0u, 0u, 0u, 0u);
-    if (kSign != 0) a = in[v];
-    if (kSign < 0) {
-      a.x = negate_packed<kIType>(a.x);
-      a.y = negate_packed<kIType>(a.y);
-      a.z = negate_packed<kIType>(a.z);
-      a.w = negate_packed<kIType>(a.w);
+  const int64_t base = int64_t(blockIdx.x) * (kThreads * kUnroll) + threadIdx.x;
+  if (base + (kUnroll - 1) * kThreads < nvec) {
+    uint4 a[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) a[u] = kSign != 0 ? in[base + u * kThreads] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) out[base + u * kThreads] = apply_sign<kIType, kSign>(a[u]);
+  } else {
+    for (int u = 0; u < kUnroll; ++u) {
+      const int64_t v = base + u * kThreads;
+      if (v < nvec) out[v] = apply_sign<kIType, kSign>(kSign != 0 ? in[v] : make_uint4(0u, 0u, 0u, 0u));
     }
-    out[v] = a;
   }
 }
 
@@ -162,7 +177,8 @@ __global__ __launch_bounds__(kThreads) void k_scale_sign_scalar(const void* __re
 
 template <int kSign>
 void launch_sign_vec(int itype, const void* in, void* out, int64_t nvec, hipStream_t s) {
-  dim3 grid(stream_groups(nvec, 2)), block(kThreads);
+  const int64_t per_group = int64_t(kThreads) * kUnroll;
+  dim3 grid(static_cast<unsigned>((nvec + per_group - 1) / per_group)), block(kThreads);
   const uint4* i4 = static_cast<const uint4*>(in);
   uint4* o4 = static_cast<uint4*>(out);
   if (itype == PBZ_I8)
@@ -204,11 +220,17 @@ __global__ __launch_bounds__(kThreads) void k_scale_N(const void* __restrict__ i
 // C = F1 N1 + F2 N2 (each product and the sum rounded separately), N = max|C| / r, F = rint(C / N).
 // A block occupies kLanes consecutive lanes, 16 bytes of F per lane.
 // ---------------------------------------------------------------------------------------------
-template <int kIType>
+template <int kNType>
+__device__ __forceinline__ double load_N(const void* N, int64_t k) {
+  if (kNType == PBZ_F64) return static_cast<const double*>(N)[k];
+  return double(static_cast<const float*>(N)[k]);
+}
+
+template <int kIType, int kNType>
 __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                       const void* __restrict__ N2, const uint4* __restrict__ F2,
-                                                      void* __restrict__ Nout, uint4* __restrict__ Fout, int ntype,
-                                                      double r, int64_t nvec, int lanes_shift) {
+                                                      void* __restrict__ Nout, uint4* __restrict__ Fout, double r,
+                                                      int64_t nvec, int lanes_shift) {
   constexpr int kPer = PerDword<kIType>::value;
   constexpr int kElems = 4 * kPer;
   const int lanes = 1 << lanes_shift;
@@ -219,46 +241,52 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
   for (int64_t base = wave_first; base < nvec; base += nthreads) {
     const int64_t v = base + (threadIdx.x & 63);
     const bool live = v < nvec;
-    const int64_t k = v >> lanes_shift;
+    const int64_t vc = live ? v : nvec - 1;      // lanes past the end redo the last vector and store nothing
+    const int64_t k = vc >> lanes_shift;
+    const uint4 a = F1[vc], b = F2[vc];
+    const double n1 = load_N<kNType>(N1, k), n2 = load_N<kNType>(N2, k);
     double c[kElems];
     double m = 0.0;
-    if (live) {
-      const uint4 a = F1[v], b = F2[v];
-      const double n1 = load_float<double>(N1, ntype, k), n2 = load_float<double>(N2, ntype, k);
-      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        double fa[kPer], fb[kPer];
-        unpack_dword<kIType>(aw[w], fa);
-        unpack_dword<kIType>(bw[w], fb);
+    for (int w = 0; w < 4; ++w) {
+      double fa[kPer], fb[kPer];
+      unpack_dword<kIType>(aw[w], fa);
+      unpack_dword<kIType>(bw[w], fb);
 #pragma unroll
-        for (int e = 0; e < kPer; ++e) {
-          double ce = unfused_sum_of_products(fa[e], n1, fb[e], n2);
-          c[w * kPer + e] = ce;
-          m = fmax(m, fabs(ce));
-        }
+      for (int e = 0; e < kPer; ++e) {
+        const double ce = unfused_sum_of_products(fa[e], n1, fb[e], n2);
+        c[w * kPer + e] = ce;
+        m = fmax(m, fabs(ce));
       }
-    } else {
-#pragma unroll
-      for (int e = 0; e < kElems; ++e) c[e] = 0.0;
     }
     for (int off = lanes >> 1; off > 0; off >>= 1) m = fmax(m, __shfl_xor(m, off, 64));
-    if (live) {
-      const double n = m / r;
-      uint32_t ow[4];
+    const double n = m / r;
+    // F = rint(C / N).  C * (1 / N) is within two ulp of the correctly rounded quotient, so its rounding to
+    // an integer can differ only when it lands within 2^-50 |t| of a half-integer; only then is the real
+    // division carried out.  The result is bit-identical to dividing every element.
+    const double inv = n > 0.0 ? 1.0 / n : 0.0;
+    uint32_t ow[4];
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        int q[kPer];
+    for (int w = 0; w < 4; ++w) {
+      int q[kPer];
 #pragma unroll
-        for (int e = 0; e < kPer; ++e) {
-          double t = n > 0.0 ? c[w * kPer + e] / n : 0.0;
-          t = fmin(fmax(rint(t), -r), r);
-          q[e] = int(t);
-        }
-        ow[w] = pack_dword<kIType>(q);
+      for (int e = 0; e < kPer; ++e) {
+        const double t = c[w * kPer + e] * inv;
+        double tr = rint(t);
+        if (fabs(fabs(t - tr) - 0.5) <= fabs(t) * 0x1p-50) tr = rint(c[w * kPer + e] / n);
+        q[e] = int(fmin(fmax(tr, -r), r));
       }
+      ow[w] = pack_dword<kIType>(q);
+    }
+    if (live) {
       Fout[v] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-      if ((v & (lanes - 1)) == 0) store_float(Nout, ntype, k, n);
+      if ((v & (lanes - 1)) == 0) {
+        if (kNType == PBZ_F64)
+          static_cast<double*>(Nout)[k] = n;
+        else
+          static_cast<float*>(Nout)[k] = float(n);
+      }
     }
   }
 }
@@ -293,13 +321,36 @@ __global__ __launch_bounds__(64) void k_add_generic(const void* __restrict__ N1,
 // ---------------------------------------------------------------------------------------------
 // Reductions (Algorithms 6-11).  One streaming pass produces five FP64 sums per workgroup,
 //   S12 = sum_k N1_k N2_k sum_j F1_kj F2_kj     S11, S22 likewise     D1 = sum_k N1_k F1_k0   D2 likewise
-// (integer block sums are exact; the scale 1/r or 1/r^2 is applied once at the end), a second tiny
-// kernel adds the partials in a fixed order and evaluates the requested statistic.
+// (integer block sums are exact; the scale 1/r or 1/r^2 is applied once at the end) and writes them to the
+// workspace; a second one-workgroup kernel adds the partials in index order and evaluates the requested
+// statistic.  The result therefore does not depend on the order in which workgroups run.
+// (A single launch in which the last workgroup to finish does the final sum was measured slower: the
+// per-workgroup ticket increments serialise on one address across the chip.)
 // ---------------------------------------------------------------------------------------------
 enum { kS12 = 0, kS11 = 1, kS22 = 2, kD1 = 3, kD2 = 4, kNumSums = 5 };
 
-__device__ __forceinline__ void store_partials(double* sums, double* __restrict__ partials) {
-  __shared__ double lds[kThreads / 64][kNumSums];
+struct ReduceTail {
+  double* partials;
+  double* out;
+  int op;
+  double r, n_blocks, vol;
+};
+
+__device__ __forceinline__ double finish_statistic(const double* s, const ReduceTail& t) {
+  switch (t.op) {
+    case kDot: return s[kS12] / (t.r * t.r);
+    case kNorm2: return sqrt(s[kS11]) / t.r;
+    case kCosine: return s[kS12] / (sqrt(s[kS11]) * sqrt(s[kS22]));
+    case kMean: return (s[kD1] / t.r) / (t.n_blocks * sqrt(t.vol));
+    // centring the first coefficients by their mean removes (sum D1)(sum D2) / n_blocks from the raw sum
+    case kCovariance: return ((s[kS12] - s[kD1] * s[kD2] / t.n_blocks) / (t.r * t.r)) / (t.n_blocks * t.vol);
+    case kVariance: return ((s[kS11] - s[kD1] * s[kD1] / t.n_blocks) / (t.r * t.r)) / (t.n_blocks * t.vol);
+    default: return 0.0;
+  }
+}
+
+// sum of `sums` over the workgroup, valid in threads 0 .. kNumSums-1 (thread i returns total i)
+__device__ __forceinline__ double group_total(const double* sums, double (*lds)[kNumSums]) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
   for (int i = 0; i < kNumSums; ++i) {
@@ -307,63 +358,95 @@ __device__ __forceinline__ void store_partials(double* sums, double* __restrict_
     if (lane == 0) lds[wave][i] = t;
   }
   __syncthreads();
-  if (threadIdx.x < kNumSums) {
-    double t = 0.0;
+  double t = 0.0;
+  if (threadIdx.x < kNumSums)
     for (int w = 0; w < kThreads / 64; ++w) t += lds[w][threadIdx.x];
-    partials[int64_t(blockIdx.x) * kReducePartialSlots + threadIdx.x] = t;
-  }
+  return t;
+}
+
+__device__ __forceinline__ void reduce_tail(double* sums, const ReduceTail& t) {
+  __shared__ double lds[kThreads / 64][kNumSums];
+  const double total = group_total(sums, lds);
+  if (threadIdx.x < kNumSums) t.partials[int64_t(blockIdx.x) * kReducePartialSlots + threadIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kThreads) void k_reduce_final(ReduceTail t, int n_partials) {
+  __shared__ double lds[kThreads / 64][kNumSums];
+  __shared__ double fin[kNumSums];
+  double acc[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
+  for (int p = threadIdx.x; p < n_partials; p += kThreads)
+#pragma unroll
+    for (int i = 0; i < kNumSums; ++i) acc[i] += t.partials[int64_t(p) * kReducePartialSlots + i];
+  const double grand = group_total(acc, lds);
+  if (threadIdx.x < kNumSums) fin[threadIdx.x] = grand;
+  __syncthreads();
+  if (threadIdx.x == 0) *t.out = finish_statistic(fin, t);
 }
 
 template <int kIType, bool kTwo, bool kDC>
-__global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
-                                                         const void* __restrict__ N2, const uint4* __restrict__ F2,
-                                                         int ntype, int64_t nvec, int vpb_shift, int64_t vpb,
-                                                         double* __restrict__ partials) {
-  double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
-  const int64_t nthreads = int64_t(gridDim.x) * kThreads;
-  for (int64_t v0 = int64_t(blockIdx.x) * kThreads + threadIdx.x; v0 < nvec; v0 += nthreads * kUnroll) {
-    uint4 a[kUnroll], b[kUnroll];
-    double n1[kUnroll], n2[kUnroll];
-    bool head[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int64_t v = v0 + u * nthreads;
-      a[u] = make_uint4(0u, 0u, 0u, 0u);
-      b[u] = a[u];
-      n1[u] = n2[u] = 0.0;
-      head[u] = false;
-      if (v < nvec) {
-        const int64_t k = vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
-        head[u] = (v - k * vpb) == 0;
-        a[u] = F1[v];
-        n1[u] = load_float<double>(N1, ntype, k);
-        if (kTwo) {
-          b[u] = F2[v];
-          n2[u] = load_float<double>(N2, ntype, k);
-        }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      sums[kS11] += dot_vec<kIType>(a[u], a[u]) * (n1[u] * n1[u]);
-      if (kTwo) {
-        sums[kS12] += dot_vec<kIType>(a[u], b[u]) * (n1[u] * n2[u]);
-        sums[kS22] += dot_vec<kIType>(b[u], b[u]) * (n2[u] * n2[u]);
-      }
-      if (kDC && head[u]) {
-        sums[kD1] += n1[u] * double(first_element<kIType>(a[u].x));
-        if (kTwo) sums[kD2] += n2[u] * double(first_element<kIType>(b[u].x));
-      }
-    }
+__device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, const uint4& b, double n1, double n2,
+                                               bool head) {
+  sums[kS11] += dot_vec<kIType>(a, a) * (n1 * n1);
+  if (kTwo) {
+    sums[kS12] += dot_vec<kIType>(a, b) * (n1 * n2);
+    sums[kS22] += dot_vec<kIType>(b, b) * (n2 * n2);
   }
-  store_partials(sums, partials);
+  if (kDC && head) {
+    sums[kD1] += n1 * double(first_element<kIType>(a.x));
+    if (kTwo) sums[kD2] += n2 * double(first_element<kIType>(b.x));
+  }
 }
 
-// thread per block, any kept count and alignment
+// N is FP32 or FP64 (template), F is viewed as 16-byte vectors; vpb vectors per block (a power of two when
+// vpb_shift >= 0).  Workgroup b streams the contiguous vectors [b * chunk, (b + 1) * chunk): per step every
+// thread issues kUnroll loads per operand, kThreads vectors apart, with no branch between them.
+template <int kIType, int kNType, bool kTwo, bool kDC>
+__global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
+                                                         const void* __restrict__ N2, const uint4* __restrict__ F2,
+                                                         int64_t nvec, int64_t chunk, int vpb_shift, int64_t vpb,
+                                                         ReduceTail tail) {
+  double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
+  const int64_t begin = int64_t(blockIdx.x) * chunk;
+  const int64_t end = begin + chunk < nvec ? begin + chunk : nvec;
+  constexpr int64_t kStep = int64_t(kThreads) * kUnroll;
+  int64_t base = begin;
+  for (; base + kStep <= end; base += kStep) {
+    uint4 a[kUnroll], b[kUnroll];
+    double n1[kUnroll], n2[kUnroll];
+    int64_t k[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int64_t v = base + u * kThreads + threadIdx.x;
+      k[u] = vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
+      a[u] = F1[v];
+      if (kTwo) b[u] = F2[v];
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      n1[u] = load_N<kNType>(N1, k[u]);
+      n2[u] = kTwo ? load_N<kNType>(N2, k[u]) : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int64_t v = base + u * kThreads + threadIdx.x;
+      accumulate_vec<kIType, kTwo, kDC>(sums, a[u], kTwo ? b[u] : a[u], n1[u], n2[u], kDC && (v - k[u] * vpb) == 0);
+    }
+  }
+  for (int64_t v = base + threadIdx.x; v < end; v += kThreads) {
+    const int64_t k = vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
+    const uint4 a = F1[v];
+    const uint4 b = kTwo ? F2[v] : a;
+    accumulate_vec<kIType, kTwo, kDC>(sums, a, b, load_N<kNType>(N1, k), kTwo ? load_N<kNType>(N2, k) : 0.0,
+                                      kDC && (v - k * vpb) == 0);
+  }
+  reduce_tail(sums, tail);
+}
+
+// thread per block, any kept count, alignment and N type
 __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restrict__ N1, const void* __restrict__ F1,
                                                              const void* __restrict__ N2, const void* __restrict__ F2,
                                                              int ntype, int itype, int64_t n_blocks, int kept,
-                                                             int two, int dc, double* __restrict__ partials) {
+                                                             int two, int dc, ReduceTail tail) {
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   for (int64_t k = int64_t(blockIdx.x) * kThreads + threadIdx.x; k < n_blocks; k += nthreads) {
@@ -387,69 +470,44 @@ __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restr
       if (two) sums[kD2] += n2 * double(load_index(F2, itype, k * kept));
     }
   }
-  store_partials(sums, partials);
+  reduce_tail(sums, tail);
 }
 
 // Algorithm 7 needs only N and the first kept index of every block
 __global__ __launch_bounds__(kThreads) void k_reduce_dc(const void* __restrict__ N1, const void* __restrict__ F1,
                                                         int ntype, int itype, int64_t n_blocks, int kept,
-                                                        double* __restrict__ partials) {
+                                                        ReduceTail tail) {
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   for (int64_t k = int64_t(blockIdx.x) * kThreads + threadIdx.x; k < n_blocks; k += nthreads)
     sums[kD1] += load_float<double>(N1, ntype, k) * double(load_index(F1, itype, k * kept));
-  store_partials(sums, partials);
+  reduce_tail(sums, tail);
 }
 
-__global__ __launch_bounds__(kThreads) void k_reduce_final(const double* __restrict__ partials, int n_partials, int op,
-                                                           double r, double n_blocks, double vol,
-                                                           double* __restrict__ out) {
-  double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
-  for (int p = threadIdx.x; p < n_partials; p += kThreads)
-#pragma unroll
-    for (int i = 0; i < kNumSums; ++i) sums[i] += partials[int64_t(p) * kReducePartialSlots + i];
-  __shared__ double lds[kThreads / 64][kNumSums];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-#pragma unroll
-  for (int i = 0; i < kNumSums; ++i) {
-    double t = wave_sum(sums[i]);
-    if (lane == 0) lds[wave][i] = t;
-  }
-  __syncthreads();
-  if (threadIdx.x != 0) return;
-  double s[kNumSums];
-  for (int i = 0; i < kNumSums; ++i) {
-    s[i] = 0.0;
-    for (int w = 0; w < kThreads / 64; ++w) s[i] += lds[w][i];
-  }
-  double res = 0.0;
-  switch (op) {
-    case kDot: res = s[kS12] / (r * r); break;
-    case kNorm2: res = sqrt(s[kS11]) / r; break;
-    case kCosine: res = s[kS12] / (sqrt(s[kS11]) * sqrt(s[kS22])); break;
-    case kMean: res = (s[kD1] / r) / (n_blocks * sqrt(vol)); break;
-    // centring the first coefficients by their mean removes (sum D1)(sum D2) / n_blocks from the raw sum
-    case kCovariance: res = ((s[kS12] - s[kD1] * s[kD2] / n_blocks) / (r * r)) / (n_blocks * vol); break;
-    case kVariance: res = ((s[kS11] - s[kD1] * s[kD1] / n_blocks) / (r * r)) / (n_blocks * vol); break;
-    default: break;
-  }
-  *out = res;
-}
-
-template <int kIType>
-void launch_reduce_vec(bool two, bool dc, dim3 grid, hipStream_t s, const void* N1, const void* F1, const void* N2,
-                       const void* F2, int ntype, int64_t nvec, int shift, int64_t vpb, double* partials) {
+template <int kIType, int kNType>
+void launch_reduce_vec2(bool two, bool dc, dim3 grid, hipStream_t s, const void* N1, const void* F1, const void* N2,
+                        const void* F2, int64_t nvec, int64_t chunk, int shift, int64_t vpb, const ReduceTail& tail) {
   const uint4* a = static_cast<const uint4*>(F1);
   const uint4* b = static_cast<const uint4*>(F2);
   dim3 block(kThreads);
   if (two && dc)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, true, true>), grid, block, 0, s, N1, a, N2, b, ntype, nvec, shift, vpb, partials);
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, tail);
   else if (two)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, true, false>), grid, block, 0, s, N1, a, N2, b, ntype, nvec, shift, vpb, partials);
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, tail);
   else if (dc)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, false, true>), grid, block, 0, s, N1, a, N2, b, ntype, nvec, shift, vpb, partials);
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, tail);
   else
-    hipLaunchKernelGGL((k_reduce_vec<kIType, false, false>), grid, block, 0, s, N1, a, N2, b, ntype, nvec, shift, vpb, partials);
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, tail);
+}
+
+template <int kIType>
+void launch_reduce_vec(int ntype, bool two, bool dc, dim3 grid, hipStream_t s, const void* N1, const void* F1,
+                       const void* N2, const void* F2, int64_t nvec, int64_t chunk, int shift, int64_t vpb,
+                       const ReduceTail& tail) {
+  if (ntype == PBZ_F64)
+    launch_reduce_vec2<kIType, PBZ_F64>(two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
+  else
+    launch_reduce_vec2<kIType, PBZ_F32>(two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
 }
 
 }  // namespace
@@ -471,18 +529,26 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
                void* Nout, void* Fout, hipStream_t s) {
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const int lanes_shift = bpb % 16 == 0 ? ilog2_exact(bpb / 16) : -1;
-  if (lanes_shift >= 0 && lanes_shift <= 6 && aligned16(F1) && aligned16(F2) && aligned16(Fout)) {
+  const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
+  if (wide_N && lanes_shift >= 0 && lanes_shift <= 6 && aligned16(F1) && aligned16(F2) && aligned16(Fout)) {
     const int64_t nvec = n_blocks * (bpb / 16);
-    dim3 grid(stream_groups(nvec, 1)), block(kThreads);
+    int64_t add_groups = (nvec + kThreads - 1) / kThreads;      // one vector per thread; the kernel loops beyond that
+    if (add_groups > (int64_t(1) << 30)) add_groups = int64_t(1) << 30;
+    dim3 grid(static_cast<unsigned>(add_groups)), block(kThreads);
     const uint4* a = static_cast<const uint4*>(F1);
     const uint4* b = static_cast<const uint4*>(F2);
     uint4* o = static_cast<uint4*>(Fout);
-    if (c->itype == PBZ_I8)
-      hipLaunchKernelGGL(k_add_vec<PBZ_I8>, grid, block, 0, s, N1, a, N2, b, Nout, o, int(c->ftype), c->r, nvec, lanes_shift);
-    else if (c->itype == PBZ_I16)
-      hipLaunchKernelGGL(k_add_vec<PBZ_I16>, grid, block, 0, s, N1, a, N2, b, Nout, o, int(c->ftype), c->r, nvec, lanes_shift);
-    else
-      hipLaunchKernelGGL(k_add_vec<PBZ_I32>, grid, block, 0, s, N1, a, N2, b, Nout, o, int(c->ftype), c->r, nvec, lanes_shift);
+#define PBZ_ADD(IT, NT) hipLaunchKernelGGL((k_add_vec<IT, NT>), grid, block, 0, s, N1, a, N2, b, Nout, o, c->r, nvec, lanes_shift)
+    if (c->ftype == PBZ_F64) {
+      if (c->itype == PBZ_I8) PBZ_ADD(PBZ_I8, PBZ_F64);
+      else if (c->itype == PBZ_I16) PBZ_ADD(PBZ_I16, PBZ_F64);
+      else PBZ_ADD(PBZ_I32, PBZ_F64);
+    } else {
+      if (c->itype == PBZ_I8) PBZ_ADD(PBZ_I8, PBZ_F32);
+      else if (c->itype == PBZ_I16) PBZ_ADD(PBZ_I16, PBZ_F32);
+      else PBZ_ADD(PBZ_I32, PBZ_F32);
+    }
+#undef PBZ_ADD
   } else {
     int64_t g = n_blocks < 65536 ? n_blocks : 65536;
     hipLaunchKernelGGL(k_add_generic, dim3(int(g)), dim3(64), 0, s, N1, F1, N2, F2, Nout, Fout, int(c->ftype),
@@ -491,38 +557,54 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
   return hip_status(hipGetLastError());
 }
 
+// contiguous vectors per workgroup: whole steps of kThreads * kUnroll, as few as keep the grid within the workspace
+static int64_t chunk_for(int64_t nvec, int* groups) {
+  const int64_t step = int64_t(kThreads) * kUnroll;
+  int64_t steps = (nvec + step * kReduceMaxGroups - 1) / (step * kReduceMaxGroups);
+  if (steps < 1) steps = 1;
+  const int64_t chunk = steps * step;
+  *groups = int((nvec + chunk - 1) / chunk);
+  return chunk;
+}
+
 int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
                   const void* F2, double* out, void* workspace, hipStream_t s) {
-  double* partials = static_cast<double*>(workspace);
+  ReduceTail tail;
+  tail.partials = static_cast<double*>(workspace);
+  tail.out = out;
+  tail.op = int(op);
+  tail.r = c->r;
+  tail.n_blocks = double(n_blocks);
+  tail.vol = double(c->vol);
   const bool two = (op == kDot || op == kCosine || op == kCovariance);
   const bool dc = (op == kCovariance || op == kVariance);
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
+  const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
   int groups;
   if (op == kMean) {
     groups = stream_groups(n_blocks, 4);
     hipLaunchKernelGGL(k_reduce_dc, dim3(groups), dim3(kThreads), 0, s, N1, F1, int(c->ftype), int(c->itype), n_blocks,
-                       c->kept, partials);
-  } else if (bpb % 16 == 0 && aligned16(F1) && (!two || aligned16(F2))) {
+                       c->kept, tail);
+  } else if (wide_N && bpb % 16 == 0 && aligned16(F1) && (!two || aligned16(F2))) {
     const int64_t vpb = bpb / 16;
     const int64_t nvec = n_blocks * vpb;
-    groups = stream_groups(nvec, kUnroll);
+    const int64_t chunk = chunk_for(nvec, &groups);
     dim3 grid(groups);
     const int shift = ilog2_exact(vpb);
     if (c->itype == PBZ_I8)
-      launch_reduce_vec<PBZ_I8>(two, dc, grid, s, N1, F1, N2, F2, int(c->ftype), nvec, shift, vpb, partials);
+      launch_reduce_vec<PBZ_I8>(int(c->ftype), two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
     else if (c->itype == PBZ_I16)
-      launch_reduce_vec<PBZ_I16>(two, dc, grid, s, N1, F1, N2, F2, int(c->ftype), nvec, shift, vpb, partials);
+      launch_reduce_vec<PBZ_I16>(int(c->ftype), two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
     else
-      launch_reduce_vec<PBZ_I32>(two, dc, grid, s, N1, F1, N2, F2, int(c->ftype), nvec, shift, vpb, partials);
+      launch_reduce_vec<PBZ_I32>(int(c->ftype), two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
   } else {
     groups = stream_groups(n_blocks, 1);
     hipLaunchKernelGGL(k_reduce_generic, dim3(groups), dim3(kThreads), 0, s, N1, F1, N2, F2, int(c->ftype),
-                       int(c->itype), n_blocks, c->kept, two ? 1 : 0, dc ? 1 : 0, partials);
+                       int(c->itype), n_blocks, c->kept, two ? 1 : 0, dc ? 1 : 0, tail);
   }
   int st = hip_status(hipGetLastError());
   if (st != PBZ_OK) return st;
-  hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(kThreads), 0, s, partials, groups, int(op), c->r, double(n_blocks),
-                     double(c->vol), out);
+  hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(kThreads), 0, s, tail, groups);
   return hip_status(hipGetLastError());
 }
 
