@@ -29,6 +29,13 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per compress launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
+# the same counters read for a plain element-wise kernel over the same array); recorded in profiles/.
+MEASURED_COMPRESS_TRAFFIC = {
+    # FETCH_SIZE 524393.0 x 1.9999 KiB + WRITE_SIZE 278528.0 x 1.0000 KiB
+    "cfg4_3d_f64_b4x4x4_i16": int((524393.0 * 1.9999 + 278528.0) * 1024),
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -170,7 +177,8 @@ def main():
     comp = per_op["compress"]
     roofline = {"bound": "hbm", "kernel": codec.kernel_name("compress", wl.shape, wl.dtype),
                 "achieved": comp["gbps_moved"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(comp["gbps_moved"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(comp["gbps_moved"] / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_COMPRESS_TRAFFIC.get(wl.name),
                 "algorithmic_bytes_per_launch": in_bytes + comp_bytes}
 
     out = {
@@ -190,7 +198,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         # sized for roughly 10-30 s of oracle time on the machine's host cores
-        sample = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (512, 512, 512)}[args.config]
+        sample = {1: (256, 256), 2: (4096, 4096), 3: (32, 1024, 1024), 4: (128, 512, 512), 5: (128, 512, 512)}[args.config]
         out["cpu_baseline"] = cpu_baseline(wl, sample)
     print(json.dumps(out))
 
