@@ -499,12 +499,14 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const flo
 // =====================================================================================================
 // Family "oct8": 3-D 8x8x8 blocks, bfloat16 arrays, FP32 arithmetic, int8 indices, low-frequency box kept
 // =====================================================================================================
-// LDS exchange layout: block b occupies 128 sixteen-byte slots ordered [y][z][half row]; the low four bits
-// of the slot are XORed with swz(b) ^ 2y so that both the plane-wise writes and the row-wise reads touch
-// sixteen different bank groups per sixteen lanes.
-__device__ __forceinline__ int oct_swz(int b) { return (b & 1) | ((b >> 1) << 2); }
-__device__ __forceinline__ int oct_slot(int b, int yy, int z, int h) {
-  return b * 128 + yy * 16 + (((z << 1) | h) ^ oct_swz(b) ^ (yy << 1));
+// LDS exchange, done in two rounds (left and right half of every 8-element row) so that a wave needs 8 KiB
+// instead of 16 KiB and twice as many waves fit a CU (the kernel is latency-bound: halving its occupancy
+// cost 40 %).  Per round block b occupies 64 sixteen-byte slots ordered [y][z]; the low four bits of the slot
+// are XORed with 2b and a permutation of y so that both the plane-wise writes (lanes differ in z, b) and the
+// row-wise reads (lanes differ in b, y) touch sixteen different bank groups per sixteen lanes.
+__device__ __forceinline__ int oct_slot(int b, int yy, int z) {
+  const int perm = ((yy >> 1) & 1) | (((yy >> 2) & 1) << 2);
+  return b * 64 + ((yy * 8 + z) ^ (2 * b) ^ perm);
 }
 
 template <int KZ, int KY, int KX, bool kRagged>
@@ -512,15 +514,17 @@ __global__ __launch_bounds__(128) void k_compress_oct8(FastGeom g, const bf16_t*
                                                        int8_t* __restrict__ F) {
   static_assert(KX == 4 || KX == 8, "a kept row is one or two dwords of int8");
   constexpr int KEPT = KZ * KY * KX;
-  __shared__ uint4 lds[2][8 * 128];
+  __shared__ uint4 lds[2][8 * 64];
   const int lane = threadIdx.x & 63;
   int64_t tx, by, bz;
   if (!decode_tile<2>(g, tx, by, bz)) return;
   uint4* st = lds[threadIdx.x >> 6];
+  const int z = lane >> 3, b = lane & 7;      // phase A: lane = (plane z, block b)
+  const int bb = lane >> 3, j = lane & 7;     // phase B: lane = (block bb, row j)
 
-  // phase A: lane = (plane z, block b); one 8x8 z-plane; transforms along x and y
+  // phase A: one 8x8 z-plane per lane; transforms along x and y
+  float v[64];
   {
-    const int z = lane >> 3, b = lane & 7;
     const int64_t bx = tx * 8 + b;
     const int64_t bxc = bx < g.gx ? bx : g.gx - 1;
     int64_t zz = bz * 8 + z;
@@ -529,7 +533,6 @@ __global__ __launch_bounds__(128) void k_compress_oct8(FastGeom g, const bf16_t*
       keep_z = zz < g.Z ? 0xffffffffu : 0u;      // planes / rows past the end: load a valid row, zero it below
       zz = zz < g.Z ? zz : g.Z - 1;
     }
-    float v[64];
     uint4 raw[8];
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
@@ -549,19 +552,18 @@ __global__ __launch_bounds__(128) void k_compress_oct8(FastGeom g, const bf16_t*
     for (int yy0 = 0; yy0 < 8; ++yy0) dct::forward<float, 8, 1>(v + yy0 * 8);
 #pragma unroll
     for (int xx = 0; xx < 8; ++xx) dct::forward<float, 8, 8>(v + xx);
-#pragma unroll
-    for (int yy0 = 0; yy0 < 8; ++yy0)
-#pragma unroll
-      for (int h = 0; h < 2; ++h) st[oct_slot(b, yy0, z, h)] = f4_bits(v + yy0 * 8 + h * 4);
   }
-  wave_lds_sync();
-  // phase B: lane = (block bb, row j); the row y = j of all eight planes; transform along z
-  const int bb = lane >> 3, j = lane & 7;
+  // exchange: afterwards the lane holds the row y = j of all eight planes of block bb; transform along z
   float u[64];
 #pragma unroll
-  for (int z = 0; z < 8; ++z)
+  for (int h = 0; h < 2; ++h) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) bits_f4(st[oct_slot(bb, j, z, h)], u + z * 8 + h * 4);
+    for (int yy0 = 0; yy0 < 8; ++yy0) st[oct_slot(b, yy0, z)] = f4_bits(v + yy0 * 8 + h * 4);
+    wave_lds_sync();
+#pragma unroll
+    for (int zz0 = 0; zz0 < 8; ++zz0) bits_f4(st[oct_slot(bb, j, zz0)], u + zz0 * 8 + h * 4);
+    wave_lds_sync();
+  }
 #pragma unroll
   for (int xx = 0; xx < 8; ++xx) dct::forward<float, 8, 8>(u + xx);
 
@@ -573,17 +575,17 @@ __global__ __launch_bounds__(128) void k_compress_oct8(FastGeom g, const bf16_t*
   const float inv = m > 0.0f ? float(g.r) / m : 0.0f;
 
   // kept entries of this lane: z < KZ, x < KX when j < KY; staged in LDS at their position in the wave's span of F
-  wave_lds_sync();                       // everyone has read its phase-B data; the buffer can be reused
+  static_assert(8 * KEPT <= 8 * 64 * 16, "the staged F of a tile fits the exchange buffer");
   uint32_t* st32 = reinterpret_cast<uint32_t*>(st);
   if (j < KY) {
 #pragma unroll
-    for (int z = 0; z < KZ; ++z)
+    for (int zq = 0; zq < KZ; ++zq)
 #pragma unroll
       for (int k = 0; k < KX / 4; ++k) {
         int q4[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) q4[e] = int(rintf(u[z * 8 + k * 4 + e] * inv));
-        st32[(bb * KEPT + (z * KY + j) * KX) / 4 + k] = IdxPack<int8_t>::pack(q4);
+        for (int e = 0; e < 4; ++e) q4[e] = int(rintf(u[zq * 8 + k * 4 + e] * inv));
+        st32[(bb * KEPT + (zq * KY + j) * KX) / 4 + k] = IdxPack<int8_t>::pack(q4);
       }
   }
   wave_lds_sync();
