@@ -31,7 +31,7 @@ int make_geom(const pbz_codec* c, const int64_t* shape, Geom* g) {
   g->vol = c->vol;
   g->kept = c->kept;
   int64_t nb = 1, elems = 1;
-  const int64_t lim = int64_t(1) << 46;
+  const int64_t lim = int64_t(1) << 40;   // elements; keeps every launch grid below 2^31 workgroups
   for (int d = 0; d < c->ndim; ++d) {
     if (shape[d] < 1) return PBZ_ERR_SHAPE;
     g->shape[d] = shape[d];
@@ -55,7 +55,7 @@ int make_geom(const pbz_codec* c, const int64_t* shape, Geom* g) {
 
 int check_blocks(const pbz_codec* c, int64_t n_blocks) {
   if (!c) return PBZ_ERR_NULL;
-  if (n_blocks < 1 || n_blocks > (int64_t(1) << 46) / c->vol) return PBZ_ERR_SHAPE;
+  if (n_blocks < 1 || n_blocks > (int64_t(1) << 40) / c->vol) return PBZ_ERR_SHAPE;   // keeps every grid below 2^31
   return PBZ_OK;
 }
 
@@ -68,12 +68,17 @@ int pbz::ensure_tables(const pbz_codec* c, const DeviceTables** out) {
   std::lock_guard<std::mutex> lock(c->mu);
   DeviceTables& t = c->dev[dev];
   if (!t.ready) {
-    if (hipMalloc(&t.H, sizeof(double) * c->h_total) != hipSuccess) return PBZ_ERR_HIP;
-    if (hipMalloc(&t.kept_pos, sizeof(int32_t) * c->vol) != hipSuccess) return PBZ_ERR_HIP;
-    if (hipMemcpy(t.H, c->H_host, sizeof(double) * c->h_total, hipMemcpyHostToDevice) != hipSuccess)
+    bool ok = hipMalloc(&t.H, sizeof(double) * c->h_total) == hipSuccess &&
+              hipMalloc(&t.kept_pos, sizeof(int32_t) * c->vol) == hipSuccess &&
+              hipMemcpy(t.H, c->H_host, sizeof(double) * c->h_total, hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(t.kept_pos, c->kept_pos, sizeof(int32_t) * c->vol, hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {   // leave nothing half-made behind
+      if (t.H) (void)hipFree(t.H);
+      if (t.kept_pos) (void)hipFree(t.kept_pos);
+      t.H = nullptr;
+      t.kept_pos = nullptr;
       return PBZ_ERR_HIP;
-    if (hipMemcpy(t.kept_pos, c->kept_pos, sizeof(int32_t) * c->vol, hipMemcpyHostToDevice) != hipSuccess)
-      return PBZ_ERR_HIP;
+    }
     t.ready = true;
   }
   *out = &t;

@@ -731,6 +731,10 @@ struct LaneKernel {
            int(c->ftype) == xtype_code<NT>() && f.bz == BZ && f.by == BY && f.bx == BX && f.kz == KZ && f.ky == KY &&
            f.kx == KX && (f.g.X * sizeof(XT)) % 16 == 0;
   }
+  static int fits(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 64, 4, &grid) ? 1 : 0;
+  }
   static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 64, 4, &grid)) return 0;
@@ -768,6 +772,10 @@ struct Quad16Kernel {
     return f.ok && !c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 1 &&
            f.by == 16 && f.bx == 16 && f.kz == 1 && f.ky == 16 && f.kx == 16 && (f.g.X * 4) % 16 == 0;
   }
+  static int fits(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 16, 2, &grid) ? 1 : 0;
+  }
   static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 16, 2, &grid)) return 0;
@@ -794,6 +802,10 @@ struct Oct8Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
     return f.ok && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 8 &&
            f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX && (f.g.X * 2) % 16 == 0;
+  }
+  static int fits(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 8, 2, &grid) ? 1 : 0;
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
     dim3 grid;
@@ -833,10 +845,10 @@ int try_compress_fast(const pbz_codec* c, const Geom& geo, const void* x, int xt
   if (!aligned16(x) || !aligned16(F)) return 0;
   const Folded f = fold(c, geo);
   if (!f.ok) return 0;
-#define X(K, NAME)                                \
-  if (K::matches(c, f, xtype)) {                  \
-    *name = NAME;                                 \
-    return dry_run ? 1 : K::compress(f.g, x, N, F, s); \
+#define X(K, NAME)                                          \
+  if (K::matches(c, f, xtype)) {                            \
+    *name = NAME;                                           \
+    return dry_run ? K::fits(f.g) : K::compress(f.g, x, N, F, s); \
   }
   PBZ_FOR_EACH_LANE_KERNEL(X)
 #undef X
@@ -848,10 +860,10 @@ int try_decompress_fast(const pbz_codec* c, const Geom& geo, const void* N, cons
   if (!aligned16(y) || !aligned16(F)) return 0;
   const Folded f = fold(c, geo);
   if (!f.ok) return 0;
-#define X(K, NAME)                                  \
-  if (K::matches(c, f, ytype)) {                    \
-    *name = NAME;                                   \
-    return dry_run ? 1 : K::decompress(f.g, N, F, y, s); \
+#define X(K, NAME)                                            \
+  if (K::matches(c, f, ytype)) {                              \
+    *name = NAME;                                             \
+    return dry_run ? K::fits(f.g) : K::decompress(f.g, N, F, y, s); \
   }
   PBZ_FOR_EACH_LANE_KERNEL(X)
 #undef X
