@@ -209,7 +209,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         # sized for roughly 10-30 s of oracle time on the machine's host cores
-        sample = {1: (256, 256), 2: (4096, 4096), 3: (32, 1024, 1024), 4: (128, 512, 512), 5: (128, 512, 512)}[args.config]
+        sample = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (512, 512, 512)}[args.config]
         out["cpu_baseline"] = cpu_baseline(wl, sample)
     print(json.dumps(out))
 
