@@ -1,5 +1,5 @@
 """Plain FP64 CPU oracle of the blockwise-transform codec (Sec. III-A, III-B) and of the
-compressed-space operations (Sec. IV-A, Table I, Algorithms 1-3 and 5-11).
+compressed-space operations (Sec. IV-A, Table I, Algorithms 1-12 and the block-wise statistics).
 
 TEST INFRASTRUCTURE ONLY: slow, unblocked, unfused, written to be checked against the
 paper by eye.  It is never on the product path and shares no code with the HIP kernels.
@@ -405,3 +405,68 @@ def asymptotic_ratio(s: Sequence[int], i: Sequence[int], ubits: int, fbits: int,
     """u prod(s) / ((f + ibits sum(P)) prod(ceil(s / i)))  (Sec. IV-C, displayed equation)."""
     nb = int(np.prod(block_grid(s, i), dtype=np.int64))
     return (ubits * float(np.prod(np.asarray(s, dtype=np.float64)))) / ((fbits + ibits * kept) * nb)
+
+
+# --------------------------------------------------------------------------------------
+# further operations of Sec. IV-A: scalar addition, SSIM, block-wise statistics
+# --------------------------------------------------------------------------------------
+def add_scalar(A: Compressed, x: float) -> Compressed:
+    """Algorithm 4: add x prod(sqrt(i)) to every first coefficient and rebin.
+
+    READING: the printed listing takes N = ||C_k||_inf before it shifts the first coefficient, so the
+    rebinned first index can exceed r; here N is taken after the shift (the only order for which the
+    result is a valid compressed array).  The returned ``t`` holds the pre-rounding C r / N.
+    """
+    _require_dc(A)
+    r = float(A.r)
+    C = specified_coefficients(A).copy()
+    C[:, 0] = C[:, 0] + float(x) * float(np.prod(np.sqrt(np.asarray(A.i, dtype=np.float64))))
+    N = np.max(np.abs(C), axis=1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = (C * r) / N.reshape(-1, 1)
+    t = np.where(N.reshape(-1, 1) > 0.0, t, 0.0)
+    out = _like(A, N, np.rint(t))
+    out.t = t
+    return out
+
+
+def ssim(A: Compressed, B: Compressed, s_l: float = 1e-4, s_c: float = 9e-4, w_l: float = 1.0,
+         w_c: float = 1.0, w_s: float = 1.0) -> float:
+    """Algorithm 12: l^w_l c^w_c s^w_s from the compressed-space means, variances and covariance."""
+    mu_a, mu_b = mean(A), mean(B)
+    var_a, var_b = variance(A), variance(B)
+    sd_a, sd_b = np.sqrt(var_a), np.sqrt(var_b)
+    cov = covariance(A, B)
+    lum = (2.0 * mu_a * mu_b + s_l) / (mu_a ** 2 + mu_b ** 2 + s_l)
+    con = (2.0 * sd_a * sd_b + s_c) / (sd_a ** 2 + sd_b ** 2 + s_c)
+    stru = (cov + s_c / 2.0) / (sd_a * sd_b + s_c / 2.0)
+    return float(lum ** w_l * con ** w_c * stru ** w_s)
+
+
+def blockwise_mean(A: Compressed) -> np.ndarray:
+    """First coefficients divided by prod(sqrt(i)) (Sec. IV-A, "Mean"); shape b."""
+    _require_dc(A)
+    c = float(np.prod(np.sqrt(np.asarray(A.i, dtype=np.float64))))
+    return (specified_coefficients(A)[:, 0] / c).reshape(A.b)
+
+
+def blockwise_covariance(A: Compressed, B: Compressed) -> np.ndarray:
+    """Block-wise means of the product of the block-wise centred coefficients (Sec. IV-A, "Covariance"):
+    centring a block by its own mean zeroes its first coefficient; shape b."""
+    _same_settings(A, B)
+    _require_dc(A)
+    C1 = specified_coefficients(A).copy()
+    C2 = specified_coefficients(B).copy()
+    C1[:, 0] = 0.0
+    C2[:, 0] = 0.0
+    return (np.sum(C1 * C2, axis=1) / float(np.prod(A.i))).reshape(A.b)
+
+
+def blockwise_variance(A: Compressed) -> np.ndarray:
+    """Block-wise mean of the squared block-wise centred coefficients (Sec. IV-A, "Variance")."""
+    return blockwise_covariance(A, A)
+
+
+def blockwise_std(A: Compressed) -> np.ndarray:
+    """Square root of the block-wise variance (Sec. IV-A, "Variance")."""
+    return np.sqrt(blockwise_variance(A))

@@ -320,3 +320,71 @@ def test_gradient_array_blocks_share_one_pattern():
     dc = C[:, 0].reshape(4, 6)
     assert np.allclose(np.diff(dc, axis=1), dc[0, 1] - dc[0, 0], atol=1e-13)
     assert dc[0, 1] - dc[0, 0] == pytest.approx(8 * 8 / (31 + 47), rel=1e-12)   # 8 px step * sqrt(64) / sum(s-1)
+
+
+# ---------------------------------------------------------------- scalar addition, SSIM, block-wise ---
+@pytest.mark.parametrize("case", CASES)
+def test_add_scalar(case):
+    A, _ = _pair(case)
+    r = A.r
+    c = math.sqrt(np.prod(A.i))
+    for x in (0.75, -3.0):
+        S = po.add_scalar(A, x)
+        want = po.specified_coefficients(A).copy()
+        want[:, 0] += x * c
+        N = np.max(np.abs(want), axis=1)
+        got = po.specified_coefficients(S)
+        slack = {"f32": 1e-6, "f64": 1e-14}[A.ftype]
+        assert np.all(np.abs(got - want) <= (N[:, None] / (2 * r)) * (1 + 1e-9) + slack * N[:, None])
+        assert np.max(np.abs(S.F.astype(np.int64))) <= r              # the fix: no index overflows
+        # every element moves by x, up to the rebinning error (at most sqrt(vol) N / (2r) per block in L2)
+        d = po.decompress_padded(S) - po.decompress_padded(A) - x
+        blk = np.sqrt(np.sum(po.to_blocks(d, A.i).reshape(A.n_blocks, -1) ** 2, axis=1))
+        assert np.all(blk <= np.sqrt(A.kept) * N / (2 * r) * (1 + 1e-6) + 1e-5 * N)
+        assert po.mean(S) == pytest.approx(po.mean(A) + x, abs=float(np.max(N)) / (2 * r) / c * 1.01 + 1e-6 * abs(x))
+    Z = po.add_scalar(A, 0.0)
+    assert np.max(np.abs(Z.F.astype(np.int64) - A.F.astype(np.int64))) <= 1
+
+
+def test_add_scalar_brute_force_tiny():
+    g = rng(21)
+    x = g.standard_normal((2, 2))
+    A = po.compress(x, (2, 2), 8, "f64")
+    S = po.add_scalar(A, 1.25)
+    c = [float(A.N[0, 0]) * int(A.F[0, j]) / 127 for j in range(4)]
+    c[0] += 1.25 * 2.0
+    n = max(abs(v) for v in c)
+    assert S.N64[0, 0] == pytest.approx(n, rel=1e-15)
+    assert [int(v) for v in S.F[0]] == [brute._round_half_even(v * 127 / n) for v in c]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_ssim(case):
+    A, B = _pair(case)
+    a, b = po.decompress_padded(A), po.decompress_padded(B)
+    assert po.ssim(A, A) == pytest.approx(1.0, abs=1e-12)
+    assert po.ssim(A, B) == pytest.approx(po.ssim(B, A), rel=1e-12)
+    assert po.ssim(A, B, w_l=0.0, w_c=0.0, w_s=0.0) == 1.0
+    s_l, s_c = 1e-4, 9e-4
+    ma, mb, va, vb = a.mean(), b.mean(), a.var(), b.var()
+    cov = np.mean((a - ma) * (b - mb))
+    want = ((2 * ma * mb + s_l) / (ma * ma + mb * mb + s_l)) * \
+           ((2 * math.sqrt(va * vb) + s_c) / (va + vb + s_c)) * ((cov + s_c / 2) / (math.sqrt(va * vb) + s_c / 2))
+    assert po.ssim(A, B, s_l, s_c) == pytest.approx(want, rel=1e-9)
+    # closed form: against a scaled copy, with no stabilisers, SSIM = (2k / (1 + k^2))^2
+    k = 3.0
+    assert po.ssim(A, po.multiply_scalar(A, k), 0.0, 0.0) == pytest.approx((2 * k / (1 + k * k)) ** 2,
+                                                                            rel=1e-6 if A.ftype == "f32" else 1e-12)
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_blockwise_statistics_equal_those_of_the_decompressed_blocks(case):
+    A, B = _pair(case)
+    a = po.to_blocks(po.decompress_padded(A), A.i).reshape(A.n_blocks, -1)
+    b = po.to_blocks(po.decompress_padded(B), B.i).reshape(B.n_blocks, -1)
+    assert np.allclose(po.blockwise_mean(A).reshape(-1), a.mean(axis=1), rtol=1e-11, atol=1e-13)
+    assert np.allclose(po.blockwise_variance(A).reshape(-1), a.var(axis=1), rtol=1e-9, atol=1e-15)
+    assert np.allclose(po.blockwise_std(A).reshape(-1), a.std(axis=1), rtol=1e-9, atol=1e-9)
+    cov = np.mean((a - a.mean(axis=1, keepdims=True)) * (b - b.mean(axis=1, keepdims=True)), axis=1)
+    assert np.allclose(po.blockwise_covariance(A, B).reshape(-1), cov, rtol=1e-9, atol=1e-15)
+    assert po.blockwise_mean(A).shape == A.b
