@@ -183,6 +183,32 @@ def main():
         per_op[name] = {"ms": round(ms, 4), "gbps": round(quoted / ms / 1e6, 1),
                         "gbps_moved": round(moved / ms / 1e6, 1),
                         "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    # operations added beyond the base hot path (scalar addition, SSIM, block-wise statistics): timed on their
+    # own after the timed region, not part of `value`
+    extra_ops = {}
+    if has_dc:
+        bw = torch.empty(lay.n_blocks, dtype=torch.float64, device=dev)
+        bw_bytes = lay.n_blocks * 8
+        extras = [
+            ("add_scalar", lambda: codec.add_scalar(N1, F1, 0.75, N_out=Nn, F_out=Fn), 2 * comp_bytes),
+            ("ssim", lambda: codec.ssim(N1, F1, N2, F2, out=scal[6:7]), 2 * comp_bytes),
+            ("blockwise_mean", lambda: codec.blockwise_mean(N1, F1, out=bw), dc_bytes + bw_bytes),
+            ("blockwise_variance", lambda: codec.blockwise_variance(N1, F1, out=bw), comp_bytes + bw_bytes),
+            ("blockwise_covariance", lambda: codec.blockwise_covariance(N1, F1, N2, F2, out=bw), 2 * comp_bytes + bw_bytes),
+        ]
+        for name, fn, moved in extras:
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            extra_ops[name] = {"ms": round(ms, 4), "gbps_moved": round(moved / ms / 1e6, 1),
+                               "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+
     comp = per_op["compress"]
     roofline = {"bound": "hbm", "kernel": codec.kernel_name("compress", wl.shape, wl.dtype),
                 "achieved": comp["gbps_moved"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -205,6 +231,7 @@ def main():
                    "uncompressed_bytes": in_bytes, "compressed_bytes": comp_bytes,
                    "input_generation_s": round(t_gen, 1)},
         "ops": per_op,
+        "extra_ops": extra_ops,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -155,6 +155,37 @@ int pbz_mean(const pbz_codec* codec, int64_t n_blocks, const void* N, const void
 int pbz_variance(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* Algorithm 4 (addition of a scalar): C = N F / r, x prod(sqrt(i)) is added to the first coefficient of every
+ * block, then N = max|C| and F = rint(C r / N).  N is taken after the shift (the printed listing takes it
+ * before, which lets the first index exceed r).  Needs the first coefficient (PBZ_ERR_DC_PRUNED otherwise).
+ * Outputs may alias the inputs. */
+int pbz_add_scalar(const pbz_codec* codec, int64_t n_blocks, const void* N_in, const void* F_in, double x,
+                   void* N_out, void* F_out, void* stream);
+
+/* Algorithm 12 (structural similarity): l^w_l c^w_c s^w_s with
+ *   l = (2 mu_A mu_B + s_l) / (mu_A^2 + mu_B^2 + s_l),  c = (2 sd_A sd_B + s_c) / (var_A + var_B + s_c),
+ *   s = (cov_AB + s_c / 2) / (sd_A sd_B + s_c / 2)
+ * from the compressed-space mean, variance and covariance (Algorithms 7-9), all taken in one pass over both
+ * operands.  One FP64 scalar to out (device); workspace as for the reductions above. */
+int pbz_ssim(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+             const void* F2, double s_l, double s_c, double w_l, double w_c, double w_s, double* out,
+             void* workspace, size_t workspace_bytes, void* stream);
+
+/* Block-wise statistics (Sec. IV-A, the block-wise variants of mean, variance, standard deviation and
+ * covariance): out (device) receives n_blocks FP64 values, one per block, in block order.
+ *   mean_k       = C_k0 / prod(sqrt(i))
+ *   covariance_k = (sum_j C1_kj C2_kj - C1_k0 C2_k0) / prod(i)   (a block centred by its own mean has no first
+ *                  coefficient);  variance_k = covariance_k(A, A);  std_k = sqrt(variance_k)
+ * All need the first coefficient (PBZ_ERR_DC_PRUNED otherwise). */
+int pbz_blockwise_mean(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
+                       void* stream);
+int pbz_blockwise_variance(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
+                           void* stream);
+int pbz_blockwise_std(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
+                      void* stream);
+int pbz_blockwise_covariance(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1,
+                             const void* N2, const void* F2, double* out, void* stream);
+
 /* Name of the kernel family pbz_compress ("compress") or pbz_decompress ("decompress") would run for
  * this shape and array type: "generic" or the name of a specialised kernel.  Host only; returns a static
  * string, or NULL on invalid arguments. */

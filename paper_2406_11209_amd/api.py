@@ -47,6 +47,13 @@ SIGNATURES = {
     "pbz_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_mean": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_variance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_add_scalar": (_c.c_int, [_p, _c.c_int64, _p, _p, _c.c_double, _p, _p, _p]),
+    "pbz_ssim": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_double, _c.c_double, _c.c_double, _c.c_double,
+                            _c.c_double, _p, _p, _c.c_size_t, _p]),
+    "pbz_blockwise_mean": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p]),
+    "pbz_blockwise_variance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p]),
+    "pbz_blockwise_std": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p]),
+    "pbz_blockwise_covariance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p]),
     "pbz_kernel_name": (_c.c_char_p, [_p, _c.c_char_p, _i64p, _c.c_int]),
     "pbz_status_string": (_c.c_char_p, [_c.c_int]),
 }
@@ -230,6 +237,36 @@ class Codec:
                                 _stream()))
         return N_out, F_out
 
+    def add_scalar(self, N, F, x: float, N_out=None, F_out=None):
+        torch = _torch()
+        N_out = torch.empty_like(N) if N_out is None else N_out
+        F_out = torch.empty_like(F) if F_out is None else F_out
+        check(self._lib.pbz_add_scalar(self._h, F.shape[0], _ptr(N), _ptr(F), float(x), _ptr(N_out), _ptr(F_out), _stream()))
+        return N_out, F_out
+
+    # ---- block-wise statistics (each returns n_blocks float64 values on the device) --------------
+    def _blockwise1(self, fn, N, F, out):
+        torch = _torch()
+        out = torch.empty(F.shape[0], dtype=torch.float64, device=N.device) if out is None else out
+        check(fn(self._h, F.shape[0], _ptr(N), _ptr(F), _ptr(out), _stream()))
+        return out
+
+    def blockwise_mean(self, N, F, out=None):
+        return self._blockwise1(self._lib.pbz_blockwise_mean, N, F, out)
+
+    def blockwise_variance(self, N, F, out=None):
+        return self._blockwise1(self._lib.pbz_blockwise_variance, N, F, out)
+
+    def blockwise_std(self, N, F, out=None):
+        return self._blockwise1(self._lib.pbz_blockwise_std, N, F, out)
+
+    def blockwise_covariance(self, N1, F1, N2, F2, out=None):
+        torch = _torch()
+        out = torch.empty(F1.shape[0], dtype=torch.float64, device=N1.device) if out is None else out
+        check(self._lib.pbz_blockwise_covariance(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), _ptr(out),
+                                                 _stream()))
+        return out
+
     # ---- reductions (each returns a 1-element float64 device tensor) --------------------------
     def _reduce2(self, fn, N1, F1, N2, F2, out):
         torch = _torch()
@@ -253,6 +290,14 @@ class Codec:
 
     def cosine_similarity(self, N1, F1, N2, F2, out=None):
         return self._reduce2(self._lib.pbz_cosine_similarity, N1, F1, N2, F2, out)
+
+    def ssim(self, N1, F1, N2, F2, s_l=1e-4, s_c=9e-4, w_l=1.0, w_c=1.0, w_s=1.0, out=None):
+        torch = _torch()
+        out = torch.empty(1, dtype=torch.float64, device=N1.device) if out is None else out
+        ws = self.workspace(N1.device)
+        check(self._lib.pbz_ssim(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), float(s_l), float(s_c),
+                                 float(w_l), float(w_c), float(w_s), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
 
     def norm2(self, N, F, out=None):
         return self._reduce1(self._lib.pbz_norm2, N, F, out)

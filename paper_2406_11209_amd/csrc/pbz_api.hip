@@ -342,6 +342,56 @@ int pbz_variance(const pbz_codec* c, int64_t n_blocks, const void* N, const void
   return reduce2(c, kVariance, n_blocks, N, F, nullptr, nullptr, out, ws, ws_bytes, stream, false, true);
 }
 
+int pbz_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* N_in, const void* F_in, double x, void* N_out,
+                   void* F_out, void* stream) {
+  if (!c || !N_in || !F_in || !N_out || !F_out) return PBZ_ERR_NULL;
+  int st = check_blocks(c, n_blocks);
+  if (st != PBZ_OK) return st;
+  if (!std::isfinite(x)) return PBZ_ERR_SCALAR;
+  if (!c->dc_kept) return PBZ_ERR_DC_PRUNED;
+  return launch_add_scalar(c, n_blocks, N_in, F_in, x, N_out, F_out, static_cast<hipStream_t>(stream));
+}
+
+int pbz_ssim(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2, const void* F2,
+             double s_l, double s_c, double w_l, double w_c, double w_s, double* out, void* ws, size_t ws_bytes,
+             void* stream) {
+  if (!c || !N1 || !F1 || !N2 || !F2 || !out || !ws) return PBZ_ERR_NULL;
+  int st = check_blocks(c, n_blocks);
+  if (st != PBZ_OK) return st;
+  if (!std::isfinite(s_l) || !std::isfinite(s_c) || !std::isfinite(w_l) || !std::isfinite(w_c) || !std::isfinite(w_s))
+    return PBZ_ERR_SCALAR;
+  if (!c->dc_kept) return PBZ_ERR_DC_PRUNED;
+  if (ws_bytes < kWorkspaceBytes || (reinterpret_cast<uintptr_t>(ws) & 15u)) return PBZ_ERR_WORKSPACE;
+  const double params[5] = {s_l, s_c, w_l, w_c, w_s};
+  return launch_reduce(c, kSsim, n_blocks, N1, F1, N2, F2, out, ws, static_cast<hipStream_t>(stream), params);
+}
+
+static int blockwise(const pbz_codec* c, int mode, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                     const void* F2, double* out, void* stream) {
+  if (!c || !N1 || !F1 || !out) return PBZ_ERR_NULL;
+  if (mode == 2 && (!N2 || !F2)) return PBZ_ERR_NULL;
+  int st = check_blocks(c, n_blocks);
+  if (st != PBZ_OK) return st;
+  if (!c->dc_kept) return PBZ_ERR_DC_PRUNED;
+  if (mode < 0) return launch_blockwise_mean(c, n_blocks, N1, F1, out, static_cast<hipStream_t>(stream));
+  return launch_blockwise(c, mode, n_blocks, N1, F1, N2, F2, out, static_cast<hipStream_t>(stream));
+}
+
+int pbz_blockwise_mean(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out, void* stream) {
+  return blockwise(c, -1, n_blocks, N, F, nullptr, nullptr, out, stream);
+}
+int pbz_blockwise_variance(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out,
+                           void* stream) {
+  return blockwise(c, 0, n_blocks, N, F, nullptr, nullptr, out, stream);
+}
+int pbz_blockwise_std(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out, void* stream) {
+  return blockwise(c, 1, n_blocks, N, F, nullptr, nullptr, out, stream);
+}
+int pbz_blockwise_covariance(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                             const void* F2, double* out, void* stream) {
+  return blockwise(c, 2, n_blocks, N1, F1, N2, F2, out, stream);
+}
+
 const char* pbz_status_string(int status) {
   switch (status) {
     case PBZ_OK: return "ok";

@@ -88,9 +88,17 @@ int launch_mul_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, con
 int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
                const void* F2, void* Nout, void* Fout, hipStream_t s);
 
-enum ReduceOp { kDot = 0, kNorm2 = 1, kCosine = 2, kMean = 3, kCovariance = 4, kVariance = 5 };
+enum ReduceOp { kDot = 0, kNorm2 = 1, kCosine = 2, kMean = 3, kCovariance = 4, kVariance = 5, kSsim = 6 };
+// ssim_params: {s_l, s_c, w_l, w_c, w_s} for kSsim, otherwise nullptr
 int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1,
-                  const void* N2, const void* F2, double* out, void* workspace, hipStream_t s);
+                  const void* N2, const void* F2, double* out, void* workspace, hipStream_t s,
+                  const double* ssim_params = nullptr);
+int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,
+                      void* Fout, hipStream_t s);
+int launch_blockwise_mean(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out,
+                          hipStream_t s);
+int launch_blockwise(const pbz_codec* c, int mode, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                     const void* F2, double* out, hipStream_t s);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PBZ_OK : PBZ_ERR_HIP; }
 

@@ -319,6 +319,164 @@ __global__ __launch_bounds__(64) void k_add_generic(const void* __restrict__ N1,
 }
 
 // ---------------------------------------------------------------------------------------------
+// Algorithm 4: addition of a scalar.  C = N F / r, the first coefficient of every block moves by
+// x prod(sqrt(i)), then N = max|C| (taken after the shift, so that no index can exceed r) and
+// F = rint(C r / N).  Same lane layout as k_add_vec.
+// ---------------------------------------------------------------------------------------------
+// a / b rounded to nearest from a correctly rounded reciprocal: one multiply, the exact remainder by fused
+// multiply-add, one correction.  Agrees with the hardware division sequence except in rare double-rounding
+// corner cases, at a sixth of its cost.
+__device__ __forceinline__ double div_by(double a, double b, double inv_b) {
+  const double q = a * inv_b;
+  const double rem = fma(-q, b, a);
+  return fma(rem, inv_b, q);
+}
+
+template <int kIType, int kNType>
+__global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
+                                                             void* __restrict__ Nout, uint4* __restrict__ Fout,
+                                                             double r, double shift, int64_t nvec, int lanes_shift) {
+  constexpr int kPer = PerDword<kIType>::value;
+  constexpr int kElems = 4 * kPer;
+  const int lanes = 1 << lanes_shift;
+  const int64_t nthreads = int64_t(gridDim.x) * kThreads;
+  const int64_t first = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+  const int64_t wave_first = first - (threadIdx.x & 63);
+  const double inv_r = 1.0 / r;
+  for (int64_t base = wave_first; base < nvec; base += nthreads) {
+    const int64_t v = base + (threadIdx.x & 63);
+    const bool live = v < nvec;
+    const int64_t vc = live ? v : nvec - 1;
+    const int64_t k = vc >> lanes_shift;
+    const uint4 a = F1[vc];
+    const double n1 = load_N<kNType>(N1, k);
+    const bool head = (vc & (lanes - 1)) == 0;
+    double c[kElems];
+    double m = 0.0;
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      double fa[kPer];
+      unpack_dword<kIType>(aw[w], fa);
+#pragma unroll
+      for (int e = 0; e < kPer; ++e) {
+        double ce = div_by(n1 * fa[e], r, inv_r);          // N F / r as printed
+        if (w == 0 && e == 0 && head) ce += shift;
+        c[w * kPer + e] = ce;
+        m = fmax(m, fabs(ce));
+      }
+    }
+    for (int off = lanes >> 1; off > 0; off >>= 1) m = fmax(m, __shfl_xor(m, off, 64));
+    // F = rint(C r / N) in the printed order (exact ties are common here: when a small-index coefficient becomes
+    // the block maximum, the others are simple fractions of r)
+    const double inv_m = m > 0.0 ? 1.0 / m : 0.0;
+    uint32_t ow[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      int q[kPer];
+#pragma unroll
+      for (int e = 0; e < kPer; ++e) {
+        const double t = m > 0.0 ? div_by(c[w * kPer + e] * r, m, inv_m) : 0.0;
+        q[e] = int(fmin(fmax(rint(t), -r), r));
+      }
+      ow[w] = pack_dword<kIType>(q);
+    }
+    if (live) {
+      Fout[v] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+      if (head) {
+        if (kNType == PBZ_F64)
+          static_cast<double*>(Nout)[k] = m;
+        else
+          static_cast<float*>(Nout)[k] = float(m);
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(64) void k_add_scalar_generic(const void* __restrict__ N1, const void* __restrict__ F1,
+                                                           void* __restrict__ Nout, void* __restrict__ Fout, int ntype,
+                                                           int itype, double r, double shift, int64_t n_blocks,
+                                                           int kept) {
+  for (int64_t k = blockIdx.x; k < n_blocks; k += gridDim.x) {
+    const double n1 = load_float<double>(N1, ntype, k);
+    double m = 0.0;
+    for (int j = threadIdx.x; j < kept; j += 64) {
+      double ce = (n1 * double(load_index(F1, itype, k * kept + j))) / r + (j == 0 ? shift : 0.0);
+      m = fmax(m, fabs(ce));
+    }
+    for (int off = 32; off > 0; off >>= 1) m = fmax(m, __shfl_xor(m, off, 64));
+    for (int j = threadIdx.x; j < kept; j += 64) {
+      double ce = (n1 * double(load_index(F1, itype, k * kept + j))) / r + (j == 0 ? shift : 0.0);
+      double t = m > 0.0 ? (ce * r) / m : 0.0;
+      store_index(Fout, itype, k * kept + j, int64_t(fmin(fmax(rint(t), -r), r)));
+    }
+    if (threadIdx.x == 0) store_float(Nout, ntype, k, m);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block-wise statistics (Sec. IV-A): one FP64 value per block.
+//   mean_k = C_k0 / prod(sqrt(i));   covariance_k = (sum_j C1_kj C2_kj - C1_k0 C2_k0) / prod(i)
+// (centring a block by its own mean zeroes its first coefficient); variance = covariance(A, A); std = sqrt.
+// ---------------------------------------------------------------------------------------------
+enum BlockwiseMode { kBwVariance = 0, kBwStd = 1, kBwCovariance = 2 };
+
+__global__ __launch_bounds__(kThreads) void k_blockwise_mean(const void* __restrict__ N1, const void* __restrict__ F1,
+                                                             int ntype, int itype, double scale, int64_t n_blocks,
+                                                             int kept, double* __restrict__ out) {
+  const int64_t nthreads = int64_t(gridDim.x) * kThreads;
+  for (int64_t k = int64_t(blockIdx.x) * kThreads + threadIdx.x; k < n_blocks; k += nthreads)
+    out[k] = load_float<double>(N1, ntype, k) * double(load_index(F1, itype, k * kept)) * scale;
+}
+
+template <int kIType, int kNType, bool kTwo>
+__global__ __launch_bounds__(kThreads) void k_blockwise_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
+                                                            const void* __restrict__ N2, const uint4* __restrict__ F2,
+                                                            double* __restrict__ out, double scale, int mode,
+                                                            int64_t nvec, int lanes_shift) {
+  const int lanes = 1 << lanes_shift;
+  const int64_t nthreads = int64_t(gridDim.x) * kThreads;
+  const int64_t first = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+  const int64_t wave_first = first - (threadIdx.x & 63);
+  for (int64_t base = wave_first; base < nvec; base += nthreads) {
+    const int64_t v = base + (threadIdx.x & 63);
+    const bool live = v < nvec;
+    const int64_t vc = live ? v : nvec - 1;
+    const int64_t k = vc >> lanes_shift;
+    const uint4 a = F1[vc];
+    const uint4 b = kTwo ? F2[vc] : a;
+    const double n1 = load_N<kNType>(N1, k);
+    const double n2 = kTwo ? load_N<kNType>(N2, k) : n1;
+    const bool head = (vc & (lanes - 1)) == 0;
+    double sum = dot_vec<kIType>(a, b);          // exact integer sum
+    if (head) sum -= double(first_element<kIType>(a.x)) * double(first_element<kIType>(b.x));
+    for (int off = lanes >> 1; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (live && head) {
+      double res = sum * (n1 * n2) * scale;
+      if (mode == kBwStd) res = sqrt(res);
+      out[k] = res;
+    }
+  }
+}
+
+__global__ __launch_bounds__(64) void k_blockwise_generic(const void* __restrict__ N1, const void* __restrict__ F1,
+                                                          const void* __restrict__ N2, const void* __restrict__ F2,
+                                                          int ntype, int itype, double* __restrict__ out, double scale,
+                                                          int mode, int64_t n_blocks, int kept) {
+  for (int64_t k = blockIdx.x; k < n_blocks; k += gridDim.x) {
+    double sum = 0.0;
+    for (int j = 1 + threadIdx.x; j < kept; j += 64)
+      sum += double(load_index(F1, itype, k * kept + j)) * double(load_index(F2, itype, k * kept + j));
+    sum = wave_sum(sum);
+    if (threadIdx.x == 0) {
+      double res = sum * (load_float<double>(N1, ntype, k) * load_float<double>(N2, ntype, k)) * scale;
+      if (mode == kBwStd) res = sqrt(res);
+      out[k] = res;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Reductions (Algorithms 6-11).  One streaming pass produces five FP64 sums per workgroup,
 //   S12 = sum_k N1_k N2_k sum_j F1_kj F2_kj     S11, S22 likewise     D1 = sum_k N1_k F1_k0   D2 likewise
 // (integer block sums are exact; the scale 1/r or 1/r^2 is applied once at the end) and writes them to the
@@ -334,6 +492,7 @@ struct ReduceTail {
   double* out;
   int op;
   double r, n_blocks, vol;
+  double s_l, s_c, w_l, w_c, w_s;   // Algorithm 12's stabilisers and weights
 };
 
 __device__ __forceinline__ double finish_statistic(const double* s, const ReduceTail& t) {
@@ -345,6 +504,19 @@ __device__ __forceinline__ double finish_statistic(const double* s, const Reduce
     // centring the first coefficients by their mean removes (sum D1)(sum D2) / n_blocks from the raw sum
     case kCovariance: return ((s[kS12] - s[kD1] * s[kD2] / t.n_blocks) / (t.r * t.r)) / (t.n_blocks * t.vol);
     case kVariance: return ((s[kS11] - s[kD1] * s[kD1] / t.n_blocks) / (t.r * t.r)) / (t.n_blocks * t.vol);
+    case kSsim: {   // Algorithm 12 from the means, variances and covariance of Algorithms 7-9
+      const double scale = 1.0 / (t.r * t.n_blocks * sqrt(t.vol));
+      const double mu_a = s[kD1] * scale, mu_b = s[kD2] * scale;
+      const double per = 1.0 / (t.r * t.r * t.n_blocks * t.vol);
+      const double var_a = fmax((s[kS11] - s[kD1] * s[kD1] / t.n_blocks) * per, 0.0);
+      const double var_b = fmax((s[kS22] - s[kD2] * s[kD2] / t.n_blocks) * per, 0.0);
+      const double cov = (s[kS12] - s[kD1] * s[kD2] / t.n_blocks) * per;
+      const double sd = sqrt(var_a) * sqrt(var_b);
+      const double lum = (2.0 * mu_a * mu_b + t.s_l) / (mu_a * mu_a + mu_b * mu_b + t.s_l);
+      const double con = (2.0 * sd + t.s_c) / (var_a + var_b + t.s_c);
+      const double str = (cov + 0.5 * t.s_c) / (sd + 0.5 * t.s_c);
+      return pow(lum, t.w_l) * pow(con, t.w_c) * pow(str, t.w_s);
+    }
     default: return 0.0;
   }
 }
@@ -568,16 +740,22 @@ static int64_t chunk_for(int64_t nvec, int* groups) {
 }
 
 int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
-                  const void* F2, double* out, void* workspace, hipStream_t s) {
+                  const void* F2, double* out, void* workspace, hipStream_t s, const double* ssim_params) {
   ReduceTail tail;
+  tail.s_l = tail.s_c = 0.0;
+  tail.w_l = tail.w_c = tail.w_s = 1.0;
+  if (ssim_params) {
+    tail.s_l = ssim_params[0]; tail.s_c = ssim_params[1];
+    tail.w_l = ssim_params[2]; tail.w_c = ssim_params[3]; tail.w_s = ssim_params[4];
+  }
   tail.partials = static_cast<double*>(workspace);
   tail.out = out;
   tail.op = int(op);
   tail.r = c->r;
   tail.n_blocks = double(n_blocks);
   tail.vol = double(c->vol);
-  const bool two = (op == kDot || op == kCosine || op == kCovariance);
-  const bool dc = (op == kCovariance || op == kVariance);
+  const bool two = (op == kDot || op == kCosine || op == kCovariance || op == kSsim);
+  const bool dc = (op == kCovariance || op == kVariance || op == kSsim);
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
   int groups;
@@ -605,6 +783,94 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
   int st = hip_status(hipGetLastError());
   if (st != PBZ_OK) return st;
   hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(kThreads), 0, s, tail, groups);
+  return hip_status(hipGetLastError());
+}
+
+int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,
+                      void* Fout, hipStream_t s) {
+  double root = 1.0;                       // prod(sqrt(i)), multiplied in dimension order
+  for (int d = 0; d < c->ndim; ++d) root *= std::sqrt(double(c->block[d]));
+  const double shift = x * root;
+  const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
+  const int lanes_shift = bpb % 16 == 0 ? ilog2_exact(bpb / 16) : -1;
+  const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
+  if (wide_N && lanes_shift >= 0 && lanes_shift <= 6 && aligned16(Fin) && aligned16(Fout)) {
+    const int64_t nvec = n_blocks * (bpb / 16);
+    int64_t groups = (nvec + kThreads - 1) / kThreads;
+    if (groups > (int64_t(1) << 30)) groups = int64_t(1) << 30;
+    dim3 grid(static_cast<unsigned>(groups)), block(kThreads);
+    const uint4* a = static_cast<const uint4*>(Fin);
+    uint4* o = static_cast<uint4*>(Fout);
+#define PBZ_ADDS(IT, NT) hipLaunchKernelGGL((k_add_scalar_vec<IT, NT>), grid, block, 0, s, Nin, a, Nout, o, c->r, shift, nvec, lanes_shift)
+    if (c->ftype == PBZ_F64) {
+      if (c->itype == PBZ_I8) PBZ_ADDS(PBZ_I8, PBZ_F64);
+      else if (c->itype == PBZ_I16) PBZ_ADDS(PBZ_I16, PBZ_F64);
+      else PBZ_ADDS(PBZ_I32, PBZ_F64);
+    } else {
+      if (c->itype == PBZ_I8) PBZ_ADDS(PBZ_I8, PBZ_F32);
+      else if (c->itype == PBZ_I16) PBZ_ADDS(PBZ_I16, PBZ_F32);
+      else PBZ_ADDS(PBZ_I32, PBZ_F32);
+    }
+#undef PBZ_ADDS
+  } else {
+    int64_t g = n_blocks < 65536 ? n_blocks : 65536;
+    hipLaunchKernelGGL(k_add_scalar_generic, dim3(int(g)), dim3(64), 0, s, Nin, Fin, Nout, Fout, int(c->ftype),
+                       int(c->itype), c->r, shift, n_blocks, c->kept);
+  }
+  return hip_status(hipGetLastError());
+}
+
+int launch_blockwise_mean(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out,
+                          hipStream_t s) {
+  const double scale = 1.0 / (c->r * std::sqrt(double(c->vol)));
+  hipLaunchKernelGGL(k_blockwise_mean, dim3(stream_groups(n_blocks, 1)), dim3(kThreads), 0, s, N, F, int(c->ftype),
+                     int(c->itype), scale, n_blocks, c->kept, out);
+  return hip_status(hipGetLastError());
+}
+
+// mode: 0 variance, 1 standard deviation, 2 covariance (N2 / F2 used only by the covariance)
+int launch_blockwise(const pbz_codec* c, int mode, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                     const void* F2, double* out, hipStream_t s) {
+  const bool two = mode == kBwCovariance;
+  if (!two) {
+    N2 = N1;
+    F2 = F1;
+  }
+  const double scale = 1.0 / (c->r * c->r * double(c->vol));
+  const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
+  const int lanes_shift = bpb % 16 == 0 ? ilog2_exact(bpb / 16) : -1;
+  const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
+  if (wide_N && lanes_shift >= 0 && lanes_shift <= 6 && aligned16(F1) && aligned16(F2)) {
+    const int64_t nvec = n_blocks * (bpb / 16);
+    int64_t groups = (nvec + kThreads - 1) / kThreads;
+    if (groups > (int64_t(1) << 30)) groups = int64_t(1) << 30;
+    dim3 grid(static_cast<unsigned>(groups)), block(kThreads);
+    const uint4* a = static_cast<const uint4*>(F1);
+    const uint4* b = static_cast<const uint4*>(F2);
+#define PBZ_BW(IT, NT)                                                                                              \
+  do {                                                                                                              \
+    if (two)                                                                                                        \
+      hipLaunchKernelGGL((k_blockwise_vec<IT, NT, true>), grid, block, 0, s, N1, a, N2, b, out, scale, mode, nvec,   \
+                         lanes_shift);                                                                              \
+    else                                                                                                            \
+      hipLaunchKernelGGL((k_blockwise_vec<IT, NT, false>), grid, block, 0, s, N1, a, N2, b, out, scale, mode, nvec,  \
+                         lanes_shift);                                                                              \
+  } while (0)
+    if (c->ftype == PBZ_F64) {
+      if (c->itype == PBZ_I8) PBZ_BW(PBZ_I8, PBZ_F64);
+      else if (c->itype == PBZ_I16) PBZ_BW(PBZ_I16, PBZ_F64);
+      else PBZ_BW(PBZ_I32, PBZ_F64);
+    } else {
+      if (c->itype == PBZ_I8) PBZ_BW(PBZ_I8, PBZ_F32);
+      else if (c->itype == PBZ_I16) PBZ_BW(PBZ_I16, PBZ_F32);
+      else PBZ_BW(PBZ_I32, PBZ_F32);
+    }
+#undef PBZ_BW
+  } else {
+    int64_t g = n_blocks < 65536 ? n_blocks : 65536;
+    hipLaunchKernelGGL(k_blockwise_generic, dim3(int(g)), dim3(64), 0, s, N1, F1, N2, F2, int(c->ftype), int(c->itype),
+                       out, scale, mode, n_blocks, c->kept);
+  }
   return hip_status(hipGetLastError());
 }
 

@@ -178,6 +178,34 @@ class Case:
         check_indices(F3.cpu().numpy(), ref.F, ref.t, po.index_radius(self.bits) * 2.0 ** -50, "add.F")
         return N3, F3
 
+    def check_add_scalar(self, N, F, x: float):
+        N2, F2 = self.codec.add_scalar(N, F, x)
+        torch.cuda.synchronize()
+        ref = po.add_scalar(self.oc(N, F), x)
+        # FP64 on both sides; the kernel multiplies by 1/r and r/N where the oracle divides: a few ulp on t
+        check_N(to_host_f64(N2), ref.N, self.ftype, "add_scalar.N")
+        check_indices(F2.cpu().numpy(), ref.F, ref.t, po.index_radius(self.bits) * 2.0 ** -48, "add_scalar.F")
+        return N2, F2
+
+    def check_blockwise(self, N1, F1, N2, F2):
+        A, B = self.oc(N1, F1), self.oc(N2, F2)
+        pairs = [("blockwise_mean", self.codec.blockwise_mean(N1, F1), po.blockwise_mean(A)),
+                 ("blockwise_variance", self.codec.blockwise_variance(N1, F1), po.blockwise_variance(A)),
+                 ("blockwise_std", self.codec.blockwise_std(N1, F1), po.blockwise_std(A)),
+                 ("blockwise_covariance", self.codec.blockwise_covariance(N1, F1, N2, F2), po.blockwise_covariance(A, B))]
+        torch.cuda.synchronize()
+        for name, got, want in pairs:
+            tol = self.tol
+            if name == "blockwise_std":      # sqrt of a difference that can cancel to ~0: compare the squares' scale
+                tol = math.sqrt(self.tol) if self.ftype != "f64" else 1e-9
+            check_array(to_host_f64(got), want.reshape(-1), tol, name)
+
+    def check_ssim(self, N1, F1, N2, F2, **kw):
+        got = float(self.codec.ssim(N1, F1, N2, F2, **kw).item())
+        want = po.ssim(self.oc(N1, F1), self.oc(N2, F2), **kw)
+        check_scalar(got, want, self.tol, 1.0, "ssim")
+        return got
+
     # --- reductions ------------------------------------------------------------------------------
     def check_reductions(self, N1, F1, N2, F2, ops=("dot", "norm2", "cosine_similarity", "mean", "covariance", "variance")):
         A, B = self.oc(N1, F1), self.oc(N2, F2)

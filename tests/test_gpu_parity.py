@@ -36,9 +36,18 @@ def run_all_ops(case: Case, out_dtypes=()):
     N3, F3 = case.check_add(N1, F1, N2, F2)
     case.check_decompress(N3, F3)
     ops = ["dot", "norm2", "cosine_similarity"]
-    if case.mask is None or bool(np.asarray(case.mask).reshape(-1)[0]):
+    has_dc = case.mask is None or bool(np.asarray(case.mask).reshape(-1)[0])
+    if has_dc:
         ops += ["mean", "covariance", "variance"]
     case.check_reductions(N1, F1, N2, F2, ops)
+    if has_dc:
+        for x in (0.75, -3.0):
+            N4, F4 = case.check_add_scalar(N1, F1, x)
+        case.check_decompress(N4, F4)
+        case.check_blockwise(N1, F1, N2, F2)
+        case.check_ssim(N1, F1, N2, F2)
+        case.check_ssim(N1, F1, N2, F2, s_l=0.01, s_c=0.03, w_l=2.0, w_c=0.5, w_s=1.0)
+        assert case.check_ssim(N1, F1, N1, F1) == pytest.approx(1.0, abs=1e-9)
     return N1, F1, N2, F2
 
 
@@ -105,9 +114,11 @@ def test_arbitrary_mask_without_dc(path):
     case = Case(x, y, "f32", block, 8, "f32", mask, path)
     N1, F1, N2, F2 = run_all_ops(case)
     assert F1.shape[1] == int(mask.sum())
-    with pytest.raises(api.PbzError) as e:
-        case.codec.mean(N1, F1)
-    assert e.value.status == -6
+    for call in (lambda: case.codec.mean(N1, F1), lambda: case.codec.add_scalar(N1, F1, 1.0),
+                 lambda: case.codec.ssim(N1, F1, N2, F2), lambda: case.codec.blockwise_variance(N1, F1)):
+        with pytest.raises(api.PbzError) as e:
+            call()
+        assert e.value.status == -6
 
 
 @pytest.mark.parametrize("config", [1, 2, 4, 5])
@@ -160,6 +171,10 @@ def test_in_place_operations_alias_their_inputs():
     Na, Fa = N1.clone(), F1.clone()
     case.codec.add(Na, Fa, N2, F2, N_out=Na, F_out=Fa)
     assert torch.equal(Na, want_aN) and torch.equal(Fa, want_aF)
+    want_sN, want_sF = case.codec.add_scalar(N1, F1, 0.5)
+    Na, Fa = N1.clone(), F1.clone()
+    case.codec.add_scalar(Na, Fa, 0.5, N_out=Na, F_out=Fa)
+    assert torch.equal(Na, want_sN) and torch.equal(Fa, want_sF)
     Nk, Fk = case.codec.mul_scalar(N1, F1, 2.0, N_out=None, F_out=F1)       # positive scalar, F aliased: untouched
     assert Fk.data_ptr() == F1.data_ptr() and torch.equal(Nk, N1 * 2)
 
