@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per compress launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
 # the same counters read for a plain element-wise kernel over the same array); recorded in profiles/.
 MEASURED_COMPRESS_TRAFFIC = {
-    # FETCH_SIZE 524393.0 x 1.9999 KiB + WRITE_SIZE 278528.0 x 1.0000 KiB
-    "cfg4_3d_f64_b4x4x4_i16": int((524393.0 * 1.9999 + 278528.0) * 1024),
+    "cfg4_3d_f64_b4x4x4_i16": int((1048722.6 + 278523.3) * 1024),     # KiB read + KiB written, scaled
+    "cfg5_3d_bf16_b8x8x8_i8_mask4x4x4": int((1048678.4 + 69642.7) * 1024),
 }
 
 
