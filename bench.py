@@ -196,6 +196,24 @@ def main():
             ("blockwise_variance", lambda: codec.blockwise_variance(N1, F1, out=bw), comp_bytes + bw_bytes),
             ("blockwise_covariance", lambda: codec.blockwise_covariance(N1, F1, N2, F2, out=bw), 2 * comp_bytes + bw_bytes),
         ]
+        if wl.block[0] == 1 and len(wl.shape) == 3:
+            # a time series: per-step statistics, all steps in one segmented call vs one call per step
+            T = wl.shape[0]
+            per = lay.n_blocks // T
+            seg = torch.empty(T, dtype=torch.float64, device=dev)
+
+            def per_step_variance():
+                for t in range(T):
+                    codec.variance(N1[t * per:(t + 1) * per], F1[t * per:(t + 1) * per], out=seg[t:t + 1])
+
+            extras += [
+                ("series_mean_segmented", lambda: codec.segmented("mean", T, per, N1, F1, out=seg), dc_bytes),
+                ("series_variance_segmented", lambda: codec.segmented("variance", T, per, N1, F1, out=seg), comp_bytes),
+                ("series_covariance_consecutive_segmented",
+                 lambda: codec.segmented("covariance", T - 1, per, N1, F1, N1[per:], F1[per:], out=seg[:T - 1]),
+                 2 * comp_bytes * (T - 1) // T),
+                ("series_variance_one_call_per_step", per_step_variance, comp_bytes),
+            ]
         for name, fn, moved in extras:
             fn()
             torch.cuda.synchronize()

@@ -155,6 +155,20 @@ int pbz_mean(const pbz_codec* codec, int64_t n_blocks, const void* N, const void
 int pbz_variance(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* Segmented reductions: the operands are n_segments consecutive runs of blocks_per_segment blocks each (e.g. the
+ * time steps of a series compressed with block extent 1 along time); out (device) receives n_segments FP64
+ * values, out[t] being the statistic of run t of operand 1 (and run t of operand 2).  Two launches for any
+ * number of segments instead of two per segment.  The covariance of consecutive steps of one series is
+ * obtained by passing N2 / F2 = N1 / F1 advanced by one run and n_segments reduced by one.  N2 / F2 are ignored
+ * (may be NULL) for norm2, mean and variance.  Workspace as for the plain reductions. */
+typedef enum {
+  PBZ_STAT_DOT = 0, PBZ_STAT_NORM2 = 1, PBZ_STAT_COSINE_SIMILARITY = 2, PBZ_STAT_MEAN = 3, PBZ_STAT_COVARIANCE = 4,
+  PBZ_STAT_VARIANCE = 5
+} pbz_statistic;
+int pbz_segmented(const pbz_codec* codec, pbz_statistic statistic, int64_t n_segments, int64_t blocks_per_segment,
+                  const void* N1, const void* F1, const void* N2, const void* F2, double* out, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
 /* Algorithm 4 (addition of a scalar): C = N F / r, x prod(sqrt(i)) is added to the first coefficient of every
  * block, then N = max|C| and F = rint(C r / N).  N is taken after the shift (the printed listing takes it
  * before, which lets the first index exceed r).  Needs the first coefficient (PBZ_ERR_DC_PRUNED otherwise).

@@ -47,6 +47,7 @@ SIGNATURES = {
     "pbz_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_mean": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_variance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_segmented": (_c.c_int, [_p, _c.c_int, _c.c_int64, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_add_scalar": (_c.c_int, [_p, _c.c_int64, _p, _p, _c.c_double, _p, _p, _p]),
     "pbz_ssim": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_double, _c.c_double, _c.c_double, _c.c_double,
                             _c.c_double, _p, _p, _c.c_size_t, _p]),
@@ -290,6 +291,18 @@ class Codec:
 
     def cosine_similarity(self, N1, F1, N2, F2, out=None):
         return self._reduce2(self._lib.pbz_cosine_similarity, N1, F1, N2, F2, out)
+
+    STATISTICS = {"dot": 0, "norm2": 1, "cosine_similarity": 2, "mean": 3, "covariance": 4, "variance": 5}
+
+    def segmented(self, statistic: str, n_segments: int, blocks_per_segment: int, N1, F1, N2=None, F2=None, out=None):
+        """pbz_segmented: one value per run of `blocks_per_segment` blocks; returns n_segments float64 values."""
+        torch = _torch()
+        out = torch.empty(n_segments, dtype=torch.float64, device=N1.device) if out is None else out
+        ws = self.workspace(N1.device)
+        check(self._lib.pbz_segmented(self._h, self.STATISTICS[statistic], int(n_segments), int(blocks_per_segment),
+                                      _ptr(N1), _ptr(F1), None if N2 is None else _ptr(N2),
+                                      None if F2 is None else _ptr(F2), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
 
     def ssim(self, N1, F1, N2, F2, s_l=1e-4, s_c=9e-4, w_l=1.0, w_c=1.0, w_s=1.0, out=None):
         torch = _torch()

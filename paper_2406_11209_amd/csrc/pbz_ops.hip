@@ -539,20 +539,24 @@ __device__ __forceinline__ double group_total(const double* sums, double (*lds)[
 __device__ __forceinline__ void reduce_tail(double* sums, const ReduceTail& t) {
   __shared__ double lds[kThreads / 64][kNumSums];
   const double total = group_total(sums, lds);
-  if (threadIdx.x < kNumSums) t.partials[int64_t(blockIdx.x) * kReducePartialSlots + threadIdx.x] = total;
+  // grid y runs over the segments of a segmented reduction (1 otherwise)
+  if (threadIdx.x < kNumSums)
+    t.partials[(int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * kReducePartialSlots + threadIdx.x] = total;
 }
 
+// one workgroup per segment: adds that segment's n_partials partial sums in index order
 __global__ __launch_bounds__(kThreads) void k_reduce_final(ReduceTail t, int n_partials) {
   __shared__ double lds[kThreads / 64][kNumSums];
   __shared__ double fin[kNumSums];
   double acc[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
+  const double* mine = t.partials + int64_t(blockIdx.x) * n_partials * kReducePartialSlots;
   for (int p = threadIdx.x; p < n_partials; p += kThreads)
 #pragma unroll
-    for (int i = 0; i < kNumSums; ++i) acc[i] += t.partials[int64_t(p) * kReducePartialSlots + i];
+    for (int i = 0; i < kNumSums; ++i) acc[i] += mine[int64_t(p) * kReducePartialSlots + i];
   const double grand = group_total(acc, lds);
   if (threadIdx.x < kNumSums) fin[threadIdx.x] = grand;
   __syncthreads();
-  if (threadIdx.x == 0) *t.out = finish_statistic(fin, t);
+  if (threadIdx.x == 0) t.out[blockIdx.x] = finish_statistic(fin, t);
 }
 
 template <int kIType, bool kTwo, bool kDC>
@@ -576,8 +580,18 @@ template <int kIType, int kNType, bool kTwo, bool kDC>
 __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                          const void* __restrict__ N2, const uint4* __restrict__ F2,
                                                          int64_t nvec, int64_t chunk, int vpb_shift, int64_t vpb,
-                                                         ReduceTail tail) {
+                                                         int64_t seg_blocks, ReduceTail tail) {
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
+  {  // segment blockIdx.y starts seg_blocks blocks (= nvec vectors) further on
+    const int64_t nb = int64_t(blockIdx.y) * seg_blocks;
+    constexpr int kNBytes = kNType == PBZ_F64 ? 8 : 4;
+    N1 = static_cast<const char*>(N1) + nb * kNBytes;
+    F1 += int64_t(blockIdx.y) * nvec;
+    if (kTwo) {
+      N2 = static_cast<const char*>(N2) + nb * kNBytes;
+      F2 += int64_t(blockIdx.y) * nvec;
+    }
+  }
   const int64_t begin = int64_t(blockIdx.x) * chunk;
   const int64_t end = begin + chunk < nvec ? begin + chunk : nvec;
   constexpr int64_t kStep = int64_t(kThreads) * kUnroll;
@@ -621,7 +635,9 @@ __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restr
                                                              int two, int dc, ReduceTail tail) {
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
-  for (int64_t k = int64_t(blockIdx.x) * kThreads + threadIdx.x; k < n_blocks; k += nthreads) {
+  const int64_t k0 = int64_t(blockIdx.y) * n_blocks;     // first block of this segment
+  for (int64_t kk = int64_t(blockIdx.x) * kThreads + threadIdx.x; kk < n_blocks; kk += nthreads) {
+    const int64_t k = k0 + kk;
     const double n1 = load_float<double>(N1, ntype, k);
     const double n2 = two ? load_float<double>(N2, ntype, k) : 0.0;
     double s11 = 0.0, s12 = 0.0, s22 = 0.0;
@@ -651,35 +667,37 @@ __global__ __launch_bounds__(kThreads) void k_reduce_dc(const void* __restrict__
                                                         ReduceTail tail) {
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
-  for (int64_t k = int64_t(blockIdx.x) * kThreads + threadIdx.x; k < n_blocks; k += nthreads)
-    sums[kD1] += load_float<double>(N1, ntype, k) * double(load_index(F1, itype, k * kept));
+  const int64_t k0 = int64_t(blockIdx.y) * n_blocks;     // first block of this segment
+  for (int64_t kk = int64_t(blockIdx.x) * kThreads + threadIdx.x; kk < n_blocks; kk += nthreads)
+    sums[kD1] += load_float<double>(N1, ntype, k0 + kk) * double(load_index(F1, itype, (k0 + kk) * kept));
   reduce_tail(sums, tail);
 }
 
 template <int kIType, int kNType>
 void launch_reduce_vec2(bool two, bool dc, dim3 grid, hipStream_t s, const void* N1, const void* F1, const void* N2,
-                        const void* F2, int64_t nvec, int64_t chunk, int shift, int64_t vpb, const ReduceTail& tail) {
+                        const void* F2, int64_t nvec, int64_t chunk, int shift, int64_t vpb, int64_t seg_blocks,
+                        const ReduceTail& tail) {
   const uint4* a = static_cast<const uint4*>(F1);
   const uint4* b = static_cast<const uint4*>(F2);
   dim3 block(kThreads);
   if (two && dc)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, tail);
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
   else if (two)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, tail);
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
   else if (dc)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, tail);
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
   else
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, tail);
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
 }
 
 template <int kIType>
 void launch_reduce_vec(int ntype, bool two, bool dc, dim3 grid, hipStream_t s, const void* N1, const void* F1,
                        const void* N2, const void* F2, int64_t nvec, int64_t chunk, int shift, int64_t vpb,
-                       const ReduceTail& tail) {
+                       int64_t seg_blocks, const ReduceTail& tail) {
   if (ntype == PBZ_F64)
-    launch_reduce_vec2<kIType, PBZ_F64>(two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
+    launch_reduce_vec2<kIType, PBZ_F64>(two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
   else
-    launch_reduce_vec2<kIType, PBZ_F32>(two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
+    launch_reduce_vec2<kIType, PBZ_F32>(two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
 }
 
 }  // namespace
@@ -729,18 +747,20 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
   return hip_status(hipGetLastError());
 }
 
-// contiguous vectors per workgroup: whole steps of kThreads * kUnroll, as few as keep the grid within the workspace
-static int64_t chunk_for(int64_t nvec, int* groups) {
+// contiguous vectors per workgroup: whole steps of kThreads * kUnroll, as few as keep the grid within max_groups
+static int64_t chunk_for(int64_t nvec, int max_groups, int* groups) {
   const int64_t step = int64_t(kThreads) * kUnroll;
-  int64_t steps = (nvec + step * kReduceMaxGroups - 1) / (step * kReduceMaxGroups);
+  int64_t steps = (nvec + step * max_groups - 1) / (step * max_groups);
   if (steps < 1) steps = 1;
   const int64_t chunk = steps * step;
   *groups = int((nvec + chunk - 1) / chunk);
   return chunk;
 }
 
+// n_segments consecutive runs of n_blocks blocks each; one result per segment (n_segments == 1: the plain reductions)
 int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
-                  const void* F2, double* out, void* workspace, hipStream_t s, const double* ssim_params) {
+                  const void* F2, double* out, void* workspace, hipStream_t s, const double* ssim_params,
+                  int64_t n_segments) {
   ReduceTail tail;
   tail.s_l = tail.s_c = 0.0;
   tail.w_l = tail.w_c = tail.w_s = 1.0;
@@ -749,7 +769,6 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     tail.w_l = ssim_params[2]; tail.w_c = ssim_params[3]; tail.w_s = ssim_params[4];
   }
   tail.partials = static_cast<double*>(workspace);
-  tail.out = out;
   tail.op = int(op);
   tail.r = c->r;
   tail.n_blocks = double(n_blocks);
@@ -758,32 +777,48 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
   const bool dc = (op == kCovariance || op == kVariance || op == kSsim);
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
-  int groups;
-  if (op == kMean) {
-    groups = stream_groups(n_blocks, 4);
-    hipLaunchKernelGGL(k_reduce_dc, dim3(groups), dim3(kThreads), 0, s, N1, F1, int(c->ftype), int(c->itype), n_blocks,
-                       c->kept, tail);
-  } else if (wide_N && bpb % 16 == 0 && aligned16(F1) && (!two || aligned16(F2))) {
-    const int64_t vpb = bpb / 16;
-    const int64_t nvec = n_blocks * vpb;
-    const int64_t chunk = chunk_for(nvec, &groups);
-    dim3 grid(groups);
-    const int shift = ilog2_exact(vpb);
-    if (c->itype == PBZ_I8)
-      launch_reduce_vec<PBZ_I8>(int(c->ftype), two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
-    else if (c->itype == PBZ_I16)
-      launch_reduce_vec<PBZ_I16>(int(c->ftype), two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
-    else
-      launch_reduce_vec<PBZ_I32>(int(c->ftype), two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, tail);
-  } else {
-    groups = stream_groups(n_blocks, 1);
-    hipLaunchKernelGGL(k_reduce_generic, dim3(groups), dim3(kThreads), 0, s, N1, F1, N2, F2, int(c->ftype),
-                       int(c->itype), n_blocks, c->kept, two ? 1 : 0, dc ? 1 : 0, tail);
+  const int64_t n_stride = n_blocks * ftype_bytes(c->ftype), f_stride = n_blocks * bpb;   // bytes per segment
+
+  // the workspace holds kReduceMaxGroups partial sums: segments are handled in batches of at most that many
+  for (int64_t seg0 = 0; seg0 < n_segments; seg0 += kReduceMaxGroups) {
+    const int batch = int(n_segments - seg0 < kReduceMaxGroups ? n_segments - seg0 : kReduceMaxGroups);
+    const int max_groups = kReduceMaxGroups / batch;          // workgroups per segment
+    const char* n1 = static_cast<const char*>(N1) + seg0 * n_stride;
+    const char* f1 = static_cast<const char*>(F1) + seg0 * f_stride;
+    const char* n2 = two ? static_cast<const char*>(N2) + seg0 * n_stride : nullptr;
+    const char* f2 = two ? static_cast<const char*>(F2) + seg0 * f_stride : nullptr;
+    tail.out = out + seg0;
+    int groups;
+    if (op == kMean) {
+      groups = stream_groups(n_blocks, 4);
+      if (groups > max_groups) groups = max_groups;
+      hipLaunchKernelGGL(k_reduce_dc, dim3(groups, batch), dim3(kThreads), 0, s, n1, f1, int(c->ftype), int(c->itype),
+                         n_blocks, c->kept, tail);
+    } else if (wide_N && bpb % 16 == 0 && aligned16(f1) && (!two || aligned16(f2)) && f_stride % 16 == 0) {
+      const int64_t vpb = bpb / 16;
+      const int64_t nvec = n_blocks * vpb;
+      const int64_t chunk = chunk_for(nvec, max_groups, &groups);
+      dim3 grid(groups, batch);
+      const int shift = ilog2_exact(vpb);
+      if (c->itype == PBZ_I8)
+        launch_reduce_vec<PBZ_I8>(int(c->ftype), two, dc, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
+      else if (c->itype == PBZ_I16)
+        launch_reduce_vec<PBZ_I16>(int(c->ftype), two, dc, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
+      else
+        launch_reduce_vec<PBZ_I32>(int(c->ftype), two, dc, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
+    } else {
+      groups = stream_groups(n_blocks, 1);
+      if (groups > max_groups) groups = max_groups;
+      hipLaunchKernelGGL(k_reduce_generic, dim3(groups, batch), dim3(kThreads), 0, s, n1, f1, n2, f2, int(c->ftype),
+                         int(c->itype), n_blocks, c->kept, two ? 1 : 0, dc ? 1 : 0, tail);
+    }
+    int st = hip_status(hipGetLastError());
+    if (st != PBZ_OK) return st;
+    hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kThreads), 0, s, tail, groups);
+    st = hip_status(hipGetLastError());
+    if (st != PBZ_OK) return st;
   }
-  int st = hip_status(hipGetLastError());
-  if (st != PBZ_OK) return st;
-  hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(kThreads), 0, s, tail, groups);
-  return hip_status(hipGetLastError());
+  return PBZ_OK;
 }
 
 int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,

@@ -71,6 +71,23 @@ def test_series_per_step_statistics():
         Na, Fa = sub(t)
         Nb, Fb = sub(t + 1)
         step_case.check_reductions(Na, Fa, Nb, Fb, ("mean", "variance", "covariance"))
+    # the same per-step values from the segmented entry point: one call per statistic for all steps
+    A = case.oc(N, F)
+    steps_o = [po.Compressed(s=(1,) + tuple(wl.shape[1:]), i=A.i, N=A.N[t:t + 1], F=A.F[t * per:(t + 1) * per], P=A.P,
+                             index_bits=A.index_bits, ftype=A.ftype) for t in range(steps)]
+    want = {"mean": [po.mean(o) for o in steps_o], "variance": [po.variance(o) for o in steps_o],
+            "norm2": [po.norm2(o) for o in steps_o]}
+    for name, ref in want.items():
+        got = case.codec.segmented(name, steps, per, N, F).cpu().numpy()
+        assert np.allclose(got, ref, rtol=1e-5, atol=0), name
+    for name, fn in (("covariance", po.covariance), ("dot", po.dot), ("cosine_similarity", po.cosine_similarity)):
+        got = case.codec.segmented(name, steps - 1, per, N, F, N[per:], F[per:]).cpu().numpy()
+        ref = [fn(steps_o[t], steps_o[t + 1]) for t in range(steps - 1)]
+        assert np.allclose(got, ref, rtol=1e-5, atol=1e-5 * max(abs(v) for v in ref)), name
+    # and equal (up to summation order) to the per-step calls on sub-ranges
+    seg_var = case.codec.segmented("variance", steps, per, N, F)
+    for t in range(steps):
+        assert seg_var[t].item() == pytest.approx(case.codec.variance(*sub(t)).item(), rel=1e-12)
     # the compressed-space statistics also track the uncompressed series (binning error only)
     got = float(case.codec.mean(*sub(2)).item())
     assert got == pytest.approx(float(np.mean(wl.A[2].astype(np.float64))), rel=2e-3)

@@ -23,7 +23,7 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     lib = api.load_library()
     names = header_functions()
-    assert len(names) == 24
+    assert len(names) == 25
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(api.SIGNATURES) == names        # the binding covers exactly the header
@@ -137,6 +137,10 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
         assert fn(nodc._h, 4, p, p, p, None) == -6
         assert fn(h, 4, p, None, p, None) == -1
     assert lib.pbz_blockwise_covariance(h, 4, p, p, None, p, p, None) == -1
+    assert lib.pbz_segmented(h, 9, 2, 4, p, p, p, p, p, p, 1 << 20, None) == -4
+    assert lib.pbz_segmented(h, 0, 2, 4, p, p, None, p, p, p, 1 << 20, None) == -1      # dot needs both operands
+    assert lib.pbz_segmented(h, 1, 0, 4, p, p, None, None, p, p, 1 << 20, None) == -7
+    assert lib.pbz_segmented(nodc._h, 3, 2, 4, p, p, None, None, p, p, 1 << 20, None) == -6
     assert lib.pbz_add_scalar(h, 4, p, p, float("nan"), p, p, None) == -9
     assert lib.pbz_ssim(h, 4, p, p, p, p, float("inf"), 0.0, 1.0, 1.0, 1.0, p, p, 1 << 20, None) == -9
     assert lib.pbz_ssim(h, 4, p, p, p, p, 0.0, 0.0, 1.0, 1.0, 1.0, p, p, 64, None) == -8
