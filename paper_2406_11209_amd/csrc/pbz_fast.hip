@@ -509,15 +509,17 @@ __device__ __forceinline__ int oct_slot(int b, int yy, int z) {
   return b * 64 + ((yy * 8 + z) ^ (2 * b) ^ perm);
 }
 
+constexpr int kOctWaves = 4;   // waves per workgroup: neighbouring tiles, so that a workgroup reads 512-byte row pieces
+
 template <int KZ, int KY, int KX, bool kRagged>
-__global__ __launch_bounds__(128) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x, float* __restrict__ N,
-                                                       int8_t* __restrict__ F) {
+__global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x,
+                                                                  float* __restrict__ N, int8_t* __restrict__ F) {
   static_assert(KX == 4 || KX == 8, "a kept row is one or two dwords of int8");
   constexpr int KEPT = KZ * KY * KX;
-  __shared__ uint4 lds[2][8 * 64];
+  __shared__ uint4 lds[kOctWaves][8 * 64];
   const int lane = threadIdx.x & 63;
   int64_t tx, by, bz;
-  if (!decode_tile<2>(g, tx, by, bz)) return;
+  if (!decode_tile<kOctWaves>(g, tx, by, bz)) return;
   uint4* st = lds[threadIdx.x >> 6];
   const int z = lane >> 3, b = lane & 7;      // phase A: lane = (plane z, block b)
   const int bb = lane >> 3, j = lane & 7;     // phase B: lane = (block bb, row j)
@@ -805,17 +807,17 @@ struct Oct8Kernel {
   }
   static int fits(FastGeom g) {
     dim3 grid;
-    return tile_grid(g, 8, 2, &grid) ? 1 : 0;
+    return tile_grid(g, 8, kOctWaves, &grid) ? 1 : 0;
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
     dim3 grid;
-    if (!tile_grid(g, 8, 2, &grid)) return 0;
+    if (!tile_grid(g, 8, kOctWaves, &grid)) return 0;
     if (g.Z % 8 || g.Y % 8)
-      hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, true>), grid, dim3(128), 0, s, g, static_cast<const bf16_t*>(x),
-                         static_cast<float*>(N), static_cast<int8_t*>(F));
+      hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, true>), grid, dim3(kOctWaves * 64), 0, s, g,
+                         static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F));
     else
-      hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, false>), grid, dim3(128), 0, s, g, static_cast<const bf16_t*>(x),
-                         static_cast<float*>(N), static_cast<int8_t*>(F));
+      hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, false>), grid, dim3(kOctWaves * 64), 0, s, g,
+                         static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
