@@ -384,6 +384,16 @@ def norm2(A: Compressed) -> float:
     return float(np.sqrt(np.sum(C * C)))
 
 
+def difference_norm2(A: Compressed, B: Compressed) -> float:
+    """||A - B||_2 (the quantity of Sec. V, fission experiment, and of the compressed-space difference of
+    Sec. V, shallow-water experiment) taken on the specified coefficients of Algorithm 3 directly:
+    sqrt(sum((C1 - C2)^2)).  The transform is orthonormal, so this is the L2 norm of the difference of the
+    two decompressed (padded) arrays; unlike negate + add + norm2 it involves no second binning."""
+    _same_settings(A, B)
+    D = specified_coefficients(A) - specified_coefficients(B)
+    return float(np.sqrt(np.sum(D * D)))
+
+
 def cosine_similarity(A: Compressed, B: Compressed) -> float:
     """Algorithm 11: dot / (||A|| ||B||)."""
     return dot(A, B) / (norm2(A) * norm2(B))

@@ -388,3 +388,39 @@ def test_blockwise_statistics_equal_those_of_the_decompressed_blocks(case):
     cov = np.mean((a - a.mean(axis=1, keepdims=True)) * (b - b.mean(axis=1, keepdims=True)), axis=1)
     assert np.allclose(po.blockwise_covariance(A, B).reshape(-1), cov, rtol=1e-9, atol=1e-15)
     assert po.blockwise_mean(A).shape == A.b
+
+
+# ---------------------------------------------------------------- difference norm ------
+@pytest.mark.parametrize("case", CASES)
+def test_difference_norm2(case):
+    """The norm of the difference of the specified coefficients is the L2 norm of the difference of the two
+    decompressed (uncropped) arrays (orthonormal transform); it obeys the polarisation identity with the
+    other reductions; and negate + add + norm2 (the route with a second binning) lands within that
+    binning's error bound of it."""
+    A, B = _pair(case)
+    a, b = po.decompress_padded(A), po.decompress_padded(B)
+    d = po.difference_norm2(A, B)
+    assert d == pytest.approx(float(np.linalg.norm((a - b).reshape(-1))), rel=1e-11)
+    assert d * d == pytest.approx(po.norm2(A) ** 2 + po.norm2(B) ** 2 - 2.0 * po.dot(A, B), rel=1e-9)
+    assert po.difference_norm2(A, A) == 0.0
+    assert po.difference_norm2(B, A) == d
+    Z = po.multiply_scalar(B, 0.0)
+    assert po.difference_norm2(A, Z) == pytest.approx(po.norm2(A), rel=1e-15)
+    S = po.add(A, po.negate(B))
+    # every coefficient of the sum is rounded by at most N_sum / (2 r); N_sum is stored in the float type too
+    slack = np.sqrt(np.sum((S.N64.reshape(-1) / (2.0 * A.r)) ** 2 * A.F.shape[1]))
+    store = 2.0 ** (-24 if A.ftype == "f32" else -53) * po.norm2(S)
+    assert abs(po.norm2(S) - d) <= slack + 4.0 * store + 1e-12
+
+
+def test_difference_norm2_brute_force_tiny():
+    g = rng(21)
+    x, y = g.standard_normal((2, 4)), g.standard_normal((2, 4))
+    A, B = po.compress(x, (2, 2), 8, "f64"), po.compress(y, (2, 2), 8, "f64")
+    total = 0.0
+    for k in range(2):
+        for j in range(4):
+            c1 = float(A.N.reshape(-1)[k]) * int(A.F[k, j]) / 127.0
+            c2 = float(B.N.reshape(-1)[k]) * int(B.F[k, j]) / 127.0
+            total += (c1 - c2) ** 2
+    assert po.difference_norm2(A, B) == pytest.approx(math.sqrt(total), rel=1e-14)
