@@ -150,6 +150,13 @@ int pbz_cosine_similarity(const pbz_codec* codec, int64_t n_blocks, const void* 
                           size_t workspace_bytes, void* stream);
 int pbz_norm2(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
               void* workspace, size_t workspace_bytes, void* stream);
+/* ||A - B||_2 of two compressed arrays (the quantity compared between adjacent time steps in Sec. V, fission
+ * experiment), taken on the specified coefficients of Algorithm 3: sqrt(sum_kj (N1_k F1_kj - N2_k F2_kj)^2) / r,
+ * each difference formed in FP64 before squaring.  The transform being orthonormal, this is the L2 norm of the
+ * difference of the two decompressed (uncropped) arrays; no intermediate compressed array and no second binning,
+ * unlike negate + add + norm2.  Arguments as for pbz_dot. */
+int pbz_difference_norm2(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                         const void* F2, double* out, void* workspace, size_t workspace_bytes, void* stream);
 int pbz_mean(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
              void* workspace, size_t workspace_bytes, void* stream);
 int pbz_variance(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
@@ -158,12 +165,12 @@ int pbz_variance(const pbz_codec* codec, int64_t n_blocks, const void* N, const 
 /* Segmented reductions: the operands are n_segments consecutive runs of blocks_per_segment blocks each (e.g. the
  * time steps of a series compressed with block extent 1 along time); out (device) receives n_segments FP64
  * values, out[t] being the statistic of run t of operand 1 (and run t of operand 2).  Two launches for any
- * number of segments instead of two per segment.  The covariance of consecutive steps of one series is
- * obtained by passing N2 / F2 = N1 / F1 advanced by one run and n_segments reduced by one.  N2 / F2 are ignored
- * (may be NULL) for norm2, mean and variance.  Workspace as for the plain reductions. */
+ * number of segments instead of two per segment.  The covariance of consecutive steps of one series (or the
+ * norm of their difference) is obtained by passing N2 / F2 = N1 / F1 advanced by one run and n_segments reduced
+ * by one.  N2 / F2 are ignored (may be NULL) for norm2, mean and variance.  Workspace as for the plain reductions. */
 typedef enum {
   PBZ_STAT_DOT = 0, PBZ_STAT_NORM2 = 1, PBZ_STAT_COSINE_SIMILARITY = 2, PBZ_STAT_MEAN = 3, PBZ_STAT_COVARIANCE = 4,
-  PBZ_STAT_VARIANCE = 5
+  PBZ_STAT_VARIANCE = 5, PBZ_STAT_DIFFERENCE_NORM2 = 6
 } pbz_statistic;
 int pbz_segmented(const pbz_codec* codec, pbz_statistic statistic, int64_t n_segments, int64_t blocks_per_segment,
                   const void* N1, const void* F1, const void* N2, const void* F2, double* out, void* workspace,

@@ -44,6 +44,7 @@ SIGNATURES = {
     "pbz_dot": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_covariance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_cosine_similarity": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_difference_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_mean": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_variance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
@@ -292,7 +293,11 @@ class Codec:
     def cosine_similarity(self, N1, F1, N2, F2, out=None):
         return self._reduce2(self._lib.pbz_cosine_similarity, N1, F1, N2, F2, out)
 
-    STATISTICS = {"dot": 0, "norm2": 1, "cosine_similarity": 2, "mean": 3, "covariance": 4, "variance": 5}
+    def difference_norm2(self, N1, F1, N2, F2, out=None):
+        return self._reduce2(self._lib.pbz_difference_norm2, N1, F1, N2, F2, out)
+
+    STATISTICS = {"dot": 0, "norm2": 1, "cosine_similarity": 2, "mean": 3, "covariance": 4, "variance": 5,
+                  "difference_norm2": 6}
 
     def segmented(self, statistic: str, n_segments: int, blocks_per_segment: int, N1, F1, N2=None, F2=None, out=None):
         """pbz_segmented: one value per run of `blocks_per_segment` blocks; returns n_segments float64 values."""

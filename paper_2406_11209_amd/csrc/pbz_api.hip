@@ -333,6 +333,10 @@ int pbz_norm2(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F
               size_t ws_bytes, void* stream) {
   return reduce2(c, kNorm2, n_blocks, N, F, nullptr, nullptr, out, ws, ws_bytes, stream, false, false);
 }
+int pbz_difference_norm2(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                         const void* F2, double* out, void* ws, size_t ws_bytes, void* stream) {
+  return reduce2(c, kDiffNorm2, n_blocks, N1, F1, N2, F2, out, ws, ws_bytes, stream, true, false);
+}
 int pbz_mean(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out, void* ws,
              size_t ws_bytes, void* stream) {
   return reduce2(c, kMean, n_blocks, N, F, nullptr, nullptr, out, ws, ws_bytes, stream, false, true);
@@ -345,8 +349,9 @@ int pbz_variance(const pbz_codec* c, int64_t n_blocks, const void* N, const void
 int pbz_segmented(const pbz_codec* c, pbz_statistic stat, int64_t n_segments, int64_t blocks_per_segment, const void* N1,
                   const void* F1, const void* N2, const void* F2, double* out, void* ws, size_t ws_bytes, void* stream) {
   if (!c || !N1 || !F1 || !out || !ws) return PBZ_ERR_NULL;
-  if (int(stat) < 0 || int(stat) > int(PBZ_STAT_VARIANCE)) return PBZ_ERR_TYPE;
-  const bool two = stat == PBZ_STAT_DOT || stat == PBZ_STAT_COSINE_SIMILARITY || stat == PBZ_STAT_COVARIANCE;
+  if (int(stat) < 0 || int(stat) > int(PBZ_STAT_DIFFERENCE_NORM2)) return PBZ_ERR_TYPE;
+  const bool two = stat == PBZ_STAT_DOT || stat == PBZ_STAT_COSINE_SIMILARITY || stat == PBZ_STAT_COVARIANCE ||
+                   stat == PBZ_STAT_DIFFERENCE_NORM2;
   const bool needs_dc = stat == PBZ_STAT_MEAN || stat == PBZ_STAT_COVARIANCE || stat == PBZ_STAT_VARIANCE;
   if (two && (!N2 || !F2)) return PBZ_ERR_NULL;
   int st = check_blocks(c, blocks_per_segment);
@@ -354,7 +359,8 @@ int pbz_segmented(const pbz_codec* c, pbz_statistic stat, int64_t n_segments, in
   if (n_segments < 1 || n_segments > (int64_t(1) << 40) / c->vol / blocks_per_segment) return PBZ_ERR_SHAPE;
   if (needs_dc && !c->dc_kept) return PBZ_ERR_DC_PRUNED;
   if (ws_bytes < kWorkspaceBytes || (reinterpret_cast<uintptr_t>(ws) & 15u)) return PBZ_ERR_WORKSPACE;
-  return launch_reduce(c, ReduceOp(int(stat)), blocks_per_segment, N1, F1, two ? N2 : nullptr, two ? F2 : nullptr, out,
+  const ReduceOp op = stat == PBZ_STAT_DIFFERENCE_NORM2 ? kDiffNorm2 : ReduceOp(int(stat));
+  return launch_reduce(c, op, blocks_per_segment, N1, F1, two ? N2 : nullptr, two ? F2 : nullptr, out,
                        ws, static_cast<hipStream_t>(stream), nullptr, n_segments);
 }
 

@@ -499,6 +499,7 @@ __device__ __forceinline__ double finish_statistic(const double* s, const Reduce
   switch (t.op) {
     case kDot: return s[kS12] / (t.r * t.r);
     case kNorm2: return sqrt(s[kS11]) / t.r;
+    case kDiffNorm2: return sqrt(s[kS11]) / t.r;    // S11 then holds sum (N1 F1 - N2 F2)^2
     case kCosine: return s[kS12] / (sqrt(s[kS11]) * sqrt(s[kS22]));
     case kMean: return (s[kD1] / t.r) / (t.n_blocks * sqrt(t.vol));
     // centring the first coefficients by their mean removes (sum D1)(sum D2) / n_blocks from the raw sum
@@ -559,9 +560,29 @@ __global__ __launch_bounds__(kThreads) void k_reduce_final(ReduceTail t, int n_p
   if (threadIdx.x == 0) t.out[blockIdx.x] = finish_statistic(fin, t);
 }
 
-template <int kIType, bool kTwo, bool kDC>
+// kDiff: the coefficients of the two operands are subtracted element by element before squaring (their
+// difference can be far smaller than either, so the block sums S11 - 2 S12 + S22 would cancel)
+template <int kIType, bool kTwo, bool kDC, bool kDiff>
 __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, const uint4& b, double n1, double n2,
                                                bool head) {
+  if (kDiff) {
+    constexpr int kPer = kIType == PBZ_I8 ? 4 : (kIType == PBZ_I16 ? 2 : 1);
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+    double acc = 0.0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      double fa[4], fb[4];
+      unpack_dword<kIType>(aw[w], fa);
+      unpack_dword<kIType>(bw[w], fb);
+#pragma unroll
+      for (int e = 0; e < kPer; ++e) {
+        const double d = n1 * fa[e] - n2 * fb[e];
+        acc += d * d;
+      }
+    }
+    sums[kS11] += acc;
+    return;
+  }
   sums[kS11] += dot_vec<kIType>(a, a) * (n1 * n1);
   if (kTwo) {
     sums[kS12] += dot_vec<kIType>(a, b) * (n1 * n2);
@@ -576,7 +597,7 @@ __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, con
 // N is FP32 or FP64 (template), F is viewed as 16-byte vectors; vpb vectors per block (a power of two when
 // vpb_shift >= 0).  Workgroup b streams the contiguous vectors [b * chunk, (b + 1) * chunk): per step every
 // thread issues kUnroll loads per operand, kThreads vectors apart, with no branch between them.
-template <int kIType, int kNType, bool kTwo, bool kDC>
+template <int kIType, int kNType, bool kTwo, bool kDC, bool kDiff = false>
 __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                          const void* __restrict__ N2, const uint4* __restrict__ F2,
                                                          int64_t nvec, int64_t chunk, int vpb_shift, int64_t vpb,
@@ -615,14 +636,14 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int64_t v = base + u * kThreads + threadIdx.x;
-      accumulate_vec<kIType, kTwo, kDC>(sums, a[u], kTwo ? b[u] : a[u], n1[u], n2[u], kDC && (v - k[u] * vpb) == 0);
+      accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a[u], kTwo ? b[u] : a[u], n1[u], n2[u], kDC && (v - k[u] * vpb) == 0);
     }
   }
   for (int64_t v = base + threadIdx.x; v < end; v += kThreads) {
     const int64_t k = vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
     const uint4 a = F1[v];
     const uint4 b = kTwo ? F2[v] : a;
-    accumulate_vec<kIType, kTwo, kDC>(sums, a, b, load_N<kNType>(N1, k), kTwo ? load_N<kNType>(N2, k) : 0.0,
+    accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a, b, load_N<kNType>(N1, k), kTwo ? load_N<kNType>(N2, k) : 0.0,
                                       kDC && (v - k * vpb) == 0);
   }
   reduce_tail(sums, tail);
@@ -632,7 +653,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
 __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restrict__ N1, const void* __restrict__ F1,
                                                              const void* __restrict__ N2, const void* __restrict__ F2,
                                                              int ntype, int itype, int64_t n_blocks, int kept,
-                                                             int two, int dc, ReduceTail tail) {
+                                                             int two, int dc, int diff, ReduceTail tail) {
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   const int64_t k0 = int64_t(blockIdx.y) * n_blocks;     // first block of this segment
@@ -640,6 +661,15 @@ __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restr
     const int64_t k = k0 + kk;
     const double n1 = load_float<double>(N1, ntype, k);
     const double n2 = two ? load_float<double>(N2, ntype, k) : 0.0;
+    if (diff) {
+      double acc = 0.0;
+      for (int j = 0; j < kept; ++j) {
+        const double d = n1 * double(load_index(F1, itype, k * kept + j)) - n2 * double(load_index(F2, itype, k * kept + j));
+        acc += d * d;
+      }
+      sums[kS11] += acc;
+      continue;
+    }
     double s11 = 0.0, s12 = 0.0, s22 = 0.0;
     for (int j = 0; j < kept; ++j) {
       const double f1 = double(load_index(F1, itype, k * kept + j));
@@ -674,13 +704,15 @@ __global__ __launch_bounds__(kThreads) void k_reduce_dc(const void* __restrict__
 }
 
 template <int kIType, int kNType>
-void launch_reduce_vec2(bool two, bool dc, dim3 grid, hipStream_t s, const void* N1, const void* F1, const void* N2,
+void launch_reduce_vec2(bool two, bool dc, bool diff, dim3 grid, hipStream_t s, const void* N1, const void* F1, const void* N2,
                         const void* F2, int64_t nvec, int64_t chunk, int shift, int64_t vpb, int64_t seg_blocks,
                         const ReduceTail& tail) {
   const uint4* a = static_cast<const uint4*>(F1);
   const uint4* b = static_cast<const uint4*>(F2);
   dim3 block(kThreads);
-  if (two && dc)
+  if (diff)
+    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
+  else if (two && dc)
     hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
   else if (two)
     hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
@@ -691,13 +723,13 @@ void launch_reduce_vec2(bool two, bool dc, dim3 grid, hipStream_t s, const void*
 }
 
 template <int kIType>
-void launch_reduce_vec(int ntype, bool two, bool dc, dim3 grid, hipStream_t s, const void* N1, const void* F1,
+void launch_reduce_vec(int ntype, bool two, bool dc, bool diff, dim3 grid, hipStream_t s, const void* N1, const void* F1,
                        const void* N2, const void* F2, int64_t nvec, int64_t chunk, int shift, int64_t vpb,
                        int64_t seg_blocks, const ReduceTail& tail) {
   if (ntype == PBZ_F64)
-    launch_reduce_vec2<kIType, PBZ_F64>(two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
+    launch_reduce_vec2<kIType, PBZ_F64>(two, dc, diff, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
   else
-    launch_reduce_vec2<kIType, PBZ_F32>(two, dc, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
+    launch_reduce_vec2<kIType, PBZ_F32>(two, dc, diff, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
 }
 
 }  // namespace
@@ -773,7 +805,8 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
   tail.r = c->r;
   tail.n_blocks = double(n_blocks);
   tail.vol = double(c->vol);
-  const bool two = (op == kDot || op == kCosine || op == kCovariance || op == kSsim);
+  const bool diff = (op == kDiffNorm2);
+  const bool two = (op == kDot || op == kCosine || op == kCovariance || op == kSsim || diff);
   const bool dc = (op == kCovariance || op == kVariance || op == kSsim);
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
@@ -801,16 +834,16 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
       dim3 grid(groups, batch);
       const int shift = ilog2_exact(vpb);
       if (c->itype == PBZ_I8)
-        launch_reduce_vec<PBZ_I8>(int(c->ftype), two, dc, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
+        launch_reduce_vec<PBZ_I8>(int(c->ftype), two, dc, diff, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
       else if (c->itype == PBZ_I16)
-        launch_reduce_vec<PBZ_I16>(int(c->ftype), two, dc, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
+        launch_reduce_vec<PBZ_I16>(int(c->ftype), two, dc, diff, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
       else
-        launch_reduce_vec<PBZ_I32>(int(c->ftype), two, dc, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
+        launch_reduce_vec<PBZ_I32>(int(c->ftype), two, dc, diff, grid, s, n1, f1, n2, f2, nvec, chunk, shift, vpb, n_blocks, tail);
     } else {
       groups = stream_groups(n_blocks, 1);
       if (groups > max_groups) groups = max_groups;
       hipLaunchKernelGGL(k_reduce_generic, dim3(groups, batch), dim3(kThreads), 0, s, n1, f1, n2, f2, int(c->ftype),
-                         int(c->itype), n_blocks, c->kept, two ? 1 : 0, dc ? 1 : 0, tail);
+                         int(c->itype), n_blocks, c->kept, two ? 1 : 0, dc ? 1 : 0, diff ? 1 : 0, tail);
     }
     int st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;

@@ -207,7 +207,8 @@ class Case:
         return got
 
     # --- reductions ------------------------------------------------------------------------------
-    def check_reductions(self, N1, F1, N2, F2, ops=("dot", "norm2", "cosine_similarity", "mean", "covariance", "variance")):
+    def check_reductions(self, N1, F1, N2, F2, ops=("dot", "norm2", "cosine_similarity", "mean", "covariance", "variance",
+                                                      "difference_norm2")):
         A, B = self.oc(N1, F1), self.oc(N2, F2)
         na, nb = po.norm2(A), po.norm2(B)
         n_el = float(A.n_blocks) * float(np.prod(self.block))
@@ -225,6 +226,8 @@ class Case:
                 got, want, floor = self.codec.covariance(N1, F1, N2, F2), po.covariance(A, B), na * nb / n_el
             elif op == "variance":
                 got, want, floor = self.codec.variance(N1, F1), po.variance(A), na * na / n_el
+            elif op == "difference_norm2":    # each difference carries a rounding relative to its operands
+                got, want, floor = self.codec.difference_norm2(N1, F1, N2, F2), po.difference_norm2(A, B), na + nb
             else:
                 raise ValueError(op)
             torch.cuda.synchronize()

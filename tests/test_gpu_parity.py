@@ -80,7 +80,8 @@ def test_series_per_step_statistics():
     for name, ref in want.items():
         got = case.codec.segmented(name, steps, per, N, F).cpu().numpy()
         assert np.allclose(got, ref, rtol=1e-5, atol=0), name
-    for name, fn in (("covariance", po.covariance), ("dot", po.dot), ("cosine_similarity", po.cosine_similarity)):
+    for name, fn in (("covariance", po.covariance), ("dot", po.dot), ("cosine_similarity", po.cosine_similarity),
+                     ("difference_norm2", po.difference_norm2)):
         got = case.codec.segmented(name, steps - 1, per, N, F, N[per:], F[per:]).cpu().numpy()
         ref = [fn(steps_o[t], steps_o[t + 1]) for t in range(steps - 1)]
         assert np.allclose(got, ref, rtol=1e-5, atol=1e-5 * max(abs(v) for v in ref)), name
