@@ -200,7 +200,23 @@ def main():
     if has_dc:
         bw = torch.empty(lay.n_blocks, dtype=torch.float64, device=dev)
         bw_bytes = lay.n_blocks * 8
+        st3 = torch.empty(3, dtype=torch.float64, device=dev)
+
+        def compress_then_three_reductions():
+            codec.compress(xA, N1, F1)
+            codec.mean(N1, F1, out=st3[0:1])
+            codec.variance(N1, F1, out=st3[1:2])
+            codec.norm2(N1, F1, out=st3[2:3])
+
+        def compress_then_one_pass():
+            codec.compress(xA, N1, F1)
+            codec.statistics(N1, F1, out=st3)
+
         extras += [
+            # a time step compressed and its mean / variance / norm taken: fused, against the separate calls
+            ("compress_statistics_fused", lambda: codec.compress_statistics(xA, N1, F1, out=st3), in_bytes + comp_bytes),
+            ("compress_then_statistics_one_pass", compress_then_one_pass, in_bytes + 2 * comp_bytes),
+            ("compress_then_mean_variance_norm2", compress_then_three_reductions, in_bytes + 3 * comp_bytes + dc_bytes),
             ("add_scalar", lambda: codec.add_scalar(N1, F1, 0.75, N_out=Nn, F_out=Fn), 2 * comp_bytes),
             ("ssim", lambda: codec.ssim(N1, F1, N2, F2, out=scal[6:7]), 2 * comp_bytes),
             ("blockwise_mean", lambda: codec.blockwise_mean(N1, F1, out=bw), dc_bytes + bw_bytes),

@@ -110,6 +110,19 @@ int pbz_compressed_bits(const pbz_codec* codec, const int64_t* shape, uint64_t* 
 int pbz_compress(const pbz_codec* codec, const void* x, pbz_ftype x_type, const int64_t* shape, void* N,
                  void* F, void* stream);
 
+/* Compression as pbz_compress plus, from the same pass over x, the statistics of the compressed array that a
+ * time-series analysis takes of every step (Sec. V): statistics (device, 3 FP64 values, written) receives
+ * {mean (Algorithm 7), variance (Algorithm 9), L2 norm (Algorithm 10)}, the values pbz_mean, pbz_variance and
+ * pbz_norm2 return for the {N, F} produced, up to FP64 summation order, without reading {N, F} back.
+ * Requires the mask to keep each block's first coefficient (PBZ_ERR_DC_PRUNED otherwise).
+ *   workspace   device, 16-byte aligned, at least the bytes pbz_compress_statistics_workspace reports for this
+ *               shape and x_type (the reduction scratch plus two FP64 sums per wave of the compress kernel);
+ *               contents on entry do not matter; PBZ_ERR_WORKSPACE when too small or misaligned. */
+int pbz_compress_statistics_workspace(const pbz_codec* codec, const int64_t* shape, pbz_ftype x_type,
+                                      size_t* bytes);
+int pbz_compress_statistics(const pbz_codec* codec, const void* x, pbz_ftype x_type, const int64_t* shape, void* N,
+                            void* F, double* statistics, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Sec. III-B: C = N F / r at the mask positions and zero elsewhere, inverse transform, merge blocks,
  * crop to `shape`, convert to y_type (round to nearest even).
  *   y       device, prod(shape) elements of y_type; written. */
@@ -150,6 +163,11 @@ int pbz_cosine_similarity(const pbz_codec* codec, int64_t n_blocks, const void* 
                           size_t workspace_bytes, void* stream);
 int pbz_norm2(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* out,
               void* workspace, size_t workspace_bytes, void* stream);
+/* {mean, variance, L2 norm} (Algorithms 7, 9, 10) of one compressed array from a single pass over {N, F}:
+ * statistics (device) receives 3 FP64 values.  Other arguments as for pbz_variance. */
+int pbz_statistics(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* statistics,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
 /* ||A - B||_2 of two compressed arrays (the quantity compared between adjacent time steps in Sec. V, fission
  * experiment), taken on the specified coefficients of Algorithm 3: sqrt(sum_kj (N1_k F1_kj - N2_k F2_kj)^2) / r,
  * each difference formed in FP64 before squaring.  The transform being orthonormal, this is the L2 norm of the

@@ -44,6 +44,9 @@ SIGNATURES = {
     "pbz_dot": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_covariance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_cosine_similarity": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_compress_statistics_workspace": (_c.c_int, [_p, _i64p, _c.c_int, _c.POINTER(_c.c_size_t)]),
+    "pbz_compress_statistics": (_c.c_int, [_p, _p, _c.c_int, _i64p, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_statistics": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_difference_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_mean": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
@@ -209,6 +212,36 @@ class Codec:
             N, F = self.empty_compressed(x.shape, x.device)
         check(self._lib.pbz_compress(self._h, _ptr(x), _ftype_of(x), _shape_arr(x.shape), _ptr(N), _ptr(F), _stream()))
         return N, F
+
+    def compress_statistics_workspace(self, shape: Sequence[int], array_type: str) -> int:
+        n = _c.c_size_t()
+        check(self._lib.pbz_compress_statistics_workspace(self._h, _shape_arr(shape), FTYPES[array_type], _c.byref(n)))
+        return n.value
+
+    def compress_statistics(self, x, N=None, F=None, out=None, workspace=None):
+        """pbz_compress_statistics: x -> (N, F, statistics) with statistics = [mean, variance, norm2] (float64)."""
+        torch = _torch()
+        if N is None or F is None:
+            N, F = self.empty_compressed(x.shape, x.device)
+        out = torch.empty(3, dtype=torch.float64, device=x.device) if out is None else out
+        if workspace is None:
+            need = _c.c_size_t()
+            check(self._lib.pbz_compress_statistics_workspace(self._h, _shape_arr(x.shape), _ftype_of(x), _c.byref(need)))
+            key = ("stats", x.device.type, x.device.index)
+            if key not in self._ws or self._ws[key].numel() < need.value:
+                self._ws[key] = torch.empty(need.value, dtype=torch.uint8, device=x.device)
+            workspace = self._ws[key]
+        check(self._lib.pbz_compress_statistics(self._h, _ptr(x), _ftype_of(x), _shape_arr(x.shape), _ptr(N), _ptr(F),
+                                                _ptr(out), _ptr(workspace), workspace.numel(), _stream()))
+        return N, F, out
+
+    def statistics(self, N, F, out=None):
+        """pbz_statistics: [mean, variance, norm2] of one compressed array from one pass (float64, 3 values)."""
+        torch = _torch()
+        out = torch.empty(3, dtype=torch.float64, device=N.device) if out is None else out
+        ws = self.workspace(N.device)
+        check(self._lib.pbz_statistics(self._h, F.shape[0], _ptr(N), _ptr(F), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
 
     def decompress(self, N, F, shape: Sequence[int], dtype=None, out=None):
         """pbz_decompress: (N, F) -> array of `shape` in `dtype` (a torch dtype; default: the working type)."""

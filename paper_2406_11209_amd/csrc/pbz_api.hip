@@ -238,6 +238,46 @@ int pbz_compress(const pbz_codec* c, const void* x, pbz_ftype x_type, const int6
   return launch_compress_generic(c, g, t, x, x_type, N, F, s);
 }
 
+int pbz_compress_statistics_workspace(const pbz_codec* c, const int64_t* shape, pbz_ftype x_type, size_t* bytes) {
+  if (!c || !shape || !bytes) return PBZ_ERR_NULL;
+  if (!valid_ftype(x_type)) return PBZ_ERR_TYPE;
+  Geom g;
+  int st = make_geom(c, shape, &g);
+  if (st != PBZ_OK) return st;
+  const int64_t tiles = c->path == PBZ_PATH_AUTO ? fast_compress_tiles(c, g, x_type) : 0;
+  *bytes = kWorkspaceBytes + size_t(tiles) * 2 * sizeof(double);
+  return PBZ_OK;
+}
+
+int pbz_compress_statistics(const pbz_codec* c, const void* x, pbz_ftype x_type, const int64_t* shape, void* N, void* F,
+                            double* statistics, void* ws, size_t ws_bytes, void* stream) {
+  if (!c || !x || !shape || !N || !F || !statistics || !ws) return PBZ_ERR_NULL;
+  if (!valid_ftype(x_type)) return PBZ_ERR_TYPE;
+  Geom g;
+  int st = make_geom(c, shape, &g);
+  if (st != PBZ_OK) return st;
+  if (!c->dc_kept) return PBZ_ERR_DC_PRUNED;
+  if (ws_bytes < kWorkspaceBytes || (reinterpret_cast<uintptr_t>(ws) & 15u)) return PBZ_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (c->path == PBZ_PATH_AUTO) {
+    // the compress kernel leaves two sums per tile behind the reduction scratch; adding them costs two small launches
+    const int64_t tiles = fast_compress_tiles(c, g, x_type);
+    if (tiles > 0 && ws_bytes >= kWorkspaceBytes + size_t(tiles) * 2 * sizeof(double)) {
+      double* tile_sums = reinterpret_cast<double*>(static_cast<char*>(ws) + kWorkspaceBytes);
+      const char* name = nullptr;
+      int r = try_compress_fast(c, g, x, x_type, N, F, s, false, &name, tile_sums);
+      if (r < 0) return r;
+      if (r > 0) return launch_statistics_from_tiles(c, g.n_blocks, tile_sums, tiles, statistics, ws, s);
+    } else if (tiles > 0) {
+      return PBZ_ERR_WORKSPACE;
+    }
+  }
+  // no specialised kernel: compress, then one pass over {N, F} for the two sums
+  st = pbz_compress(c, x, x_type, shape, N, F, stream);
+  if (st != PBZ_OK) return st;
+  return launch_reduce(c, kStatistics, g.n_blocks, N, F, nullptr, nullptr, statistics, ws, s);
+}
+
 int pbz_decompress(const pbz_codec* c, const void* N, const void* F, const int64_t* shape, void* y,
                    pbz_ftype y_type, void* stream) {
   if (!c || !N || !F || !shape || !y) return PBZ_ERR_NULL;
@@ -341,6 +381,11 @@ int pbz_mean(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F,
              size_t ws_bytes, void* stream) {
   return reduce2(c, kMean, n_blocks, N, F, nullptr, nullptr, out, ws, ws_bytes, stream, false, true);
 }
+int pbz_statistics(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* statistics, void* ws,
+                   size_t ws_bytes, void* stream) {
+  return reduce2(c, kStatistics, n_blocks, N, F, nullptr, nullptr, statistics, ws, ws_bytes, stream, false, true);
+}
+
 int pbz_variance(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out, void* ws,
                  size_t ws_bytes, void* stream) {
   return reduce2(c, kVariance, n_blocks, N, F, nullptr, nullptr, out, ws, ws_bytes, stream, false, true);

@@ -161,6 +161,46 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// ---- statistics emitted while compressing ---------------------------------------------------------------
+// With kStats a compress kernel also leaves, per wave, the two sums that the mean (Algorithm 7), the variance
+// (Algorithm 9) and the L2 norm (Algorithm 10) of the array it has just compressed are made of:
+//   S11 = sum_k N_k^2 sum_j F_kj^2   and   D1 = sum_k N_k F_k0   over the wave's blocks,
+// N_k as stored, the integer sums exact.  tile_sums[2 t], tile_sums[2 t + 1] belong to tile
+// t = bz * tiles_yx + by * tiles_x + tx; a later kernel adds them in index order.
+typedef short short2s __attribute__((ext_vector_type(2)));
+
+template <typename IT, int kWords>
+__device__ __forceinline__ double sum_of_squares(const uint32_t* w) {   // of the indices packed in w[0 .. kWords)
+  if constexpr (sizeof(IT) == 1) {
+    static_assert(kWords * 4 * 127 * 127 < (1LL << 31), "fits 32 bits");
+    int acc = 0;
+#pragma unroll
+    for (int k = 0; k < kWords; ++k) acc = __builtin_amdgcn_sdot4(int(w[k]), int(w[k]), acc, false);
+    return double(acc);
+  } else {
+    long long acc = 0;      // one dword: 2 * 32767^2 < 2^31
+#pragma unroll
+    for (int k = 0; k < kWords; ++k) {
+      short2s h;
+      h.x = short(w[k] & 0xffffu);
+      h.y = short(w[k] >> 16);
+      acc += (long long)__builtin_amdgcn_sdot2(h, h, 0, false);
+    }
+    return double(acc);
+  }
+}
+
+__device__ __forceinline__ void emit_tile_sums(double* __restrict__ tile_sums, const FastGeom& g, int64_t tx, int64_t by,
+                                               int64_t bz, double s11, double d1) {
+  s11 = wave_sum(s11);
+  d1 = wave_sum(d1);
+  if ((threadIdx.x & 63) == 0) {
+    const int64_t t = bz * int64_t(g.tiles_yx) + by * int64_t(g.tiles_x) + tx;
+    tile_sums[2 * t] = s11;
+    tile_sums[2 * t + 1] = d1;
+  }
+}
+
 __device__ __forceinline__ uint4 f4_bits(const float* v) {
   return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
 }
@@ -226,9 +266,10 @@ __device__ __forceinline__ void inverse_block(T* v) {
 // kRagged: the slow dimensions are not multiples of the block extents, so some block rows lie outside the
 // array.  Such rows are still loaded (from a clamped, valid address: a branch around a load would make the
 // compiler wait for all outstanding loads at the join) and zeroed afterwards.
-template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX, bool kRagged>
+template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX, bool kRagged,
+          bool kStats>
 __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __restrict__ x, NT* __restrict__ N,
-                                                       IT* __restrict__ F) {
+                                                       IT* __restrict__ F, double* __restrict__ tile_sums) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
   constexpr int RV = BX * int(sizeof(XT)) / 16;       // 16-byte loads per block row
   constexpr int PER16 = Unpack<T, XT>::n;
@@ -296,6 +337,10 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   }
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 64;   // first block of this wave
   if (active) N[block0 + lane] = NT(m);
+  if constexpr (kStats) {
+    const double n = active ? double(NT(m)) : 0.0;
+    emit_tile_sums(tile_sums, g, tx, by, bz, sum_of_squares<IT, KW>(w) * (n * n), n * double(IdxPack<IT>::get(w[0], 0)));
+  }
   constexpr int P = KW / 4;                                   // 16-byte pieces of F per block
   if constexpr (P >= 4) {
     // Lane-strided 16-byte stores 64 bytes or more apart run at about half the write bandwidth of linear
@@ -379,9 +424,9 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
 // =====================================================================================================
 constexpr int kQuadRow = 65;   // uint4 per LDS row: 64 + 1 of padding so that column reads spread over the banks
 
-template <bool kRagged>
+template <bool kRagged, bool kStats>
 __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float* __restrict__ x, float* __restrict__ N,
-                                                         int8_t* __restrict__ F) {
+                                                         int8_t* __restrict__ F, double* __restrict__ tile_sums) {
   __shared__ uint4 lds[2][16 * kQuadRow];
   const int lane = threadIdx.x & 63;
   int64_t tx, by, bz;
@@ -426,6 +471,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
   for (int j = 0; j < 4; ++j) dct::forward<float, 16, 1>(u + j * 16);
 
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 16;
+  double s11 = 0.0, d1 = 0.0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     float m = 0.0f;
@@ -447,8 +493,14 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
       // piece index within the wave's span of F: blk * 16 + yrow == j * 64 + lane, linear in the lane
       reinterpret_cast<uint4*>(F + (block0 + blk) * 256)[yrow] = make_uint4(w[0], w[1], w[2], w[3]);
       if (yrow == 0) N[block0 + blk] = m;
+      if constexpr (kStats) {
+        const double n = double(m);
+        s11 += sum_of_squares<int8_t, 4>(w) * (n * n);
+        if (yrow == 0) d1 += n * double(IdxPack<int8_t>::get(w[0], 0));
+      }
     }
   }
+  if constexpr (kStats) emit_tile_sums(tile_sums, g, tx, by, bz, s11, d1);
 }
 
 __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const float* __restrict__ N,
@@ -511,9 +563,10 @@ __device__ __forceinline__ int oct_slot(int b, int yy, int z) {
 
 constexpr int kOctWaves = 4;   // waves per workgroup: neighbouring tiles, so that a workgroup reads 512-byte row pieces
 
-template <int KZ, int KY, int KX, bool kRagged>
+template <int KZ, int KY, int KX, bool kRagged, bool kStats>
 __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x,
-                                                                  float* __restrict__ N, int8_t* __restrict__ F) {
+                                                                  float* __restrict__ N, int8_t* __restrict__ F,
+                                                                  double* __restrict__ tile_sums) {
   static_assert(KX == 4 || KX == 8, "a kept row is one or two dwords of int8");
   constexpr int KEPT = KZ * KY * KX;
   __shared__ uint4 lds[kOctWaves][8 * 64];
@@ -579,6 +632,8 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
   // kept entries of this lane: z < KZ, x < KX when j < KY; staged in LDS at their position in the wave's span of F
   static_assert(8 * KEPT <= 8 * 64 * 16, "the staged F of a tile fits the exchange buffer");
   uint32_t* st32 = reinterpret_cast<uint32_t*>(st);
+  int squares = 0;            // of this lane's kept indices: at most 64 * 127^2
+  uint32_t first = 0;         // the dword that starts with F_k0 (lanes with j == 0)
   if (j < KY) {
 #pragma unroll
     for (int zq = 0; zq < KZ; ++zq)
@@ -587,8 +642,18 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
         int q4[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) q4[e] = int(rintf(u[zq * 8 + k * 4 + e] * inv));
-        st32[(bb * KEPT + (zq * KY + j) * KX) / 4 + k] = IdxPack<int8_t>::pack(q4);
+        const uint32_t pw = IdxPack<int8_t>::pack(q4);
+        st32[(bb * KEPT + (zq * KY + j) * KX) / 4 + k] = pw;
+        if constexpr (kStats) {
+          squares = __builtin_amdgcn_sdot4(int(pw), int(pw), squares, false);
+          if (zq == 0 && k == 0) first = pw;
+        }
       }
+  }
+  if constexpr (kStats) {
+    const double n = tx * 8 + bb < g.gx ? double(m) : 0.0;
+    emit_tile_sums(tile_sums, g, tx, by, bz, double(squares) * (n * n),
+                   j == 0 ? n * double(IdxPack<int8_t>::get(first, 0)) : 0.0);
   }
   wave_lds_sync();
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 8;
@@ -737,15 +802,22 @@ struct LaneKernel {
     dim3 grid;
     return tile_grid(g, 64, 4, &grid) ? 1 : 0;
   }
-  static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
+  static int64_t tiles(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 64, 4, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
+  }
+  template <bool kRagged, bool kStats>
+  static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    hipLaunchKernelGGL((k_compress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kStats>), grid, dim3(256), 0, s, g,
+                       static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F), tile_sums);
+  }
+  // tile_sums != nullptr: also the per-wave statistic sums (two doubles per tile)
+  static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 64, 4, &grid)) return 0;
-    if (g.Z % BZ || g.Y % BY)
-      hipLaunchKernelGGL((k_compress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, true>), grid, dim3(256), 0, s, g,
-                         static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F));
-    else
-      hipLaunchKernelGGL((k_compress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, false>), grid, dim3(256), 0, s, g,
-                         static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F));
+    const bool ragged = g.Z % BZ || g.Y % BY;
+    if (tile_sums) ragged ? launch<true, true>(g, grid, x, N, F, tile_sums, s) : launch<false, true>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false>(g, grid, x, N, F, nullptr, s) : launch<false, false>(g, grid, x, N, F, nullptr, s);
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
@@ -778,15 +850,21 @@ struct Quad16Kernel {
     dim3 grid;
     return tile_grid(g, 16, 2, &grid) ? 1 : 0;
   }
-  static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
+  static int64_t tiles(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 16, 2, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
+  }
+  template <bool kRagged, bool kStats>
+  static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    hipLaunchKernelGGL((k_compress_quad16<kRagged, kStats>), grid, dim3(128), 0, s, g, static_cast<const float*>(x),
+                       static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
+  }
+  static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 16, 2, &grid)) return 0;
-    if (g.Y % 16)
-      hipLaunchKernelGGL(k_compress_quad16<true>, grid, dim3(128), 0, s, g, static_cast<const float*>(x),
-                         static_cast<float*>(N), static_cast<int8_t*>(F));
-    else
-      hipLaunchKernelGGL(k_compress_quad16<false>, grid, dim3(128), 0, s, g, static_cast<const float*>(x),
-                         static_cast<float*>(N), static_cast<int8_t*>(F));
+    const bool ragged = g.Y % 16;
+    if (tile_sums) ragged ? launch<true, true>(g, grid, x, N, F, tile_sums, s) : launch<false, true>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false>(g, grid, x, N, F, nullptr, s) : launch<false, false>(g, grid, x, N, F, nullptr, s);
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
@@ -809,15 +887,21 @@ struct Oct8Kernel {
     dim3 grid;
     return tile_grid(g, 8, kOctWaves, &grid) ? 1 : 0;
   }
-  static int compress(FastGeom g, const void* x, void* N, void* F, hipStream_t s) {
+  static int64_t tiles(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 8, kOctWaves, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
+  }
+  template <bool kRagged, bool kStats>
+  static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, kRagged, kStats>), grid, dim3(kOctWaves * 64), 0, s, g,
+                       static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
+  }
+  static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 8, kOctWaves, &grid)) return 0;
-    if (g.Z % 8 || g.Y % 8)
-      hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, true>), grid, dim3(kOctWaves * 64), 0, s, g,
-                         static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F));
-    else
-      hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, false>), grid, dim3(kOctWaves * 64), 0, s, g,
-                         static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F));
+    const bool ragged = g.Z % 8 || g.Y % 8;
+    if (tile_sums) ragged ? launch<true, true>(g, grid, x, N, F, tile_sums, s) : launch<false, true>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false>(g, grid, x, N, F, nullptr, s) : launch<false, false>(g, grid, x, N, F, nullptr, s);
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
@@ -843,15 +927,25 @@ using Oct8_full = Oct8Kernel<8, 8, 8>;
 }  // namespace
 
 int try_compress_fast(const pbz_codec* c, const Geom& geo, const void* x, int xtype, void* N, void* F, hipStream_t s,
-                      bool dry_run, const char** name) {
+                      bool dry_run, const char** name, double* tile_sums) {
   if (!aligned16(x) || !aligned16(F)) return 0;
   const Folded f = fold(c, geo);
   if (!f.ok) return 0;
 #define X(K, NAME)                                          \
   if (K::matches(c, f, xtype)) {                            \
     *name = NAME;                                           \
-    return dry_run ? K::fits(f.g) : K::compress(f.g, x, N, F, s); \
+    return dry_run ? K::fits(f.g) : K::compress(f.g, x, N, F, tile_sums, s); \
   }
+  PBZ_FOR_EACH_LANE_KERNEL(X)
+#undef X
+  return 0;
+}
+
+int64_t fast_compress_tiles(const pbz_codec* c, const Geom& geo, int xtype) {
+  const Folded f = fold(c, geo);
+  if (!f.ok) return 0;
+#define X(K, NAME) \
+  if (K::matches(c, f, xtype)) return K::tiles(f.g);
   PBZ_FOR_EACH_LANE_KERNEL(X)
 #undef X
   return 0;

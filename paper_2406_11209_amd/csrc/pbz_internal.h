@@ -76,8 +76,11 @@ int launch_decompress_generic(const pbz_codec* c, const Geom& g, const DeviceTab
 
 // specialised codec kernels; return 1 when they handled the call, 0 when the shape / types are not
 // covered (caller falls back to the generic kernels), negative on a HIP error
+// tile_sums != nullptr: the kernel also leaves two FP64 sums per tile (wave) there, fast_compress_tiles() pairs
+// in all, from which launch_statistics_from_tiles() makes the mean, variance and L2 norm of the compressed array
 int try_compress_fast(const pbz_codec* c, const Geom& g, const void* x, int xtype, void* N, void* F,
-                      hipStream_t s, bool dry_run, const char** name);
+                      hipStream_t s, bool dry_run, const char** name, double* tile_sums = nullptr);
+int64_t fast_compress_tiles(const pbz_codec* c, const Geom& g, int xtype);   // 0: no specialised kernel covers it
 int try_decompress_fast(const pbz_codec* c, const Geom& g, const void* N, const void* F, void* y, int ytype,
                         hipStream_t s, bool dry_run, const char** name);
 
@@ -89,12 +92,14 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
                const void* F2, void* Nout, void* Fout, hipStream_t s);
 
 enum ReduceOp { kDot = 0, kNorm2 = 1, kCosine = 2, kMean = 3, kCovariance = 4, kVariance = 5, kSsim = 6,
-                kDiffNorm2 = 7 };
+                kDiffNorm2 = 7, kStatistics = 8 /* out[0..3) = mean, variance, norm2 from one pass */ };
 // ssim_params: {s_l, s_c, w_l, w_c, w_s} for kSsim, otherwise nullptr.  n_segments > 1: the operands are
 // n_segments consecutive runs of n_blocks blocks, one result per run goes to out[0 .. n_segments).
 int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1,
                   const void* N2, const void* F2, double* out, void* workspace, hipStream_t s,
                   const double* ssim_params = nullptr, int64_t n_segments = 1);
+int launch_statistics_from_tiles(const pbz_codec* c, int64_t n_blocks, const double* tile_sums, int64_t n_tiles,
+                                 double* out, void* workspace, hipStream_t s);
 int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,
                       void* Fout, hipStream_t s);
 int launch_blockwise_mean(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out,

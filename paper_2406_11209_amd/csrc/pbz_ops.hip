@@ -557,7 +557,32 @@ __global__ __launch_bounds__(kThreads) void k_reduce_final(ReduceTail t, int n_p
   const double grand = group_total(acc, lds);
   if (threadIdx.x < kNumSums) fin[threadIdx.x] = grand;
   __syncthreads();
-  if (threadIdx.x == 0) t.out[blockIdx.x] = finish_statistic(fin, t);
+  if (threadIdx.x == 0) {
+    if (t.op == kStatistics) {            // mean, variance and norm2 of one array from the same two sums
+      ReduceTail one = t;
+      const int ops[3] = {kMean, kVariance, kNorm2};
+      for (int i = 0; i < 3; ++i) {
+        one.op = ops[i];
+        t.out[int64_t(blockIdx.x) * 3 + i] = finish_statistic(fin, one);
+      }
+    } else {
+      t.out[blockIdx.x] = finish_statistic(fin, t);
+    }
+  }
+}
+
+// per-tile sums {S11, D1} left by a compress kernel -> partial sums per workgroup, added in tile order
+__global__ __launch_bounds__(kThreads) void k_reduce_tiles(const double2* __restrict__ tile_sums, int64_t n_tiles,
+                                                           int64_t chunk, ReduceTail tail) {
+  double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
+  const int64_t begin = int64_t(blockIdx.x) * chunk;
+  const int64_t end = begin + chunk < n_tiles ? begin + chunk : n_tiles;
+  for (int64_t t = begin + threadIdx.x; t < end; t += kThreads) {
+    const double2 v = tile_sums[t];
+    sums[kS11] += v.x;
+    sums[kD1] += v.y;
+  }
+  reduce_tail(sums, tail);
 }
 
 // kDiff: the coefficients of the two operands are subtracted element by element before squaring (their
@@ -807,7 +832,7 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
   tail.vol = double(c->vol);
   const bool diff = (op == kDiffNorm2);
   const bool two = (op == kDot || op == kCosine || op == kCovariance || op == kSsim || diff);
-  const bool dc = (op == kCovariance || op == kVariance || op == kSsim);
+  const bool dc = (op == kCovariance || op == kVariance || op == kSsim || op == kStatistics);
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
   const int64_t n_stride = n_blocks * ftype_bytes(c->ftype), f_stride = n_blocks * bpb;   // bytes per segment
@@ -852,6 +877,29 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     if (st != PBZ_OK) return st;
   }
   return PBZ_OK;
+}
+
+int launch_statistics_from_tiles(const pbz_codec* c, int64_t n_blocks, const double* tile_sums, int64_t n_tiles,
+                                 double* out, void* workspace, hipStream_t s) {
+  ReduceTail tail;
+  tail.s_l = tail.s_c = 0.0;
+  tail.w_l = tail.w_c = tail.w_s = 1.0;
+  tail.partials = static_cast<double*>(workspace);
+  tail.out = out;
+  tail.op = int(kStatistics);
+  tail.r = c->r;
+  tail.n_blocks = double(n_blocks);
+  tail.vol = double(c->vol);
+  // four tiles per thread and step, at most 1024 workgroups
+  int64_t chunk = int64_t(kThreads) * 4;
+  if ((n_tiles + chunk - 1) / chunk > 1024) chunk = ((n_tiles + 1023) / 1024 + kThreads - 1) / kThreads * kThreads;
+  const int groups = int((n_tiles + chunk - 1) / chunk);
+  hipLaunchKernelGGL(k_reduce_tiles, dim3(groups), dim3(kThreads), 0, s, reinterpret_cast<const double2*>(tile_sums),
+                     n_tiles, chunk, tail);
+  int st = hip_status(hipGetLastError());
+  if (st != PBZ_OK) return st;
+  hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(kThreads), 0, s, tail, groups);
+  return hip_status(hipGetLastError());
 }
 
 int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,

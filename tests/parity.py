@@ -136,6 +136,24 @@ class Case:
         n_bad = check_indices(F.cpu().numpy(), ref.F, ref.t, self.tau)
         return N, F, ref, n_bad
 
+    def check_compress_statistics(self, N, F, which="A"):
+        """The fused entry point writes the same {N, F} as pbz_compress, and its statistics (and those of the
+        one-pass pbz_statistics) are the oracle's mean / variance / norm2 of that compressed array."""
+        x_dev = self.xA if which == "A" else self.xB
+        Ns, Fs, st = self.codec.compress_statistics(x_dev)
+        one_pass = self.codec.statistics(N, F)
+        torch.cuda.synchronize()
+        assert torch.equal(Fs, F) and torch.equal(Ns, N), "fused compress differs from pbz_compress"
+        A = self.oc(N, F)
+        na = po.norm2(A)
+        n_el = float(A.n_blocks) * float(np.prod(self.block))
+        want = (po.mean(A), po.variance(A), na)
+        floors = (na / math.sqrt(n_el), na * na / n_el, 0.0)
+        for got in (st.cpu().numpy(), one_pass.cpu().numpy()):
+            for g, w, f, name in zip(got, want, floors, ("mean", "variance", "norm2")):
+                check_scalar(float(g), w, self.tol, f, "statistics." + name)
+        return st
+
     def oc(self, N, F) -> po.Compressed:
         return oracle_compressed(N, F, self.shape, self.block, self.bits, self.ftype, self.mask)
 

@@ -41,6 +41,7 @@ def run_all_ops(case: Case, out_dtypes=()):
         ops += ["mean", "covariance", "variance"]
     case.check_reductions(N1, F1, N2, F2, ops)
     if has_dc:
+        case.check_compress_statistics(N1, F1, "A")
         for x in (0.75, -3.0):
             N4, F4 = case.check_add_scalar(N1, F1, x)
         case.check_decompress(N4, F4)
@@ -118,6 +119,33 @@ def test_ragged_shapes_and_other_settings(spec, path):
             "bf16": synth.to_bf16_bits}[dtype]
     mask = None if keep is None else synth.low_frequency_mask(block, keep)
     case = Case(cast(mk()), cast(mk()), dtype, block, bits, ftype, mask, path)
+    run_all_ops(case)
+
+
+# last extent a multiple of the block's, the slower ones ragged: the specialised kernels' padded variants,
+# partly filled waves included
+FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
+               ((37, 1048), (8, 8), 16, "f32", "f32", (4, 4), "lane_f32_8x8_i16_box4x4"),
+               ((21, 72), (8, 8), 16, "f32", "f32", None, "lane_f32_8x8_i16"),
+               ((5, 30, 20), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
+               ((9, 13, 520), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
+               ((3, 33, 48), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8"),
+               ((2, 19, 560), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8"),
+               ((17, 9, 24), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
+               ((9, 17, 200), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
+               ((17, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
+
+
+@pytest.mark.parametrize("spec", FAST_RAGGED, ids=[f"{s[0]}-{s[6]}" for s in FAST_RAGGED])
+def test_specialised_kernels_on_ragged_shapes(spec):
+    shape, block, bits, dtype, ftype, keep, kernel = spec
+    g = rng(300 + len(shape) + bits)
+    mk = lambda: synth.bump_field(shape, 6, g, (2.0, 8.0)) + 0.2 + 0.01 * g.standard_normal(shape)
+    cast = {"f64": lambda a: a, "f32": lambda a: a.astype(np.float32), "bf16": synth.to_bf16_bits}[dtype]
+    mask = None if keep is None else synth.low_frequency_mask(block, keep)
+    case = Case(cast(mk()), cast(mk()), dtype, block, bits, ftype, mask, api.PBZ_PATH_AUTO)
+    assert case.codec.kernel_name("compress", shape, dtype) == kernel
+    assert case.codec.kernel_name("decompress", shape, dtype) == kernel
     run_all_ops(case)
 
 

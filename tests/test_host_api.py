@@ -23,7 +23,7 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     lib = api.load_library()
     names = header_functions()
-    assert len(names) == 26
+    assert len(names) == 29
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(api.SIGNATURES) == names        # the binding covers exactly the header
@@ -142,6 +142,17 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.pbz_segmented(h, 1, 0, 4, p, p, None, None, p, p, 1 << 20, None) == -7
     assert lib.pbz_segmented(nodc._h, 3, 2, 4, p, p, None, None, p, p, 1 << 20, None) == -6
     assert lib.pbz_add_scalar(h, 4, p, p, float("nan"), p, p, None) == -9
+    assert lib.pbz_difference_norm2(h, 4, p, p, p, None, p, p, 1 << 20, None) == -1
+    assert lib.pbz_statistics(nodc._h, 4, p, p, p, p, 1 << 20, None) == -6
+    assert lib.pbz_statistics(h, 4, p, p, p, p, 64, None) == -8
+    need = ctypes.c_size_t()
+    assert lib.pbz_compress_statistics_workspace(h, shape, 1, ctypes.byref(need)) == 0
+    assert need.value == c.layout((16, 16)).workspace_bytes + 2 * 16      # two block rows, one wave each, two FP64 sums per wave
+    assert lib.pbz_compress_statistics_workspace(h, bad_shape, 1, ctypes.byref(need)) == -7
+    assert lib.pbz_compress_statistics(h, p, 1, shape, p, p, None, p, 1 << 20, None) == -1
+    assert lib.pbz_compress_statistics(nodc._h, p, 1, shape, p, p, p, p, 1 << 20, None) == -6
+    assert lib.pbz_compress_statistics(h, p, 1, shape, p, p, p, p, 64, None) == -8
+    assert lib.pbz_compress_statistics(h, p, 1, shape, p, p, p, p, c.layout((16, 16)).workspace_bytes, None) == -8
     assert lib.pbz_ssim(h, 4, p, p, p, p, float("inf"), 0.0, 1.0, 1.0, 1.0, p, p, 1 << 20, None) == -9
     assert lib.pbz_ssim(h, 4, p, p, p, p, 0.0, 0.0, 1.0, 1.0, 1.0, p, p, 64, None) == -8
 
