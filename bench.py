@@ -233,7 +233,19 @@ def main():
                 for t in range(T):
                     codec.variance(N1[t * per:(t + 1) * per], F1[t * per:(t + 1) * per], out=seg[t:t + 1])
 
+            st_rows = torch.empty((T, 3), dtype=torch.float64, device=dev)
+
+            def series_compress_then_segmented():
+                codec.compress(xA, N1, F1)
+                for k, name in enumerate(("mean", "variance", "norm2")):
+                    codec.segmented(name, T, per, N1, F1, out=seg)
+
             extras += [
+                # every step compressed and its mean / variance / norm emitted: one fused call vs compress + 3 segmented
+                ("series_compress_statistics_per_step_fused",
+                 lambda: codec.compress_statistics(xA, N1, F1, out=st_rows, per_step=True), in_bytes + comp_bytes),
+                ("series_compress_then_three_segmented", series_compress_then_segmented,
+                 in_bytes + 3 * comp_bytes + dc_bytes),
                 ("series_mean_segmented", lambda: codec.segmented("mean", T, per, N1, F1, out=seg), dc_bytes),
                 ("series_variance_segmented", lambda: codec.segmented("variance", T, per, N1, F1, out=seg), comp_bytes),
                 ("series_covariance_consecutive_segmented",

@@ -111,9 +111,13 @@ int pbz_compress(const pbz_codec* codec, const void* x, pbz_ftype x_type, const 
                  void* F, void* stream);
 
 /* Compression as pbz_compress plus, from the same pass over x, the statistics of the compressed array that a
- * time-series analysis takes of every step (Sec. V): statistics (device, 3 FP64 values, written) receives
+ * time-series analysis takes of every step (Sec. V): statistics (device, FP64, written) receives the triple
  * {mean (Algorithm 7), variance (Algorithm 9), L2 norm (Algorithm 10)}, the values pbz_mean, pbz_variance and
  * pbz_norm2 return for the {N, F} produced, up to FP64 summation order, without reading {N, F} back.
+ *   per_step    0: one triple for the whole array (3 values).  Non-zero: one triple per block index along
+ *               dimension 0, i.e. per run of prod(b[1:]) consecutive blocks, 3 * ceil(shape[0] / block[0]) values,
+ *               triple t at statistics[3 t]; with block extent 1 along time these are the statistics of every time
+ *               step (what pbz_segmented returns for the runs of {N, F}).
  * Requires the mask to keep each block's first coefficient (PBZ_ERR_DC_PRUNED otherwise).
  *   workspace   device, 16-byte aligned, at least the bytes pbz_compress_statistics_workspace reports for this
  *               shape and x_type (the reduction scratch plus two FP64 sums per wave of the compress kernel);
@@ -121,7 +125,8 @@ int pbz_compress(const pbz_codec* codec, const void* x, pbz_ftype x_type, const 
 int pbz_compress_statistics_workspace(const pbz_codec* codec, const int64_t* shape, pbz_ftype x_type,
                                       size_t* bytes);
 int pbz_compress_statistics(const pbz_codec* codec, const void* x, pbz_ftype x_type, const int64_t* shape, void* N,
-                            void* F, double* statistics, void* workspace, size_t workspace_bytes, void* stream);
+                            void* F, int per_step, double* statistics, void* workspace, size_t workspace_bytes,
+                            void* stream);
 
 /* Sec. III-B: C = N F / r at the mask positions and zero elsewhere, inverse transform, merge blocks,
  * crop to `shape`, convert to y_type (round to nearest even).

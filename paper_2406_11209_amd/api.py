@@ -45,7 +45,7 @@ SIGNATURES = {
     "pbz_covariance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_cosine_similarity": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_compress_statistics_workspace": (_c.c_int, [_p, _i64p, _c.c_int, _c.POINTER(_c.c_size_t)]),
-    "pbz_compress_statistics": (_c.c_int, [_p, _p, _c.c_int, _i64p, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_compress_statistics": (_c.c_int, [_p, _p, _c.c_int, _i64p, _p, _p, _c.c_int, _p, _p, _c.c_size_t, _p]),
     "pbz_statistics": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_difference_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
@@ -218,12 +218,15 @@ class Codec:
         check(self._lib.pbz_compress_statistics_workspace(self._h, _shape_arr(shape), FTYPES[array_type], _c.byref(n)))
         return n.value
 
-    def compress_statistics(self, x, N=None, F=None, out=None, workspace=None):
-        """pbz_compress_statistics: x -> (N, F, statistics) with statistics = [mean, variance, norm2] (float64)."""
+    def compress_statistics(self, x, N=None, F=None, out=None, workspace=None, per_step: bool = False):
+        """pbz_compress_statistics: x -> (N, F, statistics) with statistics = [mean, variance, norm2] (float64);
+        per_step: one such row per block index along dimension 0."""
         torch = _torch()
         if N is None or F is None:
             N, F = self.empty_compressed(x.shape, x.device)
-        out = torch.empty(3, dtype=torch.float64, device=x.device) if out is None else out
+        rows = -(-int(x.shape[0]) // int(self.block_shape[0])) if per_step else 1
+        if out is None:
+            out = torch.empty((rows, 3) if per_step else 3, dtype=torch.float64, device=x.device)
         if workspace is None:
             need = _c.c_size_t()
             check(self._lib.pbz_compress_statistics_workspace(self._h, _shape_arr(x.shape), _ftype_of(x), _c.byref(need)))
@@ -232,7 +235,8 @@ class Codec:
                 self._ws[key] = torch.empty(need.value, dtype=torch.uint8, device=x.device)
             workspace = self._ws[key]
         check(self._lib.pbz_compress_statistics(self._h, _ptr(x), _ftype_of(x), _shape_arr(x.shape), _ptr(N), _ptr(F),
-                                                _ptr(out), _ptr(workspace), workspace.numel(), _stream()))
+                                                1 if per_step else 0, _ptr(out), _ptr(workspace), workspace.numel(),
+                                                _stream()))
         return N, F, out
 
     def statistics(self, N, F, out=None):

@@ -250,7 +250,7 @@ int pbz_compress_statistics_workspace(const pbz_codec* c, const int64_t* shape, 
 }
 
 int pbz_compress_statistics(const pbz_codec* c, const void* x, pbz_ftype x_type, const int64_t* shape, void* N, void* F,
-                            double* statistics, void* ws, size_t ws_bytes, void* stream) {
+                            int per_step, double* statistics, void* ws, size_t ws_bytes, void* stream) {
   if (!c || !x || !shape || !N || !F || !statistics || !ws) return PBZ_ERR_NULL;
   if (!valid_ftype(x_type)) return PBZ_ERR_TYPE;
   Geom g;
@@ -259,6 +259,7 @@ int pbz_compress_statistics(const pbz_codec* c, const void* x, pbz_ftype x_type,
   if (!c->dc_kept) return PBZ_ERR_DC_PRUNED;
   if (ws_bytes < kWorkspaceBytes || (reinterpret_cast<uintptr_t>(ws) & 15u)) return PBZ_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t segments = per_step ? g.grid[0] : 1;       // one triple per block index along dimension 0
   if (c->path == PBZ_PATH_AUTO) {
     // the compress kernel leaves two sums per tile behind the reduction scratch; adding them costs two small launches
     const int64_t tiles = fast_compress_tiles(c, g, x_type);
@@ -267,7 +268,9 @@ int pbz_compress_statistics(const pbz_codec* c, const void* x, pbz_ftype x_type,
       const char* name = nullptr;
       int r = try_compress_fast(c, g, x, x_type, N, F, s, false, &name, tile_sums);
       if (r < 0) return r;
-      if (r > 0) return launch_statistics_from_tiles(c, g.n_blocks, tile_sums, tiles, statistics, ws, s);
+      // tiles follow the block grid's order, so the tiles of one index along dimension 0 are consecutive
+      if (r > 0) return launch_statistics_from_tiles(c, g.n_blocks / segments, tile_sums, tiles / segments, segments,
+                                                     statistics, ws, s);
     } else if (tiles > 0) {
       return PBZ_ERR_WORKSPACE;
     }
@@ -275,7 +278,8 @@ int pbz_compress_statistics(const pbz_codec* c, const void* x, pbz_ftype x_type,
   // no specialised kernel: compress, then one pass over {N, F} for the two sums
   st = pbz_compress(c, x, x_type, shape, N, F, stream);
   if (st != PBZ_OK) return st;
-  return launch_reduce(c, kStatistics, g.n_blocks, N, F, nullptr, nullptr, statistics, ws, s);
+  return launch_reduce(c, kStatistics, g.n_blocks / segments, N, F, nullptr, nullptr, statistics, ws, s, nullptr,
+                       segments);
 }
 
 int pbz_decompress(const pbz_codec* c, const void* N, const void* F, const int64_t* shape, void* y,

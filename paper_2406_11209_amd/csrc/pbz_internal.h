@@ -98,8 +98,10 @@ enum ReduceOp { kDot = 0, kNorm2 = 1, kCosine = 2, kMean = 3, kCovariance = 4, k
 int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1,
                   const void* N2, const void* F2, double* out, void* workspace, hipStream_t s,
                   const double* ssim_params = nullptr, int64_t n_segments = 1);
-int launch_statistics_from_tiles(const pbz_codec* c, int64_t n_blocks, const double* tile_sums, int64_t n_tiles,
-                                 double* out, void* workspace, hipStream_t s);
+// n_segments runs of tiles_per_segment tiles (blocks_per_segment blocks) each: out[3 t .. 3 t + 3) for run t
+int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment, const double* tile_sums,
+                                 int64_t tiles_per_segment, int64_t n_segments, double* out, void* workspace,
+                                 hipStream_t s);
 int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,
                       void* Fout, hipStream_t s);
 int launch_blockwise_mean(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out,

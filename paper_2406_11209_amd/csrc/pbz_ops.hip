@@ -571,10 +571,12 @@ __global__ __launch_bounds__(kThreads) void k_reduce_final(ReduceTail t, int n_p
   }
 }
 
-// per-tile sums {S11, D1} left by a compress kernel -> partial sums per workgroup, added in tile order
+// per-tile sums {S11, D1} left by a compress kernel -> partial sums per workgroup, added in tile order;
+// grid y runs over segments of n_tiles consecutive tiles
 __global__ __launch_bounds__(kThreads) void k_reduce_tiles(const double2* __restrict__ tile_sums, int64_t n_tiles,
                                                            int64_t chunk, ReduceTail tail) {
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
+  tile_sums += int64_t(blockIdx.y) * n_tiles;
   const int64_t begin = int64_t(blockIdx.x) * chunk;
   const int64_t end = begin + chunk < n_tiles ? begin + chunk : n_tiles;
   for (int64_t t = begin + threadIdx.x; t < end; t += kThreads) {
@@ -845,7 +847,7 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     const char* f1 = static_cast<const char*>(F1) + seg0 * f_stride;
     const char* n2 = two ? static_cast<const char*>(N2) + seg0 * n_stride : nullptr;
     const char* f2 = two ? static_cast<const char*>(F2) + seg0 * f_stride : nullptr;
-    tail.out = out + seg0;
+    tail.out = out + seg0 * (op == kStatistics ? 3 : 1);
     int groups;
     if (op == kMean) {
       groups = stream_groups(n_blocks, 4);
@@ -879,27 +881,37 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
   return PBZ_OK;
 }
 
-int launch_statistics_from_tiles(const pbz_codec* c, int64_t n_blocks, const double* tile_sums, int64_t n_tiles,
-                                 double* out, void* workspace, hipStream_t s) {
+int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment, const double* tile_sums,
+                                 int64_t tiles_per_segment, int64_t n_segments, double* out, void* workspace,
+                                 hipStream_t s) {
   ReduceTail tail;
   tail.s_l = tail.s_c = 0.0;
   tail.w_l = tail.w_c = tail.w_s = 1.0;
   tail.partials = static_cast<double*>(workspace);
-  tail.out = out;
   tail.op = int(kStatistics);
   tail.r = c->r;
-  tail.n_blocks = double(n_blocks);
+  tail.n_blocks = double(blocks_per_segment);
   tail.vol = double(c->vol);
-  // four tiles per thread and step, at most 1024 workgroups
-  int64_t chunk = int64_t(kThreads) * 4;
-  if ((n_tiles + chunk - 1) / chunk > 1024) chunk = ((n_tiles + 1023) / 1024 + kThreads - 1) / kThreads * kThreads;
-  const int groups = int((n_tiles + chunk - 1) / chunk);
-  hipLaunchKernelGGL(k_reduce_tiles, dim3(groups), dim3(kThreads), 0, s, reinterpret_cast<const double2*>(tile_sums),
-                     n_tiles, chunk, tail);
-  int st = hip_status(hipGetLastError());
-  if (st != PBZ_OK) return st;
-  hipLaunchKernelGGL(k_reduce_final, dim3(1), dim3(kThreads), 0, s, tail, groups);
-  return hip_status(hipGetLastError());
+  for (int64_t seg0 = 0; seg0 < n_segments; seg0 += kReduceMaxGroups) {
+    const int batch = int(n_segments - seg0 < kReduceMaxGroups ? n_segments - seg0 : kReduceMaxGroups);
+    int max_groups = kReduceMaxGroups / batch;
+    if (max_groups > 1024) max_groups = 1024;
+    // four tiles per thread and workgroup unless that needs more workgroups than the workspace has slots for
+    int64_t chunk = int64_t(kThreads) * 4;
+    if ((tiles_per_segment + chunk - 1) / chunk > max_groups)
+      chunk = ((tiles_per_segment + max_groups - 1) / max_groups + kThreads - 1) / kThreads * kThreads;
+    const int groups = int((tiles_per_segment + chunk - 1) / chunk);
+    tail.out = out + seg0 * 3;
+    hipLaunchKernelGGL(k_reduce_tiles, dim3(groups, batch), dim3(kThreads), 0, s,
+                       reinterpret_cast<const double2*>(tile_sums) + seg0 * tiles_per_segment, tiles_per_segment, chunk,
+                       tail);
+    int st = hip_status(hipGetLastError());
+    if (st != PBZ_OK) return st;
+    hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kThreads), 0, s, tail, groups);
+    st = hip_status(hipGetLastError());
+    if (st != PBZ_OK) return st;
+  }
+  return PBZ_OK;
 }
 
 int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,

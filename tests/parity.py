@@ -152,6 +152,19 @@ class Case:
         for got in (st.cpu().numpy(), one_pass.cpu().numpy()):
             for g, w, f, name in zip(got, want, floors, ("mean", "variance", "norm2")):
                 check_scalar(float(g), w, self.tol, f, "statistics." + name)
+        # one triple per block index along dimension 0: the oracle's statistics of each run of blocks
+        _, _, rows = self.codec.compress_statistics(x_dev, per_step=True)
+        rows = rows.cpu().numpy()
+        per = A.n_blocks // A.b[0]
+        assert rows.shape == (A.b[0], 3)
+        for t in range(A.b[0]):
+            run = po.Compressed(s=(A.i[0],) + tuple(A.s[1:]), i=A.i, N=A.N.reshape(A.b)[t:t + 1],
+                                F=A.F[t * per:(t + 1) * per], P=A.P, index_bits=A.index_bits, ftype=A.ftype)
+            nr = po.norm2(run)
+            n_run = float(per) * float(np.prod(self.block))
+            for g, w, f, name in zip(rows[t], (po.mean(run), po.variance(run), nr),
+                                     (nr / math.sqrt(n_run), nr * nr / n_run, 0.0), ("mean", "variance", "norm2")):
+                check_scalar(float(g), w, self.tol, f, f"statistics[{t}].{name}")
         return st
 
     def oc(self, N, F) -> po.Compressed:
