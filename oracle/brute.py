@@ -82,3 +82,21 @@ def decompress_block(N: float, kept: Sequence[int], shape: Sequence[int], index_
         else:
             coeffs[q] = (N * next(it)) / r
     return idct_block(coeffs, shape)
+
+
+def haar_by_averaging(v: Sequence[float]) -> List[float]:
+    """Orthonormal Haar coefficients of a power-of-two-length sequence by the textbook cascade: pairwise
+    (a + b) / sqrt(2) and (a - b) / sqrt(2), the differences of a level being that level's detail
+    coefficients, the sums feeding the next level.  Output in sequency order: overall sum first, then the
+    coarsest detail, then finer levels, each level left to right."""
+    cur = [float(t) for t in v]
+    levels: List[List[float]] = []
+    while len(cur) > 1:
+        sums = [(cur[2 * k] + cur[2 * k + 1]) / math.sqrt(2.0) for k in range(len(cur) // 2)]
+        diffs = [(cur[2 * k] - cur[2 * k + 1]) / math.sqrt(2.0) for k in range(len(cur) // 2)]
+        levels.append(diffs)
+        cur = sums
+    out = [cur[0]]
+    for diffs in reversed(levels):
+        out.extend(diffs)
+    return out

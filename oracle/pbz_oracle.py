@@ -88,6 +88,7 @@ class Compressed:
     P: np.ndarray               # bool, shape i
     index_bits: int
     ftype: str
+    transform: str = "dct"      # "dct" (Sec. III-A, the default) or "haar"
     # diagnostics for parity checks (not part of the compressed form)
     t: Optional[np.ndarray] = field(default=None, repr=False)    # pre-rounding r*C/N of kept entries
     N64: Optional[np.ndarray] = field(default=None, repr=False)  # N before the storage cast
@@ -181,25 +182,62 @@ def dct_matrix(n: int) -> np.ndarray:
     return H
 
 
-def forward_transform(B: np.ndarray, i: Sequence[int]) -> np.ndarray:
+def haar_matrix(n: int) -> np.ndarray:
+    """Orthonormal Haar wavelet matrix for n a power of two, same index convention as dct_matrix
+    (H[m][q]: sample m, coefficient q).
+
+    READING: the paper only names the Haar wavelet transform as an alternative (Sec. III-A, end of
+    "Orthonormal transform").  Taken here: the standard orthonormal Haar basis in sequency order.  q = 0 is
+    the constant 1/sqrt(n); q = 2^p + j (0 <= j < 2^p) is supported on the n / 2^p samples starting at
+    j n / 2^p, +sqrt(2^p / n) on the first half of its support and -sqrt(2^p / n) on the second.  Its
+    first coefficient is the block mean times sqrt(n), as for the DCT, so the operations that rely on
+    that property (Sec. IV-A) keep working.
+    """
+    if n < 1 or n & (n - 1):
+        raise ValueError("Haar needs a power-of-two length")
+    H = np.zeros((n, n), dtype=np.float64)
+    H[:, 0] = np.sqrt(1.0 / n)
+    q = 1
+    width = n
+    scale = 1
+    while q < n:
+        for j in range(scale):
+            lo = j * width
+            H[lo:lo + width // 2, q] = np.sqrt(scale / n)
+            H[lo + width // 2:lo + width, q] = -np.sqrt(scale / n)
+            q += 1
+        scale *= 2
+        width //= 2
+    return H
+
+
+def transform_matrix(n: int, transform: str = "dct") -> np.ndarray:
+    if transform == "dct":
+        return dct_matrix(n)
+    if transform == "haar":
+        return haar_matrix(n)
+    raise ValueError(f"unknown transform {transform!r}")
+
+
+def forward_transform(B: np.ndarray, i: Sequence[int], transform: str = "dct") -> np.ndarray:
     """C[k, q1..qd] = sum_m B[k, m1..md] H1[m1,q1] ... Hd[md,qd]  (Sec. III-A, Appendix A)."""
     d = len(i)
     C = B
     lead = B.ndim - d
     for t in range(d):
-        H = dct_matrix(int(i[t]))
+        H = transform_matrix(int(i[t]), transform)
         C = np.moveaxis(np.tensordot(C, H, axes=([lead + t], [0])), -1, lead + t)
     return C
 
 
-def inverse_transform(C: np.ndarray, i: Sequence[int]) -> np.ndarray:
+def inverse_transform(C: np.ndarray, i: Sequence[int], transform: str = "dct") -> np.ndarray:
     """B[k, m1..md] = sum_q C[k, q1..qd] H1[m1,q1] ... Hd[md,qd]: each coefficient times its
-    sampled cosine, summed (Sec. III-A, last sentence of "Orthonormal transform")."""
+    sampled function, summed (Sec. III-A, last sentence of "Orthonormal transform")."""
     d = len(i)
     B = C
     lead = C.ndim - d
     for t in range(d):
-        H = dct_matrix(int(i[t]))
+        H = transform_matrix(int(i[t]), transform)
         B = np.moveaxis(np.tensordot(B, H, axes=([lead + t], [1])), -1, lead + t)
     return B
 
@@ -222,7 +260,8 @@ def bin_blocks(C: np.ndarray, d: int, r: int):
     return N, t, np.rint(t)
 
 
-def compress_blocks(B: np.ndarray, i: Sequence[int], index_bits: int, P: Optional[np.ndarray] = None):
+def compress_blocks(B: np.ndarray, i: Sequence[int], index_bits: int, P: Optional[np.ndarray] = None,
+                    transform: str = "dct"):
     """Transform, bin and prune an array of blocks shaped (..., *i).
 
     Returns (N64, F, t_kept): the un-cast biggest coefficients, the kept indices with shape
@@ -232,7 +271,7 @@ def compress_blocks(B: np.ndarray, i: Sequence[int], index_bits: int, P: Optiona
     d = len(i)
     r = index_radius(index_bits)
     P = np.ones(i, dtype=bool) if P is None else np.asarray(P, dtype=bool).reshape(i)
-    C = forward_transform(np.asarray(B, dtype=np.float64), i)
+    C = forward_transform(np.asarray(B, dtype=np.float64), i, transform)
     N, t, I = bin_blocks(C, d, r)
     nb = int(np.prod(C.shape[: C.ndim - d], dtype=np.int64))
     vol = int(np.prod(i))
@@ -243,7 +282,7 @@ def compress_blocks(B: np.ndarray, i: Sequence[int], index_bits: int, P: Optiona
 
 
 def compress(x: np.ndarray, i: Sequence[int], index_bits: int = 8, ftype: str = "f32",
-             P: Optional[np.ndarray] = None) -> Compressed:
+             P: Optional[np.ndarray] = None, transform: str = "dct") -> Compressed:
     """Sec. III-A: convert, block, transform, bin, prune.
 
     READING: N_k is the maximum over all coefficients of the block, before pruning (the paper
@@ -259,9 +298,9 @@ def compress(x: np.ndarray, i: Sequence[int], index_bits: int = 8, ftype: str = 
     if P.sum() == 0:
         raise ValueError("the mask keeps nothing")
     B = to_blocks(x64, i)
-    N64, F, t_kept = compress_blocks(B, i, index_bits, P)
+    N64, F, t_kept = compress_blocks(B, i, index_bits, P, transform)
     return Compressed(s=tuple(x64.shape), i=i, N=store_float(N64, ftype), F=F, P=P,
-                      index_bits=index_bits, ftype=ftype, t=t_kept, N64=N64)
+                      index_bits=index_bits, ftype=ftype, transform=transform, t=t_kept, N64=N64)
 
 
 # --------------------------------------------------------------------------------------
@@ -282,7 +321,7 @@ def unflatten(A: Compressed, Chat: np.ndarray) -> np.ndarray:
 
 def decompress_padded(A: Compressed) -> np.ndarray:
     """Decompressed array before the crop, shape b (.) i."""
-    B = inverse_transform(unflatten(A, specified_coefficients(A)), A.i)
+    B = inverse_transform(unflatten(A, specified_coefficients(A)), A.i, A.transform)
     return from_blocks(B, tuple(bd * id_ for bd, id_ in zip(A.b, A.i)), A.i)
 
 
@@ -296,14 +335,14 @@ def decompress(A: Compressed) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 def _same_settings(A: Compressed, B: Compressed) -> None:
     if (A.s != B.s or A.i != B.i or A.index_bits != B.index_bits or A.ftype != B.ftype
-            or not np.array_equal(A.P, B.P)):
-        raise ValueError("operands must share shape, block shape, types and mask")
+            or A.transform != B.transform or not np.array_equal(A.P, B.P)):
+        raise ValueError("operands must share shape, block shape, types, transform and mask")
 
 
 def _like(A: Compressed, N64: np.ndarray, F: np.ndarray) -> Compressed:
     return Compressed(s=A.s, i=A.i, N=store_float(N64, A.ftype).reshape(A.b),
                       F=F.astype(INDEX_DTYPES[A.index_bits]), P=A.P, index_bits=A.index_bits,
-                      ftype=A.ftype, N64=np.asarray(N64, dtype=np.float64).reshape(A.b))
+                      ftype=A.ftype, transform=A.transform, N64=np.asarray(N64, dtype=np.float64).reshape(A.b))
 
 
 def negate(A: Compressed) -> Compressed:

@@ -424,3 +424,73 @@ def test_difference_norm2_brute_force_tiny():
             c2 = float(B.N.reshape(-1)[k]) * int(B.F[k, j]) / 127.0
             total += (c1 - c2) ** 2
     assert po.difference_norm2(A, B) == pytest.approx(math.sqrt(total), rel=1e-14)
+
+
+# ---------------------------------------------------------------- Haar transform -------
+@pytest.mark.parametrize("n", [1, 2, 4, 8, 16, 32])
+def test_haar_matrix_is_orthonormal_with_constant_first_function(n):
+    H = po.haar_matrix(n)
+    assert np.allclose(H.T @ H, np.eye(n), atol=1e-14)
+    assert np.allclose(H[:, 0], 1.0 / math.sqrt(n), atol=1e-15)
+
+
+def test_haar_matrix_closed_forms():
+    assert np.allclose(po.haar_matrix(2), po.dct_matrix(2), atol=1e-15)
+    h, s = 0.5, 1.0 / math.sqrt(2.0)
+    want = np.array([[h, h, s, 0.0], [h, h, -s, 0.0], [h, -h, 0.0, s], [h, -h, 0.0, -s]])
+    assert np.allclose(po.haar_matrix(4), want, atol=1e-15)
+
+
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32])
+def test_haar_matrix_matches_the_averaging_cascade(n):
+    v = rng(30 + n).standard_normal(n)
+    assert np.allclose(v @ po.haar_matrix(n), brute.haar_by_averaging(v), atol=1e-14)
+
+
+def test_haar_multi_dimensional_transform_is_separable_cascade():
+    x = rng(31).standard_normal((4, 8))
+    C = po.forward_transform(x[None], (4, 8), "haar")[0]
+    rows = np.array([brute.haar_by_averaging(r) for r in x])                 # along the last dimension
+    want = np.array([brute.haar_by_averaging(c) for c in rows.T]).T           # then along the first
+    assert np.allclose(C, want, atol=1e-14)
+    assert np.allclose(po.inverse_transform(C[None], (4, 8), "haar")[0], x, atol=1e-14)
+
+
+HAAR_CASES = [((24, 40), (8, 8), 8, "f32", None), ((12, 8, 16), (4, 4, 4), 16, "f64", None),
+              ((16, 16, 8), (8, 8, 8), 8, "f32", (4, 4, 4)), ((3, 32, 32), (1, 16, 16), 8, "f32", None)]
+
+
+@pytest.mark.parametrize("case", HAAR_CASES)
+def test_haar_codec_round_trip_and_statistics(case):
+    """With the Haar basis the codec keeps its properties: binning error bound per coefficient, block L2 error =
+    coefficient error norm (orthonormality), statistics of the compressed form = those of the decompressed array."""
+    shape, block, bits, ft, keep = case
+    g = rng(32)
+    x = synth.bump_field(shape, 5, g, (2.0, 6.0)) + 0.3 + 0.05 * g.standard_normal(shape)
+    y = synth.bump_field(shape, 5, g, (2.0, 6.0)) - 0.1
+    mask = None if keep is None else synth.low_frequency_mask(block, keep)
+    A = po.compress(x, block, bits, ft, mask, transform="haar")
+    B = po.compress(y, block, bits, ft, mask, transform="haar")
+    assert A.transform == "haar"
+    a, b = po.decompress_padded(A), po.decompress_padded(B)
+    C = po.forward_transform(po.to_blocks(x, block), block, "haar")
+    Chat = po.unflatten(A, po.specified_coefficients(A))
+    err = np.abs(C - Chat)
+    Pm = A.P.reshape((1,) * len(block) + tuple(block))
+    slack = 2.0 ** (-23 if ft == "f32" else -52) * np.abs(C).max()
+    bound = A.N64.reshape(A.b + (1,) * len(block)) / (2.0 * A.r)
+    assert np.all(err[np.broadcast_to(Pm, err.shape)] <= np.broadcast_to(bound, err.shape)[np.broadcast_to(Pm, err.shape)] + slack)
+    xb = po.to_blocks(x, block)
+    ab = po.to_blocks(a, block)
+    axes = tuple(range(len(block), 2 * len(block)))
+    assert np.allclose(np.sqrt(np.sum((xb - ab) ** 2, axis=axes)), np.sqrt(np.sum((C - Chat) ** 2, axis=axes)), atol=1e-10)
+    assert po.mean(A) == pytest.approx(float(np.mean(a)), rel=1e-11, abs=1e-13)
+    assert po.variance(A) == pytest.approx(float(np.var(a)), rel=1e-10)
+    assert po.dot(A, B) == pytest.approx(float(np.sum(a * b)), rel=1e-11, abs=1e-11)
+    assert po.norm2(A) == pytest.approx(float(np.linalg.norm(a.reshape(-1))), rel=1e-12)
+    assert np.allclose(po.blockwise_mean(A), po.to_blocks(a, block).mean(axis=axes), atol=1e-12)
+    # and it is a different codec from the DCT one
+    D = po.compress(x, block, bits, ft, mask)
+    assert not np.array_equal(D.F, A.F)
+    with pytest.raises(ValueError):
+        po.dot(A, D)
