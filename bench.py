@@ -44,10 +44,12 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--transform", default="dct", choices=["dct", "haar"],
+                    help="orthonormal transform of the codec (the metric is quoted with the default, the DCT)")
     return ap.parse_args()
 
 
-def cpu_baseline(wl, sample_shape):
+def cpu_baseline(wl, sample_shape, transform="dct"):
     """Time the oracle (as it stands) on a corner sub-array of A and B: the same step as the GPU's."""
     from oracle import pbz_oracle as po
     import threadpoolctl
@@ -60,10 +62,10 @@ def cpu_baseline(wl, sample_shape):
         cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
     except Exception:
         pass
-    po.compress(a[tuple(slice(0, 2 * i) for i in wl.block)], wl.block, wl.index_bits, wl.ftype, wl.mask)  # warm-up
-    B = po.compress(b, wl.block, wl.index_bits, wl.ftype, wl.mask)
+    po.compress(a[tuple(slice(0, 2 * i) for i in wl.block)], wl.block, wl.index_bits, wl.ftype, wl.mask, transform)  # warm-up
+    B = po.compress(b, wl.block, wl.index_bits, wl.ftype, wl.mask, transform)
     t0 = time.perf_counter()
-    A = po.compress(a, wl.block, wl.index_bits, wl.ftype, wl.mask)
+    A = po.compress(a, wl.block, wl.index_bits, wl.ftype, wl.mask, transform)
     t_compress = time.perf_counter() - t0
     po.decompress(A)
     po.negate(A)
@@ -112,7 +114,7 @@ def main():
         return torch.from_numpy(x).to(dev)
 
     xA, xB = up(wl.A), up(wl.B)
-    codec = Codec(wl.block, wl.ftype, wl.index_bits, wl.mask)
+    codec = Codec(wl.block, wl.ftype, wl.index_bits, wl.mask, args.transform)
     lay = codec.layout(wl.shape)
     in_bytes = xA.numel() * xA.element_size()
     comp_bytes = lay.n_bytes + lay.f_bytes
@@ -284,7 +286,7 @@ def main():
         "dtype": {"f64": "f64", "f32": "f32", "bf16": "f32"}[wl.dtype] if wl.index_bits == 8 or wl.ftype == "f64" else "f64",
         "data": "synthetic",
         "config": {"workload": wl.name, "shape": list(wl.shape), "block": list(wl.block), "array_dtype": wl.dtype,
-                   "index_bits": wl.index_bits, "kept_per_block": lay.kept_per_block,
+                   "index_bits": wl.index_bits, "kept_per_block": lay.kept_per_block, "transform": args.transform,
                    "uncompressed_bytes": in_bytes, "compressed_bytes": comp_bytes,
                    "input_generation_s": round(t_gen, 1)},
         "ops": per_op,
@@ -294,7 +296,7 @@ def main():
     if not args.no_cpu_baseline:
         # sized for roughly 10-30 s of oracle time on the machine's host cores
         sample = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (512, 512, 512)}[args.config]
-        out["cpu_baseline"] = cpu_baseline(wl, sample)
+        out["cpu_baseline"] = cpu_baseline(wl, sample, args.transform)
     print(json.dumps(out))
 
 

@@ -71,7 +71,8 @@ typedef enum {
   PBZ_ERR_WORKSPACE = -8,   /* workspace smaller than pbz_layout reports */
   PBZ_ERR_SCALAR = -9,      /* non-finite scalar */
   PBZ_ERR_HIP = -10,        /* the HIP runtime reported an error (no device, launch failure, ...) */
-  PBZ_ERR_ALLOC = -11       /* host allocation failed */
+  PBZ_ERR_ALLOC = -11,      /* host allocation failed */
+  PBZ_ERR_STATE = -12       /* the call comes too late in the handle's life (see pbz_codec_set_transform) */
 } pbz_status;
 
 /* Kernel families, for pbz_codec_set_kernel_path / pbz_kernel_name. */
@@ -87,6 +88,15 @@ typedef struct pbz_codec pbz_codec; /* opaque compression settings (Sec. III-A):
 int pbz_codec_create(pbz_codec** out, int ndim, const int64_t* block_shape, pbz_ftype work_type,
                      pbz_itype index_type, const uint8_t* mask);
 void pbz_codec_destroy(pbz_codec* codec);
+
+/* The orthonormal transform of Sec. III-A step 3: the DCT-II (the default) or the Haar wavelet transform that
+ * the same passage names as an alternative (orthonormal Haar basis in sequency order: coefficient 0 is the block
+ * sum over sqrt(n); coefficient 2^p + j is +-sqrt(2^p / n) on the two halves of the j-th run of n / 2^p samples).
+ * Both have a constant first basis function, so every operation of Sec. IV-A applies unchanged.  Arrays
+ * compressed under different transforms must not be combined.  Must be called before the handle's first
+ * compress / decompress (its per-device tables are built then): PBZ_ERR_STATE afterwards.  Needs no GPU. */
+typedef enum { PBZ_TRANSFORM_DCT = 0, PBZ_TRANSFORM_HAAR = 1 } pbz_transform;
+int pbz_codec_set_transform(pbz_codec* codec, pbz_transform transform);
 
 /* Force the slow fully general kernels (PBZ_PATH_GENERIC) instead of the specialised ones; for testing. */
 int pbz_codec_set_kernel_path(pbz_codec* codec, pbz_kernel_path path);

@@ -32,6 +32,7 @@ _i64p = _c.POINTER(_c.c_int64)
 SIGNATURES = {
     "pbz_codec_create": (_c.c_int, [_c.POINTER(_p), _c.c_int, _i64p, _c.c_int, _c.c_int, _c.POINTER(_c.c_uint8)]),
     "pbz_codec_destroy": (None, [_p]),
+    "pbz_codec_set_transform": (_c.c_int, [_p, _c.c_int]),
     "pbz_codec_set_kernel_path": (_c.c_int, [_p, _c.c_int]),
     "pbz_layout": (_c.c_int, [_p, _i64p, _i64p, _i64p, _c.POINTER(_c.c_size_t), _c.POINTER(_c.c_size_t),
                               _c.POINTER(_c.c_size_t)]),
@@ -142,11 +143,14 @@ class Layout:
     workspace_bytes: int
 
 
+TRANSFORMS = {"dct": 0, "haar": 1}
+
+
 class Codec:
     """Compression settings (block shape, working float type, index type, mask); owns a pbz_codec."""
 
     def __init__(self, block_shape: Sequence[int], work_type: str = "f32", index_type="i8",
-                 mask: Optional[np.ndarray] = None):
+                 mask: Optional[np.ndarray] = None, transform: str = "dct"):
         self._lib = load_library()
         self._h = _p()
         self.block_shape = tuple(int(v) for v in block_shape)
@@ -161,6 +165,9 @@ class Codec:
         check(self._lib.pbz_codec_create(_c.byref(self._h), len(self.block_shape), _shape_arr(self.block_shape),
                                          self.work_type, self.index_type, m))
         self._ws = {}
+        self.transform = transform
+        if transform != "dct":
+            check(self._lib.pbz_codec_set_transform(self._h, TRANSFORMS[transform]))
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None

@@ -24,6 +24,19 @@ void fill_dct(double* H, int n) {
     }
 }
 
+// orthonormal Haar matrix in sequency order, same index convention (Sec. III-A names the transform only)
+void fill_haar(double* H, int n) {
+  for (int i = 0; i < n * n; ++i) H[i] = 0.0;
+  for (int m = 0; m < n; ++m) H[m * n] = std::sqrt(1.0 / n);
+  int q = 1;
+  for (int count = 1; count < n; count *= 2) {
+    const int width = n / count;
+    const double amp = std::sqrt(double(count) / n);
+    for (int j = 0; j < count; ++j, ++q)
+      for (int m = 0; m < width; ++m) H[(j * width + m) * n + q] = m < width / 2 ? amp : -amp;
+  }
+}
+
 int make_geom(const pbz_codec* c, const int64_t* shape, Geom* g) {
   if (!c || !shape) return PBZ_ERR_NULL;
   std::memset(g, 0, sizeof(*g));
@@ -120,6 +133,7 @@ int pbz_codec_create(pbz_codec** out, int ndim, const int64_t* block_shape, pbz_
   c->compute_f64 = (work_type == PBZ_F64) || (c->index_bits > 8);
   c->kept = kept;
   c->path = PBZ_PATH_AUTO;
+  c->transform = PBZ_TRANSFORM_DCT;
   c->mask = static_cast<uint8_t*>(std::malloc(size_t(vol)));
   c->kept_pos = static_cast<int32_t*>(std::malloc(sizeof(int32_t) * size_t(vol)));
   int h_total = 0;
@@ -187,6 +201,20 @@ void pbz_codec_destroy(pbz_codec* c) {
   delete c;
 }
 
+int pbz_codec_set_transform(pbz_codec* c, pbz_transform transform) {
+  if (!c) return PBZ_ERR_NULL;
+  if (transform != PBZ_TRANSFORM_DCT && transform != PBZ_TRANSFORM_HAAR) return PBZ_ERR_TYPE;
+  std::lock_guard<std::mutex> lock(c->mu);
+  if (c->used.load()) return PBZ_ERR_STATE;          // arrays compressed so far would no longer decompress
+  c->transform = int(transform);
+  for (int d = 0; d < c->ndim; ++d) {
+    double* H = c->H_host + c->h_offset[d];
+    if (transform == PBZ_TRANSFORM_HAAR) fill_haar(H, int(c->block[d]));
+    else fill_dct(H, int(c->block[d]));
+  }
+  return PBZ_OK;
+}
+
 int pbz_codec_set_kernel_path(pbz_codec* c, pbz_kernel_path path) {
   if (!c) return PBZ_ERR_NULL;
   if (path != PBZ_PATH_AUTO && path != PBZ_PATH_GENERIC) return PBZ_ERR_TYPE;
@@ -227,6 +255,7 @@ int pbz_compress(const pbz_codec* c, const void* x, pbz_ftype x_type, const int6
   int st = make_geom(c, shape, &g);
   if (st != PBZ_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  c->used.store(true);
   if (c->path == PBZ_PATH_AUTO) {
     const char* name = nullptr;
     int r = try_compress_fast(c, g, x, x_type, N, F, s, false, &name);
@@ -260,6 +289,7 @@ int pbz_compress_statistics(const pbz_codec* c, const void* x, pbz_ftype x_type,
   if (ws_bytes < kWorkspaceBytes || (reinterpret_cast<uintptr_t>(ws) & 15u)) return PBZ_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t segments = per_step ? g.grid[0] : 1;       // one triple per block index along dimension 0
+  c->used.store(true);
   if (c->path == PBZ_PATH_AUTO) {
     // the compress kernel leaves two sums per tile behind the reduction scratch; adding them costs two small launches
     const int64_t tiles = fast_compress_tiles(c, g, x_type);
@@ -290,6 +320,7 @@ int pbz_decompress(const pbz_codec* c, const void* N, const void* F, const int64
   int st = make_geom(c, shape, &g);
   if (st != PBZ_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  c->used.store(true);
   if (c->path == PBZ_PATH_AUTO) {
     const char* name = nullptr;
     int r = try_decompress_fast(c, g, N, F, y, y_type, s, false, &name);
@@ -478,6 +509,7 @@ const char* pbz_status_string(int status) {
     case PBZ_ERR_SCALAR: return "scalar must be finite";
     case PBZ_ERR_HIP: return "HIP runtime error";
     case PBZ_ERR_ALLOC: return "host allocation failed";
+    case PBZ_ERR_STATE: return "too late in the handle's life for this call";
     default: return "unknown status";
   }
 }

@@ -22,6 +22,7 @@
 // the block shape / types / mask box match an instantiation, the last array extent is a multiple of the
 // block's last extent, and rows start 16-byte aligned.  The other dimensions may be ragged.
 #include "pbz_dct.h"
+#include "pbz_haar.h"
 #include "pbz_device.h"
 #include "pbz_internal.h"
 
@@ -220,43 +221,58 @@ struct Dct8Table {
 };
 __constant__ Dct8Table c_dct8 = Dct8Table();
 
+struct Haar8Table {       // the same for the length-8 orthonormal Haar transform
+  float h[8][8];
+  constexpr Haar8Table() : h{} {
+    for (int m = 0; m < 8; ++m) h[m][0] = float(dct::cx_sqrt(1.0 / 8.0));
+    int q = 1;
+    for (int count = 1; count < 8; count *= 2) {
+      const int width = 8 / count;
+      for (int j = 0; j < count; ++j, ++q)
+        for (int m = 0; m < width; ++m)
+          h[j * width + m][q] = float((m < width / 2 ? 1.0 : -1.0) * dct::cx_sqrt(double(count) / 8.0));
+    }
+  }
+};
+__constant__ Haar8Table c_haar8 = Haar8Table();
+
 // forward transform of a register-resident [BZ][BY][BX] block, one dimension after the other
-template <typename T, int BZ, int BY, int BX>
+template <int TF, typename T, int BZ, int BY, int BX>
 __device__ __forceinline__ void forward_block(T* v) {
   if constexpr (BX > 1) {
 #pragma unroll
-    for (int row = 0; row < BZ * BY; ++row) dct::forward<T, BX, 1>(v + row * BX);
+    for (int row = 0; row < BZ * BY; ++row) tf_forward<TF, T, BX, 1>(v + row * BX);
   }
   if constexpr (BY > 1) {
 #pragma unroll
     for (int z = 0; z < BZ; ++z)
 #pragma unroll
-      for (int xx = 0; xx < BX; ++xx) dct::forward<T, BY, BX>(v + z * BY * BX + xx);
+      for (int xx = 0; xx < BX; ++xx) tf_forward<TF, T, BY, BX>(v + z * BY * BX + xx);
   }
   if constexpr (BZ > 1) {
 #pragma unroll
-    for (int yx = 0; yx < BY * BX; ++yx) dct::forward<T, BZ, BY * BX>(v + yx);
+    for (int yx = 0; yx < BY * BX; ++yx) tf_forward<TF, T, BZ, BY * BX>(v + yx);
   }
 }
 
 // inverse transform; only the low-frequency box [KZ][KY][KX] of the input is non-zero
-template <typename T, int BZ, int BY, int BX, int KZ, int KY, int KX>
+template <int TF, typename T, int BZ, int BY, int BX, int KZ, int KY, int KX>
 __device__ __forceinline__ void inverse_block(T* v) {
   if constexpr (BZ > 1) {
 #pragma unroll
     for (int y = 0; y < KY; ++y)
 #pragma unroll
-      for (int xx = 0; xx < KX; ++xx) dct::inverse<T, BZ, BY * BX, KZ>(v + y * BX + xx);
+      for (int xx = 0; xx < KX; ++xx) tf_inverse<TF, T, BZ, BY * BX, KZ>(v + y * BX + xx);
   }
   if constexpr (BY > 1) {
 #pragma unroll
     for (int z = 0; z < BZ; ++z)
 #pragma unroll
-      for (int xx = 0; xx < KX; ++xx) dct::inverse<T, BY, BX, KY>(v + z * BY * BX + xx);
+      for (int xx = 0; xx < KX; ++xx) tf_inverse<TF, T, BY, BX, KY>(v + z * BY * BX + xx);
   }
   if constexpr (BX > 1) {
 #pragma unroll
-    for (int row = 0; row < BZ * BY; ++row) dct::inverse<T, BX, 1, KX>(v + row * BX);
+    for (int row = 0; row < BZ * BY; ++row) tf_inverse<TF, T, BX, 1, KX>(v + row * BX);
   }
 }
 
@@ -266,8 +282,8 @@ __device__ __forceinline__ void inverse_block(T* v) {
 // kRagged: the slow dimensions are not multiples of the block extents, so some block rows lie outside the
 // array.  Such rows are still loaded (from a clamped, valid address: a branch around a load would make the
 // compiler wait for all outstanding loads at the join) and zeroed afterwards.
-template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX, bool kRagged,
-          bool kStats>
+template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX,
+          bool kRagged, bool kStats>
 __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __restrict__ x, NT* __restrict__ N,
                                                        IT* __restrict__ F, double* __restrict__ tile_sums) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
@@ -315,7 +331,7 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
 #pragma unroll
   for (int i = 0; i < ROWS * RV; ++i) Unpack<T, XT>::run(raw[i], v + i * PER16);
 
-  forward_block<T, BZ, BY, BX>(v);
+  forward_block<TF, T, BZ, BY, BX>(v);
 
   T m = T(0);
 #pragma unroll
@@ -368,7 +384,8 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   }
 }
 
-template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX, bool kRagged>
+template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX,
+          bool kRagged>
 __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* __restrict__ N, const IT* __restrict__ F,
                                                          XT* __restrict__ y) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
@@ -403,7 +420,7 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
     v[(kz * BY + ky) * BX + kx] = scale * T(IdxPack<IT>::get(w[j / PER], j % PER));
   }
 
-  inverse_block<T, BZ, BY, BX, KZ, KY, KX>(v);
+  inverse_block<TF, T, BZ, BY, BX, KZ, KY, KX>(v);
 
 #pragma unroll
   for (int z = 0; z < BZ; ++z)
@@ -424,7 +441,7 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
 // =====================================================================================================
 constexpr int kQuadRow = 65;   // uint4 per LDS row: 64 + 1 of padding so that column reads spread over the banks
 
-template <bool kRagged, bool kStats>
+template <int TF, bool kRagged, bool kStats>
 __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float* __restrict__ x, float* __restrict__ N,
                                                          int8_t* __restrict__ F, double* __restrict__ tile_sums) {
   __shared__ uint4 lds[2][16 * kQuadRow];
@@ -455,7 +472,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
       bits_f4(raw[yy0], v + yy0 * 4);
     }
 #pragma unroll
-    for (int xl = 0; xl < 4; ++xl) dct::forward<float, 16, 4>(v + xl);
+    for (int xl = 0; xl < 4; ++xl) tf_forward<TF, float, 16, 4>(v + xl);
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) st[yy0 * kQuadRow + lane] = f4_bits(v + yy0 * 4);
   }
@@ -468,7 +485,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
 #pragma unroll
     for (int xq = 0; xq < 4; ++xq) bits_f4(st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq], u + j * 16 + xq * 4);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) dct::forward<float, 16, 1>(u + j * 16);
+  for (int j = 0; j < 4; ++j) tf_forward<TF, float, 16, 1>(u + j * 16);
 
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 16;
   double s11 = 0.0, d1 = 0.0;
@@ -503,6 +520,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
   if constexpr (kStats) emit_tile_sums(tile_sums, g, tx, by, bz, s11, d1);
 }
 
+template <int TF>
 __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const float* __restrict__ N,
                                                            const int8_t* __restrict__ F, float* __restrict__ y) {
   __shared__ uint4 lds[2][16 * kQuadRow];
@@ -525,7 +543,7 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const flo
       for (int i = 0; i < 16; ++i) u[j * 16 + i] = scale * float(IdxPack<int8_t>::get(w[i >> 2], i & 3));
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) dct::inverse<float, 16, 1, 16>(u + j * 16);
+    for (int j = 0; j < 4; ++j) tf_inverse<TF, float, 16, 1, 16>(u + j * 16);
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -538,7 +556,7 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const flo
 #pragma unroll
   for (int yy0 = 0; yy0 < 16; ++yy0) bits_f4(st[yy0 * kQuadRow + lane], v + yy0 * 4);
 #pragma unroll
-  for (int xl = 0; xl < 4; ++xl) dct::inverse<float, 16, 4, 16>(v + xl);
+  for (int xl = 0; xl < 4; ++xl) tf_inverse<TF, float, 16, 4, 16>(v + xl);
   if (bx < g.gx) {
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
@@ -563,7 +581,7 @@ __device__ __forceinline__ int oct_slot(int b, int yy, int z) {
 
 constexpr int kOctWaves = 4;   // waves per workgroup: neighbouring tiles, so that a workgroup reads 512-byte row pieces
 
-template <int KZ, int KY, int KX, bool kRagged, bool kStats>
+template <int TF, int KZ, int KY, int KX, bool kRagged, bool kStats>
 __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x,
                                                                   float* __restrict__ N, int8_t* __restrict__ F,
                                                                   double* __restrict__ tile_sums) {
@@ -604,9 +622,9 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
       Unpack<float, bf16_t>::run(raw[yy0], v + yy0 * 8);
     }
 #pragma unroll
-    for (int yy0 = 0; yy0 < 8; ++yy0) dct::forward<float, 8, 1>(v + yy0 * 8);
+    for (int yy0 = 0; yy0 < 8; ++yy0) tf_forward<TF, float, 8, 1>(v + yy0 * 8);
 #pragma unroll
-    for (int xx = 0; xx < 8; ++xx) dct::forward<float, 8, 8>(v + xx);
+    for (int xx = 0; xx < 8; ++xx) tf_forward<TF, float, 8, 8>(v + xx);
   }
   // exchange: afterwards the lane holds the row y = j of all eight planes of block bb; transform along z
   float u[64];
@@ -620,7 +638,7 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
     wave_lds_sync();
   }
 #pragma unroll
-  for (int xx = 0; xx < 8; ++xx) dct::forward<float, 8, 8>(u + xx);
+  for (int xx = 0; xx < 8; ++xx) tf_forward<TF, float, 8, 8>(u + xx);
 
   float m = 0.0f;
 #pragma unroll
@@ -676,7 +694,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // hardwar
   return __builtin_bit_cast(uint32_t, h);
 }
 
-template <int KZ, int KY, int KX>
+template <int TF, int KZ, int KY, int KX>
 __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float* __restrict__ N,
                                                          const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
   constexpr int KEPT = KZ * KY * KX;
@@ -700,7 +718,7 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float
   const float scale = N[block] / float(g.r);
   float hz[KZ];
 #pragma unroll
-  for (int q = 0; q < KZ; ++q) hz[q] = scale * c_dct8.h[z][q];
+  for (int q = 0; q < KZ; ++q) hz[q] = scale * (TF == kTfHaar ? c_haar8.h[z][q] : c_dct8.h[z][q]);
   float v[64];
 #pragma unroll
   for (int i = 0; i < 64; ++i) v[i] = 0.0f;
@@ -717,9 +735,9 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float
       v[yy0 * 8 + xx] = acc;
     }
 #pragma unroll
-  for (int xx = 0; xx < KX; ++xx) dct::inverse<float, 8, 8, KY>(v + xx);
+  for (int xx = 0; xx < KX; ++xx) tf_inverse<TF, float, 8, 8, KY>(v + xx);
 #pragma unroll
-  for (int yy0 = 0; yy0 < 8; ++yy0) dct::inverse<float, 8, 1, KX>(v + yy0 * 8);
+  for (int yy0 = 0; yy0 < 8; ++yy0) tf_inverse<TF, float, 8, 1, KX>(v + yy0 * 8);
 #pragma unroll
   for (int yy0 = 0; yy0 < 8; ++yy0) {
     const int64_t yy = by * 8 + yy0;
@@ -791,10 +809,10 @@ template <> constexpr int itype_code<int8_t>() { return PBZ_I8; }
 template <> constexpr int itype_code<int16_t>() { return PBZ_I16; }
 
 // One table row per instantiation.
-template <typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX>
+template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX>
 struct LaneKernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<XT>() && int(c->itype) == itype_code<IT>() &&
+    return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<XT>() && int(c->itype) == itype_code<IT>() &&
            int(c->ftype) == xtype_code<NT>() && f.bz == BZ && f.by == BY && f.bx == BX && f.kz == KZ && f.ky == KY &&
            f.kx == KX && (f.g.X * sizeof(XT)) % 16 == 0;
   }
@@ -808,7 +826,7 @@ struct LaneKernel {
   }
   template <bool kRagged, bool kStats>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kStats>), grid, dim3(256), 0, s, g,
+    hipLaunchKernelGGL((k_compress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kStats>), grid, dim3(256), 0, s, g,
                        static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F), tile_sums);
   }
   // tile_sums != nullptr: also the per-wave statistic sums (two doubles per tile)
@@ -824,26 +842,27 @@ struct LaneKernel {
     dim3 grid;
     if (!tile_grid(g, 64, 4, &grid)) return 0;
     if (g.Z % BZ || g.Y % BY)
-      hipLaunchKernelGGL((k_decompress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, true>), grid, dim3(256), 0, s, g,
+      hipLaunchKernelGGL((k_decompress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, true>), grid, dim3(256), 0, s, g,
                          static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
     else
-      hipLaunchKernelGGL((k_decompress_lane<T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, false>), grid, dim3(256), 0, s, g,
+      hipLaunchKernelGGL((k_decompress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, false>), grid, dim3(256), 0, s, g,
                          static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
 
 // 2-D 8x8, FP32 arrays: int8 (FP32 arithmetic), int16 (FP64 arithmetic) with all 64 or the 4x4 low-frequency box kept
-using Lane_f32_8x8_i8 = LaneKernel<float, float, int8_t, float, 1, 8, 8, 1, 8, 8>;
-using Lane_f32_8x8_i16_box4 = LaneKernel<double, float, int16_t, float, 1, 8, 8, 1, 4, 4>;
-using Lane_f32_8x8_i16 = LaneKernel<double, float, int16_t, float, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_f32_8x8_i8 = LaneKernel<TF, float, float, int8_t, float, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_f32_8x8_i16_box4 = LaneKernel<TF, double, float, int16_t, float, 1, 8, 8, 1, 4, 4>;
+template <int TF> using Lane_f32_8x8_i16 = LaneKernel<TF, double, float, int16_t, float, 1, 8, 8, 1, 8, 8>;
 // 3-D 4x4x4, FP64 arrays, int16
-using Lane_f64_4x4x4_i16 = LaneKernel<double, double, int16_t, double, 4, 4, 4, 4, 4, 4>;
+template <int TF> using Lane_f64_4x4x4_i16 = LaneKernel<TF, double, double, int16_t, double, 4, 4, 4, 4, 4, 4>;
 
 // 2-D 16x16 FP32 int8, nothing pruned
+template <int TF>
 struct Quad16Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && !c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 1 &&
+    return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 1 &&
            f.by == 16 && f.bx == 16 && f.kz == 1 && f.ky == 16 && f.kx == 16 && (f.g.X * 4) % 16 == 0;
   }
   static int fits(FastGeom g) {
@@ -856,7 +875,7 @@ struct Quad16Kernel {
   }
   template <bool kRagged, bool kStats>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_quad16<kRagged, kStats>), grid, dim3(128), 0, s, g, static_cast<const float*>(x),
+    hipLaunchKernelGGL((k_compress_quad16<TF, kRagged, kStats>), grid, dim3(128), 0, s, g, static_cast<const float*>(x),
                        static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
@@ -870,17 +889,17 @@ struct Quad16Kernel {
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 16, 2, &grid)) return 0;
-    hipLaunchKernelGGL(k_decompress_quad16, grid, dim3(128), 0, s, g, static_cast<const float*>(N),
+    hipLaunchKernelGGL(k_decompress_quad16<TF>, grid, dim3(128), 0, s, g, static_cast<const float*>(N),
                        static_cast<const int8_t*>(F), static_cast<float*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
 
 // 3-D 8x8x8 bfloat16 arrays, FP32 arithmetic and N, int8, box KZ x KY x KX kept
-template <int KZ, int KY, int KX>
+template <int TF, int KZ, int KY, int KX>
 struct Oct8Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 8 &&
+    return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 8 &&
            f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX && (f.g.X * 2) % 16 == 0;
   }
   static int fits(FastGeom g) {
@@ -893,7 +912,7 @@ struct Oct8Kernel {
   }
   template <bool kRagged, bool kStats>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_oct8<KZ, KY, KX, kRagged, kStats>), grid, dim3(kOctWaves * 64), 0, s, g,
+    hipLaunchKernelGGL((k_compress_oct8<TF, KZ, KY, KX, kRagged, kStats>), grid, dim3(kOctWaves * 64), 0, s, g,
                        static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
@@ -907,22 +926,26 @@ struct Oct8Kernel {
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 8, 4, &grid)) return 0;
-    hipLaunchKernelGGL((k_decompress_oct8<KZ, KY, KX>), grid, dim3(256), 0, s, g, static_cast<const float*>(N),
+    hipLaunchKernelGGL((k_decompress_oct8<TF, KZ, KY, KX>), grid, dim3(256), 0, s, g, static_cast<const float*>(N),
                        static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
-using Oct8_box4 = Oct8Kernel<4, 4, 4>;
-using Oct8_full = Oct8Kernel<8, 8, 8>;
+template <int TF> using Oct8_box4 = Oct8Kernel<TF, 4, 4, 4>;
+template <int TF> using Oct8_full = Oct8Kernel<TF, 8, 8, 8>;
 
-#define PBZ_FOR_EACH_LANE_KERNEL(X)                        \
-  X(Lane_f32_8x8_i8, "lane_f32_8x8_i8")                    \
-  X(Lane_f32_8x8_i16_box4, "lane_f32_8x8_i16_box4x4")      \
-  X(Lane_f32_8x8_i16, "lane_f32_8x8_i16")                  \
-  X(Lane_f64_4x4x4_i16, "lane_f64_4x4x4_i16")          \
-  X(Quad16Kernel, "quad16_f32_16x16_i8")                   \
-  X(Oct8_box4, "oct8_bf16_8x8x8_i8_box4x4x4")              \
-  X(Oct8_full, "oct8_bf16_8x8x8_i8")
+#define PBZ_FOR_EACH_SHAPE(X, TF, SUFFIX)                             \
+  X(Lane_f32_8x8_i8<TF>, "lane_f32_8x8_i8" SUFFIX)                     \
+  X(Lane_f32_8x8_i16_box4<TF>, "lane_f32_8x8_i16_box4x4" SUFFIX)       \
+  X(Lane_f32_8x8_i16<TF>, "lane_f32_8x8_i16" SUFFIX)                   \
+  X(Lane_f64_4x4x4_i16<TF>, "lane_f64_4x4x4_i16" SUFFIX)               \
+  X(Quad16Kernel<TF>, "quad16_f32_16x16_i8" SUFFIX)                    \
+  X(Oct8_box4<TF>, "oct8_bf16_8x8x8_i8_box4x4x4" SUFFIX)               \
+  X(Oct8_full<TF>, "oct8_bf16_8x8x8_i8" SUFFIX)
+// every shape for the DCT (plain names) and for the Haar transform (names ending in _haar)
+#define PBZ_FOR_EACH_LANE_KERNEL(X)    \
+  PBZ_FOR_EACH_SHAPE(X, kTfDct, "")    \
+  PBZ_FOR_EACH_SHAPE(X, kTfHaar, "_haar")
 
 }  // namespace
 

@@ -5,6 +5,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <atomic>
 #include <mutex>
 
 #include "pbz.h"
@@ -43,6 +44,8 @@ struct pbz_codec {
   int h_total;
   double* H_host;       // concatenated matrices
   pbz_kernel_path path;
+  int transform;        // pbz_transform
+  mutable std::atomic<bool> used{false};   // a compress / decompress has been issued: the transform is fixed from then on
   mutable std::mutex mu;
   mutable pbz::DeviceTables dev[pbz::kMaxDevices];
 };

@@ -30,6 +30,11 @@ from paper_2406_11209_amd.api import Codec
 
 TORCH_DTYPE = {"f64": torch.float64, "f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
 MAX_MISMATCH_FRACTION = 1e-4
+# Haar coefficients of the smooth synthetic fields crowd near half-integers after scaling (the oracle's own
+# pre-rounding values lie inside the tie band four times as often as for the DCT: 1.9e-3 against 4e-4 of them on
+# the 16 x 16 case), so FP32 arithmetic of any order flips more of them; every flip must still be a tie and +-1.
+MAX_MISMATCH_FRACTION_HAAR = 1e-3
+EXACT_TIE = 1e-9     # |frac(t) - 1/2| below this: a tie in exact arithmetic
 
 
 def value_tol(ftype: str) -> float:
@@ -59,15 +64,17 @@ def to_host_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
 
 
-def oracle_compressed(N: torch.Tensor, F: torch.Tensor, shape, block, index_bits, ftype, mask) -> po.Compressed:
+def oracle_compressed(N: torch.Tensor, F: torch.Tensor, shape, block, index_bits, ftype, mask,
+                      transform: str = "dct") -> po.Compressed:
     """The oracle's view of a compressed array that lives on the GPU (same bits)."""
     P = np.ones(tuple(block), dtype=bool) if mask is None else np.asarray(mask, dtype=bool).reshape(tuple(block))
     grid = po.block_grid(shape, block)
     return po.Compressed(s=tuple(shape), i=tuple(block), N=to_host_f64(N).reshape(grid), F=F.cpu().numpy(), P=P,
-                         index_bits=index_bits, ftype=ftype)
+                         index_bits=index_bits, ftype=ftype, transform=transform)
 
 
-def check_indices(F_gpu: np.ndarray, F_ref: np.ndarray, t_ref: np.ndarray, tau: float, what: str = "F"):
+def check_indices(F_gpu: np.ndarray, F_ref: np.ndarray, t_ref: np.ndarray, tau: float, what: str = "F",
+                  max_fraction: float = MAX_MISMATCH_FRACTION):
     assert F_gpu.shape == F_ref.shape, (F_gpu.shape, F_ref.shape)
     diff = F_gpu.astype(np.int64) - F_ref.astype(np.int64)
     bad = diff != 0
@@ -79,8 +86,14 @@ def check_indices(F_gpu: np.ndarray, F_ref: np.ndarray, t_ref: np.ndarray, tau: 
     dist = np.abs(np.abs(t_ref[bad] - np.floor(t_ref[bad])) - 0.5)
     assert np.all(dist <= tau), (f"{what}: {int((dist > tau).sum())} mismatches are not rounding ties "
                                  f"(worst distance {dist.max():.3e} > band {tau:.3e})")
-    allowed = max(1.0 / diff.size, MAX_MISMATCH_FRACTION)
-    assert frac <= allowed, f"{what}: {n_bad} of {diff.size} indices differ ({frac:.2e} > {allowed:.2e})"
+    # A value that is a half-integer in exact arithmetic (here: to FP64 resolution) has two equally correct
+    # indices; such positions are valid either way and do not count against the cap.  They are structurally
+    # common where the coefficients are small-integer combinations of short-mantissa inputs (Haar on bfloat16).
+    n_counted = int((dist > EXACT_TIE).sum())
+    frac = n_counted / diff.size
+    allowed = max(1.0 / diff.size, max_fraction)
+    assert frac <= allowed, (f"{what}: {n_counted} of {diff.size} indices differ at inexact ties ({frac:.2e} > "
+                             f"{allowed:.2e}); {n_bad - n_counted} more at exact ties")
     return n_bad
 
 
@@ -107,11 +120,14 @@ def check_scalar(got: float, want: float, tol: float, floor: float, what: str):
 class Case:
     """One array pair + settings, run through both implementations."""
 
+    transform = "dct"
+
     def __init__(self, A: np.ndarray, B: Optional[np.ndarray], dtype: str, block, index_bits: int, ftype: str,
-                 mask: Optional[np.ndarray] = None, path: int = 0):
+                 mask: Optional[np.ndarray] = None, path: int = 0, transform: str = "dct"):
         self.dtype, self.block, self.bits, self.ftype, self.mask = dtype, tuple(block), index_bits, ftype, mask
         self.shape = tuple(A.shape)
-        self.codec = Codec(self.block, ftype, index_bits, mask)
+        self.transform = transform
+        self.codec = Codec(self.block, ftype, index_bits, mask, transform)
         if path:
             self.codec.set_kernel_path(path)
         self.hostA, self.hostB = A, B
@@ -131,9 +147,10 @@ class Case:
         x_host = self.hostA if which == "A" else self.hostB
         N, F = self.codec.compress(x_dev)
         torch.cuda.synchronize()
-        ref = po.compress(self.host_f64(x_host), self.block, self.bits, self.ftype, self.mask)
+        ref = po.compress(self.host_f64(x_host), self.block, self.bits, self.ftype, self.mask, self.transform)
         check_N(to_host_f64(N), ref.N, self.ftype)
-        n_bad = check_indices(F.cpu().numpy(), ref.F, ref.t, self.tau)
+        n_bad = check_indices(F.cpu().numpy(), ref.F, ref.t, self.tau,
+                              max_fraction=MAX_MISMATCH_FRACTION_HAAR if self.transform == "haar" else MAX_MISMATCH_FRACTION)
         return N, F, ref, n_bad
 
     def check_compress_statistics(self, N, F, which="A"):
@@ -159,7 +176,8 @@ class Case:
         assert rows.shape == (A.b[0], 3)
         for t in range(A.b[0]):
             run = po.Compressed(s=(A.i[0],) + tuple(A.s[1:]), i=A.i, N=A.N.reshape(A.b)[t:t + 1],
-                                F=A.F[t * per:(t + 1) * per], P=A.P, index_bits=A.index_bits, ftype=A.ftype)
+                                F=A.F[t * per:(t + 1) * per], P=A.P, index_bits=A.index_bits, ftype=A.ftype,
+                                transform=A.transform)
             nr = po.norm2(run)
             n_run = float(per) * float(np.prod(self.block))
             for g, w, f, name in zip(rows[t], (po.mean(run), po.variance(run), nr),
@@ -168,7 +186,7 @@ class Case:
         return st
 
     def oc(self, N, F) -> po.Compressed:
-        return oracle_compressed(N, F, self.shape, self.block, self.bits, self.ftype, self.mask)
+        return oracle_compressed(N, F, self.shape, self.block, self.bits, self.ftype, self.mask, self.transform)
 
     def check_decompress(self, N, F, out_dtype: Optional[str] = None):
         out_dtype = out_dtype or self.dtype

@@ -149,6 +149,45 @@ def test_specialised_kernels_on_ragged_shapes(spec):
     run_all_ops(case)
 
 
+# the Haar transform (Sec. III-A, end of "Orthonormal transform") through every specialised kernel family and the
+# general kernels; shapes ragged where the family allows it
+HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
+        ((37, 72), (8, 8), 16, "f32", "f32", (4, 4), "lane_f32_8x8_i16_box4x4_haar"),
+        ((24, 72), (8, 8), 16, "f32", "f32", None, "lane_f32_8x8_i16_haar"),
+        ((9, 30, 40), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16_haar"),
+        ((3, 33, 96), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8_haar"),
+        ((17, 24, 72), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
+        ((16, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8_haar"),
+        ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "generic"),
+        ((50, 21), (2, 32), 16, "f64", "f64", None, "generic")]
+
+
+@pytest.mark.parametrize("path", [api.PBZ_PATH_AUTO, api.PBZ_PATH_GENERIC], ids=["auto", "generic"])
+@pytest.mark.parametrize("spec", HAAR, ids=[f"{s[0]}-{s[1]}-{s[6]}" for s in HAAR])
+def test_haar_transform(spec, path):
+    shape, block, bits, dtype, ftype, keep, kernel = spec
+    g = rng(400 + len(shape) + bits)
+    mk = lambda: synth.bump_field(shape, 6, g, (2.0, 8.0)) + 0.2 + 0.01 * g.standard_normal(shape)
+    cast = {"f64": lambda a: a, "f32": lambda a: a.astype(np.float32), "bf16": synth.to_bf16_bits}[dtype]
+    mask = None if keep is None else synth.low_frequency_mask(block, keep)
+    case = Case(cast(mk()), cast(mk()), dtype, block, bits, ftype, mask, path, transform="haar")
+    want = kernel if path == api.PBZ_PATH_AUTO else "generic"
+    assert case.codec.kernel_name("compress", shape, dtype) == want
+    assert case.codec.kernel_name("decompress", shape, dtype) == want
+    N1, F1, _, _ = run_all_ops(case)
+    # not the DCT's coefficients under another name: the two codecs disagree on the same input
+    dct = Case(case.hostA, None, dtype, block, bits, ftype, mask, path)
+    _, F_dct = dct.codec.compress(dct.xA)
+    assert not torch.equal(F_dct, F1)
+
+
+def test_transform_is_fixed_once_the_codec_has_compressed():
+    codec = Codec((8, 8), "f32", "i8")
+    codec.compress(torch.zeros((16, 16), dtype=torch.float32, device="cuda"))
+    torch.cuda.synchronize()
+    assert codec._lib.pbz_codec_set_transform(codec._h, 1) == -12
+
+
 @pytest.mark.parametrize("path", [api.PBZ_PATH_AUTO, api.PBZ_PATH_GENERIC], ids=["auto", "generic"])
 def test_arbitrary_mask_without_dc(path):
     g = rng(7)

@@ -23,7 +23,7 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     lib = api.load_library()
     names = header_functions()
-    assert len(names) == 29
+    assert len(names) == 30
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(api.SIGNATURES) == names        # the binding covers exactly the header
@@ -155,6 +155,19 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.pbz_compress_statistics(h, p, 1, shape, p, p, 0, p, p, c.layout((16, 16)).workspace_bytes, None) == -8
     assert lib.pbz_ssim(h, 4, p, p, p, p, float("inf"), 0.0, 1.0, 1.0, 1.0, p, p, 1 << 20, None) == -9
     assert lib.pbz_ssim(h, 4, p, p, p, p, 0.0, 0.0, 1.0, 1.0, 1.0, p, p, 64, None) == -8
+
+
+def test_transform_switch():
+    lib = api.load_library()
+    c = Codec((8, 8), "f32", "i8", transform="haar")
+    assert c.kernel_name("compress", (64, 64), "f32") == "lane_f32_8x8_i8_haar"
+    assert Codec((8, 8), "f32", "i8").kernel_name("compress", (64, 64), "f32") == "lane_f32_8x8_i8"
+    assert lib.pbz_codec_set_transform(c._h, 0) == 0        # nothing compressed yet: may still change
+    assert c.kernel_name("compress", (64, 64), "f32") == "lane_f32_8x8_i8"
+    assert lib.pbz_codec_set_transform(c._h, 7) == -4
+    assert lib.pbz_codec_set_transform(None, 1) == -1
+    with pytest.raises(KeyError):
+        Codec((8, 8), "f32", "i8", transform="walsh")
 
 
 def test_kernel_name_and_path_switch():
