@@ -10,6 +10,8 @@ import math
 import numpy as np
 import pytest
 import scipy.fft
+import scipy.special
+import scipy.stats
 
 from oracle import brute
 from oracle import pbz_oracle as po
@@ -494,3 +496,96 @@ def test_haar_codec_round_trip_and_statistics(case):
     assert not np.array_equal(D.F, A.F)
     with pytest.raises(ValueError):
         po.dot(A, D)
+
+
+# ---------------------------------------------------------------- approximate Wasserstein distance --
+def _wasserstein_inputs(case, seed=40):
+    shape, block, bits, ft, keep = case
+    g = rng(seed)
+    x = synth.bump_field(shape, 5, g, (2.0, 6.0)) + 0.3 + 0.05 * g.standard_normal(shape)
+    y = synth.bump_field(shape, 5, g, (2.0, 6.0)) - 0.1 + 0.05 * g.standard_normal(shape)
+    mask = None if keep is None else synth.low_frequency_mask(block, keep)
+    return po.compress(x, block, bits, ft, mask), po.compress(y, block, bits, ft, mask)
+
+
+def test_softmax_is_the_printed_definition():
+    x = rng(41).standard_normal(50) * 3.0
+    assert np.allclose(po.softmax(x), np.exp(x) / np.sum(np.exp(x)), rtol=1e-14)
+    assert np.allclose(po.softmax(x), scipy.special.softmax(x), rtol=1e-14)
+    assert np.isfinite(po.softmax(np.array([1000.0, 999.0]))).all()          # the plain form would overflow
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_approximate_wasserstein_order_one_is_the_library_distance(case):
+    """For p = 1 the algorithm is the textbook 1-D Wasserstein-1 distance between the two samples of
+    (softmaxed) block means, which scipy computes from the empirical CDFs instead of by sorting."""
+    A, B = _wasserstein_inputs(case)
+    a = po.softmax(po.blockwise_mean(A).reshape(-1))
+    b = po.softmax(po.blockwise_mean(B).reshape(-1))
+    want = scipy.stats.wasserstein_distance(a, b)
+    assert po.approximate_wasserstein(A, B, 1.0) == pytest.approx(want, rel=1e-9)
+
+
+@pytest.mark.parametrize("p", [1.0, 2.0, 3.5, 8.0])
+def test_approximate_wasserstein_is_the_printed_formula(p):
+    A, B = _wasserstein_inputs(CASES[0])
+    c = 8.0                                                              # prod(sqrt((8, 8)))
+    a = A.N.reshape(-1) * A.F[:, 0].astype(np.float64) / 127.0 / c
+    b = B.N.reshape(-1) * B.F[:, 0].astype(np.float64) / 127.0 / c
+    a = np.exp(a) / np.sum(np.exp(a))
+    b = np.exp(b) / np.sum(np.exp(b))
+    want = (np.sum(np.abs(np.sort(a) - np.sort(b)) ** p) / a.size) ** (1.0 / p)   # no rescaling: fine for small p
+    assert po.approximate_wasserstein(A, B, p) == pytest.approx(want, rel=1e-12)
+
+
+def test_approximate_wasserstein_high_order_in_exact_arithmetic():
+    """p = 68 (the order the paper singles out) and p = 80 (where it reports that every peak vanishes) against
+    80-digit decimal arithmetic, on an input with 4096 blocks: at p = 80 the plain FP64 formula underflows to 0,
+    the oracle does not."""
+    import decimal
+    A, B = _wasserstein_inputs(((512, 512), (8, 8), 8, "f64", None))
+    a = po.softmax(po.blockwise_mean(A).reshape(-1))
+    b = po.softmax(po.blockwise_mean(B).reshape(-1))
+    d = np.abs(np.sort(a) - np.sort(b))
+    assert float(np.sum(d ** 80.0)) == 0.0
+    for p in (68, 80):
+        with decimal.localcontext() as ctx:
+            ctx.prec = 80
+            total = sum(decimal.Decimal(float(v)) ** p for v in d) / decimal.Decimal(d.size)
+            want = float(total.ln() / p)
+        got = po.approximate_wasserstein(A, B, float(p))
+        assert got > 0.0
+        assert math.log(got) == pytest.approx(want, rel=1e-12)
+
+
+def test_approximate_wasserstein_invariants():
+    A, B = _wasserstein_inputs(CASES[3])
+    w = po.approximate_wasserstein(A, B, 2.0)
+    assert w > 0.0
+    assert po.approximate_wasserstein(B, A, 2.0) == w
+    assert po.approximate_wasserstein(A, A, 2.0) == 0.0
+    # only the multiset of block means matters: permuting the blocks of one operand changes nothing
+    perm = rng(42).permutation(A.n_blocks)
+    A2 = po.Compressed(s=A.s, i=A.i, N=A.N.reshape(-1)[perm].reshape(A.b), F=A.F[perm], P=A.P,
+                       index_bits=A.index_bits, ftype=A.ftype)
+    assert po.approximate_wasserstein(A2, B, 2.0) == pytest.approx(w, rel=1e-13)
+    # monotone in p (power means) and tending to the largest difference
+    ws = [po.approximate_wasserstein(A, B, p) for p in (1.0, 2.0, 8.0, 68.0, 2000.0)]
+    assert all(x <= y * (1 + 1e-12) for x, y in zip(ws, ws[1:]))
+    a = po.softmax(po.blockwise_mean(A).reshape(-1))
+    b = po.softmax(po.blockwise_mean(B).reshape(-1))
+    assert ws[-1] == pytest.approx(float(np.max(np.abs(np.sort(a) - np.sort(b)))), rel=1e-2)
+
+
+def test_approximate_wasserstein_skips_softmax_for_distributions():
+    """Block means that already sum to one are used as they are (the printed condition)."""
+    g = rng(43)
+    q = g.random((4, 6)); q /= q.sum()
+    r_ = g.random((4, 6)); r_ /= r_.sum()
+    # 1 x 1 blocks with int32 indices: block mean = the value itself to ~1e-10
+    A = po.compress(q, (1, 1), 32, "f64")
+    B = po.compress(r_, (1, 1), 32, "f64")
+    want = (np.sum(np.abs(np.sort(q.reshape(-1)) - np.sort(r_.reshape(-1))) ** 2.0) / q.size) ** 0.5
+    assert po.approximate_wasserstein(A, B, 2.0) == pytest.approx(want, rel=1e-8)
+    with pytest.raises(ValueError):
+        po.approximate_wasserstein(A, B, 0.5)
