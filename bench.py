@@ -200,6 +200,10 @@ def main():
         ("difference_norm2_via_negate_add_norm2", difference_by_rebinning, 2 * lay.f_bytes + 3 * comp_bytes + comp_bytes),
     ]
     if has_dc:
+        # Algorithm 13: reads the first index and N of every block, then sorts two FP64 sequences of n_blocks
+        extras.append(("approximate_wasserstein_p68",
+                       lambda: codec.approximate_wasserstein(N1, F1, N2, F2, 68.0, out=scal[7:8]),
+                       2 * (lay.n_bytes + lay.n_blocks * (lay.f_bytes // (lay.n_blocks * lay.kept_per_block)))))
         bw = torch.empty(lay.n_blocks, dtype=torch.float64, device=dev)
         bw_bytes = lay.n_blocks * 8
         st3 = torch.empty(3, dtype=torch.float64, device=dev)

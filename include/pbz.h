@@ -240,6 +240,21 @@ int pbz_blockwise_std(const pbz_codec* codec, int64_t n_blocks, const void* N, c
 int pbz_blockwise_covariance(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1,
                              const void* N2, const void* F2, double* out, void* stream);
 
+/* Algorithm 13 (Sec. IV-A, "Approximate Wasserstein distance"): the block-wise means of both arrays, each passed
+ * through softmax unless it already sums to one (taken as |sum - 1| <= 1e-9), are sorted, and
+ * (sum |P_A - P_B|^p / n_blocks)^(1/p) goes to out (device, one FP64).  The power sum is scaled by its largest
+ * term, which changes nothing in exact arithmetic and keeps the orders the paper uses (p = 68 .. 80) from
+ * underflowing.  All work (means, reductions, an 8-bit-digit radix sort of both sequences, power mean) is enqueued
+ * on `stream`; nothing is read back to the host.
+ *   p           order, finite and >= 1 (PBZ_ERR_SCALAR otherwise).
+ *   workspace   device, 16-byte aligned, at least the bytes pbz_approximate_wasserstein_workspace reports for
+ *               n_blocks (about 32 bytes per block); contents on entry do not matter.
+ * n_blocks must be below 2^31 (PBZ_ERR_SHAPE).  Requires the mask to keep each block's first coefficient. */
+int pbz_approximate_wasserstein_workspace(const pbz_codec* codec, int64_t n_blocks, size_t* bytes);
+int pbz_approximate_wasserstein(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1,
+                                const void* N2, const void* F2, double p, double* out, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
 /* Name of the kernel family pbz_compress ("compress") or pbz_decompress ("decompress") would run for
  * this shape and array type: "generic" or the name of a specialised kernel.  Host only; returns a static
  * string, or NULL on invalid arguments. */

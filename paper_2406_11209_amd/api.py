@@ -60,6 +60,8 @@ SIGNATURES = {
     "pbz_blockwise_variance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p]),
     "pbz_blockwise_std": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p]),
     "pbz_blockwise_covariance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p]),
+    "pbz_approximate_wasserstein_workspace": (_c.c_int, [_p, _c.c_int64, _c.POINTER(_c.c_size_t)]),
+    "pbz_approximate_wasserstein": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_double, _p, _p, _c.c_size_t, _p]),
     "pbz_kernel_name": (_c.c_char_p, [_p, _c.c_char_p, _i64p, _c.c_int]),
     "pbz_status_string": (_c.c_char_p, [_c.c_int]),
 }
@@ -359,6 +361,21 @@ class Codec:
         ws = self.workspace(N1.device)
         check(self._lib.pbz_ssim(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), float(s_l), float(s_c),
                                  float(w_l), float(w_c), float(w_s), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
+
+    def approximate_wasserstein(self, N1, F1, N2, F2, p: float, out=None, workspace=None):
+        """pbz_approximate_wasserstein: Algorithm 13, one float64."""
+        torch = _torch()
+        out = torch.empty(1, dtype=torch.float64, device=N1.device) if out is None else out
+        if workspace is None:
+            need = _c.c_size_t()
+            check(self._lib.pbz_approximate_wasserstein_workspace(self._h, F1.shape[0], _c.byref(need)))
+            key = ("wasserstein", N1.device.type, N1.device.index)
+            if key not in self._ws or self._ws[key].numel() < need.value:
+                self._ws[key] = torch.empty(need.value, dtype=torch.uint8, device=N1.device)
+            workspace = self._ws[key]
+        check(self._lib.pbz_approximate_wasserstein(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), float(p),
+                                                    _ptr(out), _ptr(workspace), workspace.numel(), _stream()))
         return out
 
     def norm2(self, N, F, out=None):

@@ -444,6 +444,28 @@ int pbz_segmented(const pbz_codec* c, pbz_statistic stat, int64_t n_segments, in
                        ws, static_cast<hipStream_t>(stream), nullptr, n_segments);
 }
 
+int pbz_approximate_wasserstein_workspace(const pbz_codec* c, int64_t n_blocks, size_t* bytes) {
+  if (!bytes) return PBZ_ERR_NULL;
+  int st = check_blocks(c, n_blocks);
+  if (st != PBZ_OK) return st;
+  if (n_blocks >= (int64_t(1) << 31)) return PBZ_ERR_SHAPE;      // the sort counts positions in 32 bits
+  *bytes = wasserstein_workspace_bytes(n_blocks);
+  return PBZ_OK;
+}
+
+int pbz_approximate_wasserstein(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                                const void* F2, double p, double* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!c || !N1 || !F1 || !N2 || !F2 || !out || !ws) return PBZ_ERR_NULL;
+  int st = check_blocks(c, n_blocks);
+  if (st != PBZ_OK) return st;
+  if (n_blocks >= (int64_t(1) << 31)) return PBZ_ERR_SHAPE;
+  if (!std::isfinite(p) || p < 1.0) return PBZ_ERR_SCALAR;
+  if (!c->dc_kept) return PBZ_ERR_DC_PRUNED;
+  if (ws_bytes < wasserstein_workspace_bytes(n_blocks) || (reinterpret_cast<uintptr_t>(ws) & 15u))
+    return PBZ_ERR_WORKSPACE;
+  return launch_approximate_wasserstein(c, n_blocks, N1, F1, N2, F2, p, out, ws, static_cast<hipStream_t>(stream));
+}
+
 int pbz_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* N_in, const void* F_in, double x, void* N_out,
                    void* F_out, void* stream) {
   if (!c || !N_in || !F_in || !N_out || !F_out) return PBZ_ERR_NULL;

@@ -105,6 +105,11 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
 int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment, const double* tile_sums,
                                  int64_t tiles_per_segment, int64_t n_segments, double* out, void* workspace,
                                  hipStream_t s);
+// Algorithm 13; workspace of wasserstein_workspace_bytes(n_blocks) bytes
+size_t wasserstein_workspace_bytes(int64_t n_blocks);
+int launch_approximate_wasserstein(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1,
+                                   const void* N2, const void* F2, double order, double* out, void* workspace,
+                                   hipStream_t s);
 int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,
                       void* Fout, hipStream_t s);
 int launch_blockwise_mean(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out,

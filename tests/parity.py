@@ -153,6 +153,17 @@ class Case:
                               max_fraction=MAX_MISMATCH_FRACTION_HAAR if self.transform == "haar" else MAX_MISMATCH_FRACTION)
         return N, F, ref, n_bad
 
+    def check_wasserstein(self, N1, F1, N2, F2, p: float):
+        """Algorithm 13 against the oracle.  exp and pow come from different libraries on the two sides and every
+        difference of two softmax outputs loses digits to cancellation, so the bar is 1e-9 relative, not 1e-12."""
+        got = self.codec.approximate_wasserstein(N1, F1, N2, F2, p)
+        torch.cuda.synchronize()
+        want = po.approximate_wasserstein(self.oc(N1, F1), self.oc(N2, F2), p)
+        got = float(got.item())
+        assert math.isfinite(got)
+        assert abs(got - want) <= 1e-9 * abs(want) + 1e-300, f"wasserstein(p={p}): got {got!r}, oracle {want!r}"
+        return got
+
     def check_compress_statistics(self, N, F, which="A"):
         """The fused entry point writes the same {N, F} as pbz_compress, and its statistics (and those of the
         one-pass pbz_statistics) are the oracle's mean / variance / norm2 of that compressed array."""

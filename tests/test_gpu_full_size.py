@@ -108,6 +108,7 @@ def test_full_shape(config, capsys):
         full.check_add_scalar(N1, F1, 0.75)
         full.check_blockwise(N1, F1, N2, F2)
         full.check_ssim(N1, F1, N2, F2)
+        full.check_wasserstein(N1, F1, N2, F2, 68.0)
     else:
         # the series: per-step statistics on sub-ranges, every step / consecutive pair
         per = int(np.prod(grid[1:]))

@@ -41,6 +41,9 @@ def run_all_ops(case: Case, out_dtypes=()):
         ops += ["mean", "covariance", "variance"]
     case.check_reductions(N1, F1, N2, F2, ops)
     if has_dc:
+        for p in (1.0, 2.0, 68.0):
+            case.check_wasserstein(N1, F1, N2, F2, p)
+        assert case.check_wasserstein(N1, F1, N1, F1, 3.0) == 0.0
         case.check_compress_statistics(N1, F1, "A")
         for x in (0.75, -3.0):
             N4, F4 = case.check_add_scalar(N1, F1, x)
@@ -179,6 +182,30 @@ def test_haar_transform(spec, path):
     dct = Case(case.hostA, None, dtype, block, bits, ftype, mask, path)
     _, F_dct = dct.codec.compress(dct.xA)
     assert not torch.equal(F_dct, F1)
+
+
+def test_wasserstein_of_distributions_skips_softmax_and_sorts_many_tiles():
+    """Single-element blocks reproduce their input exactly, so means that sum to one stay that way and Algorithm 13
+    uses them as they are; 40,000 blocks span many sort tiles with a ragged last one; negative and repeated
+    values exercise the key order."""
+    g = rng(77)
+    q = g.random((200, 200))
+    q /= q.sum()
+    r_ = g.random((200, 200)) ** 2
+    r_ /= r_.sum()
+    case = Case(q, r_, "f64", (1, 1), 32, "f64")
+    N1, F1 = case.codec.compress(case.xA)
+    N2, F2 = case.codec.compress(case.xB)
+    want = (np.sum(np.abs(np.sort(q.reshape(-1)) - np.sort(r_.reshape(-1))) ** 2.0) / q.size) ** 0.5
+    assert case.check_wasserstein(N1, F1, N2, F2, 2.0) == pytest.approx(want, rel=1e-7)
+    # signed values with many repeats (softmax applies: the sums are far from one)
+    a = np.round(g.standard_normal((200, 200)) * 3.0) / 4.0
+    b = -a[::-1].copy() + 0.25
+    case = Case(a, b, "f64", (1, 1), 32, "f64")
+    N1, F1 = case.codec.compress(case.xA)
+    N2, F2 = case.codec.compress(case.xB)
+    for p in (1.0, 4.0, 80.0):
+        case.check_wasserstein(N1, F1, N2, F2, p)
 
 
 def test_transform_is_fixed_once_the_codec_has_compressed():

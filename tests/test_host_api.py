@@ -23,7 +23,7 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     lib = api.load_library()
     names = header_functions()
-    assert len(names) == 30
+    assert len(names) == 32
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(api.SIGNATURES) == names        # the binding covers exactly the header
@@ -111,6 +111,7 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     shape = (ctypes.c_int64 * 2)(16, 16)
     bad_shape = (ctypes.c_int64 * 2)(16, -1)
     p = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
+    need = ctypes.c_size_t()
     assert lib.pbz_compress(h, None, 1, shape, p, p, None) == -1
     assert lib.pbz_compress(h, p, 9, shape, p, p, None) == -4
     assert lib.pbz_compress(h, p, 1, bad_shape, p, p, None) == -7
@@ -143,9 +144,15 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.pbz_segmented(nodc._h, 3, 2, 4, p, p, None, None, p, p, 1 << 20, None) == -6
     assert lib.pbz_add_scalar(h, 4, p, p, float("nan"), p, p, None) == -9
     assert lib.pbz_difference_norm2(h, 4, p, p, p, None, p, p, 1 << 20, None) == -1
+    assert lib.pbz_approximate_wasserstein_workspace(h, 1000, ctypes.byref(need)) == 0 and need.value >= 32 * 1000
+    assert lib.pbz_approximate_wasserstein_workspace(h, 1 << 31, ctypes.byref(need)) == -7
+    assert lib.pbz_approximate_wasserstein(h, 4, p, p, p, p, 0.5, p, p, 1 << 20, None) == -9
+    assert lib.pbz_approximate_wasserstein(h, 4, p, p, p, p, float("nan"), p, p, 1 << 20, None) == -9
+    assert lib.pbz_approximate_wasserstein(h, 4, p, p, p, p, 2.0, p, p, 64, None) == -8
+    assert lib.pbz_approximate_wasserstein(h, 4, p, p, None, p, 2.0, p, p, 1 << 20, None) == -1
+    assert lib.pbz_approximate_wasserstein(nodc._h, 4, p, p, p, p, 2.0, p, p, 1 << 20, None) == -6
     assert lib.pbz_statistics(nodc._h, 4, p, p, p, p, 1 << 20, None) == -6
     assert lib.pbz_statistics(h, 4, p, p, p, p, 64, None) == -8
-    need = ctypes.c_size_t()
     assert lib.pbz_compress_statistics_workspace(h, shape, 1, ctypes.byref(need)) == 0
     assert need.value == c.layout((16, 16)).workspace_bytes + 2 * 16      # two block rows, one wave each, two FP64 sums per wave
     assert lib.pbz_compress_statistics_workspace(h, bad_shape, 1, ctypes.byref(need)) == -7
