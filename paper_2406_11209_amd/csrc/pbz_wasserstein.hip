@@ -40,6 +40,7 @@ struct Workspace {
   uint64_t* buf0;          // [2][n]: means, then keys; the sorted keys end up here
   uint64_t* buf1;          // [2][n]
   uint32_t* hist;          // [2][kBins][n_tiles]
+  uint32_t* sums;          // [2][kScanGroups]: chunk sums of the histogram scan
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~size_t(255); }
@@ -59,7 +60,9 @@ size_t carve(void* base, int64_t n, Workspace* w) {
   char* d = take(sizeof(uint64_t) * 2 * size_t(n));
   char* e = take(sizeof(uint64_t) * 2 * size_t(n));
   char* f = take(sizeof(uint32_t) * 2 * kBins * size_t(n_tiles));
+  char* g = take(sizeof(uint32_t) * 2 * 1024);      // kScanGroups per operand
   if (w) {
+    w->sums = reinterpret_cast<uint32_t*>(g);
     w->params = reinterpret_cast<OperandParams*>(a);
     w->partials = reinterpret_cast<double*>(b);
     w->scalars = reinterpret_cast<double*>(c);
@@ -190,25 +193,61 @@ __global__ __launch_bounds__(64) void k_radix_hist(const uint64_t* __restrict__ 
   for (int b = lane; b < kBins; b += 64) h[int64_t(b) * n_tiles + blockIdx.x] = count[b];
 }
 
-// exclusive prefix sum, in place, over the kBins * n_tiles counts of one operand (digit-major, so that entry
-// (digit, tile) becomes the output position of that tile's first key with that digit).  One workgroup per operand.
-__global__ __launch_bounds__(1024) void k_radix_scan(uint32_t* __restrict__ hist, int64_t entries) {
-  __shared__ uint32_t totals[1024];
-  uint32_t* h = hist + int64_t(blockIdx.x) * entries;
-  const int64_t per = (entries + 1023) / 1024;
-  const int64_t begin = int64_t(threadIdx.x) * per;
-  const int64_t end = begin + per < entries ? begin + per : entries;
-  uint32_t s = 0;
-  for (int64_t i = begin; i < end; ++i) s += h[i];
-  totals[threadIdx.x] = s;
+// Exclusive prefix sum, in place, over the kBins * n_tiles counts of one operand (digit-major, so that entry
+// (digit, tile) becomes the output position of that tile's first key with that digit).  Three steps: the sum of
+// every chunk, an exclusive scan of the at most kScanGroups chunk sums by one workgroup, and a scan inside every
+// chunk started from its chunk's offset.  grid y = operand.
+constexpr int kScanGroups = 1024;
+
+__device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t v, uint32_t* lds /* blockDim.x entries */,
+                                                         uint32_t* total) {
+  lds[threadIdx.x] = v;
   __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {      // inclusive scan of the per-thread totals
-    const uint32_t add = threadIdx.x >= off ? totals[threadIdx.x - off] : 0u;
+  for (int off = 1; off < int(blockDim.x); off <<= 1) {
+    const uint32_t add = int(threadIdx.x) >= off ? lds[threadIdx.x - off] : 0u;
     __syncthreads();
-    totals[threadIdx.x] += add;
+    lds[threadIdx.x] += add;
     __syncthreads();
   }
-  uint32_t run = totals[threadIdx.x] - s;          // exclusive
+  if (total) *total = lds[blockDim.x - 1];
+  return lds[threadIdx.x] - v;
+}
+
+__global__ __launch_bounds__(kThreads) void k_scan_sums(const uint32_t* __restrict__ hist, int64_t entries,
+                                                        int64_t chunk, uint32_t* __restrict__ sums) {
+  __shared__ uint32_t lds[kThreads];
+  const uint32_t* h = hist + int64_t(blockIdx.y) * entries;
+  const int64_t begin = int64_t(blockIdx.x) * chunk;
+  const int64_t end = begin + chunk < entries ? begin + chunk : entries;
+  uint32_t s = 0;
+  for (int64_t i = begin + threadIdx.x; i < end; i += kThreads) s += h[i];
+  uint32_t total;
+  group_exclusive_scan(s, lds, &total);
+  if (threadIdx.x == 0) sums[blockIdx.y * kScanGroups + blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kScanGroups) void k_scan_top(uint32_t* __restrict__ sums, int groups) {
+  __shared__ uint32_t lds[kScanGroups];
+  uint32_t* mine = sums + blockIdx.x * kScanGroups;
+  const uint32_t v = int(threadIdx.x) < groups ? mine[threadIdx.x] : 0u;
+  const uint32_t ex = group_exclusive_scan(v, lds, nullptr);
+  if (int(threadIdx.x) < groups) mine[threadIdx.x] = ex;
+}
+
+__global__ __launch_bounds__(kThreads) void k_scan_apply(uint32_t* __restrict__ hist, int64_t entries, int64_t chunk,
+                                                         const uint32_t* __restrict__ sums) {
+  __shared__ uint32_t lds[kThreads];
+  uint32_t* h = hist + int64_t(blockIdx.y) * entries;
+  const int64_t chunk_begin = int64_t(blockIdx.x) * chunk;
+  const int64_t chunk_end = chunk_begin + chunk < entries ? chunk_begin + chunk : entries;
+  const int64_t per = chunk / kThreads;                       // chunk is a multiple of kThreads
+  int64_t begin = chunk_begin + int64_t(threadIdx.x) * per;
+  int64_t end = begin + per;
+  if (begin > chunk_end) begin = chunk_end;
+  if (end > chunk_end) end = chunk_end;
+  uint32_t s = 0;
+  for (int64_t i = begin; i < end; ++i) s += h[i];
+  uint32_t run = sums[blockIdx.y * kScanGroups + blockIdx.x] + group_exclusive_scan(s, lds, nullptr);
   for (int64_t i = begin; i < end; ++i) {
     const uint32_t v = h[i];
     h[i] = run;
@@ -332,12 +371,20 @@ int launch_approximate_wasserstein(const pbz_codec* c, int64_t n, const void* N1
   const int64_t total = 2 * n;
   hipLaunchKernelGGL(k_to_keys, dim3(unsigned((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, w.buf0, total);
   const int64_t n_tiles = (n + kTileKeys - 1) / kTileKeys;
+  const int64_t entries = int64_t(kBins) * n_tiles;
+  // 16 counts per thread unless that needs more than kScanGroups chunks
+  int64_t scan_chunk = int64_t(kThreads) * 16;
+  if ((entries + scan_chunk - 1) / scan_chunk > kScanGroups)
+    scan_chunk = ((entries + kScanGroups - 1) / kScanGroups + kThreads - 1) / kThreads * kThreads;
+  const int scan_groups = int((entries + scan_chunk - 1) / scan_chunk);
   uint64_t* src = w.buf0;
   uint64_t* dst = w.buf1;
   for (int pass = 0; pass < 64 / kRadixBits; ++pass) {
     const int shift = pass * kRadixBits;
     hipLaunchKernelGGL(k_radix_hist, dim3(unsigned(n_tiles), 2), dim3(64), 0, s, src, n, n_tiles, shift, w.hist);
-    hipLaunchKernelGGL(k_radix_scan, dim3(2), dim3(1024), 0, s, w.hist, int64_t(kBins) * n_tiles);
+    hipLaunchKernelGGL(k_scan_sums, dim3(scan_groups, 2), dim3(kThreads), 0, s, w.hist, entries, scan_chunk, w.sums);
+    hipLaunchKernelGGL(k_scan_top, dim3(2), dim3(kScanGroups), 0, s, w.sums, scan_groups);
+    hipLaunchKernelGGL(k_scan_apply, dim3(scan_groups, 2), dim3(kThreads), 0, s, w.hist, entries, scan_chunk, w.sums);
     hipLaunchKernelGGL(k_radix_scatter, dim3(unsigned(n_tiles), 2), dim3(64), 0, s, src, dst, n, n_tiles, shift, w.hist);
     uint64_t* t = src;
     src = dst;
