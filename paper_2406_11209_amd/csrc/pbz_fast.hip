@@ -750,6 +750,68 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float
   }
 }
 
+// The same computation laid out for wide arrays: a workgroup of eight waves owns 64 consecutive blocks, wave z
+// rebuilds plane z of all of them (lane = block), so that every store instruction writes one whole contiguous
+// 1 KiB row piece (measured 6.6 TB/s for this store pattern against 5.7 TB/s for the 128-byte pieces above);
+// the plane index is uniform over the wave, so its matrix row comes from scalar loads.
+template <int TF, int KZ, int KY, int KX>
+__global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const float* __restrict__ N,
+                                                              const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
+  constexpr int KEPT = KZ * KY * KX;
+  static_assert(KEPT % 16 == 0, "F blocks are whole 16-byte vectors");
+  const int lane = threadIdx.x & 63;
+  const int z = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t t = blockIdx.x;                               // tile of 64 blocks within the z-slab
+  const uint32_t slab = blockIdx.y + blockIdx.z * gridDim.y;
+  if (t >= g.tiles_yx || slab >= g.gz) return;
+  const int64_t by = t / g.tiles_x, tx = t - uint32_t(by) * g.tiles_x, bz = slab;
+  const int64_t bx = tx * 64 + lane;
+  const int64_t zz = bz * 8 + z;
+  if (bx >= g.gx || zz >= g.Z) return;
+  const int64_t block = (bz * g.gy + by) * g.gx + bx;
+
+  uint32_t w[KEPT / 4];
+#pragma unroll
+  for (int k = 0; k < KEPT / 16; ++k) {
+    const uint4 f = reinterpret_cast<const uint4*>(F + block * KEPT)[k];
+    w[4 * k] = f.x; w[4 * k + 1] = f.y; w[4 * k + 2] = f.z; w[4 * k + 3] = f.w;
+  }
+  // this lane's plane z of the inverse z transform: sum_q (N / r) H[z][q] C[q][.][.]
+  const float scale = N[block] / float(g.r);
+  float hz[KZ];
+#pragma unroll
+  for (int q = 0; q < KZ; ++q) hz[q] = scale * (TF == kTfHaar ? c_haar8.h[z][q] : c_dct8.h[z][q]);
+  float v[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) v[i] = 0.0f;
+#pragma unroll
+  for (int yy0 = 0; yy0 < KY; ++yy0)
+#pragma unroll
+    for (int xx = 0; xx < KX; ++xx) {
+      float acc = 0.0f;
+#pragma unroll
+      for (int q = 0; q < KZ; ++q) {
+        const int jf = (q * KY + yy0) * KX + xx;
+        acc += hz[q] * float(IdxPack<int8_t>::get(w[jf >> 2], jf & 3));
+      }
+      v[yy0 * 8 + xx] = acc;
+    }
+#pragma unroll
+  for (int xx = 0; xx < KX; ++xx) tf_inverse<TF, float, 8, 8, KY>(v + xx);
+#pragma unroll
+  for (int yy0 = 0; yy0 < 8; ++yy0) tf_inverse<TF, float, 8, 1, KX>(v + yy0 * 8);
+#pragma unroll
+  for (int yy0 = 0; yy0 < 8; ++yy0) {
+    const int64_t yy = by * 8 + yy0;
+    if (yy < g.Y) {
+      const float* r8 = v + yy0 * 8;
+      *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 8) =
+          make_uint4(pack_bf16x2(r8[0], r8[1]), pack_bf16x2(r8[2], r8[3]), pack_bf16x2(r8[4], r8[5]),
+                     pack_bf16x2(r8[6], r8[7]));
+    }
+  }
+}
+
 // ---- host side --------------------------------------------------------------------------------------
 struct Folded {
   bool ok;
@@ -925,9 +987,15 @@ struct Oct8Kernel {
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
-    if (!tile_grid(g, 8, 4, &grid)) return 0;
-    hipLaunchKernelGGL((k_decompress_oct8<TF, KZ, KY, KX>), grid, dim3(256), 0, s, g, static_cast<const float*>(N),
-                       static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
+    if (g.gx >= 48) {        // at least three quarters of the lanes of a 64-block tile busy
+      if (!tile_grid(g, 64, 1, &grid)) return 0;
+      hipLaunchKernelGGL((k_decompress_oct8_rows<TF, KZ, KY, KX>), grid, dim3(512), 0, s, g,
+                         static_cast<const float*>(N), static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
+    } else {
+      if (!tile_grid(g, 8, 4, &grid)) return 0;
+      hipLaunchKernelGGL((k_decompress_oct8<TF, KZ, KY, KX>), grid, dim3(256), 0, s, g, static_cast<const float*>(N),
+                         static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
+    }
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };

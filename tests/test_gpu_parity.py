@@ -136,7 +136,10 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((2, 19, 560), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8"),
                ((17, 9, 24), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 17, 200), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
-               ((17, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
+               ((17, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8"),
+               # 49 and more blocks along x: the decompress variant that stores whole row pieces
+               ((17, 9, 520), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
+               ((9, 12, 392), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
 
 
 @pytest.mark.parametrize("spec", FAST_RAGGED, ids=[f"{s[0]}-{s[6]}" for s in FAST_RAGGED])
@@ -161,6 +164,7 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((3, 33, 96), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8_haar"),
         ((17, 24, 72), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((16, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8_haar"),
+        ((9, 9, 512), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "generic"),
         ((50, 21), (2, 32), 16, "f64", "f64", None, "generic")]
 
