@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per compress launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
 # the same counters read for a plain element-wise kernel over the same array); recorded in profiles/.
 MEASURED_COMPRESS_TRAFFIC = {
-    "cfg4_3d_f64_b4x4x4_i16": int((1048722.6 + 278523.3) * 1024),     # KiB read + KiB written, scaled
-    "cfg5_3d_bf16_b8x8x8_i8_mask4x4x4": int((1048678.4 + 69642.7) * 1024),
+    "cfg4_3d_f64_b4x4x4_i16": int((1048723.8 + 278521.9) * 1024),     # KiB read + KiB written, scaled
+    "cfg5_3d_bf16_b8x8x8_i8_mask4x4x4": int((1048670.9 + 69635.0) * 1024),
 }
 
 
@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the operations timed outside the step (used for profiles of the step itself)")
     ap.add_argument("--transform", default="dct", choices=["dct", "haar"],
                     help="orthonormal transform of the codec (the metric is quoted with the default, the DCT)")
     return ap.parse_args()
@@ -259,7 +261,7 @@ def main():
                  2 * comp_bytes * (T - 1) // T),
                 ("series_variance_one_call_per_step", per_step_variance, comp_bytes),
             ]
-    for name, fn, moved in extras:
+    for name, fn, moved in ([] if args.no_extras else extras):
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
