@@ -6,7 +6,8 @@ in HBM: compress(A), decompress, negate, multiply by a scalar, add(A, B), dot, L
 covariance, variance, cosine similarity (B is compressed once, outside the timed region).  The default
 workload is the 512^3 FP64 volume with 4x4x4 blocks and int16 indices (the largest configuration whose
 operation list is exactly compress / decompress / dot / norm); `--config 5` selects the 1 GiB bfloat16
-volume, `--config 1..3` the smaller ones.
+volume, `--config 1..3` the smaller ones, `--config 6` an MRI-like FP32 stack in 4x16x16 blocks (not one of the
+benchmark workloads).
 
 Prints one JSON line:  value = GB/s of uncompressed input pushed through the whole step;  `ops` has the
 per-operation times (HIP events on the launch stream, inside the timed region), GB/s of uncompressed
@@ -42,7 +43,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the operations timed outside the step (used for profiles of the step itself)")
@@ -301,7 +302,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         # sized for roughly 10-30 s of oracle time on the machine's host cores
-        sample = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (512, 512, 512)}[args.config]
+        sample = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (512, 512, 512), 6: (128, 512, 512)}[args.config]
         out["cpu_baseline"] = cpu_baseline(wl, sample, args.transform)
     print(json.dumps(out))
 

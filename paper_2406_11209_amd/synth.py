@@ -168,6 +168,7 @@ _FULL_SHAPES: Dict[int, Tuple[int, ...]] = {
     3: (64, 1024, 1024),
     4: (512, 512, 512),
     5: (1024, 1024, 512),
+    6: (250, 1024, 1024),
 }
 
 
@@ -188,7 +189,7 @@ def _cast(x64: Optional[np.ndarray], dtype: str) -> Optional[np.ndarray]:
 
 
 def make_workload(config: int, shape: Optional[Sequence[int]] = None, second: bool = True) -> Workload:
-    """Workload ``config`` (1..5), at its full shape or at ``shape`` (same recipe, fewer
+    """Workload ``config`` (1..5: the benchmark's; 6: an MRI-like stack in 4 x 16 x 16 blocks), at its full shape or at ``shape`` (same recipe, fewer
     elements; bump counts are kept, so reduced shapes are denser in bumps).
 
     Array A uses seed BASE_SEED + 10 * config, the second operand B uses that seed + 1
@@ -222,4 +223,10 @@ def make_workload(config: int, shape: Optional[Sequence[int]] = None, second: bo
         A, B = two(lambda g: noisy_bump_field(shape, 64, 1e-3, g, "bf16"))
         return Workload("cfg5_3d_bf16_b8x8x8_i8_mask4x4x4", shape, (8, 8, 8), "bf16", "f32", 8,
                         low_frequency_mask((8, 8, 8), (4, 4, 4)), A, B)
-    raise ValueError("config must be 1..5")
+    if config == 6:
+        # beyond the five benchmark workloads: a stack shaped like the paper's MRI volumes (first dimension
+        # small and not a multiple of the block extent, so that padding matters), in the non-hypercubic block
+        # shape its MRI experiment singles out (Sec. V)
+        A, B = two(lambda g: noisy_bump_field(shape, 64, 1e-3, g, "f32"))
+        return Workload("cfg6_3d_f32_b4x16x16_i8", shape, (4, 16, 16), "f32", "f32", 8, None, A, B)
+    raise ValueError("config must be 1..6")

@@ -17,7 +17,7 @@ from parity import Case
 pytestmark = pytest.mark.gpu
 
 # reduced shapes of the five workloads: same recipe, several tiles in every dimension
-SMALL = {1: (256, 256), 2: (512, 768), 3: (4, 128, 256), 4: (64, 64, 128), 5: (64, 48, 128)}
+SMALL = {1: (256, 256), 2: (512, 768), 3: (4, 128, 256), 4: (64, 64, 128), 5: (64, 48, 128), 6: (10, 64, 128)}
 
 
 def rng(seed):
@@ -56,7 +56,7 @@ def run_all_ops(case: Case, out_dtypes=()):
 
 
 @pytest.mark.parametrize("path", [api.PBZ_PATH_AUTO, api.PBZ_PATH_GENERIC], ids=["auto", "generic"])
-@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("config", [1, 2, 3, 4, 5, 6])
 def test_workload_reduced_shape(config, path):
     wl = synth.make_workload(config, SMALL[config])
     case = Case(wl.A, wl.B, wl.dtype, wl.block, wl.index_bits, wl.ftype, wl.mask, path)
@@ -137,6 +137,9 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((17, 9, 24), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 17, 200), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((17, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8"),
+               ((9, 40, 64), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8"),       # the MRI block shape
+               ((10, 33, 144), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8"),
+               ((8, 32, 80), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8"),
                # 49 and more blocks along x: the decompress variant that stores whole row pieces
                ((17, 9, 520), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 12, 392), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
@@ -165,6 +168,7 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((17, 24, 72), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((16, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8_haar"),
         ((9, 9, 512), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
+        ((9, 20, 48), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
         ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "generic"),
         ((50, 21), (2, 32), 16, "f64", "f64", None, "generic")]
 
