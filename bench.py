@@ -200,6 +200,7 @@ def main():
 
     extras = [
         ("difference_norm2", lambda: codec.difference_norm2(N1, F1, N2, F2, out=scal[7:8]), 2 * comp_bytes),
+        ("subtract", lambda: codec.subtract(N1, F1, N2, F2, N_out=Nn, F_out=Fn), 3 * comp_bytes),
         ("difference_norm2_via_negate_add_norm2", difference_by_rebinning, 2 * lay.f_bytes + 3 * comp_bytes + comp_bytes),
     ]
     if has_dc:

@@ -157,6 +157,12 @@ int pbz_mul_scalar(const pbz_codec* codec, int64_t n_blocks, const void* N_in, c
 int pbz_add(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
             const void* F2, void* N_out, void* F_out, void* stream);
 
+/* A - B, the compressed-space difference of Sec. V (shallow-water experiment: "negation and element-wise
+ * addition"), in one pass: Algorithm 2 applied to A and Algorithm 1's negation of B without writing the
+ * negated array; bit for bit the result of pbz_negate followed by pbz_add.  Arguments as for pbz_add. */
+int pbz_subtract(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                 const void* F2, void* N_out, void* F_out, void* stream);
+
 /* Reductions.  Each writes one FP64 scalar to out (device).  `workspace` is device scratch of at least the
  * size pbz_layout reports, 16-byte aligned; its contents on entry do not matter.  Calls that may run
  * concurrently must use distinct workspaces.

@@ -42,6 +42,7 @@ SIGNATURES = {
     "pbz_negate": (_c.c_int, [_p, _c.c_int64, _p, _p, _p]),
     "pbz_mul_scalar": (_c.c_int, [_p, _c.c_int64, _p, _p, _c.c_double, _p, _p, _p]),
     "pbz_add": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _p]),
+    "pbz_subtract": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _p]),
     "pbz_dot": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_covariance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_cosine_similarity": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
@@ -282,6 +283,14 @@ class Codec:
         N_out = torch.empty_like(N1) if N_out is None else N_out
         F_out = torch.empty_like(F1) if F_out is None else F_out
         check(self._lib.pbz_add(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), _ptr(N_out), _ptr(F_out),
+                                _stream()))
+        return N_out, F_out
+
+    def subtract(self, N1, F1, N2, F2, N_out=None, F_out=None):
+        torch = _torch()
+        N_out = torch.empty_like(N1) if N_out is None else N_out
+        F_out = torch.empty_like(F1) if F_out is None else F_out
+        check(self._lib.pbz_subtract(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), _ptr(N_out), _ptr(F_out),
                                 _stream()))
         return N_out, F_out
 

@@ -379,6 +379,14 @@ int pbz_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1
   return launch_add(c, n_blocks, N1, F1, N2, F2, N_out, F_out, static_cast<hipStream_t>(stream));
 }
 
+int pbz_subtract(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2, const void* F2,
+                 void* N_out, void* F_out, void* stream) {
+  if (!c || !N1 || !F1 || !N2 || !F2 || !N_out || !F_out) return PBZ_ERR_NULL;
+  int st = check_blocks(c, n_blocks);
+  if (st != PBZ_OK) return st;
+  return launch_add(c, n_blocks, N1, F1, N2, F2, N_out, F_out, static_cast<hipStream_t>(stream), -1.0);
+}
+
 static int reduce2(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1,
                    const void* N2, const void* F2, double* out, void* ws, size_t ws_bytes, void* stream,
                    bool two, bool needs_dc) {

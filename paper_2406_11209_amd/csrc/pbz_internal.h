@@ -92,7 +92,7 @@ int launch_negate(const pbz_codec* c, int64_t n_blocks, const void* Fin, void* F
 int launch_mul_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x,
                       void* Nout, void* Fout, hipStream_t s);
 int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
-               const void* F2, void* Nout, void* Fout, hipStream_t s);
+               const void* F2, void* Nout, void* Fout, hipStream_t s, double sign2 = 1.0);   // sign2 = -1: A - B
 
 enum ReduceOp { kDot = 0, kNorm2 = 1, kCosine = 2, kMean = 3, kCovariance = 4, kVariance = 5, kSsim = 6,
                 kDiffNorm2 = 7, kStatistics = 8 /* out[0..3) = mean, variance, norm2 from one pass */ };

@@ -230,11 +230,12 @@ template <int kIType, int kNType>
 __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                       const void* __restrict__ N2, const uint4* __restrict__ F2,
                                                       void* __restrict__ Nout, uint4* __restrict__ Fout, double r,
-                                                      int64_t nvec, int lanes_shift) {
+                                                      double sign2, int64_t nvec, int lanes_shift) {
   constexpr int kPer = PerDword<kIType>::value;
   constexpr int kElems = 4 * kPer;
   const int lanes = 1 << lanes_shift;
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
+  // sign2 = -1 subtracts: F2 (-N2) is exactly (-F2) N2, so the result is bit for bit that of negate + add
   // the loop bound is uniform over the wave so that the lane exchanges below are always convergent
   const int64_t first = int64_t(blockIdx.x) * kThreads + threadIdx.x;
   const int64_t wave_first = first - (threadIdx.x & 63);
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
     const int64_t vc = live ? v : nvec - 1;      // lanes past the end redo the last vector and store nothing
     const int64_t k = vc >> lanes_shift;
     const uint4 a = F1[vc], b = F2[vc];
-    const double n1 = load_N<kNType>(N1, k), n2 = load_N<kNType>(N2, k);
+    const double n1 = load_N<kNType>(N1, k), n2 = sign2 * load_N<kNType>(N2, k);
     double c[kElems];
     double m = 0.0;
     const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
@@ -295,9 +296,9 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
 __global__ __launch_bounds__(64) void k_add_generic(const void* __restrict__ N1, const void* __restrict__ F1,
                                                     const void* __restrict__ N2, const void* __restrict__ F2,
                                                     void* __restrict__ Nout, void* __restrict__ Fout, int ntype,
-                                                    int itype, double r, int64_t n_blocks, int kept) {
+                                                    int itype, double r, double sign2, int64_t n_blocks, int kept) {
   for (int64_t k = blockIdx.x; k < n_blocks; k += gridDim.x) {
-    const double n1 = load_float<double>(N1, ntype, k), n2 = load_float<double>(N2, ntype, k);
+    const double n1 = load_float<double>(N1, ntype, k), n2 = sign2 * load_float<double>(N2, ntype, k);
     double m = 0.0;
     for (int j = threadIdx.x; j < kept; j += 64) {
       double ce = unfused_sum_of_products(double(load_index(F1, itype, k * kept + j)), n1,
@@ -775,7 +776,7 @@ int launch_mul_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, con
 }
 
 int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2, const void* F2,
-               void* Nout, void* Fout, hipStream_t s) {
+               void* Nout, void* Fout, hipStream_t s, double sign2) {
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const int lanes_shift = bpb % 16 == 0 ? ilog2_exact(bpb / 16) : -1;
   const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
@@ -787,7 +788,7 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
     const uint4* a = static_cast<const uint4*>(F1);
     const uint4* b = static_cast<const uint4*>(F2);
     uint4* o = static_cast<uint4*>(Fout);
-#define PBZ_ADD(IT, NT) hipLaunchKernelGGL((k_add_vec<IT, NT>), grid, block, 0, s, N1, a, N2, b, Nout, o, c->r, nvec, lanes_shift)
+#define PBZ_ADD(IT, NT) hipLaunchKernelGGL((k_add_vec<IT, NT>), grid, block, 0, s, N1, a, N2, b, Nout, o, c->r, sign2, nvec, lanes_shift)
     if (c->ftype == PBZ_F64) {
       if (c->itype == PBZ_I8) PBZ_ADD(PBZ_I8, PBZ_F64);
       else if (c->itype == PBZ_I16) PBZ_ADD(PBZ_I16, PBZ_F64);
@@ -801,7 +802,7 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
   } else {
     int64_t g = n_blocks < 65536 ? n_blocks : 65536;
     hipLaunchKernelGGL(k_add_generic, dim3(int(g)), dim3(64), 0, s, N1, F1, N2, F2, Nout, Fout, int(c->ftype),
-                       int(c->itype), c->r, n_blocks, c->kept);
+                       int(c->itype), c->r, sign2, n_blocks, c->kept);
   }
   return hip_status(hipGetLastError());
 }

@@ -238,6 +238,17 @@ class Case:
         check_indices(F3.cpu().numpy(), ref.F, ref.t, po.index_radius(self.bits) * 2.0 ** -50, "add.F")
         return N3, F3
 
+    def check_subtract(self, N1, F1, N2, F2):
+        """The one-pass difference: the oracle's add(A, negate(B)), and bit for bit the two-call route."""
+        N3, F3 = self.codec.subtract(N1, F1, N2, F2)
+        N4, F4 = self.codec.add(N1, F1, N2, self.codec.negate(F2))
+        torch.cuda.synchronize()
+        ref = po.add(self.oc(N1, F1), po.negate(self.oc(N2, F2)))
+        check_N(to_host_f64(N3), ref.N, self.ftype, "subtract.N")
+        check_indices(F3.cpu().numpy(), ref.F, ref.t, po.index_radius(self.bits) * 2.0 ** -50, "subtract.F")
+        assert torch.equal(N3, N4) and torch.equal(F3, F4), "subtract differs from negate + add"
+        return N3, F3
+
     def check_add_scalar(self, N, F, x: float):
         N2, F2 = self.codec.add_scalar(N, F, x)
         torch.cuda.synchronize()

@@ -35,6 +35,7 @@ def run_all_ops(case: Case, out_dtypes=()):
         case.check_mul_scalar(N1, F1, x)
     N3, F3 = case.check_add(N1, F1, N2, F2)
     case.check_decompress(N3, F3)
+    case.check_subtract(N1, F1, N2, F2)
     ops = ["dot", "norm2", "cosine_similarity"]
     has_dc = case.mask is None or bool(np.asarray(case.mask).reshape(-1)[0])
     if has_dc:
