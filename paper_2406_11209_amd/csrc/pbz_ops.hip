@@ -625,6 +625,8 @@ __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, con
 // N is FP32 or FP64 (template), F is viewed as 16-byte vectors; vpb vectors per block (a power of two when
 // vpb_shift >= 0).  Workgroup b streams the contiguous vectors [b * chunk, (b + 1) * chunk): per step every
 // thread issues kUnroll loads per operand, kThreads vectors apart, with no branch between them.
+constexpr int reduce_unroll(bool two) { return two ? kUnroll : 2 * kUnroll; }
+
 template <int kIType, int kNType, bool kTwo, bool kDC, bool kDiff = false>
 __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                          const void* __restrict__ N2, const uint4* __restrict__ F2,
@@ -643,28 +645,30 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
   }
   const int64_t begin = int64_t(blockIdx.x) * chunk;
   const int64_t end = begin + chunk < nvec ? begin + chunk : nvec;
-  constexpr int64_t kStep = int64_t(kThreads) * kUnroll;
+  constexpr int kLoads = reduce_unroll(kTwo);       // the same bytes in flight with one operand as with two
+  constexpr int64_t kStep = int64_t(kThreads) * kLoads;
   int64_t base = begin;
   for (; base + kStep <= end; base += kStep) {
-    uint4 a[kUnroll], b[kUnroll];
-    double n1[kUnroll], n2[kUnroll];
-    int64_t k[kUnroll];
+    uint4 a[kLoads], b[kTwo ? kLoads : 1];
+    double n1[kLoads], n2[kLoads];
+    int64_t k[kLoads];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kLoads; ++u) {
       const int64_t v = base + u * kThreads + threadIdx.x;
       k[u] = vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
       a[u] = F1[v];
-      if (kTwo) b[u] = F2[v];
+      if constexpr (kTwo) b[u] = F2[v];
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kLoads; ++u) {
       n1[u] = load_N<kNType>(N1, k[u]);
       n2[u] = kTwo ? load_N<kNType>(N2, k[u]) : 0.0;
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kLoads; ++u) {
       const int64_t v = base + u * kThreads + threadIdx.x;
-      accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a[u], kTwo ? b[u] : a[u], n1[u], n2[u], kDC && (v - k[u] * vpb) == 0);
+      accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a[u], kTwo ? b[kTwo ? u : 0] : a[u], n1[u], n2[u],
+                                               kDC && (v - k[u] * vpb) == 0);
     }
   }
   for (int64_t v = base + threadIdx.x; v < end; v += kThreads) {
@@ -808,8 +812,8 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
 }
 
 // contiguous vectors per workgroup: whole steps of kThreads * kUnroll, as few as keep the grid within max_groups
-static int64_t chunk_for(int64_t nvec, int max_groups, int* groups) {
-  const int64_t step = int64_t(kThreads) * kUnroll;
+static int64_t chunk_for(int64_t nvec, int max_groups, int* groups, bool two) {
+  const int64_t step = int64_t(kThreads) * reduce_unroll(two);
   int64_t steps = (nvec + step * max_groups - 1) / (step * max_groups);
   if (steps < 1) steps = 1;
   const int64_t chunk = steps * step;
@@ -858,7 +862,7 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     } else if (wide_N && bpb % 16 == 0 && aligned16(f1) && (!two || aligned16(f2)) && f_stride % 16 == 0) {
       const int64_t vpb = bpb / 16;
       const int64_t nvec = n_blocks * vpb;
-      const int64_t chunk = chunk_for(nvec, max_groups, &groups);
+      const int64_t chunk = chunk_for(nvec, max_groups, &groups, two);
       dim3 grid(groups, batch);
       const int shift = ilog2_exact(vpb);
       if (c->itype == PBZ_I8)
