@@ -524,6 +524,7 @@ __device__ __forceinline__ double finish_statistic(const double* s, const Reduce
 }
 
 // sum of `sums` over the workgroup, valid in threads 0 .. kNumSums-1 (thread i returns total i)
+template <int kWaves = kThreads / 64>
 __device__ __forceinline__ double group_total(const double* sums, double (*lds)[kNumSums]) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
@@ -534,7 +535,7 @@ __device__ __forceinline__ double group_total(const double* sums, double (*lds)[
   __syncthreads();
   double t = 0.0;
   if (threadIdx.x < kNumSums)
-    for (int w = 0; w < kThreads / 64; ++w) t += lds[w][threadIdx.x];
+    for (int w = 0; w < kWaves; ++w) t += lds[w][threadIdx.x];
   return t;
 }
 
@@ -546,16 +547,37 @@ __device__ __forceinline__ void reduce_tail(double* sums, const ReduceTail& t) {
     t.partials[(int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * kReducePartialSlots + threadIdx.x] = total;
 }
 
-// one workgroup per segment: adds that segment's n_partials partial sums in index order
-__global__ __launch_bounds__(kThreads) void k_reduce_final(ReduceTail t, int n_partials) {
-  __shared__ double lds[kThreads / 64][kNumSums];
+// one workgroup per segment: adds that segment's n_partials partial sums in a fixed order.  Every thread first
+// issues all its loads (a partial is one 64-byte record whose five sums are read as three 16-byte pieces, at
+// most kReduceMaxGroups / kFinalThreads records per thread, from a clamped index: no branch around a load), then adds: the kernel's duration is one or two memory
+// round trips instead of one per partial.
+constexpr int kFinalThreads = 1024;
+constexpr int kFinalRecords = kReduceMaxGroups / kFinalThreads;
+static_assert(kReduceMaxGroups % kFinalThreads == 0 && kReducePartialSlots == 8, "record layout");
+
+__global__ __launch_bounds__(kFinalThreads) void k_reduce_final(ReduceTail t, int n_partials) {
+  __shared__ double lds[kFinalThreads / 64][kNumSums];
   __shared__ double fin[kNumSums];
   double acc[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
-  const double* mine = t.partials + int64_t(blockIdx.x) * n_partials * kReducePartialSlots;
-  for (int p = threadIdx.x; p < n_partials; p += kThreads)
+  const double2* mine = reinterpret_cast<const double2*>(t.partials + int64_t(blockIdx.x) * n_partials * kReducePartialSlots);
+  double2 rec[kFinalRecords][3];
 #pragma unroll
-    for (int i = 0; i < kNumSums; ++i) acc[i] += mine[int64_t(p) * kReducePartialSlots + i];
-  const double grand = group_total(acc, lds);
+  for (int j = 0; j < kFinalRecords; ++j) {
+    const int p = j * kFinalThreads + int(threadIdx.x);
+    const int pc = p < n_partials ? p : 0;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) rec[j][q] = mine[int64_t(pc) * 4 + q];
+  }
+#pragma unroll
+  for (int j = 0; j < kFinalRecords; ++j)
+    if (j * kFinalThreads + int(threadIdx.x) >= n_partials) rec[j][0] = rec[j][1] = rec[j][2] = make_double2(0.0, 0.0);
+#pragma unroll
+  for (int j = 0; j < kFinalRecords; ++j) {
+    acc[0] += rec[j][0].x; acc[1] += rec[j][0].y;
+    acc[2] += rec[j][1].x; acc[3] += rec[j][1].y;
+    acc[4] += rec[j][2].x;
+  }
+  const double grand = group_total<kFinalThreads / 64>(acc, lds);
   if (threadIdx.x < kNumSums) fin[threadIdx.x] = grand;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -879,7 +901,7 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     }
     int st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;
-    hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kThreads), 0, s, tail, groups);
+    hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kFinalThreads), 0, s, tail, groups);
     st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;
   }
@@ -912,7 +934,7 @@ int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment,
                        tail);
     int st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;
-    hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kThreads), 0, s, tail, groups);
+    hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kFinalThreads), 0, s, tail, groups);
     st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;
   }
