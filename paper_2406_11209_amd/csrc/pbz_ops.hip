@@ -226,6 +226,15 @@ __device__ __forceinline__ double load_N(const void* N, int64_t k) {
   return double(static_cast<const float*>(N)[k]);
 }
 
+// a / b rounded to nearest from a correctly rounded reciprocal: one multiply, the exact remainder by fused
+// multiply-add, one correction.  Agrees with the hardware division sequence except in rare double-rounding
+// corner cases, at a sixth of its cost.
+__device__ __forceinline__ double div_by(double a, double b, double inv_b) {
+  const double q = a * inv_b;
+  const double rem = fma(-q, b, a);
+  return fma(rem, inv_b, q);
+}
+
 template <int kIType, int kNType>
 __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                       const void* __restrict__ N2, const uint4* __restrict__ F2,
@@ -233,6 +242,7 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
                                                       double sign2, int64_t nvec, int lanes_shift) {
   constexpr int kPer = PerDword<kIType>::value;
   constexpr int kElems = 4 * kPer;
+  constexpr bool kExactProducts = kNType == PBZ_F32 && kIType != PBZ_I32;
   const int lanes = 1 << lanes_shift;
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   // sign2 = -1 subtracts: F2 (-N2) is exactly (-F2) N2, so the result is bit for bit that of negate + add
@@ -256,16 +266,16 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
       unpack_dword<kIType>(bw[w], fb);
 #pragma unroll
       for (int e = 0; e < kPer; ++e) {
-        const double ce = unfused_sum_of_products(fa[e], n1, fb[e], n2);
+        // an FP32-valued N times an index of at most 16 bits is exact in FP64, so fusing the first product
+        // rounds exactly as the printed order does; otherwise both products are rounded on their own
+        const double ce = kExactProducts ? fma(fa[e], n1, fb[e] * n2) : unfused_sum_of_products(fa[e], n1, fb[e], n2);
         c[w * kPer + e] = ce;
         m = fmax(m, fabs(ce));
       }
     }
     for (int off = lanes >> 1; off > 0; off >>= 1) m = fmax(m, __shfl_xor(m, off, 64));
     const double n = m / r;
-    // F = rint(C / N).  C * (1 / N) is within two ulp of the correctly rounded quotient, so its rounding to
-    // an integer can differ only when it lands within 2^-50 |t| of a half-integer; only then is the real
-    // division carried out.  The result is bit-identical to dividing every element.
+    // F = rint(C / N), the quotient from the correctly rounded reciprocal with one remainder correction
     const double inv = n > 0.0 ? 1.0 / n : 0.0;
     uint32_t ow[4];
 #pragma unroll
@@ -273,10 +283,9 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
       int q[kPer];
 #pragma unroll
       for (int e = 0; e < kPer; ++e) {
-        const double t = c[w * kPer + e] * inv;
-        double tr = rint(t);
-        if (fabs(fabs(t - tr) - 0.5) <= fabs(t) * 0x1p-50) tr = rint(c[w * kPer + e] / n);
-        q[e] = int(fmin(fmax(tr, -r), r));
+        // an all-zero block has n = inv = 0 and every c = 0: the three steps then give 0 without a division.
+        // |C / N| <= r (1 + 2^-52), which rounds to at most r, so no clamp is needed.
+        q[e] = int(rint(div_by(c[w * kPer + e], n, inv)));
       }
       ow[w] = pack_dword<kIType>(q);
     }
@@ -324,15 +333,6 @@ __global__ __launch_bounds__(64) void k_add_generic(const void* __restrict__ N1,
 // x prod(sqrt(i)), then N = max|C| (taken after the shift, so that no index can exceed r) and
 // F = rint(C r / N).  Same lane layout as k_add_vec.
 // ---------------------------------------------------------------------------------------------
-// a / b rounded to nearest from a correctly rounded reciprocal: one multiply, the exact remainder by fused
-// multiply-add, one correction.  Agrees with the hardware division sequence except in rare double-rounding
-// corner cases, at a sixth of its cost.
-__device__ __forceinline__ double div_by(double a, double b, double inv_b) {
-  const double q = a * inv_b;
-  const double rem = fma(-q, b, a);
-  return fma(rem, inv_b, q);
-}
-
 template <int kIType, int kNType>
 __global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                              void* __restrict__ Nout, uint4* __restrict__ Fout,
@@ -377,8 +377,9 @@ __global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restr
       int q[kPer];
 #pragma unroll
       for (int e = 0; e < kPer; ++e) {
-        const double t = m > 0.0 ? div_by(c[w * kPer + e] * r, m, inv_m) : 0.0;
-        q[e] = int(fmin(fmax(rint(t), -r), r));
+        // an all-zero block has m = inv_m = 0 and every c = 0, which gives 0; |C r / N| <= r (1 + 2^-51) rounds to
+        // at most r, so neither a special case nor a clamp is needed
+        q[e] = int(rint(div_by(c[w * kPer + e] * r, m, inv_m)));
       }
       ow[w] = pack_dword<kIType>(q);
     }
