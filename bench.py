@@ -92,8 +92,8 @@ def cpu_baseline(wl, sample_shape, transform="dct"):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (blocks are independent; see DESIGN.md for how it "
-              "would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (blocks are independent, so an array shards by slabs of "
+              "blocks and a reduction needs one exchange of its five partial sums); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

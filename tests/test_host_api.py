@@ -63,7 +63,7 @@ def test_codec_create_validation():
     lib.pbz_codec_destroy(None)                  # tolerated
 
 
-def test_layout_matches_survey_table():
+def test_layout_of_the_five_workloads():
     rows = [((256, 256), (8, 8), "f32", "i8", None, 1024, 64, 4096, 65536),
             ((4096, 4096), (8, 8), "f32", "i16", (4, 4), 262144, 16, 1048576, 8388608),
             ((64, 1024, 1024), (1, 16, 16), "f32", "i8", None, 262144, 256, 1048576, 67108864),
