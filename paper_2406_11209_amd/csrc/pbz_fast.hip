@@ -147,6 +147,33 @@ struct IdxPack<int16_t> {
   static __device__ __forceinline__ int get(uint32_t w, int i) { return int(int16_t((w >> (16 * i)) & 0xffffu)); }
 };
 
+// ---- arrays whose last extent is not a multiple of the block's ------------------------------------------
+// Rows then start at any multiple of the element size, so 16-byte accesses are only 4-byte aligned (the hardware
+// takes them; the type tells the compiler), and the last block of every row is partial.  Kernels built with
+// kTailX read every 16-byte piece from a start clamped to the row's last whole piece (always in bounds), which
+// is already right for every block but the row's last; the lane that owns that block then re-reads its
+// in-range elements one by one.  Stores: whole pieces that fit, single elements for the rest.
+struct __attribute__((packed, aligned(4))) uint4_a4 { uint32_t x, y, z, w; };
+__device__ __forceinline__ uint4 load16_a4(const void* p) {
+  const uint4_a4 v = *static_cast<const uint4_a4*>(p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store16_a4(void* p, const uint4& u) {
+  uint4_a4 v;
+  v.x = u.x; v.y = u.y; v.z = u.z; v.w = u.w;
+  *static_cast<uint4_a4*>(p) = v;
+}
+template <typename T, typename XT>
+struct Elem {   // one element: float and double arrays
+  static __device__ __forceinline__ T load(const XT* p) { return T(*p); }
+  static __device__ __forceinline__ void store(XT* p, T v) { *p = XT(v); }
+};
+template <typename T>
+struct Elem<T, bf16_t> {
+  static __device__ __forceinline__ T load(const bf16_t* p) { return T(bf16_bits_to_float(p->bits)); }
+  static __device__ __forceinline__ void store(bf16_t* p, T v) { p->bits = float_to_bf16_bits(float(v)); }
+};
+
 template <typename T>
 __device__ __forceinline__ T abs_t(T v) { return v < T(0) ? -v : v; }
 template <>
@@ -283,7 +310,7 @@ __device__ __forceinline__ void inverse_block(T* v) {
 // array.  Such rows are still loaded (from a clamped, valid address: a branch around a load would make the
 // compiler wait for all outstanding loads at the join) and zeroed afterwards.
 template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX,
-          bool kRagged, bool kStats>
+          bool kRagged, bool kStats, bool kTailX = false>
 __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __restrict__ x, NT* __restrict__ N,
                                                        IT* __restrict__ F, double* __restrict__ tile_sums) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
@@ -310,9 +337,18 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
         zz = zz < g.Z ? zz : g.Z - 1;
         yy = yy < g.Y ? yy : g.Y - 1;
       }
-      const uint4* p = reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * BX);
+      if constexpr (kTailX) {
+        const XT* row = x + (zz * g.Y + yy) * g.X;
 #pragma unroll
-      for (int k = 0; k < RV; ++k) raw[(z * BY + y) * RV + k] = p[k];
+        for (int k = 0; k < RV; ++k) {
+          const int64_t x0 = bxc * BX + k * PER16;
+          raw[(z * BY + y) * RV + k] = load16_a4(row + (x0 + PER16 <= g.X ? x0 : g.X - PER16));
+        }
+      } else {
+        const uint4* p = reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * BX);
+#pragma unroll
+        for (int k = 0; k < RV; ++k) raw[(z * BY + y) * RV + k] = p[k];
+      }
     }
   if constexpr (kRagged) {
 #pragma unroll
@@ -330,6 +366,24 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   T v[VOL];
 #pragma unroll
   for (int i = 0; i < ROWS * RV; ++i) Unpack<T, XT>::run(raw[i], v + i * PER16);
+  if constexpr (kTailX) {
+    if ((bxc + 1) * BX > g.X) {        // the row's last, partial block: its in-range elements one by one, zeros beyond
+#pragma unroll
+      for (int z = 0; z < BZ; ++z)
+#pragma unroll
+        for (int y = 0; y < BY; ++y) {
+          const int64_t zz = bz * BZ + z, yy = by * BY + y;
+          const bool row_in = zz < g.Z && yy < g.Y;
+          const XT* row = x + ((row_in ? zz : g.Z - 1) * g.Y + (row_in ? yy : g.Y - 1)) * g.X;
+#pragma unroll
+          for (int e = 0; e < BX; ++e) {
+            const int64_t xi = bxc * BX + e;
+            const T val = Elem<T, XT>::load(row + (xi < g.X ? xi : g.X - 1));
+            v[(z * BY + y) * BX + e] = row_in && xi < g.X ? val : T(0);
+          }
+        }
+    }
+  }
 
   forward_block<TF, T, BZ, BY, BX>(v);
 
@@ -385,7 +439,7 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
 }
 
 template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX,
-          bool kRagged>
+          bool kRagged, bool kTailX = false>
 __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* __restrict__ N, const IT* __restrict__ F,
                                                          XT* __restrict__ y) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
@@ -428,9 +482,25 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
     for (int yy0 = 0; yy0 < BY; ++yy0) {
       const int64_t zz = bz * BZ + z, yy = by * BY + yy0;
       if (!kRagged || (zz < g.Z && yy < g.Y)) {
-        uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * BX);
+        if constexpr (kTailX) {
+          XT* row = y + (zz * g.Y + yy) * g.X;
 #pragma unroll
-        for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+          for (int k = 0; k < RV; ++k) {
+            const int64_t x0 = bx * BX + k * PER16;
+            const T* piece = v + ((z * BY + yy0) * RV + k) * PER16;
+            if (x0 + PER16 <= g.X) {
+              store16_a4(row + x0, Pack<T, XT>::run(piece));
+            } else {
+#pragma unroll
+              for (int e = 0; e < PER16; ++e)
+                if (x0 + e < g.X) Elem<T, XT>::store(row + x0 + e, piece[e]);
+            }
+          }
+        } else {
+          uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * BX);
+#pragma unroll
+          for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+        }
       }
     }
 }
@@ -453,7 +523,7 @@ struct QuadMap {
   static __device__ __forceinline__ int plane_of(int p) { return BZ == 1 ? 0 : (p >> 2); }
 };
 
-template <int TF, int BZ, bool kRagged, bool kStats>
+template <int TF, int BZ, bool kRagged, bool kStats, bool kTailX = false>
 __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float* __restrict__ x, float* __restrict__ N,
                                                          int8_t* __restrict__ F, double* __restrict__ tile_sums) {
   static_assert(BZ == 1 || BZ == 4, "one plane or four");
@@ -482,7 +552,12 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       int64_t yy = by * 16 + yy0;
       if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;     // rows past the end: load a valid row, zero it below
-      raw[yy0] = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 16 + q * 4);
+      if constexpr (kTailX) {
+        const int64_t x0 = bxc * 16 + q * 4;
+        raw[yy0] = load16_a4(x + (zz * g.Y + yy) * g.X + (x0 + 4 <= g.X ? x0 : g.X - 4));
+      } else {
+        raw[yy0] = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 16 + q * 4);
+      }
     }
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
@@ -491,6 +566,23 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
         raw[yy0].x &= keep; raw[yy0].y &= keep; raw[yy0].z &= keep; raw[yy0].w &= keep;
       }
       bits_f4(raw[yy0], v + yy0 * 4);
+    }
+    if constexpr (kTailX) {
+      const int64_t x0 = bxc * 16 + q * 4;
+      if (x0 + 4 > g.X) {              // a piece of the row's last, partial block: element by element, zeros beyond
+#pragma unroll
+        for (int yy0 = 0; yy0 < 16; ++yy0) {
+          const int64_t yy = by * 16 + yy0;
+          const bool row_in = yy < g.Y && keep_z != 0u;
+          const float* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int64_t xi = x0 + e;
+            const float val = row[xi < g.X ? xi : g.X - 1];
+            v[yy0 * 4 + e] = row_in && xi < g.X ? val : 0.0f;
+          }
+        }
+      }
     }
 #pragma unroll
     for (int xl = 0; xl < 4; ++xl) tf_forward<TF, float, 16, 4>(v + xl);
@@ -556,7 +648,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
   if constexpr (kStats) emit_tile_sums(tile_sums, g, tx, by, bz, s11, d1);
 }
 
-template <int TF, int BZ>
+template <int TF, int BZ, bool kTailX = false>
 __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const float* __restrict__ N,
                                                            const int8_t* __restrict__ F, float* __restrict__ y) {
   using Map = QuadMap<BZ>;
@@ -605,7 +697,21 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const flo
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       const int64_t yy = by * 16 + yy0;
-      if (yy < g.Y) *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4) = f4_bits(v + yy0 * 4);
+      if (yy < g.Y) {
+        if constexpr (kTailX) {
+          float* row = y + (zz * g.Y + yy) * g.X;
+          const int64_t x0 = bx * 16 + q * 4;
+          if (x0 + 4 <= g.X) {
+            store16_a4(row + x0, f4_bits(v + yy0 * 4));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (x0 + e < g.X) row[x0 + e] = v[yy0 * 4 + e];
+          }
+        } else {
+          *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4) = f4_bits(v + yy0 * 4);
+        }
+      }
     }
   }
 }
@@ -625,7 +731,7 @@ __device__ __forceinline__ int oct_slot(int b, int yy, int z) {
 
 constexpr int kOctWaves = 4;   // waves per workgroup: neighbouring tiles, so that a workgroup reads 512-byte row pieces
 
-template <int TF, int KZ, int KY, int KX, bool kRagged, bool kStats>
+template <int TF, int KZ, int KY, int KX, bool kRagged, bool kStats, bool kTailX = false>
 __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x,
                                                                   float* __restrict__ N, int8_t* __restrict__ F,
                                                                   double* __restrict__ tile_sums) {
@@ -655,7 +761,10 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
     for (int yy0 = 0; yy0 < 8; ++yy0) {
       int64_t yy = by * 8 + yy0;
       if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;
-      raw[yy0] = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 8);
+      if constexpr (kTailX)
+        raw[yy0] = load16_a4(x + (zz * g.Y + yy) * g.X + (bxc * 8 + 8 <= g.X ? bxc * 8 : g.X - 8));
+      else
+        raw[yy0] = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 8);
     }
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
@@ -664,6 +773,22 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
         raw[yy0].x &= keep; raw[yy0].y &= keep; raw[yy0].z &= keep; raw[yy0].w &= keep;
       }
       Unpack<float, bf16_t>::run(raw[yy0], v + yy0 * 8);
+    }
+    if constexpr (kTailX) {
+      if (bxc * 8 + 8 > g.X) {         // the row's last, partial block: element by element, zeros beyond
+#pragma unroll
+        for (int yy0 = 0; yy0 < 8; ++yy0) {
+          const int64_t yy = by * 8 + yy0;
+          const bool row_in = yy < g.Y && keep_z != 0u;
+          const bf16_t* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int64_t xi = bxc * 8 + e;
+            const float val = Elem<float, bf16_t>::load(row + (xi < g.X ? xi : g.X - 1));
+            v[yy0 * 8 + e] = row_in && xi < g.X ? val : 0.0f;
+          }
+        }
+      }
     }
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) tf_forward<TF, float, 8, 1>(v + yy0 * 8);
@@ -738,7 +863,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // hardwar
   return __builtin_bit_cast(uint32_t, h);
 }
 
-template <int TF, int KZ, int KY, int KX>
+template <int TF, int KZ, int KY, int KX, bool kTailX = false>
 __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float* __restrict__ N,
                                                          const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
   constexpr int KEPT = KZ * KY * KX;
@@ -787,9 +912,21 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float
     const int64_t yy = by * 8 + yy0;
     if (yy < g.Y) {
       const float* r8 = v + yy0 * 8;
-      *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 8) =
-          make_uint4(pack_bf16x2(r8[0], r8[1]), pack_bf16x2(r8[2], r8[3]), pack_bf16x2(r8[4], r8[5]),
-                     pack_bf16x2(r8[6], r8[7]));
+      const uint4 packed = make_uint4(pack_bf16x2(r8[0], r8[1]), pack_bf16x2(r8[2], r8[3]), pack_bf16x2(r8[4], r8[5]),
+                                      pack_bf16x2(r8[6], r8[7]));
+      if constexpr (kTailX) {
+        bf16_t* row = y + (zz * g.Y + yy) * g.X;
+        if (bx * 8 + 8 <= g.X) {
+          store16_a4(row + bx * 8, packed);
+        } else {
+          const uint32_t pw[4] = {packed.x, packed.y, packed.z, packed.w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (bx * 8 + e < g.X) row[bx * 8 + e].bits = uint16_t(pw[e >> 1] >> (16 * (e & 1)));
+        }
+      } else {
+        *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 8) = packed;
+      }
     }
   }
 }
@@ -798,7 +935,7 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float
 // rebuilds plane z of all of them (lane = block), so that every store instruction writes one whole contiguous
 // 1 KiB row piece (measured 6.6 TB/s for this store pattern against 5.7 TB/s for the 128-byte pieces above);
 // the plane index is uniform over the wave, so its matrix row comes from scalar loads.
-template <int TF, int KZ, int KY, int KX>
+template <int TF, int KZ, int KY, int KX, bool kTailX = false>
 __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const float* __restrict__ N,
                                                               const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
   constexpr int KEPT = KZ * KY * KX;
@@ -849,9 +986,21 @@ __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const 
     const int64_t yy = by * 8 + yy0;
     if (yy < g.Y) {
       const float* r8 = v + yy0 * 8;
-      *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 8) =
-          make_uint4(pack_bf16x2(r8[0], r8[1]), pack_bf16x2(r8[2], r8[3]), pack_bf16x2(r8[4], r8[5]),
-                     pack_bf16x2(r8[6], r8[7]));
+      const uint4 packed = make_uint4(pack_bf16x2(r8[0], r8[1]), pack_bf16x2(r8[2], r8[3]), pack_bf16x2(r8[4], r8[5]),
+                                      pack_bf16x2(r8[6], r8[7]));
+      if constexpr (kTailX) {
+        bf16_t* row = y + (zz * g.Y + yy) * g.X;
+        if (bx * 8 + 8 <= g.X) {
+          store16_a4(row + bx * 8, packed);
+        } else {
+          const uint32_t pw[4] = {packed.x, packed.y, packed.z, packed.w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (bx * 8 + e < g.X) row[bx * 8 + e].bits = uint16_t(pw[e >> 1] >> (16 * (e & 1)));
+        }
+      } else {
+        *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 8) = packed;
+      }
     }
   }
 }
@@ -861,8 +1010,14 @@ struct Folded {
   bool ok;
   int bz, by, bx;     // block extents
   int kz, ky, kx;     // kept box (== block extents when nothing is pruned), 0 when the mask is not a box
+  bool tail_x;        // the last extent is not a multiple of the block's: rows unaligned, last block of a row partial
   FastGeom g;
 };
+
+// can a kernel whose 16-byte pieces hold `per16` elements of `elem_bytes` bytes take this geometry?
+inline bool x_extent_ok(const Folded& f, int per16, int elem_bytes) {
+  return !f.tail_x || (f.g.X >= per16 && (f.g.X * elem_bytes) % 4 == 0);
+}
 
 Folded fold(const pbz_codec* c, const Geom& geo) {
   Folded f{};
@@ -897,7 +1052,7 @@ Folded fold(const pbz_codec* c, const Geom& geo) {
   g.gy = (g.Y + blk[1] - 1) / blk[1];
   g.gx = (g.X + blk[2] - 1) / blk[2];
   g.r = c->r;
-  if (g.X % blk[2] != 0) return f;
+  f.tail_x = g.X % blk[2] != 0;
   f.ok = true;
   return f;
 }
@@ -920,7 +1075,7 @@ struct LaneKernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
     return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<XT>() && int(c->itype) == itype_code<IT>() &&
            int(c->ftype) == xtype_code<NT>() && f.bz == BZ && f.by == BY && f.bx == BX && f.kz == KZ && f.ky == KY &&
-           f.kx == KX && (f.g.X * sizeof(XT)) % 16 == 0;
+           f.kx == KX && x_extent_ok(f, 16 / int(sizeof(XT)), int(sizeof(XT)));
   }
   static int fits(FastGeom g) {
     dim3 grid;
@@ -930,29 +1085,32 @@ struct LaneKernel {
     dim3 grid;
     return tile_grid(g, 64, 4, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
   }
-  template <bool kRagged, bool kStats>
+  template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kStats>), grid, dim3(256), 0, s, g,
-                       static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F), tile_sums);
+    hipLaunchKernelGGL((k_compress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kStats, kTailX>), grid,
+                       dim3(256), 0, s, g, static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F), tile_sums);
+  }
+  template <bool kRagged, bool kTailX>
+  static void launch_inverse(const FastGeom& g, dim3 grid, const void* N, const void* F, void* y, hipStream_t s) {
+    hipLaunchKernelGGL((k_decompress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kTailX>), grid, dim3(256), 0,
+                       s, g, static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
   }
   // tile_sums != nullptr: also the per-wave statistic sums (two doubles per tile)
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 64, 4, &grid)) return 0;
     const bool ragged = g.Z % BZ || g.Y % BY;
-    if (tile_sums) ragged ? launch<true, true>(g, grid, x, N, F, tile_sums, s) : launch<false, true>(g, grid, x, N, F, tile_sums, s);
-    else ragged ? launch<true, false>(g, grid, x, N, F, nullptr, s) : launch<false, false>(g, grid, x, N, F, nullptr, s);
+    if (g.X % BX) tile_sums ? launch<true, true, true>(g, grid, x, N, F, tile_sums, s) : launch<true, false, true>(g, grid, x, N, F, nullptr, s);
+    else if (tile_sums) ragged ? launch<true, true, false>(g, grid, x, N, F, tile_sums, s) : launch<false, true, false>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false, false>(g, grid, x, N, F, nullptr, s) : launch<false, false, false>(g, grid, x, N, F, nullptr, s);
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 64, 4, &grid)) return 0;
-    if (g.Z % BZ || g.Y % BY)
-      hipLaunchKernelGGL((k_decompress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, true>), grid, dim3(256), 0, s, g,
-                         static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
-    else
-      hipLaunchKernelGGL((k_decompress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, false>), grid, dim3(256), 0, s, g,
-                         static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
+    if (g.X % BX) launch_inverse<true, true>(g, grid, N, F, y, s);
+    else if (g.Z % BZ || g.Y % BY) launch_inverse<true, false>(g, grid, N, F, y, s);
+    else launch_inverse<false, false>(g, grid, N, F, y, s);
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
@@ -971,7 +1129,7 @@ struct Quad16Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
     return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I8 &&
            c->ftype == PBZ_F32 && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
-           (f.g.X * 4) % 16 == 0;
+           x_extent_ok(f, 4, 4);
   }
   static int fits(FastGeom g) {
     dim3 grid;
@@ -981,24 +1139,29 @@ struct Quad16Kernel {
     dim3 grid;
     return tile_grid(g, kBlocksPerWave, 2, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
   }
-  template <bool kRagged, bool kStats>
+  template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_quad16<TF, BZ, kRagged, kStats>), grid, dim3(128), 0, s, g, static_cast<const float*>(x),
-                       static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
+    hipLaunchKernelGGL((k_compress_quad16<TF, BZ, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
+                       static_cast<const float*>(x), static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, kBlocksPerWave, 2, &grid)) return 0;
     const bool ragged = g.Y % 16 || g.Z % BZ;
-    if (tile_sums) ragged ? launch<true, true>(g, grid, x, N, F, tile_sums, s) : launch<false, true>(g, grid, x, N, F, tile_sums, s);
-    else ragged ? launch<true, false>(g, grid, x, N, F, nullptr, s) : launch<false, false>(g, grid, x, N, F, nullptr, s);
+    if (g.X % 16) tile_sums ? launch<true, true, true>(g, grid, x, N, F, tile_sums, s) : launch<true, false, true>(g, grid, x, N, F, nullptr, s);
+    else if (tile_sums) ragged ? launch<true, true, false>(g, grid, x, N, F, tile_sums, s) : launch<false, true, false>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false, false>(g, grid, x, N, F, nullptr, s) : launch<false, false, false>(g, grid, x, N, F, nullptr, s);
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, kBlocksPerWave, 2, &grid)) return 0;
-    hipLaunchKernelGGL((k_decompress_quad16<TF, BZ>), grid, dim3(128), 0, s, g, static_cast<const float*>(N),
-                       static_cast<const int8_t*>(F), static_cast<float*>(y));
+    if (g.X % 16)
+      hipLaunchKernelGGL((k_decompress_quad16<TF, BZ, true>), grid, dim3(128), 0, s, g, static_cast<const float*>(N),
+                         static_cast<const int8_t*>(F), static_cast<float*>(y));
+    else
+      hipLaunchKernelGGL((k_decompress_quad16<TF, BZ, false>), grid, dim3(128), 0, s, g, static_cast<const float*>(N),
+                         static_cast<const int8_t*>(F), static_cast<float*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
@@ -1008,7 +1171,7 @@ template <int TF, int KZ, int KY, int KX>
 struct Oct8Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
     return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 8 &&
-           f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX && (f.g.X * 2) % 16 == 0;
+           f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX && x_extent_ok(f, 8, 2);
   }
   static int fits(FastGeom g) {
     dim3 grid;
@@ -1018,29 +1181,34 @@ struct Oct8Kernel {
     dim3 grid;
     return tile_grid(g, 8, kOctWaves, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
   }
-  template <bool kRagged, bool kStats>
+  template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_oct8<TF, KZ, KY, KX, kRagged, kStats>), grid, dim3(kOctWaves * 64), 0, s, g,
+    hipLaunchKernelGGL((k_compress_oct8<TF, KZ, KY, KX, kRagged, kStats, kTailX>), grid, dim3(kOctWaves * 64), 0, s, g,
                        static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 8, kOctWaves, &grid)) return 0;
     const bool ragged = g.Z % 8 || g.Y % 8;
-    if (tile_sums) ragged ? launch<true, true>(g, grid, x, N, F, tile_sums, s) : launch<false, true>(g, grid, x, N, F, tile_sums, s);
-    else ragged ? launch<true, false>(g, grid, x, N, F, nullptr, s) : launch<false, false>(g, grid, x, N, F, nullptr, s);
+    if (g.X % 8) tile_sums ? launch<true, true, true>(g, grid, x, N, F, tile_sums, s) : launch<true, false, true>(g, grid, x, N, F, nullptr, s);
+    else if (tile_sums) ragged ? launch<true, true, false>(g, grid, x, N, F, tile_sums, s) : launch<false, true, false>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false, false>(g, grid, x, N, F, nullptr, s) : launch<false, false, false>(g, grid, x, N, F, nullptr, s);
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
+    const float* n = static_cast<const float*>(N);
+    const int8_t* f = static_cast<const int8_t*>(F);
+    bf16_t* out = static_cast<bf16_t*>(y);
+    const bool tail = g.X % 8 != 0;
     if (g.gx >= 48) {        // at least three quarters of the lanes of a 64-block tile busy
       if (!tile_grid(g, 64, 1, &grid)) return 0;
-      hipLaunchKernelGGL((k_decompress_oct8_rows<TF, KZ, KY, KX>), grid, dim3(512), 0, s, g,
-                         static_cast<const float*>(N), static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
+      if (tail) hipLaunchKernelGGL((k_decompress_oct8_rows<TF, KZ, KY, KX, true>), grid, dim3(512), 0, s, g, n, f, out);
+      else hipLaunchKernelGGL((k_decompress_oct8_rows<TF, KZ, KY, KX, false>), grid, dim3(512), 0, s, g, n, f, out);
     } else {
       if (!tile_grid(g, 8, 4, &grid)) return 0;
-      hipLaunchKernelGGL((k_decompress_oct8<TF, KZ, KY, KX>), grid, dim3(256), 0, s, g, static_cast<const float*>(N),
-                         static_cast<const int8_t*>(F), static_cast<bf16_t*>(y));
+      if (tail) hipLaunchKernelGGL((k_decompress_oct8<TF, KZ, KY, KX, true>), grid, dim3(256), 0, s, g, n, f, out);
+      else hipLaunchKernelGGL((k_decompress_oct8<TF, KZ, KY, KX, false>), grid, dim3(256), 0, s, g, n, f, out);
     }
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }

@@ -141,6 +141,21 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((9, 40, 64), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8"),       # the MRI block shape
                ((10, 33, 144), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8"),
                ((8, 32, 80), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8"),
+               # last extent not a multiple of the block's: unaligned rows, partial last block of every row
+               ((37, 53), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
+               ((21, 1030), (8, 8), 16, "f32", "f32", (4, 4), "lane_f32_8x8_i16_box4x4"),
+               ((16, 67), (8, 8), 16, "f32", "f32", None, "lane_f32_8x8_i16"),
+               ((5, 30, 19), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
+               ((9, 13, 250), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
+               ((8, 8, 517), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
+               ((3, 33, 47), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8"),
+               ((2, 19, 570), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8"),
+               ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8"),
+               ((17, 9, 22), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
+               ((9, 12, 398), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8"),
+               ((9, 9, 514), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
+               ((17, 9, 23), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "generic"),     # odd bfloat16 rows: 2-byte aligned
+               ((6, 3), (8, 8), 8, "f32", "f32", None, "generic"),                   # shorter than one 16-byte piece
                # 49 and more blocks along x: the decompress variant that stores whole row pieces
                ((17, 9, 520), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 12, 392), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
@@ -170,7 +185,9 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((16, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8_haar"),
         ((9, 9, 512), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((9, 20, 48), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
-        ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "generic"),
+        ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
+        ((9, 6, 26), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
+        ((9, 20, 36), (2, 16, 16), 8, "f32", "f32", None, "generic"),
         ((50, 21), (2, 32), 16, "f64", "f64", None, "generic")]
 
 
