@@ -34,6 +34,7 @@ struct FastGeom {
   int64_t gz, gy, gx;     // block grid
   uint32_t tiles_x;       // waves needed to cover the gx blocks of one block row
   uint32_t tiles_yx;      // gy * tiles_x: waves per z-slab of blocks
+  int ntype;              // storage type of N (pbz_ftype): FP64, or FP32 / bfloat16 / FP16 for the kernels computing below FP64 width of N
   double r;
 };
 
@@ -189,6 +190,40 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// ---- N in its storage type ---------------------------------------------------------------------------------
+// N is written through store_float (one rounding from the compute type).  The value a later reader gets back:
+template <typename T>
+__device__ __forceinline__ double stored_N(T m, int ntype) {
+  switch (ntype) {
+    case PBZ_F64: return double(m);
+    case PBZ_F32: return double(float(m));
+    case PBZ_BF16: return double(bf16_bits_to_float(sizeof(T) == 8 ? double_to_bf16_bits(double(m)) : float_to_bf16_bits(float(m))));
+    default: return double(float(sizeof(T) == 8 ? double_to_f16(double(m)) : _Float16(float(m))));
+  }
+}
+// kCount values of N at once: one switch around all the loads, so that they are in flight together
+template <int kCount>
+__device__ __forceinline__ void load_N_many(const void* N, int ntype, const int64_t* idx, float* out) {
+  switch (ntype) {
+    case PBZ_F32:
+#pragma unroll
+      for (int i = 0; i < kCount; ++i) out[i] = static_cast<const float*>(N)[idx[i]];
+      break;
+    case PBZ_BF16:
+#pragma unroll
+      for (int i = 0; i < kCount; ++i) out[i] = bf16_bits_to_float(static_cast<const uint16_t*>(N)[idx[i]]);
+      break;
+    case PBZ_F16:
+#pragma unroll
+      for (int i = 0; i < kCount; ++i) out[i] = float(static_cast<const _Float16*>(N)[idx[i]]);
+      break;
+    default:
+#pragma unroll
+      for (int i = 0; i < kCount; ++i) out[i] = float(static_cast<const double*>(N)[idx[i]]);
+      break;
+  }
+}
+
 // ---- statistics emitted while compressing ---------------------------------------------------------------
 // With kStats a compress kernel also leaves, per wave, the two sums that the mean (Algorithm 7), the variance
 // (Algorithm 9) and the L2 norm (Algorithm 10) of the array it has just compressed are made of:
@@ -311,7 +346,7 @@ __device__ __forceinline__ void inverse_block(T* v) {
 // compiler wait for all outstanding loads at the join) and zeroed afterwards.
 template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX,
           bool kRagged, bool kStats, bool kTailX = false>
-__global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __restrict__ x, NT* __restrict__ N,
+__global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __restrict__ x, void* __restrict__ N,
                                                        IT* __restrict__ F, double* __restrict__ tile_sums) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
   constexpr int RV = BX * int(sizeof(XT)) / 16;       // 16-byte loads per block row
@@ -406,9 +441,9 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
     w[kw] = IdxPack<IT>::pack(q);
   }
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 64;   // first block of this wave
-  if (active) N[block0 + lane] = NT(m);
+  if (active) store_float(N, g.ntype, block0 + lane, m);
   if constexpr (kStats) {
-    const double n = active ? double(NT(m)) : 0.0;
+    const double n = active ? stored_N(m, g.ntype) : 0.0;
     emit_tile_sums(tile_sums, g, tx, by, bz, sum_of_squares<IT, KW>(w) * (n * n), n * double(IdxPack<IT>::get(w[0], 0)));
   }
   constexpr int P = KW / 4;                                   // 16-byte pieces of F per block
@@ -440,7 +475,7 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
 
 template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX,
           bool kRagged, bool kTailX = false>
-__global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* __restrict__ N, const IT* __restrict__ F,
+__global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void* __restrict__ N, const IT* __restrict__ F,
                                                          XT* __restrict__ y) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
   constexpr int RV = BX * int(sizeof(XT)) / 16;
@@ -463,7 +498,7 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const NT* _
     const uint4 u = src[k];
     w[4 * k] = u.x; w[4 * k + 1] = u.y; w[4 * k + 2] = u.z; w[4 * k + 3] = u.w;
   }
-  const T scale = T(N[block]) / T(g.r);          // Algorithm 3: N F / r, the division hoisted per block
+  const T scale = load_float<T>(N, g.ntype, block) / T(g.r);          // Algorithm 3: N F / r, the division hoisted per block
 
   T v[VOL];
 #pragma unroll
@@ -524,7 +559,7 @@ struct QuadMap {
 };
 
 template <int TF, int BZ, bool kRagged, bool kStats, bool kTailX = false>
-__global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float* __restrict__ x, float* __restrict__ N,
+__global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float* __restrict__ x, void* __restrict__ N,
                                                          int8_t* __restrict__ F, double* __restrict__ tile_sums) {
   static_assert(BZ == 1 || BZ == 4, "one plane or four");
   using Map = QuadMap<BZ>;
@@ -637,9 +672,9 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
       const int piece = BZ == 1 ? yrow : j * 16 + yrow;
       reinterpret_cast<uint4*>(F + (block0 + blk) * (BZ * 256))[piece] = make_uint4(w[0], w[1], w[2], w[3]);
       const bool first = yrow == 0 && (BZ == 1 || j == 0);
-      if (first) N[block0 + blk] = m;
+      if (first) store_float(N, g.ntype, block0 + blk, m);
       if constexpr (kStats) {
-        const double n = double(m);
+        const double n = stored_N(m, g.ntype);
         s11 += sum_of_squares<int8_t, 4>(w) * (n * n);
         if (first) d1 += n * double(IdxPack<int8_t>::get(w[0], 0));
       }
@@ -649,7 +684,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
 }
 
 template <int TF, int BZ, bool kTailX = false>
-__global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const float* __restrict__ N,
+__global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const void* __restrict__ N,
                                                            const int8_t* __restrict__ F, float* __restrict__ y) {
   using Map = QuadMap<BZ>;
   constexpr int BPW = Map::kBlocksPerWave;
@@ -662,13 +697,22 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const flo
   {
     const int yrow = lane & 15, bsub = lane >> 4;
     float u[64];
+    int64_t blocks[4];
+    uint4 fs[4];
+    float ns[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int64_t blk = Map::block_of(4 * j + bsub);
       if (tx * BPW + blk >= g.gx) blk = g.gx - 1 - tx * BPW;   // past the end: decode the last block again, stored nowhere
+      blocks[j] = block0 + blk;
       const int piece = BZ == 1 ? yrow : j * 16 + yrow;
-      const uint4 f = reinterpret_cast<const uint4*>(F + (block0 + blk) * (BZ * 256))[piece];
-      const float scale = N[block0 + blk] / float(g.r);
+      fs[j] = reinterpret_cast<const uint4*>(F + blocks[j] * (BZ * 256))[piece];
+    }
+    load_N_many<4>(N, g.ntype, blocks, ns);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint4 f = fs[j];
+      const float scale = ns[j] / float(g.r);
       const uint32_t w[4] = {f.x, f.y, f.z, f.w};
 #pragma unroll
       for (int i = 0; i < 16; ++i) u[j * 16 + i] = scale * float(IdxPack<int8_t>::get(w[i >> 2], i & 3));
@@ -733,7 +777,7 @@ constexpr int kOctWaves = 4;   // waves per workgroup: neighbouring tiles, so th
 
 template <int TF, int KZ, int KY, int KX, bool kRagged, bool kStats, bool kTailX = false>
 __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x,
-                                                                  float* __restrict__ N, int8_t* __restrict__ F,
+                                                                  void* __restrict__ N, int8_t* __restrict__ F,
                                                                   double* __restrict__ tile_sums) {
   static_assert(KX == 4 || KX == 8, "a kept row is one or two dwords of int8");
   constexpr int KEPT = KZ * KY * KX;
@@ -838,7 +882,7 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
       }
   }
   if constexpr (kStats) {
-    const double n = tx * 8 + bb < g.gx ? double(m) : 0.0;
+    const double n = tx * 8 + bb < g.gx ? stored_N(m, g.ntype) : 0.0;
     emit_tile_sums(tile_sums, g, tx, by, bz, double(squares) * (n * n),
                    j == 0 ? n * double(IdxPack<int8_t>::get(first, 0)) : 0.0);
   }
@@ -852,7 +896,7 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
     const int p = p0 + lane;
     if (p < PIECES && tx * 8 + p / PPB < g.gx) reinterpret_cast<uint4*>(F + block0 * KEPT)[p] = st[p];
   }
-  if (j == 0 && tx * 8 + bb < g.gx) N[block0 + bb] = m;
+  if (j == 0 && tx * 8 + bb < g.gx) store_float(N, g.ntype, block0 + bb, m);
 }
 
 typedef float float2v __attribute__((ext_vector_type(2)));
@@ -864,7 +908,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // hardwar
 }
 
 template <int TF, int KZ, int KY, int KX, bool kTailX = false>
-__global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float* __restrict__ N,
+__global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const void* __restrict__ N,
                                                          const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
   constexpr int KEPT = KZ * KY * KX;
   static_assert(KEPT % 16 == 0, "F blocks are whole 16-byte vectors");
@@ -884,7 +928,7 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float
     w[4 * k] = f.x; w[4 * k + 1] = f.y; w[4 * k + 2] = f.z; w[4 * k + 3] = f.w;
   }
   // this lane's plane z of the inverse z transform: sum_q (N / r) H[z][q] C[q][.][.]
-  const float scale = N[block] / float(g.r);
+  const float scale = load_float<float>(N, g.ntype, block) / float(g.r);
   float hz[KZ];
 #pragma unroll
   for (int q = 0; q < KZ; ++q) hz[q] = scale * (TF == kTfHaar ? c_haar8.h[z][q] : c_dct8.h[z][q]);
@@ -936,7 +980,7 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const float
 // 1 KiB row piece (measured 6.6 TB/s for this store pattern against 5.7 TB/s for the 128-byte pieces above);
 // the plane index is uniform over the wave, so its matrix row comes from scalar loads.
 template <int TF, int KZ, int KY, int KX, bool kTailX = false>
-__global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const float* __restrict__ N,
+__global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const void* __restrict__ N,
                                                               const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
   constexpr int KEPT = KZ * KY * KX;
   static_assert(KEPT % 16 == 0, "F blocks are whole 16-byte vectors");
@@ -958,7 +1002,7 @@ __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const 
     w[4 * k] = f.x; w[4 * k + 1] = f.y; w[4 * k + 2] = f.z; w[4 * k + 3] = f.w;
   }
   // this lane's plane z of the inverse z transform: sum_q (N / r) H[z][q] C[q][.][.]
-  const float scale = N[block] / float(g.r);
+  const float scale = load_float<float>(N, g.ntype, block) / float(g.r);
   float hz[KZ];
 #pragma unroll
   for (int q = 0; q < KZ; ++q) hz[q] = scale * (TF == kTfHaar ? c_haar8.h[z][q] : c_dct8.h[z][q]);
@@ -1014,6 +1058,10 @@ struct Folded {
   FastGeom g;
 };
 
+// NT = double: N is FP64; NT = float: N is FP32 or one of the 16-bit types (the kernels convert on load / store)
+template <typename NT>
+inline bool n_type_ok(int ftype) { return sizeof(NT) == 8 ? ftype == PBZ_F64 : ftype != PBZ_F64; }
+
 // can a kernel whose 16-byte pieces hold `per16` elements of `elem_bytes` bytes take this geometry?
 inline bool x_extent_ok(const Folded& f, int per16, int elem_bytes) {
   return !f.tail_x || (f.g.X >= per16 && (f.g.X * elem_bytes) % 4 == 0);
@@ -1052,6 +1100,7 @@ Folded fold(const pbz_codec* c, const Geom& geo) {
   g.gy = (g.Y + blk[1] - 1) / blk[1];
   g.gx = (g.X + blk[2] - 1) / blk[2];
   g.r = c->r;
+  g.ntype = int(c->ftype);
   f.tail_x = g.X % blk[2] != 0;
   f.ok = true;
   return f;
@@ -1074,7 +1123,7 @@ template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int
 struct LaneKernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
     return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<XT>() && int(c->itype) == itype_code<IT>() &&
-           int(c->ftype) == xtype_code<NT>() && f.bz == BZ && f.by == BY && f.bx == BX && f.kz == KZ && f.ky == KY &&
+           n_type_ok<NT>(int(c->ftype)) && f.bz == BZ && f.by == BY && f.bx == BX && f.kz == KZ && f.ky == KY &&
            f.kx == KX && x_extent_ok(f, 16 / int(sizeof(XT)), int(sizeof(XT)));
   }
   static int fits(FastGeom g) {
@@ -1088,12 +1137,12 @@ struct LaneKernel {
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     hipLaunchKernelGGL((k_compress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kStats, kTailX>), grid,
-                       dim3(256), 0, s, g, static_cast<const XT*>(x), static_cast<NT*>(N), static_cast<IT*>(F), tile_sums);
+                       dim3(256), 0, s, g, static_cast<const XT*>(x), N, static_cast<IT*>(F), tile_sums);
   }
   template <bool kRagged, bool kTailX>
   static void launch_inverse(const FastGeom& g, dim3 grid, const void* N, const void* F, void* y, hipStream_t s) {
     hipLaunchKernelGGL((k_decompress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kTailX>), grid, dim3(256), 0,
-                       s, g, static_cast<const NT*>(N), static_cast<const IT*>(F), static_cast<XT*>(y));
+                       s, g, N, static_cast<const IT*>(F), static_cast<XT*>(y));
   }
   // tile_sums != nullptr: also the per-wave statistic sums (two doubles per tile)
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
@@ -1128,7 +1177,7 @@ struct Quad16Kernel {
   static constexpr int kBlocksPerWave = BZ == 1 ? 16 : 4;
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
     return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I8 &&
-           c->ftype == PBZ_F32 && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
+           c->ftype != PBZ_F64 && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
            x_extent_ok(f, 4, 4);
   }
   static int fits(FastGeom g) {
@@ -1142,7 +1191,7 @@ struct Quad16Kernel {
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     hipLaunchKernelGGL((k_compress_quad16<TF, BZ, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
-                       static_cast<const float*>(x), static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
+                       static_cast<const float*>(x), N, static_cast<int8_t*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
@@ -1157,10 +1206,10 @@ struct Quad16Kernel {
     dim3 grid;
     if (!tile_grid(g, kBlocksPerWave, 2, &grid)) return 0;
     if (g.X % 16)
-      hipLaunchKernelGGL((k_decompress_quad16<TF, BZ, true>), grid, dim3(128), 0, s, g, static_cast<const float*>(N),
+      hipLaunchKernelGGL((k_decompress_quad16<TF, BZ, true>), grid, dim3(128), 0, s, g, N,
                          static_cast<const int8_t*>(F), static_cast<float*>(y));
     else
-      hipLaunchKernelGGL((k_decompress_quad16<TF, BZ, false>), grid, dim3(128), 0, s, g, static_cast<const float*>(N),
+      hipLaunchKernelGGL((k_decompress_quad16<TF, BZ, false>), grid, dim3(128), 0, s, g, N,
                          static_cast<const int8_t*>(F), static_cast<float*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
@@ -1170,7 +1219,7 @@ struct Quad16Kernel {
 template <int TF, int KZ, int KY, int KX>
 struct Oct8Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype == PBZ_F32 && f.bz == 8 &&
+    return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype != PBZ_F64 && f.bz == 8 &&
            f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX && x_extent_ok(f, 8, 2);
   }
   static int fits(FastGeom g) {
@@ -1184,7 +1233,7 @@ struct Oct8Kernel {
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     hipLaunchKernelGGL((k_compress_oct8<TF, KZ, KY, KX, kRagged, kStats, kTailX>), grid, dim3(kOctWaves * 64), 0, s, g,
-                       static_cast<const bf16_t*>(x), static_cast<float*>(N), static_cast<int8_t*>(F), tile_sums);
+                       static_cast<const bf16_t*>(x), N, static_cast<int8_t*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
@@ -1197,7 +1246,7 @@ struct Oct8Kernel {
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
-    const float* n = static_cast<const float*>(N);
+    const void* n = N;
     const int8_t* f = static_cast<const int8_t*>(F);
     bf16_t* out = static_cast<bf16_t*>(y);
     const bool tail = g.X % 8 != 0;

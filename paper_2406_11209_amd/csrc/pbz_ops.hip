@@ -220,10 +220,33 @@ __global__ __launch_bounds__(kThreads) void k_scale_N(const void* __restrict__ i
 // C = F1 N1 + F2 N2 (each product and the sum rounded separately), N = max|C| / r, F = rint(C / N).
 // A block occupies kLanes consecutive lanes, 16 bytes of F per lane.
 // ---------------------------------------------------------------------------------------------
+// N comes in three widths: kNType = PBZ_F64, PBZ_F32, or kN16 for the two 16-bit types, which share a kernel:
+// the 16-bit load is the same, both decodings are computed and `f16` (uniform) selects one, so that no branch
+// surrounds a load.
+constexpr int kN16 = PBZ_BF16;
+constexpr int n_kernel_type(int ftype) { return ftype == PBZ_F64 ? PBZ_F64 : (ftype == PBZ_F32 ? PBZ_F32 : kN16); }
+
 template <int kNType>
-__device__ __forceinline__ double load_N(const void* N, int64_t k) {
+__device__ __forceinline__ double load_N(const void* N, int64_t k, bool f16 = false) {
   if (kNType == PBZ_F64) return static_cast<const double*>(N)[k];
-  return double(static_cast<const float*>(N)[k]);
+  if (kNType == PBZ_F32) return double(static_cast<const float*>(N)[k]);
+  const uint16_t h = static_cast<const uint16_t*>(N)[k];
+  const float as_bf16 = bf16_bits_to_float(h);
+  const float as_f16 = float(__builtin_bit_cast(_Float16, h));
+  return double(f16 ? as_f16 : as_bf16);
+}
+
+template <int kNType>
+__device__ __forceinline__ void store_N(void* N, int64_t k, double v, bool f16 = false) {
+  if (kNType == PBZ_F64) {
+    static_cast<double*>(N)[k] = v;
+  } else if (kNType == PBZ_F32) {
+    static_cast<float*>(N)[k] = float(v);
+  } else {
+    const uint16_t as_bf16 = double_to_bf16_bits(v);
+    const uint16_t as_f16 = __builtin_bit_cast(uint16_t, double_to_f16(v));
+    static_cast<uint16_t*>(N)[k] = f16 ? as_f16 : as_bf16;
+  }
 }
 
 // a / b rounded to nearest from a correctly rounded reciprocal: one multiply, the exact remainder by fused
@@ -239,10 +262,10 @@ template <int kIType, int kNType>
 __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                       const void* __restrict__ N2, const uint4* __restrict__ F2,
                                                       void* __restrict__ Nout, uint4* __restrict__ Fout, double r,
-                                                      double sign2, int64_t nvec, int lanes_shift) {
+                                                      double sign2, int64_t nvec, int lanes_shift, int n_f16) {
   constexpr int kPer = PerDword<kIType>::value;
   constexpr int kElems = 4 * kPer;
-  constexpr bool kExactProducts = kNType == PBZ_F32 && kIType != PBZ_I32;
+  constexpr bool kExactProducts = kNType != PBZ_F64 && kIType != PBZ_I32;
   const int lanes = 1 << lanes_shift;
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   // sign2 = -1 subtracts: F2 (-N2) is exactly (-F2) N2, so the result is bit for bit that of negate + add
@@ -255,7 +278,7 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
     const int64_t vc = live ? v : nvec - 1;      // lanes past the end redo the last vector and store nothing
     const int64_t k = vc >> lanes_shift;
     const uint4 a = F1[vc], b = F2[vc];
-    const double n1 = load_N<kNType>(N1, k), n2 = sign2 * load_N<kNType>(N2, k);
+    const double n1 = load_N<kNType>(N1, k, n_f16 != 0), n2 = sign2 * load_N<kNType>(N2, k, n_f16 != 0);
     double c[kElems];
     double m = 0.0;
     const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
@@ -291,12 +314,7 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
     }
     if (live) {
       Fout[v] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-      if ((v & (lanes - 1)) == 0) {
-        if (kNType == PBZ_F64)
-          static_cast<double*>(Nout)[k] = n;
-        else
-          static_cast<float*>(Nout)[k] = float(n);
-      }
+      if ((v & (lanes - 1)) == 0) store_N<kNType>(Nout, k, n, n_f16 != 0);
     }
   }
 }
@@ -336,7 +354,8 @@ __global__ __launch_bounds__(64) void k_add_generic(const void* __restrict__ N1,
 template <int kIType, int kNType>
 __global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                              void* __restrict__ Nout, uint4* __restrict__ Fout,
-                                                             double r, double shift, int64_t nvec, int lanes_shift) {
+                                                             double r, double shift, int64_t nvec, int lanes_shift,
+                                                             int n_f16) {
   constexpr int kPer = PerDword<kIType>::value;
   constexpr int kElems = 4 * kPer;
   const int lanes = 1 << lanes_shift;
@@ -350,7 +369,7 @@ __global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restr
     const int64_t vc = live ? v : nvec - 1;
     const int64_t k = vc >> lanes_shift;
     const uint4 a = F1[vc];
-    const double n1 = load_N<kNType>(N1, k);
+    const double n1 = load_N<kNType>(N1, k, n_f16 != 0);
     const bool head = (vc & (lanes - 1)) == 0;
     double c[kElems];
     double m = 0.0;
@@ -385,12 +404,7 @@ __global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restr
     }
     if (live) {
       Fout[v] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-      if (head) {
-        if (kNType == PBZ_F64)
-          static_cast<double*>(Nout)[k] = m;
-        else
-          static_cast<float*>(Nout)[k] = float(m);
-      }
+      if (head) store_N<kNType>(Nout, k, m, n_f16 != 0);
     }
   }
 }
@@ -435,7 +449,7 @@ template <int kIType, int kNType, bool kTwo>
 __global__ __launch_bounds__(kThreads) void k_blockwise_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                             const void* __restrict__ N2, const uint4* __restrict__ F2,
                                                             double* __restrict__ out, double scale, int mode,
-                                                            int64_t nvec, int lanes_shift) {
+                                                            int64_t nvec, int lanes_shift, int n_f16) {
   const int lanes = 1 << lanes_shift;
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   const int64_t first = int64_t(blockIdx.x) * kThreads + threadIdx.x;
@@ -447,8 +461,8 @@ __global__ __launch_bounds__(kThreads) void k_blockwise_vec(const void* __restri
     const int64_t k = vc >> lanes_shift;
     const uint4 a = F1[vc];
     const uint4 b = kTwo ? F2[vc] : a;
-    const double n1 = load_N<kNType>(N1, k);
-    const double n2 = kTwo ? load_N<kNType>(N2, k) : n1;
+    const double n1 = load_N<kNType>(N1, k, n_f16 != 0);
+    const double n2 = kTwo ? load_N<kNType>(N2, k, n_f16 != 0) : n1;
     const bool head = (vc & (lanes - 1)) == 0;
     double sum = dot_vec<kIType>(a, b);          // exact integer sum
     if (head) sum -= double(first_element<kIType>(a.x)) * double(first_element<kIType>(b.x));
@@ -495,6 +509,7 @@ struct ReduceTail {
   int op;
   double r, n_blocks, vol;
   double s_l, s_c, w_l, w_c, w_s;   // Algorithm 12's stabilisers and weights
+  int n_f16;                        // N is FP16 (as opposed to bfloat16) when it is 16 bits wide
 };
 
 __device__ __forceinline__ double finish_statistic(const double* s, const ReduceTail& t) {
@@ -658,7 +673,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   {  // segment blockIdx.y starts seg_blocks blocks (= nvec vectors) further on
     const int64_t nb = int64_t(blockIdx.y) * seg_blocks;
-    constexpr int kNBytes = kNType == PBZ_F64 ? 8 : 4;
+    constexpr int kNBytes = kNType == PBZ_F64 ? 8 : (kNType == PBZ_F32 ? 4 : 2);
     N1 = static_cast<const char*>(N1) + nb * kNBytes;
     F1 += int64_t(blockIdx.y) * nvec;
     if (kTwo) {
@@ -684,8 +699,8 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
     }
 #pragma unroll
     for (int u = 0; u < kLoads; ++u) {
-      n1[u] = load_N<kNType>(N1, k[u]);
-      n2[u] = kTwo ? load_N<kNType>(N2, k[u]) : 0.0;
+      n1[u] = load_N<kNType>(N1, k[u], tail.n_f16 != 0);
+      n2[u] = kTwo ? load_N<kNType>(N2, k[u], tail.n_f16 != 0) : 0.0;
     }
 #pragma unroll
     for (int u = 0; u < kLoads; ++u) {
@@ -698,7 +713,8 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
     const int64_t k = vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
     const uint4 a = F1[v];
     const uint4 b = kTwo ? F2[v] : a;
-    accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a, b, load_N<kNType>(N1, k), kTwo ? load_N<kNType>(N2, k) : 0.0,
+    accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a, b, load_N<kNType>(N1, k, tail.n_f16 != 0),
+                                             kTwo ? load_N<kNType>(N2, k, tail.n_f16 != 0) : 0.0,
                                       kDC && (v - k * vpb) == 0);
   }
   reduce_tail(sums, tail);
@@ -783,8 +799,10 @@ void launch_reduce_vec(int ntype, bool two, bool dc, bool diff, dim3 grid, hipSt
                        int64_t seg_blocks, const ReduceTail& tail) {
   if (ntype == PBZ_F64)
     launch_reduce_vec2<kIType, PBZ_F64>(two, dc, diff, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
-  else
+  else if (ntype == PBZ_F32)
     launch_reduce_vec2<kIType, PBZ_F32>(two, dc, diff, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
+  else
+    launch_reduce_vec2<kIType, kN16>(two, dc, diff, grid, s, N1, F1, N2, F2, nvec, chunk, shift, vpb, seg_blocks, tail);
 }
 
 }  // namespace
@@ -806,8 +824,8 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
                void* Nout, void* Fout, hipStream_t s, double sign2) {
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const int lanes_shift = bpb % 16 == 0 ? ilog2_exact(bpb / 16) : -1;
-  const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
-  if (wide_N && lanes_shift >= 0 && lanes_shift <= 6 && aligned16(F1) && aligned16(F2) && aligned16(Fout)) {
+  const int n_f16 = c->ftype == PBZ_F16 ? 1 : 0;     // which of the two 16-bit types N is, when it is one
+  if (lanes_shift >= 0 && lanes_shift <= 6 && aligned16(F1) && aligned16(F2) && aligned16(Fout)) {
     const int64_t nvec = n_blocks * (bpb / 16);
     int64_t add_groups = (nvec + kThreads - 1) / kThreads;      // one vector per thread; the kernel loops beyond that
     if (add_groups > (int64_t(1) << 30)) add_groups = int64_t(1) << 30;
@@ -815,15 +833,19 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
     const uint4* a = static_cast<const uint4*>(F1);
     const uint4* b = static_cast<const uint4*>(F2);
     uint4* o = static_cast<uint4*>(Fout);
-#define PBZ_ADD(IT, NT) hipLaunchKernelGGL((k_add_vec<IT, NT>), grid, block, 0, s, N1, a, N2, b, Nout, o, c->r, sign2, nvec, lanes_shift)
+#define PBZ_ADD(IT, NT) hipLaunchKernelGGL((k_add_vec<IT, NT>), grid, block, 0, s, N1, a, N2, b, Nout, o, c->r, sign2, nvec, lanes_shift, n_f16)
     if (c->ftype == PBZ_F64) {
       if (c->itype == PBZ_I8) PBZ_ADD(PBZ_I8, PBZ_F64);
       else if (c->itype == PBZ_I16) PBZ_ADD(PBZ_I16, PBZ_F64);
       else PBZ_ADD(PBZ_I32, PBZ_F64);
-    } else {
+    } else if (c->ftype == PBZ_F32) {
       if (c->itype == PBZ_I8) PBZ_ADD(PBZ_I8, PBZ_F32);
       else if (c->itype == PBZ_I16) PBZ_ADD(PBZ_I16, PBZ_F32);
       else PBZ_ADD(PBZ_I32, PBZ_F32);
+    } else {
+      if (c->itype == PBZ_I8) PBZ_ADD(PBZ_I8, kN16);
+      else if (c->itype == PBZ_I16) PBZ_ADD(PBZ_I16, kN16);
+      else PBZ_ADD(PBZ_I32, kN16);
     }
 #undef PBZ_ADD
   } else {
@@ -856,6 +878,7 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     tail.w_l = ssim_params[2]; tail.w_c = ssim_params[3]; tail.w_s = ssim_params[4];
   }
   tail.partials = static_cast<double*>(workspace);
+  tail.n_f16 = c->ftype == PBZ_F16 ? 1 : 0;
   tail.op = int(op);
   tail.r = c->r;
   tail.n_blocks = double(n_blocks);
@@ -864,7 +887,6 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
   const bool two = (op == kDot || op == kCosine || op == kCovariance || op == kSsim || diff);
   const bool dc = (op == kCovariance || op == kVariance || op == kSsim || op == kStatistics);
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
-  const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
   const int64_t n_stride = n_blocks * ftype_bytes(c->ftype), f_stride = n_blocks * bpb;   // bytes per segment
 
   // the workspace holds kReduceMaxGroups partial sums: segments are handled in batches of at most that many
@@ -882,7 +904,7 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
       if (groups > max_groups) groups = max_groups;
       hipLaunchKernelGGL(k_reduce_dc, dim3(groups, batch), dim3(kThreads), 0, s, n1, f1, int(c->ftype), int(c->itype),
                          n_blocks, c->kept, tail);
-    } else if (wide_N && bpb % 16 == 0 && aligned16(f1) && (!two || aligned16(f2)) && f_stride % 16 == 0) {
+    } else if (bpb % 16 == 0 && aligned16(f1) && (!two || aligned16(f2)) && f_stride % 16 == 0) {
       const int64_t vpb = bpb / 16;
       const int64_t nvec = n_blocks * vpb;
       const int64_t chunk = chunk_for(nvec, max_groups, &groups, two);
@@ -916,6 +938,7 @@ int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment,
   tail.s_l = tail.s_c = 0.0;
   tail.w_l = tail.w_c = tail.w_s = 1.0;
   tail.partials = static_cast<double*>(workspace);
+  tail.n_f16 = 0;
   tail.op = int(kStatistics);
   tail.r = c->r;
   tail.n_blocks = double(blocks_per_segment);
@@ -949,23 +972,27 @@ int launch_add_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, con
   const double shift = x * root;
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const int lanes_shift = bpb % 16 == 0 ? ilog2_exact(bpb / 16) : -1;
-  const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
-  if (wide_N && lanes_shift >= 0 && lanes_shift <= 6 && aligned16(Fin) && aligned16(Fout)) {
+  const int n_f16 = c->ftype == PBZ_F16 ? 1 : 0;     // which of the two 16-bit types N is, when it is one
+  if (lanes_shift >= 0 && lanes_shift <= 6 && aligned16(Fin) && aligned16(Fout)) {
     const int64_t nvec = n_blocks * (bpb / 16);
     int64_t groups = (nvec + kThreads - 1) / kThreads;
     if (groups > (int64_t(1) << 30)) groups = int64_t(1) << 30;
     dim3 grid(static_cast<unsigned>(groups)), block(kThreads);
     const uint4* a = static_cast<const uint4*>(Fin);
     uint4* o = static_cast<uint4*>(Fout);
-#define PBZ_ADDS(IT, NT) hipLaunchKernelGGL((k_add_scalar_vec<IT, NT>), grid, block, 0, s, Nin, a, Nout, o, c->r, shift, nvec, lanes_shift)
+#define PBZ_ADDS(IT, NT) hipLaunchKernelGGL((k_add_scalar_vec<IT, NT>), grid, block, 0, s, Nin, a, Nout, o, c->r, shift, nvec, lanes_shift, n_f16)
     if (c->ftype == PBZ_F64) {
       if (c->itype == PBZ_I8) PBZ_ADDS(PBZ_I8, PBZ_F64);
       else if (c->itype == PBZ_I16) PBZ_ADDS(PBZ_I16, PBZ_F64);
       else PBZ_ADDS(PBZ_I32, PBZ_F64);
-    } else {
+    } else if (c->ftype == PBZ_F32) {
       if (c->itype == PBZ_I8) PBZ_ADDS(PBZ_I8, PBZ_F32);
       else if (c->itype == PBZ_I16) PBZ_ADDS(PBZ_I16, PBZ_F32);
       else PBZ_ADDS(PBZ_I32, PBZ_F32);
+    } else {
+      if (c->itype == PBZ_I8) PBZ_ADDS(PBZ_I8, kN16);
+      else if (c->itype == PBZ_I16) PBZ_ADDS(PBZ_I16, kN16);
+      else PBZ_ADDS(PBZ_I32, kN16);
     }
 #undef PBZ_ADDS
   } else {
@@ -995,8 +1022,8 @@ int launch_blockwise(const pbz_codec* c, int mode, int64_t n_blocks, const void*
   const double scale = 1.0 / (c->r * c->r * double(c->vol));
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const int lanes_shift = bpb % 16 == 0 ? ilog2_exact(bpb / 16) : -1;
-  const bool wide_N = c->ftype == PBZ_F64 || c->ftype == PBZ_F32;
-  if (wide_N && lanes_shift >= 0 && lanes_shift <= 6 && aligned16(F1) && aligned16(F2)) {
+  const int n_f16 = c->ftype == PBZ_F16 ? 1 : 0;     // which of the two 16-bit types N is, when it is one
+  if (lanes_shift >= 0 && lanes_shift <= 6 && aligned16(F1) && aligned16(F2)) {
     const int64_t nvec = n_blocks * (bpb / 16);
     int64_t groups = (nvec + kThreads - 1) / kThreads;
     if (groups > (int64_t(1) << 30)) groups = int64_t(1) << 30;
@@ -1007,19 +1034,23 @@ int launch_blockwise(const pbz_codec* c, int mode, int64_t n_blocks, const void*
   do {                                                                                                              \
     if (two)                                                                                                        \
       hipLaunchKernelGGL((k_blockwise_vec<IT, NT, true>), grid, block, 0, s, N1, a, N2, b, out, scale, mode, nvec,   \
-                         lanes_shift);                                                                              \
+                         lanes_shift, n_f16);                                                                       \
     else                                                                                                            \
       hipLaunchKernelGGL((k_blockwise_vec<IT, NT, false>), grid, block, 0, s, N1, a, N2, b, out, scale, mode, nvec,  \
-                         lanes_shift);                                                                              \
+                         lanes_shift, n_f16);                                                                       \
   } while (0)
     if (c->ftype == PBZ_F64) {
       if (c->itype == PBZ_I8) PBZ_BW(PBZ_I8, PBZ_F64);
       else if (c->itype == PBZ_I16) PBZ_BW(PBZ_I16, PBZ_F64);
       else PBZ_BW(PBZ_I32, PBZ_F64);
-    } else {
+    } else if (c->ftype == PBZ_F32) {
       if (c->itype == PBZ_I8) PBZ_BW(PBZ_I8, PBZ_F32);
       else if (c->itype == PBZ_I16) PBZ_BW(PBZ_I16, PBZ_F32);
       else PBZ_BW(PBZ_I32, PBZ_F32);
+    } else {
+      if (c->itype == PBZ_I8) PBZ_BW(PBZ_I8, kN16);
+      else if (c->itype == PBZ_I16) PBZ_BW(PBZ_I16, kN16);
+      else PBZ_BW(PBZ_I32, kN16);
     }
 #undef PBZ_BW
   } else {

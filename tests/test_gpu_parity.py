@@ -156,6 +156,13 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((9, 9, 514), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((17, 9, 23), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "generic"),     # odd bfloat16 rows: 2-byte aligned
                ((6, 3), (8, 8), 8, "f32", "f32", None, "generic"),                   # shorter than one 16-byte piece
+               # 16-bit working types (N stored as FP16 / bfloat16) on the specialised kernels
+               ((40, 64), (8, 8), 8, "f32", "f16", None, "lane_f32_8x8_i8"),
+               ((37, 53), (8, 8), 16, "f32", "bf16", (4, 4), "lane_f32_8x8_i16_box4x4"),
+               ((3, 33, 48), (1, 16, 16), 8, "f32", "f16", None, "quad16_f32_16x16_i8"),
+               ((9, 20, 37), (4, 16, 16), 8, "f32", "bf16", None, "quad16_f32_4x16x16_i8"),
+               ((17, 9, 24), (8, 8, 8), 8, "bf16", "bf16", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
+               ((9, 9, 520), (8, 8, 8), 8, "bf16", "f16", None, "oct8_bf16_8x8x8_i8"),
                # 49 and more blocks along x: the decompress variant that stores whole row pieces
                ((17, 9, 520), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 12, 392), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
