@@ -14,7 +14,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpbz.so")
-SOURCES = ["pbz_api.hip", "pbz_generic.hip", "pbz_ops.hip", "pbz_fast.hip", "pbz_wasserstein.hip"]
+SOURCES = ["pbz_api.hip", "pbz_generic.hip", "pbz_ops.hip", "pbz_fast.hip", "pbz_wasserstein.hip", "pbz_tiled.hip"]
 
 # Packed-FP32 code generation is switched off on purpose (the flag applies to the device pass; the host
 # pass prints a harmless "unknown feature" warning).

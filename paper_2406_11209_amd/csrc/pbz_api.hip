@@ -83,11 +83,15 @@ int pbz::ensure_tables(const pbz_codec* c, const DeviceTables** out) {
   if (!t.ready) {
     bool ok = hipMalloc(&t.H, sizeof(double) * c->h_total) == hipSuccess &&
               hipMalloc(&t.kept_pos, sizeof(int32_t) * c->vol) == hipSuccess &&
+              hipMalloc(&t.kept_list, sizeof(int32_t) * c->kept) == hipSuccess &&
+              hipMemcpy(t.kept_list, c->kept_list, sizeof(int32_t) * c->kept, hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(t.H, c->H_host, sizeof(double) * c->h_total, hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(t.kept_pos, c->kept_pos, sizeof(int32_t) * c->vol, hipMemcpyHostToDevice) == hipSuccess;
     if (!ok) {   // leave nothing half-made behind
       if (t.H) (void)hipFree(t.H);
       if (t.kept_pos) (void)hipFree(t.kept_pos);
+      if (t.kept_list) (void)hipFree(t.kept_list);
+      t.kept_list = nullptr;
       t.H = nullptr;
       t.kept_pos = nullptr;
       return PBZ_ERR_HIP;
@@ -136,6 +140,7 @@ int pbz_codec_create(pbz_codec** out, int ndim, const int64_t* block_shape, pbz_
   c->transform = PBZ_TRANSFORM_DCT;
   c->mask = static_cast<uint8_t*>(std::malloc(size_t(vol)));
   c->kept_pos = static_cast<int32_t*>(std::malloc(sizeof(int32_t) * size_t(vol)));
+  c->kept_list = static_cast<int32_t*>(std::malloc(sizeof(int32_t) * size_t(kept)));
   int h_total = 0;
   for (int d = 0; d < ndim; ++d) {
     c->block[d] = block_shape[d];
@@ -144,13 +149,14 @@ int pbz_codec_create(pbz_codec** out, int ndim, const int64_t* block_shape, pbz_
   }
   c->h_total = h_total;
   c->H_host = static_cast<double*>(std::malloc(sizeof(double) * size_t(h_total)));
-  if (!c->mask || !c->kept_pos || !c->H_host) {
+  if (!c->mask || !c->kept_pos || !c->kept_list || !c->H_host) {
     pbz_codec_destroy(c);
     return PBZ_ERR_ALLOC;
   }
   int pos = 0;
   for (int64_t j = 0; j < vol; ++j) {
     c->mask[j] = mask ? (mask[j] ? 1 : 0) : 1;
+    if (c->mask[j]) c->kept_list[pos] = int32_t(j);
     c->kept_pos[j] = c->mask[j] ? pos++ : -1;
   }
   c->dc_kept = c->mask[0] != 0;
@@ -191,12 +197,14 @@ void pbz_codec_destroy(pbz_codec* c) {
       if (have && hipSetDevice(d) == hipSuccess) {
         if (c->dev[d].H) (void)hipFree(c->dev[d].H);
         if (c->dev[d].kept_pos) (void)hipFree(c->dev[d].kept_pos);
+        if (c->dev[d].kept_list) (void)hipFree(c->dev[d].kept_list);
         (void)hipSetDevice(cur);
       }
     }
   }
   std::free(c->mask);
   std::free(c->kept_pos);
+  std::free(c->kept_list);
   std::free(c->H_host);
   delete c;
 }
@@ -264,6 +272,7 @@ int pbz_compress(const pbz_codec* c, const void* x, pbz_ftype x_type, const int6
   const DeviceTables* t = nullptr;
   st = ensure_tables(c, &t);
   if (st != PBZ_OK) return st;
+  if (tiled_kernels_cover(c)) return launch_compress_tiled(c, g, t, x, x_type, N, F, s);
   return launch_compress_generic(c, g, t, x, x_type, N, F, s);
 }
 
@@ -329,6 +338,7 @@ int pbz_decompress(const pbz_codec* c, const void* N, const void* F, const int64
   const DeviceTables* t = nullptr;
   st = ensure_tables(c, &t);
   if (st != PBZ_OK) return st;
+  if (tiled_kernels_cover(c)) return launch_decompress_tiled(c, g, t, N, F, y, y_type, s);
   return launch_decompress_generic(c, g, t, N, F, y, y_type, s);
 }
 

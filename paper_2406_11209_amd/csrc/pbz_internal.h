@@ -22,6 +22,7 @@ struct DeviceTables {
   bool ready = false;
   double* H = nullptr;          // concatenated forward matrices H_d[m][q], row-major, one per dimension
   int32_t* kept_pos = nullptr;  // [vol] position in F of intra-block entry j, or -1 when pruned
+  int32_t* kept_list = nullptr; // [kept] intra-block entry stored at position pos of F (the inverse of kept_pos)
 };
 
 }  // namespace pbz
@@ -37,6 +38,7 @@ struct pbz_codec {
   bool compute_f64;     // transform and binning precision
   uint8_t* mask;        // [vol] 0/1
   int32_t* kept_pos;    // [vol]
+  int32_t* kept_list;   // [kept]
   int kept;             // sum(P)
   bool dc_kept;
   int box[PBZ_MAX_NDIM];  // mask == low-frequency corner box of these extents (box[0] = 0 when it is not)
@@ -72,6 +74,12 @@ struct Geom {
 int ensure_tables(const pbz_codec* c, const DeviceTables** out);
 
 // generic kernels (any ndim, any power-of-two block shape within the limits, any types)
+// general kernels for block extents up to 32 (in-register transforms on LDS tiles); the dense ones below take the rest
+bool tiled_kernels_cover(const pbz_codec* c);
+int launch_compress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* x, int xtype, void* N,
+                          void* F, hipStream_t s);
+int launch_decompress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* N, const void* F,
+                            void* y, int ytype, hipStream_t s);
 int launch_compress_generic(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* x, int xtype,
                             void* N, void* F, hipStream_t s);
 int launch_decompress_generic(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* N,

@@ -1,0 +1,515 @@
+// General codec kernels for every setting without a specialised kernel whose block extents are at most 32:
+// any dimensionality up to 8, any such block shape, any mask, every array / working / index type, any shape.
+//
+// A workgroup owns a tile of G consecutive blocks (block-major order, so usually neighbours along the last
+// dimension), 4096 elements or fewer, in one LDS buffer laid out [block][intra-block index]:
+//   load     elements are enumerated (row within the block, block, position in the row), so that consecutive
+//            threads read consecutive memory across the blocks of the tile; padding is filled with zeros;
+//   passes   one per block dimension, in place: a thread takes whole 1-D lines into registers and applies the
+//            in-register transform of that length (Sec. III-A, "Orthonormal transform"; the same even/odd-split DCT
+//            or Haar cascade as the specialised kernels), a workgroup barrier between passes;
+//   binning  N_k = max |C_k| by LDS atomics on the bit patterns (non-negative floats order like integers),
+//            I = rint(r C / N_k) for the kept entries only, enumerated in F order: the tile's part of F is one
+//            contiguous run.
+// Decompression mirrors this.  The block -> coordinates decode (divisions by the grid extents) happens once per
+// block per tile; the per-element decode is shifts and masks because block extents are powers of two.
+#include "pbz_dct.h"
+#include "pbz_device.h"
+#include "pbz_haar.h"
+#include "pbz_internal.h"
+
+namespace pbz {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTileElems = 4096;
+constexpr int kMaxTileBlocks = 256;
+
+// The array's geometry right-aligned into a fixed number of dimensions (kDims = 4 or 8 in the kernels; unused
+// leading dimensions have extent, block extent and grid extent 1 and stride 0), so that every loop over the
+// dimensions unrolls and its operands stay in scalar registers instead of being fetched by a run-time index.
+struct TileGeom {
+  int G, g_shift;                 // blocks per tile
+  int vol_shift;                  // log2(prod(block))
+  int bx_shift;                   // log2 of the last block extent
+  int dims;                       // 4 or 8
+  int kept;
+  int64_t n_blocks;
+  int bshift[PBZ_MAX_NDIM];       // log2 of every block extent
+  int64_t shape[PBZ_MAX_NDIM], stride[PBZ_MAX_NDIM], grid[PBZ_MAX_NDIM];
+};
+
+// one spare slot per 32 keeps strided line accesses from piling onto one bank
+__device__ __forceinline__ int pad(int i) { return i + (i >> 5); }
+
+template <typename T> struct Bits;
+template <> struct Bits<float> {
+  typedef unsigned int type;
+  static __device__ __forceinline__ type of(float v) { return __float_as_uint(v); }
+  static __device__ __forceinline__ float from(type b) { return __uint_as_float(b); }
+};
+template <> struct Bits<double> {
+  typedef unsigned long long type;
+  static __device__ __forceinline__ type of(double v) { return (unsigned long long)__double_as_longlong(v); }
+  static __device__ __forceinline__ double from(type b) { return __longlong_as_double((long long)b); }
+};
+
+constexpr int kMaxRows = 256;                 // rows (runs along the last dimension) of a block whose offsets are tabulated
+struct TileBlocks {                           // in LDS; all but row_off per tile
+  int64_t origin[kMaxTileBlocks];             // element offset of the block's first element; -1: no such block
+  int64_t row_off[kMaxRows];                  // offset of row i of a block from the block's first element (same for all blocks)
+  uint8_t lim[kMaxTileBlocks][PBZ_MAX_NDIM];  // how many entries (at most 32) along each dimension lie inside the array
+  uint8_t full[kMaxTileBlocks];               // the block lies wholly inside the array
+};
+constexpr int kBatch = 8;                     // global loads a thread keeps in flight while filling a tile
+
+template <int kDims>
+__device__ __forceinline__ void decode_blocks(const TileGeom& tg, int64_t k0, TileBlocks* tb) {
+  for (int b = threadIdx.x; b < tg.G; b += kThreads) {
+    int64_t k = k0 + b;
+    if (k >= tg.n_blocks) {
+      tb->origin[b] = -1;
+#pragma unroll
+      for (int d = 0; d < kDims; ++d) tb->lim[b][d] = 0;
+      continue;
+    }
+    int64_t off = 0;
+    bool full = true;
+#pragma unroll
+    for (int d = PBZ_MAX_NDIM - 1; d >= PBZ_MAX_NDIM - kDims; --d) {
+      int64_t kb = 0;
+      if (tg.grid[d] > 1) {             // uniform: no division for the padded dimensions
+        kb = k % tg.grid[d];
+        k /= tg.grid[d];
+      }
+      const int64_t c0 = kb << tg.bshift[d];
+      const int64_t left = tg.shape[d] - c0;
+      const int64_t extent = int64_t(1) << tg.bshift[d];
+      tb->lim[b][d - (PBZ_MAX_NDIM - kDims)] = uint8_t(left < extent ? left : extent);
+      full = full && left >= extent;
+      off += c0 * tg.stride[d];
+    }
+    tb->origin[b] = off;
+    tb->full[b] = full ? 1 : 0;
+  }
+}
+
+// once per kernel: offsets of a block's rows relative to its first element
+template <int kDims>
+__device__ __forceinline__ void tabulate_rows(const TileGeom& tg, TileBlocks* tb) {
+  const int rows = 1 << (tg.vol_shift - tg.bx_shift);
+  if (rows > kMaxRows) return;
+  for (int i = threadIdx.x; i < rows; i += kThreads) {
+    int j = i;
+    int64_t off = 0;
+#pragma unroll
+    for (int d = PBZ_MAX_NDIM - 2; d >= PBZ_MAX_NDIM - kDims; --d) {
+      off += (j & ((1 << tg.bshift[d]) - 1)) * tg.stride[d];
+      j >>= tg.bshift[d];
+    }
+    tb->row_off[i] = off;
+  }
+}
+
+// intra-block index j of block b -> element offset; false when the element is padding
+template <int kDims>
+__device__ __forceinline__ bool locate(const TileGeom& tg, const TileBlocks* tb, int b, int j, int64_t* offset) {
+  int64_t off = tb->origin[b];
+  bool in = off >= 0;
+  if ((1 << (tg.vol_shift - tg.bx_shift)) <= kMaxRows) {      // uniform: the usual case, rows tabulated
+    *offset = off + tb->row_off[j >> tg.bx_shift] + (j & ((1 << tg.bx_shift) - 1));   // the last dimension has stride 1
+    if (in && !tb->full[b]) {                                  // blocks on the array's edge: test every coordinate
+#pragma unroll
+      for (int d = PBZ_MAX_NDIM - 1; d >= PBZ_MAX_NDIM - kDims; --d) {
+        in = in && (j & ((1 << tg.bshift[d]) - 1)) < int(tb->lim[b][d - (PBZ_MAX_NDIM - kDims)]);
+        j >>= tg.bshift[d];
+      }
+    }
+    return in;
+  }
+#pragma unroll
+  for (int d = PBZ_MAX_NDIM - 1; d >= PBZ_MAX_NDIM - kDims; --d) {
+    const int jd = j & ((1 << tg.bshift[d]) - 1);
+    j >>= tg.bshift[d];
+    in = in && jd < int(tb->lim[b][d - (PBZ_MAX_NDIM - kDims)]);
+    off += jd * tg.stride[d];
+  }
+  *offset = off;
+  return in;
+}
+
+// memory-friendly enumeration of the tile: consecutive e walk along a row across the tile's blocks
+__device__ __forceinline__ void row_major_across_blocks(const TileGeom& tg, int e, int* b, int* j) {
+  const int bx = 1 << tg.bx_shift;
+  const int xin = e & (bx - 1);
+  *b = (e >> tg.bx_shift) & (tg.G - 1);
+  *j = ((e >> (tg.bx_shift + tg.g_shift)) << tg.bx_shift) + xin;
+}
+
+template <typename T, typename XT>
+__device__ __forceinline__ T widen(XT raw) { return T(raw); }
+struct bf16_raw { uint16_t bits; };           // bfloat16 arrays are plain bit patterns
+template <typename T>
+__device__ __forceinline__ T widen_bf16(bf16_raw raw) { return T(bf16_bits_to_float(raw.bits)); }
+
+// kBatch loads are issued before the first of them is used; padding gets zeros (the load then reads element 0:
+// never a branch around a load)
+template <int kDims, typename T, typename XT, bool kBf16>
+__device__ __forceinline__ void load_tile(const TileGeom& tg, const TileBlocks* tb, const XT* x, T* buf,
+                                          int total) {
+  for (int e0 = threadIdx.x; e0 < total; e0 += kThreads * kBatch) {
+    XT raw[kBatch];
+    int slot[kBatch];
+    bool in[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int e = e0 + u * kThreads;
+      int b, j;
+      row_major_across_blocks(tg, e < total ? e : 0, &b, &j);
+      int64_t off;
+      in[u] = locate<kDims>(tg, tb, b, j, &off) && e < total;
+      slot[u] = e < total ? pad((b << tg.vol_shift) + j) : -1;
+      raw[u] = x[in[u] ? off : 0];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (slot[u] < 0) continue;
+      T v;
+      if constexpr (kBf16) v = widen_bf16<T>(raw[u]);
+      else v = widen<T, XT>(raw[u]);
+      buf[slot[u]] = in[u] ? v : T(0);
+    }
+  }
+}
+
+template <int kDims, typename T, typename XT>
+__device__ __forceinline__ void store_tile(const TileGeom& tg, const TileBlocks* tb, XT* y, const T* buf,
+                                           int total) {
+  for (int e = threadIdx.x; e < total; e += kThreads) {
+    int b, j;
+    row_major_across_blocks(tg, e, &b, &j);
+    int64_t off;
+    if (locate<kDims>(tg, tb, b, j, &off)) y[off] = XT(buf[pad((b << tg.vol_shift) + j)]);
+  }
+}
+
+template <int kDims, typename T>
+__device__ __forceinline__ void store_tile_bf16(const TileGeom& tg, const TileBlocks* tb, uint16_t* y,
+                                                const T* buf, int total) {
+  for (int e = threadIdx.x; e < total; e += kThreads) {
+    int b, j;
+    row_major_across_blocks(tg, e, &b, &j);
+    int64_t off;
+    if (locate<kDims>(tg, tb, b, j, &off)) {
+      const T v = buf[pad((b << tg.vol_shift) + j)];
+      y[off] = sizeof(T) == 8 ? double_to_bf16_bits(double(v)) : float_to_bf16_bits(float(v));
+    }
+  }
+}
+template <int kDims, typename T>
+__device__ __forceinline__ void store_tile_f16(const TileGeom& tg, const TileBlocks* tb, _Float16* y,
+                                               const T* buf, int total) {
+  for (int e = threadIdx.x; e < total; e += kThreads) {
+    int b, j;
+    row_major_across_blocks(tg, e, &b, &j);
+    int64_t off;
+    if (locate<kDims>(tg, tb, b, j, &off)) {
+      const T v = buf[pad((b << tg.vol_shift) + j)];
+      y[off] = sizeof(T) == 8 ? double_to_f16(double(v)) : _Float16(float(v));
+    }
+  }
+}
+
+// one transform pass over the lines of length n with element stride 2^inner_shift, in place
+// kMax: also fold max |.| of every transformed line into its block's entry of bmax (a line never leaves its block)
+template <typename T, int kTf, int n, bool kForward, bool kMax = false>
+__device__ __forceinline__ void pass_n(T* buf, int total, int n_shift, int inner_shift,
+                                       typename Bits<T>::type* bmax = nullptr, int vol_shift = 0) {
+  const int lines = total >> n_shift;
+  const int inner = 1 << inner_shift;
+  for (int l = threadIdx.x; l < lines; l += kThreads) {
+    const int base = ((l >> inner_shift) << (n_shift + inner_shift)) + (l & (inner - 1));
+    T v[n];
+#pragma unroll
+    for (int a = 0; a < n; ++a) v[a] = buf[pad(base + (a << inner_shift))];
+    if (kForward) tf_forward<kTf, T, n, 1>(v);
+    else tf_inverse<kTf, T, n, 1, n>(v);
+#pragma unroll
+    for (int a = 0; a < n; ++a) buf[pad(base + (a << inner_shift))] = v[a];
+    if constexpr (kMax) {
+      T m = fabs(v[0]);
+#pragma unroll
+      for (int a = 1; a < n; ++a) m = fmax(m, fabs(v[a]));
+      atomicMax(&bmax[base >> vol_shift], Bits<T>::of(m));
+    }
+  }
+}
+
+// forward: bmax != nullptr asks for the per-block maxima, taken in the last pass that has work to do
+template <int kDims, typename T, int kTf, bool kForward>
+__device__ __forceinline__ void transform_tile(const TileGeom& tg, T* buf, int total,
+                                               typename Bits<T>::type* bmax = nullptr) {
+  int last = -1;
+#pragma unroll
+  for (int d = PBZ_MAX_NDIM - kDims; d < PBZ_MAX_NDIM; ++d)
+    if (tg.bshift[d] > 0) last = d;
+  int inner_shift = tg.vol_shift;
+#pragma unroll
+  for (int d = PBZ_MAX_NDIM - kDims; d < PBZ_MAX_NDIM; ++d) {
+    const int ns = tg.bshift[d];
+    inner_shift -= ns;
+    if (ns == 0) continue;
+    if (kForward && bmax != nullptr && d == last) {
+      switch (ns) {
+        case 1: pass_n<T, kTf, 2, kForward, true>(buf, total, 1, inner_shift, bmax, tg.vol_shift); break;
+        case 2: pass_n<T, kTf, 4, kForward, true>(buf, total, 2, inner_shift, bmax, tg.vol_shift); break;
+        case 3: pass_n<T, kTf, 8, kForward, true>(buf, total, 3, inner_shift, bmax, tg.vol_shift); break;
+        case 4: pass_n<T, kTf, 16, kForward, true>(buf, total, 4, inner_shift, bmax, tg.vol_shift); break;
+        default: pass_n<T, kTf, 32, kForward, true>(buf, total, 5, inner_shift, bmax, tg.vol_shift); break;
+      }
+    } else {
+      switch (ns) {
+        case 1: pass_n<T, kTf, 2, kForward>(buf, total, 1, inner_shift); break;
+        case 2: pass_n<T, kTf, 4, kForward>(buf, total, 2, inner_shift); break;
+        case 3: pass_n<T, kTf, 8, kForward>(buf, total, 3, inner_shift); break;
+        case 4: pass_n<T, kTf, 16, kForward>(buf, total, 4, inner_shift); break;
+        default: pass_n<T, kTf, 32, kForward>(buf, total, 5, inner_shift); break;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <int kDims, typename T, int kTf>
+__global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const void* __restrict__ x, int xtype,
+                                                             void* __restrict__ N, int ntype, void* __restrict__ F,
+                                                             int itype, double r,
+                                                             const int32_t* __restrict__ kept_list) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  typedef typename Bits<T>::type bits_t;
+  const int total = tg.G << tg.vol_shift;
+  TileBlocks* tb = reinterpret_cast<TileBlocks*>(smem);
+  bits_t* bmax = reinterpret_cast<bits_t*>(smem + sizeof(TileBlocks));
+  T* binv = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + sizeof(unsigned long long) * kMaxTileBlocks);
+  T* buf = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks);
+  const int64_t n_tiles = (tg.n_blocks + tg.G - 1) >> tg.g_shift;
+  const int vol = 1 << tg.vol_shift;
+
+  tabulate_rows<kDims>(tg, tb);
+  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int64_t k0 = tile << tg.g_shift;
+    decode_blocks<kDims>(tg, k0, tb);
+    for (int b = threadIdx.x; b < tg.G; b += kThreads) bmax[b] = 0;
+    __syncthreads();
+    switch (xtype) {                       // one switch around the whole loop, not one per element
+      case PBZ_F64: load_tile<kDims, T, double, false>(tg, tb, static_cast<const double*>(x), buf, total); break;
+      case PBZ_F32: load_tile<kDims, T, float, false>(tg, tb, static_cast<const float*>(x), buf, total); break;
+      case PBZ_BF16: load_tile<kDims, T, bf16_raw, true>(tg, tb, static_cast<const bf16_raw*>(x), buf, total); break;
+      default: load_tile<kDims, T, _Float16, false>(tg, tb, static_cast<const _Float16*>(x), buf, total); break;
+    }
+    __syncthreads();
+    transform_tile<kDims, T, kTf, true>(tg, buf, total, bmax);      // leaves N_k = max |C_k| in bmax
+    if (vol == 1) {                        // single-element blocks: nothing was transformed
+      for (int e = threadIdx.x; e < total; e += kThreads) bmax[e] = Bits<T>::of(fabs(buf[pad(e)]));
+      __syncthreads();
+    }
+    for (int b = threadIdx.x; b < tg.G; b += kThreads) {
+      const T nk = Bits<T>::from(bmax[b]);
+      binv[b] = nk > T(0) ? T(1) / nk : T(0);
+      if (k0 + b < tg.n_blocks) store_float(N, ntype, k0 + b, nk);
+    }
+    __syncthreads();
+    // bin and prune: the kept entries of the tile in F order.  (r C) / N from the correctly rounded reciprocal
+    // with one remainder correction: the correctly rounded quotient without a division per entry.
+    const int n_kept = tg.G * tg.kept;
+    const bool all_kept = tg.kept == vol;            // then position pos of F holds intra-block entry pos
+    for (int e0 = threadIdx.x; e0 < n_kept; e0 += kThreads * kBatch) {
+      int b[kBatch], j[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {            // the table look-ups of a batch are in flight together
+        const int e = e0 + u * kThreads;
+        const int ec = e < n_kept ? e : 0;
+        b[u] = all_kept ? ec >> tg.vol_shift : ec / tg.kept;
+        const int pos = ec - b[u] * tg.kept;
+        j[u] = all_kept ? pos : kept_list[pos];
+        if (e >= n_kept || k0 + b[u] >= tg.n_blocks) b[u] = -1;
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        if (b[u] < 0) continue;
+        const T nk = Bits<T>::from(bmax[b[u]]), inv = binv[b[u]];
+        const T a = T(r) * buf[pad((b[u] << tg.vol_shift) + j[u])];
+        const T q = a * inv;
+        T t = fma(fma(-q, nk, a), inv, q);
+        t = fmin(fmax(rint(t), T(-r)), T(r));
+        store_index(F, itype, k0 * tg.kept + e0 + u * kThreads, int64_t(t));
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// the tile's run of F (contiguous) -> specified coefficients at their intra-block positions, kBatch loads in flight
+template <typename T, typename IT>
+__device__ __forceinline__ void scatter_coefficients(const TileGeom& tg, const IT* F, int64_t k0, const T* bn,
+                                                     T r, const int32_t* kept_list, T* buf) {
+  const int n_kept = tg.G * tg.kept;
+  const int64_t last = tg.n_blocks * int64_t(tg.kept) - 1;
+  for (int e0 = threadIdx.x; e0 < n_kept; e0 += kThreads * kBatch) {
+    IT f[kBatch];
+    int j[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int e = e0 + u * kThreads;
+      const int64_t at = k0 * tg.kept + e;
+      f[u] = F[at <= last ? at : last];
+      const int ec = e < n_kept ? e : 0;
+      const int b = ec / tg.kept;
+      j[u] = e < n_kept ? pad((b << tg.vol_shift) + kept_list[ec - b * tg.kept]) : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (j[u] < 0) continue;
+      const int e = e0 + u * kThreads;
+      buf[j[u]] = bn[e / tg.kept] * T(f[u]);
+    }
+  }
+}
+
+template <int kDims, typename T, int kTf>
+__global__ __launch_bounds__(kThreads) void k_decompress_tiled(TileGeom tg, const void* __restrict__ N, int ntype,
+                                                               const void* __restrict__ F, int itype, double r,
+                                                               void* __restrict__ y, int ytype,
+                                                               const int32_t* __restrict__ kept_list) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int total = tg.G << tg.vol_shift;
+  TileBlocks* tb = reinterpret_cast<TileBlocks*>(smem);
+  T* bn = reinterpret_cast<T*>(smem + sizeof(TileBlocks));
+  T* buf = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks);
+  const int64_t n_tiles = (tg.n_blocks + tg.G - 1) >> tg.g_shift;
+  const int vol = 1 << tg.vol_shift;
+
+  tabulate_rows<kDims>(tg, tb);
+  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int64_t k0 = tile << tg.g_shift;
+    decode_blocks<kDims>(tg, k0, tb);
+    for (int b = threadIdx.x; b < tg.G; b += kThreads)      // blocks past the end: the last one again, never stored
+      bn[b] = load_float<T>(N, ntype, k0 + b < tg.n_blocks ? k0 + b : tg.n_blocks - 1) / T(r);   // N / r once per block
+    if (tg.kept != vol)
+      for (int e = threadIdx.x; e < total; e += kThreads) buf[pad(e)] = T(0);
+    __syncthreads();
+    // Algorithm 3: N F / r at the kept positions
+    switch (itype) {
+      case PBZ_I8: scatter_coefficients<T, int8_t>(tg, static_cast<const int8_t*>(F), k0, bn, T(r), kept_list, buf); break;
+      case PBZ_I16: scatter_coefficients<T, int16_t>(tg, static_cast<const int16_t*>(F), k0, bn, T(r), kept_list, buf); break;
+      default: scatter_coefficients<T, int32_t>(tg, static_cast<const int32_t*>(F), k0, bn, T(r), kept_list, buf); break;
+    }
+    __syncthreads();
+    transform_tile<kDims, T, kTf, false>(tg, buf, total);
+    switch (ytype) {
+      case PBZ_F64: store_tile<kDims, T, double>(tg, tb, static_cast<double*>(y), buf, total); break;
+      case PBZ_F32: store_tile<kDims, T, float>(tg, tb, static_cast<float*>(y), buf, total); break;
+      case PBZ_BF16: store_tile_bf16<kDims, T>(tg, tb, static_cast<uint16_t*>(y), buf, total); break;
+      default: store_tile_f16<kDims, T>(tg, tb, static_cast<_Float16*>(y), buf, total); break;
+    }
+    __syncthreads();
+  }
+}
+
+int ilog2(int64_t v) {
+  int s = 0;
+  while ((int64_t(1) << s) < v) ++s;
+  return s;
+}
+
+TileGeom make_tile(const pbz_codec* c, const Geom& g) {
+  TileGeom tg{};
+  int G = kTileElems / c->vol;
+  if (G < 1) G = 1;
+  if (G > kMaxTileBlocks) G = kMaxTileBlocks;
+  tg.G = G;
+  tg.g_shift = ilog2(G);
+  tg.vol_shift = ilog2(c->vol);
+  tg.bx_shift = ilog2(c->block[c->ndim - 1]);
+  tg.dims = c->ndim <= 4 ? 4 : 8;
+  tg.kept = c->kept;
+  tg.n_blocks = g.n_blocks;
+  for (int d = 0; d < PBZ_MAX_NDIM; ++d) {        // right-aligned; leading dimensions of extent 1
+    const int src = d - (PBZ_MAX_NDIM - c->ndim);
+    tg.bshift[d] = src >= 0 ? ilog2(c->block[src]) : 0;
+    tg.shape[d] = src >= 0 ? g.shape[src] : 1;
+    tg.stride[d] = src >= 0 ? g.stride[src] : 0;
+    tg.grid[d] = src >= 0 ? g.grid[src] : 1;
+  }
+  return tg;
+}
+
+size_t tile_lds_bytes(const TileGeom& tg, size_t elem) {
+  const int total = tg.G << tg.vol_shift;
+  return sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks + elem * size_t(total + (total >> 5) + 1);
+}
+
+int tile_grid(int64_t n_tiles) {
+  const int64_t cap = int64_t(1) << 20;
+  return int(n_tiles < cap ? n_tiles : cap);
+}
+
+}  // namespace
+
+bool tiled_kernels_cover(const pbz_codec* c) {
+  for (int d = 0; d < c->ndim; ++d)
+    if (c->block[d] > 32) return false;
+  return true;
+}
+
+int launch_compress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* x, int xtype, void* N,
+                          void* F, hipStream_t s) {
+  const TileGeom tg = make_tile(c, g);
+  const int64_t n_tiles = (tg.n_blocks + tg.G - 1) / tg.G;
+  const dim3 grid(tile_grid(n_tiles)), block(kThreads);
+#define PBZ_TILED(T, TF)                                                                                              \
+  do {                                                                                                                \
+    if (tg.dims == 4)                                                                                                 \
+      hipLaunchKernelGGL((k_compress_tiled<4, T, TF>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, x, xtype, N,  \
+                         int(c->ftype), F, int(c->itype), c->r, t->kept_list);                                        \
+    else                                                                                                              \
+      hipLaunchKernelGGL((k_compress_tiled<8, T, TF>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, x, xtype, N,  \
+                         int(c->ftype), F, int(c->itype), c->r, t->kept_list);                                        \
+  } while (0)
+  if (c->compute_f64) {
+    if (c->transform == PBZ_TRANSFORM_HAAR) PBZ_TILED(double, kTfHaar);
+    else PBZ_TILED(double, kTfDct);
+  } else {
+    if (c->transform == PBZ_TRANSFORM_HAAR) PBZ_TILED(float, kTfHaar);
+    else PBZ_TILED(float, kTfDct);
+  }
+#undef PBZ_TILED
+  return hip_status(hipGetLastError());
+}
+
+int launch_decompress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* N, const void* F,
+                            void* y, int ytype, hipStream_t s) {
+  const TileGeom tg = make_tile(c, g);
+  const int64_t n_tiles = (tg.n_blocks + tg.G - 1) / tg.G;
+  const dim3 grid(tile_grid(n_tiles)), block(kThreads);
+#define PBZ_TILED(T, TF)                                                                                              \
+  do {                                                                                                                \
+    if (tg.dims == 4)                                                                                                 \
+      hipLaunchKernelGGL((k_decompress_tiled<4, T, TF>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, N,          \
+                         int(c->ftype), F, int(c->itype), c->r, y, ytype, t->kept_list);                              \
+    else                                                                                                              \
+      hipLaunchKernelGGL((k_decompress_tiled<8, T, TF>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, N,          \
+                         int(c->ftype), F, int(c->itype), c->r, y, ytype, t->kept_list);                              \
+  } while (0)
+  if (c->compute_f64) {
+    if (c->transform == PBZ_TRANSFORM_HAAR) PBZ_TILED(double, kTfHaar);
+    else PBZ_TILED(double, kTfDct);
+  } else {
+    if (c->transform == PBZ_TRANSFORM_HAAR) PBZ_TILED(float, kTfHaar);
+    else PBZ_TILED(float, kTfDct);
+  }
+#undef PBZ_TILED
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace pbz

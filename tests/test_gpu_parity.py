@@ -106,6 +106,8 @@ RAGGED = [((37, 53), (8, 8), 8, "f32", "f32", None),
           ((3, 33, 47), (1, 16, 16), 8, "f32", "f32", None),
           ((17, 9, 23), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4)),
           ((100,), (32,), 8, "f32", "f32", None),
+          ((300,), (64,), 8, "f32", "f32", None),                  # extents above 32: the dense general kernels
+          ((5, 300), (2, 128), 16, "f64", "f64", None),
           ((5, 6, 7, 9), (2, 2, 4, 2), 16, "f64", "f64", None),
           ((9, 40, 40), (4, 16, 16), 8, "f32", "f32", None),       # non-hypercubic block
           ((70, 70), (16, 4), 32, "f64", "f64", None),             # int32 indices
