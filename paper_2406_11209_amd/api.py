@@ -134,7 +134,13 @@ def _ptr(t) -> int:
 
 
 def _stream() -> int:
-    return _torch().cuda.current_stream().cuda_stream
+    """hipStream_t of torch's current stream on the current device (the raw getter when this torch has it: the
+    public route builds a Stream object per call, three microseconds a time)."""
+    torch = _torch()
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+    if raw is not None:
+        return raw(torch.cuda.current_device())
+    return torch.cuda.current_stream().cuda_stream
 
 
 @dataclass(frozen=True)
