@@ -154,6 +154,17 @@ struct IdxPack<int16_t> {
 // kTailX read every 16-byte piece from a start clamped to the row's last whole piece (always in bounds), which
 // is already right for every block but the row's last; the lane that owns that block then re-reads its
 // in-range elements one by one.  Stores: whole pieces that fit, single elements for the rest.
+// The uncompressed arrays are touched once and are far larger than any cache: their loads and stores carry the
+// non-temporal hint, which leaves the caches to the compressed arrays that the next operation reads again.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+  const u32x4 t = __builtin_nontemporal_load(static_cast<const u32x4*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void store16_stream(void* p, const uint4& u) {
+  const u32x4 t = {u.x, u.y, u.z, u.w};
+  __builtin_nontemporal_store(t, static_cast<u32x4*>(p));
+}
 struct __attribute__((packed, aligned(4))) uint4_a4 { uint32_t x, y, z, w; };
 __device__ __forceinline__ uint4 load16_a4(const void* p) {
   const uint4_a4 v = *static_cast<const uint4_a4*>(p);
@@ -382,7 +393,7 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
       } else {
         const uint4* p = reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * BX);
 #pragma unroll
-        for (int k = 0; k < RV; ++k) raw[(z * BY + y) * RV + k] = p[k];
+        for (int k = 0; k < RV; ++k) raw[(z * BY + y) * RV + k] = load16_stream(&p[k]);
       }
     }
   if constexpr (kRagged) {
@@ -488,8 +499,10 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
   int64_t tx, by, bz;
   if (!decode_tile<4>(g, tx, by, bz)) return;
   const int64_t bx = tx * 64 + lane;
-  if (bx >= g.gx) return;
-  const int64_t block = (bz * g.gy + by) * g.gx + bx;
+  // lanes past the end of the block row stay: they decode the row's last block again and store nothing of their
+  // own, but take part in the row-wise exchange below
+  const bool active = bx < g.gx;
+  const int64_t block = (bz * g.gy + by) * g.gx + (active ? bx : g.gx - 1);
 
   uint32_t w[KW];
   const uint4* src = reinterpret_cast<const uint4*>(F + block * KEPT);
@@ -516,11 +529,12 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
 #pragma unroll
     for (int yy0 = 0; yy0 < BY; ++yy0) {
       const int64_t zz = bz * BZ + z, yy = by * BY + yy0;
-      if (!kRagged || (zz < g.Z && yy < g.Y)) {
+      if (!kRagged || (zz < g.Z && yy < g.Y)) {             // uniform over the wave
         if constexpr (kTailX) {
           XT* row = y + (zz * g.Y + yy) * g.X;
 #pragma unroll
           for (int k = 0; k < RV; ++k) {
+            if (!active) break;
             const int64_t x0 = bx * BX + k * PER16;
             const T* piece = v + ((z * BY + yy0) * RV + k) * PER16;
             if (x0 + PER16 <= g.X) {
@@ -531,10 +545,25 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
                 if (x0 + e < g.X) Elem<T, XT>::store(row + x0 + e, piece[e]);
             }
           }
+        } else if constexpr (RV == 1) {
+          if (active) store16_stream(y + (zz * g.Y + yy) * g.X + bx * BX, Pack<T, XT>::run(v + (z * BY + yy0) * PER16));
         } else {
-          uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * BX);
+          // A lane's RV pieces of the row alternate with its neighbours', so a store instruction would write
+          // every RV-th piece; with the non-temporal hint such pieces reach memory singly (measured: twice as
+          // slow).  The row therefore goes through LDS once, so that each instruction stores 64 consecutive pieces.
+          __shared__ uint4 rowbuf[4][64 * RV];
+          uint4* st = rowbuf[threadIdx.x >> 6];
 #pragma unroll
-          for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+          for (int k = 0; k < RV; ++k) st[lane * RV + k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+          wave_lds_sync();
+          const int n_pieces = int(g.gx - tx * 64 < 64 ? g.gx - tx * 64 : 64) * RV;
+          uint4* dst = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX);
+#pragma unroll
+          for (int k = 0; k < RV; ++k) {
+            const int idx = k * 64 + lane;
+            if (idx < n_pieces) store16_stream(dst + idx, st[idx]);
+          }
+          wave_lds_sync();
         }
       }
     }
@@ -591,7 +620,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
         const int64_t x0 = bxc * 16 + q * 4;
         raw[yy0] = load16_a4(x + (zz * g.Y + yy) * g.X + (x0 + 4 <= g.X ? x0 : g.X - 4));
       } else {
-        raw[yy0] = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 16 + q * 4);
+        raw[yy0] = load16_stream(x + (zz * g.Y + yy) * g.X + bxc * 16 + q * 4);
       }
     }
 #pragma unroll
@@ -753,7 +782,7 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
               if (x0 + e < g.X) row[x0 + e] = v[yy0 * 4 + e];
           }
         } else {
-          *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4) = f4_bits(v + yy0 * 4);
+          store16_stream(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4, f4_bits(v + yy0 * 4));
         }
       }
     }
@@ -808,7 +837,7 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
       if constexpr (kTailX)
         raw[yy0] = load16_a4(x + (zz * g.Y + yy) * g.X + (bxc * 8 + 8 <= g.X ? bxc * 8 : g.X - 8));
       else
-        raw[yy0] = *reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * 8);
+        raw[yy0] = load16_stream(x + (zz * g.Y + yy) * g.X + bxc * 8);
     }
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
@@ -969,7 +998,7 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const void*
             if (bx * 8 + e < g.X) row[bx * 8 + e].bits = uint16_t(pw[e >> 1] >> (16 * (e & 1)));
         }
       } else {
-        *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 8) = packed;
+        store16_stream(y + (zz * g.Y + yy) * g.X + bx * 8, packed);
       }
     }
   }
@@ -1043,7 +1072,7 @@ __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const 
             if (bx * 8 + e < g.X) row[bx * 8 + e].bits = uint16_t(pw[e >> 1] >> (16 * (e & 1)));
         }
       } else {
-        *reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * 8) = packed;
+        store16_stream(y + (zz * g.Y + yy) * g.X + bx * 8, packed);
       }
     }
   }
