@@ -499,10 +499,8 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
   int64_t tx, by, bz;
   if (!decode_tile<4>(g, tx, by, bz)) return;
   const int64_t bx = tx * 64 + lane;
-  // lanes past the end of the block row stay: they decode the row's last block again and store nothing of their
-  // own, but take part in the row-wise exchange below
-  const bool active = bx < g.gx;
-  const int64_t block = (bz * g.gy + by) * g.gx + (active ? bx : g.gx - 1);
+  if (bx >= g.gx) return;
+  const int64_t block = (bz * g.gy + by) * g.gx + bx;
 
   uint32_t w[KW];
   const uint4* src = reinterpret_cast<const uint4*>(F + block * KEPT);
@@ -529,12 +527,11 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
 #pragma unroll
     for (int yy0 = 0; yy0 < BY; ++yy0) {
       const int64_t zz = bz * BZ + z, yy = by * BY + yy0;
-      if (!kRagged || (zz < g.Z && yy < g.Y)) {             // uniform over the wave
+      if (!kRagged || (zz < g.Z && yy < g.Y)) {
         if constexpr (kTailX) {
           XT* row = y + (zz * g.Y + yy) * g.X;
 #pragma unroll
           for (int k = 0; k < RV; ++k) {
-            if (!active) break;
             const int64_t x0 = bx * BX + k * PER16;
             const T* piece = v + ((z * BY + yy0) * RV + k) * PER16;
             if (x0 + PER16 <= g.X) {
@@ -545,25 +542,13 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
                 if (x0 + e < g.X) Elem<T, XT>::store(row + x0 + e, piece[e]);
             }
           }
-        } else if constexpr (RV == 1) {
-          if (active) store16_stream(y + (zz * g.Y + yy) * g.X + bx * BX, Pack<T, XT>::run(v + (z * BY + yy0) * PER16));
         } else {
-          // A lane's RV pieces of the row alternate with its neighbours', so a store instruction would write
-          // every RV-th piece; with the non-temporal hint such pieces reach memory singly (measured: twice as
-          // slow).  The row therefore goes through LDS once, so that each instruction stores 64 consecutive pieces.
-          __shared__ uint4 rowbuf[4][64 * RV];
-          uint4* st = rowbuf[threadIdx.x >> 6];
+          // plain stores: a lane's pieces alternate with its neighbours' within a line, which the L2 merges into
+          // whole lines; with the non-temporal hint these 16-byte pieces reach memory singly (measured: twice as
+          // slow), and passing the rows through LDS to store whole lines doubled the kernel's registers
+          uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * BX);
 #pragma unroll
-          for (int k = 0; k < RV; ++k) st[lane * RV + k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
-          wave_lds_sync();
-          const int n_pieces = int(g.gx - tx * 64 < 64 ? g.gx - tx * 64 : 64) * RV;
-          uint4* dst = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX);
-#pragma unroll
-          for (int k = 0; k < RV; ++k) {
-            const int idx = k * 64 + lane;
-            if (idx < n_pieces) store16_stream(dst + idx, st[idx]);
-          }
-          wave_lds_sync();
+          for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
         }
       }
     }
