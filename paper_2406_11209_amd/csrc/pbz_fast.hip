@@ -3,24 +3,32 @@
 // Every kernel here is "wave autonomous": a 64-lane wave owns a run of consecutive blocks along the
 // contiguous (last) array dimension, reads whole block rows straight from HBM with 16-byte loads (the
 // lanes of a wave cover a contiguous span of every row, which measures at the same bandwidth as a
-// linear copy on MI355X), transforms in registers with the even/odd-split DCT of pbz_dct.h, and writes
-// N and F.  There is no workgroup barrier anywhere; LDS, where used, is private to a wave.
+// linear copy on MI355X), transforms in registers with the even/odd-split DCT of pbz_dct.h or the Haar
+// cascade of pbz_haar.h (template switch TF), and writes N and F.  There is no workgroup barrier in the
+// compress kernels; LDS, where used, is private to a wave.
 //
 // Family "lane":   one lane owns one whole block (blocks of at most 64 elements: 8x8, 4x4x4).  Indices leave
 //                   through a wave-private LDS transpose when a block's F is 64 bytes or more, so that every
 //                   store instruction of the wave writes one contiguous span.
-// Family "quad16":  16x16 blocks, 16 blocks per wave.  Each lane first holds a 16-row x 4-column strip (the
-//                   column transform runs in registers), the wave exchanges through LDS, then each lane
-//                   holds four whole rows (row transform); rows leave as 16-byte pieces in linear order.
+// Family "quad16":  16x16 and 4x16x16 blocks, 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
+//                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
+//                   then each lane holds four whole rows (row transform, and for 4x16x16 the transform across
+//                   the four planes); rows leave as 16-byte pieces in linear order.
 // Family "oct8":    8x8x8 blocks of bfloat16 input, 8 blocks per wave.  Each lane first holds one z-plane of
 //                   a block (x and y transforms), the wave exchanges through LDS, then each lane holds one
 //                   y-row of all eight z-planes (z transform).  Decompression needs no exchange: every
-//                   lane rebuilds its own z-plane from the block's few kept coefficients.
+//                   lane rebuilds its own z-plane from the block's few kept coefficients; wide arrays use a
+//                   variant in which a wave owns one plane of 64 blocks and stores whole 1 KiB row pieces.
+//
+// Variants of every kernel: kRagged (the slower dimensions are not multiples of the block extents), kTailX
+// (neither is the last one: rows start at any 4-byte boundary, the last block of a row is partial), kStats
+// (compress also leaves the per-wave sums from which mean, variance and norm follow).  N is stored in the
+// codec's working type, converted on load / store.
 //
 // Preconditions checked on the host (otherwise the call falls back to the general kernels): the array
 // reduces to at most three dimensions (leading dimensions with block extent 1 fold into the slowest one),
-// the block shape / types / mask box match an instantiation, the last array extent is a multiple of the
-// block's last extent, and rows start 16-byte aligned.  The other dimensions may be ragged.
+// the block shape / types / mask box match an instantiation, rows are at least one 16-byte piece long and
+// start on a 4-byte boundary.
 #include "pbz_dct.h"
 #include "pbz_haar.h"
 #include "pbz_device.h"
