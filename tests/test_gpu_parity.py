@@ -106,6 +106,8 @@ RAGGED = [((37, 53), (8, 8), 8, "f32", "f32", None),
           ((3, 33, 47), (1, 16, 16), 8, "f32", "f32", None),
           ((17, 9, 23), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4)),
           ((100,), (32,), 8, "f32", "f32", None),
+          ((3, 4, 5, 6, 7), (1, 2, 2, 2, 4), 16, "f64", "f64", None),     # five dimensions
+          ((2, 3, 2, 5, 6, 7), (2, 1, 2, 1, 2, 4), 8, "f32", "f32", None),
           ((300,), (64,), 8, "f32", "f32", None),                  # extents above 32: the dense general kernels
           ((5, 300), (2, 128), 16, "f64", "f64", None),
           ((5, 6, 7, 9), (2, 2, 4, 2), 16, "f64", "f64", None),
@@ -158,6 +160,11 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((9, 9, 514), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((17, 9, 23), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "generic"),     # odd bfloat16 rows: 2-byte aligned
                ((6, 3), (8, 8), 8, "f32", "f32", None, "generic"),                   # shorter than one 16-byte piece
+               # leading dimensions with block extent 1 fold into the slowest one
+               ((3, 2, 40, 64), (1, 1, 8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
+               ((2, 3, 16, 9, 24), (1, 1, 8, 8, 8), 8, "bf16", "f32", (1, 1, 4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
+               ((2, 3, 9, 16, 24), (1, 1, 8, 8, 8), 8, "bf16", "f32", (1, 1, 4, 4, 4), "generic"),   # padding inside the fold
+               ((2, 2, 8, 30, 21), (1, 1, 4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
                # 16-bit working types (N stored as FP16 / bfloat16) on the specialised kernels
                ((40, 64), (8, 8), 8, "f32", "f16", None, "lane_f32_8x8_i8"),
                ((37, 53), (8, 8), 16, "f32", "bf16", (4, 4), "lane_f32_8x8_i16_box4x4"),
