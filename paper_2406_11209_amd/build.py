@@ -14,6 +14,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpbz.so")
+EXAMPLE = os.path.join(PKG, "c_abi_roundtrip")
 SOURCES = ["pbz_api.hip", "pbz_generic.hip", "pbz_ops.hip", "pbz_fast.hip", "pbz_wasserstein.hip", "pbz_tiled.hip"]
 
 # Packed-FP32 code generation is switched off on purpose (the flag applies to the device pass; the host
@@ -52,6 +53,10 @@ def build(verbose: bool = False) -> str:
     tmp = LIB + ".tmp"
     _run([cc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp])
     os.replace(tmp, LIB)
+    # the C ABI used from plain C (no Python, no torch): a small round-trip program next to the library
+    _run([cc, "-x", "c", os.path.join(PKG, "examples", "c_abi_roundtrip.c"), "-D__HIP_PLATFORM_AMD__",
+          "-I" + os.path.join(ROOT, "include"), "-I/opt/rocm/include", "-L" + PKG, "-lpbz", "-L/opt/rocm/lib",
+          "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib", "-o", EXAMPLE])
     return LIB
 
 

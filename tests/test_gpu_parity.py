@@ -297,6 +297,19 @@ def test_hot_path_replays_from_a_hip_graph():
     assert float(out[1].item()) > 0.0
 
 
+def test_c_abi_from_plain_c():
+    """The boundary is usable without Python or torch: a C program (built next to the library) allocates with the
+    HIP runtime, calls compress / decompress / norm2 and checks the round trip against the binning bound."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(api.__file__), "c_abi_roundtrip")
+    assert os.path.exists(exe), "c_abi_roundtrip is missing: run python -m paper_2406_11209_amd.build"
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert res.stdout.strip().endswith("ok"), res.stdout
+    assert "lane_f64_4x4x4_i16" in res.stdout
+
+
 def test_transform_is_fixed_once_the_codec_has_compressed():
     codec = Codec((8, 8), "f32", "i8")
     codec.compress(torch.zeros((16, 16), dtype=torch.float32, device="cuda"))
