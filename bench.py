@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the operations timed outside the step (used for profiles of the step itself)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time replays of it (the per-operation times still "
+                         "come from an eager pass with events); what a launch-bound caller of the small workloads does")
     ap.add_argument("--transform", default="dct", choices=["dct", "haar"],
                     help="orthonormal transform of the codec (the metric is quoted with the default, the DCT)")
     return ap.parse_args()
@@ -186,11 +189,25 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    if args.graph:
+        # the same step recorded once (every call is a plain kernel launch on the current stream) and replayed
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
 
     per_op = {}
     for i, (name, _, moved, quoted) in enumerate(ops):
-        ms = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
-        per_op[name] = {"ms": round(ms, 4), "gbps": round(quoted / ms / 1e6, 1),
+        times = [ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]
+        ms = float(np.mean(times))
+        per_op[name] = {"ms": round(ms, 4), "ms_median": round(float(np.median(times)), 4),
+                        "ms_min": round(float(np.min(times)), 4), "gbps": round(quoted / ms / 1e6, 1),
                         "gbps_moved": round(moved / ms / 1e6, 1),
                         "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBPS, 4)}
     # operations added beyond the base hot path (scalar addition, SSIM, block-wise statistics): timed on their
@@ -250,6 +267,10 @@ def main():
 
             st_rows = torch.empty((T, 3), dtype=torch.float64, device=dev)
 
+            def compress_one_call_per_step():
+                for t in range(T):
+                    codec.compress(xA[t:t + 1], N1[t * per:(t + 1) * per], F1[t * per:(t + 1) * per])
+
             def series_compress_then_segmented():
                 codec.compress(xA, N1, F1)
                 for k, name in enumerate(("mean", "variance", "norm2")):
@@ -267,6 +288,7 @@ def main():
                  lambda: codec.segmented("covariance", T - 1, per, N1, F1, N1[per:], F1[per:], out=seg[:T - 1]),
                  2 * comp_bytes * (T - 1) // T),
                 ("series_variance_one_call_per_step", per_step_variance, comp_bytes),
+                ("series_compress_one_call_per_step", compress_one_call_per_step, in_bytes + comp_bytes),
             ]
     for name, fn, moved in ([] if args.no_extras else extras):
         fn()
@@ -300,7 +322,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "shape": list(wl.shape), "block": list(wl.block), "array_dtype": wl.dtype,
                    "index_bits": wl.index_bits, "kept_per_block": lay.kept_per_block, "transform": args.transform,
-                   "uncompressed_bytes": in_bytes, "compressed_bytes": comp_bytes,
+                   "launch": "hip graph replay" if args.graph else "eager", "uncompressed_bytes": in_bytes, "compressed_bytes": comp_bytes,
                    "input_generation_s": round(t_gen, 1)},
         "ops": per_op,
         "extra_ops": extra_ops,

@@ -151,9 +151,9 @@ __device__ __forceinline__ uint4 apply_sign(uint4 a) {
 // Each workgroup streams one contiguous run of kThreads * kUnroll vectors: kUnroll independent loads per thread
 // (kThreads vectors apart), then the stores.
 template <int kIType, int kSign>
-__global__ __launch_bounds__(kThreads) void k_scale_sign_vec(const uint4* __restrict__ in, uint4* __restrict__ out,
-                                                             int64_t nvec) {
-  const int64_t base = int64_t(blockIdx.x) * (kThreads * kUnroll) + threadIdx.x;
+__device__ __forceinline__ void scale_sign_run(const uint4* __restrict__ in, uint4* __restrict__ out, int64_t nvec,
+                                               int64_t group) {
+  const int64_t base = group * (kThreads * kUnroll) + threadIdx.x;
   if (base + (kUnroll - 1) * kThreads < nvec) {
     uint4 a[kUnroll];
 #pragma unroll
@@ -166,6 +166,28 @@ __global__ __launch_bounds__(kThreads) void k_scale_sign_vec(const uint4* __rest
       if (v < nvec) out[v] = apply_sign<kIType, kSign>(kSign != 0 ? in[v] : make_uint4(0u, 0u, 0u, 0u));
     }
   }
+}
+
+template <int kIType, int kSign>
+__global__ __launch_bounds__(kThreads) void k_scale_sign_vec(const uint4* __restrict__ in, uint4* __restrict__ out,
+                                                             int64_t nvec) {
+  scale_sign_run<kIType, kSign>(in, out, nvec, blockIdx.x);
+}
+
+// Algorithm 5 in one launch: the first f_groups workgroups write F_out = sign(x) F_in, the others N_out = |x| N_in
+template <int kIType, int kSign>
+__global__ __launch_bounds__(kThreads) void k_mul_scalar_vec(const uint4* __restrict__ Fin, uint4* __restrict__ Fout,
+                                                             int64_t nvec, unsigned f_groups,
+                                                             const void* Nin, void* Nout, int ntype, double ax,
+                                                             int64_t n_blocks) {   // Nin may be Nout
+
+  if (blockIdx.x < f_groups) {
+    scale_sign_run<kIType, kSign>(Fin, Fout, nvec, blockIdx.x);
+    return;
+  }
+  const int64_t nthreads = int64_t(gridDim.x - f_groups) * kThreads;
+  for (int64_t k = int64_t(blockIdx.x - f_groups) * kThreads + threadIdx.x; k < n_blocks; k += nthreads)
+    store_float(Nout, ntype, k, load_float<double>(Nin, ntype, k) * ax);
 }
 
 __global__ __launch_bounds__(kThreads) void k_scale_sign_scalar(const void* __restrict__ in, void* __restrict__ out,
@@ -555,10 +577,32 @@ __device__ __forceinline__ double group_total(const double* sums, double (*lds)[
   return t;
 }
 
+// the requested statistic(s) of segment `segment` from its five sums
+__device__ __forceinline__ void write_statistic(const double* fin, const ReduceTail& t, int64_t segment) {
+  if (t.op == kStatistics) {            // mean, variance and norm2 of one array from the same two sums
+    ReduceTail one = t;
+    const int ops[3] = {kMean, kVariance, kNorm2};
+    for (int i = 0; i < 3; ++i) {
+      one.op = ops[i];
+      t.out[segment * 3 + i] = finish_statistic(fin, one);
+    }
+  } else {
+    t.out[segment] = finish_statistic(fin, t);
+  }
+}
+
+// grid y runs over the segments of a segmented reduction (1 otherwise).  A segment covered by a single
+// workgroup (small arrays) is finished here and needs no second launch; the sums are the same either way.
 __device__ __forceinline__ void reduce_tail(double* sums, const ReduceTail& t) {
   __shared__ double lds[kThreads / 64][kNumSums];
+  __shared__ double fin[kNumSums];
   const double total = group_total(sums, lds);
-  // grid y runs over the segments of a segmented reduction (1 otherwise)
+  if (gridDim.x == 1) {
+    if (threadIdx.x < kNumSums) fin[threadIdx.x] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) write_statistic(fin, t, blockIdx.y);
+    return;
+  }
   if (threadIdx.x < kNumSums)
     t.partials[(int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * kReducePartialSlots + threadIdx.x] = total;
 }
@@ -596,18 +640,7 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_final(ReduceTail t, in
   const double grand = group_total<kFinalThreads / 64>(acc, lds);
   if (threadIdx.x < kNumSums) fin[threadIdx.x] = grand;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    if (t.op == kStatistics) {            // mean, variance and norm2 of one array from the same two sums
-      ReduceTail one = t;
-      const int ops[3] = {kMean, kVariance, kNorm2};
-      for (int i = 0; i < 3; ++i) {
-        one.op = ops[i];
-        t.out[int64_t(blockIdx.x) * 3 + i] = finish_statistic(fin, one);
-      }
-    } else {
-      t.out[blockIdx.x] = finish_statistic(fin, t);
-    }
-  }
+  if (threadIdx.x == 0) write_statistic(fin, t, blockIdx.x);
 }
 
 // per-tile sums {S11, D1} left by a compress kernel -> partial sums per workgroup, added in tile order;
@@ -811,13 +844,41 @@ int launch_negate(const pbz_codec* c, int64_t n_blocks, const void* Fin, void* F
   return scale_sign(c, n_blocks, Fin, Fout, -1, s);
 }
 
+template <int kSign>
+static void launch_mul_scalar_vec(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double ax,
+                                  void* Nout, void* Fout, int64_t nvec, hipStream_t s) {
+  const int64_t per_group = int64_t(kThreads) * kUnroll;
+  const unsigned f_groups = static_cast<unsigned>((nvec + per_group - 1) / per_group);
+  dim3 grid(f_groups + unsigned(stream_groups(n_blocks, 4))), block(kThreads);
+  const uint4* i4 = static_cast<const uint4*>(Fin);
+  uint4* o4 = static_cast<uint4*>(Fout);
+  if (c->itype == PBZ_I8)
+    hipLaunchKernelGGL((k_mul_scalar_vec<PBZ_I8, kSign>), grid, block, 0, s, i4, o4, nvec, f_groups, Nin, Nout,
+                       int(c->ftype), ax, n_blocks);
+  else if (c->itype == PBZ_I16)
+    hipLaunchKernelGGL((k_mul_scalar_vec<PBZ_I16, kSign>), grid, block, 0, s, i4, o4, nvec, f_groups, Nin, Nout,
+                       int(c->ftype), ax, n_blocks);
+  else
+    hipLaunchKernelGGL((k_mul_scalar_vec<PBZ_I32, kSign>), grid, block, 0, s, i4, o4, nvec, f_groups, Nin, Nout,
+                       int(c->ftype), ax, n_blocks);
+}
+
 int launch_mul_scalar(const pbz_codec* c, int64_t n_blocks, const void* Nin, const void* Fin, double x, void* Nout,
                       void* Fout, hipStream_t s) {
+  const int sign = x > 0.0 ? 1 : (x < 0.0 ? -1 : 0);
+  const int64_t f_bytes = n_blocks * c->kept * itype_bytes(c->itype);
+  const bool f_untouched = sign > 0 && Fin == Fout;
+  if (!f_untouched && f_bytes % 16 == 0 && aligned16(Fin) && aligned16(Fout)) {
+    if (sign > 0) launch_mul_scalar_vec<1>(c, n_blocks, Nin, Fin, std::fabs(x), Nout, Fout, f_bytes / 16, s);
+    else if (sign < 0) launch_mul_scalar_vec<-1>(c, n_blocks, Nin, Fin, std::fabs(x), Nout, Fout, f_bytes / 16, s);
+    else launch_mul_scalar_vec<0>(c, n_blocks, Nin, Fin, std::fabs(x), Nout, Fout, f_bytes / 16, s);
+    return hip_status(hipGetLastError());
+  }
   hipLaunchKernelGGL(k_scale_N, dim3(stream_groups(n_blocks, 4)), dim3(kThreads), 0, s, Nin, Nout, int(c->ftype),
                      std::fabs(x), n_blocks);
   int st = hip_status(hipGetLastError());
   if (st != PBZ_OK) return st;
-  return scale_sign(c, n_blocks, Fin, Fout, x > 0.0 ? 1 : (x < 0.0 ? -1 : 0), s);
+  return scale_sign(c, n_blocks, Fin, Fout, sign, s);
 }
 
 int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2, const void* F2,
@@ -861,7 +922,9 @@ static int64_t chunk_for(int64_t nvec, int max_groups, int* groups, bool two) {
   const int64_t step = int64_t(kThreads) * reduce_unroll(two);
   int64_t steps = (nvec + step * max_groups - 1) / (step * max_groups);
   if (steps < 1) steps = 1;
-  const int64_t chunk = steps * step;
+  int64_t chunk = steps * step;
+  // up to four steps go to one workgroup, which then also finishes the statistic: cheaper than a second launch
+  if (nvec <= 4 * step) chunk = 4 * step;
   *groups = int((nvec + chunk - 1) / chunk);
   return chunk;
 }
@@ -924,9 +987,11 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     }
     int st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;
-    hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kFinalThreads), 0, s, tail, groups);
-    st = hip_status(hipGetLastError());
-    if (st != PBZ_OK) return st;
+    if (groups > 1) {          // a single workgroup per segment has already written the results
+      hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kFinalThreads), 0, s, tail, groups);
+      st = hip_status(hipGetLastError());
+      if (st != PBZ_OK) return st;
+    }
   }
   return PBZ_OK;
 }
@@ -958,9 +1023,11 @@ int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment,
                        tail);
     int st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;
-    hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kFinalThreads), 0, s, tail, groups);
-    st = hip_status(hipGetLastError());
-    if (st != PBZ_OK) return st;
+    if (groups > 1) {          // a single workgroup per segment has already written the results
+      hipLaunchKernelGGL(k_reduce_final, dim3(batch), dim3(kFinalThreads), 0, s, tail, groups);
+      st = hip_status(hipGetLastError());
+      if (st != PBZ_OK) return st;
+    }
   }
   return PBZ_OK;
 }
