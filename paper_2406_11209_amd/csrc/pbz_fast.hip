@@ -135,23 +135,36 @@ struct Pack<float, bf16_t> {
   }
 };
 
-// ---- index packing ---------------------------------------------------------------------------------
+// ---- binning and index packing ------------------------------------------------------------------------
+// rint(t * inv) without a rounding and a conversion instruction: one fused multiply-add onto 1.5 * 2^23 (FP32;
+// 1.5 * 2^52 in FP64) rounds the exact product to an integer in the nearest-even mode and leaves that integer,
+// in two's complement, in the low bits of the sum's (low) word.  Valid for |t * inv| < 2^22; only the low 8 or
+// 16 bits are used.
+__device__ __forceinline__ uint32_t bin_bits(float t, float inv) {
+  return __builtin_bit_cast(uint32_t, __builtin_fmaf(t, inv, 12582912.0f));
+}
+__device__ __forceinline__ uint32_t bin_bits(double t, double inv) {
+  return uint32_t(__builtin_bit_cast(uint64_t, __builtin_fma(t, inv, 6755399441055744.0)));
+}
+
+// the low bytes / halves of `per` words gathered into one dword by byte permutes
 template <typename IT>
 struct IdxPack;   // kPer indices per dword
 template <>
 struct IdxPack<int8_t> {
   static constexpr int per = 4;
-  static __device__ __forceinline__ uint32_t pack(const int* q) {
-    return (uint32_t(q[0]) & 0xffu) | ((uint32_t(q[1]) & 0xffu) << 8) | ((uint32_t(q[2]) & 0xffu) << 16) |
-           (uint32_t(q[3]) << 24);
+  static __device__ __forceinline__ uint32_t pack(const uint32_t* q) {
+    const uint32_t lo = __builtin_amdgcn_perm(q[1], q[0], 0x0c0c0400u);    // q0.b0, q1.b0
+    const uint32_t hi = __builtin_amdgcn_perm(q[3], q[2], 0x0c0c0400u);    // q2.b0, q3.b0
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
   }
   static __device__ __forceinline__ int get(uint32_t w, int i) { return int(int8_t((w >> (8 * i)) & 0xffu)); }
 };
 template <>
 struct IdxPack<int16_t> {
   static constexpr int per = 2;
-  static __device__ __forceinline__ uint32_t pack(const int* q) {
-    return (uint32_t(q[0]) & 0xffffu) | (uint32_t(q[1]) << 16);
+  static __device__ __forceinline__ uint32_t pack(const uint32_t* q) {
+    return __builtin_amdgcn_perm(q[1], q[0], 0x05040100u);
   }
   static __device__ __forceinline__ int get(uint32_t w, int i) { return int(int16_t((w >> (16 * i)) & 0xffffu)); }
 };
@@ -450,12 +463,12 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   constexpr int PER = IdxPack<IT>::per;
 #pragma unroll
   for (int kw = 0; kw < KW; ++kw) {
-    int q[PER];
+    uint32_t q[PER];
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
       const int j = kw * PER + e;                         // position in F
       const int kx = j % KX, ky = (j / KX) % KY, kz = j / (KX * KY);
-      q[e] = int(rint(v[(kz * BY + ky) * BX + kx] * inv));
+      q[e] = bin_bits(v[(kz * BY + ky) * BX + kx], inv);
     }
     w[kw] = IdxPack<IT>::pack(q);
   }
@@ -683,9 +696,9 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
     uint32_t w[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      int q4[4];
+      uint32_t q4[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) q4[e] = int(rintf(u[j * 16 + k * 4 + e] * inv));
+      for (int e = 0; e < 4; ++e) q4[e] = bin_bits(u[j * 16 + k * 4 + e], inv);
       w[k] = IdxPack<int8_t>::pack(q4);
     }
     const int blk = Map::block_of(4 * j + bsub);
@@ -892,9 +905,9 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
     for (int zq = 0; zq < KZ; ++zq)
 #pragma unroll
       for (int k = 0; k < KX / 4; ++k) {
-        int q4[4];
+        uint32_t q4[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) q4[e] = int(rintf(u[zq * 8 + k * 4 + e] * inv));
+        for (int e = 0; e < 4; ++e) q4[e] = bin_bits(u[zq * 8 + k * 4 + e], inv);
         const uint32_t pw = IdxPack<int8_t>::pack(q4);
         st32[(bb * KEPT + (zq * KY + j) * KX) / 4 + k] = pw;
         if constexpr (kStats) {

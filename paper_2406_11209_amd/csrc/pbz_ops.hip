@@ -110,13 +110,22 @@ __device__ __forceinline__ void unpack_dword(uint32_t x, double* out) {  // 4 / 
   }
 }
 
+// the low bytes (int8) or halves (int16) of 4 / 2 integers gathered into one dword by byte permutes
 template <int kIType>
 __device__ __forceinline__ uint32_t pack_dword(const int* v) {
-  if (kIType == PBZ_I8)
-    return (uint32_t(v[0]) & 0xffu) | ((uint32_t(v[1]) & 0xffu) << 8) | ((uint32_t(v[2]) & 0xffu) << 16) |
-           (uint32_t(v[3]) << 24);
-  if (kIType == PBZ_I16) return (uint32_t(v[0]) & 0xffffu) | (uint32_t(v[1]) << 16);
+  if (kIType == PBZ_I8) {
+    const uint32_t lo = __builtin_amdgcn_perm(uint32_t(v[1]), uint32_t(v[0]), 0x0c0c0400u);   // v0.b0, v1.b0
+    const uint32_t hi = __builtin_amdgcn_perm(uint32_t(v[3]), uint32_t(v[2]), 0x0c0c0400u);   // v2.b0, v3.b0
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+  }
+  if (kIType == PBZ_I16) return __builtin_amdgcn_perm(uint32_t(v[1]), uint32_t(v[0]), 0x05040100u);
   return uint32_t(v[0]);
+}
+
+// rint(t) as an integer for |t| < 2^31: adding 1.5 * 2^52 rounds t to an integer in the current (nearest-even)
+// mode and leaves that integer, in two's complement, in the low word of the sum
+__device__ __forceinline__ int rint_to_int(double t) {
+  return int(uint32_t(__builtin_bit_cast(uint64_t, t + 6755399441055744.0)));
 }
 
 // F1 N1 + F2 N2 with both products and the sum rounded separately (Algorithm 2 as printed): a fused
@@ -330,7 +339,7 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
       for (int e = 0; e < kPer; ++e) {
         // an all-zero block has n = inv = 0 and every c = 0: the three steps then give 0 without a division.
         // |C / N| <= r (1 + 2^-52), which rounds to at most r, so no clamp is needed.
-        q[e] = int(rint(div_by(c[w * kPer + e], n, inv)));
+        q[e] = rint_to_int(div_by(c[w * kPer + e], n, inv));
       }
       ow[w] = pack_dword<kIType>(q);
     }
@@ -420,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restr
       for (int e = 0; e < kPer; ++e) {
         // an all-zero block has m = inv_m = 0 and every c = 0, which gives 0; |C r / N| <= r (1 + 2^-51) rounds to
         // at most r, so neither a special case nor a clamp is needed
-        q[e] = int(rint(div_by(c[w * kPer + e] * r, m, inv_m)));
+        q[e] = rint_to_int(div_by(c[w * kPer + e] * r, m, inv_m));
       }
       ow[w] = pack_dword<kIType>(q);
     }
