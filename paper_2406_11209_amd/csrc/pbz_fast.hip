@@ -858,6 +858,8 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
   static_assert(KX == 4 || KX == 8, "a kept row is one or two dwords of int8");
   constexpr int KEPT = KZ * KY * KX;
   __shared__ uint4 lds[kOctWaves][8 * 64];
+  // a wave that is fetching its tile goes ahead of the waves that are busy transforming theirs
+  __builtin_amdgcn_s_setprio(3);
   const int lane = threadIdx.x & 63;
   int64_t tx, by, bz;
   if (!decode_tile<kOctWaves>(g, tx, by, bz)) return;
@@ -886,6 +888,7 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
       else
         raw[yy0] = load16_stream(x + (zz * g.Y + yy) * g.X + bxc * 8);
     }
+    __builtin_amdgcn_s_setprio(0);
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
       if constexpr (kRagged) {
