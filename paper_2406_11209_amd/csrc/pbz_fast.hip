@@ -7,9 +7,10 @@
 // cascade of pbz_haar.h (template switch TF), and writes N and F.  There is no workgroup barrier in the
 // compress kernels; LDS, where used, is private to a wave.
 //
-// Family "lane":   one lane owns one whole block (blocks of at most 64 elements: 8x8, 4x4x4).  Indices leave
-//                   through a wave-private LDS transpose when a block's F is 64 bytes or more, so that every
-//                   store instruction of the wave writes one contiguous span.
+// Family "lane":   one lane owns one whole block (blocks of at most 64 elements: 8x8, 4x4x4).  Where a block
+//                   row is two 16-byte pieces the two half-waves trade pieces, so that every load / store
+//                   instruction of the array covers one contiguous KiB.  Indices leave through a wave-private
+//                   LDS transpose when a block's F is 64 bytes or more, for the same reason.
 // Family "quad16":  16x16 and 4x16x16 blocks, 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
 //                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
 //                   then each lane holds four whole rows (row transform, and for 4x16x16 the transform across
@@ -594,7 +595,10 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
           // 2 KiB span.  The two half-waves trade pieces instead (lanes 32-63 hand the first piece of their row
           // to lanes 0-31 and take those lanes' second piece): the first store then writes the rows of blocks
           // 0-31 as one contiguous KiB, the second those of blocks 32-63 (workload 4: 0.251 -> 0.240 ms; with
-          // the non-temporal hint on top: 0.255 ms).
+          // the non-temporal hint on top: 0.255 ms).  The compiler hoists every row's trade above the first store
+          // (256 registers, two waves per SIMD): running the last transform pass row by row just before each
+          // row's stores brought that to 160 registers and three waves, and was slower (0.252 ms): a wave's
+          // 32 stores leaving back to back matter more than the third wave.
           uint4 h0 = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + 0) * PER16);
           uint4 h1 = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + 1) * PER16);
           swap_half_waves(h0.x, h1.x);
@@ -1249,6 +1253,14 @@ template <int TF> using Lane_f32_8x8_i16_box4 = LaneKernel<TF, double, float, in
 template <int TF> using Lane_f32_8x8_i16 = LaneKernel<TF, double, float, int16_t, float, 1, 8, 8, 1, 8, 8>;
 // 3-D 4x4x4, FP64 arrays, int16
 template <int TF> using Lane_f64_4x4x4_i16 = LaneKernel<TF, double, double, int16_t, double, 4, 4, 4, 4, 4, 4>;
+// the settings of the paper's own timing experiments that the workloads above do not cover (Sec. V-A: square 2-D
+// FP64 arrays in 8x8 blocks with int8 indices; hypercubic 2-D / 3-D arrays with int8 and int16 indices; cubic
+// arrays in blocks of 4)
+template <int TF> using Lane_f64_4x4x4_i8 = LaneKernel<TF, double, double, int8_t, double, 4, 4, 4, 4, 4, 4>;
+template <int TF> using Lane_f32_4x4x4_i8 = LaneKernel<TF, float, float, int8_t, float, 4, 4, 4, 4, 4, 4>;
+template <int TF> using Lane_f32_4x4x4_i16 = LaneKernel<TF, double, float, int16_t, float, 4, 4, 4, 4, 4, 4>;
+template <int TF> using Lane_f64_8x8_i8 = LaneKernel<TF, double, double, int8_t, double, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_f64_8x8_i16 = LaneKernel<TF, double, double, int16_t, double, 1, 8, 8, 1, 8, 8>;
 
 // 16x16 (2-D) and 4x16x16 blocks, FP32 arrays, int8, nothing pruned
 template <int TF, int BZ>
@@ -1350,6 +1362,11 @@ template <int TF> using Oct8_full = Oct8Kernel<TF, 8, 8, 8>;
   X(Lane_f32_8x8_i16_box4<TF>, "lane_f32_8x8_i16_box4x4" SUFFIX)       \
   X(Lane_f32_8x8_i16<TF>, "lane_f32_8x8_i16" SUFFIX)                   \
   X(Lane_f64_4x4x4_i16<TF>, "lane_f64_4x4x4_i16" SUFFIX)               \
+  X(Lane_f64_4x4x4_i8<TF>, "lane_f64_4x4x4_i8" SUFFIX)                 \
+  X(Lane_f32_4x4x4_i8<TF>, "lane_f32_4x4x4_i8" SUFFIX)                 \
+  X(Lane_f32_4x4x4_i16<TF>, "lane_f32_4x4x4_i16" SUFFIX)               \
+  X(Lane_f64_8x8_i8<TF>, "lane_f64_8x8_i8" SUFFIX)                     \
+  X(Lane_f64_8x8_i16<TF>, "lane_f64_8x8_i16" SUFFIX)                   \
   X(Quad16Kernel<TF COMMA 1>, "quad16_f32_16x16_i8" SUFFIX)            \
   X(Quad16Kernel<TF COMMA 4>, "quad16_f32_4x16x16_i8" SUFFIX)          \
   X(Oct8_box4<TF>, "oct8_bf16_8x8x8_i8_box4x4x4" SUFFIX)               \

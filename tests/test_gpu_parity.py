@@ -172,6 +172,19 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((9, 20, 37), (4, 16, 16), 8, "f32", "bf16", None, "quad16_f32_4x16x16_i8"),
                ((17, 9, 24), (8, 8, 8), 8, "bf16", "bf16", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 9, 520), (8, 8, 8), 8, "bf16", "f16", None, "oct8_bf16_8x8x8_i8"),
+               # the settings of the paper's own timing experiments (Sec. V-A): 2-D FP64 in 8x8 blocks, 3-D in blocks of 4
+               ((37, 64), (8, 8), 8, "f64", "f64", None, "lane_f64_8x8_i8"),
+               ((24, 1032), (8, 8), 8, "f64", "f64", None, "lane_f64_8x8_i8"),
+               ((21, 75), (8, 8), 8, "f64", "f64", None, "lane_f64_8x8_i8"),
+               ((37, 520), (8, 8), 16, "f64", "f64", None, "lane_f64_8x8_i16"),
+               ((16, 67), (8, 8), 16, "f64", "f64", None, "lane_f64_8x8_i16"),
+               ((40, 64), (8, 8), 16, "f64", "f32", None, "generic"),                 # FP64 array, N stored as FP32
+               ((5, 30, 20), (4, 4, 4), 8, "f64", "f64", None, "lane_f64_4x4x4_i8"),
+               ((9, 13, 262), (4, 4, 4), 8, "f64", "f64", None, "lane_f64_4x4x4_i8"),
+               ((9, 14, 24), (4, 4, 4), 8, "f32", "f32", None, "lane_f32_4x4x4_i8"),
+               ((5, 8, 1030), (4, 4, 4), 8, "f32", "f32", None, "lane_f32_4x4x4_i8"),
+               ((6, 30, 20), (4, 4, 4), 16, "f32", "f32", None, "lane_f32_4x4x4_i16"),
+               ((8, 9, 270), (4, 4, 4), 16, "f32", "f16", None, "lane_f32_4x4x4_i16"),
                # 49 and more blocks along x: the decompress variant that stores whole row pieces
                ((17, 9, 520), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 12, 392), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
@@ -196,6 +209,8 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((37, 72), (8, 8), 16, "f32", "f32", (4, 4), "lane_f32_8x8_i16_box4x4_haar"),
         ((24, 72), (8, 8), 16, "f32", "f32", None, "lane_f32_8x8_i16_haar"),
         ((9, 30, 40), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16_haar"),
+        ((21, 72), (8, 8), 8, "f64", "f64", None, "lane_f64_8x8_i8_haar"),
+        ((9, 14, 24), (4, 4, 4), 8, "f32", "f32", None, "lane_f32_4x4x4_i8_haar"),
         ((3, 33, 96), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8_haar"),
         ((17, 24, 72), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((16, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8_haar"),
