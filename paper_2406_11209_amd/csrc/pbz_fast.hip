@@ -8,8 +8,8 @@
 // compress kernels; LDS, where used, is private to a wave.
 //
 // Family "lane":   one lane owns one whole block (blocks of at most 64 elements: 8x8, 4x4x4).  Where a block
-//                   row is two 16-byte pieces the two half-waves trade pieces, so that every load / store
-//                   instruction of the array covers one contiguous KiB.  Indices leave through a wave-private
+//                   row is two (four) 16-byte pieces the half-waves (quarter-waves) trade pieces, so that every
+//                   load / store instruction of the array covers one contiguous KiB.  Indices leave through a wave-private
 //                   LDS transpose when a block's F is 64 bytes or more, for the same reason.
 // Family "quad16":  16x16 and 4x16x16 blocks, 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
 //                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
@@ -378,6 +378,21 @@ __device__ __forceinline__ void swap_half_waves(uint32_t& first, uint32_t& secon
   second = r[1];
 }
 
+// Rows 0-3 of 16 lanes each ("quarters"): afterwards piece k of quarter q is what was piece q of quarter k
+// (a 4 x 4 transpose between the piece index and the quarter index, in two rounds of pairwise trades; all 64
+// lanes must be active).  Its own inverse.
+__device__ __forceinline__ void swap_odd_even_rows(uint32_t& first, uint32_t& second) {
+  const auto r = __builtin_amdgcn_permlane16_swap(first, second, false, false);   // rows 1, 3 of first <-> rows 0, 2 of second
+  first = r[0];
+  second = r[1];
+}
+__device__ __forceinline__ void transpose_quarter_waves(uint4& p0, uint4& p1, uint4& p2, uint4& p3) {
+  swap_half_waves(p0.x, p2.x); swap_half_waves(p0.y, p2.y); swap_half_waves(p0.z, p2.z); swap_half_waves(p0.w, p2.w);
+  swap_half_waves(p1.x, p3.x); swap_half_waves(p1.y, p3.y); swap_half_waves(p1.z, p3.z); swap_half_waves(p1.w, p3.w);
+  swap_odd_even_rows(p0.x, p1.x); swap_odd_even_rows(p0.y, p1.y); swap_odd_even_rows(p0.z, p1.z); swap_odd_even_rows(p0.w, p1.w);
+  swap_odd_even_rows(p2.x, p3.x); swap_odd_even_rows(p2.y, p3.y); swap_odd_even_rows(p2.z, p3.z); swap_odd_even_rows(p2.w, p3.w);
+}
+
 // =====================================================================================================
 // Family "lane": one lane = one block
 // =====================================================================================================
@@ -426,12 +441,24 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
         const uint4* p = reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 2 * (lane & 31) + (lane >> 5);
         raw[(z * BY + y) * 2] = load16_stream(p);
         raw[(z * BY + y) * 2 + 1] = load16_stream(p + 64);
+      } else if (RV == 4 && whole_wave) {
+        // four pieces per block row: load j reads the rows of blocks 16j .. 16j+15 as one contiguous KiB (lane
+        // (quarter q, i) takes piece q of block 16j + i); the quarter transpose below sorts the pieces out
+        const uint4* p = reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 4 * (lane & 15) + (lane >> 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) raw[(z * BY + y) * RV + k] = load16_stream(p + 64 * k);
       } else {
         const uint4* p = reinterpret_cast<const uint4*>(x + (zz * g.Y + yy) * g.X + bxc * BX);
 #pragma unroll
         for (int k = 0; k < RV; ++k) raw[(z * BY + y) * RV + k] = load16_stream(&p[k]);
       }
     }
+  if constexpr (RV == 4 && !kTailX) {
+    if (whole_wave) {
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) transpose_quarter_waves(raw[4 * i], raw[4 * i + 1], raw[4 * i + 2], raw[4 * i + 3]);
+    }
+  }
   if constexpr (RV == 2 && !kTailX) {
     if (whole_wave) {
 #pragma unroll
@@ -608,6 +635,16 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
           uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 2 * (lane & 31) + (lane >> 5);
           p[0] = h0;
           p[64] = h1;
+        } else if (RV == 4 && whole_wave) {
+          // four pieces per block row: after the quarter transpose store j writes the rows of blocks
+          // 16j .. 16j+15 as one contiguous KiB
+          uint4 h[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) h[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+          transpose_quarter_waves(h[0], h[1], h[2], h[3]);
+          uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 4 * (lane & 15) + (lane >> 4);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) p[64 * k] = h[k];
         } else {
           // plain stores: a lane's pieces alternate with its neighbours' within a line, which the L2 merges into
           // whole lines; with the non-temporal hint these 16-byte pieces reach memory singly (measured: twice as
