@@ -132,3 +132,79 @@ def test_full_shape(config, capsys):
             b = (N1[(t + 1) * per:(t + 2) * per], F1[(t + 1) * per:(t + 2) * per])
             step.check_reductions(a[0], a[1], b[0], b[1], ("mean", "variance", "covariance"))
         full.check_reductions(N1, F1, N1, F1, ("norm2", "mean", "variance"))
+
+
+# More than 2^31 elements (and more than 2^32 bytes) in one array: every offset computed in the kernels has to be
+# 64 bits wide.  The arrays are drawn on the device (seeded) and only the sampled blocks come back to the host,
+# where the oracle compresses and decompresses them one by one.
+BEYOND_32_BITS = [((1040, 1536, 1536), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
+                  ((520, 2048, 2048), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
+                  ((3, 40000, 20000), (1, 16, 16), 16, "f32", "f32", None, "generic")]
+
+
+@pytest.mark.parametrize("spec", BEYOND_32_BITS, ids=[s[6] for s in BEYOND_32_BITS])
+def test_arrays_of_more_than_2_31_elements(spec, capsys):
+    shape, block, bits, dtype, ftype, keep, kernel = spec
+
+    def progress(msg):
+        with capsys.disabled():
+            print(f"[beyond 2^31, {kernel}] {msg}", flush=True)
+
+    assert int(np.prod(shape)) > 2 ** 31
+    progress("drawing the array on the device")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20240611)
+    x = torch.empty(shape, dtype=TORCH[dtype], device="cuda")
+    plane = int(np.prod(shape[1:]))
+    for z in range(shape[0]):          # plane by plane: no FP32 temporary of the whole array
+        x[z] = (torch.randn(plane, generator=gen, device="cuda", dtype=torch.float32) + 0.25).reshape(shape[1:]).to(TORCH[dtype])
+    mask = None if keep is None else synth.low_frequency_mask(block, keep)
+    codec = Codec(block, ftype, bits, mask)
+    assert codec.kernel_name("compress", shape, dtype) == kernel
+
+    def host_f64(t):
+        if dtype == "bf16":
+            return synth.bf16_bits_to_f32(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        return t.cpu().numpy().astype(np.float64)
+
+    grid = po.block_grid(shape, block)
+    P = np.ones(block, dtype=bool) if mask is None else mask
+    flat = sample_blocks(grid, 1500, seed=7)
+    progress("compress")
+    N, F = codec.compress(x)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(flat).cuda()
+    Nh, Fh = parity.to_host_f64(N[idx]), F[idx].cpu().numpy()
+    blocks = gather_blocks(lambda sl: host_f64(x[sl]), grid, block, flat)
+    N64, F_ref, t_ref = po.compress_blocks(blocks, block, bits, P)
+    parity.check_N(Nh, po.store_float(N64, ftype), ftype)
+    parity.check_indices(Fh, F_ref, t_ref, parity.tie_band(block, ftype, bits))
+
+    progress("decompress")
+    y = codec.decompress(N, F, shape, TORCH[dtype])
+    torch.cuda.synchronize()
+    got = gather_blocks(lambda sl: host_f64(y[sl]), grid, block, flat)
+    sub = po.Compressed(s=(len(flat) * block[0],) + tuple(block[1:]), i=tuple(block),
+                        N=Nh.reshape((len(flat),) + (1,) * (len(block) - 1)), F=Fh, P=P, index_bits=bits, ftype=ftype)
+    want = po.decompress(sub).reshape((len(flat),) + tuple(block))
+    scale = float(np.max(np.abs(want)))
+    want = np.where(inside(shape, grid, block, flat), want, 0.0)
+    tol = parity.value_tol(ftype)
+    if dtype == "bf16":
+        assert np.all(np.abs(got - want) <= 2.0 ** -8 * 1.01 * np.abs(want) + tol * scale)
+    else:
+        assert float(np.max(np.abs(got - want))) <= tol * scale
+    del y
+
+    # a reduction and an element-wise operation over the whole compressed array: the same statistic of its two halves
+    progress("norm2 and negate over the whole compressed array")
+    n_blocks = N.numel()
+    half = n_blocks // 2
+    whole = float(codec.norm2(N, F).item())
+    a = float(codec.norm2(N[:half], F[:half]).item())
+    b = float(codec.norm2(N[half:], F[half:]).item())
+    assert abs(whole - float(np.hypot(a, b))) <= 1e-12 * whole
+    picked = po.Compressed(s=sub.s, i=sub.i, N=sub.N, F=Fh, P=P, index_bits=bits, ftype=ftype)
+    G = codec.negate(F)
+    torch.cuda.synchronize()
+    assert np.array_equal(G[idx].cpu().numpy(), po.negate(picked).F)
