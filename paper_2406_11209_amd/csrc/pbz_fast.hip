@@ -15,7 +15,7 @@
 //                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
 //                   then each lane holds four whole rows (row transform, and for 4x16x16 the transform across
 //                   the four planes); rows leave as 16-byte pieces in linear order.
-// Family "oct8":    8x8x8 blocks of bfloat16 input, 8 blocks per wave.  Each lane first holds one z-plane of
+// Family "oct8":    8x8x8 blocks of bfloat16 or FP32 input, 8 blocks per wave.  Each lane first holds one z-plane of
 //                   a block (x and y transforms), the wave exchanges through LDS, then each lane holds one
 //                   y-row of all eight z-planes (z transform).  Decompression needs no exchange: every
 //                   lane rebuilds its own z-plane from the block's few kept coefficients; wide arrays use a
@@ -878,7 +878,7 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
 }
 
 // =====================================================================================================
-// Family "oct8": 3-D 8x8x8 blocks, bfloat16 arrays, FP32 arithmetic, int8 indices, low-frequency box kept
+// Family "oct8": 3-D 8x8x8 blocks, bfloat16 or FP32 arrays, FP32 arithmetic, int8 indices, low-frequency box kept
 // =====================================================================================================
 // LDS exchange, done in two rounds (left and right half of every 8-element row) so that a wave needs 8 KiB
 // instead of 16 KiB and twice as many waves fit a CU (the kernel is latency-bound: halving its occupancy
@@ -892,12 +892,14 @@ __device__ __forceinline__ int oct_slot(int b, int yy, int z) {
 
 constexpr int kOctWaves = 4;   // waves per workgroup: neighbouring tiles, so that a workgroup reads 512-byte row pieces
 
-template <int TF, int KZ, int KY, int KX, bool kRagged, bool kStats, bool kTailX = false>
-__global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, const bf16_t* __restrict__ x,
+template <int TF, typename XT, int KZ, int KY, int KX, bool kRagged, bool kStats, bool kTailX = false>
+__global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, const XT* __restrict__ x,
                                                                   void* __restrict__ N, int8_t* __restrict__ F,
                                                                   double* __restrict__ tile_sums) {
   static_assert(KX == 4 || KX == 8, "a kept row is one or two dwords of int8");
   constexpr int KEPT = KZ * KY * KX;
+  constexpr int PER16 = Unpack<float, XT>::n;     // elements per 16-byte piece: 8 (bfloat16) or 4 (FP32)
+  constexpr int RV = 8 / PER16;                   // pieces per block row
   __shared__ uint4 lds[kOctWaves][8 * 64];
   // a wave that is fetching its tile goes ahead of the waves that are busy transforming theirs
   __builtin_amdgcn_s_setprio(3);
@@ -919,24 +921,32 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
       keep_z = zz < g.Z ? 0xffffffffu : 0u;      // planes / rows past the end: load a valid row, zero it below
       zz = zz < g.Z ? zz : g.Z - 1;
     }
-    uint4 raw[8];
+    uint4 raw[8 * RV];
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
       int64_t yy = by * 8 + yy0;
       if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;
-      if constexpr (kTailX)
-        raw[yy0] = load16_a4(x + (zz * g.Y + yy) * g.X + (bxc * 8 + 8 <= g.X ? bxc * 8 : g.X - 8));
-      else
-        raw[yy0] = load16_stream(x + (zz * g.Y + yy) * g.X + bxc * 8);
+#pragma unroll
+      for (int k = 0; k < RV; ++k) {
+        const int64_t x0 = bxc * 8 + k * PER16;
+        if constexpr (kTailX)
+          raw[yy0 * RV + k] = load16_a4(x + (zz * g.Y + yy) * g.X + (x0 + PER16 <= g.X ? x0 : g.X - PER16));
+        else
+          raw[yy0 * RV + k] = load16_stream(x + (zz * g.Y + yy) * g.X + x0);
+      }
     }
     __builtin_amdgcn_s_setprio(0);
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
-      if constexpr (kRagged) {
-        const uint32_t keep = by * 8 + yy0 < g.Y ? keep_z : 0u;
-        raw[yy0].x &= keep; raw[yy0].y &= keep; raw[yy0].z &= keep; raw[yy0].w &= keep;
+#pragma unroll
+      for (int k = 0; k < RV; ++k) {
+        uint4& piece = raw[yy0 * RV + k];
+        if constexpr (kRagged) {
+          const uint32_t keep = by * 8 + yy0 < g.Y ? keep_z : 0u;
+          piece.x &= keep; piece.y &= keep; piece.z &= keep; piece.w &= keep;
+        }
+        Unpack<float, XT>::run(piece, v + yy0 * 8 + k * PER16);
       }
-      Unpack<float, bf16_t>::run(raw[yy0], v + yy0 * 8);
     }
     if constexpr (kTailX) {
       if (bxc * 8 + 8 > g.X) {         // the row's last, partial block: element by element, zeros beyond
@@ -944,11 +954,11 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
         for (int yy0 = 0; yy0 < 8; ++yy0) {
           const int64_t yy = by * 8 + yy0;
           const bool row_in = yy < g.Y && keep_z != 0u;
-          const bf16_t* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+          const XT* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const int64_t xi = bxc * 8 + e;
-            const float val = Elem<float, bf16_t>::load(row + (xi < g.X ? xi : g.X - 1));
+            const float val = Elem<float, XT>::load(row + (xi < g.X ? xi : g.X - 1));
             v[yy0 * 8 + e] = row_in && xi < g.X ? val : 0.0f;
           }
         }
@@ -1027,9 +1037,43 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // hardwar
   return __builtin_bit_cast(uint32_t, h);
 }
 
-template <int TF, int KZ, int KY, int KX, bool kTailX = false>
+// 16 bytes of an output row from FP32 values: bfloat16 through the hardware conversion
+template <typename XT>
+__device__ __forceinline__ uint4 oct_pack(const float* v) {
+  if constexpr (sizeof(XT) == 2)
+    return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+  else
+    return Pack<float, XT>::run(v);
+}
+
+// the eight values r8 of block bx's row at `row`: whole 16-byte pieces where they fit, single elements otherwise
+template <typename XT, bool kTailX>
+__device__ __forceinline__ void oct_store_row(const FastGeom& g, XT* row, int64_t bx, const float* r8) {
+  constexpr int PER16 = Unpack<float, XT>::n;
+#pragma unroll
+  for (int k = 0; k < 8 / PER16; ++k) {
+    const int64_t x0 = bx * 8 + k * PER16;
+    if constexpr (kTailX) {
+      if (x0 + PER16 <= g.X) {
+        store16_a4(row + x0, oct_pack<XT>(r8 + k * PER16));
+      } else {
+#pragma unroll
+        for (int e = 0; e < PER16; ++e)
+          if (x0 + e < g.X) Elem<float, XT>::store(row + x0 + e, r8[k * PER16 + e]);
+      }
+    } else if constexpr (PER16 == 8) {
+      store16_stream(row + x0, oct_pack<XT>(r8 + k * PER16));       // the lanes' pieces are contiguous: whole lines
+    } else {
+      // two pieces per lane, 32 bytes apart: plain stores, which the L2 merges into whole lines (with the
+      // non-temporal hint such pieces reach memory singly)
+      *reinterpret_cast<uint4*>(row + x0) = oct_pack<XT>(r8 + k * PER16);
+    }
+  }
+}
+
+template <int TF, typename XT, int KZ, int KY, int KX, bool kTailX = false>
 __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const void* __restrict__ N,
-                                                         const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
+                                                         const int8_t* __restrict__ F, XT* __restrict__ y) {
   constexpr int KEPT = KZ * KY * KX;
   static_assert(KEPT % 16 == 0, "F blocks are whole 16-byte vectors");
   const int lane = threadIdx.x & 63;
@@ -1074,24 +1118,7 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const void*
 #pragma unroll
   for (int yy0 = 0; yy0 < 8; ++yy0) {
     const int64_t yy = by * 8 + yy0;
-    if (yy < g.Y) {
-      const float* r8 = v + yy0 * 8;
-      const uint4 packed = make_uint4(pack_bf16x2(r8[0], r8[1]), pack_bf16x2(r8[2], r8[3]), pack_bf16x2(r8[4], r8[5]),
-                                      pack_bf16x2(r8[6], r8[7]));
-      if constexpr (kTailX) {
-        bf16_t* row = y + (zz * g.Y + yy) * g.X;
-        if (bx * 8 + 8 <= g.X) {
-          store16_a4(row + bx * 8, packed);
-        } else {
-          const uint32_t pw[4] = {packed.x, packed.y, packed.z, packed.w};
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (bx * 8 + e < g.X) row[bx * 8 + e].bits = uint16_t(pw[e >> 1] >> (16 * (e & 1)));
-        }
-      } else {
-        store16_stream(y + (zz * g.Y + yy) * g.X + bx * 8, packed);
-      }
-    }
+    if (yy < g.Y) oct_store_row<XT, kTailX>(g, y + (zz * g.Y + yy) * g.X, bx, v + yy0 * 8);
   }
 }
 
@@ -1099,9 +1126,9 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const void*
 // rebuilds plane z of all of them (lane = block), so that every store instruction writes one whole contiguous
 // 1 KiB row piece (measured 6.6 TB/s for this store pattern against 5.7 TB/s for the 128-byte pieces above);
 // the plane index is uniform over the wave, so its matrix row comes from scalar loads.
-template <int TF, int KZ, int KY, int KX, bool kTailX = false>
+template <int TF, typename XT, int KZ, int KY, int KX, bool kTailX = false>
 __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const void* __restrict__ N,
-                                                              const int8_t* __restrict__ F, bf16_t* __restrict__ y) {
+                                                              const int8_t* __restrict__ F, XT* __restrict__ y) {
   constexpr int KEPT = KZ * KY * KX;
   static_assert(KEPT % 16 == 0, "F blocks are whole 16-byte vectors");
   const int lane = threadIdx.x & 63;
@@ -1113,6 +1140,7 @@ __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const 
   const int64_t bx = tx * 64 + lane;
   const int64_t zz = bz * 8 + z;
   if (bx >= g.gx || zz >= g.Z) return;
+  const bool whole_wave = tx * 64 + 64 <= int64_t(g.gx);     // uniform: no lane has left
   const int64_t block = (bz * g.gy + by) * g.gx + bx;
 
   uint32_t w[KEPT / 4];
@@ -1148,24 +1176,23 @@ __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const 
 #pragma unroll
   for (int yy0 = 0; yy0 < 8; ++yy0) {
     const int64_t yy = by * 8 + yy0;
-    if (yy < g.Y) {
-      const float* r8 = v + yy0 * 8;
-      const uint4 packed = make_uint4(pack_bf16x2(r8[0], r8[1]), pack_bf16x2(r8[2], r8[3]), pack_bf16x2(r8[4], r8[5]),
-                                      pack_bf16x2(r8[6], r8[7]));
-      if constexpr (kTailX) {
-        bf16_t* row = y + (zz * g.Y + yy) * g.X;
-        if (bx * 8 + 8 <= g.X) {
-          store16_a4(row + bx * 8, packed);
-        } else {
-          const uint32_t pw[4] = {packed.x, packed.y, packed.z, packed.w};
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (bx * 8 + e < g.X) row[bx * 8 + e].bits = uint16_t(pw[e >> 1] >> (16 * (e & 1)));
-        }
-      } else {
-        store16_stream(y + (zz * g.Y + yy) * g.X + bx * 8, packed);
+    if (yy >= g.Y) continue;
+    if constexpr (sizeof(XT) == 4 && !kTailX) {
+      if (whole_wave) {
+        // FP32 rows are two 16-byte pieces per block: the half-waves trade pieces so that each store writes one
+        // contiguous KiB (the rows of 32 blocks)
+        uint4 h0 = oct_pack<XT>(v + yy0 * 8), h1 = oct_pack<XT>(v + yy0 * 8 + 4);
+        swap_half_waves(h0.x, h1.x);
+        swap_half_waves(h0.y, h1.y);
+        swap_half_waves(h0.z, h1.z);
+        swap_half_waves(h0.w, h1.w);
+        uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * 8) + 2 * (lane & 31) + (lane >> 5);
+        store16_stream(p, h0);
+        store16_stream(p + 64, h1);
+        continue;
       }
     }
+    oct_store_row<XT, kTailX>(g, y + (zz * g.Y + yy) * g.X, bx, v + yy0 * 8);
   }
 }
 
@@ -1343,12 +1370,13 @@ struct Quad16Kernel {
   }
 };
 
-// 3-D 8x8x8 bfloat16 arrays, FP32 arithmetic and N, int8, box KZ x KY x KX kept
-template <int TF, int KZ, int KY, int KX>
+// 3-D 8x8x8 bfloat16 or FP32 arrays, FP32 arithmetic and N, int8, box KZ x KY x KX kept
+template <int TF, typename XT, int KZ, int KY, int KX>
 struct Oct8Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_BF16 && c->itype == PBZ_I8 && c->ftype != PBZ_F64 && f.bz == 8 &&
-           f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX && x_extent_ok(f, 8, 2);
+    return f.ok && c->transform == TF && !c->compute_f64 && xtype == xtype_code<XT>() && c->itype == PBZ_I8 &&
+           c->ftype != PBZ_F64 && f.bz == 8 && f.by == 8 && f.bx == 8 && f.kz == KZ && f.ky == KY && f.kx == KX &&
+           x_extent_ok(f, 16 / int(sizeof(XT)), int(sizeof(XT)));
   }
   static int fits(FastGeom g) {
     dim3 grid;
@@ -1360,8 +1388,8 @@ struct Oct8Kernel {
   }
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_oct8<TF, KZ, KY, KX, kRagged, kStats, kTailX>), grid, dim3(kOctWaves * 64), 0, s, g,
-                       static_cast<const bf16_t*>(x), N, static_cast<int8_t*>(F), tile_sums);
+    hipLaunchKernelGGL((k_compress_oct8<TF, XT, KZ, KY, KX, kRagged, kStats, kTailX>), grid, dim3(kOctWaves * 64), 0, s, g,
+                       static_cast<const XT*>(x), N, static_cast<int8_t*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
@@ -1376,22 +1404,24 @@ struct Oct8Kernel {
     dim3 grid;
     const void* n = N;
     const int8_t* f = static_cast<const int8_t*>(F);
-    bf16_t* out = static_cast<bf16_t*>(y);
+    XT* out = static_cast<XT*>(y);
     const bool tail = g.X % 8 != 0;
     if (g.gx >= 48) {        // at least three quarters of the lanes of a 64-block tile busy
       if (!tile_grid(g, 64, 1, &grid)) return 0;
-      if (tail) hipLaunchKernelGGL((k_decompress_oct8_rows<TF, KZ, KY, KX, true>), grid, dim3(512), 0, s, g, n, f, out);
-      else hipLaunchKernelGGL((k_decompress_oct8_rows<TF, KZ, KY, KX, false>), grid, dim3(512), 0, s, g, n, f, out);
+      if (tail) hipLaunchKernelGGL((k_decompress_oct8_rows<TF, XT, KZ, KY, KX, true>), grid, dim3(512), 0, s, g, n, f, out);
+      else hipLaunchKernelGGL((k_decompress_oct8_rows<TF, XT, KZ, KY, KX, false>), grid, dim3(512), 0, s, g, n, f, out);
     } else {
       if (!tile_grid(g, 8, 4, &grid)) return 0;
-      if (tail) hipLaunchKernelGGL((k_decompress_oct8<TF, KZ, KY, KX, true>), grid, dim3(256), 0, s, g, n, f, out);
-      else hipLaunchKernelGGL((k_decompress_oct8<TF, KZ, KY, KX, false>), grid, dim3(256), 0, s, g, n, f, out);
+      if (tail) hipLaunchKernelGGL((k_decompress_oct8<TF, XT, KZ, KY, KX, true>), grid, dim3(256), 0, s, g, n, f, out);
+      else hipLaunchKernelGGL((k_decompress_oct8<TF, XT, KZ, KY, KX, false>), grid, dim3(256), 0, s, g, n, f, out);
     }
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
-template <int TF> using Oct8_box4 = Oct8Kernel<TF, 4, 4, 4>;
-template <int TF> using Oct8_full = Oct8Kernel<TF, 8, 8, 8>;
+template <int TF> using Oct8_box4 = Oct8Kernel<TF, bf16_t, 4, 4, 4>;
+template <int TF> using Oct8_full = Oct8Kernel<TF, bf16_t, 8, 8, 8>;
+template <int TF> using Oct8_f32_box4 = Oct8Kernel<TF, float, 4, 4, 4>;
+template <int TF> using Oct8_f32_full = Oct8Kernel<TF, float, 8, 8, 8>;
 
 #define COMMA ,
 #define PBZ_FOR_EACH_SHAPE(X, TF, SUFFIX)                             \
@@ -1407,7 +1437,9 @@ template <int TF> using Oct8_full = Oct8Kernel<TF, 8, 8, 8>;
   X(Quad16Kernel<TF COMMA 1>, "quad16_f32_16x16_i8" SUFFIX)            \
   X(Quad16Kernel<TF COMMA 4>, "quad16_f32_4x16x16_i8" SUFFIX)          \
   X(Oct8_box4<TF>, "oct8_bf16_8x8x8_i8_box4x4x4" SUFFIX)               \
-  X(Oct8_full<TF>, "oct8_bf16_8x8x8_i8" SUFFIX)
+  X(Oct8_full<TF>, "oct8_bf16_8x8x8_i8" SUFFIX)                        \
+  X(Oct8_f32_box4<TF>, "oct8_f32_8x8x8_i8_box4x4x4" SUFFIX)            \
+  X(Oct8_f32_full<TF>, "oct8_f32_8x8x8_i8" SUFFIX)
 // every shape for the DCT (plain names) and for the Haar transform (names ending in _haar)
 #define PBZ_FOR_EACH_LANE_KERNEL(X)    \
   PBZ_FOR_EACH_SHAPE(X, kTfDct, "")    \

@@ -185,6 +185,13 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((5, 8, 1030), (4, 4, 4), 8, "f32", "f32", None, "lane_f32_4x4x4_i8"),
                ((6, 30, 20), (4, 4, 4), 16, "f32", "f32", None, "lane_f32_4x4x4_i16"),
                ((8, 9, 270), (4, 4, 4), 16, "f32", "f16", None, "lane_f32_4x4x4_i16"),
+               # 8x8x8 blocks of FP32 arrays
+               ((17, 9, 24), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
+               ((9, 17, 200), (8, 8, 8), 8, "f32", "f32", None, "oct8_f32_8x8x8_i8"),
+               ((9, 9, 1032), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),   # whole waves in the row variant
+               ((9, 12, 398), (8, 8, 8), 8, "f32", "f16", None, "oct8_f32_8x8x8_i8"),
+               ((17, 9, 21), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
+               ((8, 8, 515), (8, 8, 8), 8, "f32", "bf16", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
                # 49 and more blocks along x: the decompress variant that stores whole row pieces
                ((17, 9, 520), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 12, 392), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
@@ -214,6 +221,7 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((3, 33, 96), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8_haar"),
         ((17, 24, 72), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((16, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8_haar"),
+        ((9, 9, 520), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4_haar"),
         ((9, 9, 512), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((9, 20, 48), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
         ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
