@@ -15,7 +15,7 @@
 //                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
 //                   then each lane holds four whole rows (row transform, and for 4x16x16 the transform across
 //                   the four planes); rows leave as 16-byte pieces in linear order.
-// Family "oct8":    8x8x8 blocks of bfloat16 or FP32 input, 8 blocks per wave.  Each lane first holds one z-plane of
+// Family "oct8":    8x8x8 blocks of bfloat16, FP16 or FP32 input, 8 blocks per wave.  Each lane first holds one z-plane of
 //                   a block (x and y transforms), the wave exchanges through LDS, then each lane holds one
 //                   y-row of all eight z-planes (z transform).  Decompression needs no exchange: every
 //                   lane rebuilds its own z-plane from the block's few kept coefficients; wide arrays use a
@@ -108,6 +108,20 @@ struct Unpack<T, bf16_t> {
   }
 };
 
+struct f16_t { uint16_t bits; };
+template <typename T>
+struct Unpack<T, f16_t> {
+  static constexpr int n = 8;
+  static __device__ __forceinline__ void run(const uint4& u, T* o) {
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = T(float(__builtin_bit_cast(_Float16, uint16_t(w[i] & 0xffffu))));
+      o[2 * i + 1] = T(float(__builtin_bit_cast(_Float16, uint16_t(w[i] >> 16))));
+    }
+  }
+};
+
 template <typename T, typename XT>
 struct Pack;     // T[16 / sizeof(XT)] -> 16 bytes of XT, round to nearest even
 template <typename T>
@@ -132,6 +146,18 @@ struct Pack<float, bf16_t> {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       w[i] = uint32_t(float_to_bf16_bits(v[2 * i])) | (uint32_t(float_to_bf16_bits(v[2 * i + 1])) << 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+template <>
+struct Pack<float, f16_t> {
+  static __device__ __forceinline__ uint4 run(const float* v) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      w[i] = uint32_t(__builtin_bit_cast(uint16_t, _Float16(v[2 * i]))) |
+             (uint32_t(__builtin_bit_cast(uint16_t, _Float16(v[2 * i + 1]))) << 16);
     return make_uint4(w[0], w[1], w[2], w[3]);
   }
 };
@@ -206,6 +232,12 @@ template <typename T>
 struct Elem<T, bf16_t> {
   static __device__ __forceinline__ T load(const bf16_t* p) { return T(bf16_bits_to_float(p->bits)); }
   static __device__ __forceinline__ void store(bf16_t* p, T v) { p->bits = float_to_bf16_bits(float(v)); }
+};
+
+template <typename T>
+struct Elem<T, f16_t> {
+  static __device__ __forceinline__ T load(const f16_t* p) { return T(float(__builtin_bit_cast(_Float16, p->bits))); }
+  static __device__ __forceinline__ void store(f16_t* p, T v) { p->bits = __builtin_bit_cast(uint16_t, _Float16(float(v))); }
 };
 
 template <typename T>
@@ -878,7 +910,7 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
 }
 
 // =====================================================================================================
-// Family "oct8": 3-D 8x8x8 blocks, bfloat16 or FP32 arrays, FP32 arithmetic, int8 indices, low-frequency box kept
+// Family "oct8": 3-D 8x8x8 blocks, bfloat16, FP16 or FP32 arrays, FP32 arithmetic, int8 indices, low-frequency box kept
 // =====================================================================================================
 // LDS exchange, done in two rounds (left and right half of every 8-element row) so that a wave needs 8 KiB
 // instead of 16 KiB and twice as many waves fit a CU (the kernel is latency-bound: halving its occupancy
@@ -1040,7 +1072,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // hardwar
 // 16 bytes of an output row from FP32 values: bfloat16 through the hardware conversion
 template <typename XT>
 __device__ __forceinline__ uint4 oct_pack(const float* v) {
-  if constexpr (sizeof(XT) == 2)
+  if constexpr (std::is_same<XT, bf16_t>::value)
     return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
   else
     return Pack<float, XT>::run(v);
@@ -1260,6 +1292,7 @@ constexpr int xtype_code();
 template <> constexpr int xtype_code<float>() { return PBZ_F32; }
 template <> constexpr int xtype_code<double>() { return PBZ_F64; }
 template <> constexpr int xtype_code<bf16_t>() { return PBZ_BF16; }
+template <> constexpr int xtype_code<f16_t>() { return PBZ_F16; }
 template <typename IT>
 constexpr int itype_code();
 template <> constexpr int itype_code<int8_t>() { return PBZ_I8; }
@@ -1313,6 +1346,8 @@ struct LaneKernel {
 
 // 2-D 8x8, FP32 arrays: int8 (FP32 arithmetic), int16 (FP64 arithmetic) with all 64 or the 4x4 low-frequency box kept
 template <int TF> using Lane_f32_8x8_i8 = LaneKernel<TF, float, float, int8_t, float, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_bf16_8x8_i8 = LaneKernel<TF, float, bf16_t, int8_t, float, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_f16_8x8_i8 = LaneKernel<TF, float, f16_t, int8_t, float, 1, 8, 8, 1, 8, 8>;
 template <int TF> using Lane_f32_8x8_i16_box4 = LaneKernel<TF, double, float, int16_t, float, 1, 8, 8, 1, 4, 4>;
 template <int TF> using Lane_f32_8x8_i16 = LaneKernel<TF, double, float, int16_t, float, 1, 8, 8, 1, 8, 8>;
 // 3-D 4x4x4, FP64 arrays, int16
@@ -1422,10 +1457,14 @@ template <int TF> using Oct8_box4 = Oct8Kernel<TF, bf16_t, 4, 4, 4>;
 template <int TF> using Oct8_full = Oct8Kernel<TF, bf16_t, 8, 8, 8>;
 template <int TF> using Oct8_f32_box4 = Oct8Kernel<TF, float, 4, 4, 4>;
 template <int TF> using Oct8_f32_full = Oct8Kernel<TF, float, 8, 8, 8>;
+template <int TF> using Oct8_f16_box4 = Oct8Kernel<TF, f16_t, 4, 4, 4>;
+template <int TF> using Oct8_f16_full = Oct8Kernel<TF, f16_t, 8, 8, 8>;
 
 #define COMMA ,
 #define PBZ_FOR_EACH_SHAPE(X, TF, SUFFIX)                             \
   X(Lane_f32_8x8_i8<TF>, "lane_f32_8x8_i8" SUFFIX)                     \
+  X(Lane_bf16_8x8_i8<TF>, "lane_bf16_8x8_i8" SUFFIX)                   \
+  X(Lane_f16_8x8_i8<TF>, "lane_f16_8x8_i8" SUFFIX)                     \
   X(Lane_f32_8x8_i16_box4<TF>, "lane_f32_8x8_i16_box4x4" SUFFIX)       \
   X(Lane_f32_8x8_i16<TF>, "lane_f32_8x8_i16" SUFFIX)                   \
   X(Lane_f64_4x4x4_i16<TF>, "lane_f64_4x4x4_i16" SUFFIX)               \
@@ -1439,7 +1478,9 @@ template <int TF> using Oct8_f32_full = Oct8Kernel<TF, float, 8, 8, 8>;
   X(Oct8_box4<TF>, "oct8_bf16_8x8x8_i8_box4x4x4" SUFFIX)               \
   X(Oct8_full<TF>, "oct8_bf16_8x8x8_i8" SUFFIX)                        \
   X(Oct8_f32_box4<TF>, "oct8_f32_8x8x8_i8_box4x4x4" SUFFIX)            \
-  X(Oct8_f32_full<TF>, "oct8_f32_8x8x8_i8" SUFFIX)
+  X(Oct8_f32_full<TF>, "oct8_f32_8x8x8_i8" SUFFIX)                     \
+  X(Oct8_f16_box4<TF>, "oct8_f16_8x8x8_i8_box4x4x4" SUFFIX)            \
+  X(Oct8_f16_full<TF>, "oct8_f16_8x8x8_i8" SUFFIX)
 // every shape for the DCT (plain names) and for the Haar transform (names ending in _haar)
 #define PBZ_FOR_EACH_LANE_KERNEL(X)    \
   PBZ_FOR_EACH_SHAPE(X, kTfDct, "")    \

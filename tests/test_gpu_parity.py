@@ -185,6 +185,14 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((5, 8, 1030), (4, 4, 4), 8, "f32", "f32", None, "lane_f32_4x4x4_i8"),
                ((6, 30, 20), (4, 4, 4), 16, "f32", "f32", None, "lane_f32_4x4x4_i16"),
                ((8, 9, 270), (4, 4, 4), 16, "f32", "f16", None, "lane_f32_4x4x4_i16"),
+               # 16-bit arrays in 8x8 and 8x8x8 blocks
+               ((37, 64), (8, 8), 8, "bf16", "f32", None, "lane_bf16_8x8_i8"),
+               ((21, 1046), (8, 8), 8, "bf16", "bf16", None, "lane_bf16_8x8_i8"),
+               ((40, 72), (8, 8), 8, "f16", "f32", None, "lane_f16_8x8_i8"),
+               ((19, 530), (8, 8), 8, "f16", "f16", None, "lane_f16_8x8_i8"),
+               ((17, 9, 24), (8, 8, 8), 8, "f16", "f32", (4, 4, 4), "oct8_f16_8x8x8_i8_box4x4x4"),
+               ((9, 9, 518), (8, 8, 8), 8, "f16", "f16", (4, 4, 4), "oct8_f16_8x8x8_i8_box4x4x4"),
+               ((9, 12, 64), (8, 8, 8), 8, "f16", "f32", None, "oct8_f16_8x8x8_i8"),
                # 8x8x8 blocks of FP32 arrays
                ((17, 9, 24), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
                ((9, 17, 200), (8, 8, 8), 8, "f32", "f32", None, "oct8_f32_8x8x8_i8"),
@@ -202,7 +210,8 @@ def test_specialised_kernels_on_ragged_shapes(spec):
     shape, block, bits, dtype, ftype, keep, kernel = spec
     g = rng(300 + len(shape) + bits)
     mk = lambda: synth.bump_field(shape, 6, g, (2.0, 8.0)) + 0.2 + 0.01 * g.standard_normal(shape)
-    cast = {"f64": lambda a: a, "f32": lambda a: a.astype(np.float32), "bf16": synth.to_bf16_bits}[dtype]
+    cast = {"f64": lambda a: a, "f32": lambda a: a.astype(np.float32), "bf16": synth.to_bf16_bits,
+            "f16": lambda a: a.astype(np.float16)}[dtype]
     mask = None if keep is None else synth.low_frequency_mask(block, keep)
     case = Case(cast(mk()), cast(mk()), dtype, block, bits, ftype, mask, api.PBZ_PATH_AUTO)
     assert case.codec.kernel_name("compress", shape, dtype) == kernel
