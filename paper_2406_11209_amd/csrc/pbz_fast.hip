@@ -11,7 +11,7 @@
 //                   row is two (four) 16-byte pieces the half-waves (quarter-waves) trade pieces, so that every
 //                   load / store instruction of the array covers one contiguous KiB.  Indices leave through a wave-private
 //                   LDS transpose when a block's F is 64 bytes or more, for the same reason.
-// Family "quad16":  16x16 and 4x16x16 blocks, 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
+// Family "quad16":  16x16 and 4x16x16 blocks of FP32 or 16-bit input, 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
 //                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
 //                   then each lane holds four whole rows (row transform, and for 4x16x16 the transform across
 //                   the four planes); rows leave as 16-byte pieces in linear order.
@@ -162,6 +162,14 @@ struct Pack<float, f16_t> {
   }
 };
 
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // hardware conversion, round to nearest even
+  float2v f = {a, b};
+  bf16x2 h = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
 // ---- binning and index packing ------------------------------------------------------------------------
 // rint(t * inv) without a rounding and a conversion instruction: one fused multiply-add onto 1.5 * 2^23 (FP32;
 // 1.5 * 2^52 in FP64) rounds the exact product to an integer in the nearest-even mode and leaves that integer,
@@ -213,6 +221,7 @@ __device__ __forceinline__ void store16_stream(void* p, const uint4& u) {
   const u32x4 t = {u.x, u.y, u.z, u.w};
   __builtin_nontemporal_store(t, static_cast<u32x4*>(p));
 }
+
 struct __attribute__((packed, aligned(4))) uint4_a4 { uint32_t x, y, z, w; };
 __device__ __forceinline__ uint4 load16_a4(const void* p) {
   const uint4_a4 v = *static_cast<const uint4_a4*>(p);
@@ -223,6 +232,87 @@ __device__ __forceinline__ void store16_a4(void* p, const uint4& u) {
   v.x = u.x; v.y = u.y; v.z = u.z; v.w = u.w;
   *static_cast<uint4_a4*>(p) = v;
 }
+
+__device__ __forceinline__ uint4 f4_bits(const float* v) {
+  return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+}
+__device__ __forceinline__ void bits_f4(const uint4& u, float* v) {
+  v[0] = __uint_as_float(u.x); v[1] = __uint_as_float(u.y); v[2] = __uint_as_float(u.z); v[3] = __uint_as_float(u.w);
+}
+
+// Four consecutive array elements as one piece: 16 bytes of FP32, 8 bytes of a 16-bit type.  kTailX: the piece
+// is only known to start on a 4-byte boundary.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+struct __attribute__((packed, aligned(4))) U2A4 { uint32_t x, y; };
+template <typename XT>
+struct Quad4;
+template <>
+struct Quad4<float> {
+  typedef uint4 raw_t;
+  template <bool kTailX>
+  static __device__ __forceinline__ raw_t load(const float* p) { return kTailX ? load16_a4(p) : load16_stream(p); }
+  template <bool kTailX>
+  static __device__ __forceinline__ void store(float* p, const raw_t& r) {
+    if constexpr (kTailX) store16_a4(p, r); else store16_stream(p, r);
+  }
+  static __device__ __forceinline__ void keep(raw_t& r, uint32_t m) { r.x &= m; r.y &= m; r.z &= m; r.w &= m; }
+  static __device__ __forceinline__ void unpack(const raw_t& r, float* v) { bits_f4(r, v); }
+  static __device__ __forceinline__ raw_t pack(const float* v) { return f4_bits(v); }
+};
+template <typename XT>
+struct Quad4Half {                      // XT = bf16_t or f16_t
+  typedef uint2 raw_t;
+  template <bool kTailX>
+  static __device__ __forceinline__ raw_t load(const XT* p) {
+    if constexpr (kTailX) {
+      const U2A4 t = *reinterpret_cast<const U2A4*>(p);
+      return make_uint2(t.x, t.y);
+    } else {
+      const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+      return make_uint2(t.x, t.y);
+    }
+  }
+  template <bool kTailX>
+  static __device__ __forceinline__ void store(XT* p, const raw_t& r) {
+    if constexpr (kTailX) {
+      U2A4 t;
+      t.x = r.x; t.y = r.y;
+      *reinterpret_cast<U2A4*>(p) = t;
+    } else {
+      const u32x2 t = {r.x, r.y};
+      __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+    }
+  }
+  static __device__ __forceinline__ void keep(raw_t& r, uint32_t m) { r.x &= m; r.y &= m; }
+  static __device__ __forceinline__ void unpack(const raw_t& r, float* v) {
+    const uint32_t w[2] = {r.x, r.y};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      if constexpr (std::is_same<XT, bf16_t>::value) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      } else {
+        v[2 * i] = float(__builtin_bit_cast(_Float16, uint16_t(w[i] & 0xffffu)));
+        v[2 * i + 1] = float(__builtin_bit_cast(_Float16, uint16_t(w[i] >> 16)));
+      }
+    }
+  }
+  static __device__ __forceinline__ raw_t pack(const float* v) {
+    if constexpr (std::is_same<XT, bf16_t>::value) {
+      return make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    } else {
+      uint32_t w[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        w[i] = uint32_t(__builtin_bit_cast(uint16_t, _Float16(v[2 * i]))) |
+               (uint32_t(__builtin_bit_cast(uint16_t, _Float16(v[2 * i + 1]))) << 16);
+      return make_uint2(w[0], w[1]);
+    }
+  }
+};
+template <> struct Quad4<bf16_t> : Quad4Half<bf16_t> {};
+template <> struct Quad4<f16_t> : Quad4Half<f16_t> {};
+
 template <typename T, typename XT>
 struct Elem {   // one element: float and double arrays
   static __device__ __forceinline__ T load(const XT* p) { return T(*p); }
@@ -329,12 +419,6 @@ __device__ __forceinline__ void emit_tile_sums(double* __restrict__ tile_sums, c
   }
 }
 
-__device__ __forceinline__ uint4 f4_bits(const float* v) {
-  return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
-}
-__device__ __forceinline__ void bits_f4(const uint4& u, float* v) {
-  v[0] = __uint_as_float(u.x); v[1] = __uint_as_float(u.y); v[2] = __uint_as_float(u.z); v[3] = __uint_as_float(u.w);
-}
 
 // H[m][q] of the length-8 orthonormal DCT-II as a compile-time table (for lane-dependent rows)
 struct Dct8Table {
@@ -691,7 +775,7 @@ __global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void*
 
 
 // =====================================================================================================
-// Family "quad16": BZ x 16 x 16 blocks with BZ = 1 (2-D) or 4, FP32 arrays, FP32 arithmetic, int8 indices,
+// Family "quad16": BZ x 16 x 16 blocks with BZ = 1 (2-D) or 4, FP32 / FP16 / bfloat16 arrays, FP32 arithmetic, int8 indices,
 // nothing pruned
 // =====================================================================================================
 // A wave works on 16 planes of 16 x 16 samples: plane p = 4 j + s (j, s in 0..3).  For BZ = 1 these are 16
@@ -707,9 +791,10 @@ struct QuadMap {
   static __device__ __forceinline__ int plane_of(int p) { return BZ == 1 ? 0 : (p >> 2); }
 };
 
-template <int TF, int BZ, bool kRagged, bool kStats, bool kTailX = false>
-__global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float* __restrict__ x, void* __restrict__ N,
+template <int TF, typename XT, int BZ, bool kRagged, bool kStats, bool kTailX = false>
+__global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* __restrict__ x, void* __restrict__ N,
                                                          int8_t* __restrict__ F, double* __restrict__ tile_sums) {
+  using Q4 = Quad4<XT>;
   static_assert(BZ == 1 || BZ == 4, "one plane or four");
   using Map = QuadMap<BZ>;
   constexpr int BPW = Map::kBlocksPerWave;
@@ -731,25 +816,19 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
       zz = zz < g.Z ? zz : g.Z - 1;
     }
     float v[64];
-    uint4 raw[16];
+    typename Q4::raw_t raw[16];
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       int64_t yy = by * 16 + yy0;
       if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;     // rows past the end: load a valid row, zero it below
-      if constexpr (kTailX) {
-        const int64_t x0 = bxc * 16 + q * 4;
-        raw[yy0] = load16_a4(x + (zz * g.Y + yy) * g.X + (x0 + 4 <= g.X ? x0 : g.X - 4));
-      } else {
-        raw[yy0] = load16_stream(x + (zz * g.Y + yy) * g.X + bxc * 16 + q * 4);
-      }
+      int64_t x0 = bxc * 16 + q * 4;
+      if constexpr (kTailX) x0 = x0 + 4 <= g.X ? x0 : g.X - 4;
+      raw[yy0] = Q4::template load<kTailX>(x + (zz * g.Y + yy) * g.X + x0);
     }
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
-      if constexpr (kRagged) {
-        const uint32_t keep = by * 16 + yy0 < g.Y ? keep_z : 0u;
-        raw[yy0].x &= keep; raw[yy0].y &= keep; raw[yy0].z &= keep; raw[yy0].w &= keep;
-      }
-      bits_f4(raw[yy0], v + yy0 * 4);
+      if constexpr (kRagged) Q4::keep(raw[yy0], by * 16 + yy0 < g.Y ? keep_z : 0u);
+      Q4::unpack(raw[yy0], v + yy0 * 4);
     }
     if constexpr (kTailX) {
       const int64_t x0 = bxc * 16 + q * 4;
@@ -758,11 +837,11 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
         for (int yy0 = 0; yy0 < 16; ++yy0) {
           const int64_t yy = by * 16 + yy0;
           const bool row_in = yy < g.Y && keep_z != 0u;
-          const float* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+          const XT* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int64_t xi = x0 + e;
-            const float val = row[xi < g.X ? xi : g.X - 1];
+            const float val = Elem<float, XT>::load(row + (xi < g.X ? xi : g.X - 1));
             v[yy0 * 4 + e] = row_in && xi < g.X ? val : 0.0f;
           }
         }
@@ -832,9 +911,10 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const float
   if constexpr (kStats) emit_tile_sums(tile_sums, g, tx, by, bz, s11, d1);
 }
 
-template <int TF, int BZ, bool kTailX = false>
+template <int TF, typename XT, int BZ, bool kTailX = false>
 __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const void* __restrict__ N,
-                                                           const int8_t* __restrict__ F, float* __restrict__ y) {
+                                                           const int8_t* __restrict__ F, XT* __restrict__ y) {
+  using Q4 = Quad4<XT>;
   using Map = QuadMap<BZ>;
   constexpr int BPW = Map::kBlocksPerWave;
   __shared__ uint4 lds[2][16 * kQuadRow];
@@ -892,17 +972,17 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
       const int64_t yy = by * 16 + yy0;
       if (yy < g.Y) {
         if constexpr (kTailX) {
-          float* row = y + (zz * g.Y + yy) * g.X;
+          XT* row = y + (zz * g.Y + yy) * g.X;
           const int64_t x0 = bx * 16 + q * 4;
           if (x0 + 4 <= g.X) {
-            store16_a4(row + x0, f4_bits(v + yy0 * 4));
+            Q4::template store<true>(row + x0, Q4::pack(v + yy0 * 4));
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (x0 + e < g.X) row[x0 + e] = v[yy0 * 4 + e];
+              if (x0 + e < g.X) Elem<float, XT>::store(row + x0 + e, v[yy0 * 4 + e]);
           }
         } else {
-          store16_stream(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4, f4_bits(v + yy0 * 4));
+          Q4::template store<false>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4, Q4::pack(v + yy0 * 4));
         }
       }
     }
@@ -1059,14 +1139,6 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
     if (p < PIECES && tx * 8 + p / PPB < g.gx) reinterpret_cast<uint4*>(F + block0 * KEPT)[p] = st[p];
   }
   if (j == 0 && tx * 8 + bb < g.gx) store_float(N, g.ntype, block0 + bb, m);
-}
-
-typedef float float2v __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // hardware conversion, round to nearest even
-  float2v f = {a, b};
-  bf16x2 h = __builtin_convertvector(f, bf16x2);
-  return __builtin_bit_cast(uint32_t, h);
 }
 
 // 16 bytes of an output row from FP32 values: bfloat16 through the hardware conversion
@@ -1361,14 +1433,14 @@ template <int TF> using Lane_f32_4x4x4_i16 = LaneKernel<TF, double, float, int16
 template <int TF> using Lane_f64_8x8_i8 = LaneKernel<TF, double, double, int8_t, double, 1, 8, 8, 1, 8, 8>;
 template <int TF> using Lane_f64_8x8_i16 = LaneKernel<TF, double, double, int16_t, double, 1, 8, 8, 1, 8, 8>;
 
-// 16x16 (2-D) and 4x16x16 blocks, FP32 arrays, int8, nothing pruned
-template <int TF, int BZ>
+// 16x16 (2-D) and 4x16x16 blocks, FP32 / bfloat16 / FP16 arrays, int8, nothing pruned
+template <int TF, typename XT, int BZ>
 struct Quad16Kernel {
   static constexpr int kBlocksPerWave = BZ == 1 ? 16 : 4;
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && c->transform == TF && !c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I8 &&
+    return f.ok && c->transform == TF && !c->compute_f64 && xtype == xtype_code<XT>() && c->itype == PBZ_I8 &&
            c->ftype != PBZ_F64 && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
-           x_extent_ok(f, 4, 4);
+           x_extent_ok(f, 4, int(sizeof(XT)));
   }
   static int fits(FastGeom g) {
     dim3 grid;
@@ -1380,8 +1452,8 @@ struct Quad16Kernel {
   }
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_quad16<TF, BZ, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
-                       static_cast<const float*>(x), N, static_cast<int8_t*>(F), tile_sums);
+    hipLaunchKernelGGL((k_compress_quad16<TF, XT, BZ, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
+                       static_cast<const XT*>(x), N, static_cast<int8_t*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
@@ -1396,11 +1468,11 @@ struct Quad16Kernel {
     dim3 grid;
     if (!tile_grid(g, kBlocksPerWave, 2, &grid)) return 0;
     if (g.X % 16)
-      hipLaunchKernelGGL((k_decompress_quad16<TF, BZ, true>), grid, dim3(128), 0, s, g, N,
-                         static_cast<const int8_t*>(F), static_cast<float*>(y));
+      hipLaunchKernelGGL((k_decompress_quad16<TF, XT, BZ, true>), grid, dim3(128), 0, s, g, N,
+                         static_cast<const int8_t*>(F), static_cast<XT*>(y));
     else
-      hipLaunchKernelGGL((k_decompress_quad16<TF, BZ, false>), grid, dim3(128), 0, s, g, N,
-                         static_cast<const int8_t*>(F), static_cast<float*>(y));
+      hipLaunchKernelGGL((k_decompress_quad16<TF, XT, BZ, false>), grid, dim3(128), 0, s, g, N,
+                         static_cast<const int8_t*>(F), static_cast<XT*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
@@ -1473,8 +1545,11 @@ template <int TF> using Oct8_f16_full = Oct8Kernel<TF, f16_t, 8, 8, 8>;
   X(Lane_f32_4x4x4_i16<TF>, "lane_f32_4x4x4_i16" SUFFIX)               \
   X(Lane_f64_8x8_i8<TF>, "lane_f64_8x8_i8" SUFFIX)                     \
   X(Lane_f64_8x8_i16<TF>, "lane_f64_8x8_i16" SUFFIX)                   \
-  X(Quad16Kernel<TF COMMA 1>, "quad16_f32_16x16_i8" SUFFIX)            \
-  X(Quad16Kernel<TF COMMA 4>, "quad16_f32_4x16x16_i8" SUFFIX)          \
+  X(Quad16Kernel<TF COMMA float COMMA 1>, "quad16_f32_16x16_i8" SUFFIX)            \
+  X(Quad16Kernel<TF COMMA float COMMA 4>, "quad16_f32_4x16x16_i8" SUFFIX)          \
+  X(Quad16Kernel<TF COMMA f16_t COMMA 1>, "quad16_f16_16x16_i8" SUFFIX)            \
+  X(Quad16Kernel<TF COMMA bf16_t COMMA 1>, "quad16_bf16_16x16_i8" SUFFIX)          \
+  X(Quad16Kernel<TF COMMA f16_t COMMA 4>, "quad16_f16_4x16x16_i8" SUFFIX)          \
   X(Oct8_box4<TF>, "oct8_bf16_8x8x8_i8_box4x4x4" SUFFIX)               \
   X(Oct8_full<TF>, "oct8_bf16_8x8x8_i8" SUFFIX)                        \
   X(Oct8_f32_box4<TF>, "oct8_f32_8x8x8_i8_box4x4x4" SUFFIX)            \

@@ -193,6 +193,14 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((17, 9, 24), (8, 8, 8), 8, "f16", "f32", (4, 4, 4), "oct8_f16_8x8x8_i8_box4x4x4"),
                ((9, 9, 518), (8, 8, 8), 8, "f16", "f16", (4, 4, 4), "oct8_f16_8x8x8_i8_box4x4x4"),
                ((9, 12, 64), (8, 8, 8), 8, "f16", "f32", None, "oct8_f16_8x8x8_i8"),
+               ((3, 33, 48), (1, 16, 16), 8, "f16", "f32", None, "quad16_f16_16x16_i8"),
+               ((2, 19, 560), (1, 16, 16), 8, "f16", "f16", None, "quad16_f16_16x16_i8"),
+               ((2, 35, 1046), (1, 16, 16), 8, "f16", "f32", None, "quad16_f16_16x16_i8"),     # rows start on 4-byte boundaries only
+               ((40, 1040), (16, 16), 8, "bf16", "f32", None, "quad16_bf16_16x16_i8"),
+               ((21, 78), (16, 16), 8, "bf16", "bf16", None, "quad16_bf16_16x16_i8"),
+               ((9, 40, 64), (4, 16, 16), 8, "f16", "f32", None, "quad16_f16_4x16x16_i8"),
+               ((10, 33, 150), (4, 16, 16), 8, "f16", "f32", None, "quad16_f16_4x16x16_i8"),
+               ((3, 33, 47), (1, 16, 16), 8, "f16", "f32", None, "generic"),                  # odd 16-bit rows: 2-byte aligned
                # 8x8x8 blocks of FP32 arrays
                ((17, 9, 24), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
                ((9, 17, 200), (8, 8, 8), 8, "f32", "f32", None, "oct8_f32_8x8x8_i8"),
@@ -234,6 +242,7 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((9, 9, 512), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((9, 20, 48), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
         ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
+        ((3, 33, 96), (1, 16, 16), 8, "f16", "f32", None, "quad16_f16_16x16_i8_haar"),
         ((9, 6, 26), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((9, 20, 36), (2, 16, 16), 8, "f32", "f32", None, "generic"),
         ((50, 21), (2, 32), 16, "f64", "f64", None, "generic")]
@@ -245,7 +254,8 @@ def test_haar_transform(spec, path):
     shape, block, bits, dtype, ftype, keep, kernel = spec
     g = rng(400 + len(shape) + bits)
     mk = lambda: synth.bump_field(shape, 6, g, (2.0, 8.0)) + 0.2 + 0.01 * g.standard_normal(shape)
-    cast = {"f64": lambda a: a, "f32": lambda a: a.astype(np.float32), "bf16": synth.to_bf16_bits}[dtype]
+    cast = {"f64": lambda a: a, "f32": lambda a: a.astype(np.float32), "bf16": synth.to_bf16_bits,
+            "f16": lambda a: a.astype(np.float16)}[dtype]
     mask = None if keep is None else synth.low_frequency_mask(block, keep)
     case = Case(cast(mk()), cast(mk()), dtype, block, bits, ftype, mask, path, transform="haar")
     want = kernel if path == api.PBZ_PATH_AUTO else "generic"
