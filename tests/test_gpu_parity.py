@@ -472,3 +472,44 @@ def test_unaligned_subranges_take_the_general_kernels():
     Ns, Fs = N[1:5], F[1:5]                                      # N view is 4-byte aligned only
     sub.shape = (8, 32)
     sub.check_reductions(Ns, Fs, Ns, Fs, ("dot", "norm2", "mean", "variance"))
+
+
+# Seeded random settings (dimensionality, block shape, array shape with and without ragged edges and wide last
+# dimensions, array / working / index types, low-frequency masks, both transforms) through every operation:
+# specialised and general kernels as the dispatch picks them.
+def random_settings(g):
+    nd = int(g.integers(1, 5))
+    pick = int(g.integers(0, 8))
+    fixed = {0: (8, 8), 1: (16, 16), 2: (4, 4, 4), 3: (8, 8, 8), 4: (4, 16, 16), 5: (1, 16, 16)}
+    block = fixed[pick] if pick in fixed else tuple(int(2 ** g.integers(0, 4 if nd > 2 else 6)) for _ in range(nd))
+    while int(np.prod(block)) > 4096:
+        block = block[:-1] + (max(1, block[-1] // 2),)
+    shape = tuple(int(g.integers(1, 5) * b + (g.integers(0, b) if g.integers(0, 2) else 0)) for b in block)
+    if g.integers(0, 3) == 0:        # wide last dimension: whole waves of blocks
+        shape = shape[:-1] + (int(block[-1] * g.integers(60, 140) + (g.integers(0, block[-1]) if g.integers(0, 2) else 0)),)
+    dtype = ["f32", "f64", "bf16", "f16"][int(g.integers(0, 4))]
+    ftype = "f64" if dtype == "f64" and g.integers(0, 3) else ["f32", "f32", "f16", "bf16"][int(g.integers(0, 4))]
+    bits = [8, 8, 16, 16, 32][int(g.integers(0, 5))]
+    keep = tuple(max(1, b // 2) for b in block) if g.integers(0, 3) == 0 else None
+    transform = "haar" if g.integers(0, 4) == 0 else "dct"
+    return shape, block, bits, dtype, ftype, keep, transform
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_settings(seed, capsys):
+    g = rng(9000 + seed)
+    kernels = set()
+    for n in range(60):
+        shape, block, bits, dtype, ftype, keep, transform = random_settings(g)
+        if int(np.prod(shape)) > 2_000_000:
+            continue
+        with capsys.disabled():      # name the case before it touches the GPU
+            print(f"[random settings {seed}.{n}] {shape} {block} i{bits} {dtype} {ftype} keep={keep} {transform}", flush=True)
+        mk = lambda: synth.bump_field(shape, 5, g, (2.0, 8.0)) + 0.2 + 0.01 * g.standard_normal(shape)
+        cast = {"f64": lambda a: a, "f32": lambda a: a.astype(np.float32), "bf16": synth.to_bf16_bits,
+                "f16": lambda a: a.astype(np.float16)}[dtype]
+        mask = None if keep is None else synth.low_frequency_mask(block, keep)
+        case = Case(cast(mk()), cast(mk()), dtype, block, bits, ftype, mask, api.PBZ_PATH_AUTO, transform=transform)
+        kernels.add(case.codec.kernel_name("compress", shape, dtype))
+        run_all_ops(case)
+    assert "generic" in kernels and len(kernels) > 3       # the draw reaches specialised and general kernels alike
