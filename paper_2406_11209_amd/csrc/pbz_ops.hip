@@ -490,13 +490,16 @@ __global__ __launch_bounds__(kThreads) void k_blockwise_vec(const void* __restri
     const bool live = v < nvec;
     const int64_t vc = live ? v : nvec - 1;
     const int64_t k = vc >> lanes_shift;
-    const uint4 a = F1[vc];
+    uint4 a = F1[vc];
     const uint4 b = kTwo ? F2[vc] : a;
     const double n1 = load_N<kNType>(N1, k, n_f16 != 0);
     const double n2 = kTwo ? load_N<kNType>(N2, k, n_f16 != 0) : n1;
     const bool head = (vc & (lanes - 1)) == 0;
-    double sum = dot_vec<kIType>(a, b);          // exact integer sum
-    if (head) sum -= double(first_element<kIType>(a.x)) * double(first_element<kIType>(b.x));
+    // the first coefficient is left out by clearing it in one operand (subtracting its product afterwards would
+    // cancel, and with 32-bit indices, whose products exceed 53 bits, could leave a negative sum under a root)
+    constexpr uint32_t kRest = kIType == PBZ_I8 ? 0xffffff00u : (kIType == PBZ_I16 ? 0xffff0000u : 0u);
+    a.x = head ? (a.x & kRest) : a.x;
+    double sum = dot_vec<kIType>(a, b);          // integer sum (exact for int8 / int16)
     for (int off = lanes >> 1; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
     if (live && head) {
       double res = sum * (n1 * n2) * scale;

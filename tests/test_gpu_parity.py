@@ -513,3 +513,21 @@ def test_random_settings(seed, capsys):
         kernels.add(case.codec.kernel_name("compress", shape, dtype))
         run_all_ops(case)
     assert "generic" in kernels and len(kernels) > 3       # the draw reaches specialised and general kernels alike
+
+
+def test_blockwise_std_of_constant_blocks_with_32_bit_indices():
+    """Blocks whose only non-zero coefficient is the first one, binned to +-(2^31 - 1): the squares of such indices
+    do not fit 53 bits, and the block-wise variance must still come out as exactly zero (its root not NaN)."""
+    g = rng(77)
+    per_block = g.uniform(-2.0, 2.0, size=(6, 40))
+    x = np.kron(per_block, np.ones((2, 2)))                       # every 2x2 block constant
+    for dtype, ftype in (("f64", "f64"), ("f32", "f32")):
+        case = Case(x.astype({"f64": np.float64, "f32": np.float32}[dtype]), None, dtype, (2, 2), 32, ftype)
+        N, F = case.codec.compress(case.xA)
+        torch.cuda.synchronize()
+        Fh = F.cpu().numpy()
+        assert np.all(np.abs(Fh[:, 0].astype(np.int64)) == 2 ** 31 - 1) and not Fh[:, 1:].any()
+        for name in ("blockwise_variance", "blockwise_std"):
+            got = getattr(case.codec, name)(N, F).cpu().numpy()
+            assert np.array_equal(got, np.zeros_like(got)), name
+        case.check_blockwise(N, F, N, F)
