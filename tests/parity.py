@@ -93,10 +93,11 @@ def check_indices(F_gpu: np.ndarray, F_ref: np.ndarray, t_ref: np.ndarray, tau: 
     # only 2^-22, so a half-integer in exact arithmetic can sit a few 1e-7 from one in the oracle's t.
     exact = np.maximum(EXACT_TIE, 4.0 * np.abs(t_ref[bad]) * 2.0 ** -52)
     n_counted = int((dist > exact).sum())
-    frac = n_counted / diff.size
-    allowed = max(1.0 / diff.size, max_fraction)
-    assert frac <= allowed, (f"{what}: {n_counted} of {diff.size} indices differ at inexact ties ({frac:.2e} > "
-                             f"{allowed:.2e}); {n_bad - n_counted} more at exact ties")
+    # the cap is a rate: on a small array the count it allows gets three standard deviations of counting noise
+    expected = max_fraction * diff.size
+    allowed = max(1, int(math.ceil(expected + 3.0 * math.sqrt(expected))))
+    assert n_counted <= allowed, (f"{what}: {n_counted} of {diff.size} indices differ at inexact ties (cap "
+                                  f"{max_fraction:.0e} allows {allowed}); {n_bad - n_counted} more at exact ties")
     return n_bad
 
 
