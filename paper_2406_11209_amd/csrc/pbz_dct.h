@@ -7,7 +7,8 @@
 // outputs are 1/sqrt(2) times the length-n/2 transform of s and the odd outputs are a dense (n/2 x n/2)
 // product with d.  Recursing costs 12 / 36 / 116 multiply-adds for n = 4 / 8 / 16 instead of the dense
 // 16 / 64 / 256.  Everything is unrolled at compile time so that the data stays in registers; the scale
-// factors are folded into the constants.
+// factors are folded into the constants.  The functions also compile for the host, where a test runs them
+// against an independent construction of the transform matrices.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -19,14 +20,14 @@ namespace dct {
 
 // compile-time loop: f(std::integral_constant<int, i>) for i = 0 .. N-1, so that i can index constexpr tables
 template <int I, int N, typename F>
-__device__ __forceinline__ void static_for_impl(F&& f) {
+__host__ __device__ __forceinline__ void static_for_impl(F&& f) {
   if constexpr (I < N) {
     f(std::integral_constant<int, I>{});
     static_for_impl<I + 1, N>(f);
   }
 }
 template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
+__host__ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl<0, N>(f);
 }
 
@@ -88,7 +89,7 @@ constexpr double scale_of(int halvings) {
 // Forward transform of v[0], v[S], ..., v[(n-1)S] in place; result is scale_of(H) * DCT_n.
 template <typename T, int n, int S, int H>
 struct Fwd {
-  static __device__ __forceinline__ void run(T* v) {
+  static __host__ __device__ __forceinline__ void run(T* v) {
     constexpr int h = n / 2;
     T s[h], d[h];
 #pragma unroll
@@ -113,13 +114,13 @@ struct Fwd {
 };
 template <typename T, int S, int H>
 struct Fwd<T, 1, S, H> {
-  static __device__ __forceinline__ void run(T* v) {
+  static __host__ __device__ __forceinline__ void run(T* v) {
     if (H != 0) v[0] *= T(scale_of(H));
   }
 };
 template <typename T, int S, int H>
 struct Fwd<T, 2, S, H> {
-  static __device__ __forceinline__ void run(T* v) {
+  static __host__ __device__ __forceinline__ void run(T* v) {
     T a = v[0], b = v[S];
     v[0] = (a + b) * T(scale_of(H + 1));
     v[S] = (a - b) * T(scale_of(H + 1));
@@ -130,7 +131,7 @@ struct Fwd<T, 2, S, H> {
 // Result is scale_of(H) * IDCT_n.
 template <typename T, int n, int S, int H, int K>
 struct Inv {
-  static __device__ __forceinline__ void run(T* v) {
+  static __host__ __device__ __forceinline__ void run(T* v) {
     constexpr int h = n / 2;
     constexpr int Ke = (K + 1) / 2;  // non-zero even-indexed inputs
     constexpr int Ko = K / 2;        // non-zero odd-indexed inputs
@@ -161,7 +162,7 @@ struct Inv {
 };
 template <typename T, int S, int H, int K>
 struct Inv<T, 1, S, H, K> {
-  static __device__ __forceinline__ void run(T* v) {
+  static __host__ __device__ __forceinline__ void run(T* v) {
     if (K == 0)
       v[0] = T(0);
     else if (H != 0)
@@ -170,7 +171,7 @@ struct Inv<T, 1, S, H, K> {
 };
 template <typename T, int S, int H, int K>
 struct Inv<T, 2, S, H, K> {
-  static __device__ __forceinline__ void run(T* v) {
+  static __host__ __device__ __forceinline__ void run(T* v) {
     T a = K > 0 ? v[0] * T(scale_of(H + 1)) : T(0);
     T b = K > 1 ? v[S] * T(scale_of(H + 1)) : T(0);
     v[0] = a + b;
@@ -179,11 +180,11 @@ struct Inv<T, 2, S, H, K> {
 };
 
 template <typename T, int n, int S>
-__device__ __forceinline__ void forward(T* v) {
+__host__ __device__ __forceinline__ void forward(T* v) {
   Fwd<T, n, S, 0>::run(v);
 }
 template <typename T, int n, int S, int K>
-__device__ __forceinline__ void inverse(T* v) {
+__host__ __device__ __forceinline__ void inverse(T* v) {
   Inv<T, n, S, 0, K>::run(v);
 }
 

@@ -70,12 +70,12 @@ __host__ __device__ __forceinline__ void inverse(T* v) {
 // transform selector used by the kernels: kTf = 0 the DCT, 1 the Haar transform
 constexpr int kTfDct = 0, kTfHaar = 1;
 template <int kTf, typename T, int n, int S>
-__device__ __forceinline__ void tf_forward(T* v) {
+__host__ __device__ __forceinline__ void tf_forward(T* v) {
   if constexpr (kTf == kTfHaar) haar::forward<T, n, S>(v);
   else dct::forward<T, n, S>(v);
 }
 template <int kTf, typename T, int n, int S, int K>
-__device__ __forceinline__ void tf_inverse(T* v) {
+__host__ __device__ __forceinline__ void tf_inverse(T* v) {
   if constexpr (kTf == kTfHaar) haar::inverse<T, n, S, K>(v);
   else dct::inverse<T, n, S, K>(v);
 }
