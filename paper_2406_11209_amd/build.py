@@ -15,7 +15,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpbz.so")
 EXAMPLE = os.path.join(PKG, "c_abi_roundtrip")
-SOURCES = ["pbz_api.hip", "pbz_generic.hip", "pbz_ops.hip", "pbz_fast.hip", "pbz_wasserstein.hip", "pbz_tiled.hip"]
+SOURCES = ["pbz_api.hip", "pbz_generic.hip", "pbz_ops.hip", "pbz_fast.hip", "pbz_fast_lane.hip", "pbz_fast_quad16.hip",
+           "pbz_fast_oct8.hip", "pbz_wasserstein.hip", "pbz_tiled.hip"]
 
 # Packed-FP32 code generation is switched off on purpose (the flag applies to the device pass; the host
 # pass prints a harmless "unknown feature" warning).
@@ -46,7 +47,7 @@ def build(verbose: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
     cmds = [[cc] + FLAGS + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
-    with ThreadPoolExecutor(max_workers=4) as pool:
+    with ThreadPoolExecutor(max_workers=6) as pool:
         for out in pool.map(_run, cmds):
             if verbose and out.strip():
                 print(out)

@@ -1,0 +1,280 @@
+// Specialised codec kernels, family "quad16" (see pbz_fast.hip for the overview).
+#include "pbz_fast_common.h"
+
+namespace pbz {
+namespace fast {
+namespace {
+
+// =====================================================================================================
+// Family "quad16": BZ x 16 x 16 blocks with BZ = 1 (2-D) or 4, FP32 / FP16 / bfloat16 arrays, FP32 arithmetic, int8 indices,
+// nothing pruned
+// =====================================================================================================
+// A wave works on 16 planes of 16 x 16 samples: plane p = 4 j + s (j, s in 0..3).  For BZ = 1 these are 16
+// consecutive blocks; for BZ = 4 they are the four z-planes (j) of four consecutive blocks (s), so that the lane
+// which holds one row of planes j = 0..3 of block s after the exchange can transform along z in registers.
+constexpr int kQuadRow = 65;   // uint4 per LDS row: 64 + 1 of padding so that column reads spread over the banks
+
+template <int BZ>
+struct QuadMap {
+  static constexpr int kBlocksPerWave = BZ == 1 ? 16 : 4;
+  // plane p of the wave: which block (relative to the wave's first) and which z-plane of it
+  static __device__ __forceinline__ int block_of(int p) { return BZ == 1 ? p : (p & 3); }
+  static __device__ __forceinline__ int plane_of(int p) { return BZ == 1 ? 0 : (p >> 2); }
+};
+
+template <int TF, typename XT, int BZ, bool kRagged, bool kStats, bool kTailX = false>
+__global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* __restrict__ x, void* __restrict__ N,
+                                                         int8_t* __restrict__ F, double* __restrict__ tile_sums) {
+  using Q4 = Quad4<XT>;
+  static_assert(BZ == 1 || BZ == 4, "one plane or four");
+  using Map = QuadMap<BZ>;
+  constexpr int BPW = Map::kBlocksPerWave;
+  __shared__ uint4 lds[2][16 * kQuadRow];
+  const int lane = threadIdx.x & 63;
+  int64_t tx, by, bz;
+  if (!decode_tile<2>(g, tx, by, bz)) return;
+  uint4* st = lds[threadIdx.x >> 6];
+
+  // phase A: lane = (plane p, column quarter q); strip of 16 rows x 4 columns; transform along y
+  {
+    const int p = lane >> 2, q = lane & 3;
+    const int64_t bx = tx * BPW + Map::block_of(p);
+    const int64_t bxc = bx < g.gx ? bx : g.gx - 1;
+    int64_t zz = bz * BZ + Map::plane_of(p);
+    uint32_t keep_z = 0xffffffffu;
+    if constexpr (kRagged && BZ > 1) {
+      keep_z = zz < g.Z ? 0xffffffffu : 0u;                   // planes past the end: load a valid one, zero it below
+      zz = zz < g.Z ? zz : g.Z - 1;
+    }
+    float v[64];
+    typename Q4::raw_t raw[16];
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      int64_t yy = by * 16 + yy0;
+      if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;     // rows past the end: load a valid row, zero it below
+      int64_t x0 = bxc * 16 + q * 4;
+      if constexpr (kTailX) x0 = x0 + 4 <= g.X ? x0 : g.X - 4;
+      raw[yy0] = Q4::template load<kTailX>(x + (zz * g.Y + yy) * g.X + x0);
+    }
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      if constexpr (kRagged) Q4::keep(raw[yy0], by * 16 + yy0 < g.Y ? keep_z : 0u);
+      Q4::unpack(raw[yy0], v + yy0 * 4);
+    }
+    if constexpr (kTailX) {
+      const int64_t x0 = bxc * 16 + q * 4;
+      if (x0 + 4 > g.X) {              // a piece of the row's last, partial block: element by element, zeros beyond
+#pragma unroll
+        for (int yy0 = 0; yy0 < 16; ++yy0) {
+          const int64_t yy = by * 16 + yy0;
+          const bool row_in = yy < g.Y && keep_z != 0u;
+          const XT* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int64_t xi = x0 + e;
+            const float val = Elem<float, XT>::load(row + (xi < g.X ? xi : g.X - 1));
+            v[yy0 * 4 + e] = row_in && xi < g.X ? val : 0.0f;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int xl = 0; xl < 4; ++xl) tf_forward<TF, float, 16, 4>(v + xl);
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) st[yy0 * kQuadRow + lane] = f4_bits(v + yy0 * 4);
+  }
+  wave_lds_sync();
+  // phase B: lane = (row yrow, s); four whole rows, row yrow of planes 4 j + s; transform along x (and z)
+  const int yrow = lane & 15, bsub = lane >> 4;
+  float u[64];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int xq = 0; xq < 4; ++xq) bits_f4(st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq], u + j * 16 + xq * 4);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) tf_forward<TF, float, 16, 1>(u + j * 16);
+  if constexpr (BZ == 4) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tf_forward<TF, float, 4, 16>(u + i);
+  }
+
+  const int64_t block0 = (bz * g.gy + by) * g.gx + tx * BPW;
+  double s11 = 0.0, d1 = 0.0;
+  float m4 = 0.0f;                                     // BZ = 4: the block's maximum over its four planes
+  if constexpr (BZ == 4) {
+#pragma unroll
+    for (int i = 0; i < 64; ++i) m4 = fmaxf(m4, fabsf(u[i]));
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) m4 = fmaxf(m4, __shfl_xor(m4, off, 64));
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float m = m4;
+    if constexpr (BZ == 1) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(u[j * 16 + i]));
+#pragma unroll
+      for (int off = 1; off < 16; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));   // the 16 rows of the block
+    }
+    const float inv = m > 0.0f ? float(g.r) / m : 0.0f;
+    uint32_t w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      uint32_t q4[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) q4[e] = bin_bits(u[j * 16 + k * 4 + e], inv);
+      w[k] = IdxPack<int8_t>::pack(q4);
+    }
+    const int blk = Map::block_of(4 * j + bsub);
+    if (tx * BPW + blk < g.gx) {
+      // the wave's pieces of F are linear in the lane: 16 consecutive pieces per (plane, block)
+      const int piece = BZ == 1 ? yrow : j * 16 + yrow;
+      reinterpret_cast<uint4*>(F + (block0 + blk) * (BZ * 256))[piece] = make_uint4(w[0], w[1], w[2], w[3]);
+      const bool first = yrow == 0 && (BZ == 1 || j == 0);
+      if (first) store_float(N, g.ntype, block0 + blk, m);
+      if constexpr (kStats) {
+        const double n = stored_N(m, g.ntype);
+        s11 += sum_of_squares<int8_t, 4>(w) * (n * n);
+        if (first) d1 += n * double(IdxPack<int8_t>::get(w[0], 0));
+      }
+    }
+  }
+  if constexpr (kStats) emit_tile_sums(tile_sums, g, tx, by, bz, s11, d1);
+}
+
+template <int TF, typename XT, int BZ, bool kTailX = false>
+__global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const void* __restrict__ N,
+                                                           const int8_t* __restrict__ F, XT* __restrict__ y) {
+  using Q4 = Quad4<XT>;
+  using Map = QuadMap<BZ>;
+  constexpr int BPW = Map::kBlocksPerWave;
+  __shared__ uint4 lds[2][16 * kQuadRow];
+  const int lane = threadIdx.x & 63;
+  int64_t tx, by, bz;
+  if (!decode_tile<2>(g, tx, by, bz)) return;
+  uint4* st = lds[threadIdx.x >> 6];
+  const int64_t block0 = (bz * g.gy + by) * g.gx + tx * BPW;
+  {
+    const int yrow = lane & 15, bsub = lane >> 4;
+    float u[64];
+    int64_t blocks[4];
+    uint4 fs[4];
+    float ns[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int64_t blk = Map::block_of(4 * j + bsub);
+      if (tx * BPW + blk >= g.gx) blk = g.gx - 1 - tx * BPW;   // past the end: decode the last block again, stored nowhere
+      blocks[j] = block0 + blk;
+      const int piece = BZ == 1 ? yrow : j * 16 + yrow;
+      fs[j] = reinterpret_cast<const uint4*>(F + blocks[j] * (BZ * 256))[piece];
+    }
+    load_N_many<4>(N, g.ntype, blocks, ns);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint4 f = fs[j];
+      const float scale = ns[j] / float(g.r);
+      const uint32_t w[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+      for (int i = 0; i < 16; ++i) u[j * 16 + i] = scale * float(IdxPack<int8_t>::get(w[i >> 2], i & 3));
+    }
+    if constexpr (BZ == 4) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) tf_inverse<TF, float, 4, 16, 4>(u + i);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tf_inverse<TF, float, 16, 1, 16>(u + j * 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int xq = 0; xq < 4; ++xq) st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq] = f4_bits(u + j * 16 + xq * 4);
+  }
+  wave_lds_sync();
+  const int p = lane >> 2, q = lane & 3;
+  const int64_t bx = tx * BPW + Map::block_of(p);
+  const int64_t zz = bz * BZ + Map::plane_of(p);
+  float v[64];
+#pragma unroll
+  for (int yy0 = 0; yy0 < 16; ++yy0) bits_f4(st[yy0 * kQuadRow + lane], v + yy0 * 4);
+#pragma unroll
+  for (int xl = 0; xl < 4; ++xl) tf_inverse<TF, float, 16, 4, 16>(v + xl);
+  if (bx < g.gx && zz < g.Z) {
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      const int64_t yy = by * 16 + yy0;
+      if (yy < g.Y) {
+        if constexpr (kTailX) {
+          XT* row = y + (zz * g.Y + yy) * g.X;
+          const int64_t x0 = bx * 16 + q * 4;
+          if (x0 + 4 <= g.X) {
+            Q4::template store<true>(row + x0, Q4::pack(v + yy0 * 4));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (x0 + e < g.X) Elem<float, XT>::store(row + x0 + e, v[yy0 * 4 + e]);
+          }
+        } else {
+          Q4::template store<false>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4, Q4::pack(v + yy0 * 4));
+        }
+      }
+    }
+  }
+}
+
+
+// 16x16 (2-D) and 4x16x16 blocks, FP32 / bfloat16 / FP16 arrays, int8, nothing pruned
+template <int TF, typename XT, int BZ>
+struct Quad16Kernel {
+  static constexpr int kBlocksPerWave = BZ == 1 ? 16 : 4;
+  static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
+    return f.ok && c->transform == TF && !c->compute_f64 && xtype == xtype_code<XT>() && c->itype == PBZ_I8 &&
+           c->ftype != PBZ_F64 && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
+           x_extent_ok(f, 4, int(sizeof(XT)));
+  }
+  static int fits(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, kBlocksPerWave, 2, &grid) ? 1 : 0;
+  }
+  static int64_t tiles(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, kBlocksPerWave, 2, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
+  }
+  template <bool kRagged, bool kStats, bool kTailX>
+  static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    hipLaunchKernelGGL((k_compress_quad16<TF, XT, BZ, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
+                       static_cast<const XT*>(x), N, static_cast<int8_t*>(F), tile_sums);
+  }
+  static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    dim3 grid;
+    if (!tile_grid(g, kBlocksPerWave, 2, &grid)) return 0;
+    const bool ragged = g.Y % 16 || g.Z % BZ;
+    if (g.X % 16) tile_sums ? launch<true, true, true>(g, grid, x, N, F, tile_sums, s) : launch<true, false, true>(g, grid, x, N, F, nullptr, s);
+    else if (tile_sums) ragged ? launch<true, true, false>(g, grid, x, N, F, tile_sums, s) : launch<false, true, false>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false, false>(g, grid, x, N, F, nullptr, s) : launch<false, false, false>(g, grid, x, N, F, nullptr, s);
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+  static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
+    dim3 grid;
+    if (!tile_grid(g, kBlocksPerWave, 2, &grid)) return 0;
+    if (g.X % 16)
+      hipLaunchKernelGGL((k_decompress_quad16<TF, XT, BZ, true>), grid, dim3(128), 0, s, g, N,
+                         static_cast<const int8_t*>(F), static_cast<XT*>(y));
+    else
+      hipLaunchKernelGGL((k_decompress_quad16<TF, XT, BZ, false>), grid, dim3(128), 0, s, g, N,
+                         static_cast<const int8_t*>(F), static_cast<XT*>(y));
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+};
+
+#define PBZ_ROWS(X, TF, SUFFIX) \
+  X(Quad16Kernel<TF COMMA float COMMA 1>, "quad16_f32_16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA float COMMA 4>, "quad16_f32_4x16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA f16_t COMMA 1>, "quad16_f16_16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA bf16_t COMMA 1>, "quad16_bf16_16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA f16_t COMMA 4>, "quad16_f16_4x16x16_i8" SUFFIX)
+
+}  // namespace
+
+PBZ_DEFINE_FAST_FAMILY(quad16, PBZ_ROWS)
+
+}  // namespace fast
+}  // namespace pbz
