@@ -186,3 +186,55 @@ def test_kernel_name_and_path_switch():
     assert c.kernel_name("decompress", (64, 64), "f32") == "generic"
     with pytest.raises(PbzError):
         c.set_kernel_path(5)
+
+
+# which kernel the dispatch picks (decided on the host from shapes and types alone, so testable without a GPU)
+DISPATCH = [
+    # block, work type, index type, keep, array shape, array type -> kernel
+    ((8, 8), "f32", "i8", None, (256, 256), "f32", "lane_f32_8x8_i8"),
+    ((8, 8), "f32", "i16", (4, 4), (4096, 4096), "f32", "lane_f32_8x8_i16_box4x4"),
+    ((8, 8), "f32", "i16", None, (64, 72), "f32", "lane_f32_8x8_i16"),
+    ((8, 8), "f64", "i8", None, (64, 72), "f64", "lane_f64_8x8_i8"),
+    ((8, 8), "f64", "i16", None, (61, 75), "f64", "lane_f64_8x8_i16"),
+    ((8, 8), "f32", "i8", None, (64, 72), "bf16", "lane_bf16_8x8_i8"),
+    ((8, 8), "f16", "i8", None, (64, 72), "f16", "lane_f16_8x8_i8"),
+    ((4, 4, 4), "f64", "i16", None, (512, 512, 512), "f64", "lane_f64_4x4x4_i16"),
+    ((4, 4, 4), "f64", "i8", None, (9, 13, 22), "f64", "lane_f64_4x4x4_i8"),
+    ((4, 4, 4), "f32", "i8", None, (9, 13, 24), "f32", "lane_f32_4x4x4_i8"),
+    ((4, 4, 4), "f32", "i16", None, (9, 13, 24), "f32", "lane_f32_4x4x4_i16"),
+    ((1, 16, 16), "f32", "i8", None, (64, 1024, 1024), "f32", "quad16_f32_16x16_i8"),
+    ((16, 16), "f32", "i8", None, (33, 50), "f16", "quad16_f16_16x16_i8"),
+    ((16, 16), "bf16", "i8", None, (33, 50), "bf16", "quad16_bf16_16x16_i8"),
+    ((4, 16, 16), "f32", "i8", None, (250, 1024, 1024), "f32", "quad16_f32_4x16x16_i8"),
+    ((4, 16, 16), "f32", "i8", None, (9, 20, 38), "f16", "quad16_f16_4x16x16_i8"),
+    ((8, 8, 8), "f32", "i8", (4, 4, 4), (1024, 1024, 512), "bf16", "oct8_bf16_8x8x8_i8_box4x4x4"),
+    ((8, 8, 8), "f32", "i8", None, (17, 9, 24), "bf16", "oct8_bf16_8x8x8_i8"),
+    ((8, 8, 8), "f32", "i8", (4, 4, 4), (17, 9, 21), "f32", "oct8_f32_8x8x8_i8_box4x4x4"),
+    ((8, 8, 8), "f32", "i8", None, (17, 9, 24), "f16", "oct8_f16_8x8x8_i8"),
+    ((1, 1, 8, 8), "f32", "i8", None, (3, 2, 40, 64), "f32", "lane_f32_8x8_i8"),          # leading unit-block dimensions fold
+    # no specialised kernel: the general ones
+    ((8, 8), "f32", "i32", None, (64, 64), "f32", "generic"),
+    ((8, 8), "f64", "i16", None, (64, 64), "f32", "generic"),                              # FP32 array, FP64 N
+    ((16, 16), "f32", "i16", None, (64, 64), "f32", "generic"),
+    ((8, 8, 8), "f32", "i8", (2, 2, 2), (16, 16, 16), "f32", "generic"),                   # another mask
+    ((8, 8, 8), "f64", "i8", None, (16, 16, 16), "f64", "generic"),
+    ((16, 16, 16), "f32", "i16", None, (40, 40, 66), "f32", "generic"),
+    ((2, 8, 8), "f32", "i8", None, (4, 64, 64), "f32", "generic"),
+    ((8, 8), "f32", "i8", None, (6, 3), "f32", "generic"),                                 # rows shorter than a 16-byte piece
+    ((8, 8, 8), "f32", "i8", None, (17, 9, 23), "bf16", "generic"),                        # odd 16-bit rows
+    ((2, 2, 8, 8), "f32", "i8", None, (4, 4, 64, 64), "f32", "generic"),                   # four blocked dimensions
+]
+
+
+@pytest.mark.parametrize("row", DISPATCH, ids=[f"{r[0]}-{r[1]}-{r[2]}-{r[5]}-{r[6]}" for r in DISPATCH])
+def test_dispatch_table(row):
+    block, ftype, itype, keep, shape, dtype, kernel = row
+    mask = None
+    if keep is not None:
+        mask = np.zeros(block, dtype=bool)
+        mask[tuple(slice(0, k) for k in keep)] = True
+    c = Codec(block, ftype, itype, mask)
+    assert c.kernel_name("compress", shape, dtype) == kernel
+    assert c.kernel_name("decompress", shape, dtype) == kernel
+    h = Codec(block, ftype, itype, mask, "haar")
+    assert h.kernel_name("compress", shape, dtype) == (kernel if kernel == "generic" else kernel + "_haar")
