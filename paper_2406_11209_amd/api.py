@@ -214,8 +214,10 @@ class Codec:
         return N, F
 
     def workspace(self, device):
+        """The scratch buffer of the reductions: one per device and stream, because calls that overlap on the
+        GPU must not share it."""
         torch = _torch()
-        key = (device.type, device.index)
+        key = (device.type, device.index, _stream())
         if key not in self._ws:
             self._ws[key] = torch.empty(self.layout([1] * len(self.block_shape)).workspace_bytes, dtype=torch.uint8,
                                         device=device)
@@ -246,7 +248,7 @@ class Codec:
         if workspace is None:
             need = _c.c_size_t()
             check(self._lib.pbz_compress_statistics_workspace(self._h, _shape_arr(x.shape), _ftype_of(x), _c.byref(need)))
-            key = ("stats", x.device.type, x.device.index)
+            key = ("stats", x.device.type, x.device.index, _stream())
             if key not in self._ws or self._ws[key].numel() < need.value:
                 self._ws[key] = torch.empty(need.value, dtype=torch.uint8, device=x.device)
             workspace = self._ws[key]
@@ -385,7 +387,7 @@ class Codec:
         if workspace is None:
             need = _c.c_size_t()
             check(self._lib.pbz_approximate_wasserstein_workspace(self._h, F1.shape[0], _c.byref(need)))
-            key = ("wasserstein", N1.device.type, N1.device.index)
+            key = ("wasserstein", N1.device.type, N1.device.index, _stream())
             if key not in self._ws or self._ws[key].numel() < need.value:
                 self._ws[key] = torch.empty(need.value, dtype=torch.uint8, device=N1.device)
             workspace = self._ws[key]

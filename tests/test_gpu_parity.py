@@ -531,3 +531,29 @@ def test_blockwise_std_of_constant_blocks_with_32_bit_indices():
             got = getattr(case.codec, name)(N, F).cpu().numpy()
             assert np.array_equal(got, np.zeros_like(got)), name
         case.check_blockwise(N, F, N, F)
+
+
+def test_one_codec_on_two_streams():
+    """Reductions enqueued on two streams at once through one Codec: the binding gives each stream a workspace of
+    its own, so the results are those of running them one after the other."""
+    wl = synth.make_workload(4, (128, 128, 128))
+    case = Case(wl.A, wl.B, wl.dtype, wl.block, wl.index_bits, wl.ftype, wl.mask)
+    N1, F1 = case.codec.compress(case.xA)
+    N2, F2 = case.codec.compress(case.xB)
+    want = [case.codec.norm2(N1, F1).item(), case.codec.norm2(N2, F2).item(), case.codec.dot(N1, F1, N2, F2).item(),
+            case.codec.variance(N2, F2).item()]
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Stream(), torch.cuda.Stream()
+    out = torch.zeros((50, 4), dtype=torch.float64, device="cuda")
+    for k in range(50):
+        with torch.cuda.stream(a):
+            case.codec.norm2(N1, F1, out=out[k, 0:1])
+            case.codec.dot(N1, F1, N2, F2, out=out[k, 2:3])
+        with torch.cuda.stream(b):
+            case.codec.norm2(N2, F2, out=out[k, 1:2])
+            case.codec.variance(N2, F2, out=out[k, 3:4])
+    torch.cuda.synchronize()
+    assert len(case.codec._ws) >= 3                      # the default stream's and the two side streams'
+    got = out.cpu().numpy()
+    for k in range(50):
+        assert got[k].tolist() == want, k
