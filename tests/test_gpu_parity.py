@@ -557,3 +557,79 @@ def test_one_codec_on_two_streams():
     got = out.cpu().numpy()
     for k in range(50):
         assert got[k].tolist() == want, k
+
+
+def test_random_compressed_operands(capsys):
+    """Compressed arrays drawn directly (random indices and maxima, some all-zero blocks) at 16-byte-aligned and
+    unaligned addresses: segmented reductions with few and with thousands of segments (sampled segments against
+    the oracle), whole-array reductions, and add / negate in place."""
+    import math
+    g = rng(4242)
+    TI = {8: torch.int8, 16: torch.int16, 32: torch.int32}
+    NP_I = {8: np.int8, 16: np.int16, 32: np.int32}
+    TF = {"f64": torch.float64, "f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+    def draw(n_blocks, kept, bits, ftype, off_n, off_f):
+        r = po.index_radius(bits)
+        F = g.integers(-r, r + 1, size=(n_blocks, kept)).astype(NP_I[bits])
+        F[g.integers(0, n_blocks, size=max(1, n_blocks // 7))] = 0              # some all-zero blocks
+        N = np.abs(g.standard_normal(n_blocks)) + 0.01
+        N[np.all(F == 0, axis=1)] = 0.0
+        Nt_full = torch.zeros(n_blocks + off_n, dtype=TF[ftype], device="cuda")
+        Nt = Nt_full[off_n:]; Nt.copy_(torch.from_numpy(N).to(TF[ftype]))
+        Ft_full = torch.zeros(n_blocks * kept + off_f, dtype=TI[bits], device="cuda")
+        Ft = Ft_full[off_f:].view(n_blocks, kept); Ft.copy_(torch.from_numpy(F))
+        return Nt, Ft
+    for c in range(150):
+        nd = int(g.integers(1, 4))
+        block = tuple(int(2 ** g.integers(0, 5)) for _ in range(nd))
+        while int(np.prod(block)) > 1024: block = block[:-1] + (max(1, block[-1] // 2),)
+        keep = tuple(max(1, b // 2) for b in block) if g.integers(0, 3) == 0 else None
+        mask = None if keep is None else synth.low_frequency_mask(block, keep)
+        kept = int(np.prod(block)) if mask is None else int(mask.sum())
+        bits = [8, 16, 32][int(g.integers(0, 3))]
+        ftype = ["f64", "f32", "f16", "bf16"][int(g.integers(0, 4))]
+        n_seg = int(g.integers(1, 40)) if g.integers(0, 4) else int(g.integers(2000, 5000))
+        per = int(g.integers(1, 60)) if n_seg < 100 else int(g.integers(1, 6))
+        n_blocks = n_seg * per
+        off_n = int(g.integers(0, 4)) if g.integers(0, 2) else 0
+        off_f = int(g.integers(0, 9)) if g.integers(0, 2) else 0
+        with capsys.disabled():
+            print(f"[random operands {c}] block {block} keep {keep} i{bits} {ftype} segments {n_seg} x {per}, offsets {off_n} {off_f}", flush=True)
+        codec = Codec(block, ftype, bits, mask)
+        N1, F1 = draw(n_blocks, kept, bits, ftype, off_n, off_f)
+        N2, F2 = draw(n_blocks, kept, bits, ftype, off_n, off_f)
+        grid = (n_blocks,) + (1,) * (nd - 1)
+        shape = tuple(gd * b for gd, b in zip(grid, block))
+        P = np.ones(block, dtype=bool) if mask is None else mask
+        mk = lambda N, F, lo, hi: po.Compressed(s=((hi - lo) * block[0],) + tuple(block[1:]), i=tuple(block),
+                                                N=parity.to_host_f64(N[lo:hi]).reshape((hi - lo,) + (1,) * (nd - 1)),
+                                                F=F[lo:hi].cpu().numpy(), P=P, index_bits=bits, ftype=ftype)
+        tol = parity.value_tol(ftype)
+        stats = ["dot", "norm2", "difference_norm2"] + (["mean", "variance", "covariance"] if P.reshape(-1)[0] else [])
+        picks = sorted(set([0, n_seg - 1] + [int(v) for v in g.integers(0, n_seg, size=6)]))
+        for st in stats:
+            two = st in ("dot", "covariance", "difference_norm2")
+            out = codec.segmented(st, n_seg, per, N1, F1, N2 if two else None, F2 if two else None)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            for sidx in picks:
+                A = mk(N1, F1, sidx * per, (sidx + 1) * per); B = mk(N2, F2, sidx * per, (sidx + 1) * per)
+                want = getattr(po, st)(A, B) if two else getattr(po, st)(A)
+                na, nb = po.norm2(A), po.norm2(B)
+                n_el = per * float(np.prod(block))
+                floor = {"dot": na * nb, "norm2": 0.0, "difference_norm2": na + nb, "mean": na / math.sqrt(n_el),
+                         "variance": na * na / n_el, "covariance": na * nb / n_el}[st]
+                parity.check_scalar(float(got[sidx]), want, tol, floor, f"segmented {st}[{sidx}]")
+        # whole-array reductions and element-wise operations at these addresses, in place
+        A, B = mk(N1, F1, 0, n_blocks), mk(N2, F2, 0, n_blocks)
+        parity.check_scalar(float(codec.norm2(N1, F1).item()), po.norm2(A), tol, 0.0, "norm2")
+        parity.check_scalar(float(codec.dot(N1, F1, N2, F2).item()), po.dot(A, B), tol, po.norm2(A) * po.norm2(B), "dot")
+        ref = po.add(A, B)
+        Na, Fa = N1.clone(), F1.clone()
+        codec.add(N1, F1, N2, F2, N_out=N1, F_out=F1)            # in place, at the unaligned addresses
+        torch.cuda.synchronize()
+        parity.check_N(parity.to_host_f64(N1), ref.N.reshape(-1), ftype, "add.N")
+        parity.check_indices(F1.cpu().numpy(), ref.F, ref.t, po.index_radius(bits) * 2.0 ** -50, "add.F")
+        codec.negate(F2, out=F2); torch.cuda.synchronize()
+        assert np.array_equal(F2.cpu().numpy(), po.negate(B).F)
