@@ -333,6 +333,12 @@ template <int TF> using Lane_f32_4x4x4_i8 = LaneKernel<TF, float, float, int8_t,
 template <int TF> using Lane_f32_4x4x4_i16 = LaneKernel<TF, double, float, int16_t, float, 4, 4, 4, 4, 4, 4>;
 template <int TF> using Lane_f64_8x8_i8 = LaneKernel<TF, double, double, int8_t, double, 1, 8, 8, 1, 8, 8>;
 template <int TF> using Lane_f64_8x8_i16 = LaneKernel<TF, double, double, int16_t, double, 1, 8, 8, 1, 8, 8>;
+// FP64 arrays with a narrower working type (N stored as FP32 or a 16-bit type): FP32 arithmetic with int8 indices,
+// FP64 arithmetic with int16
+template <int TF> using Lane_f64_w32_8x8_i8 = LaneKernel<TF, float, double, int8_t, float, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_f64_w32_8x8_i16 = LaneKernel<TF, double, double, int16_t, float, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_f64_w32_4x4x4_i8 = LaneKernel<TF, float, double, int8_t, float, 4, 4, 4, 4, 4, 4>;
+template <int TF> using Lane_f64_w32_4x4x4_i16 = LaneKernel<TF, double, double, int16_t, float, 4, 4, 4, 4, 4, 4>;
 
 #define PBZ_ROWS(X, TF, SUFFIX) \
   X(Lane_f32_8x8_i8<TF>, "lane_f32_8x8_i8" SUFFIX) \
@@ -345,7 +351,11 @@ template <int TF> using Lane_f64_8x8_i16 = LaneKernel<TF, double, double, int16_
   X(Lane_f32_4x4x4_i8<TF>, "lane_f32_4x4x4_i8" SUFFIX) \
   X(Lane_f32_4x4x4_i16<TF>, "lane_f32_4x4x4_i16" SUFFIX) \
   X(Lane_f64_8x8_i8<TF>, "lane_f64_8x8_i8" SUFFIX) \
-  X(Lane_f64_8x8_i16<TF>, "lane_f64_8x8_i16" SUFFIX)
+  X(Lane_f64_8x8_i16<TF>, "lane_f64_8x8_i16" SUFFIX) \
+  X(Lane_f64_w32_8x8_i8<TF>, "lane_f64_w32_8x8_i8" SUFFIX) \
+  X(Lane_f64_w32_8x8_i16<TF>, "lane_f64_w32_8x8_i16" SUFFIX) \
+  X(Lane_f64_w32_4x4x4_i8<TF>, "lane_f64_w32_4x4x4_i8" SUFFIX) \
+  X(Lane_f64_w32_4x4x4_i16<TF>, "lane_f64_w32_4x4x4_i16" SUFFIX)
 
 }  // namespace
 

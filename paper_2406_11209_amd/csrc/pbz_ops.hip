@@ -560,8 +560,13 @@ __device__ __forceinline__ double finish_statistic(const double* s, const Reduce
       const double scale = 1.0 / (t.r * t.n_blocks * sqrt(t.vol));
       const double mu_a = s[kD1] * scale, mu_b = s[kD2] * scale;
       const double per = 1.0 / (t.r * t.r * t.n_blocks * t.vol);
-      const double var_a = fmax((s[kS11] - s[kD1] * s[kD1] / t.n_blocks) * per, 0.0);
-      const double var_b = fmax((s[kS22] - s[kD2] * s[kD2] / t.n_blocks) * per, 0.0);
+      // S - D^2 / n carries rounding of a few units in the last place of S; a difference inside that noise is
+      // the variance of a constant array and is taken as zero (its root would turn 1e-16 into 1e-8)
+      const double noise = 8.0 * 2.220446049250313e-16;
+      double ca = s[kS11] - s[kD1] * s[kD1] / t.n_blocks, cb = s[kS22] - s[kD2] * s[kD2] / t.n_blocks;
+      if (ca <= noise * s[kS11]) ca = 0.0;
+      if (cb <= noise * s[kS22]) cb = 0.0;
+      const double var_a = ca * per, var_b = cb * per;
       const double cov = (s[kS12] - s[kD1] * s[kD2] / t.n_blocks) * per;
       const double sd = sqrt(var_a) * sqrt(var_b);
       const double lum = (2.0 * mu_a * mu_b + t.s_l) / (mu_a * mu_a + mu_b * mu_b + t.s_l);

@@ -279,14 +279,22 @@ class Case:
         A, B = self.oc(N1, F1), self.oc(N2, F2)
         got = float(self.codec.ssim(N1, F1, N2, F2, **kw).item())
         want = po.ssim(A, B, **kw)
-        # Variance and covariance come out of the one pass as S - D1 D2 / n, whose rounding is relative to the
-        # mean square of the arrays, not to the (possibly zero) variance; Algorithm 12 divides them by sums that
-        # can be as small as its stabilisers, so the index inherits that rounding magnified by mean square over
-        # stabiliser.  Both sides work in FP64 from the same {N, F}, hence a few units of FP64 rounding.
+        # Variance and covariance come out of the one pass as S - D1 D2 / n, whose rounding (a few units in the
+        # last place of S) is relative to the mean square of the arrays, not to the variance; Algorithm 12 takes
+        # roots of the variances and divides by sums that can be as small as its stabilisers.  Both sides work in
+        # FP64 from the same {N, F}: the bar adds what that rounding can do to the three factors.
         n_el = float(A.n_blocks) * float(np.prod(self.block))
-        mean_square = po.norm2(A) * po.norm2(B) / n_el
         s_l, s_c = kw.get("s_l", 1e-4), kw.get("s_c", 9e-4)
-        floor = 1.0 + 1e-13 / self.tol * mean_square / max(min(s_l, 0.5 * s_c), 1e-300)
+        da, db = (16 * 2.0 ** -52 * po.norm2(X) ** 2 / n_el for X in (A, B))         # on var_a, var_b (and cov)
+        va, vb = max(po.variance(A), 0.0), max(po.variance(B), 0.0)
+        root_err = lambda v, d: min(math.sqrt(d), d / (2.0 * math.sqrt(v))) if v > 0.0 else math.sqrt(d)
+        ea, eb = root_err(va, da), root_err(vb, db)
+        d_sd = ea * math.sqrt(vb) + eb * math.sqrt(va) + ea * eb
+        d_cov = math.sqrt(da * db)
+        weight = max(1.0, kw.get("w_c", 1.0), kw.get("w_s", 1.0), kw.get("w_l", 1.0))
+        slack = weight * ((2.0 * d_sd + da + db) / max(s_c, 1e-300) + (d_cov + d_sd) / max(0.5 * s_c, 1e-300)
+                          + (da + db) / max(s_l, 1e-300))
+        floor = 1.0 + slack / self.tol
         check_scalar(got, want, self.tol, floor, "ssim")
         return got
 

@@ -178,13 +178,18 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((21, 75), (8, 8), 8, "f64", "f64", None, "lane_f64_8x8_i8"),
                ((37, 520), (8, 8), 16, "f64", "f64", None, "lane_f64_8x8_i16"),
                ((16, 67), (8, 8), 16, "f64", "f64", None, "lane_f64_8x8_i16"),
-               ((40, 64), (8, 8), 16, "f64", "f32", None, "generic"),                 # FP64 array, N stored as FP32
                ((5, 30, 20), (4, 4, 4), 8, "f64", "f64", None, "lane_f64_4x4x4_i8"),
                ((9, 13, 262), (4, 4, 4), 8, "f64", "f64", None, "lane_f64_4x4x4_i8"),
                ((9, 14, 24), (4, 4, 4), 8, "f32", "f32", None, "lane_f32_4x4x4_i8"),
                ((5, 8, 1030), (4, 4, 4), 8, "f32", "f32", None, "lane_f32_4x4x4_i8"),
                ((6, 30, 20), (4, 4, 4), 16, "f32", "f32", None, "lane_f32_4x4x4_i16"),
                ((8, 9, 270), (4, 4, 4), 16, "f32", "f16", None, "lane_f32_4x4x4_i16"),
+               # FP64 arrays with an FP32 / 16-bit working type
+               ((37, 520), (8, 8), 8, "f64", "f32", None, "lane_f64_w32_8x8_i8"),
+               ((21, 75), (8, 8), 8, "f64", "f16", None, "lane_f64_w32_8x8_i8"),
+               ((24, 1032), (8, 8), 16, "f64", "f32", None, "lane_f64_w32_8x8_i16"),
+               ((9, 13, 262), (4, 4, 4), 8, "f64", "f32", None, "lane_f64_w32_4x4x4_i8"),
+               ((5, 30, 20), (4, 4, 4), 16, "f64", "bf16", None, "lane_f64_w32_4x4x4_i16"),
                # 16-bit arrays in 8x8 and 8x8x8 blocks
                ((37, 64), (8, 8), 8, "bf16", "f32", None, "lane_bf16_8x8_i8"),
                ((21, 1046), (8, 8), 8, "bf16", "bf16", None, "lane_bf16_8x8_i8"),

@@ -198,6 +198,10 @@ DISPATCH = [
     ((8, 8), "f64", "i16", None, (61, 75), "f64", "lane_f64_8x8_i16"),
     ((8, 8), "f32", "i8", None, (64, 72), "bf16", "lane_bf16_8x8_i8"),
     ((8, 8), "f16", "i8", None, (64, 72), "f16", "lane_f16_8x8_i8"),
+    ((8, 8), "f32", "i8", None, (64, 72), "f64", "lane_f64_w32_8x8_i8"),
+    ((8, 8), "bf16", "i16", None, (64, 72), "f64", "lane_f64_w32_8x8_i16"),
+    ((4, 4, 4), "f32", "i8", None, (9, 13, 22), "f64", "lane_f64_w32_4x4x4_i8"),
+    ((4, 4, 4), "f32", "i16", None, (9, 13, 22), "f64", "lane_f64_w32_4x4x4_i16"),
     ((4, 4, 4), "f64", "i16", None, (512, 512, 512), "f64", "lane_f64_4x4x4_i16"),
     ((4, 4, 4), "f64", "i8", None, (9, 13, 22), "f64", "lane_f64_4x4x4_i8"),
     ((4, 4, 4), "f32", "i8", None, (9, 13, 24), "f32", "lane_f32_4x4x4_i8"),
