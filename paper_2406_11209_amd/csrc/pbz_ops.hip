@@ -544,30 +544,58 @@ struct ReduceTail {
   double r, n_blocks, vol;
   double s_l, s_c, w_l, w_c, w_s;   // Algorithm 12's stabilisers and weights
   int n_f16;                        // N is FP16 (as opposed to bfloat16) when it is 16 bits wide
+  // Shifted first coefficients.  Variance and covariance centre the first coefficients N_k F_k0 by their mean
+  // (Algorithms 8, 9); summing them and their squares raw and subtracting afterwards would cancel against the
+  // square of the mean.  The passes that need them therefore sum d_k = N_k F_k0 - K, with K the first
+  // coefficient of the segment's first block (a pilot value: exact centring needs the mean, which is not known
+  // yet, but any K near it removes the cancellation), and put d_k^2, d1_k d2_k into S11, S22, S12 in place of
+  // the raw squares and product.  pilot_n1 == nullptr: nothing is shifted (K = 0).
+  const void* pilot_n1;
+  const void* pilot_f1;
+  const void* pilot_n2;
+  const void* pilot_f2;
+  int64_t seg_n_bytes, seg_f_bytes;  // distance between the segments' first N and F
+  int ntype, itype;
 };
 
-__device__ __forceinline__ double finish_statistic(const double* s, const ReduceTail& t) {
+// K of operand (N, F) in segment `segment`: the same expression wherever it is evaluated
+__device__ __forceinline__ double pilot_value(const void* N, const void* F, const ReduceTail& t, int64_t segment) {
+  if (!N) return 0.0;
+  const char* n = static_cast<const char*>(N) + segment * t.seg_n_bytes;
+  const char* f = static_cast<const char*>(F) + segment * t.seg_f_bytes;
+  return load_float<double>(n, t.ntype, 0) * double(load_index(f, t.itype, 0));
+}
+
+// s: the five sums, with the first coefficients shifted by K1 / K2 where the pass shifts them (else K = 0)
+__device__ __forceinline__ double finish_statistic(const double* s, const ReduceTail& t, double K1, double K2) {
+  const double n = t.n_blocks;
+  // the raw sums back from the shifted ones: sum (d + K) = D + n K, sum (d1 + K1)(d2 + K2) = S12 + K2 D1 + K1 D2 + n K1 K2
+  const double D1 = s[kD1] + n * K1, D2 = s[kD2] + n * K2;
+  const double S11 = s[kS11] + 2.0 * K1 * s[kD1] + n * K1 * K1;
+  const double S22 = s[kS22] + 2.0 * K2 * s[kD2] + n * K2 * K2;
+  const double S12 = s[kS12] + K2 * s[kD1] + K1 * s[kD2] + n * K1 * K2;
   switch (t.op) {
-    case kDot: return s[kS12] / (t.r * t.r);
-    case kNorm2: return sqrt(s[kS11]) / t.r;
+    case kDot: return S12 / (t.r * t.r);
+    case kNorm2: return sqrt(S11) / t.r;
     case kDiffNorm2: return sqrt(s[kS11]) / t.r;    // S11 then holds sum (N1 F1 - N2 F2)^2
-    case kCosine: return s[kS12] / (sqrt(s[kS11]) * sqrt(s[kS22]));
-    case kMean: return (s[kD1] / t.r) / (t.n_blocks * sqrt(t.vol));
-    // centring the first coefficients by their mean removes (sum D1)(sum D2) / n_blocks from the raw sum
-    case kCovariance: return ((s[kS12] - s[kD1] * s[kD2] / t.n_blocks) / (t.r * t.r)) / (t.n_blocks * t.vol);
-    case kVariance: return ((s[kS11] - s[kD1] * s[kD1] / t.n_blocks) / (t.r * t.r)) / (t.n_blocks * t.vol);
+    case kCosine: return S12 / (sqrt(S11) * sqrt(S22));
+    case kMean: return (D1 / t.r) / (n * sqrt(t.vol));
+    // centring the first coefficients by their mean removes (sum d1)(sum d2) / n_blocks from the sum of products,
+    // whatever constant they were shifted by
+    case kCovariance: return ((s[kS12] - s[kD1] * s[kD2] / n) / (t.r * t.r)) / (n * t.vol);
+    case kVariance: return ((s[kS11] - s[kD1] * s[kD1] / n) / (t.r * t.r)) / (n * t.vol);
     case kSsim: {   // Algorithm 12 from the means, variances and covariance of Algorithms 7-9
-      const double scale = 1.0 / (t.r * t.n_blocks * sqrt(t.vol));
-      const double mu_a = s[kD1] * scale, mu_b = s[kD2] * scale;
-      const double per = 1.0 / (t.r * t.r * t.n_blocks * t.vol);
-      // S - D^2 / n carries rounding of a few units in the last place of S; a difference inside that noise is
-      // the variance of a constant array and is taken as zero (its root would turn 1e-16 into 1e-8)
+      const double scale = 1.0 / (t.r * n * sqrt(t.vol));
+      const double mu_a = D1 * scale, mu_b = D2 * scale;
+      const double per = 1.0 / (t.r * t.r * n * t.vol);
+      // a difference inside the rounding of its two terms is the variance of a constant array: zero (its root
+      // would turn 1e-16 into 1e-8)
       const double noise = 8.0 * 2.220446049250313e-16;
-      double ca = s[kS11] - s[kD1] * s[kD1] / t.n_blocks, cb = s[kS22] - s[kD2] * s[kD2] / t.n_blocks;
+      double ca = s[kS11] - s[kD1] * s[kD1] / n, cb = s[kS22] - s[kD2] * s[kD2] / n;
       if (ca <= noise * s[kS11]) ca = 0.0;
       if (cb <= noise * s[kS22]) cb = 0.0;
       const double var_a = ca * per, var_b = cb * per;
-      const double cov = (s[kS12] - s[kD1] * s[kD2] / t.n_blocks) * per;
+      const double cov = (s[kS12] - s[kD1] * s[kD2] / n) * per;
       const double sd = sqrt(var_a) * sqrt(var_b);
       const double lum = (2.0 * mu_a * mu_b + t.s_l) / (mu_a * mu_a + mu_b * mu_b + t.s_l);
       const double con = (2.0 * sd + t.s_c) / (var_a + var_b + t.s_c);
@@ -596,15 +624,17 @@ __device__ __forceinline__ double group_total(const double* sums, double (*lds)[
 
 // the requested statistic(s) of segment `segment` from its five sums
 __device__ __forceinline__ void write_statistic(const double* fin, const ReduceTail& t, int64_t segment) {
+  const double K1 = pilot_value(t.pilot_n1, t.pilot_f1, t, segment);
+  const double K2 = pilot_value(t.pilot_n2, t.pilot_f2, t, segment);
   if (t.op == kStatistics) {            // mean, variance and norm2 of one array from the same two sums
     ReduceTail one = t;
     const int ops[3] = {kMean, kVariance, kNorm2};
     for (int i = 0; i < 3; ++i) {
       one.op = ops[i];
-      t.out[segment * 3 + i] = finish_statistic(fin, one);
+      t.out[segment * 3 + i] = finish_statistic(fin, one, K1, K2);
     }
   } else {
-    t.out[segment] = finish_statistic(fin, t);
+    t.out[segment] = finish_statistic(fin, t, K1, K2);
   }
 }
 
@@ -680,7 +710,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_tiles(const double2* __rest
 // difference can be far smaller than either, so the block sums S11 - 2 S12 + S22 would cancel)
 template <int kIType, bool kTwo, bool kDC, bool kDiff>
 __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, const uint4& b, double n1, double n2,
-                                               bool head) {
+                                               bool head, double K1 = 0.0, double K2 = 0.0) {
   if (kDiff) {
     constexpr int kPer = kIType == PBZ_I8 ? 4 : (kIType == PBZ_I16 ? 2 : 1);
     const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
@@ -699,14 +729,28 @@ __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, con
     sums[kS11] += acc;
     return;
   }
+  if (kDC) {
+    // the block's first coefficient leaves the integer sums (cleared in the vector that holds it) and enters
+    // shifted by the pilot value
+    constexpr uint32_t kRest = kIType == PBZ_I8 ? 0xffffff00u : (kIType == PBZ_I16 ? 0xffff0000u : 0u);
+    const double d1 = head ? n1 * double(first_element<kIType>(a.x)) - K1 : 0.0;
+    const double d2 = (kTwo && head) ? n2 * double(first_element<kIType>(b.x)) - K2 : 0.0;
+    uint4 ar = a, br = b;
+    ar.x = head ? (a.x & kRest) : a.x;
+    br.x = head ? (b.x & kRest) : b.x;
+    sums[kS11] += dot_vec<kIType>(ar, ar) * (n1 * n1) + d1 * d1;
+    if (kTwo) {
+      sums[kS12] += dot_vec<kIType>(ar, br) * (n1 * n2) + d1 * d2;
+      sums[kS22] += dot_vec<kIType>(br, br) * (n2 * n2) + d2 * d2;
+    }
+    sums[kD1] += d1;
+    if (kTwo) sums[kD2] += d2;
+    return;
+  }
   sums[kS11] += dot_vec<kIType>(a, a) * (n1 * n1);
   if (kTwo) {
     sums[kS12] += dot_vec<kIType>(a, b) * (n1 * n2);
     sums[kS22] += dot_vec<kIType>(b, b) * (n2 * n2);
-  }
-  if (kDC && head) {
-    sums[kD1] += n1 * double(first_element<kIType>(a.x));
-    if (kTwo) sums[kD2] += n2 * double(first_element<kIType>(b.x));
   }
 }
 
@@ -731,6 +775,8 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
       F2 += int64_t(blockIdx.y) * nvec;
     }
   }
+  const double K1 = kDC ? pilot_value(tail.pilot_n1, tail.pilot_f1, tail, blockIdx.y) : 0.0;
+  const double K2 = kDC && kTwo ? pilot_value(tail.pilot_n2, tail.pilot_f2, tail, blockIdx.y) : 0.0;
   const int64_t begin = int64_t(blockIdx.x) * chunk;
   const int64_t end = begin + chunk < nvec ? begin + chunk : nvec;
   constexpr int kLoads = reduce_unroll(kTwo);       // the same bytes in flight with one operand as with two
@@ -756,7 +802,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
     for (int u = 0; u < kLoads; ++u) {
       const int64_t v = base + u * kThreads + threadIdx.x;
       accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a[u], kTwo ? b[kTwo ? u : 0] : a[u], n1[u], n2[u],
-                                               kDC && (v - k[u] * vpb) == 0);
+                                               kDC && (v - k[u] * vpb) == 0, K1, K2);
     }
   }
   for (int64_t v = base + threadIdx.x; v < end; v += kThreads) {
@@ -765,7 +811,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
     const uint4 b = kTwo ? F2[v] : a;
     accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a, b, load_N<kNType>(N1, k, tail.n_f16 != 0),
                                              kTwo ? load_N<kNType>(N2, k, tail.n_f16 != 0) : 0.0,
-                                      kDC && (v - k * vpb) == 0);
+                                             kDC && (v - k * vpb) == 0, K1, K2);
   }
   reduce_tail(sums, tail);
 }
@@ -778,6 +824,8 @@ __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restr
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   const int64_t k0 = int64_t(blockIdx.y) * n_blocks;     // first block of this segment
+  const double K1 = dc ? pilot_value(tail.pilot_n1, tail.pilot_f1, tail, blockIdx.y) : 0.0;
+  const double K2 = dc && two ? pilot_value(tail.pilot_n2, tail.pilot_f2, tail, blockIdx.y) : 0.0;
   for (int64_t kk = int64_t(blockIdx.x) * kThreads + threadIdx.x; kk < n_blocks; kk += nthreads) {
     const int64_t k = k0 + kk;
     const double n1 = load_float<double>(N1, ntype, k);
@@ -792,7 +840,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restr
       continue;
     }
     double s11 = 0.0, s12 = 0.0, s22 = 0.0;
-    for (int j = 0; j < kept; ++j) {
+    for (int j = dc ? 1 : 0; j < kept; ++j) {       // dc: the first coefficient enters shifted, below
       const double f1 = double(load_index(F1, itype, k * kept + j));
       s11 += f1 * f1;
       if (two) {
@@ -805,8 +853,13 @@ __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restr
     sums[kS12] += s12 * (n1 * n2);
     sums[kS22] += s22 * (n2 * n2);
     if (dc) {
-      sums[kD1] += n1 * double(load_index(F1, itype, k * kept));
-      if (two) sums[kD2] += n2 * double(load_index(F2, itype, k * kept));
+      const double d1 = n1 * double(load_index(F1, itype, k * kept)) - K1;
+      const double d2 = two ? n2 * double(load_index(F2, itype, k * kept)) - K2 : 0.0;
+      sums[kS11] += d1 * d1;
+      sums[kS12] += d1 * d2;
+      sums[kS22] += d2 * d2;
+      sums[kD1] += d1;
+      sums[kD2] += d2;
     }
   }
   reduce_tail(sums, tail);
@@ -819,8 +872,9 @@ __global__ __launch_bounds__(kThreads) void k_reduce_dc(const void* __restrict__
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   const int64_t k0 = int64_t(blockIdx.y) * n_blocks;     // first block of this segment
+  const double K1 = pilot_value(tail.pilot_n1, tail.pilot_f1, tail, blockIdx.y);
   for (int64_t kk = int64_t(blockIdx.x) * kThreads + threadIdx.x; kk < n_blocks; kk += nthreads)
-    sums[kD1] += load_float<double>(N1, ntype, k0 + kk) * double(load_index(F1, itype, (k0 + kk) * kept));
+    sums[kD1] += load_float<double>(N1, ntype, k0 + kk) * double(load_index(F1, itype, (k0 + kk) * kept)) - K1;
   reduce_tail(sums, tail);
 }
 
@@ -978,6 +1032,14 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     const char* n2 = two ? static_cast<const char*>(N2) + seg0 * n_stride : nullptr;
     const char* f2 = two ? static_cast<const char*>(F2) + seg0 * f_stride : nullptr;
     tail.out = out + seg0 * (op == kStatistics ? 3 : 1);
+    tail.pilot_n1 = dc ? n1 : nullptr;
+    tail.pilot_f1 = dc ? f1 : nullptr;
+    tail.pilot_n2 = dc && two ? n2 : nullptr;
+    tail.pilot_f2 = dc && two ? f2 : nullptr;
+    tail.seg_n_bytes = n_stride;
+    tail.seg_f_bytes = f_stride;
+    tail.ntype = int(c->ftype);
+    tail.itype = int(c->itype);
     int groups;
     const bool vectors = bpb % 16 == 0 && aligned16(f1) && (!two || aligned16(f2)) && f_stride % 16 == 0;
     // Algorithm 7 needs one index per block, but memory is fetched in 128-byte lines: when a block's indices
@@ -1026,6 +1088,10 @@ int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment,
   tail.partials = static_cast<double*>(workspace);
   tail.n_f16 = 0;
   tail.op = int(kStatistics);
+  tail.pilot_n1 = tail.pilot_f1 = tail.pilot_n2 = tail.pilot_f2 = nullptr;      // the tiles' sums are not shifted
+  tail.seg_n_bytes = tail.seg_f_bytes = 0;
+  tail.ntype = int(c->ftype);
+  tail.itype = int(c->itype);
   tail.r = c->r;
   tail.n_blocks = double(blocks_per_segment);
   tail.vol = double(c->vol);

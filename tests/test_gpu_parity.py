@@ -638,3 +638,30 @@ def test_random_compressed_operands(capsys):
         parity.check_indices(F1.cpu().numpy(), ref.F, ref.t, po.index_radius(bits) * 2.0 ** -50, "add.F")
         codec.negate(F2, out=F2); torch.cuda.synchronize()
         assert np.array_equal(F2.cpu().numpy(), po.negate(B).F)
+
+
+def test_variance_of_a_field_with_a_large_offset():
+    """Variance, covariance and SSIM centre the first coefficients by their mean (Algorithms 8, 9, 12).  On a
+    field whose mean is ten orders of magnitude above its variance, sums of raw squares minus the square of the
+    sum would lose every digit; the kernels sum the first coefficients shifted by a pilot value, and the
+    results agree with the oracle's centred form relative to the variance itself, not to the mean square."""
+    g = rng(31)
+    shape = (64, 64, 96)
+    wiggle = synth.bump_field(shape, 12, g, (6.0, 20.0))
+    a = 1000.0 + 1e-2 * wiggle
+    b = 1000.0 + 1e-2 * (0.5 * wiggle + 0.5 * synth.bump_field(shape, 12, g, (6.0, 20.0)))
+    for block, bits in (((4, 4, 4), 16), ((8, 8, 8), 32), ((2, 4, 3 + 1), 16)):
+        case = Case(a, b, "f64", block, bits, "f64")
+        N1, F1 = case.codec.compress(case.xA)
+        N2, F2 = case.codec.compress(case.xB)
+        torch.cuda.synchronize()
+        A, B = case.oc(N1, F1), case.oc(N2, F2)
+        assert po.variance(A) < 1e-9 * po.mean(A) ** 2            # the regime this test is about
+        for name, got, want in (("variance", case.codec.variance(N1, F1), po.variance(A)),
+                                ("covariance", case.codec.covariance(N1, F1, N2, F2), po.covariance(A, B)),
+                                ("statistics.variance", case.codec.statistics(N1, F1)[1], po.variance(A))):
+            assert abs(float(got.item()) - want) <= 1e-7 * abs(want), (block, name, float(got.item()), want)
+        got = float(case.codec.ssim(N1, F1, N2, F2, s_l=1e-8, s_c=1e-8).item())
+        want = po.ssim(A, B, s_l=1e-8, s_c=1e-8)
+        assert abs(got - want) <= 1e-6 * abs(want), (block, "ssim", got, want)
+        assert abs(float(case.codec.mean(N1, F1).item()) - po.mean(A)) <= 1e-13 * po.mean(A)
