@@ -130,7 +130,7 @@ int pbz_compress(const pbz_codec* codec, const void* x, pbz_ftype x_type, const 
  *               step (what pbz_segmented returns for the runs of {N, F}).
  * Requires the mask to keep each block's first coefficient (PBZ_ERR_DC_PRUNED otherwise).
  *   workspace   device, 16-byte aligned, at least the bytes pbz_compress_statistics_workspace reports for this
- *               shape and x_type (the reduction scratch plus two FP64 sums per wave of the compress kernel);
+ *               shape and x_type (the reduction scratch plus four FP64 values per wave of the compress kernel);
  *               contents on entry do not matter; PBZ_ERR_WORKSPACE when too small or misaligned. */
 int pbz_compress_statistics_workspace(const pbz_codec* codec, const int64_t* shape, pbz_ftype x_type,
                                       size_t* bytes);

@@ -283,7 +283,7 @@ int pbz_compress_statistics_workspace(const pbz_codec* c, const int64_t* shape, 
   int st = make_geom(c, shape, &g);
   if (st != PBZ_OK) return st;
   const int64_t tiles = c->path == PBZ_PATH_AUTO ? fast_compress_tiles(c, g, x_type) : 0;
-  *bytes = kWorkspaceBytes + size_t(tiles) * 2 * sizeof(double);
+  *bytes = kWorkspaceBytes + size_t(tiles) * 4 * sizeof(double);
   return PBZ_OK;
 }
 
@@ -300,9 +300,9 @@ int pbz_compress_statistics(const pbz_codec* c, const void* x, pbz_ftype x_type,
   const int64_t segments = per_step ? g.grid[0] : 1;       // one triple per block index along dimension 0
   c->used.store(true);
   if (c->path == PBZ_PATH_AUTO) {
-    // the compress kernel leaves two sums per tile behind the reduction scratch; adding them costs two small launches
+    // the compress kernel leaves a record of four doubles per tile behind the reduction scratch; adding them costs two small launches
     const int64_t tiles = fast_compress_tiles(c, g, x_type);
-    if (tiles > 0 && ws_bytes >= kWorkspaceBytes + size_t(tiles) * 2 * sizeof(double)) {
+    if (tiles > 0 && ws_bytes >= kWorkspaceBytes + size_t(tiles) * 4 * sizeof(double)) {
       double* tile_sums = reinterpret_cast<double*>(static_cast<char*>(ws) + kWorkspaceBytes);
       const char* name = nullptr;
       int r = try_compress_fast(c, g, x, x_type, N, F, s, false, &name, tile_sums);

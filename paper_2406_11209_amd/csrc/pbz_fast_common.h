@@ -359,8 +359,9 @@ __device__ __forceinline__ void load_N_many(const void* N, int ntype, const int6
 // With kStats a compress kernel also leaves, per wave, the two sums that the mean (Algorithm 7), the variance
 // (Algorithm 9) and the L2 norm (Algorithm 10) of the array it has just compressed are made of:
 //   S11 = sum_k N_k^2 sum_j F_kj^2   and   D1 = sum_k N_k F_k0   over the wave's blocks,
-// N_k as stored, the integer sums exact.  tile_sums[2 t], tile_sums[2 t + 1] belong to tile
-// t = bz * tiles_yx + by * tiles_x + tx; a later kernel adds them in index order.
+// N_k as stored, the integer sums exact, the first coefficients shifted by a pilot value (see emit_tile_sums).
+// The record of tile t = bz * tiles_yx + by * tiles_x + tx starts at tile_sums[4 t]; a later kernel adds the
+// records in index order.
 typedef short short2s __attribute__((ext_vector_type(2)));
 
 template <typename IT, int kWords>
@@ -384,14 +385,26 @@ __device__ __forceinline__ double sum_of_squares(const uint32_t* w) {   // of th
   }
 }
 
+// One record of four doubles per tile: { S, D, K, count }.  `rest` is this lane's share of N_k^2 sum_j F_kj^2
+// without the blocks' first coefficients; the lanes that hold a first coefficient N_k F_k0 of a block inside the
+// array pass it as d (minus the pilot value K, the first coefficient of the tile's first block, which lane 0
+// holds) in `shifted` and count it in `count`:  S = sum rest + sum (N_k F_k0 - K)^2,  D = sum (N_k F_k0 - K).
+// Shifting keeps the later subtraction S - D^2 / n from cancelling against the square of the mean.
+__device__ __forceinline__ double tile_pilot(double first_coefficient_of_lane) {
+  return __shfl(first_coefficient_of_lane, 0, 64);
+}
 __device__ __forceinline__ void emit_tile_sums(double* __restrict__ tile_sums, const FastGeom& g, int64_t tx, int64_t by,
-                                               int64_t bz, double s11, double d1) {
-  s11 = wave_sum(s11);
-  d1 = wave_sum(d1);
+                                               int64_t bz, double rest, double shifted_squares, double shifted,
+                                               double count, double K) {
+  const double S = wave_sum(rest + shifted_squares);
+  const double D = wave_sum(shifted);
+  const double n = wave_sum(count);
   if ((threadIdx.x & 63) == 0) {
     const int64_t t = bz * int64_t(g.tiles_yx) + by * int64_t(g.tiles_x) + tx;
-    tile_sums[2 * t] = s11;
-    tile_sums[2 * t + 1] = d1;
+    tile_sums[4 * t] = S;
+    tile_sums[4 * t + 1] = D;
+    tile_sums[4 * t + 2] = K;
+    tile_sums[4 * t + 3] = n;
   }
 }
 

@@ -141,7 +141,11 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   if (active) store_float(N, g.ntype, block0 + lane, m);
   if constexpr (kStats) {
     const double n = active ? stored_N(m, g.ntype) : 0.0;
-    emit_tile_sums(tile_sums, g, tx, by, bz, sum_of_squares<IT, KW>(w) * (n * n), n * double(IdxPack<IT>::get(w[0], 0)));
+    const double f0 = double(IdxPack<IT>::get(w[0], 0));
+    const double K = tile_pilot(n * f0);                      // lane 0 always holds a block of the array
+    const double d = active ? n * f0 - K : 0.0;
+    emit_tile_sums(tile_sums, g, tx, by, bz, (sum_of_squares<IT, KW>(w) - f0 * f0) * (n * n), d * d, d,
+                   active ? 1.0 : 0.0, K);
   }
   constexpr int P = KW / 4;                                   // 16-byte pieces of F per block
   if constexpr (P >= 4) {
@@ -297,7 +301,7 @@ struct LaneKernel {
     hipLaunchKernelGGL((k_decompress_lane<TF, T, XT, IT, NT, BZ, BY, BX, KZ, KY, KX, kRagged, kTailX>), grid, dim3(256), 0,
                        s, g, N, static_cast<const IT*>(F), static_cast<XT*>(y));
   }
-  // tile_sums != nullptr: also the per-wave statistic sums (two doubles per tile)
+  // tile_sums != nullptr: also the per-wave statistic sums (four doubles per tile)
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
     if (!tile_grid(g, 64, 4, &grid)) return 0;

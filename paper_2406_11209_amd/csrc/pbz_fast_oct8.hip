@@ -167,9 +167,13 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
       }
   }
   if constexpr (kStats) {
-    const double n = tx * 8 + bb < g.gx ? stored_N(m, g.ntype) : 0.0;
-    emit_tile_sums(tile_sums, g, tx, by, bz, double(squares) * (n * n),
-                   j == 0 ? n * double(IdxPack<int8_t>::get(first, 0)) : 0.0);
+    const bool inside = tx * 8 + bb < g.gx;
+    const double n = inside ? stored_N(m, g.ntype) : 0.0;
+    const double f0 = j == 0 ? double(IdxPack<int8_t>::get(first, 0)) : 0.0;
+    const double K = tile_pilot(n * f0);                      // lane 0: row 0 of the tile's first block
+    const bool has_first = j == 0 && inside;
+    const double d = has_first ? n * f0 - K : 0.0;
+    emit_tile_sums(tile_sums, g, tx, by, bz, (double(squares) - f0 * f0) * (n * n), d * d, d, has_first ? 1.0 : 0.0, K);
   }
   wave_lds_sync();
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 8;

@@ -99,7 +99,9 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
   }
 
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * BPW;
-  double s11 = 0.0, d1 = 0.0;
+  double rest = 0.0;                                   // statistics: N^2 sum F^2 without the first coefficients,
+  double firsts[4] = {0.0, 0.0, 0.0, 0.0};             // the first coefficients N F_0 this lane holds (yrow == 0),
+  bool has_first[4] = {false, false, false, false};    // of blocks inside the array
   float m4 = 0.0f;                                     // BZ = 4: the block's maximum over its four planes
   if constexpr (BZ == 4) {
 #pragma unroll
@@ -134,12 +136,25 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
       if (first) store_float(N, g.ntype, block0 + blk, m);
       if constexpr (kStats) {
         const double n = stored_N(m, g.ntype);
-        s11 += sum_of_squares<int8_t, 4>(w) * (n * n);
-        if (first) d1 += n * double(IdxPack<int8_t>::get(w[0], 0));
+        const double f0 = first ? double(IdxPack<int8_t>::get(w[0], 0)) : 0.0;
+        rest += (sum_of_squares<int8_t, 4>(w) - f0 * f0) * (n * n);
+        firsts[j] = n * f0;
+        has_first[j] = first;
       }
     }
   }
-  if constexpr (kStats) emit_tile_sums(tile_sums, g, tx, by, bz, s11, d1);
+  if constexpr (kStats) {
+    const double K = tile_pilot(firsts[0]);            // lane 0, j = 0: the tile's first block, always inside the array
+    double sq = 0.0, d = 0.0, count = 0.0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const double dj = has_first[j] ? firsts[j] - K : 0.0;
+      sq += dj * dj;
+      d += dj;
+      count += has_first[j] ? 1.0 : 0.0;
+    }
+    emit_tile_sums(tile_sums, g, tx, by, bz, rest, sq, d, count, K);
+  }
 }
 
 template <int TF, typename XT, int BZ, bool kTailX = false>

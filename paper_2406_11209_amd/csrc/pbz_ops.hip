@@ -556,6 +556,9 @@ struct ReduceTail {
   const void* pilot_f2;
   int64_t seg_n_bytes, seg_f_bytes;  // distance between the segments' first N and F
   int ntype, itype;
+  // sums made from the tile records of a compress kernel: K is the pilot value of the segment's first tile
+  const double* pilot_tiles;         // nullptr otherwise
+  int64_t tiles_per_segment;
 };
 
 // K of operand (N, F) in segment `segment`: the same expression wherever it is evaluated
@@ -624,7 +627,8 @@ __device__ __forceinline__ double group_total(const double* sums, double (*lds)[
 
 // the requested statistic(s) of segment `segment` from its five sums
 __device__ __forceinline__ void write_statistic(const double* fin, const ReduceTail& t, int64_t segment) {
-  const double K1 = pilot_value(t.pilot_n1, t.pilot_f1, t, segment);
+  const double K1 = t.pilot_tiles ? t.pilot_tiles[segment * t.tiles_per_segment * 4 + 2]
+                                  : pilot_value(t.pilot_n1, t.pilot_f1, t, segment);
   const double K2 = pilot_value(t.pilot_n2, t.pilot_f2, t, segment);
   if (t.op == kStatistics) {            // mean, variance and norm2 of one array from the same two sums
     ReduceTail one = t;
@@ -690,18 +694,21 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_final(ReduceTail t, in
   if (threadIdx.x == 0) write_statistic(fin, t, blockIdx.x);
 }
 
-// per-tile sums {S11, D1} left by a compress kernel -> partial sums per workgroup, added in tile order;
-// grid y runs over segments of n_tiles consecutive tiles
+// per-tile records {S, D, K, count} left by a compress kernel (first coefficients shifted by the tile's own pilot
+// value K) -> partial sums per workgroup relative to the pilot value of the segment's first tile, added in tile
+// order; grid y runs over segments of n_tiles consecutive tiles
 __global__ __launch_bounds__(kThreads) void k_reduce_tiles(const double2* __restrict__ tile_sums, int64_t n_tiles,
                                                            int64_t chunk, ReduceTail tail) {
   double sums[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
-  tile_sums += int64_t(blockIdx.y) * n_tiles;
+  tile_sums += int64_t(blockIdx.y) * n_tiles * 2;
+  const double K = tile_sums[1].x;                   // the segment's first tile
   const int64_t begin = int64_t(blockIdx.x) * chunk;
   const int64_t end = begin + chunk < n_tiles ? begin + chunk : n_tiles;
   for (int64_t t = begin + threadIdx.x; t < end; t += kThreads) {
-    const double2 v = tile_sums[t];
-    sums[kS11] += v.x;
-    sums[kD1] += v.y;
+    const double2 sd = tile_sums[2 * t], kc = tile_sums[2 * t + 1];
+    const double delta = kc.x - K;                   // sum (d + delta)^2 = S + 2 delta D + count delta^2
+    sums[kS11] += sd.x + 2.0 * delta * sd.y + kc.y * delta * delta;
+    sums[kD1] += sd.y + kc.y * delta;
   }
   reduce_tail(sums, tail);
 }
@@ -1036,6 +1043,8 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     tail.pilot_f1 = dc ? f1 : nullptr;
     tail.pilot_n2 = dc && two ? n2 : nullptr;
     tail.pilot_f2 = dc && two ? f2 : nullptr;
+    tail.pilot_tiles = nullptr;
+    tail.tiles_per_segment = 0;
     tail.seg_n_bytes = n_stride;
     tail.seg_f_bytes = f_stride;
     tail.ntype = int(c->ftype);
@@ -1088,7 +1097,7 @@ int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment,
   tail.partials = static_cast<double*>(workspace);
   tail.n_f16 = 0;
   tail.op = int(kStatistics);
-  tail.pilot_n1 = tail.pilot_f1 = tail.pilot_n2 = tail.pilot_f2 = nullptr;      // the tiles' sums are not shifted
+  tail.pilot_n1 = tail.pilot_f1 = tail.pilot_n2 = tail.pilot_f2 = nullptr;      // the pilot value comes from the tiles
   tail.seg_n_bytes = tail.seg_f_bytes = 0;
   tail.ntype = int(c->ftype);
   tail.itype = int(c->itype);
@@ -1105,9 +1114,10 @@ int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment,
       chunk = ((tiles_per_segment + max_groups - 1) / max_groups + kThreads - 1) / kThreads * kThreads;
     const int groups = int((tiles_per_segment + chunk - 1) / chunk);
     tail.out = out + seg0 * 3;
+    tail.pilot_tiles = tile_sums + seg0 * tiles_per_segment * 4;
+    tail.tiles_per_segment = tiles_per_segment;
     hipLaunchKernelGGL(k_reduce_tiles, dim3(groups, batch), dim3(kThreads), 0, s,
-                       reinterpret_cast<const double2*>(tile_sums) + seg0 * tiles_per_segment, tiles_per_segment, chunk,
-                       tail);
+                       reinterpret_cast<const double2*>(tail.pilot_tiles), tiles_per_segment, chunk, tail);
     int st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;
     if (groups > 1) {          // a single workgroup per segment has already written the results

@@ -661,6 +661,15 @@ def test_variance_of_a_field_with_a_large_offset():
                                 ("covariance", case.codec.covariance(N1, F1, N2, F2), po.covariance(A, B)),
                                 ("statistics.variance", case.codec.statistics(N1, F1)[1], po.variance(A))):
             assert abs(float(got.item()) - want) <= 1e-7 * abs(want), (block, name, float(got.item()), want)
+        _, _, st = case.codec.compress_statistics(case.xA)                   # the sums the compress kernel leaves behind
+        _, _, rows = case.codec.compress_statistics(case.xA, per_step=True)
+        torch.cuda.synchronize()
+        assert abs(float(st[1].item()) - po.variance(A)) <= 1e-7 * po.variance(A), (block, "compress_statistics", st)
+        per = A.n_blocks // A.b[0]
+        for t in (0, A.b[0] - 1):
+            run = po.Compressed(s=(A.i[0],) + tuple(A.s[1:]), i=A.i, N=A.N.reshape(A.b)[t:t + 1],
+                                F=A.F[t * per:(t + 1) * per], P=A.P, index_bits=A.index_bits, ftype=A.ftype)
+            assert abs(float(rows[t, 1].item()) - po.variance(run)) <= 1e-7 * po.variance(run), (block, "per step", t)
         got = float(case.codec.ssim(N1, F1, N2, F2, s_l=1e-8, s_c=1e-8).item())
         want = po.ssim(A, B, s_l=1e-8, s_c=1e-8)
         assert abs(got - want) <= 1e-6 * abs(want), (block, "ssim", got, want)

@@ -154,7 +154,7 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.pbz_statistics(nodc._h, 4, p, p, p, p, 1 << 20, None) == -6
     assert lib.pbz_statistics(h, 4, p, p, p, p, 64, None) == -8
     assert lib.pbz_compress_statistics_workspace(h, shape, 1, ctypes.byref(need)) == 0
-    assert need.value == c.layout((16, 16)).workspace_bytes + 2 * 16      # two block rows, one wave each, two FP64 sums per wave
+    assert need.value == c.layout((16, 16)).workspace_bytes + 2 * 32      # two block rows, one wave each, four FP64 values per wave
     assert lib.pbz_compress_statistics_workspace(h, bad_shape, 1, ctypes.byref(need)) == -7
     assert lib.pbz_compress_statistics(h, p, 1, shape, p, p, 0, None, p, 1 << 20, None) == -1
     assert lib.pbz_compress_statistics(nodc._h, p, 1, shape, p, p, 0, p, p, 1 << 20, None) == -6
