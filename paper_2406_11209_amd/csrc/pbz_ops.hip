@@ -715,9 +715,24 @@ __global__ __launch_bounds__(kThreads) void k_reduce_tiles(const double2* __rest
 
 // kDiff: the coefficients of the two operands are subtracted element by element before squaring (their
 // difference can be far smaller than either, so the block sums S11 - 2 S12 + S22 would cancel)
+struct HeadTerms {          // see the kDC branch of accumulate_vec
+  uint32_t first_mask, rest_mask;
+  double K1, K2;
+};
+template <int kIType>
+__device__ __forceinline__ HeadTerms head_terms(bool head, double K1, double K2) {
+  constexpr uint32_t kRest = kIType == PBZ_I8 ? 0xffffff00u : (kIType == PBZ_I16 ? 0xffff0000u : 0u);
+  HeadTerms h;
+  h.first_mask = head ? 0xffffffffu : 0u;
+  h.rest_mask = head ? kRest : 0xffffffffu;
+  h.K1 = head ? K1 : 0.0;
+  h.K2 = head ? K2 : 0.0;
+  return h;
+}
+
 template <int kIType, bool kTwo, bool kDC, bool kDiff>
 __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, const uint4& b, double n1, double n2,
-                                               bool head, double K1 = 0.0, double K2 = 0.0) {
+                                               const HeadTerms& head) {
   if (kDiff) {
     constexpr int kPer = kIType == PBZ_I8 ? 4 : (kIType == PBZ_I16 ? 2 : 1);
     const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
@@ -737,21 +752,24 @@ __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, con
     return;
   }
   if (kDC) {
-    // the block's first coefficient leaves the integer sums (cleared in the vector that holds it) and enters
-    // shifted by the pilot value
-    constexpr uint32_t kRest = kIType == PBZ_I8 ? 0xffffff00u : (kIType == PBZ_I16 ? 0xffff0000u : 0u);
-    const double d1 = head ? n1 * double(first_element<kIType>(a.x)) - K1 : 0.0;
-    const double d2 = (kTwo && head) ? n2 * double(first_element<kIType>(b.x)) - K2 : 0.0;
+    // The block's first coefficient leaves the integer sums (cleared in the vector that holds it) and enters
+    // shifted by the pilot value.  `head` says whether this vector starts a block: first_mask = all ones and
+    // rest_mask = everything but the first element for such a vector, 0 and all ones otherwise; K1, K2 are
+    // already zero for the other vectors.
+    const double f0 = double(int(uint32_t(first_element<kIType>(a.x)) & head.first_mask));
+    const double d1 = fma(n1, f0, -head.K1);
     uint4 ar = a, br = b;
-    ar.x = head ? (a.x & kRest) : a.x;
-    br.x = head ? (b.x & kRest) : b.x;
-    sums[kS11] += dot_vec<kIType>(ar, ar) * (n1 * n1) + d1 * d1;
-    if (kTwo) {
-      sums[kS12] += dot_vec<kIType>(ar, br) * (n1 * n2) + d1 * d2;
-      sums[kS22] += dot_vec<kIType>(br, br) * (n2 * n2) + d2 * d2;
-    }
+    ar.x &= head.rest_mask;
+    sums[kS11] = fma(d1, d1, fma(dot_vec<kIType>(ar, ar), n1 * n1, sums[kS11]));
     sums[kD1] += d1;
-    if (kTwo) sums[kD2] += d2;
+    if (kTwo) {
+      const double g0 = double(int(uint32_t(first_element<kIType>(b.x)) & head.first_mask));
+      const double d2 = fma(n2, g0, -head.K2);
+      br.x &= head.rest_mask;
+      sums[kS12] = fma(d1, d2, fma(dot_vec<kIType>(ar, br), n1 * n2, sums[kS12]));
+      sums[kS22] = fma(d2, d2, fma(dot_vec<kIType>(br, br), n2 * n2, sums[kS22]));
+      sums[kD2] += d2;
+    }
     return;
   }
   sums[kS11] += dot_vec<kIType>(a, a) * (n1 * n1);
@@ -766,7 +784,7 @@ __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, con
 // thread issues kUnroll loads per operand, kThreads vectors apart, with no branch between them.
 constexpr int reduce_unroll(bool two) { return two ? kUnroll : 2 * kUnroll; }
 
-template <int kIType, int kNType, bool kTwo, bool kDC, bool kDiff = false>
+template <int kIType, int kNType, bool kTwo, bool kDC, bool kDiff = false, bool kAnyHeads = false>
 __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                          const void* __restrict__ N2, const uint4* __restrict__ F2,
                                                          int64_t nvec, int64_t chunk, int vpb_shift, int64_t vpb,
@@ -784,6 +802,11 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
   }
   const double K1 = kDC ? pilot_value(tail.pilot_n1, tail.pilot_f1, tail, blockIdx.y) : 0.0;
   const double K2 = kDC && kTwo ? pilot_value(tail.pilot_n2, tail.pilot_f2, tail, blockIdx.y) : 0.0;
+  // Whether a thread's vector starts a block does not change from step to step when the vectors per block are a
+  // power of two that divides the step (every workgroup starts at a multiple of it): its head terms are then
+  // computed once.  The host launches the kAnyHeads variant (which works them out per vector, at the price of 30
+  // more registers) for every other layout.
+  const HeadTerms fixed = head_terms<kIType>(kDC && (threadIdx.x & (vpb - 1)) == 0, K1, K2);
   const int64_t begin = int64_t(blockIdx.x) * chunk;
   const int64_t end = begin + chunk < nvec ? begin + chunk : nvec;
   constexpr int kLoads = reduce_unroll(kTwo);       // the same bytes in flight with one operand as with two
@@ -808,8 +831,9 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
 #pragma unroll
     for (int u = 0; u < kLoads; ++u) {
       const int64_t v = base + u * kThreads + threadIdx.x;
-      accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a[u], kTwo ? b[kTwo ? u : 0] : a[u], n1[u], n2[u],
-                                               kDC && (v - k[u] * vpb) == 0, K1, K2);
+      accumulate_vec<kIType, kTwo, kDC, kDiff>(
+          sums, a[u], kTwo ? b[kTwo ? u : 0] : a[u], n1[u], n2[u],
+          kAnyHeads ? head_terms<kIType>(kDC && (v - k[u] * vpb) == 0, K1, K2) : fixed);
     }
   }
   for (int64_t v = base + threadIdx.x; v < end; v += kThreads) {
@@ -818,7 +842,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
     const uint4 b = kTwo ? F2[v] : a;
     accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a, b, load_N<kNType>(N1, k, tail.n_f16 != 0),
                                              kTwo ? load_N<kNType>(N2, k, tail.n_f16 != 0) : 0.0,
-                                             kDC && (v - k * vpb) == 0, K1, K2);
+                                             kAnyHeads ? head_terms<kIType>(kDC && (v - k * vpb) == 0, K1, K2) : fixed);
   }
   reduce_tail(sums, tail);
 }
@@ -894,12 +918,19 @@ void launch_reduce_vec2(bool two, bool dc, bool diff, dim3 grid, hipStream_t s, 
   dim3 block(kThreads);
   if (diff)
     hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-  else if (two && dc)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-  else if (two)
+  else if (dc) {
+    // does the same thread meet the first vector of a block at every step?
+    const bool fixed_heads = shift >= 0 && vpb <= kThreads;
+    if (two && fixed_heads)
+      hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
+    else if (two)
+      hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
+    else if (fixed_heads)
+      hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, true, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
+    else
+      hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, true, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
+  } else if (two)
     hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-  else if (dc)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
   else
     hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
 }
