@@ -12,6 +12,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
+constexpr int kReduceGroupsOneSegment = 1024;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -1064,7 +1065,10 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
   // the workspace holds kReduceMaxGroups partial sums: segments are handled in batches of at most that many
   for (int64_t seg0 = 0; seg0 < n_segments; seg0 += kReduceMaxGroups) {
     const int batch = int(n_segments - seg0 < kReduceMaxGroups ? n_segments - seg0 : kReduceMaxGroups);
-    const int max_groups = kReduceMaxGroups / batch;          // workgroups per segment
+    // workgroups per segment.  Four per compute unit measured best for one segment (2048 and 4096: the final kernel
+    // has more records to add and the streaming kernel's workgroups last one step; 512: too few waves for the
+    // passes that carry first coefficients; workload 5 dot 0.035 -> 0.030 ms, workload 4 norm 0.059 -> 0.056 ms)
+    const int max_groups = kReduceMaxGroups / batch < kReduceGroupsOneSegment ? kReduceMaxGroups / batch : kReduceGroupsOneSegment;
     const char* n1 = static_cast<const char*>(N1) + seg0 * n_stride;
     const char* f1 = static_cast<const char*>(F1) + seg0 * f_stride;
     const char* n2 = two ? static_cast<const char*>(N2) + seg0 * n_stride : nullptr;
