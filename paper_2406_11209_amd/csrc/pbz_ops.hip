@@ -626,11 +626,16 @@ __device__ __forceinline__ double group_total(const double* sums, double (*lds)[
   return t;
 }
 
+// the pilot values of segment `segment` (zero where the pass shifts nothing)
+__device__ __forceinline__ void pilot_values(const ReduceTail& t, int64_t segment, double* K1, double* K2) {
+  *K1 = t.pilot_tiles ? t.pilot_tiles[segment * t.tiles_per_segment * 4 + 2]
+                      : pilot_value(t.pilot_n1, t.pilot_f1, t, segment);
+  *K2 = pilot_value(t.pilot_n2, t.pilot_f2, t, segment);
+}
+
 // the requested statistic(s) of segment `segment` from its five sums
-__device__ __forceinline__ void write_statistic(const double* fin, const ReduceTail& t, int64_t segment) {
-  const double K1 = t.pilot_tiles ? t.pilot_tiles[segment * t.tiles_per_segment * 4 + 2]
-                                  : pilot_value(t.pilot_n1, t.pilot_f1, t, segment);
-  const double K2 = pilot_value(t.pilot_n2, t.pilot_f2, t, segment);
+__device__ __forceinline__ void write_statistic(const double* fin, const ReduceTail& t, int64_t segment, double K1,
+                                                double K2) {
   if (t.op == kStatistics) {            // mean, variance and norm2 of one array from the same two sums
     ReduceTail one = t;
     const int ops[3] = {kMean, kVariance, kNorm2};
@@ -652,20 +657,26 @@ __device__ __forceinline__ void reduce_tail(double* sums, const ReduceTail& t) {
   if (gridDim.x == 1) {
     if (threadIdx.x < kNumSums) fin[threadIdx.x] = total;
     __syncthreads();
-    if (threadIdx.x == 0) write_statistic(fin, t, blockIdx.y);
+    if (threadIdx.x == 0) {
+      double K1, K2;
+      pilot_values(t, blockIdx.y, &K1, &K2);
+      write_statistic(fin, t, blockIdx.y, K1, K2);
+    }
     return;
   }
   if (threadIdx.x < kNumSums)
     t.partials[(int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * kReducePartialSlots + threadIdx.x] = total;
 }
 
-// one workgroup per segment: adds that segment's n_partials partial sums in a fixed order.  Every thread first
-// issues all its loads (a partial is one 64-byte record whose five sums are read as three 16-byte pieces, at
-// most kReduceMaxGroups / kFinalThreads records per thread, from a clamped index: no branch around a load), then adds: the kernel's duration is one or two memory
-// round trips instead of one per partial.
-constexpr int kFinalThreads = 1024;
-constexpr int kFinalRecords = kReduceMaxGroups / kFinalThreads;
-static_assert(kReduceMaxGroups % kFinalThreads == 0 && kReducePartialSlots == 8, "record layout");
+// one workgroup per segment: adds that segment's n_partials (<= kFinalMaxPartials) partial sums in a fixed order.
+// Every thread first issues all its loads (a partial is one 64-byte record whose five sums are read as three
+// 16-byte pieces, kFinalRecords records per thread, from a clamped index: no branch around a load; the first
+// thread also asks for the pilot values it will need at the end), then adds: the kernel's duration is one memory
+// round trip instead of one per partial plus one for the pilot values.
+constexpr int kFinalThreads = 256;
+constexpr int kFinalMaxPartials = kReduceGroupsOneSegment;
+constexpr int kFinalRecords = kFinalMaxPartials / kFinalThreads;
+static_assert(kFinalMaxPartials % kFinalThreads == 0 && kReducePartialSlots == 8, "record layout");
 
 __global__ __launch_bounds__(kFinalThreads) void k_reduce_final(ReduceTail t, int n_partials) {
   __shared__ double lds[kFinalThreads / 64][kNumSums];
@@ -680,6 +691,8 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_final(ReduceTail t, in
 #pragma unroll
     for (int q = 0; q < 3; ++q) rec[j][q] = mine[int64_t(pc) * 4 + q];
   }
+  double K1 = 0.0, K2 = 0.0;
+  if (threadIdx.x == 0) pilot_values(t, blockIdx.x, &K1, &K2);
 #pragma unroll
   for (int j = 0; j < kFinalRecords; ++j)
     if (j * kFinalThreads + int(threadIdx.x) >= n_partials) rec[j][0] = rec[j][1] = rec[j][2] = make_double2(0.0, 0.0);
@@ -692,7 +705,7 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_final(ReduceTail t, in
   const double grand = group_total<kFinalThreads / 64>(acc, lds);
   if (threadIdx.x < kNumSums) fin[threadIdx.x] = grand;
   __syncthreads();
-  if (threadIdx.x == 0) write_statistic(fin, t, blockIdx.x);
+  if (threadIdx.x == 0) write_statistic(fin, t, blockIdx.x, K1, K2);
 }
 
 // per-tile records {S, D, K, count} left by a compress kernel (first coefficients shifted by the tile's own pilot
@@ -1142,7 +1155,7 @@ int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment,
   for (int64_t seg0 = 0; seg0 < n_segments; seg0 += kReduceMaxGroups) {
     const int batch = int(n_segments - seg0 < kReduceMaxGroups ? n_segments - seg0 : kReduceMaxGroups);
     int max_groups = kReduceMaxGroups / batch;
-    if (max_groups > 1024) max_groups = 1024;
+    if (max_groups > kReduceGroupsOneSegment) max_groups = kReduceGroupsOneSegment;
     // four tiles per thread and workgroup unless that needs more workgroups than the workspace has slots for
     int64_t chunk = int64_t(kThreads) * 4;
     if ((tiles_per_segment + chunk - 1) / chunk > max_groups)
