@@ -360,6 +360,9 @@ def main():
         "ops": per_op,
         "extra_ops": extra_ops,
         "roofline": roofline,
+        # the paper gives its timings as figures only (Sec. IV-E, Fig. 2: RTX 3090, FP64 / int8 / 8x8 blocks;
+        # Fig. 3: RTX 2070 Super; Fig. 8: hardware not stated), so there is no number to divide by
+        "paper_timings": "not reported numerically (figures only: Fig. 2 on an RTX 3090, Fig. 3 on an RTX 2070 Super, Fig. 8)",
     }
     if not args.no_cpu_baseline:
         # sized for roughly 10-30 s of oracle time on the machine's host cores
