@@ -20,6 +20,9 @@
 //                   y-row of all eight z-planes (z transform).  Decompression needs no exchange: every
 //                   lane rebuilds its own z-plane from the block's few kept coefficients; wide arrays use a
 //                   variant in which a wave owns one plane of 64 blocks and stores whole 1 KiB row pieces.
+// Family "cube16":  16x16x16 blocks of FP32 input, one block per wave (int16 indices in FP64 arithmetic, int8 in FP32).
+//                   Three layouts, one per transformed dimension, with a wave-private LDS exchange between them; the
+//                   first is how rows are read (16-byte pieces), the last how F is written (whole rows of indices).
 //
 // Variants of every kernel: kRagged (the slower dimensions are not multiples of the block extents), kTailX
 // (neither is the last one: rows start at any 4-byte boundary, the last block of a row is partial), kStats
@@ -30,7 +33,7 @@
 // reduces to at most three dimensions (leading dimensions with block extent 1 fold into the slowest one),
 // the block shape / types / mask box match an instantiation, rows are at least one 16-byte piece long and
 // start on a 4-byte boundary.
-// The families live in pbz_fast_lane.hip, pbz_fast_quad16.hip and pbz_fast_oct8.hip; this file folds the array
+// The families live in pbz_fast_lane.hip, pbz_fast_quad16.hip, pbz_fast_oct8.hip and pbz_fast_cube16.hip; this file folds the array
 // and asks each family in turn.
 #include "pbz_fast_common.h"
 
@@ -45,6 +48,7 @@ int try_compress_fast(const pbz_codec* c, const Geom& geo, const void* x, int xt
   int r = fast::lane_compress(c, f, xtype, x, N, F, s, dry_run, name, tile_sums);
   if (!*name) r = fast::quad16_compress(c, f, xtype, x, N, F, s, dry_run, name, tile_sums);
   if (!*name) r = fast::oct8_compress(c, f, xtype, x, N, F, s, dry_run, name, tile_sums);
+  if (!*name) r = fast::cube16_compress(c, f, xtype, x, N, F, s, dry_run, name, tile_sums);
   return r;
 }
 
@@ -54,6 +58,7 @@ int64_t fast_compress_tiles(const pbz_codec* c, const Geom& geo, int xtype) {
   int64_t t = fast::lane_tiles(c, f, xtype);
   if (t < 0) t = fast::quad16_tiles(c, f, xtype);
   if (t < 0) t = fast::oct8_tiles(c, f, xtype);
+  if (t < 0) t = fast::cube16_tiles(c, f, xtype);
   return t < 0 ? 0 : t;
 }
 
@@ -66,6 +71,7 @@ int try_decompress_fast(const pbz_codec* c, const Geom& geo, const void* N, cons
   int r = fast::lane_decompress(c, f, ytype, N, F, y, s, dry_run, name);
   if (!*name) r = fast::quad16_decompress(c, f, ytype, N, F, y, s, dry_run, name);
   if (!*name) r = fast::oct8_decompress(c, f, ytype, N, F, y, s, dry_run, name);
+  if (!*name) r = fast::cube16_decompress(c, f, ytype, N, F, y, s, dry_run, name);
   return r;
 }
 

@@ -554,6 +554,7 @@ template <> constexpr int itype_code<int16_t>() { return PBZ_I16; }
 PBZ_FAST_FAMILY(lane)
 PBZ_FAST_FAMILY(quad16)
 PBZ_FAST_FAMILY(oct8)
+PBZ_FAST_FAMILY(cube16)
 #undef PBZ_FAST_FAMILY
 
 // Defines the three functions of a family from its X-macro list FOR_EACH(X, TF, SUFFIX) of (type, name) rows,

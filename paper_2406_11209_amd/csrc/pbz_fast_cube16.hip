@@ -1,0 +1,331 @@
+// Specialised codec kernels, family "cube16" (see pbz_fast.hip for the overview).
+#include "pbz_fast_common.h"
+
+namespace pbz {
+namespace fast {
+namespace {
+
+// =====================================================================================================
+// Family "cube16": 16 x 16 x 16 blocks of FP32 arrays, nothing pruned; int16 indices with FP64 arithmetic (the
+// setting of the paper's fission-density experiment, Sec. V) or int8 indices with FP32 arithmetic
+// =====================================================================================================
+// A wave owns one block (4096 values, 64 per lane) and passes through three layouts, one per transformed
+// dimension, with a wave-private LDS exchange between them:
+//   A  lane = (z, q)        holds rows y = 0..15 of the four columns x = 4q..4q+3 of plane z      -> transform along y
+//   C  lane = (ky, q)       holds planes z = 0..15 of the same four columns at coefficient row ky  -> transform along z
+//   B  lane = (ky, zh)      holds the whole rows x = 0..15 of planes kz = 4 zh .. 4 zh + 3        -> transform along x
+// Layout A is how the array is read (16-byte pieces of a row), layout B is how F is written (whole rows of
+// indices, consecutive in y).  An exchange moves 16 bytes per slot, i.e. four FP32 or two FP64 values of a lane's
+// column group, so FP64 takes two rounds per exchange through the same 17 KiB; the slot rows are 68 slots apart,
+// which makes both the linear writes and the transposed reads of either exchange free of bank conflicts.
+constexpr int kCubeRow = 68;                       // uint4 slots per LDS row
+constexpr int kCubeSlots = 16 * kCubeRow;
+
+template <typename T>
+struct CubeSlot;                                   // 16 bytes of a lane's values <-> uint4
+template <>
+struct CubeSlot<float> {
+  static constexpr int n = 4;
+  static __device__ __forceinline__ uint4 pack(const float* v) { return f4_bits(v); }
+  static __device__ __forceinline__ void unpack(const uint4& u, float* v) { bits_f4(u, v); }
+};
+template <>
+struct CubeSlot<double> {
+  static constexpr int n = 2;
+  static __device__ __forceinline__ uint4 pack(const double* v) {
+    const uint64_t a = __builtin_bit_cast(uint64_t, v[0]), b = __builtin_bit_cast(uint64_t, v[1]);
+    return make_uint4(uint32_t(a), uint32_t(a >> 32), uint32_t(b), uint32_t(b >> 32));
+  }
+  static __device__ __forceinline__ void unpack(const uint4& u, double* v) {
+    v[0] = __builtin_bit_cast(double, uint64_t(u.x) | (uint64_t(u.y) << 32));
+    v[1] = __builtin_bit_cast(double, uint64_t(u.z) | (uint64_t(u.w) << 32));
+  }
+};
+
+// layout A <-> layout C.  In A the lane is (z, q) and value [y * 4 + e] belongs to row y; in C the lane is
+// (ky, q) and value [z * 4 + e] belongs to plane z.  kToC: from A to C; otherwise from C to A.
+template <typename T, bool kToC>
+__device__ __forceinline__ void cube_exchange_zy(uint4* st, int lane, const T* from, T* to) {
+  using Slot = CubeSlot<T>;
+  const int hi = lane >> 2, q = lane & 3;
+#pragma unroll
+  for (int e0 = 0; e0 < 4; e0 += Slot::n) {
+    if (e0) wave_lds_sync();                       // the previous round's reads precede this round's writes
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      // A -> C: row i of plane hi goes to slot row i;  C -> A: plane i of row hi goes to slot row hi
+      const int slot = kToC ? i * kCubeRow + hi * 4 + q : hi * kCubeRow + i * 4 + q;
+      st[slot] = Slot::pack(from + i * 4 + e0);
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int slot = kToC ? hi * kCubeRow + i * 4 + q : i * kCubeRow + hi * 4 + q;
+      Slot::unpack(st[slot], to + i * 4 + e0);
+    }
+  }
+}
+
+// layout C <-> layout B.  In C the lane is (ky, q) and value [kz * 4 + e] is column 4 q + e of plane kz; in B the
+// lane is (ky, zh) = (lane & 15, lane >> 4) and value [zl * 16 + x] is column x of plane 4 zh + zl.
+template <typename T, bool kToB>
+__device__ __forceinline__ void cube_exchange_zx(uint4* st, int lane, const T* from, T* to) {
+  using Slot = CubeSlot<T>;
+  const int cy = lane >> 2, q = lane & 3;          // as a lane of layout C
+  const int ky = lane & 15, zh = lane >> 4;        // as a lane of layout B
+#pragma unroll
+  for (int e0 = 0; e0 < 4; e0 += Slot::n) {
+    if (e0) wave_lds_sync();
+    if constexpr (kToB) {
+#pragma unroll
+      for (int kz = 0; kz < 16; ++kz) st[kz * kCubeRow + q * 16 + cy] = Slot::pack(from + kz * 4 + e0);
+    } else {
+#pragma unroll
+      for (int zl = 0; zl < 4; ++zl)
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq)
+          st[(4 * zh + zl) * kCubeRow + qq * 16 + ky] = Slot::pack(from + zl * 16 + qq * 4 + e0);
+    }
+    wave_lds_sync();
+    if constexpr (kToB) {
+#pragma unroll
+      for (int zl = 0; zl < 4; ++zl)
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq)
+          Slot::unpack(st[(4 * zh + zl) * kCubeRow + qq * 16 + ky], to + zl * 16 + qq * 4 + e0);
+    } else {
+#pragma unroll
+      for (int kz = 0; kz < 16; ++kz) Slot::unpack(st[kz * kCubeRow + q * 16 + cy], to + kz * 4 + e0);
+    }
+  }
+}
+
+template <int TF, typename T, typename IT, bool kRagged, bool kStats, bool kTailX>
+__global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float* __restrict__ x, void* __restrict__ N,
+                                                         IT* __restrict__ F, double* __restrict__ tile_sums) {
+  using Q4 = Quad4<float>;
+  constexpr int PER = IdxPack<IT>::per;            // indices per dword
+  constexpr int ROWW = 16 / PER;                   // dwords per row of 16 indices
+  __shared__ uint4 lds[2][kCubeSlots];
+  const int lane = threadIdx.x & 63;
+  int64_t bx, by, bz;
+  if (!decode_tile<2>(g, bx, by, bz)) return;      // one block per tile
+  uint4* st = lds[threadIdx.x >> 6];
+
+  T a[64], c[64];
+  {  // layout A: read plane z = lane >> 2, columns 4 q .. 4 q + 3, all 16 rows
+    const int pz = lane >> 2, q = lane & 3;
+    int64_t zz = bz * 16 + pz;
+    uint32_t keep_z = 0xffffffffu;
+    if constexpr (kRagged) {
+      keep_z = zz < g.Z ? 0xffffffffu : 0u;        // planes past the end: load a valid one, zero it below
+      zz = zz < g.Z ? zz : g.Z - 1;
+    }
+    Q4::raw_t raw[16];
+    const int64_t x_first = bx * 16 + q * 4;
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      int64_t yy = by * 16 + yy0;
+      if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;
+      int64_t x0 = x_first;
+      if constexpr (kTailX) x0 = x0 + 4 <= g.X ? x0 : g.X - 4;
+      raw[yy0] = Q4::template load<kTailX>(x + (zz * g.Y + yy) * g.X + x0);
+    }
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      if constexpr (kRagged) Q4::keep(raw[yy0], by * 16 + yy0 < g.Y ? keep_z : 0u);
+      float f[4];
+      Q4::unpack(raw[yy0], f);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a[yy0 * 4 + e] = T(f[e]);
+    }
+    if constexpr (kTailX) {
+      if (x_first + 4 > g.X) {           // a piece of the row's last, partial block: element by element, zeros beyond
+#pragma unroll
+        for (int yy0 = 0; yy0 < 16; ++yy0) {
+          const int64_t yy = by * 16 + yy0;
+          const bool row_in = yy < g.Y && keep_z != 0u;
+          const float* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int64_t xi = x_first + e;
+            const float val = row[xi < g.X ? xi : g.X - 1];
+            a[yy0 * 4 + e] = row_in && xi < g.X ? T(val) : T(0);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tf_forward<TF, T, 16, 4>(a + e);
+  }
+  cube_exchange_zy<T, true>(st, lane, a, c);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) tf_forward<TF, T, 16, 4>(c + e);
+  wave_lds_sync();
+  cube_exchange_zx<T, true>(st, lane, c, a);
+#pragma unroll
+  for (int zl = 0; zl < 4; ++zl) tf_forward<TF, T, 16, 1>(a + zl * 16);
+
+  // layout B: lane = (ky, zh) holds rows (kz = 4 zh + zl, ky) of the coefficients
+  T m = T(0);
+#pragma unroll
+  for (int i = 0; i < 64; ++i) m = fmax(m, fabs(a[i]));
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) m = fmax(m, __shfl_xor(m, off, 64));
+  const T inv = m > T(0) ? T(g.r) / m : T(0);
+  const int ky = lane & 15, zh = lane >> 4;
+  const int64_t block = (bz * g.gy + by) * g.gx + bx;
+  uint32_t w[4 * ROWW];
+#pragma unroll
+  for (int zl = 0; zl < 4; ++zl)
+#pragma unroll
+    for (int k = 0; k < ROWW; ++k) {
+      uint32_t q[PER];
+#pragma unroll
+      for (int e = 0; e < PER; ++e) q[e] = bin_bits(a[zl * 16 + k * PER + e], inv);
+      w[zl * ROWW + k] = IdxPack<IT>::pack(q);
+    }
+  uint4* dst = reinterpret_cast<uint4*>(F + block * 4096);
+#pragma unroll
+  for (int zl = 0; zl < 4; ++zl)
+#pragma unroll
+    for (int k = 0; k < ROWW / 4; ++k)
+      dst[(((4 * zh + zl) * 16 + ky) * ROWW) / 4 + k] =
+          make_uint4(w[zl * ROWW + 4 * k], w[zl * ROWW + 4 * k + 1], w[zl * ROWW + 4 * k + 2], w[zl * ROWW + 4 * k + 3]);
+  if (lane == 0) store_float(N, g.ntype, block, m);
+  if constexpr (kStats) {
+    const double n = stored_N(m, g.ntype);
+    const double f0 = lane == 0 ? double(IdxPack<IT>::get(w[0], 0)) : 0.0;
+    const double rest = (sum_of_squares<IT, 4 * ROWW>(w) - f0 * f0) * (n * n);
+    const double K = tile_pilot(n * f0);           // one block per tile: its first coefficient is the pilot value
+    emit_tile_sums(tile_sums, g, bx, by, bz, rest, 0.0, 0.0, lane == 0 ? 1.0 : 0.0, K);
+  }
+}
+
+template <int TF, typename T, typename IT, bool kTailX>
+__global__ __launch_bounds__(128) void k_decompress_cube16(FastGeom g, const void* __restrict__ N,
+                                                           const IT* __restrict__ F, float* __restrict__ y) {
+  using Q4 = Quad4<float>;
+  constexpr int PER = IdxPack<IT>::per;
+  constexpr int ROWW = 16 / PER;
+  __shared__ uint4 lds[2][kCubeSlots];
+  const int lane = threadIdx.x & 63;
+  int64_t bx, by, bz;
+  if (!decode_tile<2>(g, bx, by, bz)) return;
+  uint4* st = lds[threadIdx.x >> 6];
+  const int64_t block = (bz * g.gy + by) * g.gx + bx;
+
+  T a[64], c[64];
+  {  // layout B: rows (kz = 4 zh + zl, ky) of the indices
+    const int ky = lane & 15, zh = lane >> 4;
+    const uint4* src = reinterpret_cast<const uint4*>(F + block * 4096);
+    uint4 f[4 * (ROWW / 4)];
+#pragma unroll
+    for (int zl = 0; zl < 4; ++zl)
+#pragma unroll
+      for (int k = 0; k < ROWW / 4; ++k) f[zl * (ROWW / 4) + k] = src[(((4 * zh + zl) * 16 + ky) * ROWW) / 4 + k];
+    const T scale = load_float<T>(N, g.ntype, block) / T(g.r);        // Algorithm 3: N F / r
+#pragma unroll
+    for (int zl = 0; zl < 4; ++zl)
+#pragma unroll
+      for (int k = 0; k < ROWW / 4; ++k) {
+        const uint4 u = f[zl * (ROWW / 4) + k];
+        const uint32_t uw[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+          for (int e = 0; e < PER; ++e)
+            a[zl * 16 + (4 * k + d) * PER + e] = scale * T(IdxPack<IT>::get(uw[d], e));
+      }
+#pragma unroll
+    for (int zl = 0; zl < 4; ++zl) tf_inverse<TF, T, 16, 1, 16>(a + zl * 16);
+  }
+  cube_exchange_zx<T, false>(st, lane, a, c);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) tf_inverse<TF, T, 16, 4, 16>(c + e);
+  wave_lds_sync();
+  cube_exchange_zy<T, false>(st, lane, c, a);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) tf_inverse<TF, T, 16, 4, 16>(a + e);
+
+  // layout A: plane z = lane >> 2, columns 4 q .. 4 q + 3
+  const int pz = lane >> 2, q = lane & 3;
+  const int64_t zz = bz * 16 + pz;
+  if (zz < g.Z) {
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) {
+      const int64_t yy = by * 16 + yy0;
+      if (yy < g.Y) {
+        float f[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = float(a[yy0 * 4 + e]);
+        float* row = y + (zz * g.Y + yy) * g.X;
+        const int64_t x0 = bx * 16 + q * 4;
+        if constexpr (kTailX) {
+          if (x0 + 4 <= g.X) {
+            Q4::template store<true>(row + x0, Q4::pack(f));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (x0 + e < g.X) row[x0 + e] = f[e];
+          }
+        } else {
+          Q4::template store<false>(row + x0, Q4::pack(f));
+        }
+      }
+    }
+  }
+}
+
+template <int TF, typename T, typename IT>
+struct Cube16Kernel {
+  static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
+    return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<float>() &&
+           int(c->itype) == itype_code<IT>() && f.bz == 16 && f.by == 16 && f.bx == 16 && f.kz == 16 && f.ky == 16 &&
+           f.kx == 16 && x_extent_ok(f, 4, 4);
+  }
+  static int fits(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 1, 2, &grid) ? 1 : 0;
+  }
+  static int64_t tiles(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 1, 2, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
+  }
+  template <bool kRagged, bool kStats, bool kTailX>
+  static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    hipLaunchKernelGGL((k_compress_cube16<TF, T, IT, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
+                       static_cast<const float*>(x), N, static_cast<IT*>(F), tile_sums);
+  }
+  static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    dim3 grid;
+    if (!tile_grid(g, 1, 2, &grid)) return 0;
+    const bool ragged = g.Y % 16 || g.Z % 16;
+    if (g.X % 16) tile_sums ? launch<true, true, true>(g, grid, x, N, F, tile_sums, s) : launch<true, false, true>(g, grid, x, N, F, nullptr, s);
+    else if (tile_sums) ragged ? launch<true, true, false>(g, grid, x, N, F, tile_sums, s) : launch<false, true, false>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false, false>(g, grid, x, N, F, nullptr, s) : launch<false, false, false>(g, grid, x, N, F, nullptr, s);
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+  static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
+    dim3 grid;
+    if (!tile_grid(g, 1, 2, &grid)) return 0;
+    if (g.X % 16)
+      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, true>), grid, dim3(128), 0, s, g, N, static_cast<const IT*>(F),
+                         static_cast<float*>(y));
+    else
+      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, false>), grid, dim3(128), 0, s, g, N, static_cast<const IT*>(F),
+                         static_cast<float*>(y));
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+};
+
+#define PBZ_ROWS(X, TF, SUFFIX) \
+  X(Cube16Kernel<TF COMMA double COMMA int16_t>, "cube16_f32_16x16x16_i16" SUFFIX) \
+  X(Cube16Kernel<TF COMMA float COMMA int8_t>, "cube16_f32_16x16x16_i8" SUFFIX)
+
+}  // namespace
+
+PBZ_DEFINE_FAST_FAMILY(cube16, PBZ_ROWS)
+
+}  // namespace fast
+}  // namespace pbz
