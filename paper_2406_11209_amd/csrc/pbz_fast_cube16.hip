@@ -16,10 +16,18 @@ namespace {
 //   B  lane = (ky, zh)      holds the whole rows x = 0..15 of planes kz = 4 zh .. 4 zh + 3        -> transform along x
 // Layout A is how the array is read (16-byte pieces of a row), layout B is how F is written (whole rows of
 // indices, consecutive in y).  An exchange moves 16 bytes per slot, i.e. four FP32 or two FP64 values of a lane's
-// column group, so FP64 takes two rounds per exchange through the same 17 KiB; the slot rows are 68 slots apart,
-// which makes both the linear writes and the transposed reads of either exchange free of bank conflicts.
-constexpr int kCubeRow = 68;                       // uint4 slots per LDS row
+// column group, so FP64 takes two rounds per exchange through the same 16 KiB.  A 16-byte LDS access is served
+// eight consecutive lanes at a time, and those eight must fall into different slots modulo 8; one side of either
+// exchange is linear in the lane, the other side's slot index is swizzled so that it meets the rule as well
+// (shader counters: 768 conflict cycles per wave with a plain transposed index, none with the swizzles).
+constexpr int kCubeRow = 64;                       // uint4 slots per LDS row
 constexpr int kCubeSlots = 16 * kCubeRow;
+constexpr int kCubeWaves = 2;                      // blocks (consecutive along x) per workgroup
+
+// exchange A <-> C: element (row y, plane z, column group q)
+__device__ __forceinline__ int cube_slot_zy(int y, int z, int q) { return y * kCubeRow + ((z * 4 + q) ^ ((y & 1) << 2)); }
+// exchange C <-> B: element (plane kz, column group q, row y)
+__device__ __forceinline__ int cube_slot_zx(int kz, int q, int y) { return kz * kCubeRow + q * 16 + ((y + 2 * q) & 15); }
 
 template <typename T>
 struct CubeSlot;                                   // 16 bytes of a lane's values <-> uint4
@@ -53,15 +61,13 @@ __device__ __forceinline__ void cube_exchange_zy(uint4* st, int lane, const T* f
     if (e0) wave_lds_sync();                       // the previous round's reads precede this round's writes
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      // A -> C: row i of plane hi goes to slot row i;  C -> A: plane i of row hi goes to slot row hi
-      const int slot = kToC ? i * kCubeRow + hi * 4 + q : hi * kCubeRow + i * 4 + q;
-      st[slot] = Slot::pack(from + i * 4 + e0);
+      // A -> C: this lane is plane hi and value i its row;  C -> A: this lane is row hi and value i its plane
+      st[kToC ? cube_slot_zy(i, hi, q) : cube_slot_zy(hi, i, q)] = Slot::pack(from + i * 4 + e0);
     }
     wave_lds_sync();
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int slot = kToC ? hi * kCubeRow + i * 4 + q : i * kCubeRow + hi * 4 + q;
-      Slot::unpack(st[slot], to + i * 4 + e0);
+      Slot::unpack(st[kToC ? cube_slot_zy(hi, i, q) : cube_slot_zy(i, hi, q)], to + i * 4 + e0);
     }
   }
 }
@@ -78,13 +84,13 @@ __device__ __forceinline__ void cube_exchange_zx(uint4* st, int lane, const T* f
     if (e0) wave_lds_sync();
     if constexpr (kToB) {
 #pragma unroll
-      for (int kz = 0; kz < 16; ++kz) st[kz * kCubeRow + q * 16 + cy] = Slot::pack(from + kz * 4 + e0);
+      for (int kz = 0; kz < 16; ++kz) st[cube_slot_zx(kz, q, cy)] = Slot::pack(from + kz * 4 + e0);
     } else {
 #pragma unroll
       for (int zl = 0; zl < 4; ++zl)
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq)
-          st[(4 * zh + zl) * kCubeRow + qq * 16 + ky] = Slot::pack(from + zl * 16 + qq * 4 + e0);
+          st[cube_slot_zx(4 * zh + zl, qq, ky)] = Slot::pack(from + zl * 16 + qq * 4 + e0);
     }
     wave_lds_sync();
     if constexpr (kToB) {
@@ -92,24 +98,24 @@ __device__ __forceinline__ void cube_exchange_zx(uint4* st, int lane, const T* f
       for (int zl = 0; zl < 4; ++zl)
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq)
-          Slot::unpack(st[(4 * zh + zl) * kCubeRow + qq * 16 + ky], to + zl * 16 + qq * 4 + e0);
+          Slot::unpack(st[cube_slot_zx(4 * zh + zl, qq, ky)], to + zl * 16 + qq * 4 + e0);
     } else {
 #pragma unroll
-      for (int kz = 0; kz < 16; ++kz) Slot::unpack(st[kz * kCubeRow + q * 16 + cy], to + kz * 4 + e0);
+      for (int kz = 0; kz < 16; ++kz) Slot::unpack(st[cube_slot_zx(kz, q, cy)], to + kz * 4 + e0);
     }
   }
 }
 
 template <int TF, typename T, typename IT, bool kRagged, bool kStats, bool kTailX>
-__global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float* __restrict__ x, void* __restrict__ N,
+__global__ __launch_bounds__(64 * kCubeWaves) void k_compress_cube16(FastGeom g, const float* __restrict__ x, void* __restrict__ N,
                                                          IT* __restrict__ F, double* __restrict__ tile_sums) {
   using Q4 = Quad4<float>;
   constexpr int PER = IdxPack<IT>::per;            // indices per dword
   constexpr int ROWW = 16 / PER;                   // dwords per row of 16 indices
-  __shared__ uint4 lds[2][kCubeSlots];
+  __shared__ uint4 lds[kCubeWaves][kCubeSlots];
   const int lane = threadIdx.x & 63;
   int64_t bx, by, bz;
-  if (!decode_tile<2>(g, bx, by, bz)) return;      // one block per tile
+  if (!decode_tile<kCubeWaves>(g, bx, by, bz)) return;      // one block per tile
   uint4* st = lds[threadIdx.x >> 6];
 
   T a[64], c[64];
@@ -203,15 +209,15 @@ __global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float
 }
 
 template <int TF, typename T, typename IT, bool kTailX>
-__global__ __launch_bounds__(128) void k_decompress_cube16(FastGeom g, const void* __restrict__ N,
+__global__ __launch_bounds__(64 * kCubeWaves) void k_decompress_cube16(FastGeom g, const void* __restrict__ N,
                                                            const IT* __restrict__ F, float* __restrict__ y) {
   using Q4 = Quad4<float>;
   constexpr int PER = IdxPack<IT>::per;
   constexpr int ROWW = 16 / PER;
-  __shared__ uint4 lds[2][kCubeSlots];
+  __shared__ uint4 lds[kCubeWaves][kCubeSlots];
   const int lane = threadIdx.x & 63;
   int64_t bx, by, bz;
-  if (!decode_tile<2>(g, bx, by, bz)) return;
+  if (!decode_tile<kCubeWaves>(g, bx, by, bz)) return;
   uint4* st = lds[threadIdx.x >> 6];
   const int64_t block = (bz * g.gy + by) * g.gx + bx;
 
@@ -286,20 +292,20 @@ struct Cube16Kernel {
   }
   static int fits(FastGeom g) {
     dim3 grid;
-    return tile_grid(g, 1, 2, &grid) ? 1 : 0;
+    return tile_grid(g, 1, kCubeWaves, &grid) ? 1 : 0;
   }
   static int64_t tiles(FastGeom g) {
     dim3 grid;
-    return tile_grid(g, 1, 2, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
+    return tile_grid(g, 1, kCubeWaves, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
   }
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_cube16<TF, T, IT, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
+    hipLaunchKernelGGL((k_compress_cube16<TF, T, IT, kRagged, kStats, kTailX>), grid, dim3(64 * kCubeWaves), 0, s, g,
                        static_cast<const float*>(x), N, static_cast<IT*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
-    if (!tile_grid(g, 1, 2, &grid)) return 0;
+    if (!tile_grid(g, 1, kCubeWaves, &grid)) return 0;
     const bool ragged = g.Y % 16 || g.Z % 16;
     if (g.X % 16) tile_sums ? launch<true, true, true>(g, grid, x, N, F, tile_sums, s) : launch<true, false, true>(g, grid, x, N, F, nullptr, s);
     else if (tile_sums) ragged ? launch<true, true, false>(g, grid, x, N, F, tile_sums, s) : launch<false, true, false>(g, grid, x, N, F, tile_sums, s);
@@ -308,12 +314,12 @@ struct Cube16Kernel {
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
-    if (!tile_grid(g, 1, 2, &grid)) return 0;
+    if (!tile_grid(g, 1, kCubeWaves, &grid)) return 0;
     if (g.X % 16)
-      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, true>), grid, dim3(128), 0, s, g, N, static_cast<const IT*>(F),
+      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, true>), grid, dim3(64 * kCubeWaves), 0, s, g, N, static_cast<const IT*>(F),
                          static_cast<float*>(y));
     else
-      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, false>), grid, dim3(128), 0, s, g, N, static_cast<const IT*>(F),
+      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, false>), grid, dim3(64 * kCubeWaves), 0, s, g, N, static_cast<const IT*>(F),
                          static_cast<float*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
