@@ -9,25 +9,47 @@ namespace {
 // Family "cube16": 16 x 16 x 16 blocks of FP32 arrays, nothing pruned; int16 indices with FP64 arithmetic (the
 // setting of the paper's fission-density experiment, Sec. V) or int8 indices with FP32 arithmetic
 // =====================================================================================================
-// A wave owns one block (4096 values, 64 per lane) and passes through three layouts, one per transformed
-// dimension, with a wave-private LDS exchange between them:
-//   A  lane = (z, q)        holds rows y = 0..15 of the four columns x = 4q..4q+3 of plane z      -> transform along y
-//   C  lane = (ky, q)       holds planes z = 0..15 of the same four columns at coefficient row ky  -> transform along z
-//   B  lane = (ky, zh)      holds the whole rows x = 0..15 of planes kz = 4 zh .. 4 zh + 3        -> transform along x
-// Layout A is how the array is read (16-byte pieces of a row), layout B is how F is written (whole rows of
-// indices, consecutive in y).  An exchange moves 16 bytes per slot, i.e. four FP32 or two FP64 values of a lane's
-// column group, so FP64 takes two rounds per exchange through the same 16 KiB.  A 16-byte LDS access is served
-// eight consecutive lanes at a time, and those eight must fall into different slots modulo 8; one side of either
-// exchange is linear in the lane, the other side's slot index is swizzled so that it meets the rule as well
-// (shader counters: 768 conflict cycles per wave with a plain transposed index, none with the swizzles).
+// A workgroup of two waves owns two blocks that are neighbours along x; wave w ends up with block w (4096 values,
+// 64 per lane).  The values pass through three layouts, one per transformed dimension, with an LDS exchange
+// between them:
+//   A  wave w, lane = (zl, blk, q)  holds rows y = 0..15 of the four columns x = 4q..4q+3 of plane z = 8 w + zl of
+//                                   block blk                                                 -> transform along y
+//   C  wave = block, lane = (ky, q) holds planes z = 0..15 of the same four columns at coefficient row ky
+//                                                                                             -> transform along z
+//   B  wave = block, lane = (ky, zh) holds the whole rows x = 0..15 of planes kz = 4 zh .. 4 zh + 3
+//                                                                                             -> transform along x
+// Layout A is how the array is read and written: eight consecutive lanes cover the 128 contiguous bytes that the
+// two blocks have in one array row, so that every memory line is touched by one instruction of one wave (with
+// one block per wave and 64-byte pieces, two waves shared every line and the counters showed 1.46 bytes fetched
+// per byte of input and 1.23 written per byte of output).  The exchange between A and C therefore crosses the two
+// waves (workgroup barriers); the one between C and B is private to a wave.  Layout B is how F is written
+// (whole rows of indices, consecutive in y).  An exchange moves 16 bytes per slot, i.e. four FP32 or two FP64
+// values of a lane's column group, so FP64 takes two rounds per exchange through the same 16 KiB per block.  A
+// 16-byte LDS access is served eight consecutive lanes at a time, and those eight must fall into different slots
+// modulo 8; one side of either exchange is linear in the lane, the other side's slot index is swizzled so that
+// it meets the rule as well (shader counters: 768 conflict cycles per wave with a plain transposed index, none
+// with the swizzles).
 constexpr int kCubeRow = 64;                       // uint4 slots per LDS row
-constexpr int kCubeSlots = 16 * kCubeRow;
-constexpr int kCubeWaves = 2;                      // blocks (consecutive along x) per workgroup
+constexpr int kCubeSlots = 16 * kCubeRow;          // per block
 
-// exchange A <-> C: element (row y, plane z, column group q)
-__device__ __forceinline__ int cube_slot_zy(int y, int z, int q) { return y * kCubeRow + ((z * 4 + q) ^ ((y & 1) << 2)); }
-// exchange C <-> B: element (plane kz, column group q, row y)
+// exchange A <-> C: element (row y, plane z, column group q) of block blk, in the workgroup's LDS
+__device__ __forceinline__ int cube_slot_zy(int blk, int y, int z, int q) {
+  return blk * kCubeSlots + y * kCubeRow + ((z * 4 + q) ^ (((y & 1) ^ blk) << 2));
+}
+// exchange C <-> B: element (plane kz, column group q, row y), in the block's own LDS
 __device__ __forceinline__ int cube_slot_zx(int kz, int q, int y) { return kz * kCubeRow + q * 16 + ((y + 2 * q) & 15); }
+
+// Which pair of blocks does this workgroup own?  Uniform over the workgroup (both waves stay or leave together).
+__device__ __forceinline__ bool decode_pair(const FastGeom& g, int64_t& pair_x, int64_t& by, int64_t& bz) {
+  const uint32_t t = blockIdx.x;
+  const uint32_t slab = blockIdx.y + blockIdx.z * gridDim.y;
+  if (t >= g.tiles_yx || slab >= g.gz) return false;
+  const uint32_t row = t / g.tiles_x;
+  pair_x = t - row * g.tiles_x;
+  by = row;
+  bz = slab;
+  return true;
+}
 
 template <typename T>
 struct CubeSlot;                                   // 16 bytes of a lane's values <-> uint4
@@ -50,25 +72,24 @@ struct CubeSlot<double> {
   }
 };
 
-// layout A <-> layout C.  In A the lane is (z, q) and value [y * 4 + e] belongs to row y; in C the lane is
-// (ky, q) and value [z * 4 + e] belongs to plane z.  kToC: from A to C; otherwise from C to A.
+// layout A <-> layout C across the two waves of the workgroup.  In A, wave w's lane (zl, blk, q) holds value
+// [y * 4 + e] of plane 8 w + zl of block blk; in C, wave w's lane (ky, q) holds value [z * 4 + e] of block w.
+// kToC: from A to C; otherwise from C to A.  Both waves must call it (barriers).
 template <typename T, bool kToC>
-__device__ __forceinline__ void cube_exchange_zy(uint4* st, int lane, const T* from, T* to) {
+__device__ __forceinline__ void cube_exchange_zy(uint4* lds, int wave, int lane, const T* from, T* to) {
   using Slot = CubeSlot<T>;
-  const int hi = lane >> 2, q = lane & 3;
+  const int z = 8 * wave + (lane >> 3), blk = (lane >> 2) & 1, q = lane & 3;     // as a lane of layout A
+  const int cy = lane >> 2;                                                      // as a lane of layout C
 #pragma unroll
   for (int e0 = 0; e0 < 4; e0 += Slot::n) {
-    if (e0) wave_lds_sync();                       // the previous round's reads precede this round's writes
+    if (e0) __syncthreads();                       // the previous round's reads precede this round's writes
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      // A -> C: this lane is plane hi and value i its row;  C -> A: this lane is row hi and value i its plane
-      st[kToC ? cube_slot_zy(i, hi, q) : cube_slot_zy(hi, i, q)] = Slot::pack(from + i * 4 + e0);
-    }
-    wave_lds_sync();
+    for (int i = 0; i < 16; ++i)
+      lds[kToC ? cube_slot_zy(blk, i, z, q) : cube_slot_zy(wave, cy, i, q)] = Slot::pack(from + i * 4 + e0);
+    __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      Slot::unpack(st[kToC ? cube_slot_zy(hi, i, q) : cube_slot_zy(i, hi, q)], to + i * 4 + e0);
-    }
+    for (int i = 0; i < 16; ++i)
+      Slot::unpack(lds[kToC ? cube_slot_zy(wave, cy, i, q) : cube_slot_zy(blk, i, z, q)], to + i * 4 + e0);
   }
 }
 
@@ -107,20 +128,25 @@ __device__ __forceinline__ void cube_exchange_zx(uint4* st, int lane, const T* f
 }
 
 template <int TF, typename T, typename IT, bool kRagged, bool kStats, bool kTailX>
-__global__ __launch_bounds__(64 * kCubeWaves) void k_compress_cube16(FastGeom g, const float* __restrict__ x, void* __restrict__ N,
+__global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float* __restrict__ x, void* __restrict__ N,
                                                          IT* __restrict__ F, double* __restrict__ tile_sums) {
   using Q4 = Quad4<float>;
   constexpr int PER = IdxPack<IT>::per;            // indices per dword
   constexpr int ROWW = 16 / PER;                   // dwords per row of 16 indices
-  __shared__ uint4 lds[kCubeWaves][kCubeSlots];
+  __shared__ uint4 lds[2 * kCubeSlots];
   const int lane = threadIdx.x & 63;
-  int64_t bx, by, bz;
-  if (!decode_tile<kCubeWaves>(g, bx, by, bz)) return;      // one block per tile
-  uint4* st = lds[threadIdx.x >> 6];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int64_t pair_x, by, bz;
+  if (!decode_pair(g, pair_x, by, bz)) return;
+  // The pair's second block may lie past the end of the row: its lanes then load the first block again, and the
+  // wave that would own it works on those values and stores nothing (it still takes part in the barriers).
+  const int64_t bx = pair_x * 2 + wave;            // this wave's block
+  const bool block_in = bx < g.gx;
 
   T a[64], c[64];
-  {  // layout A: read plane z = lane >> 2, columns 4 q .. 4 q + 3, all 16 rows
-    const int pz = lane >> 2, q = lane & 3;
+  {  // layout A: plane z = 8 wave + (lane >> 3) of block (lane >> 2) & 1, columns 4 q .. 4 q + 3, all 16 rows
+    const int pz = 8 * wave + (lane >> 3), blk = (lane >> 2) & 1, q = lane & 3;
+    const int64_t bxl = pair_x * 2 + blk < g.gx ? pair_x * 2 + blk : g.gx - 1;
     int64_t zz = bz * 16 + pz;
     uint32_t keep_z = 0xffffffffu;
     if constexpr (kRagged) {
@@ -128,7 +154,7 @@ __global__ __launch_bounds__(64 * kCubeWaves) void k_compress_cube16(FastGeom g,
       zz = zz < g.Z ? zz : g.Z - 1;
     }
     Q4::raw_t raw[16];
-    const int64_t x_first = bx * 16 + q * 4;
+    const int64_t x_first = bxl * 16 + q * 4;
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       int64_t yy = by * 16 + yy0;
@@ -164,13 +190,15 @@ __global__ __launch_bounds__(64 * kCubeWaves) void k_compress_cube16(FastGeom g,
 #pragma unroll
     for (int e = 0; e < 4; ++e) tf_forward<TF, T, 16, 4>(a + e);
   }
-  cube_exchange_zy<T, true>(st, lane, a, c);
+  cube_exchange_zy<T, true>(lds, wave, lane, a, c);
 #pragma unroll
   for (int e = 0; e < 4; ++e) tf_forward<TF, T, 16, 4>(c + e);
+  uint4* st = lds + wave * kCubeSlots;             // from here on a wave stays inside its block's half
   wave_lds_sync();
   cube_exchange_zx<T, true>(st, lane, c, a);
 #pragma unroll
   for (int zl = 0; zl < 4; ++zl) tf_forward<TF, T, 16, 1>(a + zl * 16);
+  if (!block_in) return;
 
   // layout B: lane = (ky, zh) holds rows (kz = 4 zh + zl, ky) of the coefficients
   T m = T(0);
@@ -203,23 +231,29 @@ __global__ __launch_bounds__(64 * kCubeWaves) void k_compress_cube16(FastGeom g,
     const double n = stored_N(m, g.ntype);
     const double f0 = lane == 0 ? double(IdxPack<IT>::get(w[0], 0)) : 0.0;
     const double rest = (sum_of_squares<IT, 4 * ROWW>(w) - f0 * f0) * (n * n);
-    const double K = tile_pilot(n * f0);           // one block per tile: its first coefficient is the pilot value
-    emit_tile_sums(tile_sums, g, bx, by, bz, rest, 0.0, 0.0, lane == 0 ? 1.0 : 0.0, K);
+    const double K = tile_pilot(n * f0);           // one record per block: its first coefficient is the pilot value
+    FastGeom per_block = g;                        // records are indexed by block, not by pair
+    per_block.tiles_x = uint32_t(g.gx);
+    per_block.tiles_yx = uint32_t(g.gx * g.gy);
+    emit_tile_sums(tile_sums, per_block, bx, by, bz, rest, 0.0, 0.0, lane == 0 ? 1.0 : 0.0, K);
   }
 }
 
 template <int TF, typename T, typename IT, bool kTailX>
-__global__ __launch_bounds__(64 * kCubeWaves) void k_decompress_cube16(FastGeom g, const void* __restrict__ N,
+__global__ __launch_bounds__(128) void k_decompress_cube16(FastGeom g, const void* __restrict__ N,
                                                            const IT* __restrict__ F, float* __restrict__ y) {
   using Q4 = Quad4<float>;
   constexpr int PER = IdxPack<IT>::per;
   constexpr int ROWW = 16 / PER;
-  __shared__ uint4 lds[kCubeWaves][kCubeSlots];
+  __shared__ uint4 lds[2 * kCubeSlots];
   const int lane = threadIdx.x & 63;
-  int64_t bx, by, bz;
-  if (!decode_tile<kCubeWaves>(g, bx, by, bz)) return;
-  uint4* st = lds[threadIdx.x >> 6];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int64_t pair_x, by, bz;
+  if (!decode_pair(g, pair_x, by, bz)) return;
+  // a second block past the end of the row: that wave decodes the first block again, and nothing of it is stored
+  const int64_t bx = pair_x * 2 + wave < g.gx ? pair_x * 2 + wave : g.gx - 1;
   const int64_t block = (bz * g.gy + by) * g.gx + bx;
+  uint4* st = lds + wave * kCubeSlots;
 
   T a[64], c[64];
   {  // layout B: rows (kz = 4 zh + zl, ky) of the indices
@@ -250,14 +284,15 @@ __global__ __launch_bounds__(64 * kCubeWaves) void k_decompress_cube16(FastGeom 
 #pragma unroll
   for (int e = 0; e < 4; ++e) tf_inverse<TF, T, 16, 4, 16>(c + e);
   wave_lds_sync();
-  cube_exchange_zy<T, false>(st, lane, c, a);
+  cube_exchange_zy<T, false>(lds, wave, lane, c, a);
 #pragma unroll
   for (int e = 0; e < 4; ++e) tf_inverse<TF, T, 16, 4, 16>(a + e);
 
-  // layout A: plane z = lane >> 2, columns 4 q .. 4 q + 3
-  const int pz = lane >> 2, q = lane & 3;
+  // layout A: plane z = 8 wave + (lane >> 3) of block (lane >> 2) & 1, columns 4 q .. 4 q + 3
+  const int pz = 8 * wave + (lane >> 3), blk = (lane >> 2) & 1, q = lane & 3;
   const int64_t zz = bz * 16 + pz;
-  if (zz < g.Z) {
+  const int64_t bxl = pair_x * 2 + blk;
+  if (zz < g.Z && bxl < g.gx) {
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       const int64_t yy = by * 16 + yy0;
@@ -266,7 +301,7 @@ __global__ __launch_bounds__(64 * kCubeWaves) void k_decompress_cube16(FastGeom 
 #pragma unroll
         for (int e = 0; e < 4; ++e) f[e] = float(a[yy0 * 4 + e]);
         float* row = y + (zz * g.Y + yy) * g.X;
-        const int64_t x0 = bx * 16 + q * 4;
+        const int64_t x0 = bxl * 16 + q * 4;
         if constexpr (kTailX) {
           if (x0 + 4 <= g.X) {
             Q4::template store<true>(row + x0, Q4::pack(f));
@@ -290,22 +325,26 @@ struct Cube16Kernel {
            int(c->itype) == itype_code<IT>() && f.bz == 16 && f.by == 16 && f.bx == 16 && f.kz == 16 && f.ky == 16 &&
            f.kx == 16 && x_extent_ok(f, 4, 4);
   }
+  // one workgroup per pair of blocks; the statistics records are per block
+  static bool grid_for(FastGeom& g, dim3* grid) {
+    return g.gx * g.gy < (int64_t(1) << 31) && tile_grid(g, 2, 1, grid);
+  }
   static int fits(FastGeom g) {
     dim3 grid;
-    return tile_grid(g, 1, kCubeWaves, &grid) ? 1 : 0;
+    return grid_for(g, &grid) ? 1 : 0;
   }
   static int64_t tiles(FastGeom g) {
     dim3 grid;
-    return tile_grid(g, 1, kCubeWaves, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
+    return grid_for(g, &grid) ? g.gz * g.gy * g.gx : 0;
   }
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_cube16<TF, T, IT, kRagged, kStats, kTailX>), grid, dim3(64 * kCubeWaves), 0, s, g,
+    hipLaunchKernelGGL((k_compress_cube16<TF, T, IT, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
                        static_cast<const float*>(x), N, static_cast<IT*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
-    if (!tile_grid(g, 1, kCubeWaves, &grid)) return 0;
+    if (!grid_for(g, &grid)) return 0;
     const bool ragged = g.Y % 16 || g.Z % 16;
     if (g.X % 16) tile_sums ? launch<true, true, true>(g, grid, x, N, F, tile_sums, s) : launch<true, false, true>(g, grid, x, N, F, nullptr, s);
     else if (tile_sums) ragged ? launch<true, true, false>(g, grid, x, N, F, tile_sums, s) : launch<false, true, false>(g, grid, x, N, F, tile_sums, s);
@@ -314,12 +353,12 @@ struct Cube16Kernel {
   }
   static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
     dim3 grid;
-    if (!tile_grid(g, 1, kCubeWaves, &grid)) return 0;
+    if (!grid_for(g, &grid)) return 0;
     if (g.X % 16)
-      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, true>), grid, dim3(64 * kCubeWaves), 0, s, g, N, static_cast<const IT*>(F),
+      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, true>), grid, dim3(128), 0, s, g, N, static_cast<const IT*>(F),
                          static_cast<float*>(y));
     else
-      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, false>), grid, dim3(64 * kCubeWaves), 0, s, g, N, static_cast<const IT*>(F),
+      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, false>), grid, dim3(128), 0, s, g, N, static_cast<const IT*>(F),
                          static_cast<float*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
