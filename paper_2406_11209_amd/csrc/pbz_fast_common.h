@@ -216,6 +216,27 @@ __device__ __forceinline__ void bits_f4(const uint4& u, float* v) {
   v[0] = __uint_as_float(u.x); v[1] = __uint_as_float(u.y); v[2] = __uint_as_float(u.z); v[3] = __uint_as_float(u.w);
 }
 
+template <typename T>
+struct ExchangeSlot;                                   // 16 bytes of a lane's values <-> one uint4 slot of an LDS exchange
+template <>
+struct ExchangeSlot<float> {
+  static constexpr int n = 4;
+  static __device__ __forceinline__ uint4 pack(const float* v) { return f4_bits(v); }
+  static __device__ __forceinline__ void unpack(const uint4& u, float* v) { bits_f4(u, v); }
+};
+template <>
+struct ExchangeSlot<double> {
+  static constexpr int n = 2;
+  static __device__ __forceinline__ uint4 pack(const double* v) {
+    const uint64_t a = __builtin_bit_cast(uint64_t, v[0]), b = __builtin_bit_cast(uint64_t, v[1]);
+    return make_uint4(uint32_t(a), uint32_t(a >> 32), uint32_t(b), uint32_t(b >> 32));
+  }
+  static __device__ __forceinline__ void unpack(const uint4& u, double* v) {
+    v[0] = __builtin_bit_cast(double, uint64_t(u.x) | (uint64_t(u.y) << 32));
+    v[1] = __builtin_bit_cast(double, uint64_t(u.z) | (uint64_t(u.w) << 32));
+  }
+};
+
 // Four consecutive array elements as one piece: 16 bytes of FP32, 8 bytes of a 16-bit type.  kTailX: the piece
 // is only known to start on a 4-byte boundary.
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));

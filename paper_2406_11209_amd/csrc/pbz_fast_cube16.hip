@@ -51,33 +51,12 @@ __device__ __forceinline__ bool decode_pair(const FastGeom& g, int64_t& pair_x, 
   return true;
 }
 
-template <typename T>
-struct CubeSlot;                                   // 16 bytes of a lane's values <-> uint4
-template <>
-struct CubeSlot<float> {
-  static constexpr int n = 4;
-  static __device__ __forceinline__ uint4 pack(const float* v) { return f4_bits(v); }
-  static __device__ __forceinline__ void unpack(const uint4& u, float* v) { bits_f4(u, v); }
-};
-template <>
-struct CubeSlot<double> {
-  static constexpr int n = 2;
-  static __device__ __forceinline__ uint4 pack(const double* v) {
-    const uint64_t a = __builtin_bit_cast(uint64_t, v[0]), b = __builtin_bit_cast(uint64_t, v[1]);
-    return make_uint4(uint32_t(a), uint32_t(a >> 32), uint32_t(b), uint32_t(b >> 32));
-  }
-  static __device__ __forceinline__ void unpack(const uint4& u, double* v) {
-    v[0] = __builtin_bit_cast(double, uint64_t(u.x) | (uint64_t(u.y) << 32));
-    v[1] = __builtin_bit_cast(double, uint64_t(u.z) | (uint64_t(u.w) << 32));
-  }
-};
-
 // layout A <-> layout C across the two waves of the workgroup.  In A, wave w's lane (zl, blk, q) holds value
 // [y * 4 + e] of plane 8 w + zl of block blk; in C, wave w's lane (ky, q) holds value [z * 4 + e] of block w.
 // kToC: from A to C; otherwise from C to A.  Both waves must call it (barriers).
 template <typename T, bool kToC>
 __device__ __forceinline__ void cube_exchange_zy(uint4* lds, int wave, int lane, const T* from, T* to) {
-  using Slot = CubeSlot<T>;
+  using Slot = ExchangeSlot<T>;
   const int z = 8 * wave + (lane >> 3), blk = (lane >> 2) & 1, q = lane & 3;     // as a lane of layout A
   const int cy = lane >> 2;                                                      // as a lane of layout C
 #pragma unroll
@@ -97,7 +76,7 @@ __device__ __forceinline__ void cube_exchange_zy(uint4* lds, int wave, int lane,
 // lane is (ky, zh) = (lane & 15, lane >> 4) and value [zl * 16 + x] is column x of plane 4 zh + zl.
 template <typename T, bool kToB>
 __device__ __forceinline__ void cube_exchange_zx(uint4* st, int lane, const T* from, T* to) {
-  using Slot = CubeSlot<T>;
+  using Slot = ExchangeSlot<T>;
   const int cy = lane >> 2, q = lane & 3;          // as a lane of layout C
   const int ky = lane & 15, zh = lane >> 4;        // as a lane of layout B
 #pragma unroll

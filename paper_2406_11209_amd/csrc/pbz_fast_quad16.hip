@@ -6,8 +6,8 @@ namespace fast {
 namespace {
 
 // =====================================================================================================
-// Family "quad16": BZ x 16 x 16 blocks with BZ = 1 (2-D) or 4, FP32 / FP16 / bfloat16 arrays, FP32 arithmetic, int8 indices,
-// nothing pruned
+// Family "quad16": BZ x 16 x 16 blocks with BZ = 1 (2-D) or 4, FP32 / FP16 / bfloat16 arrays, nothing pruned; int8 indices
+// in FP32 arithmetic, or int16 indices in FP64 arithmetic (T, IT), whose exchange takes two rounds of two values per slot
 // =====================================================================================================
 // A wave works on 16 planes of 16 x 16 samples: plane p = 4 j + s (j, s in 0..3).  For BZ = 1 these are 16
 // consecutive blocks; for BZ = 4 they are the four z-planes (j) of four consecutive blocks (s), so that the lane
@@ -22,10 +22,13 @@ struct QuadMap {
   static __device__ __forceinline__ int plane_of(int p) { return BZ == 1 ? 0 : (p >> 2); }
 };
 
-template <int TF, typename XT, int BZ, bool kRagged, bool kStats, bool kTailX = false>
+template <int TF, typename T, typename IT, typename XT, int BZ, bool kRagged, bool kStats, bool kTailX = false>
 __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* __restrict__ x, void* __restrict__ N,
-                                                         int8_t* __restrict__ F, double* __restrict__ tile_sums) {
+                                                         IT* __restrict__ F, double* __restrict__ tile_sums) {
   using Q4 = Quad4<XT>;
+  using Slot = ExchangeSlot<T>;
+  constexpr int PER = IdxPack<IT>::per;            // indices per dword
+  constexpr int ROWW = 16 / PER;                   // dwords per row of 16 indices
   static_assert(BZ == 1 || BZ == 4, "one plane or four");
   using Map = QuadMap<BZ>;
   constexpr int BPW = Map::kBlocksPerWave;
@@ -35,6 +38,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
   if (!decode_tile<2>(g, tx, by, bz)) return;
   uint4* st = lds[threadIdx.x >> 6];
 
+  T v[64];
   // phase A: lane = (plane p, column quarter q); strip of 16 rows x 4 columns; transform along y
   {
     const int p = lane >> 2, q = lane & 3;
@@ -46,7 +50,6 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
       keep_z = zz < g.Z ? 0xffffffffu : 0u;                   // planes past the end: load a valid one, zero it below
       zz = zz < g.Z ? zz : g.Z - 1;
     }
-    float v[64];
     typename Q4::raw_t raw[16];
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
@@ -59,7 +62,10 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       if constexpr (kRagged) Q4::keep(raw[yy0], by * 16 + yy0 < g.Y ? keep_z : 0u);
-      Q4::unpack(raw[yy0], v + yy0 * 4);
+      float f[4];
+      Q4::unpack(raw[yy0], f);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[yy0 * 4 + e] = T(f[e]);
     }
     if constexpr (kTailX) {
       const int64_t x0 = bxc * 16 + q * 4;
@@ -73,71 +79,79 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
           for (int e = 0; e < 4; ++e) {
             const int64_t xi = x0 + e;
             const float val = Elem<float, XT>::load(row + (xi < g.X ? xi : g.X - 1));
-            v[yy0 * 4 + e] = row_in && xi < g.X ? val : 0.0f;
+            v[yy0 * 4 + e] = row_in && xi < g.X ? T(val) : T(0);
           }
         }
       }
     }
 #pragma unroll
-    for (int xl = 0; xl < 4; ++xl) tf_forward<TF, float, 16, 4>(v + xl);
-#pragma unroll
-    for (int yy0 = 0; yy0 < 16; ++yy0) st[yy0 * kQuadRow + lane] = f4_bits(v + yy0 * 4);
+    for (int xl = 0; xl < 4; ++xl) tf_forward<TF, T, 16, 4>(v + xl);
   }
-  wave_lds_sync();
-  // phase B: lane = (row yrow, s); four whole rows, row yrow of planes 4 j + s; transform along x (and z)
+  // exchange: lane (p, q) -> lane (row yrow, s), which takes four whole rows, row yrow of planes 4 j + s
   const int yrow = lane & 15, bsub = lane >> 4;
-  float u[64];
+  T u[64];
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
+  for (int e0 = 0; e0 < 4; e0 += Slot::n) {
+    if (e0) wave_lds_sync();                       // the previous round's reads precede this round's writes
 #pragma unroll
-    for (int xq = 0; xq < 4; ++xq) bits_f4(st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq], u + j * 16 + xq * 4);
+    for (int yy0 = 0; yy0 < 16; ++yy0) st[yy0 * kQuadRow + lane] = Slot::pack(v + yy0 * 4 + e0);
+    wave_lds_sync();
 #pragma unroll
-  for (int j = 0; j < 4; ++j) tf_forward<TF, float, 16, 1>(u + j * 16);
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int xq = 0; xq < 4; ++xq)
+        Slot::unpack(st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq], u + j * 16 + xq * 4 + e0);
+  }
+  // phase B: transform along x (and z)
+#pragma unroll
+  for (int j = 0; j < 4; ++j) tf_forward<TF, T, 16, 1>(u + j * 16);
   if constexpr (BZ == 4) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) tf_forward<TF, float, 4, 16>(u + i);
+    for (int i = 0; i < 16; ++i) tf_forward<TF, T, 4, 16>(u + i);
   }
 
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * BPW;
   double rest = 0.0;                                   // statistics: N^2 sum F^2 without the first coefficients,
   double firsts[4] = {0.0, 0.0, 0.0, 0.0};             // the first coefficients N F_0 this lane holds (yrow == 0),
   bool has_first[4] = {false, false, false, false};    // of blocks inside the array
-  float m4 = 0.0f;                                     // BZ = 4: the block's maximum over its four planes
+  T m4 = T(0);                                         // BZ = 4: the block's maximum over its four planes
   if constexpr (BZ == 4) {
 #pragma unroll
-    for (int i = 0; i < 64; ++i) m4 = fmaxf(m4, fabsf(u[i]));
+    for (int i = 0; i < 64; ++i) m4 = fmax(m4, fabs(u[i]));
 #pragma unroll
-    for (int off = 1; off < 16; off <<= 1) m4 = fmaxf(m4, __shfl_xor(m4, off, 64));
+    for (int off = 1; off < 16; off <<= 1) m4 = fmax(m4, __shfl_xor(m4, off, 64));
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    float m = m4;
+    T m = m4;
     if constexpr (BZ == 1) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(u[j * 16 + i]));
+      for (int i = 0; i < 16; ++i) m = fmax(m, fabs(u[j * 16 + i]));
 #pragma unroll
-      for (int off = 1; off < 16; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));   // the 16 rows of the block
+      for (int off = 1; off < 16; off <<= 1) m = fmax(m, __shfl_xor(m, off, 64));   // the 16 rows of the block
     }
-    const float inv = m > 0.0f ? float(g.r) / m : 0.0f;
-    uint32_t w[4];
+    const T inv = m > T(0) ? T(g.r) / m : T(0);
+    uint32_t w[ROWW];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      uint32_t q4[4];
+    for (int k = 0; k < ROWW; ++k) {
+      uint32_t qs[PER];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) q4[e] = bin_bits(u[j * 16 + k * 4 + e], inv);
-      w[k] = IdxPack<int8_t>::pack(q4);
+      for (int e = 0; e < PER; ++e) qs[e] = bin_bits(u[j * 16 + k * PER + e], inv);
+      w[k] = IdxPack<IT>::pack(qs);
     }
     const int blk = Map::block_of(4 * j + bsub);
     if (tx * BPW + blk < g.gx) {
       // the wave's pieces of F are linear in the lane: 16 consecutive pieces per (plane, block)
-      const int piece = BZ == 1 ? yrow : j * 16 + yrow;
-      reinterpret_cast<uint4*>(F + (block0 + blk) * (BZ * 256))[piece] = make_uint4(w[0], w[1], w[2], w[3]);
+      const int piece = BZ == 1 ? yrow : j * 16 + yrow;       // row of 16 indices within the block
+      uint4* dst = reinterpret_cast<uint4*>(F + (block0 + blk) * (BZ * 256)) + piece * (ROWW / 4);
+#pragma unroll
+      for (int k = 0; k < ROWW / 4; ++k) dst[k] = make_uint4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
       const bool first = yrow == 0 && (BZ == 1 || j == 0);
       if (first) store_float(N, g.ntype, block0 + blk, m);
       if constexpr (kStats) {
         const double n = stored_N(m, g.ntype);
-        const double f0 = first ? double(IdxPack<int8_t>::get(w[0], 0)) : 0.0;
-        rest += (sum_of_squares<int8_t, 4>(w) - f0 * f0) * (n * n);
+        const double f0 = first ? double(IdxPack<IT>::get(w[0], 0)) : 0.0;
+        rest += (sum_of_squares<IT, ROWW>(w) - f0 * f0) * (n * n);
         firsts[j] = n * f0;
         has_first[j] = first;
       }
@@ -157,23 +171,26 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
   }
 }
 
-template <int TF, typename XT, int BZ, bool kTailX = false>
+template <int TF, typename T, typename IT, typename XT, int BZ, bool kTailX = false>
 __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const void* __restrict__ N,
-                                                           const int8_t* __restrict__ F, XT* __restrict__ y) {
+                                                           const IT* __restrict__ F, XT* __restrict__ y) {
   using Q4 = Quad4<XT>;
   using Map = QuadMap<BZ>;
+  using Slot = ExchangeSlot<T>;
   constexpr int BPW = Map::kBlocksPerWave;
+  constexpr int PER = IdxPack<IT>::per;
+  constexpr int ROWW = 16 / PER;
   __shared__ uint4 lds[2][16 * kQuadRow];
   const int lane = threadIdx.x & 63;
   int64_t tx, by, bz;
   if (!decode_tile<2>(g, tx, by, bz)) return;
   uint4* st = lds[threadIdx.x >> 6];
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * BPW;
+  const int yrow = lane & 15, bsub = lane >> 4;
+  T u[64];
   {
-    const int yrow = lane & 15, bsub = lane >> 4;
-    float u[64];
     int64_t blocks[4];
-    uint4 fs[4];
+    uint4 fs[4][ROWW / 4];
     float ns[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -181,54 +198,71 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
       if (tx * BPW + blk >= g.gx) blk = g.gx - 1 - tx * BPW;   // past the end: decode the last block again, stored nowhere
       blocks[j] = block0 + blk;
       const int piece = BZ == 1 ? yrow : j * 16 + yrow;
-      fs[j] = reinterpret_cast<const uint4*>(F + blocks[j] * (BZ * 256))[piece];
+      const uint4* src = reinterpret_cast<const uint4*>(F + blocks[j] * (BZ * 256)) + piece * (ROWW / 4);
+#pragma unroll
+      for (int k = 0; k < ROWW / 4; ++k) fs[j][k] = src[k];
     }
     load_N_many<4>(N, g.ntype, blocks, ns);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint4 f = fs[j];
-      const float scale = ns[j] / float(g.r);
-      const uint32_t w[4] = {f.x, f.y, f.z, f.w};
+      const T scale = T(ns[j]) / T(g.r);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) u[j * 16 + i] = scale * float(IdxPack<int8_t>::get(w[i >> 2], i & 3));
+      for (int k = 0; k < ROWW / 4; ++k) {
+        const uint4 f = fs[j][k];
+        const uint32_t w[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+          for (int e = 0; e < PER; ++e)
+            u[j * 16 + (4 * k + d) * PER + e] = scale * T(IdxPack<IT>::get(w[d], e));
+      }
     }
     if constexpr (BZ == 4) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) tf_inverse<TF, float, 4, 16, 4>(u + i);
+      for (int i = 0; i < 16; ++i) tf_inverse<TF, T, 4, 16, 4>(u + i);
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) tf_inverse<TF, float, 16, 1, 16>(u + j * 16);
+    for (int j = 0; j < 4; ++j) tf_inverse<TF, T, 16, 1, 16>(u + j * 16);
+  }
+  // exchange: lane (row yrow, s) -> lane (plane p, column quarter q)
+  T v[64];
+#pragma unroll
+  for (int e0 = 0; e0 < 4; e0 += Slot::n) {
+    if (e0) wave_lds_sync();
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int xq = 0; xq < 4; ++xq) st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq] = f4_bits(u + j * 16 + xq * 4);
+      for (int xq = 0; xq < 4; ++xq)
+        st[yrow * kQuadRow + (4 * j + bsub) * 4 + xq] = Slot::pack(u + j * 16 + xq * 4 + e0);
+    wave_lds_sync();
+#pragma unroll
+    for (int yy0 = 0; yy0 < 16; ++yy0) Slot::unpack(st[yy0 * kQuadRow + lane], v + yy0 * 4 + e0);
   }
-  wave_lds_sync();
   const int p = lane >> 2, q = lane & 3;
   const int64_t bx = tx * BPW + Map::block_of(p);
   const int64_t zz = bz * BZ + Map::plane_of(p);
-  float v[64];
 #pragma unroll
-  for (int yy0 = 0; yy0 < 16; ++yy0) bits_f4(st[yy0 * kQuadRow + lane], v + yy0 * 4);
-#pragma unroll
-  for (int xl = 0; xl < 4; ++xl) tf_inverse<TF, float, 16, 4, 16>(v + xl);
+  for (int xl = 0; xl < 4; ++xl) tf_inverse<TF, T, 16, 4, 16>(v + xl);
   if (bx < g.gx && zz < g.Z) {
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       const int64_t yy = by * 16 + yy0;
       if (yy < g.Y) {
+        float f[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = float(v[yy0 * 4 + e]);
         if constexpr (kTailX) {
           XT* row = y + (zz * g.Y + yy) * g.X;
           const int64_t x0 = bx * 16 + q * 4;
           if (x0 + 4 <= g.X) {
-            Q4::template store<true>(row + x0, Q4::pack(v + yy0 * 4));
+            Q4::template store<true>(row + x0, Q4::pack(f));
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (x0 + e < g.X) Elem<float, XT>::store(row + x0 + e, v[yy0 * 4 + e]);
+              if (x0 + e < g.X) Elem<float, XT>::store(row + x0 + e, f[e]);
           }
         } else {
-          Q4::template store<false>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4, Q4::pack(v + yy0 * 4));
+          Q4::template store<false>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4, Q4::pack(f));
         }
       }
     }
@@ -236,12 +270,13 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
 }
 
 
-// 16x16 (2-D) and 4x16x16 blocks, FP32 / bfloat16 / FP16 arrays, int8, nothing pruned
-template <int TF, typename XT, int BZ>
+// 16x16 (2-D) and 4x16x16 blocks, FP32 / bfloat16 / FP16 arrays, nothing pruned; T = float with int8, double with int16
+template <int TF, typename T, typename IT, typename XT, int BZ>
 struct Quad16Kernel {
   static constexpr int kBlocksPerWave = BZ == 1 ? 16 : 4;
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && c->transform == TF && !c->compute_f64 && xtype == xtype_code<XT>() && c->itype == PBZ_I8 &&
+    return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<XT>() &&
+           int(c->itype) == itype_code<IT>() &&
            c->ftype != PBZ_F64 && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
            x_extent_ok(f, 4, int(sizeof(XT)));
   }
@@ -255,8 +290,8 @@ struct Quad16Kernel {
   }
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_quad16<TF, XT, BZ, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
-                       static_cast<const XT*>(x), N, static_cast<int8_t*>(F), tile_sums);
+    hipLaunchKernelGGL((k_compress_quad16<TF, T, IT, XT, BZ, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
+                       static_cast<const XT*>(x), N, static_cast<IT*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
@@ -271,21 +306,23 @@ struct Quad16Kernel {
     dim3 grid;
     if (!tile_grid(g, kBlocksPerWave, 2, &grid)) return 0;
     if (g.X % 16)
-      hipLaunchKernelGGL((k_decompress_quad16<TF, XT, BZ, true>), grid, dim3(128), 0, s, g, N,
-                         static_cast<const int8_t*>(F), static_cast<XT*>(y));
+      hipLaunchKernelGGL((k_decompress_quad16<TF, T, IT, XT, BZ, true>), grid, dim3(128), 0, s, g, N,
+                         static_cast<const IT*>(F), static_cast<XT*>(y));
     else
-      hipLaunchKernelGGL((k_decompress_quad16<TF, XT, BZ, false>), grid, dim3(128), 0, s, g, N,
-                         static_cast<const int8_t*>(F), static_cast<XT*>(y));
+      hipLaunchKernelGGL((k_decompress_quad16<TF, T, IT, XT, BZ, false>), grid, dim3(128), 0, s, g, N,
+                         static_cast<const IT*>(F), static_cast<XT*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
 
 #define PBZ_ROWS(X, TF, SUFFIX) \
-  X(Quad16Kernel<TF COMMA float COMMA 1>, "quad16_f32_16x16_i8" SUFFIX) \
-  X(Quad16Kernel<TF COMMA float COMMA 4>, "quad16_f32_4x16x16_i8" SUFFIX) \
-  X(Quad16Kernel<TF COMMA f16_t COMMA 1>, "quad16_f16_16x16_i8" SUFFIX) \
-  X(Quad16Kernel<TF COMMA bf16_t COMMA 1>, "quad16_bf16_16x16_i8" SUFFIX) \
-  X(Quad16Kernel<TF COMMA f16_t COMMA 4>, "quad16_f16_4x16x16_i8" SUFFIX)
+  X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA float COMMA 1>, "quad16_f32_16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA float COMMA 4>, "quad16_f32_4x16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA f16_t COMMA 1>, "quad16_f16_16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA bf16_t COMMA 1>, "quad16_bf16_16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA f16_t COMMA 4>, "quad16_f16_4x16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA float COMMA 1>, "quad16_f32_16x16_i16" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA float COMMA 4>, "quad16_f32_4x16x16_i16" SUFFIX)
 
 }  // namespace
 

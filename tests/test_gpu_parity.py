@@ -213,6 +213,12 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((9, 12, 398), (8, 8, 8), 8, "f32", "f16", None, "oct8_f32_8x8x8_i8"),
                ((17, 9, 21), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
                ((8, 8, 515), (8, 8, 8), 8, "f32", "bf16", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
+               # int16 indices (FP64 arithmetic) in 16x16 and 4x16x16 blocks
+               ((3, 33, 48), (1, 16, 16), 16, "f32", "f32", None, "quad16_f32_16x16_i16"),
+               ((40, 1046), (16, 16), 16, "f32", "f16", None, "quad16_f32_16x16_i16"),
+               ((21, 272), (16, 16), 16, "f32", "bf16", None, "quad16_f32_16x16_i16"),
+               ((9, 20, 37), (4, 16, 16), 16, "f32", "f32", None, "quad16_f32_4x16x16_i16"),
+               ((10, 33, 160), (4, 16, 16), 16, "f32", "f32", None, "quad16_f32_4x16x16_i16"),
                # 16x16x16 blocks of FP32 arrays (the fission-density experiment's setting, Sec. V: int16), one block per wave
                ((32, 16, 48), (16, 16, 16), 16, "f32", "f32", None, "cube16_f32_16x16x16_i16"),
                ((20, 37, 64), (16, 16, 16), 16, "f32", "f32", None, "cube16_f32_16x16x16_i16"),
@@ -257,6 +263,8 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
         ((3, 33, 96), (1, 16, 16), 8, "f16", "f32", None, "quad16_f16_16x16_i8_haar"),
         ((9, 6, 26), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
+        ((3, 33, 96), (1, 16, 16), 16, "f32", "f32", None, "quad16_f32_16x16_i16_haar"),
+        ((9, 20, 37), (4, 16, 16), 16, "f32", "f32", None, "quad16_f32_4x16x16_i16_haar"),
         ((20, 37, 64), (16, 16, 16), 16, "f32", "f32", None, "cube16_f32_16x16x16_i16_haar"),
         ((17, 16, 70), (16, 16, 16), 8, "f32", "f32", None, "cube16_f32_16x16x16_i8_haar"),
         ((9, 20, 36), (2, 16, 16), 8, "f32", "f32", None, "generic"),

@@ -215,6 +215,9 @@ DISPATCH = [
     ((8, 8, 8), "f32", "i8", None, (17, 9, 24), "bf16", "oct8_bf16_8x8x8_i8"),
     ((8, 8, 8), "f32", "i8", (4, 4, 4), (17, 9, 21), "f32", "oct8_f32_8x8x8_i8_box4x4x4"),
     ((8, 8, 8), "f32", "i8", None, (17, 9, 24), "f16", "oct8_f16_8x8x8_i8"),
+    ((16, 16), "f32", "i16", None, (64, 64), "f32", "quad16_f32_16x16_i16"),
+    ((1, 16, 16), "f16", "i16", None, (5, 33, 50), "f32", "quad16_f32_16x16_i16"),
+    ((4, 16, 16), "f32", "i16", None, (9, 20, 38), "f32", "quad16_f32_4x16x16_i16"),
     ((16, 16, 16), "f32", "i16", None, (40, 40, 66), "f32", "cube16_f32_16x16x16_i16"),
     ((16, 16, 16), "bf16", "i16", None, (32, 32, 64), "f32", "cube16_f32_16x16x16_i16"),
     ((16, 16, 16), "f32", "i8", None, (100, 500, 500), "f32", "cube16_f32_16x16x16_i8"),
@@ -222,7 +225,7 @@ DISPATCH = [
     # no specialised kernel: the general ones
     ((8, 8), "f32", "i32", None, (64, 64), "f32", "generic"),
     ((8, 8), "f64", "i16", None, (64, 64), "f32", "generic"),                              # FP32 array, FP64 N
-    ((16, 16), "f32", "i16", None, (64, 64), "f32", "generic"),
+    ((16, 16), "f32", "i16", None, (64, 64), "f16", "generic"),                            # 16-bit array, int16
     ((8, 8, 8), "f32", "i8", (2, 2, 2), (16, 16, 16), "f32", "generic"),                   # another mask
     ((8, 8, 8), "f64", "i8", None, (16, 16, 16), "f64", "generic"),
     ((16, 16, 16), "f64", "i16", None, (40, 40, 66), "f64", "generic"),
