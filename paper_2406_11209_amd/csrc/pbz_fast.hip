@@ -5,13 +5,13 @@
 // lanes of a wave cover a contiguous span of every row, which measures at the same bandwidth as a
 // linear copy on MI355X), transforms in registers with the even/odd-split DCT of pbz_dct.h or the Haar
 // cascade of pbz_haar.h (template switch TF), and writes N and F.  There is no workgroup barrier in the
-// compress kernels; LDS, where used, is private to a wave.
+// compress kernels and LDS, where used, is private to a wave (one exception: the first exchange of "cube16").
 //
 // Family "lane":   one lane owns one whole block (blocks of at most 64 elements: 8x8, 4x4x4).  Where a block
 //                   row is two (four) 16-byte pieces the half-waves (quarter-waves) trade pieces, so that every
 //                   load / store instruction of the array covers one contiguous KiB.  Indices leave through a wave-private
 //                   LDS transpose when a block's F is 64 bytes or more, for the same reason.
-// Family "quad16":  16x16 and 4x16x16 blocks of FP32 or 16-bit input, 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
+// Family "quad16":  16x16 and 4x16x16 blocks of FP32 or 16-bit input (int8; FP32 input also int16 in FP64 arithmetic), 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
 //                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
 //                   then each lane holds four whole rows (row transform, and for 4x16x16 the transform across
 //                   the four planes); rows leave as 16-byte pieces in linear order.
@@ -20,9 +20,10 @@
 //                   y-row of all eight z-planes (z transform).  Decompression needs no exchange: every
 //                   lane rebuilds its own z-plane from the block's few kept coefficients; wide arrays use a
 //                   variant in which a wave owns one plane of 64 blocks and stores whole 1 KiB row pieces.
-// Family "cube16":  16x16x16 blocks of FP32 input, one block per wave (int16 indices in FP64 arithmetic, int8 in FP32).
-//                   Three layouts, one per transformed dimension, with a wave-private LDS exchange between them; the
-//                   first is how rows are read (16-byte pieces), the last how F is written (whole rows of indices).
+// Family "cube16":  16x16x16 blocks of FP32 input (int16 indices in FP64 arithmetic, int8 in FP32), two neighbouring blocks
+//                   per workgroup of two waves.  Three layouts, one per transformed dimension, with an LDS exchange
+//                   between them; the first is how rows are read (eight lanes cover the 128 bytes the two blocks have
+//                   in a row), the last how F is written (whole rows of indices).
 //
 // Variants of every kernel: kRagged (the slower dimensions are not multiples of the block extents), kTailX
 // (neither is the last one: rows start at any 4-byte boundary, the last block of a row is partial), kStats
