@@ -37,13 +37,12 @@ __constant__ Haar8Table c_haar8 = Haar8Table();
 // =====================================================================================================
 // LDS exchange, done in two rounds (left and right half of every 8-element row) so that a wave needs 8 KiB
 // instead of 16 KiB and twice as many waves fit a CU (the kernel is latency-bound: halving its occupancy
-// cost 40 %).  Per round block b occupies 64 sixteen-byte slots ordered [y][z]; the low four bits of the slot
-// are XORed with 2b and a permutation of y so that both the plane-wise writes (lanes differ in z, b) and the
-// row-wise reads (lanes differ in b, y) touch sixteen different bank groups per sixteen lanes.
-__device__ __forceinline__ int oct_slot(int b, int yy, int z) {
-  const int perm = ((yy >> 1) & 1) | (((yy >> 2) & 1) << 2);
-  return b * 64 + ((yy * 8 + z) ^ (2 * b) ^ perm);
-}
+// cost 40 %).  Per round block b occupies 64 sixteen-byte slots ordered [y][z].  A 16-byte LDS access is served
+// eight consecutive lanes at a time, and those eight must fall into different slots modulo 8: the plane-wise
+// writes come from lanes that differ in b, the row-wise reads from lanes that differ in y, so the low three bits
+// of the slot are z ^ y ^ b (shader counters: 200 -> 8 bank-conflict cycles per wave against the earlier swizzle,
+// which spread sixteen lanes over sixteen slots but put pairs of the eight into one).
+__device__ __forceinline__ int oct_slot(int b, int yy, int z) { return b * 64 + yy * 8 + ((z ^ yy ^ b) & 7); }
 
 constexpr int kOctWaves = 4;   // waves per workgroup: neighbouring tiles, so that a workgroup reads 512-byte row pieces
 
