@@ -139,7 +139,9 @@ def test_full_shape(config, capsys):
 # where the oracle compresses and decompresses them one by one.
 BEYOND_32_BITS = [((1040, 1536, 1536), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                   ((520, 2048, 2048), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
-                  ((3, 40000, 20000), (1, 16, 16), 16, "f32", "f32", None, "generic")]
+                  ((3, 40000, 20000), (1, 16, 16), 16, "f32", "f32", None, "quad16_f32_16x16_i16"),
+                  ((528, 2048, 2048), (16, 16, 16), 8, "f32", "f32", None, "cube16_f32_16x16x16_i8"),
+                  ((3, 40000, 20000), (1, 32, 16), 16, "f32", "f32", None, "generic")]
 
 
 @pytest.mark.parametrize("spec", BEYOND_32_BITS, ids=[s[6] for s in BEYOND_32_BITS])
