@@ -464,6 +464,236 @@ struct Oct8Kernel {
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
+// =====================================================================================================
+// 8x8x8 blocks of FP32 arrays with int16 indices: FP64 arithmetic, nothing pruned.  The same two layouts and the
+// same LDS slots as above; a slot holds two FP64 values, so the exchange takes four rounds (a quarter of every
+// 8-element row each) through the same 8 KiB per wave.  A row of eight indices is one 16-byte piece of F and the
+// eight lanes of a block write 128 contiguous bytes, so F needs no staging.
+// =====================================================================================================
+template <int TF, bool kRagged, bool kStats, bool kTailX>
+__global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8_i16(FastGeom g, const float* __restrict__ x,
+                                                                      void* __restrict__ N, int16_t* __restrict__ F,
+                                                                      double* __restrict__ tile_sums) {
+  using Slot = ExchangeSlot<double>;
+  __shared__ uint4 lds[kOctWaves][8 * 64];
+  const int lane = threadIdx.x & 63;
+  int64_t tx, by, bz;
+  if (!decode_tile<kOctWaves>(g, tx, by, bz)) return;
+  uint4* st = lds[threadIdx.x >> 6];
+  const int z = lane >> 3, b = lane & 7;      // phase A: lane = (plane z, block b)
+  const int bb = lane >> 3, j = lane & 7;     // phase B: lane = (block bb, row j)
+
+  double v[64];
+  {
+    const int64_t bx = tx * 8 + b;
+    const int64_t bxc = bx < g.gx ? bx : g.gx - 1;
+    int64_t zz = bz * 8 + z;
+    uint32_t keep_z = 0xffffffffu;
+    if constexpr (kRagged) {
+      keep_z = zz < g.Z ? 0xffffffffu : 0u;      // planes / rows past the end: load a valid row, zero it below
+      zz = zz < g.Z ? zz : g.Z - 1;
+    }
+    uint4 raw[16];
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) {
+      int64_t yy = by * 8 + yy0;
+      if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int64_t x0 = bxc * 8 + k * 4;
+        if constexpr (kTailX)
+          raw[yy0 * 2 + k] = load16_a4(x + (zz * g.Y + yy) * g.X + (x0 + 4 <= g.X ? x0 : g.X - 4));
+        else
+          raw[yy0 * 2 + k] = load16_stream(x + (zz * g.Y + yy) * g.X + x0);
+      }
+    }
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        uint4& piece = raw[yy0 * 2 + k];
+        if constexpr (kRagged) {
+          const uint32_t keep = by * 8 + yy0 < g.Y ? keep_z : 0u;
+          piece.x &= keep; piece.y &= keep; piece.z &= keep; piece.w &= keep;
+        }
+        float f[4];
+        bits_f4(piece, f);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[yy0 * 8 + k * 4 + e] = double(f[e]);
+      }
+    }
+    if constexpr (kTailX) {
+      if (bxc * 8 + 8 > g.X) {         // the row's last, partial block: element by element, zeros beyond
+#pragma unroll
+        for (int yy0 = 0; yy0 < 8; ++yy0) {
+          const int64_t yy = by * 8 + yy0;
+          const bool row_in = yy < g.Y && keep_z != 0u;
+          const float* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int64_t xi = bxc * 8 + e;
+            const float val = row[xi < g.X ? xi : g.X - 1];
+            v[yy0 * 8 + e] = row_in && xi < g.X ? double(val) : 0.0;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) tf_forward<TF, double, 8, 1>(v + yy0 * 8);
+#pragma unroll
+    for (int xx = 0; xx < 8; ++xx) tf_forward<TF, double, 8, 8>(v + xx);
+  }
+  // exchange: afterwards the lane holds the row y = j of all eight planes of block bb; transform along z
+  double u[64];
+#pragma unroll
+  for (int h = 0; h < 8; h += Slot::n) {
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) st[oct_slot(b, yy0, z)] = Slot::pack(v + yy0 * 8 + h);
+    wave_lds_sync();
+#pragma unroll
+    for (int zz0 = 0; zz0 < 8; ++zz0) Slot::unpack(st[oct_slot(bb, j, zz0)], u + zz0 * 8 + h);
+    wave_lds_sync();
+  }
+#pragma unroll
+  for (int xx = 0; xx < 8; ++xx) tf_forward<TF, double, 8, 8>(u + xx);
+
+  double m = 0.0;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) m = fmax(m, fabs(u[i]));
+#pragma unroll
+  for (int off = 1; off < 8; off <<= 1) m = fmax(m, __shfl_xor(m, off, 64));     // the 8 rows of the block
+  const double inv = m > 0.0 ? g.r / m : 0.0;
+  const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 8;
+  const bool inside = tx * 8 + bb < g.gx;
+  uint32_t w[32];
+#pragma unroll
+  for (int zq = 0; zq < 8; ++zq)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t q2[2] = {bin_bits(u[zq * 8 + 2 * k], inv), bin_bits(u[zq * 8 + 2 * k + 1], inv)};
+      w[zq * 4 + k] = IdxPack<int16_t>::pack(q2);
+    }
+  if (inside) {
+    uint4* dst = reinterpret_cast<uint4*>(F + (block0 + bb) * 512) + j;            // row (kz, j) at dst[kz * 8]
+#pragma unroll
+    for (int zq = 0; zq < 8; ++zq) dst[zq * 8] = make_uint4(w[zq * 4], w[zq * 4 + 1], w[zq * 4 + 2], w[zq * 4 + 3]);
+    if (j == 0) store_float(N, g.ntype, block0 + bb, m);
+  }
+  if constexpr (kStats) {
+    const double n = inside ? stored_N(m, g.ntype) : 0.0;
+    const double f0 = j == 0 ? double(IdxPack<int16_t>::get(w[0], 0)) : 0.0;
+    const double K = tile_pilot(n * f0);                      // lane 0: row 0 of the tile's first block
+    const bool has_first = j == 0 && inside;
+    const double d = has_first ? n * f0 - K : 0.0;
+    emit_tile_sums(tile_sums, g, tx, by, bz, (sum_of_squares<int16_t, 32>(w) - f0 * f0) * (n * n), d * d, d,
+                   has_first ? 1.0 : 0.0, K);
+  }
+}
+
+template <int TF, bool kTailX>
+__global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_i16(FastGeom g, const void* __restrict__ N,
+                                                                        const int16_t* __restrict__ F,
+                                                                        float* __restrict__ y) {
+  using Slot = ExchangeSlot<double>;
+  __shared__ uint4 lds[kOctWaves][8 * 64];
+  const int lane = threadIdx.x & 63;
+  int64_t tx, by, bz;
+  if (!decode_tile<kOctWaves>(g, tx, by, bz)) return;
+  uint4* st = lds[threadIdx.x >> 6];
+  const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 8;
+  const int z = lane >> 3, b = lane & 7;
+  const int bb = lane >> 3, j = lane & 7;
+
+  double u[64];
+  {
+    // a block past the end of the row: decode the row's last block again; nothing of it is stored
+    const int64_t blk = tx * 8 + bb < g.gx ? bb : g.gx - 1 - tx * 8;
+    const uint4* rows = reinterpret_cast<const uint4*>(F + (block0 + blk) * 512) + j;
+    uint4 f[8];
+#pragma unroll
+    for (int kz = 0; kz < 8; ++kz) f[kz] = rows[kz * 8];
+    const double scale = load_float<double>(N, g.ntype, block0 + blk) / g.r;          // Algorithm 3: N F / r
+#pragma unroll
+    for (int kz = 0; kz < 8; ++kz) {
+      const uint32_t fw[4] = {f[kz].x, f[kz].y, f[kz].z, f[kz].w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) u[kz * 8 + e] = scale * double(IdxPack<int16_t>::get(fw[e >> 1], e & 1));
+    }
+#pragma unroll
+    for (int xx = 0; xx < 8; ++xx) tf_inverse<TF, double, 8, 8, 8>(u + xx);
+  }
+  double v[64];
+#pragma unroll
+  for (int h = 0; h < 8; h += Slot::n) {
+#pragma unroll
+    for (int zz0 = 0; zz0 < 8; ++zz0) st[oct_slot(bb, j, zz0)] = Slot::pack(u + zz0 * 8 + h);
+    wave_lds_sync();
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) Slot::unpack(st[oct_slot(b, yy0, z)], v + yy0 * 8 + h);
+    wave_lds_sync();
+  }
+#pragma unroll
+  for (int xx = 0; xx < 8; ++xx) tf_inverse<TF, double, 8, 8, 8>(v + xx);
+#pragma unroll
+  for (int yy0 = 0; yy0 < 8; ++yy0) tf_inverse<TF, double, 8, 1, 8>(v + yy0 * 8);
+  const int64_t bx = tx * 8 + b;
+  const int64_t zz = bz * 8 + z;
+  if (bx < g.gx && zz < g.Z) {
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) {
+      const int64_t yy = by * 8 + yy0;
+      if (yy < g.Y) {
+        float r8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r8[e] = float(v[yy0 * 8 + e]);
+        oct_store_row<float, kTailX>(g, y + (zz * g.Y + yy) * g.X, bx, r8);
+      }
+    }
+  }
+}
+
+template <int TF>
+struct Oct8I16Kernel {
+  static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
+    return f.ok && c->transform == TF && c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I16 &&
+           c->ftype != PBZ_F64 && f.bz == 8 && f.by == 8 && f.bx == 8 && f.kz == 8 && f.ky == 8 && f.kx == 8 &&
+           x_extent_ok(f, 4, 4);
+  }
+  static int fits(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 8, kOctWaves, &grid) ? 1 : 0;
+  }
+  static int64_t tiles(FastGeom g) {
+    dim3 grid;
+    return tile_grid(g, 8, kOctWaves, &grid) ? g.gz * int64_t(g.tiles_yx) : 0;
+  }
+  template <bool kRagged, bool kStats, bool kTailX>
+  static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    hipLaunchKernelGGL((k_compress_oct8_i16<TF, kRagged, kStats, kTailX>), grid, dim3(kOctWaves * 64), 0, s, g,
+                       static_cast<const float*>(x), N, static_cast<int16_t*>(F), tile_sums);
+  }
+  static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
+    dim3 grid;
+    if (!tile_grid(g, 8, kOctWaves, &grid)) return 0;
+    const bool ragged = g.Y % 8 || g.Z % 8;
+    if (g.X % 8) tile_sums ? launch<true, true, true>(g, grid, x, N, F, tile_sums, s) : launch<true, false, true>(g, grid, x, N, F, nullptr, s);
+    else if (tile_sums) ragged ? launch<true, true, false>(g, grid, x, N, F, tile_sums, s) : launch<false, true, false>(g, grid, x, N, F, tile_sums, s);
+    else ragged ? launch<true, false, false>(g, grid, x, N, F, nullptr, s) : launch<false, false, false>(g, grid, x, N, F, nullptr, s);
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+  static int decompress(FastGeom g, const void* N, const void* F, void* y, hipStream_t s) {
+    dim3 grid;
+    if (!tile_grid(g, 8, kOctWaves, &grid)) return 0;
+    if (g.X % 8)
+      hipLaunchKernelGGL((k_decompress_oct8_i16<TF, true>), grid, dim3(kOctWaves * 64), 0, s, g, N,
+                         static_cast<const int16_t*>(F), static_cast<float*>(y));
+    else
+      hipLaunchKernelGGL((k_decompress_oct8_i16<TF, false>), grid, dim3(kOctWaves * 64), 0, s, g, N,
+                         static_cast<const int16_t*>(F), static_cast<float*>(y));
+    return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
+  }
+};
+
 template <int TF> using Oct8_box4 = Oct8Kernel<TF, bf16_t, 4, 4, 4>;
 template <int TF> using Oct8_full = Oct8Kernel<TF, bf16_t, 8, 8, 8>;
 template <int TF> using Oct8_f32_box4 = Oct8Kernel<TF, float, 4, 4, 4>;
@@ -477,7 +707,8 @@ template <int TF> using Oct8_f16_full = Oct8Kernel<TF, f16_t, 8, 8, 8>;
   X(Oct8_f32_box4<TF>, "oct8_f32_8x8x8_i8_box4x4x4" SUFFIX) \
   X(Oct8_f32_full<TF>, "oct8_f32_8x8x8_i8" SUFFIX) \
   X(Oct8_f16_box4<TF>, "oct8_f16_8x8x8_i8_box4x4x4" SUFFIX) \
-  X(Oct8_f16_full<TF>, "oct8_f16_8x8x8_i8" SUFFIX)
+  X(Oct8_f16_full<TF>, "oct8_f16_8x8x8_i8" SUFFIX) \
+  X(Oct8I16Kernel<TF>, "oct8_f32_8x8x8_i16" SUFFIX)
 
 }  // namespace
 

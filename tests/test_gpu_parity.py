@@ -213,6 +213,11 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((9, 12, 398), (8, 8, 8), 8, "f32", "f16", None, "oct8_f32_8x8x8_i8"),
                ((17, 9, 21), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
                ((8, 8, 515), (8, 8, 8), 8, "f32", "bf16", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
+               # int16 indices (FP64 arithmetic) in 8x8x8 blocks
+               ((16, 8, 64), (8, 8, 8), 16, "f32", "f32", None, "oct8_f32_8x8x8_i16"),
+               ((17, 9, 200), (8, 8, 8), 16, "f32", "f32", None, "oct8_f32_8x8x8_i16"),
+               ((9, 12, 398), (8, 8, 8), 16, "f32", "f16", None, "oct8_f32_8x8x8_i16"),
+               ((9, 17, 21), (8, 8, 8), 16, "f32", "bf16", None, "oct8_f32_8x8x8_i16"),
                # int16 indices (FP64 arithmetic) in 16x16 and 4x16x16 blocks
                ((3, 33, 48), (1, 16, 16), 16, "f32", "f32", None, "quad16_f32_16x16_i16"),
                ((40, 1046), (16, 16), 16, "f32", "f16", None, "quad16_f32_16x16_i16"),
@@ -263,6 +268,7 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((9, 20, 37), (4, 16, 16), 8, "f32", "f32", None, "quad16_f32_4x16x16_i8_haar"),
         ((3, 33, 96), (1, 16, 16), 8, "f16", "f32", None, "quad16_f16_16x16_i8_haar"),
         ((9, 6, 26), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
+        ((17, 9, 72), (8, 8, 8), 16, "f32", "f32", None, "oct8_f32_8x8x8_i16_haar"),
         ((3, 33, 96), (1, 16, 16), 16, "f32", "f32", None, "quad16_f32_16x16_i16_haar"),
         ((9, 20, 37), (4, 16, 16), 16, "f32", "f32", None, "quad16_f32_4x16x16_i16_haar"),
         ((20, 37, 64), (16, 16, 16), 16, "f32", "f32", None, "cube16_f32_16x16x16_i16_haar"),
