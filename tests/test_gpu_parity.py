@@ -381,6 +381,18 @@ def test_c_abi_from_plain_c():
     assert "lane_f64_4x4x4_i16" in res.stdout
 
 
+def test_codec_repeat_example():
+    """The timing / profiling driver runs one small setting and names the kernel the dispatch picked."""
+    import os
+    import subprocess
+    import sys
+    script = os.path.join(os.path.dirname(api.__file__), "examples", "codec_repeat.py")
+    res = subprocess.run([sys.executable, script, "--shape", "32", "32", "48", "--block", "16", "16", "16", "--itype", "i16",
+                          "--repeat", "2"], capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert res.stdout.startswith("cube16_f32_16x16x16_i16: compress"), res.stdout
+
+
 def test_transform_is_fixed_once_the_codec_has_compressed():
     codec = Codec((8, 8), "f32", "i8")
     codec.compress(torch.zeros((16, 16), dtype=torch.float32, device="cuda"))
