@@ -72,7 +72,8 @@ typedef enum {
   PBZ_ERR_SCALAR = -9,      /* non-finite scalar */
   PBZ_ERR_HIP = -10,        /* the HIP runtime reported an error (no device, launch failure, ...) */
   PBZ_ERR_ALLOC = -11,      /* host allocation failed */
-  PBZ_ERR_STATE = -12       /* the call comes too late in the handle's life (see pbz_codec_set_transform) */
+  PBZ_ERR_STATE = -12,      /* the call comes too late in the handle's life (see pbz_codec_set_transform) */
+  PBZ_ERR_CAPACITY = -13    /* the input exceeds what the library's fixed scratch array serves (pbz_segmented_static) */
 } pbz_status;
 
 /* Kernel families, for pbz_codec_set_kernel_path / pbz_kernel_name. */
@@ -214,6 +215,25 @@ typedef enum {
 int pbz_segmented(const pbz_codec* codec, pbz_statistic statistic, int64_t n_segments, int64_t blocks_per_segment,
                   const void* N1, const void* F1, const void* N2, const void* F2, double* out, void* workspace,
                   size_t workspace_bytes, void* stream);
+
+/* pbz_segmented for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same statistics, arguments and results (bit for bit) as pbz_segmented, without
+ * the workspace: the partial sums go to a 256 KiB array inside the library's device image, of which every GPU the
+ * library runs on holds one copy until the process ends.  The call itself allocates and frees nothing on the host
+ * or the device and enqueues kernels only (no memset or copy nodes).  The array's device address is looked up at
+ * the first call on each device, so make that call outside graph capture.
+ *   n_segments   at most PBZ_STATIC_MAX_SEGMENTS, and n_segments * blocks_per_segment * prod(i) at most
+ *                PBZ_STATIC_MAX_ELEMENTS: PBZ_ERR_CAPACITY beyond either (use pbz_segmented with a workspace).
+ *   n_segments = 1 gives the plain reductions (pbz_dot, pbz_norm2, ...).
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU (different streams,
+ * or graphs replayed concurrently) race on it and return garbage; calls ordered by a stream or by graph
+ * dependencies are safe.  Nothing has to be cleared between calls: every record read has been written by the
+ * same call. */
+#define PBZ_STATIC_MAX_SEGMENTS 4096
+#define PBZ_STATIC_MAX_ELEMENTS (INT64_C(1) << 40)
+int pbz_segmented_static(const pbz_codec* codec, pbz_statistic statistic, int64_t n_segments,
+                         int64_t blocks_per_segment, const void* N1, const void* F1, const void* N2, const void* F2,
+                         double* out, void* stream);
 
 /* Algorithm 4 (addition of a scalar): C = N F / r, x prod(sqrt(i)) is added to the first coefficient of every
  * block, then N = max|C| and F = rint(C r / N).  N is taken after the shift (the printed listing takes it

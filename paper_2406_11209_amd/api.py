@@ -54,6 +54,7 @@ SIGNATURES = {
     "pbz_mean": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_variance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_segmented": (_c.c_int, [_p, _c.c_int, _c.c_int64, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_segmented_static": (_c.c_int, [_p, _c.c_int, _c.c_int64, _c.c_int64, _p, _p, _p, _p, _p, _p]),
     "pbz_add_scalar": (_c.c_int, [_p, _c.c_int64, _p, _p, _c.c_double, _p, _p, _p]),
     "pbz_ssim": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_double, _c.c_double, _c.c_double, _c.c_double,
                             _c.c_double, _p, _p, _c.c_size_t, _p]),
@@ -370,6 +371,18 @@ class Codec:
         check(self._lib.pbz_segmented(self._h, self.STATISTICS[statistic], int(n_segments), int(blocks_per_segment),
                                       _ptr(N1), _ptr(F1), None if N2 is None else _ptr(N2),
                                       None if F2 is None else _ptr(F2), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
+
+    def segmented_static(self, statistic: str, n_segments: int, blocks_per_segment: int, N1, F1, N2=None, F2=None,
+                         out=None):
+        """pbz_segmented_static: as `segmented`, on the library's fixed scratch array; `out` must be given by
+        callers that may not allocate."""
+        if out is None:
+            out = _torch().empty(n_segments, dtype=_torch().float64, device=N1.device)
+        check(self._lib.pbz_segmented_static(self._h, self.STATISTICS[statistic], int(n_segments),
+                                             int(blocks_per_segment), _ptr(N1), _ptr(F1),
+                                             None if N2 is None else _ptr(N2), None if F2 is None else _ptr(F2),
+                                             _ptr(out), _stream()))
         return out
 
     def ssim(self, N1, F1, N2, F2, s_l=1e-4, s_c=9e-4, w_l=1.0, w_c=1.0, w_s=1.0, out=None):

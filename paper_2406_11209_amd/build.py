@@ -16,7 +16,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpbz.so")
 EXAMPLE = os.path.join(PKG, "c_abi_roundtrip")
 SOURCES = ["pbz_api.hip", "pbz_generic.hip", "pbz_ops.hip", "pbz_fast.hip", "pbz_fast_lane.hip", "pbz_fast_quad16.hip",
-           "pbz_fast_oct8.hip", "pbz_fast_cube16.hip", "pbz_wasserstein.hip", "pbz_tiled.hip"]
+           "pbz_fast_oct8.hip", "pbz_fast_cube16.hip", "pbz_wasserstein.hip", "pbz_tiled.hip", "pbz_static.hip"]
 
 # Packed-FP32 code generation is switched off on purpose (the flag applies to the device pass; the host
 # pass prints a harmless "unknown feature" warning).

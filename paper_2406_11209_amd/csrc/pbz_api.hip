@@ -550,6 +550,8 @@ const char* pbz_status_string(int status) {
     case PBZ_ERR_HIP: return "HIP runtime error";
     case PBZ_ERR_ALLOC: return "host allocation failed";
     case PBZ_ERR_STATE: return "too late in the handle's life for this call";
+    case PBZ_ERR_CAPACITY:
+      return "input beyond the capacity of the library's fixed scratch array (at most 4096 segments and 2^40 elements)";
     default: return "unknown status";
   }
 }

@@ -23,14 +23,14 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     lib = api.load_library()
     names = header_functions()
-    assert len(names) == 33
+    assert len(names) == 34
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(api.SIGNATURES) == names        # the binding covers exactly the header
 
 
 def test_status_strings():
-    for code in range(0, -12, -1):
+    for code in range(0, -14, -1):
         assert api.status_string(code) not in ("", "unknown status")
     assert api.status_string(-99) == "unknown status"
 
@@ -142,6 +142,14 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.pbz_segmented(h, 0, 2, 4, p, p, None, p, p, p, 1 << 20, None) == -1      # dot needs both operands
     assert lib.pbz_segmented(h, 1, 0, 4, p, p, None, None, p, p, 1 << 20, None) == -7
     assert lib.pbz_segmented(nodc._h, 3, 2, 4, p, p, None, None, p, p, 1 << 20, None) == -6
+    # the variant on the library's fixed scratch array: the same checks, and its own capacity limits
+    assert lib.pbz_segmented_static(h, 9, 2, 4, p, p, p, p, p, None) == -4
+    assert lib.pbz_segmented_static(h, 0, 2, 4, p, p, None, p, p, None) == -1
+    assert lib.pbz_segmented_static(h, 1, 0, 4, p, p, None, None, p, None) == -7
+    assert lib.pbz_segmented_static(h, 1, 2, 0, p, p, None, None, p, None) == -7
+    assert lib.pbz_segmented_static(nodc._h, 3, 2, 4, p, p, None, None, p, None) == -6
+    assert lib.pbz_segmented_static(h, 1, 4097, 4, p, p, None, None, p, None) == -13
+    assert lib.pbz_segmented_static(h, 1, 2, (1 << 40) // 64 // 2 + 1, p, p, None, None, p, None) == -13
     assert lib.pbz_add_scalar(h, 4, p, p, float("nan"), p, p, None) == -9
     assert lib.pbz_difference_norm2(h, 4, p, p, p, None, p, p, 1 << 20, None) == -1
     assert lib.pbz_approximate_wasserstein_workspace(h, 1000, ctypes.byref(need)) == 0 and need.value >= 32 * 1000
