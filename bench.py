@@ -3,21 +3,25 @@
 
 A "step" is one pass of every hot-path operation over one synthetic workload that is already resident
 in HBM: compress(A), decompress, negate, multiply by a scalar, add(A, B), mean, dot, L2 norm, cosine
-similarity, covariance, variance (B is compressed once, outside the timed region).  The default
-workload is the 512^3 FP64 volume with 4x4x4 blocks and int16 indices (the largest configuration whose
-operation list is exactly compress / decompress / dot / norm); `--config 5` selects the 1 GiB bfloat16
-volume, `--config 1..3` the smaller ones, `--config 6` an MRI-like FP32 stack in 4x16x16 blocks (not one of the
-benchmark workloads).
+similarity, covariance, variance (B is compressed once, outside the timed region).
 
-Prints one JSON line:  value = GB/s of uncompressed input pushed through the whole step;  `ops` has the
-per-operation times (HIP events on the launch stream, inside the timed region), GB/s of uncompressed
-input (codec) or of compressed bytes read (reductions), GB/s of algorithmic bytes moved and that as a
-fraction of the 8 TB/s HBM peak;  `roofline` describes the dominant kernel (compress);  `cpu_baseline`
-is the FP64 numpy oracle timed on a bounded sample of the same workload on this machine's host cores.
+With no `--config` the run covers both 1 GiB workloads: the 512^3 FP64 volume in 4x4x4 blocks with int16
+indices (the headline: `value`, `ms_per_step`, `ops`, `roofline`, `cpu_baseline` at the top level of the
+JSON line are its figures) and the 1024x1024x512 bfloat16 volume in 8x8x8 blocks with int8 indices and
+the 4x4x4 low-frequency box kept; each is timed for `--steps` steps after `--warmup` untimed ones, and
+`workloads` holds the full record of both.  `--config N` times workload N alone (1..3: the smaller ones,
+6: an MRI-like FP32 stack in 4x16x16 blocks, not one of the benchmark's five).
+
+Per operation: time (HIP events on the launch stream, inside the timed region), GB/s of uncompressed input
+(codec) or of compressed bytes read (reductions), GB/s of algorithmic bytes moved and that as a fraction of
+the 8 TB/s HBM peak.  `roofline` describes the dominant kernel of the step, by measured time, and lists
+both codec kernels; `cpu_baseline` is the FP64 numpy oracle timed on a bounded sample of the same workload
+on this machine's host cores.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -29,13 +33,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+LLC_BYTES = 256 * 1024 * 1024
 
-# HBM bytes per compress launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
-# the same counters read for a plain element-wise kernel over the same array); recorded in profiles/.
-MEASURED_COMPRESS_TRAFFIC = {
-    "cfg4_3d_f64_b4x4x4_i16": int((1048692.6 + 278521.4) * 1024),     # KiB read + KiB written, scaled
-    "cfg5_3d_bf16_b8x8x8_i8_mask4x4x4": int((1048679.0 + 69632.8) * 1024),
+# HBM bytes per launch of the two codec kernels from hardware counters: rocprofv3 --pmc FETCH_SIZE and --pmc
+# WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for pbz_stream_copy over the same
+# 1 GiB array.  {workload: (profiles/ file the figures are taken from, {op: (KiB read, KiB written)})}
+MEASURED_TRAFFIC_KIB = {
+    "cfg4_3d_f64_b4x4x4_i16": ("profiles/hot_path_step__cfg4_512cube_f64_4x4x4_i16.md",
+                               {"compress": (1048681.9, 278528.0), "decompress": (278690.5, 1048576.0)}),
+    "cfg5_3d_bf16_b8x8x8_i8_mask4x4x4": ("profiles/hot_path_step__cfg5_1024x1024x512_bf16_8x8x8_i8_box4.md",
+                                         {"compress": (1048679.0, 69632.8), "decompress": (69766.0, 1048576.0)}),
 }
+
+# corner sub-array of A and B the oracle is timed on: roughly 10-30 s of host time per workload
+CPU_SAMPLE = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (256, 512, 512),
+              6: (128, 512, 512)}
 
 
 def parse():
@@ -43,7 +55,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5, 6])
+    ap.add_argument("--config", type=int, default=None, choices=[1, 2, 3, 4, 5, 6],
+                    help="time this workload alone (default: the two 1 GiB workloads, 4 then 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the operations timed outside the step (used for profiles of the step itself)")
@@ -79,9 +92,11 @@ def cpu_baseline(wl, sample_shape, transform="dct"):
     po.add(A, B)
     po.dot(A, B)
     po.norm2(A)
-    po.mean(A)
-    po.covariance(A, B)
-    po.variance(A)
+    has_dc = bool(A.P.reshape(-1)[0])
+    if has_dc:
+        po.mean(A)
+        po.covariance(A, B)
+        po.variance(A)
     po.cosine_similarity(A, B)
     dt = time.perf_counter() - t0
     in_bytes = a.size * wl.elem_bytes
@@ -101,27 +116,27 @@ def cpu_baseline(wl, sample_shape, transform="dct"):
                          a8.size * wl.elem_bytes / t_single / 1e9)}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (blocks are independent, so an array shards by slabs of "
-              "blocks and a reduction needs one exchange of its five partial sums); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def stream_copy_gbps(torch, api, x, y, repeats=5):
+    """Rate of the library's plain copy kernel over the workload's uncompressed array (bytes read + written)."""
+    api.stream_copy(y, x)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(repeats):
+        api.stream_copy(y, x)
+    c1.record()
+    torch.cuda.synchronize()
+    return 2 * x.numel() * x.element_size() * repeats / c0.elapsed_time(c1) / 1e6
 
-    import torch
-    from paper_2406_11209_amd import synth
+
+def run_workload(config, args, torch, dev):
+    """Times workload `config`; returns its record (the fields a single-workload JSON line is made of)."""
+    from paper_2406_11209_amd import api, synth
     from paper_2406_11209_amd.api import Codec
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
     t_gen = time.perf_counter()
-    wl = synth.make_workload(args.config)
+    wl = synth.make_workload(config)
     t_gen = time.perf_counter() - t_gen
-    tdt = {"f64": torch.float64, "f32": torch.float32, "bf16": torch.bfloat16}[wl.dtype]
 
     def up(x):
         if wl.dtype == "bf16":
@@ -150,7 +165,8 @@ def main():
     for _ in range(n_sets - 1):
         sets.append((xA.clone(), torch.empty_like(N1), torch.empty_like(F1), N2.clone(), F2.clone(),
                      torch.empty_like(Nn), torch.empty_like(Fn), torch.empty_like(y)))
-    cache_state = "cold" if n_sets * step_bytes >= 600_000_000 else "warm (the workload is too small to rotate out of the last-level cache)"
+    between_steps = "cold" if n_sets * step_bytes >= 600_000_000 else \
+        "warm (the workload is too small to rotate out of the last-level cache)"
     rotation = [0]
 
     def rotate():
@@ -159,8 +175,9 @@ def main():
         xA, N1, F1, N2, F2, Nn, Fn, y = sets[rotation[0]]
 
     # (name, callable, algorithmic bytes moved, bytes the headline GB/s is quoted on).  Order: the codec, the
-    # operations that write arrays, then the reductions; the light mean goes first among those because whatever
-    # follows a writer also waits for the tail of its write-back.
+    # operations that write arrays, then the reductions.  Whatever follows a writer also waits for the tail of its
+    # write-back (measured: the reduction placed right after `add` takes 20 us longer on the FP64 volume, whichever
+    # reduction it is), so the light `mean` goes first among the reductions.
     ops = [
         ("compress", lambda: codec.compress(xA, N1, F1), in_bytes + comp_bytes, in_bytes),
         ("decompress", lambda: codec.decompress(N1, F1, wl.shape, out=y), in_bytes + comp_bytes, in_bytes),
@@ -182,6 +199,8 @@ def main():
             ("covariance", lambda: codec.covariance(N1, F1, N2, F2, out=scal[4:5]), 2 * comp_bytes, 2 * comp_bytes),
             ("variance", lambda: codec.variance(N1, F1, out=scal[5:6]), comp_bytes, comp_bytes),
         ]
+    reads_compressed_only = {"negate", "mul_scalar", "add", "mean", "dot", "norm2", "cosine_similarity", "covariance",
+                             "variance"}
 
     def step(events=None):
         if n_sets > 1:
@@ -193,18 +212,10 @@ def main():
             if events is not None:
                 events[i][1].record()
 
-    # A plain element-wise kernel of known traffic (reads and writes the uncompressed array once): the reference
-    # dispatch that hardware-counter runs of this script scale FETCH_SIZE / WRITE_SIZE by, and the box's
-    # practical streaming bandwidth to put next to the 8 TB/s datasheet peak.
-    torch.neg(xA, out=y)
-    torch.cuda.synchronize()
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(5):
-        torch.neg(xA, out=y)
-    c1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 2 * in_bytes * 5 / c0.elapsed_time(c1) / 1e6
+    # The library's plain copy kernel over the uncompressed array: the box's practical streaming bandwidth, put
+    # next to the 8 TB/s datasheet peak, and the reference dispatch that hardware-counter runs of this script
+    # scale FETCH_SIZE / WRITE_SIZE by.
+    copy_gbps = stream_copy_gbps(torch, api, xA, y)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -216,7 +227,8 @@ def main():
         step(ev[k])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    steps = args.steps
+    ms_per_step = dt / steps * 1e3
     if args.graph:
         # the same step recorded once (every call is a plain kernel launch on the current stream) and replayed
         # (one step per buffer set, so that a replay rotates through the sets like the eager loop does)
@@ -231,8 +243,8 @@ def main():
         for k in range(replays):
             graph.replay()
         torch.cuda.synchronize()
-        args.steps = replays * n_sets
-        ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+        steps = replays * n_sets
+        ms_per_step = (time.perf_counter() - t0) / steps * 1e3
 
     per_op = {}
     for i, (name, _, moved, quoted) in enumerate(ops):
@@ -242,8 +254,16 @@ def main():
                         "ms_min": round(float(np.min(times)), 4), "gbps": round(quoted / ms / 1e6, 1),
                         "gbps_moved": round(moved / ms / 1e6, 1),
                         "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBPS, 4)}
-    # operations added beyond the base hot path (scalar addition, SSIM, block-wise statistics): timed on their
-    # own after the timed region, not part of `value`
+        # what the operation's operands can have found in the 256 MB last-level cache: within a step every
+        # operation re-reads compressed arrays that the one before it wrote or read
+        if name in reads_compressed_only and comp_bytes < LLC_BYTES:
+            per_op[name]["operands"] = "in-step: a compressed operand fits the last-level cache, so hbm_frac is not pure HBM traffic"
+        elif name in reads_compressed_only:
+            per_op[name]["operands"] = "in-step: a compressed operand exceeds the last-level cache"
+        else:
+            per_op[name]["operands"] = "uncompressed array streamed from / to HBM"
+
+    # operations beyond the base hot path, timed on their own after the timed region, not part of `value`
     extra_ops = {}
     Fm = torch.empty_like(F1)
 
@@ -335,39 +355,91 @@ def main():
         extra_ops[name] = {"ms": round(ms, 4), "gbps_moved": round(moved / ms / 1e6, 1),
                            "hbm_frac": round(moved / ms / 1e6 / HBM_PEAK_GBPS, 4)}
 
-    comp = per_op["compress"]
-    roofline = {"bound": "hbm", "kernel": codec.kernel_name("compress", wl.shape, wl.dtype),
-                "achieved": comp["gbps_moved"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(comp["gbps_moved"] / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_COMPRESS_TRAFFIC.get(wl.name),
+    # the dominant kernel of the step by measured time: one of the two codec kernels (each is a single launch
+    # whose event time is its duration); both are listed
+    traffic_file, traffic = MEASURED_TRAFFIC_KIB.get(wl.name, (None, {}))
+    codec_kernels = {}
+    for name in ("compress", "decompress"):
+        rec = per_op[name]
+        kib = traffic.get(name) if args.transform == "dct" else None
+        codec_kernels[name] = {"kernel": codec.kernel_name(name, wl.shape, wl.dtype), "ms": rec["ms"],
+                               "achieved": rec["gbps_moved"], "frac": round(rec["gbps_moved"] / HBM_PEAK_GBPS, 4),
+                               "traffic": None if kib is None else int(round((kib[0] + kib[1]) * 1024)),
+                               "frac_of_measured_copy": round(rec["gbps_moved"] / copy_gbps, 4)}
+    dominant = max(codec_kernels, key=lambda n: codec_kernels[n]["ms"])
+    dom = codec_kernels[dominant]
+    roofline = {"bound": "hbm", "kernel": dom["kernel"] + " (" + dominant + ")", "achieved": dom["achieved"],
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom["frac"], "traffic": dom["traffic"],
+                "traffic_source": traffic_file if dom["traffic"] is not None else None,
                 "algorithmic_bytes_per_launch": in_bytes + comp_bytes,
                 "measured_streaming_copy_gbps": round(copy_gbps, 1),
-                "frac_of_measured_copy": round(comp["gbps_moved"] / copy_gbps, 4)}
+                "streaming_copy_kernel": "pbz_stream_copy over the workload's uncompressed array",
+                "frac_of_measured_copy": dom["frac_of_measured_copy"],
+                "codec_kernels": codec_kernels}
 
-    out = {
-        "metric": "compress/decompress GB/s + compressed dot/L2-norm GB/s; fraction of HBM peak",
+    record = {
         "value": round(in_bytes / (ms_per_step * 1e-3) / 1e9, 2),
-        "unit": "GB/s of uncompressed input through one whole hot-path step",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4),
+        "steps": steps,
         "dtype": {"f64": "f64", "f32": "f32", "bf16": "f32"}[wl.dtype] if wl.index_bits == 8 or wl.ftype == "f64" else "f64",
-        "data": "synthetic",
         "config": {"workload": wl.name, "shape": list(wl.shape), "block": list(wl.block), "array_dtype": wl.dtype,
                    "index_bits": wl.index_bits, "kept_per_block": lay.kept_per_block, "transform": args.transform,
                    "launch": "hip graph replay" if args.graph else "eager",
-                   "caches": cache_state, "buffer_sets": n_sets, "uncompressed_bytes": in_bytes, "compressed_bytes": comp_bytes,
+                   "caches": "between steps: " + between_steps + "; within a step every operation follows the previous "
+                             "one directly (see ops[*].operands)",
+                   "buffer_sets": n_sets, "uncompressed_bytes": in_bytes, "compressed_bytes": comp_bytes,
                    "input_generation_s": round(t_gen, 1)},
         "ops": per_op,
         "extra_ops": extra_ops,
         "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        record["cpu_baseline"] = cpu_baseline(wl, CPU_SAMPLE[config], args.transform)
+    del sets, xA, xB, N1, F1, N2, F2, Nn, Fn, y, Fm
+    gc.collect()
+    torch.cuda.empty_cache()
+    return record
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (blocks are independent, so an array shards by slabs of "
+              "blocks and a reduction needs one exchange of its five partial sums); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    configs = [args.config] if args.config is not None else [4, 5]
+    records = [run_workload(c, args, torch, dev) for c in configs]
+    head = records[0]
+    out = {
+        "metric": "compress/decompress GB/s + compressed dot/L2-norm GB/s; fraction of HBM peak",
+        "value": head["value"],
+        "unit": "GB/s of uncompressed input through one whole hot-path step",
+        "n_gpus": 1, "steps": head["steps"], "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"],
+        "data": "synthetic",
+        "config": head["config"],
+        "ops": head["ops"],
+        "extra_ops": head["extra_ops"],
+        "roofline": head["roofline"],
         # the paper gives its timings as figures only (Sec. IV-E, Fig. 2: RTX 3090, FP64 / int8 / 8x8 blocks;
         # Fig. 3: RTX 2070 Super; Fig. 8: hardware not stated), so there is no number to divide by
         "paper_timings": "not reported numerically (figures only: Fig. 2 on an RTX 3090, Fig. 3 on an RTX 2070 Super, Fig. 8)",
     }
-    if not args.no_cpu_baseline:
-        # sized for roughly 10-30 s of oracle time on the machine's host cores
-        sample = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (512, 512, 512), 6: (128, 512, 512)}[args.config]
-        out["cpu_baseline"] = cpu_baseline(wl, sample, args.transform)
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    if len(records) > 1:
+        # every workload of the run, the headline included, each timed for the same number of steps
+        out["workloads"] = {r["config"]["workload"]: r for r in records}
     print(json.dumps(out))
 
 

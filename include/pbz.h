@@ -48,18 +48,26 @@
 extern "C" {
 #endif
 
+/* The enumerations below are plain ints at the ABI.  A C++ caller sees them with a fixed underlying type, so that a
+ * value outside the list, which every entry point answers with an error status, is an ordinary int there too. */
+#ifdef __cplusplus
+#define PBZ_ENUM : int
+#else
+#define PBZ_ENUM
+#endif
+
 #define PBZ_MAX_NDIM 8
 #define PBZ_MAX_BLOCK_EXTENT 256   /* per-dimension block extent limit */
 #define PBZ_MAX_BLOCK_VOLUME 4096  /* elements per block limit */
 
 /* Float types of Sec. III-A ("Data type conversion"): array element types and the working type f. */
-typedef enum { PBZ_F64 = 0, PBZ_F32 = 1, PBZ_BF16 = 2, PBZ_F16 = 3 } pbz_ftype;
+typedef enum PBZ_ENUM { PBZ_F64 = 0, PBZ_F32 = 1, PBZ_BF16 = 2, PBZ_F16 = 3 } pbz_ftype;
 /* Bin index types of Sec. III-A ("Binning"); the index radius is r = 2^(bits-1) - 1.
  * PBZ_I64 is declared because the paper lists it, but is rejected with PBZ_ERR_TYPE: its radius is not
  * representable in FP64. */
-typedef enum { PBZ_I8 = 0, PBZ_I16 = 1, PBZ_I32 = 2, PBZ_I64 = 3 } pbz_itype;
+typedef enum PBZ_ENUM { PBZ_I8 = 0, PBZ_I16 = 1, PBZ_I32 = 2, PBZ_I64 = 3 } pbz_itype;
 
-typedef enum {
+typedef enum PBZ_ENUM {
   PBZ_OK = 0,
   PBZ_ERR_NULL = -1,        /* a required pointer is NULL */
   PBZ_ERR_NDIM = -2,        /* ndim outside 1..PBZ_MAX_NDIM */
@@ -77,7 +85,7 @@ typedef enum {
 } pbz_status;
 
 /* Kernel families, for pbz_codec_set_kernel_path / pbz_kernel_name. */
-typedef enum { PBZ_PATH_AUTO = 0, PBZ_PATH_GENERIC = 1 } pbz_kernel_path;
+typedef enum PBZ_ENUM { PBZ_PATH_AUTO = 0, PBZ_PATH_GENERIC = 1 } pbz_kernel_path;
 
 typedef struct pbz_codec pbz_codec; /* opaque compression settings (Sec. III-A): i, f, index type, P */
 
@@ -96,7 +104,7 @@ void pbz_codec_destroy(pbz_codec* codec);
  * Both have a constant first basis function, so every operation of Sec. IV-A applies unchanged.  Arrays
  * compressed under different transforms must not be combined.  Must be called before the handle's first
  * compress / decompress (its per-device tables are built then): PBZ_ERR_STATE afterwards.  Needs no GPU. */
-typedef enum { PBZ_TRANSFORM_DCT = 0, PBZ_TRANSFORM_HAAR = 1 } pbz_transform;
+typedef enum PBZ_ENUM { PBZ_TRANSFORM_DCT = 0, PBZ_TRANSFORM_HAAR = 1 } pbz_transform;
 int pbz_codec_set_transform(pbz_codec* codec, pbz_transform transform);
 
 /* Force the slow fully general kernels (PBZ_PATH_GENERIC) instead of the specialised ones; for testing. */
@@ -208,7 +216,7 @@ int pbz_variance(const pbz_codec* codec, int64_t n_blocks, const void* N, const 
  * number of segments instead of two per segment.  The covariance of consecutive steps of one series (or the
  * norm of their difference) is obtained by passing N2 / F2 = N1 / F1 advanced by one run and n_segments reduced
  * by one.  N2 / F2 are ignored (may be NULL) for norm2, mean and variance.  Workspace as for the plain reductions. */
-typedef enum {
+typedef enum PBZ_ENUM {
   PBZ_STAT_DOT = 0, PBZ_STAT_NORM2 = 1, PBZ_STAT_COSINE_SIMILARITY = 2, PBZ_STAT_MEAN = 3, PBZ_STAT_COVARIANCE = 4,
   PBZ_STAT_VARIANCE = 5, PBZ_STAT_DIFFERENCE_NORM2 = 6
 } pbz_statistic;
@@ -280,6 +288,13 @@ int pbz_approximate_wasserstein_workspace(const pbz_codec* codec, int64_t n_bloc
 int pbz_approximate_wasserstein(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1,
                                 const void* N2, const void* F2, double p, double* out, void* workspace,
                                 size_t workspace_bytes, void* stream);
+
+/* A plain copy kernel of known traffic: dst[0 .. bytes) = src[0 .. bytes), both device, 16-byte aligned
+ * (PBZ_ERR_WORKSPACE otherwise), not overlapping; bytes between 1 and 2^43 (PBZ_ERR_SHAPE otherwise).  It moves
+ * `bytes` in and `bytes` out and nothing else, which makes it the yardstick of the measurements (Sec. IV-E times
+ * the method's operations against array size; here they are set against the memory system's own rate): the box's
+ * practical streaming bandwidth, and the reference dispatch that hardware-counter readings are scaled by. */
+int pbz_stream_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 /* Name of the kernel family pbz_compress ("compress") or pbz_decompress ("decompress") would run for
  * this shape and array type: "generic" or the name of a specialised kernel.  Host only; returns a static

@@ -14,7 +14,8 @@ from typing import Optional, Sequence, Tuple
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libpbz.so")
+# PBZ_LIBRARY names another build of the same library (the host-only sanitizer build that a CPU test makes)
+LIB_PATH = os.environ.get("PBZ_LIBRARY") or os.path.join(_PKG, "libpbz.so")
 
 PBZ_F64, PBZ_F32, PBZ_BF16, PBZ_F16 = 0, 1, 2, 3
 PBZ_I8, PBZ_I16, PBZ_I32, PBZ_I64 = 0, 1, 2, 3
@@ -64,6 +65,7 @@ SIGNATURES = {
     "pbz_blockwise_covariance": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p]),
     "pbz_approximate_wasserstein_workspace": (_c.c_int, [_p, _c.c_int64, _c.POINTER(_c.c_size_t)]),
     "pbz_approximate_wasserstein": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_double, _p, _p, _c.c_size_t, _p]),
+    "pbz_stream_copy": (_c.c_int, [_p, _p, _c.c_size_t, _p]),
     "pbz_kernel_name": (_c.c_char_p, [_p, _c.c_char_p, _i64p, _c.c_int]),
     "pbz_status_string": (_c.c_char_p, [_c.c_int]),
 }
@@ -144,6 +146,15 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+def stream_copy(dst, src) -> None:
+    """pbz_stream_copy: dst <- src (device tensors of equal byte size), the plain copy kernel the measurements use
+    as their yardstick."""
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != n:
+        raise ValueError("stream_copy needs tensors of equal byte size")
+    check(load_library().pbz_stream_copy(_ptr(dst), _ptr(src), n, _stream()))
+
+
 @dataclass(frozen=True)
 class Layout:
     n_blocks: int
@@ -175,6 +186,7 @@ class Codec:
         check(self._lib.pbz_codec_create(_c.byref(self._h), len(self.block_shape), _shape_arr(self.block_shape),
                                          self.work_type, self.index_type, m))
         self._ws = {}
+        self._layouts = {}
         self.transform = transform
         if transform != "dct":
             check(self._lib.pbz_codec_set_transform(self._h, TRANSFORMS[transform]))
@@ -189,6 +201,16 @@ class Codec:
         check(self._lib.pbz_codec_set_kernel_path(self._h, int(path)))
 
     def layout(self, shape: Sequence[int]) -> Layout:
+        key = tuple(int(v) for v in shape)
+        hit = self._layouts.get(key)
+        if hit is not None:
+            return hit
+        lay = self._layout(key)
+        if len(self._layouts) < 64:
+            self._layouts[key] = lay
+        return lay
+
+    def _layout(self, shape: Sequence[int]) -> Layout:
         if len(shape) != len(self.block_shape):
             raise ValueError("shape and block shape must have the same dimensionality")
         nb, kp = _c.c_int64(), _c.c_int64()
@@ -224,11 +246,21 @@ class Codec:
                                         device=device)
         return self._ws[key]
 
+    def _check_compressed(self, shape: Sequence[int], N, F) -> None:
+        """N and F must be what pbz_layout says for `shape`: the C side trusts the pointers it is given."""
+        lay = self.layout(shape)               # also checks that shape has the block shape's dimensionality
+        if N.dtype != _torch_ftype(self.work_type) or F.dtype != _torch_itype(self.index_type):
+            raise ValueError("N / F have the wrong dtype for this codec")
+        if N.numel() != lay.n_blocks or F.numel() != lay.n_blocks * lay.kept_per_block:
+            raise ValueError(f"N / F do not have the size of the compressed form of an array of shape {tuple(shape)}")
+
     # ---- codec -----------------------------------------------------------------------------
     def compress(self, x, N=None, F=None):
         """pbz_compress: x (device tensor) -> (N, F)."""
         if N is None or F is None:
             N, F = self.empty_compressed(x.shape, x.device)
+        else:
+            self._check_compressed(x.shape, N, F)
         check(self._lib.pbz_compress(self._h, _ptr(x), _ftype_of(x), _shape_arr(x.shape), _ptr(N), _ptr(F), _stream()))
         return N, F
 
@@ -243,6 +275,8 @@ class Codec:
         torch = _torch()
         if N is None or F is None:
             N, F = self.empty_compressed(x.shape, x.device)
+        else:
+            self._check_compressed(x.shape, N, F)
         rows = -(-int(x.shape[0]) // int(self.block_shape[0])) if per_step else 1
         if out is None:
             out = torch.empty((rows, 3) if per_step else 3, dtype=torch.float64, device=x.device)
@@ -269,8 +303,11 @@ class Codec:
     def decompress(self, N, F, shape: Sequence[int], dtype=None, out=None):
         """pbz_decompress: (N, F) -> array of `shape` in `dtype` (a torch dtype; default: the working type)."""
         torch = _torch()
+        self._check_compressed(shape, N, F)
         if out is None:
             out = torch.empty(tuple(int(v) for v in shape), dtype=dtype or _torch_ftype(self.work_type), device=N.device)
+        elif out.numel() != int(np.prod([int(v) for v in shape])):
+            raise ValueError("out does not have the array's size")
         check(self._lib.pbz_decompress(self._h, _ptr(N), _ptr(F), _shape_arr(shape), _ptr(out), _ftype_of(out), _stream()))
         return out
 

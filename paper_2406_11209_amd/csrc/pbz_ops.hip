@@ -159,9 +159,11 @@ __device__ __forceinline__ uint4 apply_sign(uint4 a) {
 }
 
 // Each workgroup streams one contiguous run of kThreads * kUnroll vectors: kUnroll independent loads per thread
-// (kThreads vectors apart), then the stores.
+// (kThreads vectors apart), then the stores.  The element-wise kernels of this file may be called in place (an
+// output aliasing the operand it replaces), so none of their pointers is declared __restrict__; every lane reads
+// all it needs of an element before it writes that element.
 template <int kIType, int kSign>
-__device__ __forceinline__ void scale_sign_run(const uint4* __restrict__ in, uint4* __restrict__ out, int64_t nvec,
+__device__ __forceinline__ void scale_sign_run(const uint4* in, uint4* out, int64_t nvec,
                                                int64_t group) {
   const int64_t base = group * (kThreads * kUnroll) + threadIdx.x;
   if (base + (kUnroll - 1) * kThreads < nvec) {
@@ -179,14 +181,14 @@ __device__ __forceinline__ void scale_sign_run(const uint4* __restrict__ in, uin
 }
 
 template <int kIType, int kSign>
-__global__ __launch_bounds__(kThreads) void k_scale_sign_vec(const uint4* __restrict__ in, uint4* __restrict__ out,
+__global__ __launch_bounds__(kThreads) void k_scale_sign_vec(const uint4* in, uint4* out,
                                                              int64_t nvec) {
   scale_sign_run<kIType, kSign>(in, out, nvec, blockIdx.x);
 }
 
 // Algorithm 5 in one launch: the first f_groups workgroups write F_out = sign(x) F_in, the others N_out = |x| N_in
 template <int kIType, int kSign>
-__global__ __launch_bounds__(kThreads) void k_mul_scalar_vec(const uint4* __restrict__ Fin, uint4* __restrict__ Fout,
+__global__ __launch_bounds__(kThreads) void k_mul_scalar_vec(const uint4* Fin, uint4* Fout,
                                                              int64_t nvec, unsigned f_groups,
                                                              const void* Nin, void* Nout, int ntype, double ax,
                                                              int64_t n_blocks) {   // Nin may be Nout
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void k_mul_scalar_vec(const uint4* __rest
     store_float(Nout, ntype, k, load_float<double>(Nin, ntype, k) * ax);
 }
 
-__global__ __launch_bounds__(kThreads) void k_scale_sign_scalar(const void* __restrict__ in, void* __restrict__ out,
+__global__ __launch_bounds__(kThreads) void k_scale_sign_scalar(const void* in, void* out,
                                                                 int itype, int sign, int64_t n) {
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   for (int64_t e = int64_t(blockIdx.x) * kThreads + threadIdx.x; e < n; e += nthreads)
@@ -240,7 +242,7 @@ int scale_sign(const pbz_codec* c, int64_t n_blocks, const void* in, void* out, 
 }
 
 // Algorithm 5, N part: N_out = N_in |x| rounded to the working type
-__global__ __launch_bounds__(kThreads) void k_scale_N(const void* __restrict__ in, void* __restrict__ out, int ntype,
+__global__ __launch_bounds__(kThreads) void k_scale_N(const void* in, void* out, int ntype,
                                                       double ax, int64_t n) {
   const int64_t nthreads = int64_t(gridDim.x) * kThreads;
   for (int64_t k = int64_t(blockIdx.x) * kThreads + threadIdx.x; k < n; k += nthreads)
@@ -291,9 +293,9 @@ __device__ __forceinline__ double div_by(double a, double b, double inv_b) {
 }
 
 template <int kIType, int kNType>
-__global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
-                                                      const void* __restrict__ N2, const uint4* __restrict__ F2,
-                                                      void* __restrict__ Nout, uint4* __restrict__ Fout, double r,
+__global__ __launch_bounds__(kThreads) void k_add_vec(const void* N1, const uint4* F1,
+                                                      const void* N2, const uint4* F2,
+                                                      void* Nout, uint4* Fout, double r,
                                                       double sign2, int64_t nvec, int lanes_shift, int n_f16) {
   constexpr int kPer = PerDword<kIType>::value;
   constexpr int kElems = 4 * kPer;
@@ -352,9 +354,9 @@ __global__ __launch_bounds__(kThreads) void k_add_vec(const void* __restrict__ N
 }
 
 // one wave per block, any kept count, any alignment
-__global__ __launch_bounds__(64) void k_add_generic(const void* __restrict__ N1, const void* __restrict__ F1,
-                                                    const void* __restrict__ N2, const void* __restrict__ F2,
-                                                    void* __restrict__ Nout, void* __restrict__ Fout, int ntype,
+__global__ __launch_bounds__(64) void k_add_generic(const void* N1, const void* F1,
+                                                    const void* N2, const void* F2,
+                                                    void* Nout, void* Fout, int ntype,
                                                     int itype, double r, double sign2, int64_t n_blocks, int kept) {
   for (int64_t k = blockIdx.x; k < n_blocks; k += gridDim.x) {
     const double n1 = load_float<double>(N1, ntype, k), n2 = sign2 * load_float<double>(N2, ntype, k);
@@ -384,8 +386,8 @@ __global__ __launch_bounds__(64) void k_add_generic(const void* __restrict__ N1,
 // F = rint(C r / N).  Same lane layout as k_add_vec.
 // ---------------------------------------------------------------------------------------------
 template <int kIType, int kNType>
-__global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
-                                                             void* __restrict__ Nout, uint4* __restrict__ Fout,
+__global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* N1, const uint4* F1,
+                                                             void* Nout, uint4* Fout,
                                                              double r, double shift, int64_t nvec, int lanes_shift,
                                                              int n_f16) {
   constexpr int kPer = PerDword<kIType>::value;
@@ -441,8 +443,8 @@ __global__ __launch_bounds__(kThreads) void k_add_scalar_vec(const void* __restr
   }
 }
 
-__global__ __launch_bounds__(64) void k_add_scalar_generic(const void* __restrict__ N1, const void* __restrict__ F1,
-                                                           void* __restrict__ Nout, void* __restrict__ Fout, int ntype,
+__global__ __launch_bounds__(64) void k_add_scalar_generic(const void* N1, const void* F1,
+                                                           void* Nout, void* Fout, int ntype,
                                                            int itype, double r, double shift, int64_t n_blocks,
                                                            int kept) {
   for (int64_t k = blockIdx.x; k < n_blocks; k += gridDim.x) {

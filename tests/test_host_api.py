@@ -23,7 +23,7 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     lib = api.load_library()
     names = header_functions()
-    assert len(names) == 34
+    assert len(names) == 35
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(api.SIGNATURES) == names        # the binding covers exactly the header
@@ -92,7 +92,7 @@ def test_layout_ragged_and_errors():
 
 def test_compressed_bits_follow_the_papers_component_list(golden):
     # Sec. IV-C example: (3,224,224), block 4^3, FP32 N, int16, no pruning -> ratio ~2.91; int8 + half pruned -> ~10.66
-    for s, u, i, f, ib, kept, want in golden("paper_compression_ratios.txt"):
+    for s, u, i, f, ib, kept, want, stored in golden("paper_compression_ratios.txt"):
         s = tuple(int(v) for v in s.split(","))
         i = tuple(int(v) for v in i.split(","))
         mask = np.zeros(int(np.prod(i)), dtype=bool)
@@ -101,6 +101,7 @@ def test_compressed_bits_follow_the_papers_component_list(golden):
         bits = c.compressed_bits(s)
         d, nb = len(s), 3136
         assert bits == 4 + 64 * d + 64 + 64 * d + int(np.prod(i)) + int(f) * nb + int(ib) * int(kept) * nb
+        assert bits == int(stored)                 # the count added up by hand from the paper's component list
         assert abs(int(u) * int(np.prod(s)) / bits - float(want)) < 0.01
 
 
@@ -150,6 +151,9 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.pbz_segmented_static(nodc._h, 3, 2, 4, p, p, None, None, p, None) == -6
     assert lib.pbz_segmented_static(h, 1, 4097, 4, p, p, None, None, p, None) == -13
     assert lib.pbz_segmented_static(h, 1, 2, (1 << 40) // 64 // 2 + 1, p, p, None, None, p, None) == -13
+    assert lib.pbz_stream_copy(None, p, 64, None) == -1
+    assert lib.pbz_stream_copy(p, p, 0, None) == -7
+    assert lib.pbz_stream_copy(p, ctypes.c_void_p(264), 64, None) == -8
     assert lib.pbz_add_scalar(h, 4, p, p, float("nan"), p, p, None) == -9
     assert lib.pbz_difference_norm2(h, 4, p, p, p, None, p, p, 1 << 20, None) == -1
     assert lib.pbz_approximate_wasserstein_workspace(h, 1000, ctypes.byref(need)) == 0 and need.value >= 32 * 1000
@@ -261,3 +265,24 @@ def test_dispatch_table(row):
     assert c.kernel_name("decompress", shape, dtype) == kernel
     h = Codec(block, ftype, itype, mask, "haar")
     assert h.kernel_name("compress", shape, dtype) == (kernel if kernel == "generic" else kernel + "_haar")
+
+
+def test_binding_checks_compressed_buffers_before_the_call():
+    """The C side trusts the pointers it is given, so the binding compares N, F and the output with the layout of the
+    shape it passes: wrong dimensionality, size or dtype never reaches the library."""
+    import torch
+    c = Codec((8, 8), "f32", "i8")
+    x = torch.zeros((16, 16))
+    N, F = torch.zeros(4), torch.zeros((4, 64), dtype=torch.int8)
+    with pytest.raises(ValueError, match="dimensionality"):
+        c.decompress(N, F, (16,))
+    with pytest.raises(ValueError, match="size"):
+        c.decompress(N[:3], F, (16, 16))
+    with pytest.raises(ValueError, match="size"):
+        c.decompress(N, F, (16, 24))
+    with pytest.raises(ValueError, match="dtype"):
+        c.compress(x, N.double(), F)
+    with pytest.raises(ValueError, match="dtype"):
+        c.compress(x, N, F.to(torch.int16))
+    with pytest.raises(ValueError, match="array's size"):
+        c.decompress(N, F, (16, 16), out=torch.zeros((16, 8)))

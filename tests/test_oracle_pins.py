@@ -215,13 +215,16 @@ def test_stored_N_is_rounded_to_float_type():
 
 # ---------------------------------------------------------------- storage accounting ---
 def test_printed_compression_ratios(golden):
-    for s, u, i, f, ib, kept, want in golden("paper_compression_ratios.txt"):
+    for s, u, i, f, ib, kept, want, stored in golden("paper_compression_ratios.txt"):
         s = tuple(int(v) for v in s.split(","))
         i = tuple(int(v) for v in i.split(","))
         ratio = po.asymptotic_ratio(s, i, int(u), int(f), int(ib), int(kept))
         assert abs(ratio - float(want)) < 0.01
-        exact = int(u) * int(np.prod(s)) / po.compressed_bits(s, i, int(f), int(ib), int(kept))
-        assert abs(exact - ratio) / ratio < 1e-3               # header bits are negligible here
+        # every term of the component list, header included: the count added up by hand in the golden file
+        bits = po.compressed_bits(s, i, int(f), int(ib), int(kept))
+        assert bits == int(stored)
+        # and the ratio it gives is the printed one to the printed two decimals (the asymptotic 10.6667 is not)
+        assert f"{int(u) * int(np.prod(s)) / bits:.2f}" == want
 
 
 # ---------------------------------------------------------------- compressed-space ops --
