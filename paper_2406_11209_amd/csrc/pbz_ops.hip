@@ -559,9 +559,6 @@ struct ReduceTail {
   const void* pilot_f2;
   int64_t seg_n_bytes, seg_f_bytes;  // distance between the segments' first N and F
   int ntype, itype;
-  // sums made from the tile records of a compress kernel: K is the pilot value of the segment's first tile
-  const double* pilot_tiles;         // nullptr otherwise
-  int64_t tiles_per_segment;
 };
 
 // K of operand (N, F) in segment `segment`: the same expression wherever it is evaluated
@@ -628,13 +625,6 @@ __device__ __forceinline__ double group_total(const double* sums, double (*lds)[
   return t;
 }
 
-// the pilot values of segment `segment` (zero where the pass shifts nothing)
-__device__ __forceinline__ void pilot_values(const ReduceTail& t, int64_t segment, double* K1, double* K2) {
-  *K1 = t.pilot_tiles ? t.pilot_tiles[segment * t.tiles_per_segment * 4 + 2]
-                      : pilot_value(t.pilot_n1, t.pilot_f1, t, segment);
-  *K2 = pilot_value(t.pilot_n2, t.pilot_f2, t, segment);
-}
-
 // the requested statistic(s) of segment `segment` from its five sums
 __device__ __forceinline__ void write_statistic(const double* fin, const ReduceTail& t, int64_t segment, double K1,
                                                 double K2) {
@@ -652,29 +642,32 @@ __device__ __forceinline__ void write_statistic(const double* fin, const ReduceT
 
 // grid y runs over the segments of a segmented reduction (1 otherwise).  A segment covered by a single
 // workgroup (small arrays) is finished here and needs no second launch; the sums are the same either way.
-__device__ __forceinline__ void reduce_tail(double* sums, const ReduceTail& t) {
+// K1, K2: the pilot values the sums were shifted by (zero where the pass shifts nothing).  Every workgroup of a
+// segment has the same ones; they travel in the partial record (slots kPilot1, kPilot2), so that the final kernel
+// finds them in the records it reads anyway instead of fetching N and F of the segment's first block once more.
+constexpr int kPilot1 = 5, kPilot2 = 6;
+static_assert(kPilot2 < kReducePartialSlots, "record layout");
+
+__device__ __forceinline__ void reduce_tail(double* sums, const ReduceTail& t, double K1, double K2) {
   __shared__ double lds[kThreads / 64][kNumSums];
   __shared__ double fin[kNumSums];
   const double total = group_total(sums, lds);
   if (gridDim.x == 1) {
     if (threadIdx.x < kNumSums) fin[threadIdx.x] = total;
     __syncthreads();
-    if (threadIdx.x == 0) {
-      double K1, K2;
-      pilot_values(t, blockIdx.y, &K1, &K2);
-      write_statistic(fin, t, blockIdx.y, K1, K2);
-    }
+    if (threadIdx.x == 0) write_statistic(fin, t, blockIdx.y, K1, K2);
     return;
   }
-  if (threadIdx.x < kNumSums)
-    t.partials[(int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * kReducePartialSlots + threadIdx.x] = total;
+  double* record = t.partials + (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * kReducePartialSlots;
+  if (threadIdx.x < kNumSums) record[threadIdx.x] = total;
+  if (threadIdx.x == kPilot1) record[kPilot1] = K1;
+  if (threadIdx.x == kPilot2) record[kPilot2] = K2;
 }
 
 // one workgroup per segment: adds that segment's n_partials (<= kFinalMaxPartials) partial sums in a fixed order.
-// Every thread first issues all its loads (a partial is one 64-byte record whose five sums are read as three
-// 16-byte pieces, kFinalRecords records per thread, from a clamped index: no branch around a load; the first
-// thread also asks for the pilot values it will need at the end), then adds: the kernel's duration is one memory
-// round trip instead of one per partial plus one for the pilot values.
+// Every thread first issues all its loads (a partial is one 64-byte record, read as four 16-byte pieces,
+// kFinalRecords records per thread, from a clamped index: no branch around a load), then adds: the kernel's
+// duration is one memory round trip.  The pilot values are those of the segment's first record, which thread 0 holds.
 constexpr int kFinalThreads = 256;
 constexpr int kFinalMaxPartials = kReduceGroupsOneSegment;
 constexpr int kFinalRecords = kFinalMaxPartials / kFinalThreads;
@@ -685,16 +678,16 @@ __global__ __launch_bounds__(kFinalThreads) void k_reduce_final(ReduceTail t, in
   __shared__ double fin[kNumSums];
   double acc[kNumSums] = {0.0, 0.0, 0.0, 0.0, 0.0};
   const double2* mine = reinterpret_cast<const double2*>(t.partials + int64_t(blockIdx.x) * n_partials * kReducePartialSlots);
-  double2 rec[kFinalRecords][3];
+  double2 rec[kFinalRecords][4];
 #pragma unroll
   for (int j = 0; j < kFinalRecords; ++j) {
     const int p = j * kFinalThreads + int(threadIdx.x);
     const int pc = p < n_partials ? p : 0;
 #pragma unroll
-    for (int q = 0; q < 3; ++q) rec[j][q] = mine[int64_t(pc) * 4 + q];
+    for (int q = 0; q < (j == 0 ? 4 : 3); ++q) rec[j][q] = mine[int64_t(pc) * 4 + q];
   }
-  double K1 = 0.0, K2 = 0.0;
-  if (threadIdx.x == 0) pilot_values(t, blockIdx.x, &K1, &K2);
+  __builtin_amdgcn_sched_barrier(0);      // all loads requested before the first is waited for
+  const double K1 = rec[0][2].y, K2 = rec[0][3].x;      // slots kPilot1, kPilot2 (of record 0 in thread 0)
 #pragma unroll
   for (int j = 0; j < kFinalRecords; ++j)
     if (j * kFinalThreads + int(threadIdx.x) >= n_partials) rec[j][0] = rec[j][1] = rec[j][2] = make_double2(0.0, 0.0);
@@ -726,7 +719,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_tiles(const double2* __rest
     sums[kS11] += sd.x + 2.0 * delta * sd.y + kc.y * delta * delta;
     sums[kD1] += sd.y + kc.y * delta;
   }
-  reduce_tail(sums, tail);
+  reduce_tail(sums, tail, K, 0.0);
 }
 
 // kDiff: the coefficients of the two operands are subtracted element by element before squaring (their
@@ -800,6 +793,13 @@ __device__ __forceinline__ void accumulate_vec(double* sums, const uint4& a, con
 // thread issues kUnroll loads per operand, kThreads vectors apart, with no branch between them.
 constexpr int reduce_unroll(bool two) { return two ? kUnroll : 2 * kUnroll; }
 
+// block that vector v belongs to: a shift when the vectors per block are a power of two (kGeneral = false)
+template <bool kGeneral>
+__device__ __forceinline__ int64_t block_of(int64_t v, int vpb_shift, int64_t vpb) {
+  if constexpr (kGeneral) return vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
+  else return v >> vpb_shift;
+}
+
 template <int kIType, int kNType, bool kTwo, bool kDC, bool kDiff = false, bool kAnyHeads = false>
 __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict__ N1, const uint4* __restrict__ F1,
                                                          const void* __restrict__ N2, const uint4* __restrict__ F2,
@@ -816,12 +816,17 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
       F2 += int64_t(blockIdx.y) * nvec;
     }
   }
-  const double K1 = kDC ? pilot_value(tail.pilot_n1, tail.pilot_f1, tail, blockIdx.y) : 0.0;
-  const double K2 = kDC && kTwo ? pilot_value(tail.pilot_n2, tail.pilot_f2, tail, blockIdx.y) : 0.0;
+  // the segment's pilot values (its first block's N F0, the expression of pilot_value): here N1 / F1 already point at
+  // the segment and the types are the kernel's own, so the two loads carry no branch and no wait of their own
+  const double K1 = kDC ? load_N<kNType>(N1, 0, tail.n_f16 != 0) * double(first_element<kIType>(F1[0].x)) : 0.0;
+  const double K2 = kDC && kTwo ? load_N<kNType>(N2, 0, tail.n_f16 != 0) * double(first_element<kIType>(F2[0].x)) : 0.0;
   // Whether a thread's vector starts a block does not change from step to step when the vectors per block are a
   // power of two that divides the step (every workgroup starts at a multiple of it): its head terms are then
-  // computed once.  The host launches the kAnyHeads variant (which works them out per vector, at the price of 30
-  // more registers) for every other layout.
+  // computed once, and a vector's block is a shift away.  The host launches the kAnyHeads variant (which works the
+  // head terms out per vector, at the price of 30 more registers, and divides) for every other layout.  Keeping the
+  // division out of the common variant matters beyond its cost: with the two alternatives behind a run-time test
+  // the compiler put a full wait after each load of the 16-bit-index passes that carry first coefficients, eight
+  // memory round trips per step instead of one.
   const HeadTerms fixed = head_terms<kIType>(kDC && (threadIdx.x & (vpb - 1)) == 0, K1, K2);
   const int64_t begin = int64_t(blockIdx.x) * chunk;
   const int64_t end = begin + chunk < nvec ? begin + chunk : nvec;
@@ -835,7 +840,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
 #pragma unroll
     for (int u = 0; u < kLoads; ++u) {
       const int64_t v = base + u * kThreads + threadIdx.x;
-      k[u] = vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
+      k[u] = block_of<kAnyHeads>(v, vpb_shift, vpb);
       a[u] = F1[v];
       if constexpr (kTwo) b[u] = F2[v];
     }
@@ -844,6 +849,11 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
       n1[u] = load_N<kNType>(N1, k[u], tail.n_f16 != 0);
       n2[u] = kTwo ? load_N<kNType>(N2, k[u], tail.n_f16 != 0) : 0.0;
     }
+    // The passes that carry first coefficients request every load of the step before any of its arithmetic: left
+    // to itself the instruction scheduler sinks their loads towards the first use to save registers, and the step
+    // then takes one memory round trip per vector instead of one in all (workload 4: variance 57.6 -> 49 us,
+    // covariance 111 -> 103.5 us).  The other passes are scheduled well as they are, and the fence costs them 0.5 us.
+    if constexpr (kDC) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < kLoads; ++u) {
       const int64_t v = base + u * kThreads + threadIdx.x;
@@ -853,14 +863,14 @@ __global__ __launch_bounds__(kThreads) void k_reduce_vec(const void* __restrict_
     }
   }
   for (int64_t v = base + threadIdx.x; v < end; v += kThreads) {
-    const int64_t k = vpb_shift >= 0 ? (v >> vpb_shift) : (v / vpb);
+    const int64_t k = block_of<kAnyHeads>(v, vpb_shift, vpb);
     const uint4 a = F1[v];
     const uint4 b = kTwo ? F2[v] : a;
     accumulate_vec<kIType, kTwo, kDC, kDiff>(sums, a, b, load_N<kNType>(N1, k, tail.n_f16 != 0),
                                              kTwo ? load_N<kNType>(N2, k, tail.n_f16 != 0) : 0.0,
                                              kAnyHeads ? head_terms<kIType>(kDC && (v - k * vpb) == 0, K1, K2) : fixed);
   }
-  reduce_tail(sums, tail);
+  reduce_tail(sums, tail, K1, K2);
 }
 
 // thread per block, any kept count, alignment and N type
@@ -909,7 +919,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_generic(const void* __restr
       sums[kD2] += d2;
     }
   }
-  reduce_tail(sums, tail);
+  reduce_tail(sums, tail, K1, K2);
 }
 
 // Algorithm 7 needs only N and the first kept index of every block
@@ -922,7 +932,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_dc(const void* __restrict__
   const double K1 = pilot_value(tail.pilot_n1, tail.pilot_f1, tail, blockIdx.y);
   for (int64_t kk = int64_t(blockIdx.x) * kThreads + threadIdx.x; kk < n_blocks; kk += nthreads)
     sums[kD1] += load_float<double>(N1, ntype, k0 + kk) * double(load_index(F1, itype, (k0 + kk) * kept)) - K1;
-  reduce_tail(sums, tail);
+  reduce_tail(sums, tail, K1, 0.0);
 }
 
 template <int kIType, int kNType>
@@ -932,23 +942,27 @@ void launch_reduce_vec2(bool two, bool dc, bool diff, dim3 grid, hipStream_t s, 
   const uint4* a = static_cast<const uint4*>(F1);
   const uint4* b = static_cast<const uint4*>(F2);
   dim3 block(kThreads);
-  if (diff)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-  else if (dc) {
+  const bool pow2 = shift >= 0;        // vectors per block a power of two: the variants without a division
+#define PBZ_REDUCE(TWO, DC, DIFF, GENERAL) \
+  hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, TWO, DC, DIFF, GENERAL>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail)
+  if (diff) {
+    if (pow2) PBZ_REDUCE(true, false, true, false);
+    else PBZ_REDUCE(true, false, true, true);
+  } else if (dc) {
     // does the same thread meet the first vector of a block at every step?
-    const bool fixed_heads = shift >= 0 && vpb <= kThreads;
-    if (two && fixed_heads)
-      hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-    else if (two)
-      hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, true, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-    else if (fixed_heads)
-      hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, true, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-    else
-      hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, true, false, true>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-  } else if (two)
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, true, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
-  else
-    hipLaunchKernelGGL((k_reduce_vec<kIType, kNType, false, false>), grid, block, 0, s, N1, a, N2, b, nvec, chunk, shift, vpb, seg_blocks, tail);
+    const bool fixed_heads = pow2 && vpb <= kThreads;
+    if (two && fixed_heads) PBZ_REDUCE(true, true, false, false);
+    else if (two) PBZ_REDUCE(true, true, false, true);
+    else if (fixed_heads) PBZ_REDUCE(false, true, false, false);
+    else PBZ_REDUCE(false, true, false, true);
+  } else if (two) {
+    if (pow2) PBZ_REDUCE(true, false, false, false);
+    else PBZ_REDUCE(true, false, false, true);
+  } else {
+    if (pow2) PBZ_REDUCE(false, false, false, false);
+    else PBZ_REDUCE(false, false, false, true);
+  }
+#undef PBZ_REDUCE
 }
 
 template <int kIType>
@@ -1093,8 +1107,6 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     tail.pilot_f1 = dc ? f1 : nullptr;
     tail.pilot_n2 = dc && two ? n2 : nullptr;
     tail.pilot_f2 = dc && two ? f2 : nullptr;
-    tail.pilot_tiles = nullptr;
-    tail.tiles_per_segment = 0;
     tail.seg_n_bytes = n_stride;
     tail.seg_f_bytes = f_stride;
     tail.ntype = int(c->ftype);
@@ -1164,10 +1176,9 @@ int launch_statistics_from_tiles(const pbz_codec* c, int64_t blocks_per_segment,
       chunk = ((tiles_per_segment + max_groups - 1) / max_groups + kThreads - 1) / kThreads * kThreads;
     const int groups = int((tiles_per_segment + chunk - 1) / chunk);
     tail.out = out + seg0 * 3;
-    tail.pilot_tiles = tile_sums + seg0 * tiles_per_segment * 4;
-    tail.tiles_per_segment = tiles_per_segment;
     hipLaunchKernelGGL(k_reduce_tiles, dim3(groups, batch), dim3(kThreads), 0, s,
-                       reinterpret_cast<const double2*>(tail.pilot_tiles), tiles_per_segment, chunk, tail);
+                       reinterpret_cast<const double2*>(tile_sums + seg0 * tiles_per_segment * 4), tiles_per_segment,
+                       chunk, tail);
     int st = hip_status(hipGetLastError());
     if (st != PBZ_OK) return st;
     if (groups > 1) {          // a single workgroup per segment has already written the results
