@@ -39,14 +39,18 @@ LLC_BYTES = 256 * 1024 * 1024
 # WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for pbz_stream_copy over the same
 # 1 GiB array.  {workload: (profiles/ file the figures are taken from, {op: (KiB read, KiB written)})}
 MEASURED_TRAFFIC_KIB = {
+    "cfg2_2d_f32_b8x8_i16_mask4x4": ("profiles/hot_path_step__cfg2_4096sq_f32_8x8_i16_box4.md",
+                                     {"compress": (65637.1, 9218.1), "decompress": (9324.2, 65536.0)}),
+    "cfg3_series_f32_b1x16x16_i8": ("profiles/hot_path_step__cfg3_64x1024x1024_f32_1x16x16_i8.md",
+                                    {"compress": (262309.7, 66564.4), "decompress": (66729.2, 262521.2)}),
     "cfg4_3d_f64_b4x4x4_i16": ("profiles/hot_path_step__cfg4_512cube_f64_4x4x4_i16.md",
-                               {"compress": (1048681.9, 278528.0), "decompress": (278690.5, 1048576.0)}),
+                               {"compress": (1048708.6, 278528.0), "decompress": (278697.7, 1048576.0)}),
     "cfg5_3d_bf16_b8x8x8_i8_mask4x4x4": ("profiles/hot_path_step__cfg5_1024x1024x512_bf16_8x8x8_i8_box4.md",
-                                         {"compress": (1048679.0, 69632.8), "decompress": (69766.0, 1048576.0)}),
+                                         {"compress": (1048690.4, 69632.6), "decompress": (69722.1, 1049201.1)}),
 }
 
 # corner sub-array of A and B the oracle is timed on: roughly 10-30 s of host time per workload
-CPU_SAMPLE = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (256, 512, 512),
+CPU_SAMPLE = {1: (256, 256), 2: (4096, 4096), 3: (64, 1024, 1024), 4: (512, 512, 512), 5: (512, 1024, 512),
               6: (128, 512, 512)}
 
 
