@@ -11,8 +11,18 @@
 //   binning  N_k = max |C_k| by LDS atomics on the bit patterns (non-negative floats order like integers),
 //            I = rint(r C / N_k) for the kept entries only, enumerated in F order: the tile's part of F is one
 //            contiguous run.
+// Wherever the layout allows it the array and F are moved in wider units than one element, so that the index
+// arithmetic (what these kernels spend most of their instructions on) is done once per unit: 16-byte pieces of the
+// array when a block row holds at least one, rows start on 16-byte boundaries and the last extent is a multiple of
+// the piece (a piece then lies wholly inside one block row and wholly inside or outside the array), and runs of four
+// kept entries of F when the kept count is a multiple of four.  512 x 512 x 256 FP64 in 8 x 8 x 8 blocks, int16:
+// 168 vector instructions per element and 1.1 TB/s moved with element-wise accesses, 119 and 2.0-2.2 TB/s this way;
+// with the transform passes taken out the same kernel moves 3.8 TB/s, so what bounds it now are the passes (LDS
+// round trips and barriers as much as their arithmetic), no longer the index arithmetic of the loads and stores.
 // Decompression mirrors this.  The block -> coordinates decode (divisions by the grid extents) happens once per
 // block per tile; the per-element decode is shifts and masks because block extents are powers of two.
+#include <type_traits>
+
 #include "pbz_dct.h"
 #include "pbz_device.h"
 #include "pbz_haar.h"
@@ -34,12 +44,16 @@ struct TileGeom {
   int bx_shift;                   // log2 of the last block extent
   int dims;                       // 4 or 8
   int kept;
+  int vec_x;                      // the array may be moved in 16-byte pieces (see the overview)
+  int vec_f;                      // F may be moved in runs of four entries
   int64_t n_blocks;
   int bshift[PBZ_MAX_NDIM];       // log2 of every block extent
   int64_t shape[PBZ_MAX_NDIM], stride[PBZ_MAX_NDIM], grid[PBZ_MAX_NDIM];
 };
 
-// one spare slot per 32 keeps strided line accesses from piling onto one bank
+// one spare slot per 32 keeps strided line accesses from piling onto one bank (one per 16 for FP64 values, whose
+// 32 fill the banks twice over, changed nothing measurable)
+template <typename T>
 __device__ __forceinline__ int pad(int i) { return i + (i >> 5); }
 
 template <typename T> struct Bits;
@@ -168,7 +182,7 @@ __device__ __forceinline__ void load_tile(const TileGeom& tg, const TileBlocks* 
       row_major_across_blocks(tg, e < total ? e : 0, &b, &j);
       int64_t off;
       in[u] = locate<kDims>(tg, tb, b, j, &off) && e < total;
-      slot[u] = e < total ? pad((b << tg.vol_shift) + j) : -1;
+      slot[u] = e < total ? pad<T>((b << tg.vol_shift) + j) : -1;
       raw[u] = x[in[u] ? off : 0];
     }
 #pragma unroll
@@ -189,7 +203,7 @@ __device__ __forceinline__ void store_tile(const TileGeom& tg, const TileBlocks*
     int b, j;
     row_major_across_blocks(tg, e, &b, &j);
     int64_t off;
-    if (locate<kDims>(tg, tb, b, j, &off)) y[off] = XT(buf[pad((b << tg.vol_shift) + j)]);
+    if (locate<kDims>(tg, tb, b, j, &off)) y[off] = XT(buf[pad<T>((b << tg.vol_shift) + j)]);
   }
 }
 
@@ -201,7 +215,7 @@ __device__ __forceinline__ void store_tile_bf16(const TileGeom& tg, const TileBl
     row_major_across_blocks(tg, e, &b, &j);
     int64_t off;
     if (locate<kDims>(tg, tb, b, j, &off)) {
-      const T v = buf[pad((b << tg.vol_shift) + j)];
+      const T v = buf[pad<T>((b << tg.vol_shift) + j)];
       y[off] = sizeof(T) == 8 ? double_to_bf16_bits(double(v)) : float_to_bf16_bits(float(v));
     }
   }
@@ -214,8 +228,204 @@ __device__ __forceinline__ void store_tile_f16(const TileGeom& tg, const TileBlo
     row_major_across_blocks(tg, e, &b, &j);
     int64_t off;
     if (locate<kDims>(tg, tb, b, j, &off)) {
-      const T v = buf[pad((b << tg.vol_shift) + j)];
+      const T v = buf[pad<T>((b << tg.vol_shift) + j)];
       y[off] = sizeof(T) == 8 ? double_to_f16(double(v)) : _Float16(float(v));
+    }
+  }
+}
+
+// ---- the array in 16-byte pieces ----------------------------------------------------------------------------
+template <typename T, typename XT>
+__device__ __forceinline__ void unpack_piece(const uint4& raw, T* out) {
+  constexpr int P = 16 / int(sizeof(XT));
+  XT e[P];
+  __builtin_memcpy(e, &raw, 16);
+#pragma unroll
+  for (int i = 0; i < P; ++i) {
+    if constexpr (std::is_same<XT, bf16_raw>::value) out[i] = widen_bf16<T>(e[i]);
+    else out[i] = widen<T, XT>(e[i]);
+  }
+}
+
+template <typename T, typename XT>
+__device__ __forceinline__ uint4 pack_piece(const T* v) {
+  constexpr int P = 16 / int(sizeof(XT));
+  XT e[P];
+#pragma unroll
+  for (int i = 0; i < P; ++i) {
+    if constexpr (std::is_same<XT, bf16_raw>::value)
+      e[i].bits = sizeof(T) == 8 ? double_to_bf16_bits(double(v[i])) : float_to_bf16_bits(float(v[i]));
+    else if constexpr (std::is_same<XT, _Float16>::value)
+      e[i] = sizeof(T) == 8 ? double_to_f16(double(v[i])) : _Float16(float(v[i]));
+    else
+      e[i] = XT(v[i]);
+  }
+  uint4 raw;
+  __builtin_memcpy(&raw, e, 16);
+  return raw;
+}
+
+// piece p of the tile -> block and intra-block index of its first element; consecutive p walk along a row across
+// the tile's blocks, like row_major_across_blocks
+template <int P>
+__device__ __forceinline__ void piece_across_blocks(const TileGeom& tg, int p, int* b, int* j) {
+  constexpr int pshift = P == 2 ? 1 : (P == 4 ? 2 : 3);
+  const int ppr_shift = tg.bx_shift - pshift;                 // pieces per block row
+  *b = (p >> ppr_shift) & (tg.G - 1);
+  *j = ((p >> (ppr_shift + tg.g_shift)) << tg.bx_shift) + ((p & ((1 << ppr_shift) - 1)) << pshift);
+}
+
+constexpr int kPieceBatch = 4;                // 16-byte loads a thread keeps in flight while filling a tile
+
+template <int kDims, typename T, typename XT>
+__device__ __forceinline__ void load_tile_pieces(const TileGeom& tg, const TileBlocks* tb, const XT* x, T* buf,
+                                                 int total) {
+  constexpr int P = 16 / int(sizeof(XT));
+  const int n_pieces = total / P;
+  for (int p0 = threadIdx.x; p0 < n_pieces; p0 += kThreads * kPieceBatch) {
+    uint4 raw[kPieceBatch];
+    int slot[kPieceBatch];
+    bool in[kPieceBatch];
+#pragma unroll
+    for (int u = 0; u < kPieceBatch; ++u) {
+      const int p = p0 + u * kThreads;
+      int b, j;
+      piece_across_blocks<P>(tg, p < n_pieces ? p : 0, &b, &j);
+      int64_t off;
+      in[u] = locate<kDims>(tg, tb, b, j, &off) && p < n_pieces;     // the piece's first element decides for all of it
+      slot[u] = p < n_pieces ? pad<T>((b << tg.vol_shift) + j) : -1;    // a piece never straddles a padding boundary
+      raw[u] = *reinterpret_cast<const uint4*>(x + (in[u] ? off : 0));
+    }
+#pragma unroll
+    for (int u = 0; u < kPieceBatch; ++u) {
+      if (slot[u] < 0) continue;
+      T v[P];
+      unpack_piece<T, XT>(raw[u], v);
+#pragma unroll
+      for (int i = 0; i < P; ++i) buf[slot[u] + i] = in[u] ? v[i] : T(0);
+    }
+  }
+}
+
+template <int kDims, typename T, typename XT>
+__device__ __forceinline__ void store_tile_pieces(const TileGeom& tg, const TileBlocks* tb, XT* y, const T* buf,
+                                                  int total) {
+  constexpr int P = 16 / int(sizeof(XT));
+  const int n_pieces = total / P;
+  for (int p = threadIdx.x; p < n_pieces; p += kThreads) {
+    int b, j;
+    piece_across_blocks<P>(tg, p, &b, &j);
+    int64_t off;
+    if (locate<kDims>(tg, tb, b, j, &off)) {
+      const int slot = pad<T>((b << tg.vol_shift) + j);
+      T v[P];
+#pragma unroll
+      for (int i = 0; i < P; ++i) v[i] = buf[slot + i];
+      *reinterpret_cast<uint4*>(y + off) = pack_piece<T, XT>(v);
+    }
+  }
+}
+
+// ---- F in runs of four entries --------------------------------------------------------------------------------
+// rint(t) as an integer for |t| below 2^22 (FP32) / 2^31 (FP64): adding 1.5 * 2^23 (2^52) rounds t to an integer in
+// the current (nearest-even) mode and leaves it, in two's complement, in the low bits of the sum
+__device__ __forceinline__ int round_to_int(float t) { return int(__float_as_uint(t + 12582912.0f)) - 0x4B400000; }
+__device__ __forceinline__ int round_to_int(double t) {
+  return int(uint32_t(__builtin_bit_cast(uint64_t, t + 6755399441055744.0)));
+}
+
+template <typename IT> struct Quad;           // four indices as one store / load
+template <> struct Quad<int8_t> {
+  typedef uint32_t type;
+  static __device__ __forceinline__ type pack(const int* v) {
+    return (uint32_t(v[0]) & 0xffu) | ((uint32_t(v[1]) & 0xffu) << 8) | ((uint32_t(v[2]) & 0xffu) << 16) | (uint32_t(v[3]) << 24);
+  }
+  static __device__ __forceinline__ void unpack(type w, int* v) {
+    v[0] = int(int8_t(w & 0xffu)); v[1] = int(int8_t((w >> 8) & 0xffu)); v[2] = int(int8_t((w >> 16) & 0xffu)); v[3] = int(int8_t(w >> 24));
+  }
+};
+template <> struct Quad<int16_t> {
+  typedef uint2 type;
+  static __device__ __forceinline__ type pack(const int* v) {
+    return make_uint2((uint32_t(v[0]) & 0xffffu) | (uint32_t(v[1]) << 16), (uint32_t(v[2]) & 0xffffu) | (uint32_t(v[3]) << 16));
+  }
+  static __device__ __forceinline__ void unpack(type w, int* v) {
+    v[0] = int(int16_t(w.x & 0xffffu)); v[1] = int(int16_t(w.x >> 16)); v[2] = int(int16_t(w.y & 0xffffu)); v[3] = int(int16_t(w.y >> 16));
+  }
+};
+template <> struct Quad<int32_t> {
+  typedef uint4 type;
+  static __device__ __forceinline__ type pack(const int* v) {
+    return make_uint4(uint32_t(v[0]), uint32_t(v[1]), uint32_t(v[2]), uint32_t(v[3]));
+  }
+  static __device__ __forceinline__ void unpack(type w, int* v) {
+    v[0] = int(w.x); v[1] = int(w.y); v[2] = int(w.z); v[3] = int(w.w);
+  }
+};
+
+// intra-block entries of the four kept positions pos .. pos + 3 (pos a multiple of four)
+__device__ __forceinline__ void kept_entries(bool all_kept, const int32_t* kept_list, int pos, int* j) {
+  if (all_kept) {
+    j[0] = pos; j[1] = pos + 1; j[2] = pos + 2; j[3] = pos + 3;
+  } else {
+    const int4 q = *reinterpret_cast<const int4*>(kept_list + pos);
+    j[0] = q.x; j[1] = q.y; j[2] = q.z; j[3] = q.w;
+  }
+}
+
+// bin and prune, four kept entries per thread and step: one block look-up, one store.  |r C / N| <= r (1 + ulp)
+// rounds to at most r, so no clamp is needed; an all-zero block has N = 1/N = 0 and every C = 0, which gives 0.
+template <typename T, typename IT>
+__device__ __forceinline__ void bin_quads(const TileGeom& tg, const T* buf, const typename Bits<T>::type* bmax,
+                                          const T* binv, T r, IT* F, int64_t k0, const int32_t* kept_list) {
+  typedef typename Quad<IT>::type quad_t;
+  const bool all_kept = tg.kept == (1 << tg.vol_shift);
+  const int n_quads = (tg.G * tg.kept) >> 2;
+  quad_t* out = reinterpret_cast<quad_t*>(F + k0 * tg.kept);
+  for (int q = threadIdx.x; q < n_quads; q += kThreads) {
+    const int e = q << 2;
+    const int b = all_kept ? e >> tg.vol_shift : e / tg.kept;
+    if (k0 + b >= tg.n_blocks) continue;
+    int j[4], idx[4];
+    kept_entries(all_kept, kept_list, e - b * tg.kept, j);
+    const T nk = Bits<T>::from(bmax[b]), inv = binv[b];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const T a = r * buf[pad<T>((b << tg.vol_shift) + j[i])];
+      const T quo = a * inv;
+      idx[i] = round_to_int(fma(fma(-quo, nk, a), inv, quo));
+    }
+    out[q] = Quad<IT>::pack(idx);
+  }
+}
+
+// the tile's run of F -> specified coefficients at their intra-block positions, four entries per load
+template <typename T, typename IT>
+__device__ __forceinline__ void scatter_quads(const TileGeom& tg, const IT* F, int64_t k0, const T* bn,
+                                              const int32_t* kept_list, T* buf) {
+  typedef typename Quad<IT>::type quad_t;
+  const bool all_kept = tg.kept == (1 << tg.vol_shift);
+  const int n_quads = (tg.G * tg.kept) >> 2;
+  const int64_t last = ((tg.n_blocks - k0) * int64_t(tg.kept) >> 2) - 1;      // last quad of the tile that exists
+  const quad_t* in = reinterpret_cast<const quad_t*>(F + k0 * tg.kept);
+  for (int q0 = threadIdx.x; q0 < n_quads; q0 += kThreads * kPieceBatch) {
+    quad_t raw[kPieceBatch];
+#pragma unroll
+    for (int u = 0; u < kPieceBatch; ++u) {
+      const int q = q0 + u * kThreads;
+      raw[u] = in[q <= last ? q : last];
+    }
+#pragma unroll
+    for (int u = 0; u < kPieceBatch; ++u) {
+      const int q = q0 + u * kThreads;
+      if (q >= n_quads || q > last) continue;
+      const int e = q << 2;
+      const int b = all_kept ? e >> tg.vol_shift : e / tg.kept;
+      int j[4], f[4];
+      kept_entries(all_kept, kept_list, e - b * tg.kept, j);
+      Quad<IT>::unpack(raw[u], f);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) buf[pad<T>((b << tg.vol_shift) + j[i])] = bn[b] * T(f[i]);
     }
   }
 }
@@ -231,11 +441,11 @@ __device__ __forceinline__ void pass_n(T* buf, int total, int n_shift, int inner
     const int base = ((l >> inner_shift) << (n_shift + inner_shift)) + (l & (inner - 1));
     T v[n];
 #pragma unroll
-    for (int a = 0; a < n; ++a) v[a] = buf[pad(base + (a << inner_shift))];
+    for (int a = 0; a < n; ++a) v[a] = buf[pad<T>(base + (a << inner_shift))];
     if (kForward) tf_forward<kTf, T, n, 1>(v);
     else tf_inverse<kTf, T, n, 1, n>(v);
 #pragma unroll
-    for (int a = 0; a < n; ++a) buf[pad(base + (a << inner_shift))] = v[a];
+    for (int a = 0; a < n; ++a) buf[pad<T>(base + (a << inner_shift))] = v[a];
     if constexpr (kMax) {
       T m = fabs(v[0]);
 #pragma unroll
@@ -301,16 +511,25 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
     decode_blocks<kDims>(tg, k0, tb);
     for (int b = threadIdx.x; b < tg.G; b += kThreads) bmax[b] = 0;
     __syncthreads();
-    switch (xtype) {                       // one switch around the whole loop, not one per element
-      case PBZ_F64: load_tile<kDims, T, double, false>(tg, tb, static_cast<const double*>(x), buf, total); break;
-      case PBZ_F32: load_tile<kDims, T, float, false>(tg, tb, static_cast<const float*>(x), buf, total); break;
-      case PBZ_BF16: load_tile<kDims, T, bf16_raw, true>(tg, tb, static_cast<const bf16_raw*>(x), buf, total); break;
-      default: load_tile<kDims, T, _Float16, false>(tg, tb, static_cast<const _Float16*>(x), buf, total); break;
+    if (tg.vec_x) {
+      switch (xtype) {                     // one switch around the whole loop, not one per element
+        case PBZ_F64: load_tile_pieces<kDims, T, double>(tg, tb, static_cast<const double*>(x), buf, total); break;
+        case PBZ_F32: load_tile_pieces<kDims, T, float>(tg, tb, static_cast<const float*>(x), buf, total); break;
+        case PBZ_BF16: load_tile_pieces<kDims, T, bf16_raw>(tg, tb, static_cast<const bf16_raw*>(x), buf, total); break;
+        default: load_tile_pieces<kDims, T, _Float16>(tg, tb, static_cast<const _Float16*>(x), buf, total); break;
+      }
+    } else {
+      switch (xtype) {
+        case PBZ_F64: load_tile<kDims, T, double, false>(tg, tb, static_cast<const double*>(x), buf, total); break;
+        case PBZ_F32: load_tile<kDims, T, float, false>(tg, tb, static_cast<const float*>(x), buf, total); break;
+        case PBZ_BF16: load_tile<kDims, T, bf16_raw, true>(tg, tb, static_cast<const bf16_raw*>(x), buf, total); break;
+        default: load_tile<kDims, T, _Float16, false>(tg, tb, static_cast<const _Float16*>(x), buf, total); break;
+      }
     }
     __syncthreads();
     transform_tile<kDims, T, kTf, true>(tg, buf, total, bmax);      // leaves N_k = max |C_k| in bmax
     if (vol == 1) {                        // single-element blocks: nothing was transformed
-      for (int e = threadIdx.x; e < total; e += kThreads) bmax[e] = Bits<T>::of(fabs(buf[pad(e)]));
+      for (int e = threadIdx.x; e < total; e += kThreads) bmax[e] = Bits<T>::of(fabs(buf[pad<T>(e)]));
       __syncthreads();
     }
     for (int b = threadIdx.x; b < tg.G; b += kThreads) {
@@ -321,8 +540,15 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
     __syncthreads();
     // bin and prune: the kept entries of the tile in F order.  (r C) / N from the correctly rounded reciprocal
     // with one remainder correction: the correctly rounded quotient without a division per entry.
-    const int n_kept = tg.G * tg.kept;
+    const int n_kept = tg.vec_f ? 0 : tg.G * tg.kept;
     const bool all_kept = tg.kept == vol;            // then position pos of F holds intra-block entry pos
+    if (tg.vec_f) {
+      switch (itype) {
+        case PBZ_I8: bin_quads<T, int8_t>(tg, buf, bmax, binv, T(r), static_cast<int8_t*>(F), k0, kept_list); break;
+        case PBZ_I16: bin_quads<T, int16_t>(tg, buf, bmax, binv, T(r), static_cast<int16_t*>(F), k0, kept_list); break;
+        default: bin_quads<T, int32_t>(tg, buf, bmax, binv, T(r), static_cast<int32_t*>(F), k0, kept_list); break;
+      }
+    }
     for (int e0 = threadIdx.x; e0 < n_kept; e0 += kThreads * kBatch) {
       int b[kBatch], j[kBatch];
 #pragma unroll
@@ -338,7 +564,7 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
       for (int u = 0; u < kBatch; ++u) {
         if (b[u] < 0) continue;
         const T nk = Bits<T>::from(bmax[b[u]]), inv = binv[b[u]];
-        const T a = T(r) * buf[pad((b[u] << tg.vol_shift) + j[u])];
+        const T a = T(r) * buf[pad<T>((b[u] << tg.vol_shift) + j[u])];
         const T q = a * inv;
         T t = fma(fma(-q, nk, a), inv, q);
         t = fmin(fmax(rint(t), T(-r)), T(r));
@@ -365,7 +591,7 @@ __device__ __forceinline__ void scatter_coefficients(const TileGeom& tg, const I
       f[u] = F[at <= last ? at : last];
       const int ec = e < n_kept ? e : 0;
       const int b = ec / tg.kept;
-      j[u] = e < n_kept ? pad((b << tg.vol_shift) + kept_list[ec - b * tg.kept]) : -1;
+      j[u] = e < n_kept ? pad<T>((b << tg.vol_shift) + kept_list[ec - b * tg.kept]) : -1;
     }
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
@@ -396,21 +622,38 @@ __global__ __launch_bounds__(kThreads) void k_decompress_tiled(TileGeom tg, cons
     for (int b = threadIdx.x; b < tg.G; b += kThreads)      // blocks past the end: the last one again, never stored
       bn[b] = load_float<T>(N, ntype, k0 + b < tg.n_blocks ? k0 + b : tg.n_blocks - 1) / T(r);   // N / r once per block
     if (tg.kept != vol)
-      for (int e = threadIdx.x; e < total; e += kThreads) buf[pad(e)] = T(0);
+      for (int e = threadIdx.x; e < total; e += kThreads) buf[pad<T>(e)] = T(0);
     __syncthreads();
     // Algorithm 3: N F / r at the kept positions
-    switch (itype) {
-      case PBZ_I8: scatter_coefficients<T, int8_t>(tg, static_cast<const int8_t*>(F), k0, bn, T(r), kept_list, buf); break;
-      case PBZ_I16: scatter_coefficients<T, int16_t>(tg, static_cast<const int16_t*>(F), k0, bn, T(r), kept_list, buf); break;
-      default: scatter_coefficients<T, int32_t>(tg, static_cast<const int32_t*>(F), k0, bn, T(r), kept_list, buf); break;
+    if (tg.vec_f) {
+      switch (itype) {
+        case PBZ_I8: scatter_quads<T, int8_t>(tg, static_cast<const int8_t*>(F), k0, bn, kept_list, buf); break;
+        case PBZ_I16: scatter_quads<T, int16_t>(tg, static_cast<const int16_t*>(F), k0, bn, kept_list, buf); break;
+        default: scatter_quads<T, int32_t>(tg, static_cast<const int32_t*>(F), k0, bn, kept_list, buf); break;
+      }
+    } else {
+      switch (itype) {
+        case PBZ_I8: scatter_coefficients<T, int8_t>(tg, static_cast<const int8_t*>(F), k0, bn, T(r), kept_list, buf); break;
+        case PBZ_I16: scatter_coefficients<T, int16_t>(tg, static_cast<const int16_t*>(F), k0, bn, T(r), kept_list, buf); break;
+        default: scatter_coefficients<T, int32_t>(tg, static_cast<const int32_t*>(F), k0, bn, T(r), kept_list, buf); break;
+      }
     }
     __syncthreads();
     transform_tile<kDims, T, kTf, false>(tg, buf, total);
-    switch (ytype) {
-      case PBZ_F64: store_tile<kDims, T, double>(tg, tb, static_cast<double*>(y), buf, total); break;
-      case PBZ_F32: store_tile<kDims, T, float>(tg, tb, static_cast<float*>(y), buf, total); break;
-      case PBZ_BF16: store_tile_bf16<kDims, T>(tg, tb, static_cast<uint16_t*>(y), buf, total); break;
-      default: store_tile_f16<kDims, T>(tg, tb, static_cast<_Float16*>(y), buf, total); break;
+    if (tg.vec_x) {
+      switch (ytype) {
+        case PBZ_F64: store_tile_pieces<kDims, T, double>(tg, tb, static_cast<double*>(y), buf, total); break;
+        case PBZ_F32: store_tile_pieces<kDims, T, float>(tg, tb, static_cast<float*>(y), buf, total); break;
+        case PBZ_BF16: store_tile_pieces<kDims, T, bf16_raw>(tg, tb, static_cast<bf16_raw*>(y), buf, total); break;
+        default: store_tile_pieces<kDims, T, _Float16>(tg, tb, static_cast<_Float16*>(y), buf, total); break;
+      }
+    } else {
+      switch (ytype) {
+        case PBZ_F64: store_tile<kDims, T, double>(tg, tb, static_cast<double*>(y), buf, total); break;
+        case PBZ_F32: store_tile<kDims, T, float>(tg, tb, static_cast<float*>(y), buf, total); break;
+        case PBZ_BF16: store_tile_bf16<kDims, T>(tg, tb, static_cast<uint16_t*>(y), buf, total); break;
+        default: store_tile_f16<kDims, T>(tg, tb, static_cast<_Float16*>(y), buf, total); break;
+      }
     }
     __syncthreads();
   }
@@ -433,6 +676,7 @@ TileGeom make_tile(const pbz_codec* c, const Geom& g) {
   tg.bx_shift = ilog2(c->block[c->ndim - 1]);
   tg.dims = c->ndim <= 4 ? 4 : 8;
   tg.kept = c->kept;
+  tg.vec_x = tg.vec_f = 0;
   tg.n_blocks = g.n_blocks;
   for (int d = 0; d < PBZ_MAX_NDIM; ++d) {        // right-aligned; leading dimensions of extent 1
     const int src = d - (PBZ_MAX_NDIM - c->ndim);
@@ -442,6 +686,16 @@ TileGeom make_tile(const pbz_codec* c, const Geom& g) {
     tg.grid[d] = src >= 0 ? g.grid[src] : 1;
   }
   return tg;
+}
+
+// may the array (elements of array_type at `array`) be moved in 16-byte pieces, and F in runs of four entries?
+void choose_units(const pbz_codec* c, const Geom& g, const void* array, int array_type, const void* F, TileGeom* tg) {
+  const int64_t piece = 16 / ftype_bytes(array_type);        // elements per piece
+  const int64_t last = g.shape[c->ndim - 1];
+  tg->vec_x = c->block[c->ndim - 1] >= piece && last % piece == 0 && (reinterpret_cast<uintptr_t>(array) & 15u) == 0;
+  // every tile starts at a multiple of four entries (whole blocks of a kept count that is one); the kept-position
+  // table is read four entries at a time as well (it comes from hipMalloc: aligned)
+  tg->vec_f = c->kept % 4 == 0 && (reinterpret_cast<uintptr_t>(F) % size_t(4 * itype_bytes(c->itype))) == 0;
 }
 
 size_t tile_lds_bytes(const TileGeom& tg, size_t elem) {
@@ -464,7 +718,8 @@ bool tiled_kernels_cover(const pbz_codec* c) {
 
 int launch_compress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* x, int xtype, void* N,
                           void* F, hipStream_t s) {
-  const TileGeom tg = make_tile(c, g);
+  TileGeom tg = make_tile(c, g);
+  choose_units(c, g, x, xtype, F, &tg);
   const int64_t n_tiles = (tg.n_blocks + tg.G - 1) / tg.G;
   const dim3 grid(tile_grid(n_tiles)), block(kThreads);
 #define PBZ_TILED(T, TF)                                                                                              \
@@ -489,7 +744,8 @@ int launch_compress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables*
 
 int launch_decompress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables* t, const void* N, const void* F,
                             void* y, int ytype, hipStream_t s) {
-  const TileGeom tg = make_tile(c, g);
+  TileGeom tg = make_tile(c, g);
+  choose_units(c, g, y, ytype, F, &tg);
   const int64_t n_tiles = (tg.n_blocks + tg.G - 1) / tg.G;
   const dim3 grid(tile_grid(n_tiles)), block(kThreads);
 #define PBZ_TILED(T, TF)                                                                                              \

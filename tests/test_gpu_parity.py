@@ -715,3 +715,41 @@ def test_variance_of_a_field_with_a_large_offset():
         want = po.ssim(A, B, s_l=1e-8, s_c=1e-8)
         assert abs(got - want) <= 1e-6 * abs(want), (block, "ssim", got, want)
         assert abs(float(case.codec.mean(N1, F1).item()) - po.mean(A)) <= 1e-13 * po.mean(A)
+
+
+def test_general_kernels_on_arrays_that_do_not_start_on_a_16_byte_boundary():
+    """The general kernels move the array in 16-byte pieces when rows start on 16-byte boundaries and element by
+    element otherwise: the same array at an aligned and at a misaligned address (and the compressed form written to
+    a misaligned F) must give the same bits, and decompress back to the same values at either address."""
+    g = rng(21)
+    for shape, block, bits, dtype, keep in (((24, 64), (2, 16), 8, torch.float32, None),
+                                            ((6, 16, 32), (2, 4, 8), 16, torch.float64, None),
+                                            ((40, 48), (8, 8), 32, torch.float32, (4, 4))):
+        n = int(np.prod(shape))
+        host = synth.bump_field(shape, 5, g, (2.0, 8.0)) + 0.1 * g.standard_normal(shape)
+        flat = torch.zeros(n + 3, dtype=dtype, device="cuda")
+        aligned = torch.from_numpy(host).to(dtype).cuda().contiguous()
+        shifted = flat[1:1 + n].view(shape)
+        shifted.copy_(aligned)
+        assert shifted.data_ptr() % 16 != 0 and aligned.data_ptr() % 16 == 0
+        ftype = "f64" if dtype == torch.float64 else "f32"
+        mask = None if keep is None else synth.low_frequency_mask(block, keep)
+        codec = Codec(block, ftype, bits, mask)
+        codec.set_kernel_path(api.PBZ_PATH_GENERIC)
+        N1, F1 = codec.compress(aligned)
+        N2, F2 = codec.compress(shifted)
+        lay = codec.layout(shape)
+        Fbuf = torch.zeros(lay.n_blocks * lay.kept_per_block + 1, dtype=F1.dtype, device="cuda")
+        F3 = Fbuf[1:].view(lay.n_blocks, lay.kept_per_block)                 # F at an address that is not a multiple of four entries
+        N3 = torch.empty_like(N1)
+        codec.compress(aligned, N3, F3)
+        torch.cuda.synchronize()
+        assert torch.equal(N1, N2) and torch.equal(F1, F2) and torch.equal(N1, N3) and torch.equal(F1, F3)
+        y1 = codec.decompress(N1, F1, shape, dtype)
+        y2 = torch.zeros(n + 3, dtype=dtype, device="cuda")[1:1 + n].view(shape)
+        codec.decompress(N3, F3, shape, out=y2)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, y2)
+        case = Case(aligned.cpu().numpy(), None, ftype, block, bits, ftype, mask, api.PBZ_PATH_GENERIC)
+        case.check_compress("A")
+        case.check_decompress(N1, F1)
