@@ -289,6 +289,7 @@ def run_workload(config, args, torch, dev):
         bw = torch.empty(lay.n_blocks, dtype=torch.float64, device=dev)
         bw_bytes = lay.n_blocks * 8
         st3 = torch.empty(3, dtype=torch.float64, device=dev)
+        pair9 = torch.empty(9, dtype=torch.float64, device=dev)
 
         def compress_then_three_reductions():
             codec.compress(xA, N1, F1)
@@ -307,6 +308,8 @@ def run_workload(config, args, torch, dev):
             ("compress_then_mean_variance_norm2", compress_then_three_reductions, in_bytes + 3 * comp_bytes + dc_bytes),
             ("add_scalar", lambda: codec.add_scalar(N1, F1, 0.75, N_out=Nn, F_out=Fn), 2 * comp_bytes),
             ("ssim", lambda: codec.ssim(N1, F1, N2, F2, out=scal[6:7]), 2 * comp_bytes),
+            # dot, cosine, covariance and both operands' mean / variance / norm from one pass over both
+            ("pair_statistics_nine_values", lambda: codec.pair_statistics(N1, F1, N2, F2, out=pair9), 2 * comp_bytes),
             ("blockwise_mean", lambda: codec.blockwise_mean(N1, F1, out=bw), dc_bytes + bw_bytes),
             ("blockwise_variance", lambda: codec.blockwise_variance(N1, F1, out=bw), comp_bytes + bw_bytes),
             ("blockwise_covariance", lambda: codec.blockwise_covariance(N1, F1, N2, F2, out=bw), 2 * comp_bytes + bw_bytes),

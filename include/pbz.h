@@ -198,6 +198,15 @@ int pbz_norm2(const pbz_codec* codec, int64_t n_blocks, const void* N, const voi
 int pbz_statistics(const pbz_codec* codec, int64_t n_blocks, const void* N, const void* F, double* statistics,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Every statistic of Algorithms 6-11 of a pair of compressed arrays from a single pass over both: the five sums
+ * that pass takes (sum C1.C2, sum C1.C1, sum C2.C2 and the two sums of first coefficients) determine them all, so
+ * a caller that wants several (as Algorithm 12 does internally) pays for one.  statistics (device) receives 9 FP64
+ * values: {dot, cosine similarity, covariance, mean_A, mean_B, variance_A, variance_B, norm_A, norm_B}, each the
+ * value its own entry point returns up to FP64 summation order.  Needs the first coefficient of every block
+ * (PBZ_ERR_DC_PRUNED otherwise).  Other arguments as for pbz_dot. */
+int pbz_pair_statistics(const pbz_codec* codec, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                        const void* F2, double* statistics, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ||A - B||_2 of two compressed arrays (the quantity compared between adjacent time steps in Sec. V, fission
  * experiment), taken on the specified coefficients of Algorithm 3: sqrt(sum_kj (N1_k F1_kj - N2_k F2_kj)^2) / r,
  * each difference formed in FP64 before squaring.  The transform being orthonormal, this is the L2 norm of the

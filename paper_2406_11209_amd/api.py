@@ -50,6 +50,7 @@ SIGNATURES = {
     "pbz_compress_statistics_workspace": (_c.c_int, [_p, _i64p, _c.c_int, _c.POINTER(_c.c_size_t)]),
     "pbz_compress_statistics": (_c.c_int, [_p, _p, _c.c_int, _i64p, _p, _p, _c.c_int, _p, _p, _c.c_size_t, _p]),
     "pbz_statistics": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
+    "pbz_pair_statistics": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_difference_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_norm2": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
     "pbz_mean": (_c.c_int, [_p, _c.c_int64, _p, _p, _p, _p, _c.c_size_t, _p]),
@@ -298,6 +299,18 @@ class Codec:
         out = torch.empty(3, dtype=torch.float64, device=N.device) if out is None else out
         ws = self.workspace(N.device)
         check(self._lib.pbz_statistics(self._h, F.shape[0], _ptr(N), _ptr(F), _ptr(out), _ptr(ws), ws.numel(), _stream()))
+        return out
+
+    PAIR_STATISTICS = ("dot", "cosine_similarity", "covariance", "mean_a", "mean_b", "variance_a", "variance_b",
+                       "norm2_a", "norm2_b")
+
+    def pair_statistics(self, N1, F1, N2, F2, out=None):
+        """pbz_pair_statistics: the nine values named in PAIR_STATISTICS from one pass over both arrays (float64)."""
+        torch = _torch()
+        out = torch.empty(9, dtype=torch.float64, device=N1.device) if out is None else out
+        ws = self.workspace(N1.device)
+        check(self._lib.pbz_pair_statistics(self._h, F1.shape[0], _ptr(N1), _ptr(F1), _ptr(N2), _ptr(F2), _ptr(out),
+                                            _ptr(ws), ws.numel(), _stream()))
         return out
 
     def decompress(self, N, F, shape: Sequence[int], dtype=None, out=None):

@@ -439,6 +439,11 @@ int pbz_statistics(const pbz_codec* c, int64_t n_blocks, const void* N, const vo
   return reduce2(c, kStatistics, n_blocks, N, F, nullptr, nullptr, statistics, ws, ws_bytes, stream, false, true);
 }
 
+int pbz_pair_statistics(const pbz_codec* c, int64_t n_blocks, const void* N1, const void* F1, const void* N2,
+                        const void* F2, double* statistics, void* ws, size_t ws_bytes, void* stream) {
+  return reduce2(c, kPairStatistics, n_blocks, N1, F1, N2, F2, statistics, ws, ws_bytes, stream, true, true);
+}
+
 int pbz_variance(const pbz_codec* c, int64_t n_blocks, const void* N, const void* F, double* out, void* ws,
                  size_t ws_bytes, void* stream) {
   return reduce2(c, kVariance, n_blocks, N, F, nullptr, nullptr, out, ws, ws_bytes, stream, false, true);

@@ -103,7 +103,8 @@ int launch_add(const pbz_codec* c, int64_t n_blocks, const void* N1, const void*
                const void* F2, void* Nout, void* Fout, hipStream_t s, double sign2 = 1.0);   // sign2 = -1: A - B
 
 enum ReduceOp { kDot = 0, kNorm2 = 1, kCosine = 2, kMean = 3, kCovariance = 4, kVariance = 5, kSsim = 6,
-                kDiffNorm2 = 7, kStatistics = 8 /* out[0..3) = mean, variance, norm2 from one pass */ };
+                kDiffNorm2 = 7, kStatistics = 8 /* out[0..3) = mean, variance, norm2 from one pass */,
+                kPairStatistics = 9 /* out[0..9): see pbz_pair_statistics */ };
 // ssim_params: {s_l, s_c, w_l, w_c, w_s} for kSsim, otherwise nullptr.  n_segments > 1: the operands are
 // n_segments consecutive runs of n_blocks blocks, one result per run goes to out[0 .. n_segments).
 int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void* N1, const void* F1,

@@ -635,6 +635,17 @@ __device__ __forceinline__ void write_statistic(const double* fin, const ReduceT
       one.op = ops[i];
       t.out[segment * 3 + i] = finish_statistic(fin, one, K1, K2);
     }
+  } else if (t.op == kPairStatistics) { // every statistic of a pair of arrays from the five sums of one pass
+    ReduceTail one = t;
+    const double swapped[kNumSums] = {fin[kS12], fin[kS22], fin[kS11], fin[kD2], fin[kD1]};   // the operands exchanged
+    const int both[3] = {kDot, kCosine, kCovariance}, each[3] = {kMean, kVariance, kNorm2};
+    for (int i = 0; i < 3; ++i) {
+      one.op = both[i];
+      t.out[segment * 9 + i] = finish_statistic(fin, one, K1, K2);
+      one.op = each[i];
+      t.out[segment * 9 + 3 + 2 * i] = finish_statistic(fin, one, K1, K2);
+      t.out[segment * 9 + 4 + 2 * i] = finish_statistic(swapped, one, K2, K1);
+    }
   } else {
     t.out[segment] = finish_statistic(fin, t, K1, K2);
   }
@@ -1086,8 +1097,9 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
   tail.n_blocks = double(n_blocks);
   tail.vol = double(c->vol);
   const bool diff = (op == kDiffNorm2);
-  const bool two = (op == kDot || op == kCosine || op == kCovariance || op == kSsim || diff);
-  const bool dc = (op == kCovariance || op == kVariance || op == kSsim || op == kStatistics || op == kMean);
+  const bool two = (op == kDot || op == kCosine || op == kCovariance || op == kSsim || op == kPairStatistics || diff);
+  const bool dc = (op == kCovariance || op == kVariance || op == kSsim || op == kStatistics || op == kMean ||
+                   op == kPairStatistics);
   const int64_t bpb = int64_t(c->kept) * itype_bytes(c->itype);
   const int64_t n_stride = n_blocks * ftype_bytes(c->ftype), f_stride = n_blocks * bpb;   // bytes per segment
 
@@ -1102,7 +1114,7 @@ int launch_reduce(const pbz_codec* c, ReduceOp op, int64_t n_blocks, const void*
     const char* f1 = static_cast<const char*>(F1) + seg0 * f_stride;
     const char* n2 = two ? static_cast<const char*>(N2) + seg0 * n_stride : nullptr;
     const char* f2 = two ? static_cast<const char*>(F2) + seg0 * f_stride : nullptr;
-    tail.out = out + seg0 * (op == kStatistics ? 3 : 1);
+    tail.out = out + seg0 * (op == kStatistics ? 3 : (op == kPairStatistics ? 9 : 1));
     tail.pilot_n1 = dc ? n1 : nullptr;
     tail.pilot_f1 = dc ? f1 : nullptr;
     tail.pilot_n2 = dc && two ? n2 : nullptr;

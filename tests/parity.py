@@ -244,6 +244,21 @@ class Case:
                 check_scalar(float(g), w, self.tol, f, f"statistics[{t}].{name}")
         return st
 
+    def check_pair_statistics(self, N1, F1, N2, F2):
+        """The nine statistics of one pass over both operands, each against the oracle's own function."""
+        got = self.codec.pair_statistics(N1, F1, N2, F2)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy()
+        A, B = self.oc(N1, F1), self.oc(N2, F2)
+        na, nb = po.norm2(A), po.norm2(B)
+        n_el = float(A.n_blocks) * float(np.prod(self.block))
+        want = [(po.dot(A, B), na * nb), (po.cosine_similarity(A, B), 1.0), (po.covariance(A, B), na * nb / n_el),
+                (po.mean(A), na / math.sqrt(n_el)), (po.mean(B), nb / math.sqrt(n_el)),
+                (po.variance(A), na * na / n_el), (po.variance(B), nb * nb / n_el), (na, 0.0), (nb, 0.0)]
+        for name, g, (w, floor) in zip(self.codec.PAIR_STATISTICS, got, want):
+            check_scalar(float(g), w, self.tol, floor, "pair_statistics." + name)
+        return got
+
     def oc(self, N, F) -> po.Compressed:
         return oracle_compressed(N, F, self.shape, self.block, self.bits, self.ftype, self.mask, self.transform)
 

@@ -138,6 +138,7 @@ def test_full_shape(config, capsys):
         full.check_add_scalar(N1, F1, 0.75)
         full.check_blockwise(N1, F1, N2, F2)
         full.check_ssim(N1, F1, N2, F2)
+        full.check_pair_statistics(N1, F1, N2, F2)
         full.check_wasserstein(N1, F1, N2, F2, 68.0)
     else:
         # the series: per-step statistics on sub-ranges, every step / consecutive pair

@@ -46,6 +46,7 @@ def run_all_ops(case: Case, out_dtypes=()):
             case.check_wasserstein(N1, F1, N2, F2, p)
         assert case.check_wasserstein(N1, F1, N1, F1, 3.0) == 0.0
         case.check_compress_statistics(N1, F1, "A")
+        case.check_pair_statistics(N1, F1, N2, F2)
         for x in (0.75, -3.0):
             N4, F4 = case.check_add_scalar(N1, F1, x)
         case.check_decompress(N4, F4)

@@ -23,7 +23,7 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     lib = api.load_library()
     names = header_functions()
-    assert len(names) == 35
+    assert len(names) == 36
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(api.SIGNATURES) == names        # the binding covers exactly the header
@@ -163,6 +163,9 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert lib.pbz_approximate_wasserstein(h, 4, p, p, p, p, 2.0, p, p, 64, None) == -8
     assert lib.pbz_approximate_wasserstein(h, 4, p, p, None, p, 2.0, p, p, 1 << 20, None) == -1
     assert lib.pbz_approximate_wasserstein(nodc._h, 4, p, p, p, p, 2.0, p, p, 1 << 20, None) == -6
+    assert lib.pbz_pair_statistics(nodc._h, 4, p, p, p, p, p, p, 1 << 20, None) == -6
+    assert lib.pbz_pair_statistics(h, 4, p, p, p, None, p, p, 1 << 20, None) == -1
+    assert lib.pbz_pair_statistics(h, 4, p, p, p, p, p, p, 64, None) == -8
     assert lib.pbz_statistics(nodc._h, 4, p, p, p, p, 1 << 20, None) == -6
     assert lib.pbz_statistics(h, 4, p, p, p, p, 64, None) == -8
     assert lib.pbz_compress_statistics_workspace(h, shape, 1, ctypes.byref(need)) == 0
