@@ -107,28 +107,51 @@ def check(status: int) -> None:
         raise PbzError(status, status_string(status))
 
 
+_SHAPES = {}
+
+
 def _shape_arr(shape: Sequence[int]):
-    return (_c.c_int64 * len(shape))(*[int(v) for v in shape])
+    """int64[ndim] for the C side; the arrays of the shapes seen so far are kept (a call builds none)."""
+    key = tuple(shape)
+    arr = _SHAPES.get(key)
+    if arr is None:
+        arr = (_c.c_int64 * len(key))(*[int(v) for v in key])
+        if len(_SHAPES) < 256:
+            _SHAPES[key] = arr
+    return arr
+
+
+_torch_module = None
+_FTYPE_OF = {}       # torch dtype -> pbz_ftype
+_TORCH_FTYPE = {}    # pbz_ftype -> torch dtype
+_TORCH_ITYPE = {}    # pbz_itype -> torch dtype
 
 
 def _torch():
-    import torch
-    return torch
+    global _torch_module
+    if _torch_module is None:
+        import torch
+        _torch_module = torch
+        _FTYPE_OF.update({torch.float64: PBZ_F64, torch.float32: PBZ_F32, torch.bfloat16: PBZ_BF16,
+                          torch.float16: PBZ_F16})
+        _TORCH_FTYPE.update({v: k for k, v in _FTYPE_OF.items()})
+        _TORCH_ITYPE.update({PBZ_I8: torch.int8, PBZ_I16: torch.int16, PBZ_I32: torch.int32})
+    return _torch_module
 
 
 def _ftype_of(t) -> int:
-    torch = _torch()
-    return {torch.float64: PBZ_F64, torch.float32: PBZ_F32, torch.bfloat16: PBZ_BF16, torch.float16: PBZ_F16}[t.dtype]
+    _torch()
+    return _FTYPE_OF[t.dtype]
 
 
 def _torch_ftype(code: int):
-    torch = _torch()
-    return {PBZ_F64: torch.float64, PBZ_F32: torch.float32, PBZ_BF16: torch.bfloat16, PBZ_F16: torch.float16}[code]
+    _torch()
+    return _TORCH_FTYPE[code]
 
 
 def _torch_itype(code: int):
-    torch = _torch()
-    return {PBZ_I8: torch.int8, PBZ_I16: torch.int16, PBZ_I32: torch.int32}[code]
+    _torch()
+    return _TORCH_ITYPE[code]
 
 
 def _ptr(t) -> int:
