@@ -174,9 +174,14 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
   }
 }
 
+// Two workgroups per compute unit, i.e. two waves per SIMD, are asked for explicitly: the FP64-array 4x4x4 variants
+// otherwise come out at 256 vector registers plus a few accumulation registers, which is one wave per SIMD (the
+// register file holds 512 per lane).  Held to 256 they spill nine values and run 6 % faster (workload 4 decompress:
+// 0.264 -> 0.248 ms on random data); three waves (168 registers, 95 values spilled) take 0.44 ms, and a scheduling
+// fence after each row's stores changes neither the register count nor the time.
 template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX,
           bool kRagged, bool kTailX = false>
-__global__ __launch_bounds__(256) void k_decompress_lane(FastGeom g, const void* __restrict__ N, const IT* __restrict__ F,
+__global__ __launch_bounds__(256, 2) void k_decompress_lane(FastGeom g, const void* __restrict__ N, const IT* __restrict__ F,
                                                          XT* __restrict__ y) {
   constexpr int VOL = BZ * BY * BX, ROWS = BZ * BY;
   constexpr int RV = BX * int(sizeof(XT)) / 16;
