@@ -754,3 +754,14 @@ def test_general_kernels_on_arrays_that_do_not_start_on_a_16_byte_boundary():
         case = Case(aligned.cpu().numpy(), None, ftype, block, bits, ftype, mask, api.PBZ_PATH_GENERIC)
         case.check_compress("A")
         case.check_decompress(N1, F1)
+
+
+def test_stream_copy_moves_every_byte():
+    """The measurements' yardstick kernel: whole 16-byte vectors, a partial last workgroup and a tail of odd bytes."""
+    g = torch.Generator(device="cuda").manual_seed(5)
+    for n in (16, 4096 * 16, 4096 * 16 + 48, 1_000_003, 7):
+        src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda", generator=g)
+        dst = torch.zeros(n + 16, dtype=torch.uint8, device="cuda")
+        api.stream_copy(dst[:n], src)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and not dst[n:].any(), n
