@@ -68,88 +68,96 @@ template <> struct Bits<double> {
   static __device__ __forceinline__ double from(type b) { return __longlong_as_double((long long)b); }
 };
 
-constexpr int kMaxRows = 256;                 // rows (runs along the last dimension) of a block whose offsets are tabulated
-struct TileBlocks {                           // in LDS; all but row_off per tile
-  int64_t origin[kMaxTileBlocks];             // element offset of the block's first element; -1: no such block
-  int64_t row_off[kMaxRows];                  // offset of row i of a block from the block's first element (same for all blocks)
-  uint8_t lim[kMaxTileBlocks][PBZ_MAX_NDIM];  // how many entries (at most 32) along each dimension lie inside the array
-  uint8_t full[kMaxTileBlocks];               // the block lies wholly inside the array
+constexpr int kMaxRows = 256;                 // rows (runs along the last dimension) of a block whose place is tabulated
+
+// One byte per dimension (right-aligned: byte kDims - 1 belongs to the last one).  A block's `lim` holds how many
+// entries (0 .. 32) along each dimension lie inside the array; a position's `coord` holds 0x80 | coordinate
+// (0 .. 31).  Byte by byte, coord - lim = 128 + c - l lies in [96, 159], so nothing is borrowed across bytes, and
+// bit 7 of a byte is clear exactly when c < l: one subtraction tests all dimensions at once.
+template <int kDims> struct Packed;
+template <> struct Packed<4> { typedef uint32_t type; static constexpr uint32_t kHigh = 0x80808080u; };
+template <> struct Packed<8> { typedef uint64_t type; static constexpr uint64_t kHigh = 0x8080808080808080ull; };
+
+struct BlockInfo {                            // 16 bytes: one LDS read
+  int64_t origin;                             // element offset of the block's first element
+  uint64_t lim;                               // all zero: no such block (past the end of the array's blocks)
+};
+struct RowInfo {                              // 16 bytes: one LDS read
+  int64_t off;                                // offset of the row's first element from the block's first element
+  uint64_t coord;                             // the last dimension's byte holds 0x80: the caller adds the position in the row
+};
+struct TileBlocks {                           // in LDS; blk per tile, row once per kernel (same for all blocks)
+  BlockInfo blk[kMaxTileBlocks];
+  RowInfo row[kMaxRows];
 };
 constexpr int kBatch = 8;                     // global loads a thread keeps in flight while filling a tile
+
+template <int kDims>
+__device__ __forceinline__ bool inside(uint64_t lim, uint64_t coord) {
+  typedef typename Packed<kDims>::type packed_t;
+  return ((packed_t(coord) - packed_t(lim)) & Packed<kDims>::kHigh) == 0;
+}
 
 template <int kDims>
 __device__ __forceinline__ void decode_blocks(const TileGeom& tg, int64_t k0, TileBlocks* tb) {
   for (int b = threadIdx.x; b < tg.G; b += kThreads) {
     int64_t k = k0 + b;
-    if (k >= tg.n_blocks) {
-      tb->origin[b] = -1;
+    BlockInfo info;
+    info.origin = 0;
+    info.lim = 0;
+    if (k < tg.n_blocks) {
 #pragma unroll
-      for (int d = 0; d < kDims; ++d) tb->lim[b][d] = 0;
-      continue;
-    }
-    int64_t off = 0;
-    bool full = true;
-#pragma unroll
-    for (int d = PBZ_MAX_NDIM - 1; d >= PBZ_MAX_NDIM - kDims; --d) {
-      int64_t kb = 0;
-      if (tg.grid[d] > 1) {             // uniform: no division for the padded dimensions
-        kb = k % tg.grid[d];
-        k /= tg.grid[d];
+      for (int d = PBZ_MAX_NDIM - 1; d >= PBZ_MAX_NDIM - kDims; --d) {
+        int64_t kb = 0;
+        if (tg.grid[d] > 1) {             // uniform: no division for the padded dimensions
+          kb = k % tg.grid[d];
+          k /= tg.grid[d];
+        }
+        const int64_t c0 = kb << tg.bshift[d];
+        const int64_t left = tg.shape[d] - c0;
+        const int64_t extent = int64_t(1) << tg.bshift[d];
+        info.lim |= uint64_t(left < extent ? left : extent) << (8 * (d - (PBZ_MAX_NDIM - kDims)));
+        info.origin += c0 * tg.stride[d];
       }
-      const int64_t c0 = kb << tg.bshift[d];
-      const int64_t left = tg.shape[d] - c0;
-      const int64_t extent = int64_t(1) << tg.bshift[d];
-      tb->lim[b][d - (PBZ_MAX_NDIM - kDims)] = uint8_t(left < extent ? left : extent);
-      full = full && left >= extent;
-      off += c0 * tg.stride[d];
     }
-    tb->origin[b] = off;
-    tb->full[b] = full ? 1 : 0;
+    tb->blk[b] = info;
   }
 }
 
-// once per kernel: offsets of a block's rows relative to its first element
+// row i of a block (rows are numbered in the block's own row-major order)
+template <int kDims>
+__device__ __forceinline__ RowInfo row_info(const TileGeom& tg, int i) {
+  RowInfo r;
+  r.off = 0;
+  r.coord = Packed<kDims>::kHigh;
+#pragma unroll
+  for (int d = PBZ_MAX_NDIM - 2; d >= PBZ_MAX_NDIM - kDims; --d) {
+    const int jd = i & ((1 << tg.bshift[d]) - 1);
+    i >>= tg.bshift[d];
+    r.off += jd * tg.stride[d];
+    r.coord += uint64_t(jd) << (8 * (d - (PBZ_MAX_NDIM - kDims)));
+  }
+  return r;
+}
+
+// once per kernel
 template <int kDims>
 __device__ __forceinline__ void tabulate_rows(const TileGeom& tg, TileBlocks* tb) {
   const int rows = 1 << (tg.vol_shift - tg.bx_shift);
   if (rows > kMaxRows) return;
-  for (int i = threadIdx.x; i < rows; i += kThreads) {
-    int j = i;
-    int64_t off = 0;
-#pragma unroll
-    for (int d = PBZ_MAX_NDIM - 2; d >= PBZ_MAX_NDIM - kDims; --d) {
-      off += (j & ((1 << tg.bshift[d]) - 1)) * tg.stride[d];
-      j >>= tg.bshift[d];
-    }
-    tb->row_off[i] = off;
-  }
+  for (int i = threadIdx.x; i < rows; i += kThreads) tb->row[i] = row_info<kDims>(tg, i);
 }
 
-// intra-block index j of block b -> element offset; false when the element is padding
+// intra-block index j of block b -> element offset; false when the element is padding.  No branch: two 16-byte
+// LDS reads, one packed comparison.
 template <int kDims>
 __device__ __forceinline__ bool locate(const TileGeom& tg, const TileBlocks* tb, int b, int j, int64_t* offset) {
-  int64_t off = tb->origin[b];
-  bool in = off >= 0;
-  if ((1 << (tg.vol_shift - tg.bx_shift)) <= kMaxRows) {      // uniform: the usual case, rows tabulated
-    *offset = off + tb->row_off[j >> tg.bx_shift] + (j & ((1 << tg.bx_shift) - 1));   // the last dimension has stride 1
-    if (in && !tb->full[b]) {                                  // blocks on the array's edge: test every coordinate
-#pragma unroll
-      for (int d = PBZ_MAX_NDIM - 1; d >= PBZ_MAX_NDIM - kDims; --d) {
-        in = in && (j & ((1 << tg.bshift[d]) - 1)) < int(tb->lim[b][d - (PBZ_MAX_NDIM - kDims)]);
-        j >>= tg.bshift[d];
-      }
-    }
-    return in;
-  }
-#pragma unroll
-  for (int d = PBZ_MAX_NDIM - 1; d >= PBZ_MAX_NDIM - kDims; --d) {
-    const int jd = j & ((1 << tg.bshift[d]) - 1);
-    j >>= tg.bshift[d];
-    in = in && jd < int(tb->lim[b][d - (PBZ_MAX_NDIM - kDims)]);
-    off += jd * tg.stride[d];
-  }
-  *offset = off;
-  return in;
+  const int i = j >> tg.bx_shift, xin = j & ((1 << tg.bx_shift) - 1);
+  const bool tabulated = (1 << (tg.vol_shift - tg.bx_shift)) <= kMaxRows;     // uniform: the usual case
+  const RowInfo r = tabulated ? tb->row[i] : row_info<kDims>(tg, i);
+  const BlockInfo k = tb->blk[b];
+  *offset = k.origin + r.off + xin;                                            // the last dimension has stride 1
+  return inside<kDims>(k.lim, r.coord + (uint64_t(xin) << (8 * (kDims - 1))));
 }
 
 // memory-friendly enumeration of the tile: consecutive e walk along a row across the tile's blocks
@@ -386,12 +394,22 @@ __device__ __forceinline__ void bin_quads(const TileGeom& tg, const T* buf, cons
     const int e = q << 2;
     const int b = all_kept ? e >> tg.vol_shift : e / tg.kept;
     if (k0 + b >= tg.n_blocks) continue;
-    int j[4], idx[4];
-    kept_entries(all_kept, kept_list, e - b * tg.kept, j);
+    T c[4];
+    if (all_kept) {                  // position e of the tile's F is element e of the tile; four in a row share a group of 32
+      const T* src = buf + pad<T>(e);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) c[i] = src[i];
+    } else {
+      int j[4];
+      kept_entries(false, kept_list, e - b * tg.kept, j);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) c[i] = buf[pad<T>((b << tg.vol_shift) + j[i])];
+    }
+    int idx[4];
     const T nk = Bits<T>::from(bmax[b]), inv = binv[b];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const T a = r * buf[pad<T>((b << tg.vol_shift) + j[i])];
+      const T a = r * c[i];
       const T quo = a * inv;
       idx[i] = round_to_int(fma(fma(-quo, nk, a), inv, quo));
     }
@@ -421,11 +439,19 @@ __device__ __forceinline__ void scatter_quads(const TileGeom& tg, const IT* F, i
       if (q >= n_quads || q > last) continue;
       const int e = q << 2;
       const int b = all_kept ? e >> tg.vol_shift : e / tg.kept;
-      int j[4], f[4];
-      kept_entries(all_kept, kept_list, e - b * tg.kept, j);
+      int f[4];
       Quad<IT>::unpack(raw[u], f);
+      const T scale = bn[b];
+      if (all_kept) {
+        T* dst = buf + pad<T>(e);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) buf[pad<T>((b << tg.vol_shift) + j[i])] = bn[b] * T(f[i]);
+        for (int i = 0; i < 4; ++i) dst[i] = scale * T(f[i]);
+      } else {
+        int j[4];
+        kept_entries(false, kept_list, e - b * tg.kept, j);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) buf[pad<T>((b << tg.vol_shift) + j[i])] = scale * T(f[i]);
+      }
     }
   }
 }
@@ -439,13 +465,16 @@ __device__ __forceinline__ void pass_n(T* buf, int total, int n_shift, int inner
   const int inner = 1 << inner_shift;
   for (int l = threadIdx.x; l < lines; l += kThreads) {
     const int base = ((l >> inner_shift) << (n_shift + inner_shift)) + (l & (inner - 1));
+    // pad(base + a * inner) = pad(base) + pad(a * inner): the line starts at a multiple of its span or, when that
+    // span is below 32, stays inside one group of 32; the second term is the same for all threads (scalar unit)
+    T* line = buf + pad<T>(base);
     T v[n];
 #pragma unroll
-    for (int a = 0; a < n; ++a) v[a] = buf[pad<T>(base + (a << inner_shift))];
+    for (int a = 0; a < n; ++a) v[a] = line[pad<T>(a << inner_shift)];
     if (kForward) tf_forward<kTf, T, n, 1>(v);
     else tf_inverse<kTf, T, n, 1, n>(v);
 #pragma unroll
-    for (int a = 0; a < n; ++a) buf[pad<T>(base + (a << inner_shift))] = v[a];
+    for (int a = 0; a < n; ++a) line[pad<T>(a << inner_shift)] = v[a];
     if constexpr (kMax) {
       T m = fabs(v[0]);
 #pragma unroll
@@ -455,7 +484,8 @@ __device__ __forceinline__ void pass_n(T* buf, int total, int n_shift, int inner
   }
 }
 
-// forward: bmax != nullptr asks for the per-block maxima, taken in the last pass that has work to do
+// forward: bmax != nullptr asks for the per-block maxima, taken in the last pass that has work to do.  The loop over
+// the dimensions is kept a loop (one copy of each pass per kernel instead of one per dimension).
 template <int kDims, typename T, int kTf, bool kForward>
 __device__ __forceinline__ void transform_tile(const TileGeom& tg, T* buf, int total,
                                                typename Bits<T>::type* bmax = nullptr) {
@@ -464,7 +494,7 @@ __device__ __forceinline__ void transform_tile(const TileGeom& tg, T* buf, int t
   for (int d = PBZ_MAX_NDIM - kDims; d < PBZ_MAX_NDIM; ++d)
     if (tg.bshift[d] > 0) last = d;
   int inner_shift = tg.vol_shift;
-#pragma unroll
+#pragma nounroll
   for (int d = PBZ_MAX_NDIM - kDims; d < PBZ_MAX_NDIM; ++d) {
     const int ns = tg.bshift[d];
     inner_shift -= ns;
@@ -502,12 +532,12 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
   bits_t* bmax = reinterpret_cast<bits_t*>(smem + sizeof(TileBlocks));
   T* binv = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + sizeof(unsigned long long) * kMaxTileBlocks);
   T* buf = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks);
-  const int64_t n_tiles = (tg.n_blocks + tg.G - 1) >> tg.g_shift;
   const int vol = 1 << tg.vol_shift;
-
-  tabulate_rows<kDims>(tg, tb);
-  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    const int64_t k0 = tile << tg.g_shift;
+  // one tile per workgroup, so that what the decode below needs of the geometry is dead before the loops start
+  const int64_t k0 = (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) << tg.g_shift;
+  if (k0 >= tg.n_blocks) return;               // uniform over the workgroup
+  {
+    tabulate_rows<kDims>(tg, tb);
     decode_blocks<kDims>(tg, k0, tb);
     for (int b = threadIdx.x; b < tg.G; b += kThreads) bmax[b] = 0;
     __syncthreads();
@@ -571,7 +601,6 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
         store_index(F, itype, k0 * tg.kept + e0 + u * kThreads, int64_t(t));
       }
     }
-    __syncthreads();
   }
 }
 
@@ -612,12 +641,11 @@ __global__ __launch_bounds__(kThreads) void k_decompress_tiled(TileGeom tg, cons
   TileBlocks* tb = reinterpret_cast<TileBlocks*>(smem);
   T* bn = reinterpret_cast<T*>(smem + sizeof(TileBlocks));
   T* buf = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks);
-  const int64_t n_tiles = (tg.n_blocks + tg.G - 1) >> tg.g_shift;
   const int vol = 1 << tg.vol_shift;
-
-  tabulate_rows<kDims>(tg, tb);
-  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    const int64_t k0 = tile << tg.g_shift;
+  const int64_t k0 = (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) << tg.g_shift;   // one tile per workgroup
+  if (k0 >= tg.n_blocks) return;               // uniform over the workgroup
+  {
+    tabulate_rows<kDims>(tg, tb);
     decode_blocks<kDims>(tg, k0, tb);
     for (int b = threadIdx.x; b < tg.G; b += kThreads)      // blocks past the end: the last one again, never stored
       bn[b] = load_float<T>(N, ntype, k0 + b < tg.n_blocks ? k0 + b : tg.n_blocks - 1) / T(r);   // N / r once per block
@@ -655,7 +683,6 @@ __global__ __launch_bounds__(kThreads) void k_decompress_tiled(TileGeom tg, cons
         default: store_tile_f16<kDims, T>(tg, tb, static_cast<_Float16*>(y), buf, total); break;
       }
     }
-    __syncthreads();
   }
 }
 
@@ -703,9 +730,11 @@ size_t tile_lds_bytes(const TileGeom& tg, size_t elem) {
   return sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks + elem * size_t(total + (total >> 5) + 1);
 }
 
-int tile_grid(int64_t n_tiles) {
+// one workgroup per tile: x up to 2^20, the rest in y (at most 2^40 elements in tiles of 256 or more: y <= 4096)
+dim3 tile_grid(int64_t n_tiles) {
   const int64_t cap = int64_t(1) << 20;
-  return int(n_tiles < cap ? n_tiles : cap);
+  if (n_tiles <= cap) return dim3(unsigned(n_tiles));
+  return dim3(unsigned(cap), unsigned((n_tiles + cap - 1) / cap));
 }
 
 }  // namespace
@@ -721,7 +750,7 @@ int launch_compress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables*
   TileGeom tg = make_tile(c, g);
   choose_units(c, g, x, xtype, F, &tg);
   const int64_t n_tiles = (tg.n_blocks + tg.G - 1) / tg.G;
-  const dim3 grid(tile_grid(n_tiles)), block(kThreads);
+  const dim3 grid = tile_grid(n_tiles), block(kThreads);
 #define PBZ_TILED(T, TF)                                                                                              \
   do {                                                                                                                \
     if (tg.dims == 4)                                                                                                 \
@@ -747,7 +776,7 @@ int launch_decompress_tiled(const pbz_codec* c, const Geom& g, const DeviceTable
   TileGeom tg = make_tile(c, g);
   choose_units(c, g, y, ytype, F, &tg);
   const int64_t n_tiles = (tg.n_blocks + tg.G - 1) / tg.G;
-  const dim3 grid(tile_grid(n_tiles)), block(kThreads);
+  const dim3 grid = tile_grid(n_tiles), block(kThreads);
 #define PBZ_TILED(T, TF)                                                                                              \
   do {                                                                                                                \
     if (tg.dims == 4)                                                                                                 \

@@ -114,6 +114,10 @@ RAGGED = [((37, 53), (8, 8), 8, "f32", "f32", None),
           ((5, 6, 7, 9), (2, 2, 4, 2), 16, "f64", "f64", None),
           ((9, 40, 40), (4, 16, 16), 8, "f32", "f32", None),       # non-hypercubic block
           ((70, 70), (16, 4), 32, "f64", "f64", None),             # int32 indices
+          ((40, 33, 3), (32, 16, 2), 8, "f32", "f32", None),       # 512 rows per block: more than the row table holds
+          ((33, 40, 2), (32, 32, 1), 16, "f64", "f64", None),      # 1024 rows of one element
+          ((3, 2, 3, 2, 5, 3, 6, 9), (2, 1, 2, 2, 4, 1, 2, 8), 16, "f32", "f32", None),   # eight dimensions
+          ((3, 2, 2, 2, 2, 2, 3, 38), (2, 2, 2, 2, 2, 2, 2, 4), 8, "f64", "f64", None),   # 128 rows of four, ragged
           ((40, 40), (8, 8), 8, "f16", "f16", None),               # 16-bit working types
           ((40, 40), (8, 8), 8, "f32", "bf16", None)]
 
