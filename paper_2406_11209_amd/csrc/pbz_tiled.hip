@@ -86,10 +86,23 @@ struct RowInfo {                              // 16 bytes: one LDS read
   int64_t off;                                // offset of the row's first element from the block's first element
   uint64_t coord;                             // the last dimension's byte holds 0x80: the caller adds the position in the row
 };
-struct TileBlocks {                           // in LDS; blk per tile, row once per kernel (same for all blocks)
-  BlockInfo blk[kMaxTileBlocks];
-  RowInfo row[kMaxRows];
+struct TileBlocks {                           // both in LDS, sized by the tile: G blocks, the rows of one block
+  BlockInfo* blk;
+  RowInfo* row;                               // filled when a block has at most kMaxRows rows
 };
+
+// The workgroup's LDS: G block records, the row records, 16 bytes per block for the kernels' own per-block
+// values (maxima and reciprocals, or N / r), then the padded tile.
+__device__ __host__ inline int tabulated_rows(int vol_shift, int bx_shift) {
+  const int rows = 1 << (vol_shift - bx_shift);
+  return rows <= kMaxRows ? rows : 0;
+}
+__device__ __host__ inline size_t per_block_offset(int G, int vol_shift, int bx_shift) {
+  return 16 * size_t(G + tabulated_rows(vol_shift, bx_shift));
+}
+__device__ __host__ inline size_t tile_offset(int G, int vol_shift, int bx_shift) {
+  return per_block_offset(G, vol_shift, bx_shift) + 16 * size_t(G);
+}
 constexpr int kBatch = 8;                     // global loads a thread keeps in flight while filling a tile
 
 template <int kDims>
@@ -99,7 +112,7 @@ __device__ __forceinline__ bool inside(uint64_t lim, uint64_t coord) {
 }
 
 template <int kDims>
-__device__ __forceinline__ void decode_blocks(const TileGeom& tg, int64_t k0, TileBlocks* tb) {
+__device__ __forceinline__ void decode_blocks(const TileGeom& tg, int64_t k0, const TileBlocks& tb) {
   for (int b = threadIdx.x; b < tg.G; b += kThreads) {
     int64_t k = k0 + b;
     BlockInfo info;
@@ -120,7 +133,7 @@ __device__ __forceinline__ void decode_blocks(const TileGeom& tg, int64_t k0, Ti
         info.origin += c0 * tg.stride[d];
       }
     }
-    tb->blk[b] = info;
+    tb.blk[b] = info;
   }
 }
 
@@ -142,20 +155,20 @@ __device__ __forceinline__ RowInfo row_info(const TileGeom& tg, int i) {
 
 // once per kernel
 template <int kDims>
-__device__ __forceinline__ void tabulate_rows(const TileGeom& tg, TileBlocks* tb) {
+__device__ __forceinline__ void tabulate_rows(const TileGeom& tg, const TileBlocks& tb) {
   const int rows = 1 << (tg.vol_shift - tg.bx_shift);
   if (rows > kMaxRows) return;
-  for (int i = threadIdx.x; i < rows; i += kThreads) tb->row[i] = row_info<kDims>(tg, i);
+  for (int i = threadIdx.x; i < rows; i += kThreads) tb.row[i] = row_info<kDims>(tg, i);
 }
 
 // intra-block index j of block b -> element offset; false when the element is padding.  No branch: two 16-byte
 // LDS reads, one packed comparison.
 template <int kDims>
-__device__ __forceinline__ bool locate(const TileGeom& tg, const TileBlocks* tb, int b, int j, int64_t* offset) {
+__device__ __forceinline__ bool locate(const TileGeom& tg, const TileBlocks& tb, int b, int j, int64_t* offset) {
   const int i = j >> tg.bx_shift, xin = j & ((1 << tg.bx_shift) - 1);
   const bool tabulated = (1 << (tg.vol_shift - tg.bx_shift)) <= kMaxRows;     // uniform: the usual case
-  const RowInfo r = tabulated ? tb->row[i] : row_info<kDims>(tg, i);
-  const BlockInfo k = tb->blk[b];
+  const RowInfo r = tabulated ? tb.row[i] : row_info<kDims>(tg, i);
+  const BlockInfo k = tb.blk[b];
   *offset = k.origin + r.off + xin;                                            // the last dimension has stride 1
   return inside<kDims>(k.lim, r.coord + (uint64_t(xin) << (8 * (kDims - 1))));
 }
@@ -177,7 +190,7 @@ __device__ __forceinline__ T widen_bf16(bf16_raw raw) { return T(bf16_bits_to_fl
 // kBatch loads are issued before the first of them is used; padding gets zeros (the load then reads element 0:
 // never a branch around a load)
 template <int kDims, typename T, typename XT, bool kBf16>
-__device__ __forceinline__ void load_tile(const TileGeom& tg, const TileBlocks* tb, const XT* x, T* buf,
+__device__ __forceinline__ void load_tile(const TileGeom& tg, const TileBlocks& tb, const XT* x, T* buf,
                                           int total) {
   for (int e0 = threadIdx.x; e0 < total; e0 += kThreads * kBatch) {
     XT raw[kBatch];
@@ -205,7 +218,7 @@ __device__ __forceinline__ void load_tile(const TileGeom& tg, const TileBlocks* 
 }
 
 template <int kDims, typename T, typename XT>
-__device__ __forceinline__ void store_tile(const TileGeom& tg, const TileBlocks* tb, XT* y, const T* buf,
+__device__ __forceinline__ void store_tile(const TileGeom& tg, const TileBlocks& tb, XT* y, const T* buf,
                                            int total) {
   for (int e = threadIdx.x; e < total; e += kThreads) {
     int b, j;
@@ -216,7 +229,7 @@ __device__ __forceinline__ void store_tile(const TileGeom& tg, const TileBlocks*
 }
 
 template <int kDims, typename T>
-__device__ __forceinline__ void store_tile_bf16(const TileGeom& tg, const TileBlocks* tb, uint16_t* y,
+__device__ __forceinline__ void store_tile_bf16(const TileGeom& tg, const TileBlocks& tb, uint16_t* y,
                                                 const T* buf, int total) {
   for (int e = threadIdx.x; e < total; e += kThreads) {
     int b, j;
@@ -229,7 +242,7 @@ __device__ __forceinline__ void store_tile_bf16(const TileGeom& tg, const TileBl
   }
 }
 template <int kDims, typename T>
-__device__ __forceinline__ void store_tile_f16(const TileGeom& tg, const TileBlocks* tb, _Float16* y,
+__device__ __forceinline__ void store_tile_f16(const TileGeom& tg, const TileBlocks& tb, _Float16* y,
                                                const T* buf, int total) {
   for (int e = threadIdx.x; e < total; e += kThreads) {
     int b, j;
@@ -286,7 +299,7 @@ __device__ __forceinline__ void piece_across_blocks(const TileGeom& tg, int p, i
 constexpr int kPieceBatch = 4;                // 16-byte loads a thread keeps in flight while filling a tile
 
 template <int kDims, typename T, typename XT>
-__device__ __forceinline__ void load_tile_pieces(const TileGeom& tg, const TileBlocks* tb, const XT* x, T* buf,
+__device__ __forceinline__ void load_tile_pieces(const TileGeom& tg, const TileBlocks& tb, const XT* x, T* buf,
                                                  int total) {
   constexpr int P = 16 / int(sizeof(XT));
   const int n_pieces = total / P;
@@ -316,7 +329,7 @@ __device__ __forceinline__ void load_tile_pieces(const TileGeom& tg, const TileB
 }
 
 template <int kDims, typename T, typename XT>
-__device__ __forceinline__ void store_tile_pieces(const TileGeom& tg, const TileBlocks* tb, XT* y, const T* buf,
+__device__ __forceinline__ void store_tile_pieces(const TileGeom& tg, const TileBlocks& tb, XT* y, const T* buf,
                                                   int total) {
   constexpr int P = 16 / int(sizeof(XT));
   const int n_pieces = total / P;
@@ -479,14 +492,23 @@ __device__ __forceinline__ void pass_n(T* buf, int total, int n_shift, int inner
       T m = fabs(v[0]);
 #pragma unroll
       for (int a = 1; a < n; ++a) m = fmax(m, fabs(v[a]));
-      atomicMax(&bmax[base >> vol_shift], Bits<T>::of(m));
+      // Consecutive lines belong to one block in runs of (lines per block), a power of two, so the lanes of a wave
+      // that share a block are an aligned group: they combine by lane exchanges and one of them does the atomic
+      // (64 lanes on one address would be served one after the other).  A group is active or idle as a whole:
+      // the number of lines is a multiple of the run.
+      const int run = 1 << (vol_shift - n_shift);
+      const int group = run < 64 ? run : 64;
+      for (int step = 1; step < group; step <<= 1) m = fmax(m, __shfl_xor(m, step));
+      if ((threadIdx.x & (group - 1)) == 0) atomicMax(&bmax[base >> vol_shift], Bits<T>::of(m));
     }
   }
 }
 
 // forward: bmax != nullptr asks for the per-block maxima, taken in the last pass that has work to do.  The loop over
-// the dimensions is kept a loop (one copy of each pass per kernel instead of one per dimension).
-template <int kDims, typename T, int kTf, bool kForward>
+// the dimensions is kept a loop (one copy of each pass per kernel instead of one per dimension).  kMaxShift: log2 of
+// the longest line the kernel is built for (the passes for longer lines set the kernel's register count: 64 values
+// per thread for a line of 32 in FP64).
+template <int kDims, typename T, int kTf, bool kForward, int kMaxShift>
 __device__ __forceinline__ void transform_tile(const TileGeom& tg, T* buf, int total,
                                                typename Bits<T>::type* bmax = nullptr) {
   int last = -1;
@@ -504,23 +526,31 @@ __device__ __forceinline__ void transform_tile(const TileGeom& tg, T* buf, int t
         case 1: pass_n<T, kTf, 2, kForward, true>(buf, total, 1, inner_shift, bmax, tg.vol_shift); break;
         case 2: pass_n<T, kTf, 4, kForward, true>(buf, total, 2, inner_shift, bmax, tg.vol_shift); break;
         case 3: pass_n<T, kTf, 8, kForward, true>(buf, total, 3, inner_shift, bmax, tg.vol_shift); break;
-        case 4: pass_n<T, kTf, 16, kForward, true>(buf, total, 4, inner_shift, bmax, tg.vol_shift); break;
-        default: pass_n<T, kTf, 32, kForward, true>(buf, total, 5, inner_shift, bmax, tg.vol_shift); break;
+        case 4:
+          if constexpr (kMaxShift >= 4) pass_n<T, kTf, 16, kForward, true>(buf, total, 4, inner_shift, bmax, tg.vol_shift);
+          break;
+        default:
+          if constexpr (kMaxShift >= 5) pass_n<T, kTf, 32, kForward, true>(buf, total, 5, inner_shift, bmax, tg.vol_shift);
+          break;
       }
     } else {
       switch (ns) {
         case 1: pass_n<T, kTf, 2, kForward>(buf, total, 1, inner_shift); break;
         case 2: pass_n<T, kTf, 4, kForward>(buf, total, 2, inner_shift); break;
         case 3: pass_n<T, kTf, 8, kForward>(buf, total, 3, inner_shift); break;
-        case 4: pass_n<T, kTf, 16, kForward>(buf, total, 4, inner_shift); break;
-        default: pass_n<T, kTf, 32, kForward>(buf, total, 5, inner_shift); break;
+        case 4:
+          if constexpr (kMaxShift >= 4) pass_n<T, kTf, 16, kForward>(buf, total, 4, inner_shift);
+          break;
+        default:
+          if constexpr (kMaxShift >= 5) pass_n<T, kTf, 32, kForward>(buf, total, 5, inner_shift);
+          break;
       }
     }
     __syncthreads();
   }
 }
 
-template <int kDims, typename T, int kTf>
+template <int kDims, typename T, int kTf, int kMaxShift>
 __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const void* __restrict__ x, int xtype,
                                                              void* __restrict__ N, int ntype, void* __restrict__ F,
                                                              int itype, double r,
@@ -528,10 +558,13 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
   extern __shared__ __align__(16) unsigned char smem[];
   typedef typename Bits<T>::type bits_t;
   const int total = tg.G << tg.vol_shift;
-  TileBlocks* tb = reinterpret_cast<TileBlocks*>(smem);
-  bits_t* bmax = reinterpret_cast<bits_t*>(smem + sizeof(TileBlocks));
-  T* binv = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + sizeof(unsigned long long) * kMaxTileBlocks);
-  T* buf = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks);
+  TileBlocks tb;
+  tb.blk = reinterpret_cast<BlockInfo*>(smem);
+  tb.row = reinterpret_cast<RowInfo*>(smem + 16 * tg.G);
+  unsigned char* per_block = smem + per_block_offset(tg.G, tg.vol_shift, tg.bx_shift);
+  bits_t* bmax = reinterpret_cast<bits_t*>(per_block);
+  T* binv = reinterpret_cast<T*>(per_block + 8 * tg.G);
+  T* buf = reinterpret_cast<T*>(smem + tile_offset(tg.G, tg.vol_shift, tg.bx_shift));
   const int vol = 1 << tg.vol_shift;
   // one tile per workgroup, so that what the decode below needs of the geometry is dead before the loops start
   const int64_t k0 = (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) << tg.g_shift;
@@ -557,7 +590,7 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
       }
     }
     __syncthreads();
-    transform_tile<kDims, T, kTf, true>(tg, buf, total, bmax);      // leaves N_k = max |C_k| in bmax
+    transform_tile<kDims, T, kTf, true, kMaxShift>(tg, buf, total, bmax);      // leaves N_k = max |C_k| in bmax
     if (vol == 1) {                        // single-element blocks: nothing was transformed
       for (int e = threadIdx.x; e < total; e += kThreads) bmax[e] = Bits<T>::of(fabs(buf[pad<T>(e)]));
       __syncthreads();
@@ -631,16 +664,18 @@ __device__ __forceinline__ void scatter_coefficients(const TileGeom& tg, const I
   }
 }
 
-template <int kDims, typename T, int kTf>
+template <int kDims, typename T, int kTf, int kMaxShift>
 __global__ __launch_bounds__(kThreads) void k_decompress_tiled(TileGeom tg, const void* __restrict__ N, int ntype,
                                                                const void* __restrict__ F, int itype, double r,
                                                                void* __restrict__ y, int ytype,
                                                                const int32_t* __restrict__ kept_list) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int total = tg.G << tg.vol_shift;
-  TileBlocks* tb = reinterpret_cast<TileBlocks*>(smem);
-  T* bn = reinterpret_cast<T*>(smem + sizeof(TileBlocks));
-  T* buf = reinterpret_cast<T*>(smem + sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks);
+  TileBlocks tb;
+  tb.blk = reinterpret_cast<BlockInfo*>(smem);
+  tb.row = reinterpret_cast<RowInfo*>(smem + 16 * tg.G);
+  T* bn = reinterpret_cast<T*>(smem + per_block_offset(tg.G, tg.vol_shift, tg.bx_shift));
+  T* buf = reinterpret_cast<T*>(smem + tile_offset(tg.G, tg.vol_shift, tg.bx_shift));
   const int vol = 1 << tg.vol_shift;
   const int64_t k0 = (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) << tg.g_shift;   // one tile per workgroup
   if (k0 >= tg.n_blocks) return;               // uniform over the workgroup
@@ -667,7 +702,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress_tiled(TileGeom tg, cons
       }
     }
     __syncthreads();
-    transform_tile<kDims, T, kTf, false>(tg, buf, total);
+    transform_tile<kDims, T, kTf, false, kMaxShift>(tg, buf, total);
     if (tg.vec_x) {
       switch (ytype) {
         case PBZ_F64: store_tile_pieces<kDims, T, double>(tg, tb, static_cast<double*>(y), buf, total); break;
@@ -727,7 +762,7 @@ void choose_units(const pbz_codec* c, const Geom& g, const void* array, int arra
 
 size_t tile_lds_bytes(const TileGeom& tg, size_t elem) {
   const int total = tg.G << tg.vol_shift;
-  return sizeof(TileBlocks) + 2 * sizeof(unsigned long long) * kMaxTileBlocks + elem * size_t(total + (total >> 5) + 1);
+  return tile_offset(tg.G, tg.vol_shift, tg.bx_shift) + elem * size_t(total + (total >> 5) + 1);
 }
 
 // one workgroup per tile: x up to 2^20, the rest in y (at most 2^40 elements in tiles of 256 or more: y <= 4096)
@@ -751,14 +786,22 @@ int launch_compress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables*
   choose_units(c, g, x, xtype, F, &tg);
   const int64_t n_tiles = (tg.n_blocks + tg.G - 1) / tg.G;
   const dim3 grid = tile_grid(n_tiles), block(kThreads);
-#define PBZ_TILED(T, TF)                                                                                              \
+  int max_shift = 0;                               // log2 of the longest line
+  for (int d = 0; d < PBZ_MAX_NDIM; ++d) max_shift = tg.bshift[d] > max_shift ? tg.bshift[d] : max_shift;
+#define PBZ_TILED_M(T, TF, M)                                                                                         \
   do {                                                                                                                \
     if (tg.dims == 4)                                                                                                 \
-      hipLaunchKernelGGL((k_compress_tiled<4, T, TF>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, x, xtype, N,  \
-                         int(c->ftype), F, int(c->itype), c->r, t->kept_list);                                        \
+      hipLaunchKernelGGL((k_compress_tiled<4, T, TF, M>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, x, xtype, \
+                         N, int(c->ftype), F, int(c->itype), c->r, t->kept_list);                                     \
     else                                                                                                              \
-      hipLaunchKernelGGL((k_compress_tiled<8, T, TF>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, x, xtype, N,  \
-                         int(c->ftype), F, int(c->itype), c->r, t->kept_list);                                        \
+      hipLaunchKernelGGL((k_compress_tiled<8, T, TF, M>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, x, xtype, \
+                         N, int(c->ftype), F, int(c->itype), c->r, t->kept_list);                                     \
+  } while (0)
+#define PBZ_TILED(T, TF)                                                                                              \
+  do {                                                                                                                \
+    if (max_shift <= 3) PBZ_TILED_M(T, TF, 3);                                                                        \
+    else if (max_shift == 4) PBZ_TILED_M(T, TF, 4);                                                                   \
+    else PBZ_TILED_M(T, TF, 5);                                                                                       \
   } while (0)
   if (c->compute_f64) {
     if (c->transform == PBZ_TRANSFORM_HAAR) PBZ_TILED(double, kTfHaar);
@@ -768,6 +811,7 @@ int launch_compress_tiled(const pbz_codec* c, const Geom& g, const DeviceTables*
     else PBZ_TILED(float, kTfDct);
   }
 #undef PBZ_TILED
+#undef PBZ_TILED_M
   return hip_status(hipGetLastError());
 }
 
@@ -777,14 +821,22 @@ int launch_decompress_tiled(const pbz_codec* c, const Geom& g, const DeviceTable
   choose_units(c, g, y, ytype, F, &tg);
   const int64_t n_tiles = (tg.n_blocks + tg.G - 1) / tg.G;
   const dim3 grid = tile_grid(n_tiles), block(kThreads);
-#define PBZ_TILED(T, TF)                                                                                              \
+  int max_shift = 0;                               // log2 of the longest line
+  for (int d = 0; d < PBZ_MAX_NDIM; ++d) max_shift = tg.bshift[d] > max_shift ? tg.bshift[d] : max_shift;
+#define PBZ_TILED_M(T, TF, M)                                                                                         \
   do {                                                                                                                \
     if (tg.dims == 4)                                                                                                 \
-      hipLaunchKernelGGL((k_decompress_tiled<4, T, TF>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, N,          \
+      hipLaunchKernelGGL((k_decompress_tiled<4, T, TF, M>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, N,      \
                          int(c->ftype), F, int(c->itype), c->r, y, ytype, t->kept_list);                              \
     else                                                                                                              \
-      hipLaunchKernelGGL((k_decompress_tiled<8, T, TF>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, N,          \
+      hipLaunchKernelGGL((k_decompress_tiled<8, T, TF, M>), grid, block, tile_lds_bytes(tg, sizeof(T)), s, tg, N,      \
                          int(c->ftype), F, int(c->itype), c->r, y, ytype, t->kept_list);                              \
+  } while (0)
+#define PBZ_TILED(T, TF)                                                                                              \
+  do {                                                                                                                \
+    if (max_shift <= 3) PBZ_TILED_M(T, TF, 3);                                                                        \
+    else if (max_shift == 4) PBZ_TILED_M(T, TF, 4);                                                                   \
+    else PBZ_TILED_M(T, TF, 5);                                                                                       \
   } while (0)
   if (c->compute_f64) {
     if (c->transform == PBZ_TRANSFORM_HAAR) PBZ_TILED(double, kTfHaar);
@@ -794,6 +846,7 @@ int launch_decompress_tiled(const pbz_codec* c, const Geom& g, const DeviceTable
     else PBZ_TILED(float, kTfDct);
   }
 #undef PBZ_TILED
+#undef PBZ_TILED_M
   return hip_status(hipGetLastError());
 }
 
