@@ -12,13 +12,19 @@
 //            I = rint(r C / N_k) for the kept entries only, enumerated in F order: the tile's part of F is one
 //            contiguous run.
 // Wherever the layout allows it the array and F are moved in wider units than one element, so that the index
-// arithmetic (what these kernels spend most of their instructions on) is done once per unit: 16-byte pieces of the
-// array when a block row holds at least one, rows start on 16-byte boundaries and the last extent is a multiple of
-// the piece (a piece then lies wholly inside one block row and wholly inside or outside the array), and runs of four
-// kept entries of F when the kept count is a multiple of four.  512 x 512 x 256 FP64 in 8 x 8 x 8 blocks, int16:
-// 168 vector instructions per element and 1.1 TB/s moved with element-wise accesses, 119 and 2.0-2.2 TB/s this way;
-// with the transform passes taken out the same kernel moves 3.8 TB/s, so what bounds it now are the passes (LDS
-// round trips and barriers as much as their arithmetic), no longer the index arithmetic of the loads and stores.
+// arithmetic is done once per unit: 16-byte pieces of the array when a block row holds at least one, rows start on
+// 16-byte boundaries and the last extent is a multiple of the piece (a piece then lies wholly inside one block row
+// and wholly inside or outside the array), and runs of four kept entries of F when the kept count is a multiple of
+// four.  Finding an element costs two 16-byte LDS reads (the block's record, the row's record) and one packed
+// comparison that tests all dimensions' bounds at once; no branch.  A workgroup takes exactly one tile, so what
+// the block decode needs of the geometry is dead before the loops start (with a loop over tiles the compiler kept
+// all of it live and spilled scalar registers into vector lanes inside the hottest loops), the loop over the
+// dimensions is a real loop (one copy of each pass), and the kernels are built per longest line (8, 16, 32), because
+// the pass for a line of 32 FP64 values alone needs 150 registers, the others 42-77.
+// 512 x 512 x 256 FP64 in 8 x 8 x 8 blocks, int16: 168 vector instructions per element and 1.1 TB/s moved with
+// element-wise accesses, 119 and 2.0-2.2 TB/s with pieces, 58 and 3.2 TB/s as described here.  Taking out
+// one part at a time (compress, that case, 0.208 ms): without the passes 0.131 ms, without the array loads
+// 0.166 ms, without binning and stores 0.178 ms, with none of them 0.037 ms (launch, block decode, N).
 // Decompression mirrors this.  The block -> coordinates decode (divisions by the grid extents) happens once per
 // block per tile; the per-element decode is shifts and masks because block extents are powers of two.
 #include <type_traits>
@@ -302,13 +308,15 @@ template <int kDims, typename T, typename XT>
 __device__ __forceinline__ void load_tile_pieces(const TileGeom& tg, const TileBlocks& tb, const XT* x, T* buf,
                                                  int total) {
   constexpr int P = 16 / int(sizeof(XT));
+  // a thread's share of a 4096-element tile is 16 elements: all of its pieces are requested before the first is used
+  constexpr int kInFlight = sizeof(XT) == 8 ? 8 : kPieceBatch;
   const int n_pieces = total / P;
-  for (int p0 = threadIdx.x; p0 < n_pieces; p0 += kThreads * kPieceBatch) {
-    uint4 raw[kPieceBatch];
-    int slot[kPieceBatch];
-    bool in[kPieceBatch];
+  for (int p0 = threadIdx.x; p0 < n_pieces; p0 += kThreads * kInFlight) {
+    uint4 raw[kInFlight];
+    int slot[kInFlight];
+    bool in[kInFlight];
 #pragma unroll
-    for (int u = 0; u < kPieceBatch; ++u) {
+    for (int u = 0; u < kInFlight; ++u) {
       const int p = p0 + u * kThreads;
       int b, j;
       piece_across_blocks<P>(tg, p < n_pieces ? p : 0, &b, &j);
@@ -318,7 +326,7 @@ __device__ __forceinline__ void load_tile_pieces(const TileGeom& tg, const TileB
       raw[u] = *reinterpret_cast<const uint4*>(x + (in[u] ? off : 0));
     }
 #pragma unroll
-    for (int u = 0; u < kPieceBatch; ++u) {
+    for (int u = 0; u < kInFlight; ++u) {
       if (slot[u] < 0) continue;
       T v[P];
       unpack_piece<T, XT>(raw[u], v);
