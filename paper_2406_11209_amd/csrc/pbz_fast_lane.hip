@@ -242,8 +242,11 @@ __global__ __launch_bounds__(256, 2) void k_decompress_lane(FastGeom g, const vo
           // A block row is two 16-byte pieces, so a plain store instruction would write every other piece of a
           // 2 KiB span.  The two half-waves trade pieces instead (lanes 32-63 hand the first piece of their row
           // to lanes 0-31 and take those lanes' second piece): the first store then writes the rows of blocks
-          // 0-31 as one contiguous KiB, the second those of blocks 32-63 (workload 4: 0.251 -> 0.240 ms; with
-          // the non-temporal hint on top: 0.255 ms).  The compiler hoists every row's trade above the first store
+          // 0-31 as one contiguous KiB, the second those of blocks 32-63 (workload 4: 0.251 -> 0.240 ms).  Whole
+          // KiB per instruction is also what the non-temporal hint needs (back-to-back repeats of workload 4:
+          // 0.248 -> 0.238 ms; inside the benchmark step the kernel itself shows 0.254 ms, because it now waits
+          // for its own writes, and the negate after it 0.090 instead of 0.111 ms; the step is 15 us shorter).
+          // The compiler hoists every row's trade above the first store
           // (256 registers, two waves per SIMD): running the last transform pass row by row just before each
           // row's stores brought that to 160 registers and three waves, and was slower (0.252 ms): a wave's
           // 32 stores leaving back to back matter more than the third wave.
@@ -254,25 +257,29 @@ __global__ __launch_bounds__(256, 2) void k_decompress_lane(FastGeom g, const vo
           swap_half_waves(h0.z, h1.z);
           swap_half_waves(h0.w, h1.w);
           uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 2 * (lane & 31) + (lane >> 5);
-          p[0] = h0;
-          p[64] = h1;
+          store16_stream(p, h0);
+          store16_stream(p + 64, h1);
         } else if (RV == 4 && whole_wave) {
           // four pieces per block row: after the quarter transpose store j writes the rows of blocks
-          // 16j .. 16j+15 as one contiguous KiB
+          // 16j .. 16j+15 as one contiguous KiB (8192^2 FP64 in 8x8 blocks, non-temporal: 0.129 -> 0.104 ms)
           uint4 h[4];
 #pragma unroll
           for (int k = 0; k < 4; ++k) h[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
           transpose_quarter_waves(h[0], h[1], h[2], h[3]);
           uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 4 * (lane & 15) + (lane >> 4);
 #pragma unroll
-          for (int k = 0; k < 4; ++k) p[64 * k] = h[k];
+          for (int k = 0; k < 4; ++k) store16_stream(p + 64 * k, h[k]);
         } else {
-          // plain stores: a lane's pieces alternate with its neighbours' within a line, which the L2 merges into
-          // whole lines; with the non-temporal hint these 16-byte pieces reach memory singly (measured: twice as
-          // slow), and passing the rows through LDS to store whole lines doubled the kernel's registers
           uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * BX);
+          if constexpr (RV == 1) {     // one piece per block row: the lanes' pieces are contiguous as they are
+            store16_stream(p, Pack<T, XT>::run(v + (z * BY + yy0) * PER16));
+          } else {
+            // a partly filled wave.  Plain stores: a lane's pieces alternate with its neighbours' within a line,
+            // which the L2 merges into whole lines; with the non-temporal hint these 16-byte pieces reach memory
+            // singly (measured: twice as slow)
 #pragma unroll
-          for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+            for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+          }
         }
       }
     }
