@@ -1,4 +1,6 @@
 // Specialised codec kernels, family "lane" (see pbz_fast.hip for the overview).
+#include <type_traits>
+
 #include "pbz_fast_common.h"
 
 namespace pbz {
@@ -176,9 +178,11 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
 
 // Two workgroups per compute unit, i.e. two waves per SIMD, are asked for explicitly: the FP64-array 4x4x4 variants
 // otherwise come out at 256 vector registers plus a few accumulation registers, which is one wave per SIMD (the
-// register file holds 512 per lane).  Held to 256 they spill nine values and run 6 % faster (workload 4 decompress:
-// 0.264 -> 0.248 ms on random data); three waves (168 registers, 95 values spilled) take 0.44 ms, and a scheduling
-// fence after each row's stores changes neither the register count nor the time.
+// register file holds 512 per lane).  Held to 256 they run 6 % faster (workload 4 decompress: 0.264 -> 0.248 ms on
+// random data); three waves (168 registers, 95 values spilled) take 0.44 ms, and a scheduling fence after each
+// row's stores changes neither the register count nor the time.  With the choice between the whole-wave stores
+// and those of a partly filled wave made once, outside the loops over the rows, the bound costs no spill (with
+// the choice inside the loops: nine values per lane, 4.5 % more bytes written than the array has).
 template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX,
           bool kRagged, bool kTailX = false>
 __global__ __launch_bounds__(256, 2) void k_decompress_lane(FastGeom g, const void* __restrict__ N, const IT* __restrict__ F,
@@ -218,74 +222,82 @@ __global__ __launch_bounds__(256, 2) void k_decompress_lane(FastGeom g, const vo
 
   inverse_block<TF, T, BZ, BY, BX, KZ, KY, KX>(v);
 
-#pragma unroll
-  for (int z = 0; z < BZ; ++z)
-#pragma unroll
-    for (int yy0 = 0; yy0 < BY; ++yy0) {
-      const int64_t zz = bz * BZ + z, yy = by * BY + yy0;
-      if (!kRagged || (zz < g.Z && yy < g.Y)) {
-        if constexpr (kTailX) {
-          XT* row = y + (zz * g.Y + yy) * g.X;
-#pragma unroll
-          for (int k = 0; k < RV; ++k) {
-            const int64_t x0 = bx * BX + k * PER16;
-            const T* piece = v + ((z * BY + yy0) * RV + k) * PER16;
-            if (x0 + PER16 <= g.X) {
-              store16_a4(row + x0, Pack<T, XT>::run(piece));
-            } else {
-#pragma unroll
-              for (int e = 0; e < PER16; ++e)
-                if (x0 + e < g.X) Elem<T, XT>::store(row + x0 + e, piece[e]);
+  // whole waves and partly filled ones store differently; the choice is made once, outside the loops over the rows
+  auto store_rows = [&](auto whole_tag) {
+    constexpr bool kWhole = decltype(whole_tag)::value;
+  #pragma unroll
+    for (int z = 0; z < BZ; ++z)
+  #pragma unroll
+      for (int yy0 = 0; yy0 < BY; ++yy0) {
+        const int64_t zz = bz * BZ + z, yy = by * BY + yy0;
+        if (!kRagged || (zz < g.Z && yy < g.Y)) {
+          if constexpr (kTailX) {
+            XT* row = y + (zz * g.Y + yy) * g.X;
+  #pragma unroll
+            for (int k = 0; k < RV; ++k) {
+              const int64_t x0 = bx * BX + k * PER16;
+              const T* piece = v + ((z * BY + yy0) * RV + k) * PER16;
+              if (x0 + PER16 <= g.X) {
+                store16_a4(row + x0, Pack<T, XT>::run(piece));
+              } else {
+  #pragma unroll
+                for (int e = 0; e < PER16; ++e)
+                  if (x0 + e < g.X) Elem<T, XT>::store(row + x0 + e, piece[e]);
+              }
             }
-          }
-        } else if (RV == 2 && whole_wave) {
-          // A block row is two 16-byte pieces, so a plain store instruction would write every other piece of a
-          // 2 KiB span.  The two half-waves trade pieces instead (lanes 32-63 hand the first piece of their row
-          // to lanes 0-31 and take those lanes' second piece): the first store then writes the rows of blocks
-          // 0-31 as one contiguous KiB, the second those of blocks 32-63 (workload 4: 0.251 -> 0.240 ms).  Whole
-          // KiB per instruction is also what the non-temporal hint needs (back-to-back repeats of workload 4:
-          // 0.248 -> 0.238 ms; inside the benchmark step the kernel itself shows 0.254 ms, because it now waits
-          // for its own writes, and the negate after it 0.090 instead of 0.111 ms; the step is 15 us shorter).
-          // The compiler hoists every row's trade above the first store
-          // (256 registers, two waves per SIMD): running the last transform pass row by row just before each
-          // row's stores brought that to 160 registers and three waves, and was slower (0.252 ms): a wave's
-          // 32 stores leaving back to back matter more than the third wave.
-          uint4 h0 = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + 0) * PER16);
-          uint4 h1 = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + 1) * PER16);
-          swap_half_waves(h0.x, h1.x);
-          swap_half_waves(h0.y, h1.y);
-          swap_half_waves(h0.z, h1.z);
-          swap_half_waves(h0.w, h1.w);
-          uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 2 * (lane & 31) + (lane >> 5);
-          store16_stream(p, h0);
-          store16_stream(p + 64, h1);
-        } else if (RV == 4 && whole_wave) {
-          // four pieces per block row: after the quarter transpose store j writes the rows of blocks
-          // 16j .. 16j+15 as one contiguous KiB (8192^2 FP64 in 8x8 blocks, non-temporal: 0.129 -> 0.104 ms)
-          uint4 h[4];
-#pragma unroll
-          for (int k = 0; k < 4; ++k) h[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
-          transpose_quarter_waves(h[0], h[1], h[2], h[3]);
-          uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 4 * (lane & 15) + (lane >> 4);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) store16_stream(p + 64 * k, h[k]);
-        } else {
-          uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * BX);
-          if constexpr (RV == 1) {     // one piece per block row: the lanes' pieces are contiguous as they are
-            store16_stream(p, Pack<T, XT>::run(v + (z * BY + yy0) * PER16));
+          } else if constexpr (RV == 2 && kWhole) {
+            // A block row is two 16-byte pieces, so a plain store instruction would write every other piece of a
+            // 2 KiB span.  The two half-waves trade pieces instead (lanes 32-63 hand the first piece of their row
+            // to lanes 0-31 and take those lanes' second piece): the first store then writes the rows of blocks
+            // 0-31 as one contiguous KiB, the second those of blocks 32-63 (workload 4: 0.251 -> 0.240 ms).  Whole
+            // KiB per instruction is also what the non-temporal hint needs (back-to-back repeats of workload 4:
+            // 0.248 -> 0.238 ms; inside the benchmark step the kernel now waits for its own writes and still
+            // shows 0.249 ms, the negate after it 0.090 instead of 0.111 ms).
+            // The compiler hoists every row's trade above the first store
+            // (256 registers, two waves per SIMD): running the last transform pass row by row just before each
+            // row's stores brought that to 160 registers and three waves, and was slower (0.252 ms): a wave's
+            // 32 stores leaving back to back matter more than the third wave.
+            uint4 h0 = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + 0) * PER16);
+            uint4 h1 = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + 1) * PER16);
+            swap_half_waves(h0.x, h1.x);
+            swap_half_waves(h0.y, h1.y);
+            swap_half_waves(h0.z, h1.z);
+            swap_half_waves(h0.w, h1.w);
+            uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 2 * (lane & 31) + (lane >> 5);
+            store16_stream(p, h0);
+            store16_stream(p + 64, h1);
+          } else if constexpr (RV == 4 && kWhole) {
+            // four pieces per block row: after the quarter transpose store j writes the rows of blocks
+            // 16j .. 16j+15 as one contiguous KiB (8192^2 FP64 in 8x8 blocks, non-temporal: 0.129 -> 0.104 ms)
+            uint4 h[4];
+  #pragma unroll
+            for (int k = 0; k < 4; ++k) h[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+            transpose_quarter_waves(h[0], h[1], h[2], h[3]);
+            uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * BX) + 4 * (lane & 15) + (lane >> 4);
+  #pragma unroll
+            for (int k = 0; k < 4; ++k) store16_stream(p + 64 * k, h[k]);
           } else {
-            // a partly filled wave.  Plain stores: a lane's pieces alternate with its neighbours' within a line,
-            // which the L2 merges into whole lines; with the non-temporal hint these 16-byte pieces reach memory
-            // singly (measured: twice as slow)
-#pragma unroll
-            for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+            uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + bx * BX);
+            if constexpr (RV == 1) {     // one piece per block row: the lanes' pieces are contiguous as they are
+              store16_stream(p, Pack<T, XT>::run(v + (z * BY + yy0) * PER16));
+            } else {
+              // a partly filled wave.  Plain stores: a lane's pieces alternate with its neighbours' within a line,
+              // which the L2 merges into whole lines; with the non-temporal hint these 16-byte pieces reach memory
+              // singly (measured: twice as slow)
+  #pragma unroll
+              for (int k = 0; k < RV; ++k) p[k] = Pack<T, XT>::run(v + ((z * BY + yy0) * RV + k) * PER16);
+            }
           }
         }
       }
-    }
+  };
+  if constexpr (kTailX || RV == 1 || (RV != 2 && RV != 4)) {
+    store_rows(std::false_type{});
+  } else {
+    if (whole_wave) store_rows(std::true_type{});
+    else store_rows(std::false_type{});
+  }
 }
-
-
 
 // One table row per instantiation.
 template <int TF, typename T, typename XT, typename IT, typename NT, int BZ, int BY, int BX, int KZ, int KY, int KX>
