@@ -33,34 +33,14 @@
 #include "pbz_device.h"
 #include "pbz_haar.h"
 #include "pbz_internal.h"
+#include "pbz_tile_index.h"
 
 namespace pbz {
 namespace {
 
+using namespace tile;
+
 constexpr int kThreads = 256;
-constexpr int kTileElems = 4096;
-constexpr int kMaxTileBlocks = 256;
-
-// The array's geometry right-aligned into a fixed number of dimensions (kDims = 4 or 8 in the kernels; unused
-// leading dimensions have extent, block extent and grid extent 1 and stride 0), so that every loop over the
-// dimensions unrolls and its operands stay in scalar registers instead of being fetched by a run-time index.
-struct TileGeom {
-  int G, g_shift;                 // blocks per tile
-  int vol_shift;                  // log2(prod(block))
-  int bx_shift;                   // log2 of the last block extent
-  int dims;                       // 4 or 8
-  int kept;
-  int vec_x;                      // the array may be moved in 16-byte pieces (see the overview)
-  int vec_f;                      // F may be moved in runs of four entries
-  int64_t n_blocks;
-  int bshift[PBZ_MAX_NDIM];       // log2 of every block extent
-  int64_t shape[PBZ_MAX_NDIM], stride[PBZ_MAX_NDIM], grid[PBZ_MAX_NDIM];
-};
-
-// one spare slot per 32 keeps strided line accesses from piling onto one bank (one per 16 for FP64 values, whose
-// 32 fill the banks twice over, changed nothing measurable)
-template <typename T>
-__device__ __forceinline__ int pad(int i) { return i + (i >> 5); }
 
 template <typename T> struct Bits;
 template <> struct Bits<float> {
@@ -74,89 +54,16 @@ template <> struct Bits<double> {
   static __device__ __forceinline__ double from(type b) { return __longlong_as_double((long long)b); }
 };
 
-constexpr int kMaxRows = 256;                 // rows (runs along the last dimension) of a block whose place is tabulated
-
-// One byte per dimension (right-aligned: byte kDims - 1 belongs to the last one).  A block's `lim` holds how many
-// entries (0 .. 32) along each dimension lie inside the array; a position's `coord` holds 0x80 | coordinate
-// (0 .. 31).  Byte by byte, coord - lim = 128 + c - l lies in [96, 159], so nothing is borrowed across bytes, and
-// bit 7 of a byte is clear exactly when c < l: one subtraction tests all dimensions at once.
-template <int kDims> struct Packed;
-template <> struct Packed<4> { typedef uint32_t type; static constexpr uint32_t kHigh = 0x80808080u; };
-template <> struct Packed<8> { typedef uint64_t type; static constexpr uint64_t kHigh = 0x8080808080808080ull; };
-
-struct BlockInfo {                            // 16 bytes: one LDS read
-  int64_t origin;                             // element offset of the block's first element
-  uint64_t lim;                               // all zero: no such block (past the end of the array's blocks)
-};
-struct RowInfo {                              // 16 bytes: one LDS read
-  int64_t off;                                // offset of the row's first element from the block's first element
-  uint64_t coord;                             // the last dimension's byte holds 0x80: the caller adds the position in the row
-};
 struct TileBlocks {                           // both in LDS, sized by the tile: G blocks, the rows of one block
   BlockInfo* blk;
   RowInfo* row;                               // filled when a block has at most kMaxRows rows
 };
 
-// The workgroup's LDS: G block records, the row records, 16 bytes per block for the kernels' own per-block
-// values (maxima and reciprocals, or N / r), then the padded tile.
-__device__ __host__ inline int tabulated_rows(int vol_shift, int bx_shift) {
-  const int rows = 1 << (vol_shift - bx_shift);
-  return rows <= kMaxRows ? rows : 0;
-}
-__device__ __host__ inline size_t per_block_offset(int G, int vol_shift, int bx_shift) {
-  return 16 * size_t(G + tabulated_rows(vol_shift, bx_shift));
-}
-__device__ __host__ inline size_t tile_offset(int G, int vol_shift, int bx_shift) {
-  return per_block_offset(G, vol_shift, bx_shift) + 16 * size_t(G);
-}
 constexpr int kBatch = 8;                     // global loads a thread keeps in flight while filling a tile
 
 template <int kDims>
-__device__ __forceinline__ bool inside(uint64_t lim, uint64_t coord) {
-  typedef typename Packed<kDims>::type packed_t;
-  return ((packed_t(coord) - packed_t(lim)) & Packed<kDims>::kHigh) == 0;
-}
-
-template <int kDims>
 __device__ __forceinline__ void decode_blocks(const TileGeom& tg, int64_t k0, const TileBlocks& tb) {
-  for (int b = threadIdx.x; b < tg.G; b += kThreads) {
-    int64_t k = k0 + b;
-    BlockInfo info;
-    info.origin = 0;
-    info.lim = 0;
-    if (k < tg.n_blocks) {
-#pragma unroll
-      for (int d = PBZ_MAX_NDIM - 1; d >= PBZ_MAX_NDIM - kDims; --d) {
-        int64_t kb = 0;
-        if (tg.grid[d] > 1) {             // uniform: no division for the padded dimensions
-          kb = k % tg.grid[d];
-          k /= tg.grid[d];
-        }
-        const int64_t c0 = kb << tg.bshift[d];
-        const int64_t left = tg.shape[d] - c0;
-        const int64_t extent = int64_t(1) << tg.bshift[d];
-        info.lim |= uint64_t(left < extent ? left : extent) << (8 * (d - (PBZ_MAX_NDIM - kDims)));
-        info.origin += c0 * tg.stride[d];
-      }
-    }
-    tb.blk[b] = info;
-  }
-}
-
-// row i of a block (rows are numbered in the block's own row-major order)
-template <int kDims>
-__device__ __forceinline__ RowInfo row_info(const TileGeom& tg, int i) {
-  RowInfo r;
-  r.off = 0;
-  r.coord = Packed<kDims>::kHigh;
-#pragma unroll
-  for (int d = PBZ_MAX_NDIM - 2; d >= PBZ_MAX_NDIM - kDims; --d) {
-    const int jd = i & ((1 << tg.bshift[d]) - 1);
-    i >>= tg.bshift[d];
-    r.off += jd * tg.stride[d];
-    r.coord += uint64_t(jd) << (8 * (d - (PBZ_MAX_NDIM - kDims)));
-  }
-  return r;
+  for (int b = threadIdx.x; b < tg.G; b += kThreads) tb.blk[b] = block_info<kDims>(tg, k0 + b);
 }
 
 // once per kernel
@@ -174,17 +81,7 @@ __device__ __forceinline__ bool locate(const TileGeom& tg, const TileBlocks& tb,
   const int i = j >> tg.bx_shift, xin = j & ((1 << tg.bx_shift) - 1);
   const bool tabulated = (1 << (tg.vol_shift - tg.bx_shift)) <= kMaxRows;     // uniform: the usual case
   const RowInfo r = tabulated ? tb.row[i] : row_info<kDims>(tg, i);
-  const BlockInfo k = tb.blk[b];
-  *offset = k.origin + r.off + xin;                                            // the last dimension has stride 1
-  return inside<kDims>(k.lim, r.coord + (uint64_t(xin) << (8 * (kDims - 1))));
-}
-
-// memory-friendly enumeration of the tile: consecutive e walk along a row across the tile's blocks
-__device__ __forceinline__ void row_major_across_blocks(const TileGeom& tg, int e, int* b, int* j) {
-  const int bx = 1 << tg.bx_shift;
-  const int xin = e & (bx - 1);
-  *b = (e >> tg.bx_shift) & (tg.G - 1);
-  *j = ((e >> (tg.bx_shift + tg.g_shift)) << tg.bx_shift) + xin;
+  return locate_in<kDims>(tb.blk[b], r, xin, offset);
 }
 
 template <typename T, typename XT>
@@ -209,7 +106,7 @@ __device__ __forceinline__ void load_tile(const TileGeom& tg, const TileBlocks& 
       row_major_across_blocks(tg, e < total ? e : 0, &b, &j);
       int64_t off;
       in[u] = locate<kDims>(tg, tb, b, j, &off) && e < total;
-      slot[u] = e < total ? pad<T>((b << tg.vol_shift) + j) : -1;
+      slot[u] = e < total ? pad((b << tg.vol_shift) + j) : -1;
       raw[u] = x[in[u] ? off : 0];
     }
 #pragma unroll
@@ -230,7 +127,7 @@ __device__ __forceinline__ void store_tile(const TileGeom& tg, const TileBlocks&
     int b, j;
     row_major_across_blocks(tg, e, &b, &j);
     int64_t off;
-    if (locate<kDims>(tg, tb, b, j, &off)) y[off] = XT(buf[pad<T>((b << tg.vol_shift) + j)]);
+    if (locate<kDims>(tg, tb, b, j, &off)) y[off] = XT(buf[pad((b << tg.vol_shift) + j)]);
   }
 }
 
@@ -242,7 +139,7 @@ __device__ __forceinline__ void store_tile_bf16(const TileGeom& tg, const TileBl
     row_major_across_blocks(tg, e, &b, &j);
     int64_t off;
     if (locate<kDims>(tg, tb, b, j, &off)) {
-      const T v = buf[pad<T>((b << tg.vol_shift) + j)];
+      const T v = buf[pad((b << tg.vol_shift) + j)];
       y[off] = sizeof(T) == 8 ? double_to_bf16_bits(double(v)) : float_to_bf16_bits(float(v));
     }
   }
@@ -255,7 +152,7 @@ __device__ __forceinline__ void store_tile_f16(const TileGeom& tg, const TileBlo
     row_major_across_blocks(tg, e, &b, &j);
     int64_t off;
     if (locate<kDims>(tg, tb, b, j, &off)) {
-      const T v = buf[pad<T>((b << tg.vol_shift) + j)];
+      const T v = buf[pad((b << tg.vol_shift) + j)];
       y[off] = sizeof(T) == 8 ? double_to_f16(double(v)) : _Float16(float(v));
     }
   }
@@ -292,16 +189,6 @@ __device__ __forceinline__ uint4 pack_piece(const T* v) {
   return raw;
 }
 
-// piece p of the tile -> block and intra-block index of its first element; consecutive p walk along a row across
-// the tile's blocks, like row_major_across_blocks
-template <int P>
-__device__ __forceinline__ void piece_across_blocks(const TileGeom& tg, int p, int* b, int* j) {
-  constexpr int pshift = P == 2 ? 1 : (P == 4 ? 2 : 3);
-  const int ppr_shift = tg.bx_shift - pshift;                 // pieces per block row
-  *b = (p >> ppr_shift) & (tg.G - 1);
-  *j = ((p >> (ppr_shift + tg.g_shift)) << tg.bx_shift) + ((p & ((1 << ppr_shift) - 1)) << pshift);
-}
-
 constexpr int kPieceBatch = 4;                // 16-byte loads a thread keeps in flight while filling a tile
 
 template <int kDims, typename T, typename XT>
@@ -322,7 +209,7 @@ __device__ __forceinline__ void load_tile_pieces(const TileGeom& tg, const TileB
       piece_across_blocks<P>(tg, p < n_pieces ? p : 0, &b, &j);
       int64_t off;
       in[u] = locate<kDims>(tg, tb, b, j, &off) && p < n_pieces;     // the piece's first element decides for all of it
-      slot[u] = p < n_pieces ? pad<T>((b << tg.vol_shift) + j) : -1;    // a piece never straddles a padding boundary
+      slot[u] = p < n_pieces ? pad((b << tg.vol_shift) + j) : -1;    // a piece never straddles a padding boundary
       raw[u] = *reinterpret_cast<const uint4*>(x + (in[u] ? off : 0));
     }
 #pragma unroll
@@ -346,7 +233,7 @@ __device__ __forceinline__ void store_tile_pieces(const TileGeom& tg, const Tile
     piece_across_blocks<P>(tg, p, &b, &j);
     int64_t off;
     if (locate<kDims>(tg, tb, b, j, &off)) {
-      const int slot = pad<T>((b << tg.vol_shift) + j);
+      const int slot = pad((b << tg.vol_shift) + j);
       T v[P];
 #pragma unroll
       for (int i = 0; i < P; ++i) v[i] = buf[slot + i];
@@ -417,14 +304,14 @@ __device__ __forceinline__ void bin_quads(const TileGeom& tg, const T* buf, cons
     if (k0 + b >= tg.n_blocks) continue;
     T c[4];
     if (all_kept) {                  // position e of the tile's F is element e of the tile; four in a row share a group of 32
-      const T* src = buf + pad<T>(e);
+      const T* src = buf + pad(e);
 #pragma unroll
       for (int i = 0; i < 4; ++i) c[i] = src[i];
     } else {
       int j[4];
       kept_entries(false, kept_list, e - b * tg.kept, j);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) c[i] = buf[pad<T>((b << tg.vol_shift) + j[i])];
+      for (int i = 0; i < 4; ++i) c[i] = buf[pad((b << tg.vol_shift) + j[i])];
     }
     int idx[4];
     const T nk = Bits<T>::from(bmax[b]), inv = binv[b];
@@ -464,14 +351,14 @@ __device__ __forceinline__ void scatter_quads(const TileGeom& tg, const IT* F, i
       Quad<IT>::unpack(raw[u], f);
       const T scale = bn[b];
       if (all_kept) {
-        T* dst = buf + pad<T>(e);
+        T* dst = buf + pad(e);
 #pragma unroll
         for (int i = 0; i < 4; ++i) dst[i] = scale * T(f[i]);
       } else {
         int j[4];
         kept_entries(false, kept_list, e - b * tg.kept, j);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) buf[pad<T>((b << tg.vol_shift) + j[i])] = scale * T(f[i]);
+        for (int i = 0; i < 4; ++i) buf[pad((b << tg.vol_shift) + j[i])] = scale * T(f[i]);
       }
     }
   }
@@ -483,19 +370,18 @@ template <typename T, int kTf, int n, bool kForward, bool kMax = false>
 __device__ __forceinline__ void pass_n(T* buf, int total, int n_shift, int inner_shift,
                                        typename Bits<T>::type* bmax = nullptr, int vol_shift = 0) {
   const int lines = total >> n_shift;
-  const int inner = 1 << inner_shift;
   for (int l = threadIdx.x; l < lines; l += kThreads) {
-    const int base = ((l >> inner_shift) << (n_shift + inner_shift)) + (l & (inner - 1));
+    const int base = line_base(l, n_shift, inner_shift);
     // pad(base + a * inner) = pad(base) + pad(a * inner): the line starts at a multiple of its span or, when that
     // span is below 32, stays inside one group of 32; the second term is the same for all threads (scalar unit)
-    T* line = buf + pad<T>(base);
+    T* line = buf + pad(base);
     T v[n];
 #pragma unroll
-    for (int a = 0; a < n; ++a) v[a] = line[pad<T>(a << inner_shift)];
+    for (int a = 0; a < n; ++a) v[a] = line[pad(a << inner_shift)];
     if (kForward) tf_forward<kTf, T, n, 1>(v);
     else tf_inverse<kTf, T, n, 1, n>(v);
 #pragma unroll
-    for (int a = 0; a < n; ++a) line[pad<T>(a << inner_shift)] = v[a];
+    for (int a = 0; a < n; ++a) line[pad(a << inner_shift)] = v[a];
     if constexpr (kMax) {
       T m = fabs(v[0]);
 #pragma unroll
@@ -600,7 +486,7 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
     __syncthreads();
     transform_tile<kDims, T, kTf, true, kMaxShift>(tg, buf, total, bmax);      // leaves N_k = max |C_k| in bmax
     if (vol == 1) {                        // single-element blocks: nothing was transformed
-      for (int e = threadIdx.x; e < total; e += kThreads) bmax[e] = Bits<T>::of(fabs(buf[pad<T>(e)]));
+      for (int e = threadIdx.x; e < total; e += kThreads) bmax[e] = Bits<T>::of(fabs(buf[pad(e)]));
       __syncthreads();
     }
     for (int b = threadIdx.x; b < tg.G; b += kThreads) {
@@ -635,7 +521,7 @@ __global__ __launch_bounds__(kThreads) void k_compress_tiled(TileGeom tg, const 
       for (int u = 0; u < kBatch; ++u) {
         if (b[u] < 0) continue;
         const T nk = Bits<T>::from(bmax[b[u]]), inv = binv[b[u]];
-        const T a = T(r) * buf[pad<T>((b[u] << tg.vol_shift) + j[u])];
+        const T a = T(r) * buf[pad((b[u] << tg.vol_shift) + j[u])];
         const T q = a * inv;
         T t = fma(fma(-q, nk, a), inv, q);
         t = fmin(fmax(rint(t), T(-r)), T(r));
@@ -661,7 +547,7 @@ __device__ __forceinline__ void scatter_coefficients(const TileGeom& tg, const I
       f[u] = F[at <= last ? at : last];
       const int ec = e < n_kept ? e : 0;
       const int b = ec / tg.kept;
-      j[u] = e < n_kept ? pad<T>((b << tg.vol_shift) + kept_list[ec - b * tg.kept]) : -1;
+      j[u] = e < n_kept ? pad((b << tg.vol_shift) + kept_list[ec - b * tg.kept]) : -1;
     }
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
@@ -693,7 +579,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress_tiled(TileGeom tg, cons
     for (int b = threadIdx.x; b < tg.G; b += kThreads)      // blocks past the end: the last one again, never stored
       bn[b] = load_float<T>(N, ntype, k0 + b < tg.n_blocks ? k0 + b : tg.n_blocks - 1) / T(r);   // N / r once per block
     if (tg.kept != vol)
-      for (int e = threadIdx.x; e < total; e += kThreads) buf[pad<T>(e)] = T(0);
+      for (int e = threadIdx.x; e < total; e += kThreads) buf[pad(e)] = T(0);
     __syncthreads();
     // Algorithm 3: N F / r at the kept positions
     if (tg.vec_f) {
@@ -729,33 +615,8 @@ __global__ __launch_bounds__(kThreads) void k_decompress_tiled(TileGeom tg, cons
   }
 }
 
-int ilog2(int64_t v) {
-  int s = 0;
-  while ((int64_t(1) << s) < v) ++s;
-  return s;
-}
-
 TileGeom make_tile(const pbz_codec* c, const Geom& g) {
-  TileGeom tg{};
-  int G = kTileElems / c->vol;
-  if (G < 1) G = 1;
-  if (G > kMaxTileBlocks) G = kMaxTileBlocks;
-  tg.G = G;
-  tg.g_shift = ilog2(G);
-  tg.vol_shift = ilog2(c->vol);
-  tg.bx_shift = ilog2(c->block[c->ndim - 1]);
-  tg.dims = c->ndim <= 4 ? 4 : 8;
-  tg.kept = c->kept;
-  tg.vec_x = tg.vec_f = 0;
-  tg.n_blocks = g.n_blocks;
-  for (int d = 0; d < PBZ_MAX_NDIM; ++d) {        // right-aligned; leading dimensions of extent 1
-    const int src = d - (PBZ_MAX_NDIM - c->ndim);
-    tg.bshift[d] = src >= 0 ? ilog2(c->block[src]) : 0;
-    tg.shape[d] = src >= 0 ? g.shape[src] : 1;
-    tg.stride[d] = src >= 0 ? g.stride[src] : 0;
-    tg.grid[d] = src >= 0 ? g.grid[src] : 1;
-  }
-  return tg;
+  return make_tile_geom(c->ndim, c->block, g.shape, c->kept);
 }
 
 // may the array (elements of array_type at `array`) be moved in 16-byte pieces, and F in runs of four entries?
