@@ -180,6 +180,13 @@ struct IdxPack<int16_t> {
   static __device__ __forceinline__ int get(uint32_t w, int i) { return int(int16_t((w >> (16 * i)) & 0xffffu)); }
 };
 
+template <>
+struct IdxPack<int32_t> {
+  static constexpr int per = 1;
+  static __device__ __forceinline__ uint32_t pack(const uint32_t* q) { return q[0]; }
+  static __device__ __forceinline__ int get(uint32_t w, int) { return int(w); }
+};
+
 // ---- arrays whose last extent is not a multiple of the block's ------------------------------------------
 // Rows then start at any multiple of the element size, so 16-byte accesses are only 4-byte aligned (the hardware
 // takes them; the type tells the compiler), and the last block of every row is partial.  Kernels built with
@@ -393,6 +400,14 @@ __device__ __forceinline__ double sum_of_squares(const uint32_t* w) {   // of th
 #pragma unroll
     for (int k = 0; k < kWords; ++k) acc = __builtin_amdgcn_sdot4(int(w[k]), int(w[k]), acc, false);
     return double(acc);
+  } else if constexpr (sizeof(IT) == 4) {
+    double acc = 0.0;       // squares of 32-bit indices reach 2^62: summed in FP64, like the reductions over such indices
+#pragma unroll
+    for (int k = 0; k < kWords; ++k) {
+      const double f = double(int32_t(w[k]));
+      acc += f * f;
+    }
+    return acc;
   } else {
     long long acc = 0;      // one dword: 2 * 32767^2 < 2^31
 #pragma unroll
@@ -562,6 +577,7 @@ template <typename IT>
 constexpr int itype_code();
 template <> constexpr int itype_code<int8_t>() { return PBZ_I8; }
 template <> constexpr int itype_code<int16_t>() { return PBZ_I16; }
+template <> constexpr int itype_code<int32_t>() { return PBZ_I32; }
 
 // A family's table of instantiations, tried in order.  compress / decompress: 0 when no instantiation matches
 // (`*name` stays null), else the kernel's name in `*name` and 1 / a negative status (dry_run: 1 when the launch

@@ -368,6 +368,12 @@ template <int TF> using Lane_f64_w32_8x8_i16 = LaneKernel<TF, double, double, in
 template <int TF> using Lane_f64_w32_4x4x4_i8 = LaneKernel<TF, float, double, int8_t, float, 4, 4, 4, 4, 4, 4>;
 template <int TF> using Lane_f64_w32_4x4x4_i16 = LaneKernel<TF, double, double, int16_t, float, 4, 4, 4, 4, 4, 4>;
 
+// int32 indices (FP64 arithmetic whatever the array's type): a block's F is 256 bytes, 16 pieces per lane
+template <int TF> using Lane_f32_8x8_i32 = LaneKernel<TF, double, float, int32_t, float, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_f64_8x8_i32 = LaneKernel<TF, double, double, int32_t, double, 1, 8, 8, 1, 8, 8>;
+template <int TF> using Lane_f32_4x4x4_i32 = LaneKernel<TF, double, float, int32_t, float, 4, 4, 4, 4, 4, 4>;
+template <int TF> using Lane_f64_4x4x4_i32 = LaneKernel<TF, double, double, int32_t, double, 4, 4, 4, 4, 4, 4>;
+
 #define PBZ_ROWS(X, TF, SUFFIX) \
   X(Lane_f32_8x8_i8<TF>, "lane_f32_8x8_i8" SUFFIX) \
   X(Lane_bf16_8x8_i8<TF>, "lane_bf16_8x8_i8" SUFFIX) \
@@ -383,7 +389,11 @@ template <int TF> using Lane_f64_w32_4x4x4_i16 = LaneKernel<TF, double, double, 
   X(Lane_f64_w32_8x8_i8<TF>, "lane_f64_w32_8x8_i8" SUFFIX) \
   X(Lane_f64_w32_8x8_i16<TF>, "lane_f64_w32_8x8_i16" SUFFIX) \
   X(Lane_f64_w32_4x4x4_i8<TF>, "lane_f64_w32_4x4x4_i8" SUFFIX) \
-  X(Lane_f64_w32_4x4x4_i16<TF>, "lane_f64_w32_4x4x4_i16" SUFFIX)
+  X(Lane_f64_w32_4x4x4_i16<TF>, "lane_f64_w32_4x4x4_i16" SUFFIX) \
+  X(Lane_f32_8x8_i32<TF>, "lane_f32_8x8_i32" SUFFIX) \
+  X(Lane_f64_8x8_i32<TF>, "lane_f64_8x8_i32" SUFFIX) \
+  X(Lane_f32_4x4x4_i32<TF>, "lane_f32_4x4x4_i32" SUFFIX) \
+  X(Lane_f64_4x4x4_i32<TF>, "lane_f64_4x4x4_i32" SUFFIX)
 
 }  // namespace
 

@@ -195,6 +195,17 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((24, 1032), (8, 8), 16, "f64", "f32", None, "lane_f64_w32_8x8_i16"),
                ((9, 13, 262), (4, 4, 4), 8, "f64", "f32", None, "lane_f64_w32_4x4x4_i8"),
                ((5, 30, 20), (4, 4, 4), 16, "f64", "bf16", None, "lane_f64_w32_4x4x4_i16"),
+               # int32 indices on the lane kernels (a block's F is 256 bytes)
+               ((21, 72), (8, 8), 32, "f32", "f32", None, "lane_f32_8x8_i32"),
+               ((37, 1032), (8, 8), 32, "f32", "f16", None, "lane_f32_8x8_i32"),
+               ((16, 67), (8, 8), 32, "f32", "f32", None, "lane_f32_8x8_i32"),
+               ((37, 520), (8, 8), 32, "f64", "f64", None, "lane_f64_8x8_i32"),
+               ((21, 75), (8, 8), 32, "f64", "f64", None, "lane_f64_8x8_i32"),
+               ((9, 14, 24), (4, 4, 4), 32, "f32", "f32", None, "lane_f32_4x4x4_i32"),
+               ((5, 8, 1030), (4, 4, 4), 32, "f32", "bf16", None, "lane_f32_4x4x4_i32"),
+               ((5, 30, 20), (4, 4, 4), 32, "f64", "f64", None, "lane_f64_4x4x4_i32"),
+               ((9, 13, 262), (4, 4, 4), 32, "f64", "f64", None, "lane_f64_4x4x4_i32"),
+               ((8, 8, 517), (4, 4, 4), 32, "f64", "f64", None, "lane_f64_4x4x4_i32"),
                # 16-bit arrays in 8x8 and 8x8x8 blocks
                ((37, 64), (8, 8), 8, "bf16", "f32", None, "lane_bf16_8x8_i8"),
                ((21, 1046), (8, 8), 8, "bf16", "bf16", None, "lane_bf16_8x8_i8"),
@@ -264,6 +275,8 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((9, 30, 40), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16_haar"),
         ((21, 72), (8, 8), 8, "f64", "f64", None, "lane_f64_8x8_i8_haar"),
         ((9, 14, 24), (4, 4, 4), 8, "f32", "f32", None, "lane_f32_4x4x4_i8_haar"),
+        ((21, 72), (8, 8), 32, "f32", "f32", None, "lane_f32_8x8_i32_haar"),
+        ((5, 30, 19), (4, 4, 4), 32, "f64", "f64", None, "lane_f64_4x4x4_i32_haar"),
         ((3, 33, 96), (1, 16, 16), 8, "f32", "f32", None, "quad16_f32_16x16_i8_haar"),
         ((17, 24, 72), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((16, 9, 24), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8_haar"),

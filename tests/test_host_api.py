@@ -239,8 +239,13 @@ DISPATCH = [
     ((16, 16, 16), "bf16", "i16", None, (32, 32, 64), "f32", "cube16_f32_16x16x16_i16"),
     ((16, 16, 16), "f32", "i8", None, (100, 500, 500), "f32", "cube16_f32_16x16x16_i8"),
     ((1, 1, 8, 8), "f32", "i8", None, (3, 2, 40, 64), "f32", "lane_f32_8x8_i8"),          # leading unit-block dimensions fold
+    ((8, 8), "f32", "i32", None, (64, 64), "f32", "lane_f32_8x8_i32"),
+    ((8, 8), "f64", "i32", None, (37, 67), "f64", "lane_f64_8x8_i32"),
+    ((4, 4, 4), "bf16", "i32", None, (9, 14, 24), "f32", "lane_f32_4x4x4_i32"),
+    ((4, 4, 4), "f64", "i32", None, (512, 512, 512), "f64", "lane_f64_4x4x4_i32"),
     # no specialised kernel: the general ones
-    ((8, 8), "f32", "i32", None, (64, 64), "f32", "generic"),
+    ((16, 16), "f32", "i32", None, (64, 64), "f32", "generic"),
+    ((8, 8), "f32", "i32", (4, 4), (64, 64), "f32", "generic"),                            # int32 with a box
     ((8, 8), "f64", "i16", None, (64, 64), "f32", "generic"),                              # FP32 array, FP64 N
     ((16, 16), "f32", "i16", None, (64, 64), "f16", "generic"),                            # 16-bit array, int16
     ((8, 8, 8), "f32", "i8", (2, 2, 2), (16, 16, 16), "f32", "generic"),                   # another mask
