@@ -15,6 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpbz.so")
 EXAMPLE = os.path.join(PKG, "c_abi_roundtrip")
+PATTERNS = os.path.join(PKG, "memory_patterns")
 SOURCES = ["pbz_api.hip", "pbz_generic.hip", "pbz_ops.hip", "pbz_fast.hip", "pbz_fast_lane.hip", "pbz_fast_quad16.hip",
            "pbz_fast_oct8.hip", "pbz_fast_cube16.hip", "pbz_wasserstein.hip", "pbz_tiled.hip", "pbz_static.hip", "pbz_copy.hip"]
 
@@ -58,6 +59,8 @@ def build(verbose: bool = False) -> str:
     _run([cc, "-x", "c", os.path.join(PKG, "examples", "c_abi_roundtrip.c"), "-D__HIP_PLATFORM_AMD__",
           "-I" + os.path.join(ROOT, "include"), "-I/opt/rocm/include", "-L" + PKG, "-lpbz", "-L/opt/rocm/lib",
           "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib", "-o", EXAMPLE])
+    # the memory-system yardsticks (no library code): what the box gives for the kernels' access patterns
+    _run([cc] + FLAGS[:-2] + [os.path.join(PKG, "examples", "memory_patterns.hip"), "-o", PATTERNS])
     return LIB
 
 
