@@ -117,6 +117,31 @@ __global__ __launch_bounds__(256) void k_lane(const u32x4* __restrict__ F, const
   }
 }
 
+// the compress direction of the same array: 32 load instructions per wave that each cover one contiguous KiB of the
+// array (non-temporal, as in the kernel), then F as eight contiguous KiB per wave and N
+__global__ __launch_bounds__(256) void k_lane_compress(const u32x4* __restrict__ x, u32x4* __restrict__ F,
+                                                       double* __restrict__ N) {
+  const int lane = threadIdx.x & 63;
+  const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  constexpr int64_t tiles_x = LGX / 64;
+  const int64_t tx = tile % tiles_x, by = (tile / tiles_x) % LGY, bz = tile / (tiles_x * LGY);
+  u32x4 w[32];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int z = r >> 2, yy = r & 3;
+    const u32x4* p = x + (bz * 4 + z) * kPlanePieces + ((by * 4 + yy) * LX + tx * 256) / 2 + 2 * (lane & 31) + (lane >> 5);
+    w[2 * r] = __builtin_nontemporal_load(p);
+    w[2 * r + 1] = __builtin_nontemporal_load(p + 64);
+  }
+  u32x4 acc = w[0];
+#pragma unroll
+  for (int i = 1; i < 32; ++i) acc ^= w[i];
+  const int64_t block0 = (bz * LGY + by) * LGX + tx * 64;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) F[block0 * 8 + k * 64 + lane] = acc + uint32_t(k);
+  N[block0 + lane] = double(acc.x);
+}
+
 template <bool kLoads, bool kStores, bool kHint, int kArrange>
 void lane_case(const char* what, const u32x4* F, const double* N, u32x4* y, uint32_t* sink) {
   const unsigned grid = unsigned(LGX * LGY * LGZ / 64 / 4);
@@ -215,6 +240,12 @@ int main() {
     lane_case<true, true, true, 2>("non-temporal, workgroup: 4 block rows, wave w on plane w", F, N, y, sink);
     lane_case<true, true, true, 3>("non-temporal, workgroup: 2 block rows x 2 halves, wave w on plane w", F, N, y, sink);
     lane_case<true, true, true, 0>("loads + stores, non-temporal stores (again)", F, N, y, sink);
+    {
+      const unsigned grid = unsigned(LGX * LGY * LGZ / 64 / 4);
+      const float ms = time_ms([&] { hipLaunchKernelGGL(k_lane_compress, dim3(grid), dim3(256), 0, 0, y, F, N); });
+      std::printf("lane 4x4x4 FP64   %-68s %.3f ms  %5.0f GB/s\n", "compress direction: array loads (1 GiB), F and N stores (272 MiB)",
+                  ms, (double(LGX * LGY * LGZ) * 136.0 + double(LX * LY * LZ) * 8.0) / ms / 1e6);
+    }
     CHECK(hipFree(F));
     CHECK(hipFree(N));
     CHECK(hipFree(y));
