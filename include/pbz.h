@@ -107,7 +107,7 @@ void pbz_codec_destroy(pbz_codec* codec);
 typedef enum PBZ_ENUM { PBZ_TRANSFORM_DCT = 0, PBZ_TRANSFORM_HAAR = 1 } pbz_transform;
 int pbz_codec_set_transform(pbz_codec* codec, pbz_transform transform);
 
-/* Force the slow fully general kernels (PBZ_PATH_GENERIC) instead of the specialised ones; for testing. */
+/* Force the general kernels (PBZ_PATH_GENERIC) instead of the ones specialised to a block shape; for testing. */
 int pbz_codec_set_kernel_path(pbz_codec* codec, pbz_kernel_path path);
 
 /* Sizes of the compressed form of an array of shape `shape` (host, ndim entries): number of blocks
