@@ -15,7 +15,8 @@
 //                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
 //                   then each lane holds four whole rows (row transform, and for 4x16x16 the transform across
 //                   the four planes); rows leave as 16-byte pieces in linear order.
-// Family "oct8":    8x8x8 blocks of bfloat16, FP16 or FP32 input (int8; FP32 input also int16 in FP64 arithmetic), 8 blocks per wave.  Each lane first holds one z-plane of
+// Family "oct8":    8x8x8 blocks of bfloat16, FP16 or FP32 input (int8; in FP64 arithmetic also FP32 input with int16 / int32
+//                   and FP64 input with int8 to int32), 8 blocks per wave.  Each lane first holds one z-plane of
 //                   a block (x and y transforms), the wave exchanges through LDS, then each lane holds one
 //                   y-row of all eight z-planes (z transform).  Decompression needs no exchange: every
 //                   lane rebuilds its own z-plane from the block's few kept coefficients; wide arrays use a

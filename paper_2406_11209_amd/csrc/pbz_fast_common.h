@@ -400,15 +400,8 @@ __device__ __forceinline__ double sum_of_squares(const uint32_t* w) {   // of th
 #pragma unroll
     for (int k = 0; k < kWords; ++k) acc = __builtin_amdgcn_sdot4(int(w[k]), int(w[k]), acc, false);
     return double(acc);
-  } else if constexpr (sizeof(IT) == 4) {
-    double acc = 0.0;       // squares of 32-bit indices reach 2^62: summed in FP64, like the reductions over such indices
-#pragma unroll
-    for (int k = 0; k < kWords; ++k) {
-      const double f = double(int32_t(w[k]));
-      acc += f * f;
-    }
-    return acc;
   } else {
+    static_assert(sizeof(IT) == 2, "exact integer sums: 8- and 16-bit indices only");
     long long acc = 0;      // one dword: 2 * 32767^2 < 2^31
 #pragma unroll
     for (int k = 0; k < kWords; ++k) {
@@ -418,6 +411,27 @@ __device__ __forceinline__ double sum_of_squares(const uint32_t* w) {   // of th
       acc += (long long)__builtin_amdgcn_sdot2(h, h, 0, false);
     }
     return double(acc);
+  }
+}
+
+// The same sum without the first index of w[0] when `skip_first` (the statistics take a block's first coefficient
+// separately, shifted by a pilot value).  8- and 16-bit indices: exact integer sum minus the exact square.  32-bit
+// indices: squares reach 2^62, so the sum is taken in FP64 and the first index, usually by far the largest, is left
+// out instead of being subtracted (the difference would cancel to nothing).
+template <typename IT, int kWords>
+__device__ __forceinline__ double sum_of_squares_rest(const uint32_t* w, bool skip_first) {
+  if constexpr (sizeof(IT) == 4) {
+    const double f0 = double(int32_t(w[0]));
+    double acc = skip_first ? 0.0 : f0 * f0;
+#pragma unroll
+    for (int k = 1; k < kWords; ++k) {
+      const double f = double(int32_t(w[k]));
+      acc += f * f;
+    }
+    return acc;
+  } else {
+    const double f0 = skip_first ? double(IdxPack<IT>::get(w[0], 0)) : 0.0;
+    return sum_of_squares<IT, kWords>(w) - f0 * f0;
   }
 }
 

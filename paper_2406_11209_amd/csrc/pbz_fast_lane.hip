@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void k_compress_lane(FastGeom g, const XT* __r
     const double f0 = double(IdxPack<IT>::get(w[0], 0));
     const double K = tile_pilot(n * f0);                      // lane 0 always holds a block of the array
     const double d = active ? n * f0 - K : 0.0;
-    emit_tile_sums(tile_sums, g, tx, by, bz, (sum_of_squares<IT, KW>(w) - f0 * f0) * (n * n), d * d, d,
+    emit_tile_sums(tile_sums, g, tx, by, bz, sum_of_squares_rest<IT, KW>(w, true) * (n * n), d * d, d,
                    active ? 1.0 : 0.0, K);
   }
   constexpr int P = KW / 4;                                   // 16-byte pieces of F per block

@@ -465,16 +465,44 @@ struct Oct8Kernel {
   }
 };
 // =====================================================================================================
-// 8x8x8 blocks of FP32 arrays with int16 indices: FP64 arithmetic, nothing pruned.  The same two layouts and the
-// same LDS slots as above; a slot holds two FP64 values, so the exchange takes four rounds (a quarter of every
-// 8-element row each) through the same 8 KiB per wave.  A row of eight indices is one 16-byte piece of F and the
-// eight lanes of a block write 128 contiguous bytes, so F needs no staging.
+// 8x8x8 blocks in FP64 arithmetic, nothing pruned: FP32 arrays with int16 or int32 indices, FP64 arrays with int8,
+// int16 or int32.  The same two layouts and the same LDS slots as above; a slot holds two FP64 values, so the
+// exchange takes four rounds (a quarter of every 8-element row each) through the same 8 KiB per wave.  A row of
+// eight indices is 8, 16 or 32 bytes of F and the eight lanes of a block write consecutive rows, so F needs no
+// staging.  A row of the array is two (FP32) or four (FP64) 16-byte pieces of a lane.
 // =====================================================================================================
-template <int TF, bool kRagged, bool kStats, bool kTailX>
-__global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8_i16(FastGeom g, const float* __restrict__ x,
-                                                                      void* __restrict__ N, int16_t* __restrict__ F,
-                                                                      double* __restrict__ tile_sums) {
+template <int kWords>
+__device__ __forceinline__ void store_words(void* dst, const uint32_t* w) {      // 2, 4 or 8 dwords, naturally aligned
+  if constexpr (kWords == 2) {
+    *static_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < kWords / 4; ++k)
+      static_cast<uint4*>(dst)[k] = make_uint4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
+  }
+}
+template <int kWords>
+__device__ __forceinline__ void load_words(const void* src, uint32_t* w) {
+  if constexpr (kWords == 2) {
+    const uint2 u = *static_cast<const uint2*>(src);
+    w[0] = u.x; w[1] = u.y;
+  } else {
+#pragma unroll
+    for (int k = 0; k < kWords / 4; ++k) {
+      const uint4 u = static_cast<const uint4*>(src)[k];
+      w[4 * k] = u.x; w[4 * k + 1] = u.y; w[4 * k + 2] = u.z; w[4 * k + 3] = u.w;
+    }
+  }
+}
+
+template <int TF, typename XT, typename IT, bool kRagged, bool kStats, bool kTailX>
+__global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8_wide(FastGeom g, const XT* __restrict__ x,
+                                                                       void* __restrict__ N, IT* __restrict__ F,
+                                                                       double* __restrict__ tile_sums) {
   using Slot = ExchangeSlot<double>;
+  constexpr int PER16 = Unpack<double, XT>::n;     // elements per 16-byte piece: 4 (FP32) or 2 (FP64)
+  constexpr int RV = 8 / PER16;                    // pieces per block row
+  constexpr int PER = IdxPack<IT>::per, RW = 8 / PER;       // indices per dword, dwords per row of eight indices
   __shared__ uint4 lds[kOctWaves][8 * 64];
   const int lane = threadIdx.x & 63;
   int64_t tx, by, bz;
@@ -493,33 +521,30 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8_i16(FastGeom g
       keep_z = zz < g.Z ? 0xffffffffu : 0u;      // planes / rows past the end: load a valid row, zero it below
       zz = zz < g.Z ? zz : g.Z - 1;
     }
-    uint4 raw[16];
+    uint4 raw[8 * RV];
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
       int64_t yy = by * 8 + yy0;
       if constexpr (kRagged) yy = yy < g.Y ? yy : g.Y - 1;
 #pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        const int64_t x0 = bxc * 8 + k * 4;
+      for (int k = 0; k < RV; ++k) {
+        const int64_t x0 = bxc * 8 + k * PER16;
         if constexpr (kTailX)
-          raw[yy0 * 2 + k] = load16_a4(x + (zz * g.Y + yy) * g.X + (x0 + 4 <= g.X ? x0 : g.X - 4));
+          raw[yy0 * RV + k] = load16_a4(x + (zz * g.Y + yy) * g.X + (x0 + PER16 <= g.X ? x0 : g.X - PER16));
         else
-          raw[yy0 * 2 + k] = load16_stream(x + (zz * g.Y + yy) * g.X + x0);
+          raw[yy0 * RV + k] = load16_stream(x + (zz * g.Y + yy) * g.X + x0);
       }
     }
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
 #pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        uint4& piece = raw[yy0 * 2 + k];
+      for (int k = 0; k < RV; ++k) {
+        uint4& piece = raw[yy0 * RV + k];
         if constexpr (kRagged) {
           const uint32_t keep = by * 8 + yy0 < g.Y ? keep_z : 0u;
           piece.x &= keep; piece.y &= keep; piece.z &= keep; piece.w &= keep;
         }
-        float f[4];
-        bits_f4(piece, f);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[yy0 * 8 + k * 4 + e] = double(f[e]);
+        Unpack<double, XT>::run(piece, v + yy0 * 8 + k * PER16);
       }
     }
     if constexpr (kTailX) {
@@ -528,11 +553,11 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8_i16(FastGeom g
         for (int yy0 = 0; yy0 < 8; ++yy0) {
           const int64_t yy = by * 8 + yy0;
           const bool row_in = yy < g.Y && keep_z != 0u;
-          const float* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+          const XT* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const int64_t xi = bxc * 8 + e;
-            const float val = row[xi < g.X ? xi : g.X - 1];
+            const XT val = row[xi < g.X ? xi : g.X - 1];
             v[yy0 * 8 + e] = row_in && xi < g.X ? double(val) : 0.0;
           }
         }
@@ -565,36 +590,65 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8_i16(FastGeom g
   const double inv = m > 0.0 ? g.r / m : 0.0;
   const int64_t block0 = (bz * g.gy + by) * g.gx + tx * 8;
   const bool inside = tx * 8 + bb < g.gx;
-  uint32_t w[32];
+  uint32_t w[8 * RW];
 #pragma unroll
   for (int zq = 0; zq < 8; ++zq)
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const uint32_t q2[2] = {bin_bits(u[zq * 8 + 2 * k], inv), bin_bits(u[zq * 8 + 2 * k + 1], inv)};
-      w[zq * 4 + k] = IdxPack<int16_t>::pack(q2);
+    for (int k = 0; k < RW; ++k) {
+      uint32_t q[PER];
+#pragma unroll
+      for (int e = 0; e < PER; ++e) q[e] = bin_bits(u[zq * 8 + k * PER + e], inv);
+      w[zq * RW + k] = IdxPack<IT>::pack(q);
     }
   if (inside) {
-    uint4* dst = reinterpret_cast<uint4*>(F + (block0 + bb) * 512) + j;            // row (kz, j) at dst[kz * 8]
+    IT* dst = F + (block0 + bb) * 512 + j * 8;                                     // row (kz, j) at dst + kz * 64
 #pragma unroll
-    for (int zq = 0; zq < 8; ++zq) dst[zq * 8] = make_uint4(w[zq * 4], w[zq * 4 + 1], w[zq * 4 + 2], w[zq * 4 + 3]);
+    for (int zq = 0; zq < 8; ++zq) store_words<RW>(dst + zq * 64, w + zq * RW);
     if (j == 0) store_float(N, g.ntype, block0 + bb, m);
   }
   if constexpr (kStats) {
     const double n = inside ? stored_N(m, g.ntype) : 0.0;
-    const double f0 = j == 0 ? double(IdxPack<int16_t>::get(w[0], 0)) : 0.0;
+    const double f0 = j == 0 ? double(IdxPack<IT>::get(w[0], 0)) : 0.0;
     const double K = tile_pilot(n * f0);                      // lane 0: row 0 of the tile's first block
     const bool has_first = j == 0 && inside;
     const double d = has_first ? n * f0 - K : 0.0;
-    emit_tile_sums(tile_sums, g, tx, by, bz, (sum_of_squares<int16_t, 32>(w) - f0 * f0) * (n * n), d * d, d,
+    emit_tile_sums(tile_sums, g, tx, by, bz, sum_of_squares_rest<IT, 8 * RW>(w, j == 0) * (n * n), d * d, d,
                    has_first ? 1.0 : 0.0, K);
   }
 }
 
-template <int TF, bool kTailX>
-__global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_i16(FastGeom g, const void* __restrict__ N,
-                                                                        const int16_t* __restrict__ F,
-                                                                        float* __restrict__ y) {
+// the eight FP64 values r8 of block bx's row at `row`, as the array's type
+template <typename XT, bool kTailX>
+__device__ __forceinline__ void oct_store_row_wide(const FastGeom& g, XT* row, int64_t bx, const double* r8) {
+  if constexpr (sizeof(XT) == 4) {
+    float f8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f8[e] = float(r8[e]);
+    oct_store_row<float, kTailX>(g, row, bx, f8);
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int64_t x0 = bx * 8 + k * 2;
+      if constexpr (kTailX) {
+        if (x0 + 2 <= g.X) {
+          store16_a4(row + x0, Pack<double, double>::run(r8 + 2 * k));
+        } else if (x0 < g.X) {
+          row[x0] = r8[2 * k];
+        }
+      } else {
+        // four pieces per lane, 64 bytes apart: plain stores, which the L2 merges into whole lines
+        *reinterpret_cast<uint4*>(row + x0) = Pack<double, double>::run(r8 + 2 * k);
+      }
+    }
+  }
+}
+
+template <int TF, typename XT, typename IT, bool kTailX>
+__global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_wide(FastGeom g, const void* __restrict__ N,
+                                                                         const IT* __restrict__ F,
+                                                                         XT* __restrict__ y) {
   using Slot = ExchangeSlot<double>;
+  constexpr int PER = IdxPack<IT>::per, RW = 8 / PER;
   __shared__ uint4 lds[kOctWaves][8 * 64];
   const int lane = threadIdx.x & 63;
   int64_t tx, by, bz;
@@ -608,16 +662,15 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_i16(FastGeom
   {
     // a block past the end of the row: decode the row's last block again; nothing of it is stored
     const int64_t blk = tx * 8 + bb < g.gx ? bb : g.gx - 1 - tx * 8;
-    const uint4* rows = reinterpret_cast<const uint4*>(F + (block0 + blk) * 512) + j;
-    uint4 f[8];
+    const IT* rows = F + (block0 + blk) * 512 + j * 8;
+    uint32_t fw[8][RW];
 #pragma unroll
-    for (int kz = 0; kz < 8; ++kz) f[kz] = rows[kz * 8];
+    for (int kz = 0; kz < 8; ++kz) load_words<RW>(rows + kz * 64, fw[kz]);
     const double scale = load_float<double>(N, g.ntype, block0 + blk) / g.r;          // Algorithm 3: N F / r
 #pragma unroll
     for (int kz = 0; kz < 8; ++kz) {
-      const uint32_t fw[4] = {f[kz].x, f[kz].y, f[kz].z, f[kz].w};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) u[kz * 8 + e] = scale * double(IdxPack<int16_t>::get(fw[e >> 1], e & 1));
+      for (int e = 0; e < 8; ++e) u[kz * 8 + e] = scale * double(IdxPack<IT>::get(fw[kz][e / PER], e % PER));
     }
 #pragma unroll
     for (int xx = 0; xx < 8; ++xx) tf_inverse<TF, double, 8, 8, 8>(u + xx);
@@ -638,26 +691,54 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_i16(FastGeom
   for (int yy0 = 0; yy0 < 8; ++yy0) tf_inverse<TF, double, 8, 1, 8>(v + yy0 * 8);
   const int64_t bx = tx * 8 + b;
   const int64_t zz = bz * 8 + z;
-  if (bx < g.gx && zz < g.Z) {
+  if constexpr (!kTailX) {
+    // A row of a block is two (FP32) or four (FP64) 16-byte pieces, 32 or 64 bytes apart from the next lane's:
+    // stored as they are, an instruction would write every second or fourth piece of the run that the eight blocks
+    // of a plane have in a row (measured, 512 x 512 x 256 FP64: 3.0 TB/s moved).  The rows go through the wave's LDS
+    // instead, 512 pieces per round: lane (z, b) writes pieces P = RV b + k of its rows, and on the way out 8 RV
+    // consecutive lanes take one row's pieces in order, so that an instruction stores two or four whole 256- or
+    // 512-byte rows, with the non-temporal hint (6.7 TB/s).  Slot P ^ (P / 8) keeps every eight consecutive lanes in
+    // distinct 16-byte slots modulo 8 in both directions.
+    constexpr int PER16 = 16 / int(sizeof(XT)), RV = 8 / PER16;      // elements per piece, pieces per block row
+    constexpr int kRowsPerRound = 512 / (64 * RV);
+#pragma unroll
+    for (int round = 0; round < 8 / kRowsPerRound; ++round) {
+#pragma unroll
+      for (int h = 0; h < kRowsPerRound; ++h)
+#pragma unroll
+        for (int k = 0; k < RV; ++k) {
+          const int P = b * RV + k;
+          st[(h * 8 + z) * (8 * RV) + (P ^ (P >> 3))] = Pack<double, XT>::run(v + (round * kRowsPerRound + h) * 8 + PER16 * k);
+        }
+      wave_lds_sync();
+      constexpr int kLanesPerRow = 8 * RV, kRowsPerInst = 64 / kLanesPerRow;
+#pragma unroll
+      for (int i = 0; i < kRowsPerRound * 8 / kRowsPerInst; ++i) {
+        const int rr = i * kRowsPerInst + lane / kLanesPerRow, P = lane % kLanesPerRow;      // row (h, z) of the round
+        const int64_t yy = by * 8 + round * kRowsPerRound + rr / 8, zr = bz * 8 + rr % 8;
+        const uint4 piece = st[rr * kLanesPerRow + (P ^ (P >> 3))];
+        if (tx * 8 + P / RV < g.gx && zr < g.Z && yy < g.Y)
+          store16_stream(y + (zr * g.Y + yy) * g.X + tx * 64 + P * PER16, piece);
+      }
+      wave_lds_sync();
+    }
+  } else if (bx < g.gx && zz < g.Z) {
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
       const int64_t yy = by * 8 + yy0;
-      if (yy < g.Y) {
-        float r8[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) r8[e] = float(v[yy0 * 8 + e]);
-        oct_store_row<float, kTailX>(g, y + (zz * g.Y + yy) * g.X, bx, r8);
-      }
+      if (yy < g.Y) oct_store_row_wide<XT, kTailX>(g, y + (zz * g.Y + yy) * g.X, bx, v + yy0 * 8);
     }
   }
 }
 
-template <int TF>
-struct Oct8I16Kernel {
+template <int TF, typename XT, typename IT>
+struct Oct8WideKernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && c->transform == TF && c->compute_f64 && xtype == PBZ_F32 && c->itype == PBZ_I16 &&
-           c->ftype != PBZ_F64 && f.bz == 8 && f.by == 8 && f.bx == 8 && f.kz == 8 && f.ky == 8 && f.kx == 8 &&
-           x_extent_ok(f, 4, 4);
+    // FP32 arrays: N in FP32 or a 16-bit type (with FP64 N the working type is FP64 and the array FP32: not built);
+    // FP64 arrays: any N.  int8 with an FP32 array computes in FP32 and belongs to the kernels above.
+    return f.ok && c->transform == TF && c->compute_f64 && xtype == xtype_code<XT>() &&
+           int(c->itype) == itype_code<IT>() && (sizeof(XT) == 8 || c->ftype != PBZ_F64) && f.bz == 8 && f.by == 8 &&
+           f.bx == 8 && f.kz == 8 && f.ky == 8 && f.kx == 8 && x_extent_ok(f, 16 / int(sizeof(XT)), int(sizeof(XT)));
   }
   static int fits(FastGeom g) {
     dim3 grid;
@@ -669,8 +750,8 @@ struct Oct8I16Kernel {
   }
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_oct8_i16<TF, kRagged, kStats, kTailX>), grid, dim3(kOctWaves * 64), 0, s, g,
-                       static_cast<const float*>(x), N, static_cast<int16_t*>(F), tile_sums);
+    hipLaunchKernelGGL((k_compress_oct8_wide<TF, XT, IT, kRagged, kStats, kTailX>), grid, dim3(kOctWaves * 64), 0, s, g,
+                       static_cast<const XT*>(x), N, static_cast<IT*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
@@ -685,11 +766,11 @@ struct Oct8I16Kernel {
     dim3 grid;
     if (!tile_grid(g, 8, kOctWaves, &grid)) return 0;
     if (g.X % 8)
-      hipLaunchKernelGGL((k_decompress_oct8_i16<TF, true>), grid, dim3(kOctWaves * 64), 0, s, g, N,
-                         static_cast<const int16_t*>(F), static_cast<float*>(y));
+      hipLaunchKernelGGL((k_decompress_oct8_wide<TF, XT, IT, true>), grid, dim3(kOctWaves * 64), 0, s, g, N,
+                         static_cast<const IT*>(F), static_cast<XT*>(y));
     else
-      hipLaunchKernelGGL((k_decompress_oct8_i16<TF, false>), grid, dim3(kOctWaves * 64), 0, s, g, N,
-                         static_cast<const int16_t*>(F), static_cast<float*>(y));
+      hipLaunchKernelGGL((k_decompress_oct8_wide<TF, XT, IT, false>), grid, dim3(kOctWaves * 64), 0, s, g, N,
+                         static_cast<const IT*>(F), static_cast<XT*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
@@ -700,6 +781,11 @@ template <int TF> using Oct8_f32_box4 = Oct8Kernel<TF, float, 4, 4, 4>;
 template <int TF> using Oct8_f32_full = Oct8Kernel<TF, float, 8, 8, 8>;
 template <int TF> using Oct8_f16_box4 = Oct8Kernel<TF, f16_t, 4, 4, 4>;
 template <int TF> using Oct8_f16_full = Oct8Kernel<TF, f16_t, 8, 8, 8>;
+template <int TF> using Oct8_f32_i16 = Oct8WideKernel<TF, float, int16_t>;
+template <int TF> using Oct8_f32_i32 = Oct8WideKernel<TF, float, int32_t>;
+template <int TF> using Oct8_f64_i8 = Oct8WideKernel<TF, double, int8_t>;
+template <int TF> using Oct8_f64_i16 = Oct8WideKernel<TF, double, int16_t>;
+template <int TF> using Oct8_f64_i32 = Oct8WideKernel<TF, double, int32_t>;
 
 #define PBZ_ROWS(X, TF, SUFFIX) \
   X(Oct8_box4<TF>, "oct8_bf16_8x8x8_i8_box4x4x4" SUFFIX) \
@@ -708,7 +794,11 @@ template <int TF> using Oct8_f16_full = Oct8Kernel<TF, f16_t, 8, 8, 8>;
   X(Oct8_f32_full<TF>, "oct8_f32_8x8x8_i8" SUFFIX) \
   X(Oct8_f16_box4<TF>, "oct8_f16_8x8x8_i8_box4x4x4" SUFFIX) \
   X(Oct8_f16_full<TF>, "oct8_f16_8x8x8_i8" SUFFIX) \
-  X(Oct8I16Kernel<TF>, "oct8_f32_8x8x8_i16" SUFFIX)
+  X(Oct8_f32_i16<TF>, "oct8_f32_8x8x8_i16" SUFFIX) \
+  X(Oct8_f32_i32<TF>, "oct8_f32_8x8x8_i32" SUFFIX) \
+  X(Oct8_f64_i8<TF>, "oct8_f64_8x8x8_i8" SUFFIX) \
+  X(Oct8_f64_i16<TF>, "oct8_f64_8x8x8_i16" SUFFIX) \
+  X(Oct8_f64_i32<TF>, "oct8_f64_8x8x8_i32" SUFFIX)
 
 }  // namespace
 

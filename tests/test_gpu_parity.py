@@ -234,6 +234,17 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((17, 9, 200), (8, 8, 8), 16, "f32", "f32", None, "oct8_f32_8x8x8_i16"),
                ((9, 12, 398), (8, 8, 8), 16, "f32", "f16", None, "oct8_f32_8x8x8_i16"),
                ((9, 17, 21), (8, 8, 8), 16, "f32", "bf16", None, "oct8_f32_8x8x8_i16"),
+               # 8x8x8 blocks of FP64 arrays (FP64 arithmetic, int8 to int32), and int32 indices on FP32 arrays
+               ((16, 8, 64), (8, 8, 8), 16, "f64", "f64", None, "oct8_f64_8x8x8_i16"),
+               ((17, 9, 200), (8, 8, 8), 16, "f64", "f64", None, "oct8_f64_8x8x8_i16"),
+               ((9, 12, 395), (8, 8, 8), 16, "f64", "f32", None, "oct8_f64_8x8x8_i16"),
+               ((9, 17, 21), (8, 8, 8), 8, "f64", "f64", None, "oct8_f64_8x8x8_i8"),
+               ((16, 16, 136), (8, 8, 8), 8, "f64", "f64", None, "oct8_f64_8x8x8_i8"),
+               ((17, 9, 72), (8, 8, 8), 32, "f64", "f64", None, "oct8_f64_8x8x8_i32"),
+               ((8, 9, 67), (8, 8, 8), 32, "f64", "f64", None, "oct8_f64_8x8x8_i32"),
+               ((17, 9, 72), (8, 8, 8), 32, "f32", "f32", None, "oct8_f32_8x8x8_i32"),
+               ((9, 12, 398), (8, 8, 8), 32, "f32", "f16", None, "oct8_f32_8x8x8_i32"),
+               ((9, 17, 21), (8, 8, 8), 32, "f32", "f32", None, "oct8_f32_8x8x8_i32"),
                # int16 indices (FP64 arithmetic) in 16x16 and 4x16x16 blocks
                ((3, 33, 48), (1, 16, 16), 16, "f32", "f32", None, "quad16_f32_16x16_i16"),
                ((40, 1046), (16, 16), 16, "f32", "f16", None, "quad16_f32_16x16_i16"),
@@ -287,6 +298,8 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((3, 33, 96), (1, 16, 16), 8, "f16", "f32", None, "quad16_f16_16x16_i8_haar"),
         ((9, 6, 26), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4_haar"),
         ((17, 9, 72), (8, 8, 8), 16, "f32", "f32", None, "oct8_f32_8x8x8_i16_haar"),
+        ((17, 9, 70), (8, 8, 8), 16, "f64", "f64", None, "oct8_f64_8x8x8_i16_haar"),
+        ((9, 16, 24), (8, 8, 8), 8, "f64", "f64", None, "oct8_f64_8x8x8_i8_haar"),
         ((3, 33, 96), (1, 16, 16), 16, "f32", "f32", None, "quad16_f32_16x16_i16_haar"),
         ((9, 20, 37), (4, 16, 16), 16, "f32", "f32", None, "quad16_f32_4x16x16_i16_haar"),
         ((20, 37, 64), (16, 16, 16), 16, "f32", "f32", None, "cube16_f32_16x16x16_i16_haar"),
@@ -709,7 +722,8 @@ def test_variance_of_a_field_with_a_large_offset():
     # the last two: a block's indices are 3 and 512 sixteen-byte vectors, so which thread of the reduction meets a
     # block's first vector changes from step to step
     for block, bits, mask in (((4, 4, 4), 16, None), ((8, 8, 8), 32, None), ((2, 4, 3 + 1), 16, None),
-                              ((1, 8, 8), 8, six_rows), ((4, 32, 32), 16, None)):
+                              ((1, 8, 8), 8, six_rows), ((4, 32, 32), 16, None), ((4, 4, 4), 32, None),
+                              ((1, 8, 8), 32, None), ((8, 8, 8), 16, None), ((2, 8, 8), 32, None)):
         case = Case(a, b, "f64", block, bits, "f64", mask)
         N1, F1 = case.codec.compress(case.xA)
         N2, F2 = case.codec.compress(case.xB)

@@ -232,6 +232,11 @@ DISPATCH = [
     ((8, 8, 8), "f32", "i8", None, (17, 9, 24), "f16", "oct8_f16_8x8x8_i8"),
     ((8, 8, 8), "f32", "i16", None, (17, 9, 21), "f32", "oct8_f32_8x8x8_i16"),
     ((8, 8, 8), "f16", "i16", None, (16, 16, 64), "f32", "oct8_f32_8x8x8_i16"),
+    ((8, 8, 8), "f32", "i32", None, (17, 9, 21), "f32", "oct8_f32_8x8x8_i32"),
+    ((8, 8, 8), "f64", "i8", None, (16, 16, 16), "f64", "oct8_f64_8x8x8_i8"),
+    ((8, 8, 8), "f64", "i16", None, (512, 512, 256), "f64", "oct8_f64_8x8x8_i16"),
+    ((8, 8, 8), "f32", "i16", None, (17, 9, 23), "f64", "oct8_f64_8x8x8_i16"),             # FP64 array, FP32 N
+    ((8, 8, 8), "f64", "i32", None, (17, 9, 23), "f64", "oct8_f64_8x8x8_i32"),
     ((16, 16), "f32", "i16", None, (64, 64), "f32", "quad16_f32_16x16_i16"),
     ((1, 16, 16), "f16", "i16", None, (5, 33, 50), "f32", "quad16_f32_16x16_i16"),
     ((4, 16, 16), "f32", "i16", None, (9, 20, 38), "f32", "quad16_f32_4x16x16_i16"),
@@ -249,7 +254,8 @@ DISPATCH = [
     ((8, 8), "f64", "i16", None, (64, 64), "f32", "generic"),                              # FP32 array, FP64 N
     ((16, 16), "f32", "i16", None, (64, 64), "f16", "generic"),                            # 16-bit array, int16
     ((8, 8, 8), "f32", "i8", (2, 2, 2), (16, 16, 16), "f32", "generic"),                   # another mask
-    ((8, 8, 8), "f64", "i8", None, (16, 16, 16), "f64", "generic"),
+    ((8, 8, 8), "f32", "i8", None, (16, 16, 16), "f64", "generic"),                        # FP64 array, FP32 arithmetic
+    ((8, 8, 8), "f64", "i16", None, (16, 16, 16), "f32", "generic"),                       # FP32 array, FP64 N
     ((8, 8, 8), "f32", "i16", (4, 4, 4), (16, 16, 16), "f32", "generic"),                  # int16 with a box
     ((8, 8, 8), "f32", "i16", None, (16, 16, 16), "bf16", "generic"),                      # int16, 16-bit array
     ((16, 16, 16), "f64", "i16", None, (40, 40, 66), "f64", "generic"),
