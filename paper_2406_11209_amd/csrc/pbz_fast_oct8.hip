@@ -221,6 +221,45 @@ __device__ __forceinline__ void oct_store_row(const FastGeom& g, XT* row, int64_
   }
 }
 
+// Rows of 32-bit or 64-bit elements.  A row of a block is two (FP32) or four (FP64) 16-byte pieces, 32 or 64 bytes
+// apart from the next lane's: stored as they are, an instruction would write every second or fourth piece of the
+// run that the eight blocks of a plane have in a row (measured, 512 x 512 x 256 FP64: 3.0 TB/s moved).  Here the
+// finished planes v (lane = (plane z, block b), 64 values of type T each) go through the wave's 8 KiB of LDS
+// instead, 512 pieces per round: lane (z, b) writes pieces P = RV b + k of its rows, and on the way out 8 RV
+// consecutive lanes take one row's pieces in order, so that an instruction stores two or four whole 256- or
+// 512-byte rows, with the non-temporal hint (6.7 TB/s).  Slot P ^ (P / 8) keeps every eight consecutive lanes in
+// distinct 16-byte slots modulo 8 in both directions.  Whole rows only (X a multiple of 8); blocks, rows and
+// planes past the array's end are left out.
+template <typename T, typename XT>
+__device__ __forceinline__ void oct_store_rows_through_lds(const FastGeom& g, uint4* st, XT* __restrict__ y, int64_t tx,
+                                                           int64_t by, int64_t bz, int lane, const T* v) {
+  constexpr int PER16 = 16 / int(sizeof(XT)), RV = 8 / PER16;      // elements per piece, pieces per block row
+  static_assert(RV == 2 || RV == 4, "16-bit rows are one piece per block and contiguous as they are");
+  constexpr int kRowsPerRound = 512 / (64 * RV);
+  constexpr int kLanesPerRow = 8 * RV, kRowsPerInst = 64 / kLanesPerRow;
+  const int z = lane >> 3, b = lane & 7;
+#pragma unroll
+  for (int round = 0; round < 8 / kRowsPerRound; ++round) {
+#pragma unroll
+    for (int h = 0; h < kRowsPerRound; ++h)
+#pragma unroll
+      for (int k = 0; k < RV; ++k) {
+        const int P = b * RV + k;
+        st[(h * 8 + z) * kLanesPerRow + (P ^ (P >> 3))] = Pack<T, XT>::run(v + (round * kRowsPerRound + h) * 8 + PER16 * k);
+      }
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < kRowsPerRound * 8 / kRowsPerInst; ++i) {
+      const int rr = i * kRowsPerInst + lane / kLanesPerRow, P = lane % kLanesPerRow;      // row (h, z) of the round
+      const int64_t yy = by * 8 + round * kRowsPerRound + rr / 8, zr = bz * 8 + rr % 8;
+      const uint4 piece = st[rr * kLanesPerRow + (P ^ (P >> 3))];
+      if (tx * 8 + P / RV < g.gx && zr < g.Z && yy < g.Y)
+        store16_stream(y + (zr * g.Y + yy) * g.X + tx * 64 + P * PER16, piece);
+    }
+    wave_lds_sync();
+  }
+}
+
 template <int TF, typename XT, int KZ, int KY, int KX, bool kTailX = false>
 __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const void* __restrict__ N,
                                                          const int8_t* __restrict__ F, XT* __restrict__ y) {
@@ -276,7 +315,8 @@ __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const void*
 // 512 indices, eight times the work.  This variant mirrors the compress kernel instead: lane = (block bb, row j)
 // takes row j of all eight coefficient planes (eight 8-byte pieces of F), transforms back along z, the wave
 // exchanges through LDS (the same slots and two half rounds as compress), then lane = (plane z, block b)
-// transforms back along y and x and stores its plane.  512 x 512 x 1024: FP32 0.458 -> 0.338 ms, bfloat16 0.395 -> 0.144 ms.
+// transforms back along y and x and stores its plane.  512 x 512 x 1024: FP32 0.458 -> 0.338 ms, bfloat16 0.395 -> 0.144 ms;
+// FP32 rows regrouped through LDS before they are stored: 0.338 -> 0.214 ms.
 template <int TF, typename XT, bool kTailX>
 __global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_full(FastGeom g, const void* __restrict__ N,
                                                                          const int8_t* __restrict__ F,
@@ -325,6 +365,10 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_full(FastGeo
   for (int xx = 0; xx < 8; ++xx) tf_inverse<TF, float, 8, 8, 8>(v + xx);
 #pragma unroll
   for (int yy0 = 0; yy0 < 8; ++yy0) tf_inverse<TF, float, 8, 1, 8>(v + yy0 * 8);
+  if constexpr (sizeof(XT) == 4 && !kTailX) {
+    oct_store_rows_through_lds<float, XT>(g, st, y, tx, by, bz, lane, v);
+    return;
+  }
   const int z = lane >> 3, b = lane & 7;
   const int64_t bx = tx * 8 + b;
   const int64_t zz = bz * 8 + z;
@@ -692,36 +736,7 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_wide(FastGeo
   const int64_t bx = tx * 8 + b;
   const int64_t zz = bz * 8 + z;
   if constexpr (!kTailX) {
-    // A row of a block is two (FP32) or four (FP64) 16-byte pieces, 32 or 64 bytes apart from the next lane's:
-    // stored as they are, an instruction would write every second or fourth piece of the run that the eight blocks
-    // of a plane have in a row (measured, 512 x 512 x 256 FP64: 3.0 TB/s moved).  The rows go through the wave's LDS
-    // instead, 512 pieces per round: lane (z, b) writes pieces P = RV b + k of its rows, and on the way out 8 RV
-    // consecutive lanes take one row's pieces in order, so that an instruction stores two or four whole 256- or
-    // 512-byte rows, with the non-temporal hint (6.7 TB/s).  Slot P ^ (P / 8) keeps every eight consecutive lanes in
-    // distinct 16-byte slots modulo 8 in both directions.
-    constexpr int PER16 = 16 / int(sizeof(XT)), RV = 8 / PER16;      // elements per piece, pieces per block row
-    constexpr int kRowsPerRound = 512 / (64 * RV);
-#pragma unroll
-    for (int round = 0; round < 8 / kRowsPerRound; ++round) {
-#pragma unroll
-      for (int h = 0; h < kRowsPerRound; ++h)
-#pragma unroll
-        for (int k = 0; k < RV; ++k) {
-          const int P = b * RV + k;
-          st[(h * 8 + z) * (8 * RV) + (P ^ (P >> 3))] = Pack<double, XT>::run(v + (round * kRowsPerRound + h) * 8 + PER16 * k);
-        }
-      wave_lds_sync();
-      constexpr int kLanesPerRow = 8 * RV, kRowsPerInst = 64 / kLanesPerRow;
-#pragma unroll
-      for (int i = 0; i < kRowsPerRound * 8 / kRowsPerInst; ++i) {
-        const int rr = i * kRowsPerInst + lane / kLanesPerRow, P = lane % kLanesPerRow;      // row (h, z) of the round
-        const int64_t yy = by * 8 + round * kRowsPerRound + rr / 8, zr = bz * 8 + rr % 8;
-        const uint4 piece = st[rr * kLanesPerRow + (P ^ (P >> 3))];
-        if (tx * 8 + P / RV < g.gx && zr < g.Z && yy < g.Y)
-          store16_stream(y + (zr * g.Y + yy) * g.X + tx * 64 + P * PER16, piece);
-      }
-      wave_lds_sync();
-    }
+    oct_store_rows_through_lds<double, XT>(g, st, y, tx, by, bz, lane, v);
   } else if (bx < g.gx && zz < g.Z) {
 #pragma unroll
     for (int yy0 = 0; yy0 < 8; ++yy0) {
