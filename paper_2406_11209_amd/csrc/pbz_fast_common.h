@@ -316,6 +316,60 @@ struct Quad4Half {                      // XT = bf16_t or f16_t
 };
 template <> struct Quad4<bf16_t> : Quad4Half<bf16_t> {};
 template <> struct Quad4<f16_t> : Quad4Half<f16_t> {};
+struct U4x2 { uint4 lo, hi; };
+template <>
+struct Quad4<double> {                  // four FP64 elements: two 16-byte pieces
+  typedef U4x2 raw_t;
+  template <bool kTailX>
+  static __device__ __forceinline__ raw_t load(const double* p) {
+    raw_t r;
+    r.lo = kTailX ? load16_a4(p) : load16_stream(p);
+    r.hi = kTailX ? load16_a4(p + 2) : load16_stream(p + 2);
+    return r;
+  }
+  template <bool kTailX>
+  static __device__ __forceinline__ void store(double* p, const raw_t& r) {
+    if constexpr (kTailX) {
+      store16_a4(p, r.lo);
+      store16_a4(p + 2, r.hi);
+    } else {
+      // two pieces per lane, 32 bytes apart: plain stores, which the L2 merges into whole lines
+      *reinterpret_cast<uint4*>(p) = r.lo;
+      *reinterpret_cast<uint4*>(p + 2) = r.hi;
+    }
+  }
+  static __device__ __forceinline__ void keep(raw_t& r, uint32_t m) {
+    r.lo.x &= m; r.lo.y &= m; r.lo.z &= m; r.lo.w &= m;
+    r.hi.x &= m; r.hi.y &= m; r.hi.z &= m; r.hi.w &= m;
+  }
+};
+// four elements of the array as values of the arithmetic type T, and back (one rounding from T to XT)
+template <typename T, typename XT>
+__device__ __forceinline__ void quad4_unpack(const typename Quad4<XT>::raw_t& r, T* v) {
+  if constexpr (sizeof(XT) == 8) {
+    Unpack<T, double>::run(r.lo, v);
+    Unpack<T, double>::run(r.hi, v + 2);
+  } else {
+    float f[4];
+    Quad4<XT>::unpack(r, f);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = T(f[e]);
+  }
+}
+template <typename T, typename XT>
+__device__ __forceinline__ typename Quad4<XT>::raw_t quad4_pack(const T* v) {
+  if constexpr (sizeof(XT) == 8) {
+    typename Quad4<XT>::raw_t r;
+    r.lo = Pack<T, double>::run(v);
+    r.hi = Pack<T, double>::run(v + 2);
+    return r;
+  } else {
+    float f[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) f[e] = float(v[e]);
+    return Quad4<XT>::pack(f);
+  }
+}
 
 template <typename T, typename XT>
 struct Elem {   // one element: float and double arrays
@@ -361,24 +415,24 @@ __device__ __forceinline__ double stored_N(T m, int ntype) {
   }
 }
 // kCount values of N at once: one switch around all the loads, so that they are in flight together
-template <int kCount>
-__device__ __forceinline__ void load_N_many(const void* N, int ntype, const int64_t* idx, float* out) {
+template <int kCount, typename T>
+__device__ __forceinline__ void load_N_many(const void* N, int ntype, const int64_t* idx, T* out) {
   switch (ntype) {
     case PBZ_F32:
 #pragma unroll
-      for (int i = 0; i < kCount; ++i) out[i] = static_cast<const float*>(N)[idx[i]];
+      for (int i = 0; i < kCount; ++i) out[i] = T(static_cast<const float*>(N)[idx[i]]);
       break;
     case PBZ_BF16:
 #pragma unroll
-      for (int i = 0; i < kCount; ++i) out[i] = bf16_bits_to_float(static_cast<const uint16_t*>(N)[idx[i]]);
+      for (int i = 0; i < kCount; ++i) out[i] = T(bf16_bits_to_float(static_cast<const uint16_t*>(N)[idx[i]]));
       break;
     case PBZ_F16:
 #pragma unroll
-      for (int i = 0; i < kCount; ++i) out[i] = float(static_cast<const _Float16*>(N)[idx[i]]);
+      for (int i = 0; i < kCount; ++i) out[i] = T(float(static_cast<const _Float16*>(N)[idx[i]]));
       break;
     default:
 #pragma unroll
-      for (int i = 0; i < kCount; ++i) out[i] = float(static_cast<const double*>(N)[idx[i]]);
+      for (int i = 0; i < kCount; ++i) out[i] = T(static_cast<const double*>(N)[idx[i]]);
       break;
   }
 }

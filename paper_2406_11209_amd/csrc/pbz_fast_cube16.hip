@@ -6,8 +6,9 @@ namespace fast {
 namespace {
 
 // =====================================================================================================
-// Family "cube16": 16 x 16 x 16 blocks of FP32 arrays, nothing pruned; int16 indices with FP64 arithmetic (the
-// setting of the paper's fission-density experiment, Sec. V) or int8 indices with FP32 arithmetic
+// Family "cube16": 16 x 16 x 16 blocks, nothing pruned.  FP32 arrays with int16 indices in FP64 arithmetic (the
+// setting of the paper's fission-density experiment, Sec. V), with int32 likewise, or with int8 in FP32
+// arithmetic; FP64 arrays with int8 to int32 in FP64 arithmetic (a lane's four columns are then two 16-byte pieces)
 // =====================================================================================================
 // A workgroup of two waves owns two blocks that are neighbours along x; wave w ends up with block w (4096 values,
 // 64 per lane).  The values pass through three layouts, one per transformed dimension, with an LDS exchange
@@ -106,10 +107,10 @@ __device__ __forceinline__ void cube_exchange_zx(uint4* st, int lane, const T* f
   }
 }
 
-template <int TF, typename T, typename IT, bool kRagged, bool kStats, bool kTailX>
-__global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float* __restrict__ x, void* __restrict__ N,
+template <int TF, typename T, typename IT, typename XT, bool kRagged, bool kStats, bool kTailX>
+__global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const XT* __restrict__ x, void* __restrict__ N,
                                                          IT* __restrict__ F, double* __restrict__ tile_sums) {
-  using Q4 = Quad4<float>;
+  using Q4 = Quad4<XT>;
   constexpr int PER = IdxPack<IT>::per;            // indices per dword
   constexpr int ROWW = 16 / PER;                   // dwords per row of 16 indices
   __shared__ uint4 lds[2 * kCubeSlots];
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float
       keep_z = zz < g.Z ? 0xffffffffu : 0u;        // planes past the end: load a valid one, zero it below
       zz = zz < g.Z ? zz : g.Z - 1;
     }
-    Q4::raw_t raw[16];
+    typename Q4::raw_t raw[16];
     const int64_t x_first = bxl * 16 + q * 4;
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
@@ -145,10 +146,7 @@ __global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       if constexpr (kRagged) Q4::keep(raw[yy0], by * 16 + yy0 < g.Y ? keep_z : 0u);
-      float f[4];
-      Q4::unpack(raw[yy0], f);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) a[yy0 * 4 + e] = T(f[e]);
+      quad4_unpack<T, XT>(raw[yy0], a + yy0 * 4);
     }
     if constexpr (kTailX) {
       if (x_first + 4 > g.X) {           // a piece of the row's last, partial block: element by element, zeros beyond
@@ -156,11 +154,11 @@ __global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float
         for (int yy0 = 0; yy0 < 16; ++yy0) {
           const int64_t yy = by * 16 + yy0;
           const bool row_in = yy < g.Y && keep_z != 0u;
-          const float* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
+          const XT* row = x + (zz * g.Y + (yy < g.Y ? yy : g.Y - 1)) * g.X;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int64_t xi = x_first + e;
-            const float val = row[xi < g.X ? xi : g.X - 1];
+            const XT val = row[xi < g.X ? xi : g.X - 1];
             a[yy0 * 4 + e] = row_in && xi < g.X ? T(val) : T(0);
           }
         }
@@ -209,7 +207,7 @@ __global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float
   if constexpr (kStats) {
     const double n = stored_N(m, g.ntype);
     const double f0 = lane == 0 ? double(IdxPack<IT>::get(w[0], 0)) : 0.0;
-    const double rest = (sum_of_squares<IT, 4 * ROWW>(w) - f0 * f0) * (n * n);
+    const double rest = sum_of_squares_rest<IT, 4 * ROWW>(w, lane == 0) * (n * n);
     const double K = tile_pilot(n * f0);           // one record per block: its first coefficient is the pilot value
     FastGeom per_block = g;                        // records are indexed by block, not by pair
     per_block.tiles_x = uint32_t(g.gx);
@@ -218,10 +216,10 @@ __global__ __launch_bounds__(128) void k_compress_cube16(FastGeom g, const float
   }
 }
 
-template <int TF, typename T, typename IT, bool kTailX>
+template <int TF, typename T, typename IT, typename XT, bool kTailX>
 __global__ __launch_bounds__(128) void k_decompress_cube16(FastGeom g, const void* __restrict__ N,
-                                                           const IT* __restrict__ F, float* __restrict__ y) {
-  using Q4 = Quad4<float>;
+                                                           const IT* __restrict__ F, XT* __restrict__ y) {
+  using Q4 = Quad4<XT>;
   constexpr int PER = IdxPack<IT>::per;
   constexpr int ROWW = 16 / PER;
   __shared__ uint4 lds[2 * kCubeSlots];
@@ -276,33 +274,30 @@ __global__ __launch_bounds__(128) void k_decompress_cube16(FastGeom g, const voi
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       const int64_t yy = by * 16 + yy0;
       if (yy < g.Y) {
-        float f[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) f[e] = float(a[yy0 * 4 + e]);
-        float* row = y + (zz * g.Y + yy) * g.X;
+        XT* row = y + (zz * g.Y + yy) * g.X;
         const int64_t x0 = bxl * 16 + q * 4;
         if constexpr (kTailX) {
           if (x0 + 4 <= g.X) {
-            Q4::template store<true>(row + x0, Q4::pack(f));
+            Q4::template store<true>(row + x0, quad4_pack<T, XT>(a + yy0 * 4));
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (x0 + e < g.X) row[x0 + e] = f[e];
+              if (x0 + e < g.X) row[x0 + e] = XT(a[yy0 * 4 + e]);
           }
         } else {
-          Q4::template store<false>(row + x0, Q4::pack(f));
+          Q4::template store<false>(row + x0, quad4_pack<T, XT>(a + yy0 * 4));
         }
       }
     }
   }
 }
 
-template <int TF, typename T, typename IT>
+template <int TF, typename T, typename IT, typename XT>
 struct Cube16Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<float>() &&
+    return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<XT>() &&
            int(c->itype) == itype_code<IT>() && f.bz == 16 && f.by == 16 && f.bx == 16 && f.kz == 16 && f.ky == 16 &&
-           f.kx == 16 && x_extent_ok(f, 4, 4);
+           f.kx == 16 && x_extent_ok(f, 4, int(sizeof(XT)));
   }
   // one workgroup per pair of blocks; the statistics records are per block
   static bool grid_for(FastGeom& g, dim3* grid) {
@@ -318,8 +313,8 @@ struct Cube16Kernel {
   }
   template <bool kRagged, bool kStats, bool kTailX>
   static void launch(const FastGeom& g, dim3 grid, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
-    hipLaunchKernelGGL((k_compress_cube16<TF, T, IT, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
-                       static_cast<const float*>(x), N, static_cast<IT*>(F), tile_sums);
+    hipLaunchKernelGGL((k_compress_cube16<TF, T, IT, XT, kRagged, kStats, kTailX>), grid, dim3(128), 0, s, g,
+                       static_cast<const XT*>(x), N, static_cast<IT*>(F), tile_sums);
   }
   static int compress(FastGeom g, const void* x, void* N, void* F, double* tile_sums, hipStream_t s) {
     dim3 grid;
@@ -334,18 +329,22 @@ struct Cube16Kernel {
     dim3 grid;
     if (!grid_for(g, &grid)) return 0;
     if (g.X % 16)
-      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, true>), grid, dim3(128), 0, s, g, N, static_cast<const IT*>(F),
-                         static_cast<float*>(y));
+      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, XT, true>), grid, dim3(128), 0, s, g, N,
+                         static_cast<const IT*>(F), static_cast<XT*>(y));
     else
-      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, false>), grid, dim3(128), 0, s, g, N, static_cast<const IT*>(F),
-                         static_cast<float*>(y));
+      hipLaunchKernelGGL((k_decompress_cube16<TF, T, IT, XT, false>), grid, dim3(128), 0, s, g, N,
+                         static_cast<const IT*>(F), static_cast<XT*>(y));
     return hipGetLastError() == hipSuccess ? 1 : PBZ_ERR_HIP;
   }
 };
 
 #define PBZ_ROWS(X, TF, SUFFIX) \
-  X(Cube16Kernel<TF COMMA double COMMA int16_t>, "cube16_f32_16x16x16_i16" SUFFIX) \
-  X(Cube16Kernel<TF COMMA float COMMA int8_t>, "cube16_f32_16x16x16_i8" SUFFIX)
+  X(Cube16Kernel<TF COMMA double COMMA int16_t COMMA float>, "cube16_f32_16x16x16_i16" SUFFIX) \
+  X(Cube16Kernel<TF COMMA float COMMA int8_t COMMA float>, "cube16_f32_16x16x16_i8" SUFFIX) \
+  X(Cube16Kernel<TF COMMA double COMMA int32_t COMMA float>, "cube16_f32_16x16x16_i32" SUFFIX) \
+  X(Cube16Kernel<TF COMMA double COMMA int8_t COMMA double>, "cube16_f64_16x16x16_i8" SUFFIX) \
+  X(Cube16Kernel<TF COMMA double COMMA int16_t COMMA double>, "cube16_f64_16x16x16_i16" SUFFIX) \
+  X(Cube16Kernel<TF COMMA double COMMA int32_t COMMA double>, "cube16_f64_16x16x16_i32" SUFFIX)
 
 }  // namespace
 

@@ -6,8 +6,9 @@ namespace fast {
 namespace {
 
 // =====================================================================================================
-// Family "quad16": BZ x 16 x 16 blocks with BZ = 1 (2-D) or 4, FP32 / FP16 / bfloat16 arrays, nothing pruned; int8 indices
-// in FP32 arithmetic, or int16 indices in FP64 arithmetic (T, IT), whose exchange takes two rounds of two values per slot
+// Family "quad16": BZ x 16 x 16 blocks with BZ = 1 (2-D) or 4, nothing pruned.  FP32 / FP16 / bfloat16 arrays with int8
+// indices in FP32 arithmetic; FP32 arrays with int16 / int32 and FP64 arrays with int8 to int32 in FP64 arithmetic
+// (T, IT, XT), whose exchange takes two rounds of two values per slot
 // =====================================================================================================
 // A wave works on 16 planes of 16 x 16 samples: plane p = 4 j + s (j, s in 0..3).  For BZ = 1 these are 16
 // consecutive blocks; for BZ = 4 they are the four z-planes (j) of four consecutive blocks (s), so that the lane
@@ -62,10 +63,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
 #pragma unroll
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       if constexpr (kRagged) Q4::keep(raw[yy0], by * 16 + yy0 < g.Y ? keep_z : 0u);
-      float f[4];
-      Q4::unpack(raw[yy0], f);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[yy0 * 4 + e] = T(f[e]);
+      quad4_unpack<T, XT>(raw[yy0], v + yy0 * 4);
     }
     if constexpr (kTailX) {
       const int64_t x0 = bxc * 16 + q * 4;
@@ -78,8 +76,8 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int64_t xi = x0 + e;
-            const float val = Elem<float, XT>::load(row + (xi < g.X ? xi : g.X - 1));
-            v[yy0 * 4 + e] = row_in && xi < g.X ? T(val) : T(0);
+            const T val = Elem<T, XT>::load(row + (xi < g.X ? xi : g.X - 1));
+            v[yy0 * 4 + e] = row_in && xi < g.X ? val : T(0);
           }
         }
       }
@@ -151,7 +149,7 @@ __global__ __launch_bounds__(128) void k_compress_quad16(FastGeom g, const XT* _
       if constexpr (kStats) {
         const double n = stored_N(m, g.ntype);
         const double f0 = first ? double(IdxPack<IT>::get(w[0], 0)) : 0.0;
-        rest += (sum_of_squares<IT, ROWW>(w) - f0 * f0) * (n * n);
+        rest += sum_of_squares_rest<IT, ROWW>(w, first) * (n * n);
         firsts[j] = n * f0;
         has_first[j] = first;
       }
@@ -191,7 +189,7 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
   {
     int64_t blocks[4];
     uint4 fs[4][ROWW / 4];
-    float ns[4];
+    T ns[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int64_t blk = Map::block_of(4 * j + bsub);
@@ -202,10 +200,10 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
 #pragma unroll
       for (int k = 0; k < ROWW / 4; ++k) fs[j][k] = src[k];
     }
-    load_N_many<4>(N, g.ntype, blocks, ns);
+    load_N_many<4, T>(N, g.ntype, blocks, ns);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const T scale = T(ns[j]) / T(g.r);
+      const T scale = ns[j] / T(g.r);
 #pragma unroll
       for (int k = 0; k < ROWW / 4; ++k) {
         const uint4 f = fs[j][k];
@@ -248,21 +246,18 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
     for (int yy0 = 0; yy0 < 16; ++yy0) {
       const int64_t yy = by * 16 + yy0;
       if (yy < g.Y) {
-        float f[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) f[e] = float(v[yy0 * 4 + e]);
         if constexpr (kTailX) {
           XT* row = y + (zz * g.Y + yy) * g.X;
           const int64_t x0 = bx * 16 + q * 4;
           if (x0 + 4 <= g.X) {
-            Q4::template store<true>(row + x0, Q4::pack(f));
+            Q4::template store<true>(row + x0, quad4_pack<T, XT>(v + yy0 * 4));
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (x0 + e < g.X) Elem<float, XT>::store(row + x0 + e, f[e]);
+              if (x0 + e < g.X) Elem<T, XT>::store(row + x0 + e, v[yy0 * 4 + e]);
           }
         } else {
-          Q4::template store<false>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4, Q4::pack(f));
+          Q4::template store<false>(y + (zz * g.Y + yy) * g.X + bx * 16 + q * 4, quad4_pack<T, XT>(v + yy0 * 4));
         }
       }
     }
@@ -270,14 +265,14 @@ __global__ __launch_bounds__(128) void k_decompress_quad16(FastGeom g, const voi
 }
 
 
-// 16x16 (2-D) and 4x16x16 blocks, FP32 / bfloat16 / FP16 arrays, nothing pruned; T = float with int8, double with int16
+// 16x16 (2-D) and 4x16x16 blocks, nothing pruned; T = float with int8 (FP32 / bfloat16 / FP16 arrays), double otherwise
 template <int TF, typename T, typename IT, typename XT, int BZ>
 struct Quad16Kernel {
   static constexpr int kBlocksPerWave = BZ == 1 ? 16 : 4;
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
     return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<XT>() &&
            int(c->itype) == itype_code<IT>() &&
-           c->ftype != PBZ_F64 && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
+           (sizeof(XT) == 8 || c->ftype != PBZ_F64) && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
            x_extent_ok(f, 4, int(sizeof(XT)));
   }
   static int fits(FastGeom g) {
@@ -322,7 +317,13 @@ struct Quad16Kernel {
   X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA bf16_t COMMA 1>, "quad16_bf16_16x16_i8" SUFFIX) \
   X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA f16_t COMMA 4>, "quad16_f16_4x16x16_i8" SUFFIX) \
   X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA float COMMA 1>, "quad16_f32_16x16_i16" SUFFIX) \
-  X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA float COMMA 4>, "quad16_f32_4x16x16_i16" SUFFIX)
+  X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA float COMMA 4>, "quad16_f32_4x16x16_i16" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int32_t COMMA float COMMA 1>, "quad16_f32_16x16_i32" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int32_t COMMA float COMMA 4>, "quad16_f32_4x16x16_i32" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int8_t COMMA double COMMA 1>, "quad16_f64_16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA double COMMA 1>, "quad16_f64_16x16_i16" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int32_t COMMA double COMMA 1>, "quad16_f64_16x16_i32" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA double COMMA 4>, "quad16_f64_4x16x16_i16" SUFFIX)
 
 }  // namespace
 

@@ -259,6 +259,24 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((32, 16, 48), (16, 16, 16), 8, "f32", "f32", None, "cube16_f32_16x16x16_i8"),
                ((20, 37, 70), (16, 16, 16), 8, "f32", "f32", None, "cube16_f32_16x16x16_i8"),
                ((2, 16, 20, 32), (1, 16, 16, 16), 8, "f32", "f16", None, "cube16_f32_16x16x16_i8"),
+               # int32 indices and FP64 arrays in 16x16, 4x16x16 and 16x16x16 blocks
+               ((3, 33, 48), (1, 16, 16), 32, "f32", "f32", None, "quad16_f32_16x16_i32"),
+               ((21, 270), (16, 16), 32, "f32", "f16", None, "quad16_f32_16x16_i32"),
+               ((9, 20, 37), (4, 16, 16), 32, "f32", "f32", None, "quad16_f32_4x16x16_i32"),
+               ((3, 33, 48), (1, 16, 16), 16, "f64", "f64", None, "quad16_f64_16x16_i16"),
+               ((40, 1046), (16, 16), 16, "f64", "f32", None, "quad16_f64_16x16_i16"),
+               ((21, 77), (16, 16), 8, "f64", "f64", None, "quad16_f64_16x16_i8"),
+               ((2, 19, 560), (1, 16, 16), 32, "f64", "f64", None, "quad16_f64_16x16_i32"),
+               ((9, 20, 37), (4, 16, 16), 16, "f64", "f64", None, "quad16_f64_4x16x16_i16"),
+               ((10, 33, 160), (4, 16, 16), 16, "f64", "f16", None, "quad16_f64_4x16x16_i16"),
+               ((20, 37, 64), (16, 16, 16), 32, "f32", "f32", None, "cube16_f32_16x16x16_i32"),
+               ((17, 16, 70), (16, 16, 16), 32, "f32", "bf16", None, "cube16_f32_16x16x16_i32"),
+               ((20, 37, 64), (16, 16, 16), 16, "f32", "f64", None, "cube16_f32_16x16x16_i16"),      # FP32 array, FP64 N
+               ((32, 16, 48), (16, 16, 16), 16, "f64", "f64", None, "cube16_f64_16x16x16_i16"),
+               ((20, 37, 64), (16, 16, 16), 16, "f64", "f64", None, "cube16_f64_16x16x16_i16"),
+               ((17, 16, 71), (16, 16, 16), 16, "f64", "f32", None, "cube16_f64_16x16x16_i16"),
+               ((16, 33, 21), (16, 16, 16), 8, "f64", "f64", None, "cube16_f64_16x16x16_i8"),
+               ((20, 37, 70), (16, 16, 16), 32, "f64", "f64", None, "cube16_f64_16x16x16_i32"),
                # 49 and more blocks along x: the decompress variant that stores whole row pieces
                ((17, 9, 520), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "oct8_bf16_8x8x8_i8_box4x4x4"),
                ((9, 12, 392), (8, 8, 8), 8, "bf16", "f32", None, "oct8_bf16_8x8x8_i8")]
@@ -304,6 +322,10 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((9, 20, 37), (4, 16, 16), 16, "f32", "f32", None, "quad16_f32_4x16x16_i16_haar"),
         ((20, 37, 64), (16, 16, 16), 16, "f32", "f32", None, "cube16_f32_16x16x16_i16_haar"),
         ((17, 16, 70), (16, 16, 16), 8, "f32", "f32", None, "cube16_f32_16x16x16_i8_haar"),
+        ((3, 33, 96), (1, 16, 16), 32, "f32", "f32", None, "quad16_f32_16x16_i32_haar"),
+        ((3, 33, 90), (1, 16, 16), 16, "f64", "f64", None, "quad16_f64_16x16_i16_haar"),
+        ((20, 37, 64), (16, 16, 16), 16, "f64", "f64", None, "cube16_f64_16x16x16_i16_haar"),
+        ((17, 16, 70), (16, 16, 16), 32, "f32", "f32", None, "cube16_f32_16x16x16_i32_haar"),
         ((9, 20, 36), (2, 16, 16), 8, "f32", "f32", None, "generic"),
         ((50, 21), (2, 32), 16, "f64", "f64", None, "generic")]
 
@@ -723,7 +745,8 @@ def test_variance_of_a_field_with_a_large_offset():
     # block's first vector changes from step to step
     for block, bits, mask in (((4, 4, 4), 16, None), ((8, 8, 8), 32, None), ((2, 4, 3 + 1), 16, None),
                               ((1, 8, 8), 8, six_rows), ((4, 32, 32), 16, None), ((4, 4, 4), 32, None),
-                              ((1, 8, 8), 32, None), ((8, 8, 8), 16, None), ((2, 8, 8), 32, None)):
+                              ((1, 8, 8), 32, None), ((8, 8, 8), 16, None), ((2, 8, 8), 32, None),
+                              ((16, 16, 16), 32, None), ((1, 16, 16), 32, None), ((4, 16, 16), 16, None)):
         case = Case(a, b, "f64", block, bits, "f64", mask)
         N1, F1 = case.codec.compress(case.xA)
         N2, F2 = case.codec.compress(case.xB)
