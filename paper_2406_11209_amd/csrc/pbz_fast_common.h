@@ -323,8 +323,18 @@ struct Quad4<double> {                  // four FP64 elements: two 16-byte piece
   template <bool kTailX>
   static __device__ __forceinline__ raw_t load(const double* p) {
     raw_t r;
-    r.lo = kTailX ? load16_a4(p) : load16_stream(p);
-    r.hi = kTailX ? load16_a4(p + 2) : load16_stream(p + 2);
+    if constexpr (kTailX) {
+      r.lo = load16_a4(p);
+      r.hi = load16_a4(p + 2);
+    } else {
+      // The two halves are requested one right after the other: no other memory instruction may be scheduled
+      // across the barrier (everything else may).  Left alone, the compiler issued a strip's sixteen upper pieces
+      // before its sixteen lower ones, and a line fetched with the non-temporal hint was gone by the time its
+      // other half was asked for (counters, 1 GiB array: 1.8 GiB fetched; 1.17 GiB with plain loads in that order).
+      r.lo = load16_stream(p);
+      r.hi = load16_stream(p + 2);
+      __builtin_amdgcn_sched_barrier(0x38f);
+    }
     return r;
   }
   template <bool kTailX>

@@ -10,7 +10,7 @@ import sys
 import torch
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)))))
-from paper_2406_11209_amd.api import Codec  # noqa: E402
+from paper_2406_11209_amd.api import PBZ_PATH_GENERIC, Codec  # noqa: E402
 
 TORCH = {"f64": torch.float64, "f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
@@ -24,9 +24,13 @@ def main():
     ap.add_argument("--itype", default="i8", choices=["i8", "i16", "i32"])
     ap.add_argument("--transform", default="dct", choices=["dct", "haar"])
     ap.add_argument("--repeat", type=int, default=5)
+    ap.add_argument("--path", default="auto", choices=["auto", "generic"],
+                    help="generic: the general kernels, also where a specialised kernel exists")
     args = ap.parse_args()
     shape = tuple(args.shape)
     codec = Codec(tuple(args.block), args.ftype, args.itype, None, args.transform)
+    if args.path == "generic":
+        codec.set_kernel_path(PBZ_PATH_GENERIC)
     gen = torch.Generator(device="cuda").manual_seed(240611209)
     x = torch.randn(shape, dtype=torch.float32, device="cuda", generator=gen).to(TORCH[args.dtype])
     N, F = codec.compress(x)
