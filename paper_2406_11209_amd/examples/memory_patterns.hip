@@ -16,6 +16,9 @@
 //                     block), one row per instruction, against a linear sweep; loads and stores.
 //   small read        a 68 MiB buffer (the compressed operand of that array) read by nothing but loads, for several
 //                     grids: the floor of any reduction over it.
+//   vector ALU        sixteen independent chains of one instruction type per lane and no memory access, eight waves
+//                     per SIMD: how often a SIMD issues a vector instruction of that type and operand form, the
+//                     yardstick for kernels whose time is their arithmetic.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -215,6 +218,48 @@ void read_case(const u32x4* a, int64_t nvec, int groups, uint32_t* sink) {
               g, kInFlight, ms * 1e3, double(nvec) * 16.0 / ms / 1e6);
 }
 
+// ---- vector ALU issue rate -------------------------------------------------------------------------------------
+struct OpFma { template <typename T> static __device__ __forceinline__ T run(T a, T b, T c) { return a * b + c; } };
+struct OpAdd { template <typename T> static __device__ __forceinline__ T run(T a, T, T c) { return a + c; } };
+struct OpMul { template <typename T> static __device__ __forceinline__ T run(T a, T b, T) { return a * b; } };
+struct OpMax { static __device__ __forceinline__ float run(float a, float, float c) { return fmaxf(a, c); } };
+struct OpRint { static __device__ __forceinline__ float run(float a, float, float) { return rintf(a); } };
+struct OpXor { static __device__ __forceinline__ uint32_t run(uint32_t a, uint32_t, uint32_t c) { return a ^ c; } };
+struct OpShl { static __device__ __forceinline__ uint32_t run(uint32_t a, uint32_t b, uint32_t) { return a << (b & 31); } };
+
+// kScalarOperand: b and c stay what kernel arguments are, scalar registers; otherwise they are moved to vector registers
+template <typename T, typename Op, bool kScalarOperand>
+__global__ __launch_bounds__(256) void k_alu(T* out, T b, T c, int iters) {
+  constexpr int kChains = 16;
+  T a[kChains];
+#pragma unroll
+  for (int i = 0; i < kChains; ++i) a[i] = T(threadIdx.x + i);
+  if constexpr (!kScalarOperand) {
+    b += T(threadIdx.x >> 20);
+    c += T(threadIdx.x >> 21);
+    asm volatile("" : "+v"(b), "+v"(c));
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < kChains; ++i) a[i] = Op::run(a[i], b, c);
+  }
+  T s = 0;
+#pragma unroll
+  for (int i = 0; i < kChains; ++i) s += a[i];
+  if (s == T(123456)) out[threadIdx.x] = s;      // never true for the operands used: keeps the chains alive
+}
+
+template <typename T, typename Op, bool kScalarOperand = false>
+void alu_case(const char* what, void* out) {
+  // 64 workgroups of four waves per compute unit (256 units), eight resident at a time
+  const int iters = 512, groups = 256 * 64;
+  const float ms = time_ms([&] {
+    hipLaunchKernelGGL((k_alu<T, Op, kScalarOperand>), dim3(groups), dim3(256), 0, 0, static_cast<T*>(out), T(3), T(5), iters);
+  }, 5);
+  const double per_simd = double(iters) * 16 * (groups / 256);        // wave-instructions per SIMD: one wave of a workgroup each
+  std::printf("vector ALU        %-68s %.3f ms  %.2f ns per wave-instruction per SIMD\n", what, ms, ms * 1e6 / per_simd);
+}
+
 }  // namespace
 
 int main() {
@@ -271,6 +316,17 @@ int main() {
     }
     CHECK(hipFree(a));
   }
+  alu_case<float, OpFma>("FP32 multiply-add, vector-register operands", sink);
+  alu_case<float, OpAdd>("FP32 add", sink);
+  alu_case<float, OpMul>("FP32 multiply", sink);
+  alu_case<float, OpAdd, true>("FP32 add, one operand a scalar register", sink);
+  alu_case<float, OpFma, true>("FP32 multiply-add, two operands scalar registers", sink);
+  alu_case<float, OpMax>("FP32 maximum (two instructions: one operand is canonicalised first)", sink);
+  alu_case<float, OpRint>("FP32 round to integer", sink);
+  alu_case<uint32_t, OpXor>("32-bit xor", sink);
+  alu_case<uint32_t, OpShl>("32-bit shift", sink);
+  alu_case<double, OpFma>("FP64 multiply-add", sink);
+  alu_case<double, OpAdd>("FP64 add", sink);
   CHECK(hipFree(sink));
   return 0;
 }
