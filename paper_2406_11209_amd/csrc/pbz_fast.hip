@@ -11,19 +11,19 @@
 //                   row is two (four) 16-byte pieces the half-waves (quarter-waves) trade pieces, so that every
 //                   load / store instruction of the array covers one contiguous KiB.  Indices leave through a wave-private
 //                   LDS transpose when a block's F is 64 bytes or more, for the same reason.
-// Family "quad16":  16x16 and 4x16x16 blocks of FP32 or 16-bit input (int8; in FP64 arithmetic also FP32 input with int16 / int32
-//                   and FP64 input with int8 to int32), 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
+// Family "quad16":  16x16 and 4x16x16 blocks of FP32, 16-bit or FP64 input (int8 in FP32 arithmetic; in FP64 arithmetic FP32 input
+//                   with int16 / int32 and FP64 input with int8 to int32), 16 planes of 16x16 per wave.  Each lane first holds a 16-row x
 //                   4-column strip (the column transform runs in registers), the wave exchanges through LDS,
 //                   then each lane holds four whole rows (row transform, and for 4x16x16 the transform across
 //                   the four planes); rows leave as 16-byte pieces in linear order.
-// Family "oct8":    8x8x8 blocks of bfloat16, FP16 or FP32 input (int8; in FP64 arithmetic also FP32 input with int16 / int32
-//                   and FP64 input with int8 to int32), 8 blocks per wave.  Each lane first holds one z-plane of
+// Family "oct8":    8x8x8 blocks of bfloat16, FP16, FP32 or FP64 input (int8 in FP32 arithmetic; in FP64 arithmetic FP32 input
+//                   with int16 / int32 and FP64 input with int8 to int32), 8 blocks per wave.  Each lane first holds one z-plane of
 //                   a block (x and y transforms), the wave exchanges through LDS, then each lane holds one
 //                   y-row of all eight z-planes (z transform).  Decompression needs no exchange: every
 //                   lane rebuilds its own z-plane from the block's few kept coefficients; wide arrays use a
 //                   variant in which a wave owns one plane of 64 blocks and stores whole 1 KiB row pieces.
-// Family "cube16":  16x16x16 blocks of FP32 input (int16 / int32 indices in FP64 arithmetic, int8 in FP32) or FP64 input (int8 to
-//                   int32, FP64 arithmetic), two neighbouring blocks
+// Family "cube16":  16x16x16 blocks of FP32 input (int16 / int32 indices in FP64 arithmetic, int8 in FP32) or FP64 input (int8 in
+//                   FP32 arithmetic, int8 to int32 in FP64), two neighbouring blocks
 //                   per workgroup of two waves.  Three layouts, one per transformed dimension, with an LDS exchange
 //                   between them; the first is how rows are read (eight lanes cover the 128 bytes the two blocks have
 //                   in a row), the last how F is written (whole rows of indices).

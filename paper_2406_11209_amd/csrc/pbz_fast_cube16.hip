@@ -344,7 +344,8 @@ struct Cube16Kernel {
   X(Cube16Kernel<TF COMMA double COMMA int32_t COMMA float>, "cube16_f32_16x16x16_i32" SUFFIX) \
   X(Cube16Kernel<TF COMMA double COMMA int8_t COMMA double>, "cube16_f64_16x16x16_i8" SUFFIX) \
   X(Cube16Kernel<TF COMMA double COMMA int16_t COMMA double>, "cube16_f64_16x16x16_i16" SUFFIX) \
-  X(Cube16Kernel<TF COMMA double COMMA int32_t COMMA double>, "cube16_f64_16x16x16_i32" SUFFIX)
+  X(Cube16Kernel<TF COMMA double COMMA int32_t COMMA double>, "cube16_f64_16x16x16_i32" SUFFIX) \
+  X(Cube16Kernel<TF COMMA float COMMA int8_t COMMA double>, "cube16_f64_w32_16x16x16_i8" SUFFIX)
 
 }  // namespace
 

@@ -46,6 +46,86 @@ __device__ __forceinline__ int oct_slot(int b, int yy, int z) { return b * 64 + 
 
 constexpr int kOctWaves = 4;   // waves per workgroup: neighbouring tiles, so that a workgroup reads 512-byte row pieces
 
+// Rows of 32-bit or 64-bit elements.  A row of a block is two (FP32) or four (FP64) 16-byte pieces, 32 or 64 bytes
+// apart from the next lane's: stored as they are, an instruction would write every second or fourth piece of the
+// run that the eight blocks of a plane have in a row (measured, 512 x 512 x 256 FP64: 3.0 TB/s moved).  Here the
+// finished planes v (lane = (plane z, block b), 64 values of type T each) go through the wave's 8 KiB of LDS
+// instead, 512 pieces per round: lane (z, b) writes pieces P = RV b + k of its rows, and on the way out 8 RV
+// consecutive lanes take one row's pieces in order, so that an instruction stores two or four whole 256- or
+// 512-byte rows, with the non-temporal hint (6.7 TB/s).  Slot P ^ (P / 8) keeps every eight consecutive lanes in
+// distinct 16-byte slots modulo 8 in both directions.  Whole rows only (X a multiple of 8); blocks, rows and
+// planes past the array's end are left out.
+template <typename T, typename XT>
+__device__ __forceinline__ void oct_store_rows_through_lds(const FastGeom& g, uint4* st, XT* __restrict__ y, int64_t tx,
+                                                           int64_t by, int64_t bz, int lane, const T* v) {
+  constexpr int PER16 = 16 / int(sizeof(XT)), RV = 8 / PER16;      // elements per piece, pieces per block row
+  static_assert(RV == 2 || RV == 4, "16-bit rows are one piece per block and contiguous as they are");
+  constexpr int kRowsPerRound = 512 / (64 * RV);
+  constexpr int kLanesPerRow = 8 * RV, kRowsPerInst = 64 / kLanesPerRow;
+  const int z = lane >> 3, b = lane & 7;
+#pragma unroll
+  for (int round = 0; round < 8 / kRowsPerRound; ++round) {
+#pragma unroll
+    for (int h = 0; h < kRowsPerRound; ++h)
+#pragma unroll
+      for (int k = 0; k < RV; ++k) {
+        const int P = b * RV + k;
+        st[(h * 8 + z) * kLanesPerRow + (P ^ (P >> 3))] = Pack<T, XT>::run(v + (round * kRowsPerRound + h) * 8 + PER16 * k);
+      }
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < kRowsPerRound * 8 / kRowsPerInst; ++i) {
+      const int rr = i * kRowsPerInst + lane / kLanesPerRow, P = lane % kLanesPerRow;      // row (h, z) of the round
+      const int64_t yy = by * 8 + round * kRowsPerRound + rr / 8, zr = bz * 8 + rr % 8;
+      const uint4 piece = st[rr * kLanesPerRow + (P ^ (P >> 3))];
+      if (tx * 8 + P / RV < g.gx && zr < g.Z && yy < g.Y)
+        store16_stream(y + (zr * g.Y + yy) * g.X + tx * 64 + P * PER16, piece);
+    }
+    wave_lds_sync();
+  }
+}
+
+// The same regrouping for the way in: 8 RV consecutive lanes load one whole 256- or 512-byte row of the eight
+// blocks, all 8 RV pieces of a lane are requested before the first is used, and the lanes (plane z, block b) then
+// read their own rows' pieces back from LDS.  Pieces of blocks, rows and planes past the array's end are zeros.
+template <typename T, typename XT>
+__device__ __forceinline__ void oct_load_rows_through_lds(const FastGeom& g, uint4* st, const XT* __restrict__ x, int64_t tx,
+                                                          int64_t by, int64_t bz, int lane, T* v) {
+  constexpr int PER16 = 16 / int(sizeof(XT)), RV = 8 / PER16;
+  constexpr int kRowsPerRound = 512 / (64 * RV), kRounds = 8 / kRowsPerRound;
+  constexpr int kLanesPerRow = 8 * RV, kRowsPerInst = 64 / kLanesPerRow, kInstPerRound = kRowsPerRound * 8 / kRowsPerInst;
+  const int z = lane >> 3, b = lane & 7;
+  const int P = lane % kLanesPerRow;
+  uint4 raw[kRounds * kInstPerRound];
+#pragma unroll
+  for (int round = 0; round < kRounds; ++round)
+#pragma unroll
+    for (int i = 0; i < kInstPerRound; ++i) {
+      const int rr = i * kRowsPerInst + lane / kLanesPerRow;                               // row (h, z) of the round
+      const int64_t yy = by * 8 + round * kRowsPerRound + rr / 8, zr = bz * 8 + rr % 8;
+      raw[round * kInstPerRound + i] = make_uint4(0u, 0u, 0u, 0u);
+      if (tx * 8 + P / RV < g.gx && zr < g.Z && yy < g.Y)
+        raw[round * kInstPerRound + i] = load16_stream(x + (zr * g.Y + yy) * g.X + tx * 64 + P * PER16);
+    }
+#pragma unroll
+  for (int round = 0; round < kRounds; ++round) {
+    if (round) wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < kInstPerRound; ++i) {
+      const int rr = i * kRowsPerInst + lane / kLanesPerRow;
+      st[rr * kLanesPerRow + (P ^ (P >> 3))] = raw[round * kInstPerRound + i];
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int h = 0; h < kRowsPerRound; ++h)
+#pragma unroll
+      for (int k = 0; k < RV; ++k) {
+        const int Q = b * RV + k;
+        Unpack<T, XT>::run(st[(h * 8 + z) * kLanesPerRow + (Q ^ (Q >> 3))], v + (round * kRowsPerRound + h) * 8 + PER16 * k);
+      }
+  }
+}
+
 template <int TF, typename XT, int KZ, int KY, int KX, bool kRagged, bool kStats, bool kTailX = false>
 __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, const XT* __restrict__ x,
                                                                   void* __restrict__ N, int8_t* __restrict__ F,
@@ -66,7 +146,16 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_compress_oct8(FastGeom g, co
 
   // phase A: one 8x8 z-plane per lane; transforms along x and y
   float v[64];
-  {
+  if constexpr (sizeof(XT) == 8 && !kTailX) {
+    // FP64 arrays: four pieces per lane and row, 64 bytes apart; whole rows in piece order, regrouped through LDS
+    oct_load_rows_through_lds<float, XT>(g, st, x, tx, by, bz, lane, v);
+    __builtin_amdgcn_s_setprio(0);
+    wave_lds_sync();                   // the exchange below writes the same LDS
+#pragma unroll
+    for (int yy0 = 0; yy0 < 8; ++yy0) tf_forward<TF, float, 8, 1>(v + yy0 * 8);
+#pragma unroll
+    for (int xx = 0; xx < 8; ++xx) tf_forward<TF, float, 8, 8>(v + xx);
+  } else {
     const int64_t bx = tx * 8 + b;
     const int64_t bxc = bx < g.gx ? bx : g.gx - 1;
     int64_t zz = bz * 8 + z;
@@ -221,86 +310,6 @@ __device__ __forceinline__ void oct_store_row(const FastGeom& g, XT* row, int64_
   }
 }
 
-// Rows of 32-bit or 64-bit elements.  A row of a block is two (FP32) or four (FP64) 16-byte pieces, 32 or 64 bytes
-// apart from the next lane's: stored as they are, an instruction would write every second or fourth piece of the
-// run that the eight blocks of a plane have in a row (measured, 512 x 512 x 256 FP64: 3.0 TB/s moved).  Here the
-// finished planes v (lane = (plane z, block b), 64 values of type T each) go through the wave's 8 KiB of LDS
-// instead, 512 pieces per round: lane (z, b) writes pieces P = RV b + k of its rows, and on the way out 8 RV
-// consecutive lanes take one row's pieces in order, so that an instruction stores two or four whole 256- or
-// 512-byte rows, with the non-temporal hint (6.7 TB/s).  Slot P ^ (P / 8) keeps every eight consecutive lanes in
-// distinct 16-byte slots modulo 8 in both directions.  Whole rows only (X a multiple of 8); blocks, rows and
-// planes past the array's end are left out.
-template <typename T, typename XT>
-__device__ __forceinline__ void oct_store_rows_through_lds(const FastGeom& g, uint4* st, XT* __restrict__ y, int64_t tx,
-                                                           int64_t by, int64_t bz, int lane, const T* v) {
-  constexpr int PER16 = 16 / int(sizeof(XT)), RV = 8 / PER16;      // elements per piece, pieces per block row
-  static_assert(RV == 2 || RV == 4, "16-bit rows are one piece per block and contiguous as they are");
-  constexpr int kRowsPerRound = 512 / (64 * RV);
-  constexpr int kLanesPerRow = 8 * RV, kRowsPerInst = 64 / kLanesPerRow;
-  const int z = lane >> 3, b = lane & 7;
-#pragma unroll
-  for (int round = 0; round < 8 / kRowsPerRound; ++round) {
-#pragma unroll
-    for (int h = 0; h < kRowsPerRound; ++h)
-#pragma unroll
-      for (int k = 0; k < RV; ++k) {
-        const int P = b * RV + k;
-        st[(h * 8 + z) * kLanesPerRow + (P ^ (P >> 3))] = Pack<T, XT>::run(v + (round * kRowsPerRound + h) * 8 + PER16 * k);
-      }
-    wave_lds_sync();
-#pragma unroll
-    for (int i = 0; i < kRowsPerRound * 8 / kRowsPerInst; ++i) {
-      const int rr = i * kRowsPerInst + lane / kLanesPerRow, P = lane % kLanesPerRow;      // row (h, z) of the round
-      const int64_t yy = by * 8 + round * kRowsPerRound + rr / 8, zr = bz * 8 + rr % 8;
-      const uint4 piece = st[rr * kLanesPerRow + (P ^ (P >> 3))];
-      if (tx * 8 + P / RV < g.gx && zr < g.Z && yy < g.Y)
-        store16_stream(y + (zr * g.Y + yy) * g.X + tx * 64 + P * PER16, piece);
-    }
-    wave_lds_sync();
-  }
-}
-
-// The same regrouping for the way in: 8 RV consecutive lanes load one whole 256- or 512-byte row of the eight
-// blocks, all 8 RV pieces of a lane are requested before the first is used, and the lanes (plane z, block b) then
-// read their own rows' pieces back from LDS.  Pieces of blocks, rows and planes past the array's end are zeros.
-template <typename T, typename XT>
-__device__ __forceinline__ void oct_load_rows_through_lds(const FastGeom& g, uint4* st, const XT* __restrict__ x, int64_t tx,
-                                                          int64_t by, int64_t bz, int lane, T* v) {
-  constexpr int PER16 = 16 / int(sizeof(XT)), RV = 8 / PER16;
-  constexpr int kRowsPerRound = 512 / (64 * RV), kRounds = 8 / kRowsPerRound;
-  constexpr int kLanesPerRow = 8 * RV, kRowsPerInst = 64 / kLanesPerRow, kInstPerRound = kRowsPerRound * 8 / kRowsPerInst;
-  const int z = lane >> 3, b = lane & 7;
-  const int P = lane % kLanesPerRow;
-  uint4 raw[kRounds * kInstPerRound];
-#pragma unroll
-  for (int round = 0; round < kRounds; ++round)
-#pragma unroll
-    for (int i = 0; i < kInstPerRound; ++i) {
-      const int rr = i * kRowsPerInst + lane / kLanesPerRow;                               // row (h, z) of the round
-      const int64_t yy = by * 8 + round * kRowsPerRound + rr / 8, zr = bz * 8 + rr % 8;
-      raw[round * kInstPerRound + i] = make_uint4(0u, 0u, 0u, 0u);
-      if (tx * 8 + P / RV < g.gx && zr < g.Z && yy < g.Y)
-        raw[round * kInstPerRound + i] = load16_stream(x + (zr * g.Y + yy) * g.X + tx * 64 + P * PER16);
-    }
-#pragma unroll
-  for (int round = 0; round < kRounds; ++round) {
-    if (round) wave_lds_sync();
-#pragma unroll
-    for (int i = 0; i < kInstPerRound; ++i) {
-      const int rr = i * kRowsPerInst + lane / kLanesPerRow;
-      st[rr * kLanesPerRow + (P ^ (P >> 3))] = raw[round * kInstPerRound + i];
-    }
-    wave_lds_sync();
-#pragma unroll
-    for (int h = 0; h < kRowsPerRound; ++h)
-#pragma unroll
-      for (int k = 0; k < RV; ++k) {
-        const int Q = b * RV + k;
-        Unpack<T, XT>::run(st[(h * 8 + z) * kLanesPerRow + (Q ^ (Q >> 3))], v + (round * kRowsPerRound + h) * 8 + PER16 * k);
-      }
-  }
-}
-
 template <int TF, typename XT, int KZ, int KY, int KX, bool kTailX = false>
 __global__ __launch_bounds__(256) void k_decompress_oct8(FastGeom g, const void* __restrict__ N,
                                                          const int8_t* __restrict__ F, XT* __restrict__ y) {
@@ -406,7 +415,7 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_full(FastGeo
   for (int xx = 0; xx < 8; ++xx) tf_inverse<TF, float, 8, 8, 8>(v + xx);
 #pragma unroll
   for (int yy0 = 0; yy0 < 8; ++yy0) tf_inverse<TF, float, 8, 1, 8>(v + yy0 * 8);
-  if constexpr (sizeof(XT) == 4 && !kTailX) {
+  if constexpr (sizeof(XT) >= 4 && !kTailX) {
     oct_store_rows_through_lds<float, XT>(g, st, y, tx, by, bz, lane, v);
     return;
   }
@@ -497,7 +506,7 @@ __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const 
 }
 
 
-// 3-D 8x8x8 bfloat16 or FP32 arrays, FP32 arithmetic and N, int8, box KZ x KY x KX kept
+// 3-D 8x8x8 bfloat16, FP16, FP32 or FP64 arrays, FP32 arithmetic, N in FP32 or a 16-bit type, int8, box KZ x KY x KX kept
 template <int TF, typename XT, int KZ, int KY, int KX>
 struct Oct8Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
@@ -797,10 +806,9 @@ __global__ __launch_bounds__(kOctWaves * 64) void k_decompress_oct8_wide(FastGeo
 template <int TF, typename XT, typename IT>
 struct Oct8WideKernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
-    // FP32 arrays: N in FP32 or a 16-bit type (with FP64 N the working type is FP64 and the array FP32: not built);
-    // FP64 arrays: any N.  int8 with an FP32 array computes in FP32 and belongs to the kernels above.
+    // N of any type.  int8 with an FP32 array and FP32 / 16-bit N computes in FP32 and belongs to the kernels above.
     return f.ok && c->transform == TF && c->compute_f64 && xtype == xtype_code<XT>() &&
-           int(c->itype) == itype_code<IT>() && (sizeof(XT) == 8 || c->ftype != PBZ_F64) && f.bz == 8 && f.by == 8 &&
+           int(c->itype) == itype_code<IT>() && f.bz == 8 && f.by == 8 &&
            f.bx == 8 && f.kz == 8 && f.ky == 8 && f.kx == 8 && x_extent_ok(f, 16 / int(sizeof(XT)), int(sizeof(XT)));
   }
   static int fits(FastGeom g) {
@@ -844,6 +852,8 @@ template <int TF> using Oct8_f32_box4 = Oct8Kernel<TF, float, 4, 4, 4>;
 template <int TF> using Oct8_f32_full = Oct8Kernel<TF, float, 8, 8, 8>;
 template <int TF> using Oct8_f16_box4 = Oct8Kernel<TF, f16_t, 4, 4, 4>;
 template <int TF> using Oct8_f16_full = Oct8Kernel<TF, f16_t, 8, 8, 8>;
+template <int TF> using Oct8_f64w32_box4 = Oct8Kernel<TF, double, 4, 4, 4>;
+template <int TF> using Oct8_f64w32_full = Oct8Kernel<TF, double, 8, 8, 8>;
 template <int TF> using Oct8_f32_i16 = Oct8WideKernel<TF, float, int16_t>;
 template <int TF> using Oct8_f32_i32 = Oct8WideKernel<TF, float, int32_t>;
 template <int TF> using Oct8_f64_i8 = Oct8WideKernel<TF, double, int8_t>;
@@ -857,6 +867,8 @@ template <int TF> using Oct8_f64_i32 = Oct8WideKernel<TF, double, int32_t>;
   X(Oct8_f32_full<TF>, "oct8_f32_8x8x8_i8" SUFFIX) \
   X(Oct8_f16_box4<TF>, "oct8_f16_8x8x8_i8_box4x4x4" SUFFIX) \
   X(Oct8_f16_full<TF>, "oct8_f16_8x8x8_i8" SUFFIX) \
+  X(Oct8_f64w32_box4<TF>, "oct8_f64_w32_8x8x8_i8_box4x4x4" SUFFIX) \
+  X(Oct8_f64w32_full<TF>, "oct8_f64_w32_8x8x8_i8" SUFFIX) \
   X(Oct8_f32_i16<TF>, "oct8_f32_8x8x8_i16" SUFFIX) \
   X(Oct8_f32_i32<TF>, "oct8_f32_8x8x8_i32" SUFFIX) \
   X(Oct8_f64_i8<TF>, "oct8_f64_8x8x8_i8" SUFFIX) \

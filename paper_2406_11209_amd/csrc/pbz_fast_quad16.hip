@@ -272,7 +272,7 @@ struct Quad16Kernel {
   static bool matches(const pbz_codec* c, const Folded& f, int xtype) {
     return f.ok && c->transform == TF && c->compute_f64 == (sizeof(T) == 8) && xtype == xtype_code<XT>() &&
            int(c->itype) == itype_code<IT>() &&
-           (sizeof(XT) == 8 || c->ftype != PBZ_F64) && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
+           (sizeof(T) == 8 || c->ftype != PBZ_F64) && f.bz == BZ && f.by == 16 && f.bx == 16 && f.kz == BZ && f.ky == 16 && f.kx == 16 &&
            x_extent_ok(f, 4, int(sizeof(XT)));
   }
   static int fits(FastGeom g) {
@@ -323,7 +323,11 @@ struct Quad16Kernel {
   X(Quad16Kernel<TF COMMA double COMMA int8_t COMMA double COMMA 1>, "quad16_f64_16x16_i8" SUFFIX) \
   X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA double COMMA 1>, "quad16_f64_16x16_i16" SUFFIX) \
   X(Quad16Kernel<TF COMMA double COMMA int32_t COMMA double COMMA 1>, "quad16_f64_16x16_i32" SUFFIX) \
-  X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA double COMMA 4>, "quad16_f64_4x16x16_i16" SUFFIX)
+  X(Quad16Kernel<TF COMMA double COMMA int16_t COMMA double COMMA 4>, "quad16_f64_4x16x16_i16" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int8_t COMMA double COMMA 4>, "quad16_f64_4x16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA double COMMA int32_t COMMA double COMMA 4>, "quad16_f64_4x16x16_i32" SUFFIX) \
+  X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA double COMMA 1>, "quad16_f64_w32_16x16_i8" SUFFIX) \
+  X(Quad16Kernel<TF COMMA float COMMA int8_t COMMA double COMMA 4>, "quad16_f64_w32_4x16x16_i8" SUFFIX)
 
 }  // namespace
 

@@ -272,6 +272,22 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((20, 37, 64), (16, 16, 16), 32, "f32", "f32", None, "cube16_f32_16x16x16_i32"),
                ((17, 16, 70), (16, 16, 16), 32, "f32", "bf16", None, "cube16_f32_16x16x16_i32"),
                ((20, 37, 64), (16, 16, 16), 16, "f32", "f64", None, "cube16_f32_16x16x16_i16"),      # FP32 array, FP64 N
+               ((17, 9, 72), (8, 8, 8), 16, "f32", "f64", None, "oct8_f32_8x8x8_i16"),
+               ((3, 33, 48), (1, 16, 16), 32, "f32", "f64", None, "quad16_f32_16x16_i32"),
+               ((9, 20, 37), (4, 16, 16), 16, "f32", "f64", None, "quad16_f32_4x16x16_i16"),
+               ((9, 20, 37), (4, 16, 16), 32, "f64", "f64", None, "quad16_f64_4x16x16_i32"),
+               ((8, 32, 80), (4, 16, 16), 8, "f64", "f64", None, "quad16_f64_4x16x16_i8"),
+               # FP64 arrays with an FP32 / 16-bit working type and int8 indices: FP32 arithmetic
+               ((3, 33, 48), (1, 16, 16), 8, "f64", "f32", None, "quad16_f64_w32_16x16_i8"),
+               ((21, 77), (16, 16), 8, "f64", "f16", None, "quad16_f64_w32_16x16_i8"),
+               ((9, 20, 37), (4, 16, 16), 8, "f64", "f32", None, "quad16_f64_w32_4x16x16_i8"),
+               ((17, 9, 72), (8, 8, 8), 8, "f64", "f32", None, "oct8_f64_w32_8x8x8_i8"),
+               ((9, 12, 77), (8, 8, 8), 8, "f64", "bf16", None, "oct8_f64_w32_8x8x8_i8"),
+               ((17, 9, 72), (8, 8, 8), 8, "f64", "f32", (4, 4, 4), "oct8_f64_w32_8x8x8_i8_box4x4x4"),
+               ((9, 12, 398), (8, 8, 8), 8, "f64", "f32", (4, 4, 4), "oct8_f64_w32_8x8x8_i8_box4x4x4"),
+               ((9, 17, 21), (8, 8, 8), 8, "f64", "f16", (4, 4, 4), "oct8_f64_w32_8x8x8_i8_box4x4x4"),
+               ((20, 37, 64), (16, 16, 16), 8, "f64", "f32", None, "cube16_f64_w32_16x16x16_i8"),
+               ((17, 16, 71), (16, 16, 16), 8, "f64", "f16", None, "cube16_f64_w32_16x16x16_i8"),
                ((32, 16, 48), (16, 16, 16), 16, "f64", "f64", None, "cube16_f64_16x16x16_i16"),
                ((20, 37, 64), (16, 16, 16), 16, "f64", "f64", None, "cube16_f64_16x16x16_i16"),
                ((17, 16, 71), (16, 16, 16), 16, "f64", "f32", None, "cube16_f64_16x16x16_i16"),
@@ -326,6 +342,9 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((3, 33, 90), (1, 16, 16), 16, "f64", "f64", None, "quad16_f64_16x16_i16_haar"),
         ((20, 37, 64), (16, 16, 16), 16, "f64", "f64", None, "cube16_f64_16x16x16_i16_haar"),
         ((17, 16, 70), (16, 16, 16), 32, "f32", "f32", None, "cube16_f32_16x16x16_i32_haar"),
+        ((17, 9, 72), (8, 8, 8), 8, "f64", "f32", None, "oct8_f64_w32_8x8x8_i8_haar"),
+        ((3, 33, 90), (1, 16, 16), 8, "f64", "f32", None, "quad16_f64_w32_16x16_i8_haar"),
+        ((20, 37, 64), (16, 16, 16), 8, "f64", "f32", None, "cube16_f64_w32_16x16x16_i8_haar"),
         ((9, 20, 36), (2, 16, 16), 8, "f32", "f32", None, "generic"),
         ((50, 21), (2, 32), 16, "f64", "f64", None, "generic")]
 

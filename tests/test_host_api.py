@@ -252,23 +252,32 @@ DISPATCH = [
     ((4, 16, 16), "f64", "i16", None, (9, 20, 38), "f64", "quad16_f64_4x16x16_i16"),
     ((16, 16, 16), "f32", "i32", None, (40, 40, 66), "f32", "cube16_f32_16x16x16_i32"),
     ((16, 16, 16), "f64", "i16", None, (40, 40, 66), "f32", "cube16_f32_16x16x16_i16"),    # FP32 array, FP64 N
+    ((8, 8, 8), "f64", "i16", None, (16, 16, 16), "f32", "oct8_f32_8x8x8_i16"),
+    ((16, 16), "f64", "i32", None, (64, 64), "f32", "quad16_f32_16x16_i32"),
+    ((4, 16, 16), "f64", "i16", None, (8, 32, 32), "f32", "quad16_f32_4x16x16_i16"),
     ((16, 16, 16), "f64", "i8", None, (40, 40, 66), "f64", "cube16_f64_16x16x16_i8"),
     ((16, 16, 16), "f64", "i16", None, (512, 512, 512), "f64", "cube16_f64_16x16x16_i16"),
     ((16, 16, 16), "f64", "i32", None, (17, 16, 71), "f64", "cube16_f64_16x16x16_i32"),
+    ((4, 16, 16), "f64", "i32", None, (8, 32, 32), "f64", "quad16_f64_4x16x16_i32"),
+    ((4, 16, 16), "f64", "i8", None, (8, 32, 32), "f64", "quad16_f64_4x16x16_i8"),
+    # FP64 arrays with an FP32 / 16-bit working type and int8: FP32 arithmetic
+    ((16, 16), "f32", "i8", None, (64, 64), "f64", "quad16_f64_w32_16x16_i8"),
+    ((4, 16, 16), "bf16", "i8", None, (9, 20, 38), "f64", "quad16_f64_w32_4x16x16_i8"),
+    ((8, 8, 8), "f32", "i8", None, (16, 16, 16), "f64", "oct8_f64_w32_8x8x8_i8"),
+    ((8, 8, 8), "f16", "i8", (4, 4, 4), (17, 9, 21), "f64", "oct8_f64_w32_8x8x8_i8_box4x4x4"),
+    ((16, 16, 16), "f32", "i8", None, (40, 40, 66), "f64", "cube16_f64_w32_16x16x16_i8"),
     ((1, 1, 8, 8), "f32", "i8", None, (3, 2, 40, 64), "f32", "lane_f32_8x8_i8"),          # leading unit-block dimensions fold
     ((8, 8), "f32", "i32", None, (64, 64), "f32", "lane_f32_8x8_i32"),
     ((8, 8), "f64", "i32", None, (37, 67), "f64", "lane_f64_8x8_i32"),
     ((4, 4, 4), "bf16", "i32", None, (9, 14, 24), "f32", "lane_f32_4x4x4_i32"),
     ((4, 4, 4), "f64", "i32", None, (512, 512, 512), "f64", "lane_f64_4x4x4_i32"),
     # no specialised kernel: the general ones
-    ((16, 16), "f32", "i8", None, (64, 64), "f64", "generic"),                             # FP64 array, FP32 arithmetic
-    ((4, 16, 16), "f64", "i32", None, (8, 32, 32), "f64", "generic"),
+    ((2, 16, 16), "f32", "i8", None, (8, 64, 64), "f64", "generic"),
     ((8, 8), "f32", "i32", (4, 4), (64, 64), "f32", "generic"),                            # int32 with a box
     ((8, 8), "f64", "i16", None, (64, 64), "f32", "generic"),                              # FP32 array, FP64 N
     ((16, 16), "f32", "i16", None, (64, 64), "f16", "generic"),                            # 16-bit array, int16
     ((8, 8, 8), "f32", "i8", (2, 2, 2), (16, 16, 16), "f32", "generic"),                   # another mask
-    ((8, 8, 8), "f32", "i8", None, (16, 16, 16), "f64", "generic"),                        # FP64 array, FP32 arithmetic
-    ((8, 8, 8), "f64", "i16", None, (16, 16, 16), "f32", "generic"),                       # FP32 array, FP64 N
+    ((8, 8, 8), "f64", "i8", None, (16, 16, 16), "f32", "generic"),                        # FP32 array, FP64 N, int8
     ((8, 8, 8), "f32", "i16", (4, 4, 4), (16, 16, 16), "f32", "generic"),                  # int16 with a box
     ((8, 8, 8), "f32", "i16", None, (16, 16, 16), "bf16", "generic"),                      # int16, 16-bit array
     ((16, 16, 16), "f32", "i16", (8, 8, 8), (32, 32, 64), "f32", "generic"),
