@@ -345,6 +345,35 @@ HAAR = [((40, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8_haar"),
         ((17, 9, 72), (8, 8, 8), 8, "f64", "f32", None, "oct8_f64_w32_8x8x8_i8_haar"),
         ((3, 33, 90), (1, 16, 16), 8, "f64", "f32", None, "quad16_f64_w32_16x16_i8_haar"),
         ((20, 37, 64), (16, 16, 16), 8, "f64", "f32", None, "cube16_f64_w32_16x16x16_i8_haar"),
+        # the remaining Haar instantiations, one row each
+        ((21, 72), (8, 8), 8, "f64", "f32", None, "lane_f64_w32_8x8_i8_haar"),
+        ((21, 72), (8, 8), 16, "f64", "f32", None, "lane_f64_w32_8x8_i16_haar"),
+        ((37, 67), (8, 8), 16, "f64", "f64", None, "lane_f64_8x8_i16_haar"),
+        ((21, 72), (8, 8), 32, "f64", "f64", None, "lane_f64_8x8_i32_haar"),
+        ((21, 72), (8, 8), 8, "f16", "f32", None, "lane_f16_8x8_i8_haar"),
+        ((21, 72), (8, 8), 8, "bf16", "f32", None, "lane_bf16_8x8_i8_haar"),
+        ((21, 78), (16, 16), 32, "f64", "f64", None, "quad16_f64_16x16_i32_haar"),
+        ((21, 78), (16, 16), 8, "f64", "f64", None, "quad16_f64_16x16_i8_haar"),
+        ((21, 78), (16, 16), 8, "bf16", "f32", None, "quad16_bf16_16x16_i8_haar"),
+        ((9, 14, 24), (4, 4, 4), 16, "f32", "f32", None, "lane_f32_4x4x4_i16_haar"),
+        ((9, 14, 24), (4, 4, 4), 32, "f32", "f32", None, "lane_f32_4x4x4_i32_haar"),
+        ((9, 13, 22), (4, 4, 4), 8, "f64", "f32", None, "lane_f64_w32_4x4x4_i8_haar"),
+        ((9, 13, 22), (4, 4, 4), 16, "f64", "f32", None, "lane_f64_w32_4x4x4_i16_haar"),
+        ((9, 13, 22), (4, 4, 4), 8, "f64", "f64", None, "lane_f64_4x4x4_i8_haar"),
+        ((17, 9, 24), (8, 8, 8), 8, "f32", "f32", None, "oct8_f32_8x8x8_i8_haar"),
+        ((17, 9, 21), (8, 8, 8), 32, "f32", "f32", None, "oct8_f32_8x8x8_i32_haar"),
+        ((17, 9, 21), (8, 8, 8), 8, "f64", "f32", (4, 4, 4), "oct8_f64_w32_8x8x8_i8_box4x4x4_haar"),
+        ((17, 9, 23), (8, 8, 8), 32, "f64", "f64", None, "oct8_f64_8x8x8_i32_haar"),
+        ((17, 9, 24), (8, 8, 8), 8, "f16", "f32", None, "oct8_f16_8x8x8_i8_haar"),
+        ((17, 9, 24), (8, 8, 8), 8, "f16", "f32", (4, 4, 4), "oct8_f16_8x8x8_i8_box4x4x4_haar"),
+        ((9, 20, 37), (4, 16, 16), 32, "f32", "f32", None, "quad16_f32_4x16x16_i32_haar"),
+        ((9, 20, 37), (4, 16, 16), 8, "f64", "f32", None, "quad16_f64_w32_4x16x16_i8_haar"),
+        ((9, 20, 37), (4, 16, 16), 16, "f64", "f64", None, "quad16_f64_4x16x16_i16_haar"),
+        ((9, 20, 37), (4, 16, 16), 32, "f64", "f64", None, "quad16_f64_4x16x16_i32_haar"),
+        ((9, 20, 37), (4, 16, 16), 8, "f64", "f64", None, "quad16_f64_4x16x16_i8_haar"),
+        ((9, 20, 38), (4, 16, 16), 8, "f16", "f32", None, "quad16_f16_4x16x16_i8_haar"),
+        ((17, 16, 70), (16, 16, 16), 32, "f64", "f64", None, "cube16_f64_16x16x16_i32_haar"),
+        ((16, 33, 21), (16, 16, 16), 8, "f64", "f64", None, "cube16_f64_16x16x16_i8_haar"),
         ((9, 20, 36), (2, 16, 16), 8, "f32", "f32", None, "generic"),
         ((50, 21), (2, 32), 16, "f64", "f64", None, "generic")]
 

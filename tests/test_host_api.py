@@ -321,3 +321,32 @@ def test_binding_checks_compressed_buffers_before_the_call():
         c.compress(x, N, F.to(torch.int16))
     with pytest.raises(ValueError, match="array's size"):
         c.decompress(N, F, (16, 16), out=torch.zeros((16, 8)))
+
+
+def test_every_specialised_kernel_has_a_gpu_parity_row():
+    """The dispatch is walked over block shapes, array / working / index types, masks and both transforms (on the host:
+    no kernel runs); every specialised kernel it can name must be named by a row of the GPU parity tables, so that a
+    kernel cannot be added without a test that runs it against the oracle."""
+    import itertools
+
+    import test_gpu_parity as gpu_rows
+    covered = {row[6] for row in gpu_rows.FAST_RAGGED} | {row[6] for row in gpu_rows.HAAR}
+    boxes = {(8, 8): [(4, 4)], (8, 8, 8): [(4, 4, 4)]}
+    reachable = {}
+    for block in [(8, 8), (16, 16), (4, 4, 4), (8, 8, 8), (4, 16, 16), (16, 16, 16)]:
+        shape = tuple(2 * b for b in block[:-1]) + (6 * block[-1],)
+        for dtype, ftype, itype, keep, transform in itertools.product(
+                ("f32", "f64", "f16", "bf16"), ("f32", "f64", "f16", "bf16"), ("i8", "i16", "i32"),
+                [None] + boxes.get(block, []), ("dct", "haar")):
+            mask = None
+            if keep is not None:
+                mask = np.zeros(block, dtype=bool)
+                mask[tuple(slice(0, k) for k in keep)] = True
+            c = Codec(block, ftype, itype, mask, transform)
+            name = c.kernel_name("compress", shape, dtype)
+            assert c.kernel_name("decompress", shape, dtype) == name
+            if name != "generic":
+                reachable.setdefault(name, (block, dtype, ftype, itype, keep))
+    assert len(reachable) > 100
+    missing = {name: how for name, how in reachable.items() if name not in covered}
+    assert not missing, f"specialised kernels without a GPU parity row: {missing}"
