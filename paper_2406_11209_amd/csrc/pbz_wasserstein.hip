@@ -7,8 +7,8 @@
 //   2. their sum and maximum, then sum of exp(x - max) (two-stage reductions; a one-workgroup kernel turns the
 //      partial sums into the parameters of the softmax and the decision whether to apply it),
 //   3. the raw means are sorted (softmax is increasing, so it commutes with sorting) by a least-significant-digit
-//      radix sort on an order-preserving 64-bit image of the doubles, 8 bits per pass, both operands in the same
-//      launches (grid y),
+//      radix sort on an order-preserving 64-bit image of the doubles, 8 bits per pass and three launches per pass,
+//      both operands in the same launches (grid y),
 //   4. m = max |P_A - P_B|, then sum (|P_A - P_B| / m)^p, then m (sum / n)^(1/p): the scaling by m changes
 //      nothing in exact arithmetic and keeps orders such as p = 68 .. 80 from underflowing.
 // All sums are two-stage with a fixed order, so the result is reproducible run to run.
@@ -23,8 +23,10 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kRadixBits = 8;
 constexpr int kBins = 1 << kRadixBits;
+constexpr int kSortThreads = 256;                // threads of a sorting workgroup: four waves, one thread per digit
 constexpr int kKeysPerLane = 16;
-constexpr int kTileKeys = 64 * kKeysPerLane;     // keys one wave ranks
+constexpr int kWaveKeys = 64 * kKeysPerLane;     // keys one wave ranks
+constexpr int kTileKeys = kSortThreads * kKeysPerLane;   // keys of a tile (one workgroup)
 constexpr int kStatGroups = 256;                 // workgroups per operand in the small reductions
 constexpr double kSumTolerance = 1e-9;           // "the means sum to one" is taken as |sum - 1| <= this
 
@@ -40,7 +42,7 @@ struct Workspace {
   uint64_t* buf0;          // [2][n]: means, then keys; the sorted keys end up here
   uint64_t* buf1;          // [2][n]
   uint32_t* hist;          // [2][kBins][n_tiles]
-  uint32_t* sums;          // [2][kScanGroups]: chunk sums of the histogram scan
+  uint32_t* sums;          // [2][kBins]: the digits' totals
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~size_t(255); }
@@ -60,7 +62,7 @@ size_t carve(void* base, int64_t n, Workspace* w) {
   char* d = take(sizeof(uint64_t) * 2 * size_t(n));
   char* e = take(sizeof(uint64_t) * 2 * size_t(n));
   char* f = take(sizeof(uint32_t) * 2 * kBins * size_t(n_tiles));
-  char* g = take(sizeof(uint32_t) * 2 * 1024);      // kScanGroups per operand
+  char* g = take(sizeof(uint32_t) * 2 * kBins);
   if (w) {
     w->sums = reinterpret_cast<uint32_t*>(g);
     w->params = reinterpret_cast<OperandParams*>(a);
@@ -171,33 +173,61 @@ __global__ __launch_bounds__(kThreads) void k_to_keys(uint64_t* __restrict__ buf
 }
 
 // ---- radix sort, one pass = histogram per tile, exclusive scan over (digit, tile), stable scatter --------------
-// A tile is kTileKeys consecutive keys, ranked by one wave: element j * 64 + lane of the tile belongs to lane
-// `lane` in round j, so rounds and, within a round, lanes follow the input order.
-__global__ __launch_bounds__(64) void k_radix_hist(const uint64_t* __restrict__ keys, int64_t n, int64_t n_tiles,
-                                                   int shift, uint32_t* __restrict__ hist) {
-  __shared__ uint32_t count[kBins];
-  const int lane = threadIdx.x;
-  const uint64_t* in = keys + int64_t(blockIdx.y) * n;
-  uint32_t* h = hist + int64_t(blockIdx.y) * kBins * n_tiles;
+// A tile is kTileKeys consecutive keys, ranked by one workgroup of four waves: wave w takes the tile's w-th quarter,
+// and element j * 64 + lane of that quarter belongs to lane `lane` in round j, so waves, rounds and, within a
+// round, lanes follow the input order.
+
+// the lanes of this round that hold the same digit as this one (valid lanes only)
+__device__ __forceinline__ uint64_t same_digit_lanes(uint32_t digit, bool valid) {
+  uint64_t peers = __ballot(valid);
 #pragma unroll
-  for (int b = lane; b < kBins; b += 64) count[b] = 0;
-  wave_lds_sync();
-  const int64_t base = int64_t(blockIdx.x) * kTileKeys;
-#pragma unroll
-  for (int j = 0; j < kKeysPerLane; ++j) {
-    const int64_t i = base + j * 64 + lane;
-    if (i < n) atomicAdd(&count[(in[i] >> shift) & (kBins - 1)], 1u);
+  for (int b = 0; b < kRadixBits; ++b) {
+    const uint64_t set = __ballot(valid && ((digit >> b) & 1u));
+    peers &= ((digit >> b) & 1u) ? set : ~set;
   }
-  wave_lds_sync();
-#pragma unroll
-  for (int b = lane; b < kBins; b += 64) h[int64_t(b) * n_tiles + blockIdx.x] = count[b];
+  return peers;
 }
 
-// Exclusive prefix sum, in place, over the kBins * n_tiles counts of one operand (digit-major, so that entry
-// (digit, tile) becomes the output position of that tile's first key with that digit).  Three steps: the sum of
-// every chunk, an exclusive scan of the at most kScanGroups chunk sums by one workgroup, and a scan inside every
-// chunk started from its chunk's offset.  grid y = operand.
-constexpr int kScanGroups = 1024;
+// One count per digit and tile.  The lanes of a round that share a digit add their number with one atomic (the
+// high digits of block means are the same for nearly all keys: one atomic per key would serialise on one address).
+__global__ __launch_bounds__(kSortThreads) void k_radix_hist(const uint64_t* __restrict__ keys, int64_t n,
+                                                             int64_t n_tiles, int shift, uint32_t* __restrict__ hist) {
+  __shared__ uint32_t count[kBins];
+  static_assert(kBins == kSortThreads, "one thread per digit");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t* in = keys + int64_t(blockIdx.y) * n;
+  uint32_t* h = hist + int64_t(blockIdx.y) * kBins * n_tiles;
+  count[threadIdx.x] = 0;
+  __syncthreads();
+  // which lane counts which key does not matter here: two neighbouring keys per lane and load, all loads first
+  const int64_t base = int64_t(blockIdx.x) * kTileKeys + wave * kWaveKeys;
+  const uint64_t below = (uint64_t(1) << lane) - 1;      // lanes before this one
+  uint64_t key[kKeysPerLane];
+  const bool whole = base + kWaveKeys <= n && (reinterpret_cast<uintptr_t>(in) & 15u) == 0;      // uniform over the wave
+  if (whole) {
+#pragma unroll
+    for (int j = 0; j < kKeysPerLane / 2; ++j) {
+      const uint4 two = *reinterpret_cast<const uint4*>(in + base + (j * 64 + lane) * 2);
+      key[2 * j] = uint64_t(two.x) | (uint64_t(two.y) << 32);
+      key[2 * j + 1] = uint64_t(two.z) | (uint64_t(two.w) << 32);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < kKeysPerLane; ++j) {
+      const int64_t i = base + j * 64 + lane;
+      key[j] = i < n ? in[i] : 0;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kKeysPerLane; ++j) {
+    const bool valid = whole || base + j * 64 + lane < n;
+    const uint32_t digit = uint32_t(key[j] >> shift) & (kBins - 1);
+    const uint64_t peers = same_digit_lanes(digit, valid);
+    if (valid && (peers & below) == 0) atomicAdd(&count[digit], uint32_t(__popcll(peers)));
+  }
+  __syncthreads();
+  h[int64_t(threadIdx.x) * n_tiles + blockIdx.x] = count[threadIdx.x];
+}
 
 __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t v, uint32_t* lds /* blockDim.x entries */,
                                                          uint32_t* total) {
@@ -210,89 +240,115 @@ __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t v, uint32_t* l
     __syncthreads();
   }
   if (total) *total = lds[blockDim.x - 1];
-  return lds[threadIdx.x] - v;
+  const uint32_t ex = lds[threadIdx.x] - v;
+  __syncthreads();                                        // the buffer may be used again right away
+  return ex;
 }
 
-__global__ __launch_bounds__(kThreads) void k_scan_sums(const uint32_t* __restrict__ hist, int64_t entries,
-                                                        int64_t chunk, uint32_t* __restrict__ sums) {
-  __shared__ uint32_t lds[kThreads];
-  const uint32_t* h = hist + int64_t(blockIdx.y) * entries;
-  const int64_t begin = int64_t(blockIdx.x) * chunk;
-  const int64_t end = begin + chunk < entries ? begin + chunk : entries;
-  uint32_t s = 0;
-  for (int64_t i = begin + threadIdx.x; i < end; i += kThreads) s += h[i];
-  uint32_t total;
-  group_exclusive_scan(s, lds, &total);
-  if (threadIdx.x == 0) sums[blockIdx.y * kScanGroups + blockIdx.x] = total;
-}
-
-__global__ __launch_bounds__(kScanGroups) void k_scan_top(uint32_t* __restrict__ sums, int groups) {
-  __shared__ uint32_t lds[kScanGroups];
-  uint32_t* mine = sums + blockIdx.x * kScanGroups;
-  const uint32_t v = int(threadIdx.x) < groups ? mine[threadIdx.x] : 0u;
-  const uint32_t ex = group_exclusive_scan(v, lds, nullptr);
-  if (int(threadIdx.x) < groups) mine[threadIdx.x] = ex;
-}
-
-__global__ __launch_bounds__(kThreads) void k_scan_apply(uint32_t* __restrict__ hist, int64_t entries, int64_t chunk,
-                                                         const uint32_t* __restrict__ sums) {
-  __shared__ uint32_t lds[kThreads];
-  uint32_t* h = hist + int64_t(blockIdx.y) * entries;
-  const int64_t chunk_begin = int64_t(blockIdx.x) * chunk;
-  const int64_t chunk_end = chunk_begin + chunk < entries ? chunk_begin + chunk : entries;
-  const int64_t per = chunk / kThreads;                       // chunk is a multiple of kThreads
-  int64_t begin = chunk_begin + int64_t(threadIdx.x) * per;
-  int64_t end = begin + per;
-  if (begin > chunk_end) begin = chunk_end;
-  if (end > chunk_end) end = chunk_end;
-  uint32_t s = 0;
-  for (int64_t i = begin; i < end; ++i) s += h[i];
-  uint32_t run = sums[blockIdx.y * kScanGroups + blockIdx.x] + group_exclusive_scan(s, lds, nullptr);
-  for (int64_t i = begin; i < end; ++i) {
-    const uint32_t v = h[i];
-    h[i] = run;
-    run += v;
+// Per digit (grid x) and operand (grid y): the counts of the digit's tiles become their exclusive prefix sums, in
+// place, and the digit's total goes to totals.  The scatter kernel adds the totals of the lower digits itself.
+__global__ __launch_bounds__(kSortThreads) void k_scan_digit(uint32_t* __restrict__ hist, int64_t n_tiles,
+                                                             uint32_t* __restrict__ totals) {
+  __shared__ uint32_t lds[kSortThreads];
+  uint32_t* row = hist + (int64_t(blockIdx.y) * kBins + blockIdx.x) * n_tiles;
+  uint32_t carry = 0;
+  for (int64_t t0 = 0; t0 < n_tiles; t0 += kSortThreads) {
+    const int64_t t = t0 + threadIdx.x;
+    const uint32_t v = t < n_tiles ? row[t] : 0u;
+    uint32_t chunk_total;
+    const uint32_t ex = group_exclusive_scan(v, lds, &chunk_total);
+    if (t < n_tiles) row[t] = carry + ex;
+    carry += chunk_total;
   }
+  if (threadIdx.x == 0) totals[blockIdx.y * kBins + blockIdx.x] = carry;
 }
 
-__global__ __launch_bounds__(64) void k_radix_scatter(const uint64_t* __restrict__ keys_in,
-                                                      uint64_t* __restrict__ keys_out, int64_t n, int64_t n_tiles,
-                                                      int shift, const uint32_t* __restrict__ hist) {
-  __shared__ uint32_t next[kBins];                 // output position of the tile's next key, per digit
-  const int lane = threadIdx.x;
+// The keys of a tile are first put in digit order in LDS (ranks within a wave from lane ballots and a per-wave
+// cursor per digit, then the waves' counts are chained), and then written out in that order, so that consecutive
+// threads write consecutive keys of a digit's run.  A digit that all n keys share (the sign and exponent bytes of
+// block means, typically) leaves the order as it is: the tile is copied.
+__global__ __launch_bounds__(kSortThreads) void k_radix_scatter(const uint64_t* __restrict__ keys_in,
+                                                                uint64_t* __restrict__ keys_out, int64_t n,
+                                                                int64_t n_tiles, int shift,
+                                                                const uint32_t* __restrict__ hist,
+                                                                const uint32_t* __restrict__ totals) {
+  __shared__ uint64_t sorted[kTileKeys];
+  __shared__ uint32_t cursor[kSortThreads / 64][kBins];   // per wave: count so far, later the wave's offset in its digit
+  __shared__ uint32_t tile_first[kBins];                  // position in the tile of the first key with that digit
+  __shared__ uint32_t out_first[kBins];                   // position in the output of that key
+  __shared__ uint32_t scan[kSortThreads];
+  __shared__ uint32_t uniform;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t* in = keys_in + int64_t(blockIdx.y) * n;
   uint64_t* out = keys_out + int64_t(blockIdx.y) * n;
-  const uint32_t* h = hist + int64_t(blockIdx.y) * kBins * n_tiles;
-#pragma unroll
-  for (int b = lane; b < kBins; b += 64) next[b] = h[int64_t(b) * n_tiles + blockIdx.x];
-  const int64_t base = int64_t(blockIdx.x) * kTileKeys;
+  const int64_t tile_base = int64_t(blockIdx.x) * kTileKeys;
+  const int64_t base = tile_base + wave * kWaveKeys;
   uint64_t key[kKeysPerLane];
 #pragma unroll
   for (int j = 0; j < kKeysPerLane; ++j) {
     const int64_t i = base + j * 64 + lane;
     key[j] = i < n ? in[i] : 0;
   }
-  wave_lds_sync();
+  const uint32_t digit_total = totals[blockIdx.y * kBins + threadIdx.x];
+  if (threadIdx.x == 0) uniform = 0;
+#pragma unroll
+  for (int w = 0; w < kSortThreads / 64; ++w) cursor[w][threadIdx.x] = 0;
+  __syncthreads();
+  if (int64_t(digit_total) == n) uniform = 1;
+  const uint32_t digit_first = group_exclusive_scan(digit_total, scan, nullptr);   // (contains the barrier)
+  if (uniform) {
+#pragma unroll
+    for (int j = 0; j < kKeysPerLane; ++j) {
+      const int64_t i = base + j * 64 + lane;
+      if (i < n) out[i] = key[j];
+    }
+    return;
+  }
   const uint64_t below = (uint64_t(1) << lane) - 1;      // lanes before this one
+  uint32_t local[kKeysPerLane];                          // rank among the wave's keys with the same digit
 #pragma unroll
   for (int j = 0; j < kKeysPerLane; ++j) {
     const bool valid = base + j * 64 + lane < n;
     const uint32_t digit = uint32_t(key[j] >> shift) & (kBins - 1);
-    // lanes of this round that hold the same digit
-    uint64_t peers = __ballot(valid);
-#pragma unroll
-    for (int b = 0; b < kRadixBits; ++b) {
-      const uint64_t set = __ballot(valid && ((digit >> b) & 1u));
-      peers &= ((digit >> b) & 1u) ? set : ~set;
-    }
-    const uint32_t start = valid ? next[digit] : 0u;
+    const uint64_t peers = same_digit_lanes(digit, valid);
+    const uint32_t start = valid ? cursor[wave][digit] : 0u;
     wave_lds_sync();                                       // every lane has read before any leader writes
-    if (valid) {
-      const uint32_t rank = uint32_t(__popcll(peers & below));
-      if (rank == 0) next[digit] = start + uint32_t(__popcll(peers));   // the first peer moves the digit's cursor
-      out[start + rank] = key[j];
-    }
+    const uint32_t rank = uint32_t(__popcll(peers & below));
+    if (valid && rank == 0) cursor[wave][digit] = start + uint32_t(__popcll(peers));
+    local[j] = start + rank;
     wave_lds_sync();
+  }
+  __syncthreads();
+  {  // thread d: the waves' counts of digit d become the waves' offsets; the tile's count of d is scanned over d
+    uint32_t run = 0;
+#pragma unroll
+    for (int w = 0; w < kSortThreads / 64; ++w) {
+      const uint32_t c = cursor[w][threadIdx.x];
+      cursor[w][threadIdx.x] = run;
+      run += c;
+    }
+    tile_first[threadIdx.x] = group_exclusive_scan(run, scan, nullptr);
+    out_first[threadIdx.x] = digit_first + hist[int64_t(blockIdx.y) * kBins * n_tiles + int64_t(threadIdx.x) * n_tiles + blockIdx.x];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < kKeysPerLane; ++j) {
+    if (base + j * 64 + lane < n) {
+      const uint32_t digit = uint32_t(key[j] >> shift) & (kBins - 1);
+      sorted[tile_first[digit] + cursor[wave][digit] + local[j]] = key[j];
+    }
+  }
+  __syncthreads();
+  const int64_t left = n - tile_base;
+  const int count = left < kTileKeys ? int(left) : kTileKeys;
+#pragma unroll
+  for (int k = 0; k < kKeysPerLane; ++k) {
+    const int i = k * kSortThreads + threadIdx.x;
+    if (i < count) {
+      const uint64_t v = sorted[i];
+      const uint32_t digit = uint32_t(v >> shift) & (kBins - 1);
+      out[out_first[digit] + uint32_t(i) - tile_first[digit]] = v;
+    }
   }
 }
 
@@ -371,21 +427,14 @@ int launch_approximate_wasserstein(const pbz_codec* c, int64_t n, const void* N1
   const int64_t total = 2 * n;
   hipLaunchKernelGGL(k_to_keys, dim3(unsigned((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, w.buf0, total);
   const int64_t n_tiles = (n + kTileKeys - 1) / kTileKeys;
-  const int64_t entries = int64_t(kBins) * n_tiles;
-  // 16 counts per thread unless that needs more than kScanGroups chunks
-  int64_t scan_chunk = int64_t(kThreads) * 16;
-  if ((entries + scan_chunk - 1) / scan_chunk > kScanGroups)
-    scan_chunk = ((entries + kScanGroups - 1) / kScanGroups + kThreads - 1) / kThreads * kThreads;
-  const int scan_groups = int((entries + scan_chunk - 1) / scan_chunk);
   uint64_t* src = w.buf0;
   uint64_t* dst = w.buf1;
   for (int pass = 0; pass < 64 / kRadixBits; ++pass) {
     const int shift = pass * kRadixBits;
-    hipLaunchKernelGGL(k_radix_hist, dim3(unsigned(n_tiles), 2), dim3(64), 0, s, src, n, n_tiles, shift, w.hist);
-    hipLaunchKernelGGL(k_scan_sums, dim3(scan_groups, 2), dim3(kThreads), 0, s, w.hist, entries, scan_chunk, w.sums);
-    hipLaunchKernelGGL(k_scan_top, dim3(2), dim3(kScanGroups), 0, s, w.sums, scan_groups);
-    hipLaunchKernelGGL(k_scan_apply, dim3(scan_groups, 2), dim3(kThreads), 0, s, w.hist, entries, scan_chunk, w.sums);
-    hipLaunchKernelGGL(k_radix_scatter, dim3(unsigned(n_tiles), 2), dim3(64), 0, s, src, dst, n, n_tiles, shift, w.hist);
+    hipLaunchKernelGGL(k_radix_hist, dim3(unsigned(n_tiles), 2), dim3(kSortThreads), 0, s, src, n, n_tiles, shift, w.hist);
+    hipLaunchKernelGGL(k_scan_digit, dim3(kBins, 2), dim3(kSortThreads), 0, s, w.hist, n_tiles, w.sums);
+    hipLaunchKernelGGL(k_radix_scatter, dim3(unsigned(n_tiles), 2), dim3(kSortThreads), 0, s, src, dst, n, n_tiles, shift,
+                       w.hist, w.sums);
     uint64_t* t = src;
     src = dst;
     dst = t;
