@@ -161,6 +161,9 @@ BEYOND_32_BITS = [((1040, 1536, 1536), (8, 8, 8), 8, "bf16", "f32", (4, 4, 4), "
                   ((520, 2048, 2048), (4, 4, 4), 16, "f64", "f64", None, "lane_f64_4x4x4_i16"),
                   ((3, 40000, 20000), (1, 16, 16), 16, "f32", "f32", None, "quad16_f32_16x16_i16"),
                   ((528, 2048, 2048), (16, 16, 16), 8, "f32", "f32", None, "cube16_f32_16x16x16_i8"),
+                  ((520, 2048, 2048), (8, 8, 8), 16, "f64", "f64", None, "oct8_f64_8x8x8_i16"),
+                  ((528, 2048, 2048), (16, 16, 16), 16, "f32", "f32", None, "cube16_f32_16x16x16_i16"),
+                  ((3, 40000, 20000), (1, 16, 16), 16, "f64", "f64", None, "quad16_f64_16x16_i16"),
                   ((3, 40000, 20000), (1, 32, 16), 16, "f32", "f32", None, "generic")]
 
 
