@@ -501,6 +501,20 @@ __global__ __launch_bounds__(512) void k_decompress_oct8_rows(FastGeom g, const 
         continue;
       }
     }
+    if constexpr (sizeof(XT) == 8 && !kTailX) {
+      if (whole_wave) {
+        // FP64 rows are four pieces per block: the quarter-waves trade them so that store k writes the rows of
+        // blocks 16 k .. 16 k + 15 as one contiguous KiB (512^3, FP32 working type: 0.354 -> 0.2 ms)
+        uint4 h[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) h[k] = oct_pack<XT>(v + yy0 * 8 + 2 * k);
+        transpose_quarter_waves(h[0], h[1], h[2], h[3]);
+        uint4* p = reinterpret_cast<uint4*>(y + (zz * g.Y + yy) * g.X + tx * 64 * 8) + 4 * (lane & 15) + (lane >> 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) store16_stream(p + 64 * k, h[k]);
+        continue;
+      }
+    }
     oct_store_row<XT, kTailX>(g, y + (zz * g.Y + yy) * g.X, bx, v + yy0 * 8);
   }
 }

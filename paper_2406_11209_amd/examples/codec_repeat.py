@@ -7,6 +7,7 @@ import argparse
 import os
 import sys
 
+import numpy as np
 import torch
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)))))
@@ -23,12 +24,18 @@ def main():
     ap.add_argument("--ftype", default="f32", choices=list(TORCH), help="working float type (storage type of N)")
     ap.add_argument("--itype", default="i8", choices=["i8", "i16", "i32"])
     ap.add_argument("--transform", default="dct", choices=["dct", "haar"])
+    ap.add_argument("--keep", type=int, nargs="+", default=None,
+                    help="keep only the low-frequency box of this shape of every block (default: keep everything)")
     ap.add_argument("--repeat", type=int, default=5)
     ap.add_argument("--path", default="auto", choices=["auto", "generic"],
                     help="generic: the general kernels, also where a specialised kernel exists")
     args = ap.parse_args()
     shape = tuple(args.shape)
-    codec = Codec(tuple(args.block), args.ftype, args.itype, None, args.transform)
+    mask = None
+    if args.keep is not None:
+        mask = np.zeros(tuple(args.block), dtype=bool)
+        mask[tuple(slice(0, k) for k in args.keep)] = True
+    codec = Codec(tuple(args.block), args.ftype, args.itype, mask, args.transform)
     if args.path == "generic":
         codec.set_kernel_path(PBZ_PATH_GENERIC)
     gen = torch.Generator(device="cuda").manual_seed(240611209)

@@ -286,6 +286,9 @@ FAST_RAGGED = [((37, 64), (8, 8), 8, "f32", "f32", None, "lane_f32_8x8_i8"),
                ((17, 9, 72), (8, 8, 8), 8, "f64", "f32", (4, 4, 4), "oct8_f64_w32_8x8x8_i8_box4x4x4"),
                ((9, 12, 398), (8, 8, 8), 8, "f64", "f32", (4, 4, 4), "oct8_f64_w32_8x8x8_i8_box4x4x4"),
                ((9, 17, 21), (8, 8, 8), 8, "f64", "f16", (4, 4, 4), "oct8_f64_w32_8x8x8_i8_box4x4x4"),
+               # 64 and more blocks along x: whole waves, whose rows leave as contiguous KiB after lane trades
+               ((9, 9, 712), (8, 8, 8), 8, "f64", "f32", (4, 4, 4), "oct8_f64_w32_8x8x8_i8_box4x4x4"),
+               ((9, 9, 712), (8, 8, 8), 8, "f32", "f32", (4, 4, 4), "oct8_f32_8x8x8_i8_box4x4x4"),
                ((20, 37, 64), (16, 16, 16), 8, "f64", "f32", None, "cube16_f64_w32_16x16x16_i8"),
                ((17, 16, 71), (16, 16, 16), 8, "f64", "f16", None, "cube16_f64_w32_16x16x16_i8"),
                ((32, 16, 48), (16, 16, 16), 16, "f64", "f64", None, "cube16_f64_16x16x16_i16"),
